@@ -1,0 +1,142 @@
+/*
+ * zapformat -- per-decode-step vocabulary mask for grammar-constrained decoding on MI355X.
+ *
+ * The operations follow the paper's statement of the problem:
+ *   - a context-free grammar A -> alpha (Section 3.1) whose terminals are byte strings or
+ *     byte-level regular expressions matched by finite-state machines (Section 4.1);
+ *   - an Earley recognizer state per query, updated after every decoded token with
+ *     Scan / Complete / Compact / Predict (Sections 3.2 and 4.2, ZapFormat pruning);
+ *   - at every decoding step, a validity verdict for EVERY vocabulary token, applied to the
+ *     logits by writing -inf over the invalid ones (Sections 3.3 and 4.1).
+ *
+ * All functions return ZF_OK (0) or a negative error code; nothing aborts or throws across
+ * this boundary.  Handles are opaque, owned by the library and released only by *_destroy.
+ * "host" / "device" in a comment says where a pointer must live.  The library needs a HIP
+ * device for zf_compute_mask / zf_apply_mask; there is no CPU substitute for them.
+ */
+#ifndef ZAPFORMAT_H
+#define ZAPFORMAT_H
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    ZF_OK = 0,
+    ZF_ERR_INVALID_ARG = -1, /* null pointer, bad size, bad dtype, state of another engine */
+    ZF_ERR_GRAMMAR = -2,     /* bad symbol id, bad regex, terminal with empty language or that
+                                matches the empty string, start symbol derives nothing */
+    ZF_ERR_REJECTED = -3,    /* token / bytes not allowed in this state; the state is unchanged */
+    ZF_ERR_RANGE = -4,       /* token id outside [0, V) */
+    ZF_ERR_DEVICE = -5,      /* HIP call failed, or the engine was compiled without a device */
+    ZF_ERR_OOM = -6,
+    ZF_ERR_OVERFLOW = -7     /* an Earley set outgrew even the device fallback arena; the mask
+                                written by this call is not valid */
+};
+
+const char *zf_strerror(int code); /* static string */
+const char *zf_last_error(void);   /* thread-local detail of the last failure on this thread */
+
+typedef struct zf_engine zf_engine; /* immutable after zf_compile; may be shared by many states */
+typedef struct zf_state zf_state;   /* one query: the (pruned) Earley chart of its prefix */
+
+/* A grammar (Section 3.1).  All arrays are host memory, owned by the caller, copied by
+ * zf_compile.  Nonterminals are 0..n_nonterminals-1.  rhs_sym >= 0 is a nonterminal id,
+ * rhs_sym < 0 is terminal ~rhs_sym.  An empty right-hand side is an epsilon rule. */
+typedef struct {
+    int32_t n_nonterminals, start;
+    int32_t n_rules;
+    const int32_t *rule_lhs; /* [n_rules] */
+    const int32_t *rhs_off;  /* [n_rules+1] CSR offsets into rhs_sym */
+    const int32_t *rhs_sym;
+    int32_t n_terminals;
+    const uint8_t *term_kind; /* [n_terminals] 0 = literal bytes, 1 = byte-regex source */
+    const int64_t *term_off;  /* [n_terminals+1] CSR offsets into term_data */
+    const uint8_t *term_data;
+} zf_grammar_desc;
+
+/* The vocabulary: token v is bytes[off[v] .. off[v+1]).  Host memory.  Tokens are arbitrary
+ * byte strings (they may split multi-byte characters, Section 2); duplicates are legal and get
+ * equal verdicts; a zero-length token is never allowed. */
+typedef struct {
+    int32_t V;
+    const int64_t *off;
+    const uint8_t *bytes;
+} zf_vocab_desc;
+
+typedef struct {
+    int32_t pruning;       /* 1 = ZapFormat Compact phase on (Section 4.2), 0 = keep every item */
+    int32_t lane_item_cap; /* per-lane Earley item budget of the mask kernel, 0 = default;
+                              anything that does not fit goes to the exact fallback pass */
+    int32_t device;        /* HIP device ordinal, or -1 = host tables only (no mask calls) */
+} zf_options;
+
+typedef struct {
+    int64_t n_sets, n_items;   /* chart as it stands (after Compact when pruning is on) */
+    int64_t items_created;     /* every item ever added by Scan/Complete since the last reset */
+    int64_t bytes_fed;
+    int32_t accepting;
+} zf_stats;
+
+typedef struct {
+    int32_t V, W;                 /* W = ceil(V/32) mask words per row */
+    int32_t n_nonterminals, n_rules, n_positions;
+    int32_t n_dfa_states, n_byte_classes;
+    int32_t n_trie_nodes, n_strings; /* distinct non-empty token strings */
+    int32_t lane_item_cap, device;
+} zf_engine_info;
+
+typedef struct {               /* device time of the last zf_compute_mask, for reporting only */
+    int64_t overflow_chunks;   /* trie chunks handed to the fallback pass in the last call */
+    int64_t chart_bytes;       /* bytes uploaded for the last call */
+} zf_mask_report;
+
+/* compile(grammar rules, vocab byte strings): clean the grammar (useless rules, nullable
+ * symbols: Section 4.5), build one byte-level DFA per terminal (Section 4.1), flatten the
+ * vocabulary into a prefix trie, upload the immutable tables.  *out is set on success only. */
+int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_options *opt, zf_engine **out);
+void zf_engine_destroy(zf_engine *e);
+int zf_engine_get_info(const zf_engine *e, zf_engine_info *out);
+
+int zf_state_new(zf_engine *e, zf_state **out); /* chart of the empty prefix */
+int zf_state_clone(const zf_state *s, zf_state **out);
+int zf_state_reset(zf_state *s);
+void zf_state_destroy(zf_state *s);
+
+/* advance(state, token_id): feed the token's bytes through Scan -> Complete -> Compact ->
+ * Predict (Sections 3.2, 4.2).  All or nothing: on ZF_ERR_REJECTED the state is unchanged. */
+int zf_advance(zf_state *s, int32_t token_id);
+int zf_advance_bytes(zf_state *s, const uint8_t *bytes /* host */, int64_t n);
+int zf_is_accepting(const zf_state *s, int32_t *out); /* is the prefix a sentence of the grammar? */
+int zf_state_stats(const zf_state *s, zf_stats *out);
+/* Copy the chart out for inspection: items as int32 triples (dotted position, origin set, DFA
+ * state), set_off[n_sets+1].  Pass null buffers to query sizes through zf_state_stats. */
+int zf_state_chart(const zf_state *s, int32_t *items /* host [n_items][3] */, int64_t *set_off /* host */);
+/* Describe a dotted position: lhs nonterminal id (original numbering), rule index (original),
+ * dot.  For tests that compare charts with the paper's worked examples. */
+int zf_position_info(const zf_engine *e, int32_t position, int32_t *lhs, int32_t *rule, int32_t *dot);
+
+/* compute_mask(states[batch]): for every row and every token v, bit (v & 31) of word (v >> 5)
+ * of d_mask[row] becomes 1 iff the token's bytes, fed one at a time, never empty the Earley
+ * set (Section 4.1: all tokens are checked at every step).  d_mask: device, [batch][W]
+ * uint32, fully overwritten, padding bits zero.  The states' charts are snapshotted before
+ * the call returns.  The work is enqueued on hip_stream (a hipStream_t, null = default
+ * stream); the call waits for its own kernels so that ZF_ERR_OVERFLOW can be reported. */
+int zf_compute_mask(zf_engine *e, zf_state *const *states /* host array */, int32_t batch,
+                    uint32_t *d_mask, void *hip_stream);
+int zf_last_mask_report(const zf_engine *e, zf_mask_report *out);
+
+/* apply_mask(logits): out[b][v] = bit(b, v) ? logits[b][v] (bit copy) : -inf (Section 3.3).
+ * d_logits / d_out: device, [batch][row_stride_elems] with V valid elements per row; d_out may
+ * equal d_logits.  dtype: 0 = fp32, 1 = bf16.  Asynchronous on hip_stream. */
+int zf_apply_mask(zf_engine *e, const void *d_logits, void *d_out, int32_t dtype, int32_t batch,
+                  int64_t row_stride_elems, const uint32_t *d_mask, void *hip_stream);
+
+/* Diagnostic: the same verdicts computed on the host from the compiled tables (trie, DFAs,
+ * chart).  Never used by zf_compute_mask; exists so the host logic can be tested without a GPU. */
+int zf_debug_host_mask(zf_engine *e, const zf_state *s, uint32_t *mask /* host [W] */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,373 @@
+// The C boundary: argument checks, engine / state life cycle, advance, chart packing and
+// upload, kernel launches.
+#include <hip/hip_runtime_api.h>
+#include <cstring>
+#include <new>
+#include "zf_internal.h"
+#include "zf_launch.h"
+
+using namespace zf;
+
+namespace zf {
+static thread_local std::string g_err;
+void set_error(const std::string &m) { g_err = m; }
+}  // namespace zf
+
+// Device-side resources of an engine.
+struct DeviceSide {
+    int device = 0;
+    DeviceTables tab{};
+    std::vector<void *> owned;           // table allocations
+    // per-call buffers, grown on demand
+    void *d_chart = nullptr; size_t chart_cap = 0;
+    void *h_stage = nullptr; size_t stage_cap = 0;   // pinned
+    uint32_t *d_rank_mask = nullptr; size_t rank_cap = 0;
+    uint2 *d_overflow = nullptr; size_t overflow_cap = 0;
+    uint32_t *d_counters = nullptr;
+    uint32_t *h_counters = nullptr;      // pinned
+    uint2 *d_fb_items = nullptr;
+    uint32_t *d_fb_ss = nullptr;
+    zf_mask_report report{};
+};
+
+namespace {
+
+int fail(int code, const std::string &m) { set_error(m); return code; }
+#define HIP_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return fail(ZF_ERR_DEVICE, std::string(#expr) + ": " + hipGetErrorString(e_)); } while (0)
+
+template <class Tv>
+int upload(DeviceSide *d, const std::vector<Tv> &v, const Tv **out) {
+    void *p = nullptr;
+    size_t bytes = std::max<size_t>(v.size() * sizeof(Tv), 16);
+    HIP_TRY(hipMalloc(&p, bytes));
+    d->owned.push_back(p);
+    if (!v.empty()) HIP_TRY(hipMemcpy(p, v.data(), v.size() * sizeof(Tv), hipMemcpyHostToDevice));
+    *out = (const Tv *)p;
+    return ZF_OK;
+}
+
+void free_device(DeviceSide *d) {
+    if (!d) return;
+    (void)hipSetDevice(d->device);
+    for (void *p : d->owned) (void)hipFree(p);
+    if (d->d_chart) (void)hipFree(d->d_chart);
+    if (d->h_stage) (void)hipHostFree(d->h_stage);
+    if (d->d_rank_mask) (void)hipFree(d->d_rank_mask);
+    if (d->d_overflow) (void)hipFree(d->d_overflow);
+    if (d->d_counters) (void)hipFree(d->d_counters);
+    if (d->h_counters) (void)hipHostFree(d->h_counters);
+    if (d->d_fb_items) (void)hipFree(d->d_fb_items);
+    if (d->d_fb_ss) (void)hipFree(d->d_fb_ss);
+    delete d;
+}
+
+int setup_device(zf_engine *e) {
+    DeviceSide *d = new (std::nothrow) DeviceSide();
+    if (!d) return fail(ZF_ERR_OOM, "out of memory");
+    e->dev = d;
+    d->device = e->opt.device;
+    HIP_TRY(hipSetDevice(d->device));
+    const Tables &t = e->tab;
+    const Trie &tr = e->trie;
+    DeviceTables &T = d->tab;
+    int rc;
+    std::vector<uint8_t> cls(t.cls, t.cls + 256);
+#define UP(field, vec) if ((rc = upload(d, vec, &T.field)) != ZF_OK) return rc
+    UP(sym, t.sym); UP(end_pos, t.end_pos); UP(cls, cls); UP(delta, t.delta); UP(qflags, t.qflags);
+    UP(term_start, t.term_start); UP(scan_off, t.scan_off); UP(scan_list, t.scan_list);
+    UP(comp_off, t.comp_off); UP(comp_list, t.comp_list);
+    UP(nodes, tr.nodes); UP(parent, tr.parent); UP(chunk_begin, tr.chunk_begin); UP(chunk_end, tr.chunk_end);
+    UP(chunk_anc, tr.chunk_anc); UP(rank_of, tr.rank_of);
+#undef UP
+    T.N = t.N; T.n_cls = t.n_cls; T.n_nodes = (int)tr.nodes.size(); T.n_chunks = (int)tr.chunk_begin.size();
+    T.n_strings = tr.n_strings; T.V = e->V; T.W = e->W; T.Wr = T.n_chunks;
+    HIP_TRY(hipMalloc((void **)&d->d_counters, 16));
+    HIP_TRY(hipHostMalloc((void **)&d->h_counters, 16, hipHostMallocDefault));
+    HIP_TRY(hipMalloc((void **)&d->d_fb_items, (size_t)FB_ITEMS_PER_LANE * FB_LANES * sizeof(uint2)));
+    HIP_TRY(hipMalloc((void **)&d->d_fb_ss, (size_t)(FB_DEPTH_MAX + 2) * FB_LANES * sizeof(uint32_t)));
+    return ZF_OK;
+}
+
+int feed_token_bytes(zf_state *s, const uint8_t *bytes, int64_t n) {
+    if (n <= 0) return fail(ZF_ERR_REJECTED, "an empty token is never allowed");
+    const Tables &t = s->eng->tab;
+    const bool pruning = s->eng->opt.pruning != 0;
+    Chart &c = s->chart;
+    const uint32_t keep = c.n_sets();
+    int64_t created = 0;
+    bool accepted = false;
+    for (int64_t i = 0; i < n; i++) {
+        StepResult r = earley_step(t, c, bytes[i], !pruning, &created);
+        accepted = r.accepted;
+        // a byte is rejected when its set is empty; a completed sentence that cannot be extended
+        // is still fine as the last byte
+        if (!r.alive || (!r.kernel_nonempty && i + 1 < n)) {
+            c.truncate(keep);
+            return fail(ZF_ERR_REJECTED, "byte " + std::to_string(i) + " of the input cannot extend the prefix");
+        }
+    }
+    s->accepting = accepted;
+    s->items_created += created;
+    s->bytes_fed += n;
+    if (pruning) chart_compact(t, c);   // Compact: after Complete, before the next Predict
+    return ZF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *zf_strerror(int code) {
+    switch (code) {
+    case ZF_OK: return "ok";
+    case ZF_ERR_INVALID_ARG: return "invalid argument";
+    case ZF_ERR_GRAMMAR: return "invalid grammar";
+    case ZF_ERR_REJECTED: return "input rejected by the grammar";
+    case ZF_ERR_RANGE: return "token id out of range";
+    case ZF_ERR_DEVICE: return "device error";
+    case ZF_ERR_OOM: return "out of memory";
+    case ZF_ERR_OVERFLOW: return "Earley set exceeded the fallback arena";
+    }
+    return "unknown error";
+}
+const char *zf_last_error(void) { return g_err.c_str(); }
+
+int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_options *opt, zf_engine **out) {
+    if (!g || !v || !out || v->V < 0 || (v->V && !v->off)) return fail(ZF_ERR_INVALID_ARG, "null argument");
+    for (int i = 0; i < v->V; i++) {
+        int64_t n = v->off[i + 1] - v->off[i];
+        if (n < 0 || n > MAX_TOKEN_LEN_ON_DEVICE) return fail(ZF_ERR_INVALID_ARG, "token " + std::to_string(i) + ": length must be 0..255");
+    }
+    zf_engine *e = new (std::nothrow) zf_engine();
+    if (!e) return fail(ZF_ERR_OOM, "out of memory");
+    e->opt = opt ? *opt : zf_options{1, 0, 0};
+    if (e->opt.lane_item_cap <= 0 || e->opt.lane_item_cap > LANE_CAP_MAX) e->opt.lane_item_cap = LANE_CAP_MAX;
+    try {
+        if (!build_tables(g, e->tab)) { delete e; return ZF_ERR_GRAMMAR; }
+        e->V = v->V; e->W = (v->V + 31) / 32;
+        e->voc_off.assign(v->off, v->off + v->V + 1);
+        e->voc_bytes.assign(v->bytes, v->bytes + v->off[v->V]);
+        build_trie(v, e->trie);
+    } catch (const std::bad_alloc &) { delete e; return fail(ZF_ERR_OOM, "out of memory"); }
+    if (e->opt.device >= 0) {
+        int rc = setup_device(e);
+        if (rc != ZF_OK) { free_device(e->dev); delete e; return rc; }
+    }
+    *out = e;
+    return ZF_OK;
+}
+
+void zf_engine_destroy(zf_engine *e) {
+    if (!e) return;
+    free_device(e->dev);
+    delete e;
+}
+
+int zf_engine_get_info(const zf_engine *e, zf_engine_info *o) {
+    if (!e || !o) return fail(ZF_ERR_INVALID_ARG, "null argument");
+    o->V = e->V; o->W = e->W; o->n_nonterminals = e->tab.N; o->n_rules = e->tab.n_rules_kept; o->n_positions = e->tab.P;
+    o->n_dfa_states = e->tab.Q; o->n_byte_classes = e->tab.n_cls; o->n_trie_nodes = (int)e->trie.nodes.size();
+    o->n_strings = e->trie.n_strings; o->lane_item_cap = e->opt.lane_item_cap; o->device = e->opt.device;
+    return ZF_OK;
+}
+
+int zf_state_new(zf_engine *e, zf_state **out) {
+    if (!e || !out) return fail(ZF_ERR_INVALID_ARG, "null argument");
+    zf_state *s = new (std::nothrow) zf_state();
+    if (!s) return fail(ZF_ERR_OOM, "out of memory");
+    s->eng = e;
+    *out = s;
+    return zf_state_reset(s);
+}
+
+int zf_state_reset(zf_state *s) {
+    if (!s) return fail(ZF_ERR_INVALID_ARG, "null argument");
+    const Tables &t = s->eng->tab;
+    chart_init(t, s->chart);
+    // the empty prefix is a sentence iff the start symbol is nullable: then the initial set holds
+    // the completed start rule; drop completed items as every later set does (pruning on)
+    s->accepting = false;
+    Chart &c = s->chart;
+    size_t w = 0;
+    for (size_t i = 0; i < c.items.size(); i++) {
+        bool done = (t.sym[c.items[i].p] >> SYM_KIND_SHIFT) == SYM_END;
+        if (done) s->accepting = true;
+        if (!done || !s->eng->opt.pruning) c.items[w++] = c.items[i];
+    }
+    c.items.resize(w);
+    c.set_off[1] = (uint32_t)w;
+    s->items_created = 0; s->bytes_fed = 0;
+    return ZF_OK;
+}
+
+int zf_state_clone(const zf_state *s, zf_state **out) {
+    if (!s || !out) return fail(ZF_ERR_INVALID_ARG, "null argument");
+    zf_state *c = new (std::nothrow) zf_state(*s);
+    if (!c) return fail(ZF_ERR_OOM, "out of memory");
+    *out = c;
+    return ZF_OK;
+}
+
+void zf_state_destroy(zf_state *s) { delete s; }
+
+int zf_advance(zf_state *s, int32_t token) {
+    if (!s) return fail(ZF_ERR_INVALID_ARG, "null argument");
+    const zf_engine *e = s->eng;
+    if (token < 0 || token >= e->V) return fail(ZF_ERR_RANGE, "token id out of range");
+    return feed_token_bytes(s, e->voc_bytes.data() + e->voc_off[token], e->voc_off[token + 1] - e->voc_off[token]);
+}
+
+int zf_advance_bytes(zf_state *s, const uint8_t *bytes, int64_t n) {
+    if (!s || (n > 0 && !bytes) || n < 0) return fail(ZF_ERR_INVALID_ARG, "null argument");
+    if (n == 0) return ZF_OK;
+    return feed_token_bytes(s, bytes, n);
+}
+
+int zf_is_accepting(const zf_state *s, int32_t *out) {
+    if (!s || !out) return fail(ZF_ERR_INVALID_ARG, "null argument");
+    *out = s->accepting;
+    return ZF_OK;
+}
+
+int zf_state_stats(const zf_state *s, zf_stats *o) {
+    if (!s || !o) return fail(ZF_ERR_INVALID_ARG, "null argument");
+    o->n_sets = s->chart.n_sets(); o->n_items = (int64_t)s->chart.items.size();
+    o->items_created = s->items_created; o->bytes_fed = s->bytes_fed; o->accepting = s->accepting;
+    return ZF_OK;
+}
+
+int zf_state_chart(const zf_state *s, int32_t *items, int64_t *set_off) {
+    if (!s) return fail(ZF_ERR_INVALID_ARG, "null argument");
+    if (items) for (size_t i = 0; i < s->chart.items.size(); i++) {
+        items[3 * i] = s->chart.items[i].p; items[3 * i + 1] = (int32_t)s->chart.items[i].o; items[3 * i + 2] = s->chart.items[i].q;
+    }
+    if (set_off) for (size_t k = 0; k < s->chart.set_off.size(); k++) set_off[k] = s->chart.set_off[k];
+    return ZF_OK;
+}
+
+int zf_position_info(const zf_engine *e, int32_t p, int32_t *lhs, int32_t *rule, int32_t *dot) {
+    if (!e || p < 0 || p >= e->tab.P) return fail(ZF_ERR_INVALID_ARG, "bad position");
+    if (lhs) *lhs = e->tab.pos_lhs_orig[p];
+    if (rule) *rule = e->tab.pos_rule[p];
+    if (dot) *dot = e->tab.pos_dot[p];
+    return ZF_OK;
+}
+
+int zf_debug_host_mask(zf_engine *e, const zf_state *s, uint32_t *mask) {
+    if (!e || !s || !mask || s->eng != e) return fail(ZF_ERR_INVALID_ARG, "bad argument");
+    const Tables &t = e->tab;
+    const Trie &tr = e->trie;
+    Chart c = s->chart;
+    const uint32_t m0 = c.n_sets();
+    std::vector<uint8_t> ok(tr.n_strings, 0);
+    for (uint32_t i = 0; i < tr.nodes.size();) {
+        const TrieNode &nd = tr.nodes[i];
+        c.truncate(m0 + nd.depth - 1);
+        StepResult r = earley_step(t, c, nd.byte, false, nullptr);
+        if (nd.has_string && r.alive) ok[nd.rank] = 1;
+        i = r.kernel_nonempty ? i + 1 : nd.skip;
+    }
+    memset(mask, 0, sizeof(uint32_t) * e->W);
+    for (int v = 0; v < e->V; v++) {
+        uint32_t r = tr.rank_of[v];
+        if (r != 0xFFFFFFFFu && ok[r]) mask[v >> 5] |= 1u << (v & 31);
+    }
+    return ZF_OK;
+}
+
+int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream) {
+    if (!e || !states || batch <= 0 || !d_mask) return fail(ZF_ERR_INVALID_ARG, "bad argument");
+    DeviceSide *d = e->dev;
+    if (!d) return fail(ZF_ERR_DEVICE, "engine was compiled without a device (device = -1)");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    HIP_TRY(hipSetDevice(d->device));
+    // ---- pack the charts: [RowChart x batch][set offsets][items] ----
+    size_t n_off = 0, n_items = 0;
+    for (int b = 0; b < batch; b++) {
+        if (!states[b] || states[b]->eng != e) return fail(ZF_ERR_INVALID_ARG, "state " + std::to_string(b) + " is null or belongs to another engine");
+        n_off += states[b]->chart.set_off.size();
+        n_items += states[b]->chart.items.size();
+    }
+    auto align16 = [](size_t x) { return (x + 15) & ~(size_t)15; };
+    const size_t off_rows = 0, off_so = align16(sizeof(RowChart) * batch), off_items = align16(off_so + 4 * n_off);
+    const size_t total = off_items + sizeof(Item) * n_items + 16;
+    if (total > d->stage_cap) {
+        if (d->h_stage) (void)hipHostFree(d->h_stage);
+        if (d->d_chart) (void)hipFree(d->d_chart);
+        d->h_stage = nullptr; d->d_chart = nullptr; d->stage_cap = d->chart_cap = 0;
+        size_t cap = total * 2 + 4096;
+        HIP_TRY(hipHostMalloc(&d->h_stage, cap, hipHostMallocDefault));
+        HIP_TRY(hipMalloc(&d->d_chart, cap));
+        d->stage_cap = d->chart_cap = cap;
+    }
+    {
+        uint8_t *h = (uint8_t *)d->h_stage;
+        RowChart *rows = (RowChart *)(h + off_rows);
+        uint32_t *so = (uint32_t *)(h + off_so);
+        Item *items = (Item *)(h + off_items);
+        uint32_t so_at = 0, it_at = 0;
+        for (int b = 0; b < batch; b++) {
+            const Chart &c = states[b]->chart;
+            rows[b] = RowChart{c.n_sets(), so_at, it_at, 0};
+            memcpy(so + so_at, c.set_off.data(), 4 * c.set_off.size());
+            if (!c.items.empty()) memcpy(items + it_at, c.items.data(), sizeof(Item) * c.items.size());
+            so_at += (uint32_t)c.set_off.size(); it_at += (uint32_t)c.items.size();
+        }
+    }
+    HIP_TRY(hipMemcpyAsync(d->d_chart, d->h_stage, total, hipMemcpyHostToDevice, stream));
+    // ---- per-call device buffers ----
+    const size_t need_rank = (size_t)batch * d->tab.Wr;
+    if (need_rank > d->rank_cap) {
+        if (d->d_rank_mask) (void)hipFree(d->d_rank_mask);
+        if (d->d_overflow) (void)hipFree(d->d_overflow);
+        d->d_rank_mask = nullptr; d->d_overflow = nullptr; d->rank_cap = d->overflow_cap = 0;
+        HIP_TRY(hipMalloc((void **)&d->d_rank_mask, need_rank * 4 + 16));
+        HIP_TRY(hipMalloc((void **)&d->d_overflow, need_rank * sizeof(uint2) + 16));
+        d->rank_cap = d->overflow_cap = need_rank;
+    }
+    MaskArgs a{};
+    a.tab = d->tab;
+    a.rows = (const RowChart *)((uint8_t *)d->d_chart + off_rows);
+    a.set_off = (const uint32_t *)((uint8_t *)d->d_chart + off_so);
+    a.items = (const Item *)((uint8_t *)d->d_chart + off_items);
+    a.rank_mask = d->d_rank_mask;
+    a.out_mask = d_mask;
+    a.counters = d->d_counters;
+    a.overflow_list = d->d_overflow;
+    a.overflow_cap = (uint32_t)d->overflow_cap;
+    a.fb_items = d->d_fb_items;
+    a.fb_set_start = d->d_fb_ss;
+    a.batch = batch;
+    a.lane_cap = e->opt.lane_item_cap;
+    HIP_TRY(hipMemsetAsync(d->d_counters, 0, 16, stream));
+    if (d->tab.n_chunks > 0) {
+        HIP_TRY(launch_mask_main(a, stream));
+        HIP_TRY(launch_mask_fallback(a, stream));
+    }
+    HIP_TRY(launch_permute(a, stream));
+    HIP_TRY(hipMemcpyAsync(d->h_counters, d->d_counters, 16, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    d->report.overflow_chunks = d->h_counters[0];
+    d->report.chart_bytes = (int64_t)total;
+    if (d->h_counters[1]) return fail(ZF_ERR_OVERFLOW, std::to_string(d->h_counters[1]) + " trie chunks exceeded the fallback arena");
+    return ZF_OK;
+}
+
+int zf_last_mask_report(const zf_engine *e, zf_mask_report *out) {
+    if (!e || !out || !e->dev) return fail(ZF_ERR_INVALID_ARG, "bad argument");
+    *out = e->dev->report;
+    return ZF_OK;
+}
+
+int zf_apply_mask(zf_engine *e, const void *d_logits, void *d_out, int32_t dtype, int32_t batch,
+                  int64_t row_stride, const uint32_t *d_mask, void *hip_stream) {
+    if (!e || !d_logits || !d_out || !d_mask || batch <= 0 || (dtype != 0 && dtype != 1) || row_stride < e->V)
+        return fail(ZF_ERR_INVALID_ARG, "bad argument");
+    if (!e->dev) return fail(ZF_ERR_DEVICE, "engine was compiled without a device (device = -1)");
+    HIP_TRY(hipSetDevice(e->dev->device));
+    if (e->V == 0) return ZF_OK;
+    HIP_TRY(launch_apply_mask(d_logits, d_out, dtype, batch, row_stride, e->V, e->W, d_mask, (hipStream_t)hip_stream));
+    return ZF_OK;
+}
+
+}  // extern "C"

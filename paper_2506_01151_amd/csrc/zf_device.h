@@ -1,0 +1,72 @@
+// Plain-data layouts shared by the host code and the HIP kernels.
+#pragma once
+#include <stdint.h>
+
+namespace zf {
+
+// Encoding of the symbol that follows the dot at a dotted position.
+enum : uint16_t {
+    SYM_KIND_SHIFT = 14,
+    SYM_NT = 0,        // low 13 bits: nonterminal id; bit 13: the nonterminal is nullable
+    SYM_TERM = 1,      // low 14 bits: terminal id
+    SYM_END = 2,       // dot at the end of the rule; low 14 bits: lhs nonterminal
+    SYM_NULLABLE_BIT = 1u << 13,
+    SYM_ID_MASK_NT = (1u << 13) - 1,
+    SYM_ID_MASK = (1u << 14) - 1,
+    DFA_DEAD = 0xFFFF,
+};
+enum : uint8_t { QF_ACCEPT = 1, QF_CONT = 2 };
+
+// One Earley item.  p: dotted position (index into sym[]); q: DFA state when the postdot
+// symbol is a terminal (global state numbering, so q also names the terminal), else 0;
+// o: index of the set the rule started in (the classic origin).
+struct Item {
+    uint16_t p, q;
+    uint32_t o;
+};
+
+// One trie node, preorder layout.  skip = index of the first node after this subtree.
+// rank = number of string-carrying nodes before this one (so a node that carries a string
+// owns bit `rank` of the rank-ordered verdict bitmap).
+struct TrieNode {
+    uint32_t skip;
+    uint32_t rank;
+    uint8_t byte, depth, has_string, pad;
+    uint32_t pad2;
+};
+
+static const int MAX_TOKEN_LEN_ON_DEVICE = 255;   // deeper nodes never occur: depth is a uint8
+static const int CHUNK_RANKS = 32;                // one lane walks the nodes of 32 strings = one word
+static const int CHUNK_ANC = 16;                  // ancestors stored per chunk (longer paths use parent links)
+
+// Immutable per-engine tables in device memory.
+struct DeviceTables {
+    const uint16_t *sym;        // [P]
+    const uint16_t *end_pos;    // [N] position whose sym is END|X
+    const uint8_t *cls;         // [256] byte -> class
+    const uint16_t *delta;      // [Q][n_cls]
+    const uint8_t *qflags;      // [Q]
+    const uint16_t *term_start; // [T]
+    const uint32_t *scan_off;   // [N*n_cls+1] CSR into scan_list
+    const uint32_t *scan_list;  // p | q' << 16
+    const uint32_t *comp_off;   // [N*N+1] CSR into comp_list
+    const uint16_t *comp_list;  // advanced positions
+    const TrieNode *nodes;      // [n_nodes]
+    const uint32_t *parent;     // [n_nodes] parent node index, 0xFFFFFFFF for depth-1 nodes
+    const uint32_t *chunk_begin; // [n_chunks] first node of the chunk
+    const uint32_t *chunk_end;   // [n_chunks] one past the last string node of the chunk
+    const uint32_t *chunk_anc;   // [n_chunks][CHUNK_ANC] ancestors of the chunk's first node, depth 1 first
+    const uint32_t *rank_of;    // [V] rank of token v's string, 0xFFFFFFFF for the empty token
+    int32_t N, n_cls, n_nodes, n_chunks, n_strings, V, W, Wr;
+};
+
+// Per-row header of the uploaded chart.  Items of set k: items[item_base + set_off[set_base+k] ..
+// item_base + set_off[set_base+k+1]).
+struct RowChart {
+    uint32_t n_sets;     // m; the last set (m-1) is the current one
+    uint32_t set_base;   // index into the shared set_off array
+    uint32_t item_base;  // index into the shared item array
+    uint32_t pad;
+};
+
+}  // namespace zf

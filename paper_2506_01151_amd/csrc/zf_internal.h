@@ -1,0 +1,94 @@
+// Host-side structures of the library (grammar tables, trie, chart, engine, state).
+#pragma once
+#include <cstdint>
+#include <string>
+#include <vector>
+#include "zf_device.h"
+#include "../../include/zapformat.h"
+
+namespace zf {
+
+void set_error(const std::string &msg);   // thread-local detail string
+
+// ---- byte-level DFA of one terminal ---------------------------------------------------
+struct Dfa {
+    // trans[state*256 + byte] = next state or -1; state 0 is the start state.  Every state can
+    // reach an accepting state (trimmed), so "alive" means "the terminal can still finish".
+    std::vector<int32_t> trans;
+    std::vector<uint8_t> accept;
+    int n_states() const { return (int)accept.size(); }
+};
+// Returns false and sets the error string on a syntax error.
+bool regex_to_dfa(const uint8_t *src, size_t n, Dfa &out);
+void literal_to_dfa(const uint8_t *bytes, size_t n, Dfa &out);
+
+// ---- compiled grammar tables ------------------------------------------------------------
+struct Tables {
+    int N = 0;                        // nonterminals kept + 1 (the added start symbol S' = N-1)
+    int T = 0;                        // terminals
+    int P = 0;                        // dotted positions
+    int Q = 0;                        // DFA states over all terminals
+    int n_cls = 0;
+    int start_pos = 0;                // position of (S' -> . S)
+    std::vector<uint16_t> sym;        // [P]
+    std::vector<uint16_t> lhs_of;     // [P] lhs of the rule that contains the position
+    std::vector<uint16_t> end_pos;    // [N]
+    uint8_t cls[256];
+    std::vector<uint16_t> delta;      // [Q*n_cls]
+    std::vector<uint8_t> qflags;      // [Q]
+    std::vector<uint16_t> term_start; // [T]
+    std::vector<uint32_t> scan_off, scan_list;
+    std::vector<uint32_t> comp_off;
+    std::vector<uint16_t> comp_list;
+    std::vector<uint8_t> reach;       // [N*N] reach[Y*N+X] = 1 iff X can be a left corner of Y (X in PRED(Y))
+    // for zf_position_info: original rule index / lhs / dot of each position (-1 for added ones)
+    std::vector<int32_t> pos_rule, pos_dot, pos_lhs_orig;
+    int n_rules_kept = 0;
+};
+bool build_tables(const zf_grammar_desc *g, Tables &t);
+
+// ---- vocabulary trie ------------------------------------------------------------------------
+struct Trie {
+    std::vector<TrieNode> nodes;      // preorder
+    std::vector<uint32_t> parent;
+    std::vector<uint32_t> chunk_begin, chunk_end, chunk_anc;
+    std::vector<uint32_t> rank_of;    // [V]
+    int n_strings = 0;
+};
+void build_trie(const zf_vocab_desc *v, Trie &t);
+
+// ---- chart --------------------------------------------------------------------------------------
+struct Chart {
+    std::vector<Item> items;
+    std::vector<uint32_t> set_off{0};   // n_sets + 1 entries
+    uint32_t n_sets() const { return (uint32_t)set_off.size() - 1; }
+    void truncate(uint32_t n) { set_off.resize(n + 1); items.resize(set_off[n]); }
+};
+struct StepResult { bool alive, kernel_nonempty, accepted; };
+// Scan `byte` from the last set into a new set and close it (Complete + implicit Predict).
+// The new set is appended even when it ends up empty.  keep_completed keeps the end-of-rule
+// items in the set (pruning off); otherwise they are dropped once the set is closed.
+StepResult earley_step(const Tables &t, Chart &c, uint8_t byte, bool keep_completed, int64_t *items_created);
+void chart_init(const Tables &t, Chart &c);
+// ZapFormat Compact: keep only what the last set can still reach through Complete look-ups.
+void chart_compact(const Tables &t, Chart &c);
+
+}  // namespace zf
+
+struct zf_engine {
+    zf::Tables tab;
+    zf::Trie trie;
+    zf_options opt;
+    int32_t V = 0, W = 0;
+    std::vector<int64_t> voc_off;
+    std::vector<uint8_t> voc_bytes;
+    bool start_nullable = false;
+    struct DeviceSide *dev = nullptr;   // null when compiled with device = -1
+};
+
+struct zf_state {
+    zf_engine *eng;
+    zf::Chart chart;
+    bool accepting = false;
+    int64_t items_created = 0, bytes_fed = 0;
+};

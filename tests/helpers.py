@@ -1,0 +1,40 @@
+"""Shared helpers for the parity tests (harness only: sampling, bookkeeping)."""
+import numpy as np
+from workloads import vocab as wvocab
+from workloads.configs import pick_set_bit
+
+
+def popcount(words) -> int:
+    return int(np.unpackbits(np.ascontiguousarray(words).view(np.uint8)).sum())
+
+
+class OracleRun:
+    """Drives oracle states along a seeded trajectory: at every step the next token is drawn
+    uniformly from the oracle-valid mask; a row whose mask is empty (its sentence is complete
+    and cannot be extended) is reset, which stands for 'query finished, next query'."""
+
+    def __init__(self, oracle, tokens, samplers, n_threads=8):
+        self.o, self.tokens = oracle, tokens
+        self.off, self.data = wvocab.vocab_csr(tokens)
+        self.samplers = samplers
+        self.states = [oracle.new_state() for _ in samplers]
+        self.n_threads = n_threads
+        self.resets = 0
+
+    def masks(self):
+        return np.stack([s.mask(self.off, self.data, self.n_threads) for s in self.states])
+
+    def step(self, masks):
+        """Sample one token per row from `masks` and feed it.  Returns token ids (-1 = reset)."""
+        out = []
+        for b, s in enumerate(self.states):
+            n = popcount(masks[b])
+            if n == 0:
+                self.states[b] = self.o.new_state()
+                self.resets += 1
+                out.append(-1)
+                continue
+            t = pick_set_bit(masks[b], self.samplers[b].below(n))
+            assert s.feed_bytes(self.tokens[t])
+            out.append(t)
+        return out
