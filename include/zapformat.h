@@ -86,9 +86,11 @@ typedef struct {
     int32_t lane_item_cap, device;
 } zf_engine_info;
 
-typedef struct {               /* device time of the last zf_compute_mask, for reporting only */
+typedef struct {               /* facts about the last zf_compute_mask, for reporting only */
     int64_t overflow_chunks;   /* trie chunks handed to the fallback pass in the last call */
     int64_t chart_bytes;       /* bytes uploaded for the last call */
+    float main_ms, fallback_ms, permute_ms; /* kernel durations from HIP events on the call's
+                                               stream; 0 unless zf_engine_set_profiling is on */
 } zf_mask_report;
 
 /* compile(grammar rules, vocab byte strings): clean the grammar (useless rules, nullable
@@ -125,6 +127,9 @@ int zf_position_info(const zf_engine *e, int32_t position, int32_t *lhs, int32_t
 int zf_compute_mask(zf_engine *e, zf_state *const *states /* host array */, int32_t batch,
                     uint32_t *d_mask, void *hip_stream);
 int zf_last_mask_report(const zf_engine *e, zf_mask_report *out);
+/* on != 0: zf_compute_mask brackets each of its kernels with HIP events (a few microseconds
+ * of extra host time per call) and zf_last_mask_report returns their durations. */
+int zf_engine_set_profiling(zf_engine *e, int32_t on);
 
 /* apply_mask(logits): out[b][v] = bit(b, v) ? logits[b][v] (bit copy) : -inf (Section 3.3).
  * d_logits / d_out: device, [batch][row_stride_elems] with V valid elements per row; d_out may
@@ -135,6 +140,10 @@ int zf_apply_mask(zf_engine *e, const void *d_logits, void *d_out, int32_t dtype
 /* Diagnostic: the same verdicts computed on the host from the compiled tables (trie, DFAs,
  * chart).  Never used by zf_compute_mask; exists so the host logic can be tested without a GPU. */
 int zf_debug_host_mask(zf_engine *e, const zf_state *s, uint32_t *mask /* host [W] */);
+/* Same, plus counters of the walk in stats[0..4] (host): byte steps taken, steps that left a
+ * live set, largest item count of one trie path, largest single set, chunks whose path
+ * outgrows lane_item_cap (an estimate of what the fallback pass receives). */
+int zf_debug_host_mask_stats(zf_engine *e, const zf_state *s, uint32_t *mask /* host [W] */, int64_t *stats);
 
 #ifdef __cplusplus
 }

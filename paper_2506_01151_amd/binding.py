@@ -43,13 +43,14 @@ class EngineInfo(ctypes.Structure):
 
 
 class MaskReport(ctypes.Structure):
-    _fields_ = [("overflow_chunks", c_i64), ("chart_bytes", c_i64)]
+    _fields_ = [("overflow_chunks", c_i64), ("chart_bytes", c_i64), ("main_ms", ctypes.c_float),
+                ("fallback_ms", ctypes.c_float), ("permute_ms", ctypes.c_float)]
 
 
 EXPORTS = ["zf_strerror", "zf_last_error", "zf_compile", "zf_engine_destroy", "zf_engine_get_info",
            "zf_state_new", "zf_state_clone", "zf_state_reset", "zf_state_destroy", "zf_advance",
            "zf_advance_bytes", "zf_is_accepting", "zf_state_stats", "zf_state_chart", "zf_position_info",
-           "zf_compute_mask", "zf_last_mask_report", "zf_apply_mask", "zf_debug_host_mask"]
+           "zf_compute_mask", "zf_last_mask_report", "zf_engine_set_profiling", "zf_apply_mask", "zf_debug_host_mask", "zf_debug_host_mask_stats"]
 
 
 class ZfError(RuntimeError):
@@ -85,8 +86,10 @@ def load_library():
     L.zf_position_info.argtypes = [c_vp, c_i32, ctypes.POINTER(c_i32), ctypes.POINTER(c_i32), ctypes.POINTER(c_i32)]
     L.zf_compute_mask.argtypes = [c_vp, c_vp, c_i32, c_vp, c_vp]
     L.zf_last_mask_report.argtypes = [c_vp, c_vp]
+    L.zf_engine_set_profiling.argtypes = [c_vp, c_i32]
     L.zf_apply_mask.argtypes = [c_vp, c_vp, c_vp, c_i32, c_i32, c_i64, c_vp, c_vp]
     L.zf_debug_host_mask.argtypes = [c_vp, c_vp, c_vp]
+    L.zf_debug_host_mask_stats.argtypes = [c_vp, c_vp, c_vp, c_vp]
     _lib = L
     return L
 
@@ -149,6 +152,12 @@ class State:
                 out.append((k, int(items[i, 0]), int(items[i, 1]), int(items[i, 2])))
         return out, int(st.n_sets)
 
+    def debug_host_mask_stats(self):
+        out = np.zeros(self.engine.W, dtype=np.uint32)
+        st = np.zeros(8, dtype=np.int64)
+        _check(_lib.zf_debug_host_mask_stats(self.engine.h, self.h, out.ctypes.data, st.ctypes.data))
+        return out, dict(steps=int(st[0]), alive=int(st[1]), max_path=int(st[2]), max_set=int(st[3]), chunks_over=int(st[4]))
+
     def debug_host_mask(self) -> np.ndarray:
         out = np.zeros(self.engine.W, dtype=np.uint32)
         _check(_lib.zf_debug_host_mask(self.engine.h, self.h, out.ctypes.data))
@@ -197,6 +206,9 @@ class Engine:
     def compute_mask(self, states, d_mask_ptr: int, stream: int = 0):
         arr = (c_vp * len(states))(*[s.h for s in states])
         _check(_lib.zf_compute_mask(self.h, arr, len(states), d_mask_ptr, stream))
+
+    def set_profiling(self, on: bool):
+        _check(_lib.zf_engine_set_profiling(self.h, int(on)))
 
     def mask_report(self) -> MaskReport:
         r = MaskReport()

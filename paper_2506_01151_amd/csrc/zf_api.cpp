@@ -28,6 +28,8 @@ struct DeviceSide {
     uint2 *d_fb_items = nullptr;
     uint32_t *d_fb_ss = nullptr;
     zf_mask_report report{};
+    bool profiling = false;
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
 };
 
 namespace {
@@ -58,6 +60,7 @@ void free_device(DeviceSide *d) {
     if (d->h_counters) (void)hipHostFree(d->h_counters);
     if (d->d_fb_items) (void)hipFree(d->d_fb_items);
     if (d->d_fb_ss) (void)hipFree(d->d_fb_ss);
+    for (auto &ev : d->ev) if (ev) (void)hipEventDestroy(ev);
     delete d;
 }
 
@@ -253,8 +256,12 @@ int zf_position_info(const zf_engine *e, int32_t p, int32_t *lhs, int32_t *rule,
     return ZF_OK;
 }
 
-int zf_debug_host_mask(zf_engine *e, const zf_state *s, uint32_t *mask) {
+int zf_debug_host_mask(zf_engine *e, const zf_state *s, uint32_t *mask) { return zf_debug_host_mask_stats(e, s, mask, nullptr); }
+
+int zf_debug_host_mask_stats(zf_engine *e, const zf_state *s, uint32_t *mask, int64_t *stats) {
     if (!e || !s || !mask || s->eng != e) return fail(ZF_ERR_INVALID_ARG, "bad argument");
+    int64_t n_steps = 0, n_alive = 0, max_path = 0, max_set = 0, chunks_over = 0;
+    std::vector<uint8_t> chunk_over((e->trie.n_strings + CHUNK_RANKS - 1) / CHUNK_RANKS + 1, 0);
     const Tables &t = e->tab;
     const Trie &tr = e->trie;
     Chart c = s->chart;
@@ -265,8 +272,15 @@ int zf_debug_host_mask(zf_engine *e, const zf_state *s, uint32_t *mask) {
         c.truncate(m0 + nd.depth - 1);
         StepResult r = earley_step(t, c, nd.byte, false, nullptr);
         if (nd.has_string && r.alive) ok[nd.rank] = 1;
+        n_steps++; n_alive += r.alive;
+        int64_t path = (int64_t)c.items.size() - c.set_off[m0];
+        int64_t last = (int64_t)c.items.size() - c.set_off[c.n_sets() - 1];
+        if (path > max_path) max_path = path;
+        if (last > max_set) max_set = last;
+        if (path > e->opt.lane_item_cap && !chunk_over[nd.rank / CHUNK_RANKS]) { chunk_over[nd.rank / CHUNK_RANKS] = 1; chunks_over++; }
         i = r.kernel_nonempty ? i + 1 : nd.skip;
     }
+    if (stats) { stats[0] = n_steps; stats[1] = n_alive; stats[2] = max_path; stats[3] = max_set; stats[4] = chunks_over; }
     memset(mask, 0, sizeof(uint32_t) * e->W);
     for (int v = 0; v < e->V; v++) {
         uint32_t r = tr.rank_of[v];
@@ -340,13 +354,22 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     a.batch = batch;
     a.lane_cap = e->opt.lane_item_cap;
     HIP_TRY(hipMemsetAsync(d->d_counters, 0, 16, stream));
-    if (d->tab.n_chunks > 0) {
-        HIP_TRY(launch_mask_main(a, stream));
-        HIP_TRY(launch_mask_fallback(a, stream));
-    }
+    const bool prof = d->profiling;
+    if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
+    if (d->tab.n_chunks > 0) HIP_TRY(launch_mask_main(a, stream));
+    if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));
+    if (d->tab.n_chunks > 0) HIP_TRY(launch_mask_fallback(a, stream));
+    if (prof) HIP_TRY(hipEventRecord(d->ev[2], stream));
     HIP_TRY(launch_permute(a, stream));
+    if (prof) HIP_TRY(hipEventRecord(d->ev[3], stream));
     HIP_TRY(hipMemcpyAsync(d->h_counters, d->d_counters, 16, hipMemcpyDeviceToHost, stream));
     HIP_TRY(hipStreamSynchronize(stream));
+    d->report.main_ms = d->report.fallback_ms = d->report.permute_ms = 0.f;
+    if (prof) {
+        HIP_TRY(hipEventElapsedTime(&d->report.main_ms, d->ev[0], d->ev[1]));
+        HIP_TRY(hipEventElapsedTime(&d->report.fallback_ms, d->ev[1], d->ev[2]));
+        HIP_TRY(hipEventElapsedTime(&d->report.permute_ms, d->ev[2], d->ev[3]));
+    }
     d->report.overflow_chunks = d->h_counters[0];
     d->report.chart_bytes = (int64_t)total;
     if (d->h_counters[1]) return fail(ZF_ERR_OVERFLOW, std::to_string(d->h_counters[1]) + " trie chunks exceeded the fallback arena");
@@ -356,6 +379,14 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
 int zf_last_mask_report(const zf_engine *e, zf_mask_report *out) {
     if (!e || !out || !e->dev) return fail(ZF_ERR_INVALID_ARG, "bad argument");
     *out = e->dev->report;
+    return ZF_OK;
+}
+
+int zf_engine_set_profiling(zf_engine *e, int32_t on) {
+    if (!e || !e->dev) return fail(ZF_ERR_INVALID_ARG, "bad argument");
+    HIP_TRY(hipSetDevice(e->dev->device));
+    if (on) for (auto &ev : e->dev->ev) if (!ev) HIP_TRY(hipEventCreate(&ev));
+    e->dev->profiling = on != 0;
     return ZF_OK;
 }
 
