@@ -29,7 +29,7 @@ class VocabDesc(ctypes.Structure):
 
 
 class Options(ctypes.Structure):
-    _fields_ = [("pruning", c_i32), ("lane_item_cap", c_i32), ("device", c_i32)]
+    _fields_ = [("pruning", c_i32), ("lane_item_cap", c_i32), ("device", c_i32), ("chunk_strings", c_i32), ("fallback_item_cap", c_i32)]
 
 
 class Stats(ctypes.Structure):
@@ -43,7 +43,7 @@ class EngineInfo(ctypes.Structure):
 
 
 class MaskReport(ctypes.Structure):
-    _fields_ = [("overflow_chunks", c_i64), ("chart_bytes", c_i64), ("main_ms", ctypes.c_float),
+    _fields_ = [("overflow_chunks", c_i64), ("overflow_chunks_level3", c_i64), ("chart_bytes", c_i64), ("main_ms", ctypes.c_float),
                 ("fallback_ms", ctypes.c_float), ("permute_ms", ctypes.c_float)]
 
 
@@ -167,7 +167,7 @@ class State:
 class Engine:
     """compile(grammar rules, vocab byte strings)."""
 
-    def __init__(self, grammar, vocab_tokens, *, pruning=True, lane_item_cap=0, device=0):
+    def __init__(self, grammar, vocab_tokens, *, pruning=True, lane_item_cap=0, device=0, chunk_strings=0, fallback_item_cap=0):
         load_library()
         csr = grammar.csr()
         self._keep = csr
@@ -179,7 +179,7 @@ class Engine:
         np.cumsum([len(t) for t in vocab_tokens], out=off[1:])
         data = np.frombuffer(b"".join(vocab_tokens) or b"\0", dtype=np.uint8).copy()
         vd = VocabDesc(len(vocab_tokens), off.ctypes.data, data.ctypes.data)
-        opt = Options(int(bool(pruning)), lane_item_cap, device)
+        opt = Options(int(bool(pruning)), lane_item_cap, device, chunk_strings, fallback_item_cap)
         h = c_vp()
         self.h = None
         _check(_lib.zf_compile(ctypes.byref(gd), ctypes.byref(vd), ctypes.byref(opt), ctypes.byref(h)))

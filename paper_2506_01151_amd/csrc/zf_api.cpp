@@ -22,7 +22,8 @@ struct DeviceSide {
     void *d_chart = nullptr; size_t chart_cap = 0;
     void *h_stage = nullptr; size_t stage_cap = 0;   // pinned
     uint32_t *d_rank_mask = nullptr; size_t rank_cap = 0;
-    uint2 *d_overflow = nullptr; size_t overflow_cap = 0;
+    uint2 *d_overflow = nullptr, *d_overflow2 = nullptr; size_t overflow_cap = 0;
+    int mode = 2;
     uint32_t *d_counters = nullptr;
     uint32_t *h_counters = nullptr;      // pinned
     uint2 *d_fb_items = nullptr;
@@ -38,13 +39,16 @@ int fail(int code, const std::string &m) { set_error(m); return code; }
 #define HIP_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return fail(ZF_ERR_DEVICE, std::string(#expr) + ": " + hipGetErrorString(e_)); } while (0)
 
 template <class Tv>
-int upload(DeviceSide *d, const std::vector<Tv> &v, const Tv **out) {
+int upload(DeviceSide *d, const std::vector<Tv> &v, const Tv **out, uint32_t *bytes_out = nullptr) {
+    // padded to a multiple of 16 bytes (zero filled) so that blocks can stage it with 16-byte copies
     void *p = nullptr;
-    size_t bytes = std::max<size_t>(v.size() * sizeof(Tv), 16);
+    size_t bytes = (std::max<size_t>(v.size() * sizeof(Tv), 16) + 15) & ~(size_t)15;
     HIP_TRY(hipMalloc(&p, bytes));
     d->owned.push_back(p);
+    HIP_TRY(hipMemset(p, 0, bytes));
     if (!v.empty()) HIP_TRY(hipMemcpy(p, v.data(), v.size() * sizeof(Tv), hipMemcpyHostToDevice));
     *out = (const Tv *)p;
+    if (bytes_out) *bytes_out = (uint32_t)bytes;
     return ZF_OK;
 }
 
@@ -56,6 +60,7 @@ void free_device(DeviceSide *d) {
     if (d->h_stage) (void)hipHostFree(d->h_stage);
     if (d->d_rank_mask) (void)hipFree(d->d_rank_mask);
     if (d->d_overflow) (void)hipFree(d->d_overflow);
+    if (d->d_overflow2) (void)hipFree(d->d_overflow2);
     if (d->d_counters) (void)hipFree(d->d_counters);
     if (d->h_counters) (void)hipHostFree(d->h_counters);
     if (d->d_fb_items) (void)hipFree(d->d_fb_items);
@@ -75,19 +80,22 @@ int setup_device(zf_engine *e) {
     DeviceTables &T = d->tab;
     int rc;
     std::vector<uint8_t> cls(t.cls, t.cls + 256);
-#define UP(field, vec) if ((rc = upload(d, vec, &T.field)) != ZF_OK) return rc
-    UP(sym, t.sym); UP(end_pos, t.end_pos); UP(cls, cls); UP(delta, t.delta); UP(qflags, t.qflags);
-    UP(term_start, t.term_start); UP(scan_off, t.scan_off); UP(scan_list, t.scan_list);
-    UP(comp_off, t.comp_off); UP(comp_list, t.comp_list);
-    UP(nodes, tr.nodes); UP(parent, tr.parent); UP(chunk_begin, tr.chunk_begin); UP(chunk_end, tr.chunk_end);
-    UP(chunk_anc, tr.chunk_anc); UP(rank_of, tr.rank_of);
+#define UP(field, vec, bytes) if ((rc = upload(d, vec, &T.field, bytes)) != ZF_OK) return rc
+    UP(sym, t.sym, &T.small_bytes[0]); UP(advpq, t.advpq, &T.small_bytes[1]); UP(cls, cls, &T.small_bytes[2]);
+    UP(qinfo, t.qinfo, &T.small_bytes[3]); UP(scan_off, t.scan_off, &T.small_bytes[4]); UP(comp_off, t.comp_off, &T.small_bytes[5]);
+    UP(delta, t.delta_dense, &T.big_bytes[0]); UP(scan_list, t.scan_list, &T.big_bytes[1]); UP(comp_list, t.comp_list, &T.big_bytes[2]);
+    UP(nodes, tr.nodes, nullptr); UP(parent, tr.parent, nullptr); UP(chunk_begin, tr.chunk_begin, nullptr); UP(chunk_end, tr.chunk_end, nullptr);
+    UP(chunk_anc, tr.chunk_anc, nullptr); UP(rank_of, tr.rank_of, nullptr);
 #undef UP
-    T.N = t.N; T.n_cls = t.n_cls; T.n_nodes = (int)tr.nodes.size(); T.n_chunks = (int)tr.chunk_begin.size();
-    T.n_strings = tr.n_strings; T.V = e->V; T.W = e->W; T.Wr = T.n_chunks;
+    T.N = t.N; T.n_cls = t.n_cls; T.end_base = t.end_base; T.n_nodes = (int)tr.nodes.size(); T.n_chunks = (int)tr.chunk_begin.size();
+    T.n_strings = tr.n_strings; T.V = e->V; T.W = e->W; T.chunk_ranks = tr.chunk_ranks;
+    T.Wr = (T.n_chunks * tr.chunk_ranks + 31) / 32;
+    d->mode = choose_table_mode(T);
+    HIP_TRY(prepare_kernels());
     HIP_TRY(hipMalloc((void **)&d->d_counters, 16));
     HIP_TRY(hipHostMalloc((void **)&d->h_counters, 16, hipHostMallocDefault));
-    HIP_TRY(hipMalloc((void **)&d->d_fb_items, (size_t)FB_ITEMS_PER_LANE * FB_LANES * sizeof(uint2)));
-    HIP_TRY(hipMalloc((void **)&d->d_fb_ss, (size_t)(FB_DEPTH_MAX + 2) * FB_LANES * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc((void **)&d->d_fb_items, (size_t)FB3_ITEMS_PER_LANE * FB3_LANES * sizeof(uint2)));
+    HIP_TRY(hipMalloc((void **)&d->d_fb_ss, (size_t)(FB_DEPTH_MAX + 2) * FB3_LANES * sizeof(uint32_t)));
     return ZF_OK;
 }
 
@@ -143,14 +151,17 @@ int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_option
     }
     zf_engine *e = new (std::nothrow) zf_engine();
     if (!e) return fail(ZF_ERR_OOM, "out of memory");
-    e->opt = opt ? *opt : zf_options{1, 0, 0};
-    if (e->opt.lane_item_cap <= 0 || e->opt.lane_item_cap > LANE_CAP_MAX) e->opt.lane_item_cap = LANE_CAP_MAX;
+    e->opt = opt ? *opt : zf_options{1, 0, 0, 0, 0};
+    if (e->opt.lane_item_cap <= 0) e->opt.lane_item_cap = LANE_CAP_DEFAULT;
+    if (e->opt.lane_item_cap > LANE_CAP_MAX) e->opt.lane_item_cap = LANE_CAP_MAX;
+    if (e->opt.fallback_item_cap <= 0 || e->opt.fallback_item_cap > FB2_CAP) e->opt.fallback_item_cap = FB2_CAP;
+    if (e->opt.chunk_strings != 8 && e->opt.chunk_strings != 16 && e->opt.chunk_strings != 32) e->opt.chunk_strings = 8;
     try {
         if (!build_tables(g, e->tab)) { delete e; return ZF_ERR_GRAMMAR; }
         e->V = v->V; e->W = (v->V + 31) / 32;
         e->voc_off.assign(v->off, v->off + v->V + 1);
         e->voc_bytes.assign(v->bytes, v->bytes + v->off[v->V]);
-        build_trie(v, e->trie);
+        build_trie(v, e->opt.chunk_strings, e->trie);
     } catch (const std::bad_alloc &) { delete e; return fail(ZF_ERR_OOM, "out of memory"); }
     if (e->opt.device >= 0) {
         int rc = setup_device(e);
@@ -261,6 +272,7 @@ int zf_debug_host_mask(zf_engine *e, const zf_state *s, uint32_t *mask) { return
 int zf_debug_host_mask_stats(zf_engine *e, const zf_state *s, uint32_t *mask, int64_t *stats) {
     if (!e || !s || !mask || s->eng != e) return fail(ZF_ERR_INVALID_ARG, "bad argument");
     int64_t n_steps = 0, n_alive = 0, max_path = 0, max_set = 0, chunks_over = 0;
+    const int CHUNK_RANKS = e->trie.chunk_ranks;
     std::vector<uint8_t> chunk_over((e->trie.n_strings + CHUNK_RANKS - 1) / CHUNK_RANKS + 1, 0);
     const Tables &t = e->tab;
     const Trie &tr = e->trie;
@@ -330,14 +342,16 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     }
     HIP_TRY(hipMemcpyAsync(d->d_chart, d->h_stage, total, hipMemcpyHostToDevice, stream));
     // ---- per-call device buffers ----
-    const size_t need_rank = (size_t)batch * d->tab.Wr;
-    if (need_rank > d->rank_cap) {
+    const size_t need_rank = (size_t)batch * d->tab.Wr, need_ovf = (size_t)batch * d->tab.n_chunks;
+    if (need_rank > d->rank_cap || need_ovf > d->overflow_cap) {
         if (d->d_rank_mask) (void)hipFree(d->d_rank_mask);
         if (d->d_overflow) (void)hipFree(d->d_overflow);
-        d->d_rank_mask = nullptr; d->d_overflow = nullptr; d->rank_cap = d->overflow_cap = 0;
+        if (d->d_overflow2) (void)hipFree(d->d_overflow2);
+        d->d_rank_mask = nullptr; d->d_overflow = d->d_overflow2 = nullptr; d->rank_cap = d->overflow_cap = 0;
         HIP_TRY(hipMalloc((void **)&d->d_rank_mask, need_rank * 4 + 16));
-        HIP_TRY(hipMalloc((void **)&d->d_overflow, need_rank * sizeof(uint2) + 16));
-        d->rank_cap = d->overflow_cap = need_rank;
+        HIP_TRY(hipMalloc((void **)&d->d_overflow, need_ovf * sizeof(uint2) + 16));
+        HIP_TRY(hipMalloc((void **)&d->d_overflow2, need_ovf * sizeof(uint2) + 16));
+        d->rank_cap = need_rank; d->overflow_cap = need_ovf;
     }
     MaskArgs a{};
     a.tab = d->tab;
@@ -348,6 +362,9 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     a.out_mask = d_mask;
     a.counters = d->d_counters;
     a.overflow_list = d->d_overflow;
+    a.overflow_list2 = d->d_overflow2;
+    a.mode = d->mode;
+    a.fb2_cap = e->opt.fallback_item_cap;
     a.overflow_cap = (uint32_t)d->overflow_cap;
     a.fb_items = d->d_fb_items;
     a.fb_set_start = d->d_fb_ss;
@@ -358,7 +375,7 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
     if (d->tab.n_chunks > 0) HIP_TRY(launch_mask_main(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));
-    if (d->tab.n_chunks > 0) HIP_TRY(launch_mask_fallback(a, stream));
+    if (d->tab.n_chunks > 0) { HIP_TRY(launch_mask_fallback2(a, stream)); HIP_TRY(launch_mask_fallback3(a, stream)); }
     if (prof) HIP_TRY(hipEventRecord(d->ev[2], stream));
     HIP_TRY(launch_permute(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[3], stream));
@@ -371,8 +388,9 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
         HIP_TRY(hipEventElapsedTime(&d->report.permute_ms, d->ev[2], d->ev[3]));
     }
     d->report.overflow_chunks = d->h_counters[0];
+    d->report.overflow_chunks_level3 = d->h_counters[1];
     d->report.chart_bytes = (int64_t)total;
-    if (d->h_counters[1]) return fail(ZF_ERR_OVERFLOW, std::to_string(d->h_counters[1]) + " trie chunks exceeded the fallback arena");
+    if (d->h_counters[2]) return fail(ZF_ERR_OVERFLOW, std::to_string(d->h_counters[2]) + " trie chunks exceeded the fallback arena");
     return ZF_OK;
 }
 

@@ -159,6 +159,35 @@ bool build_tables(const zf_grammar_desc *g, Tables &t) {
     }
     t.P = (int)t.sym.size();
     if (t.P >= 0xFFFF) { set_error("grammar: too many dotted positions"); return false; }
+    t.end_base = t.end_pos[0];
+    t.advpq.assign(t.P, 0);
+    for (int p = 0; p < t.P; p++) {
+        uint16_t code = t.sym[p];
+        int k = code >> SYM_KIND_SHIFT;
+        if (k == SYM_END) t.advpq[p] = t.end_pos[code & SYM_ID_MASK];
+        else if (k == SYM_TERM) t.advpq[p] = (uint32_t)p | ((uint32_t)t.term_start[code & SYM_ID_MASK] << 16);
+        else t.advpq[p] = (uint32_t)p;
+    }
+    // hybrid DFA encoding for the device: literal chains carry their byte, other states a dense row
+    t.qinfo.assign(Q, 0);
+    t.delta_dense.clear();
+    for (int k = 0; k < T; k++) {
+        const bool lit = g->term_kind[k] == 0;
+        for (int s = 0; s < dfas[k].n_states(); s++) {
+            int q = base[k] + s;
+            uint32_t info = t.qflags[q];
+            if (lit) {
+                int b = 0;
+                for (int x = 0; x < 256; x++) if (dfas[k].trans[s * 256 + x] >= 0) b = x;
+                info |= QF_LITERAL | ((uint32_t)b << 8);
+            } else {
+                uint32_t row = (uint32_t)(t.delta_dense.size() / t.n_cls);
+                t.delta_dense.insert(t.delta_dense.end(), t.delta.begin() + (size_t)q * t.n_cls, t.delta.begin() + (size_t)(q + 1) * t.n_cls);
+                info |= row << 16;
+            }
+            t.qinfo[q] = info;
+        }
+    }
     // ---- PRED / I / SCAN / COMP ----
     // lead[Z] = positions of Z's rules reachable from the rule start over nullable symbols
     std::vector<std::vector<int>> lead(N);
@@ -217,7 +246,8 @@ bool build_tables(const zf_grammar_desc *g, Tables &t) {
 }
 
 // ---- vocabulary -> flattened prefix trie ---------------------------------------------------
-void build_trie(const zf_vocab_desc *v, Trie &t) {
+void build_trie(const zf_vocab_desc *v, int CHUNK_RANKS, Trie &t) {
+    t.chunk_ranks = CHUNK_RANKS;
     const int V = v->V;
     std::vector<int> order;
     for (int i = 0; i < V; i++) if (v->off[i + 1] > v->off[i]) order.push_back(i);

@@ -15,7 +15,9 @@ enum : uint16_t {
     SYM_ID_MASK = (1u << 14) - 1,
     DFA_DEAD = 0xFFFF,
 };
-enum : uint8_t { QF_ACCEPT = 1, QF_CONT = 2 };
+// Per-DFA-state word: flags | expected byte << 8 | dense transition row << 16.  States of a
+// literal terminal form a chain (one expected byte, next state = q + 1) and need no table row.
+enum : uint8_t { QF_ACCEPT = 1, QF_CONT = 2, QF_LITERAL = 4 };
 
 // One Earley item.  p: dotted position (index into sym[]); q: DFA state when the postdot
 // symbol is a terminal (global state numbering, so q also names the terminal), else 0;
@@ -36,28 +38,31 @@ struct TrieNode {
 };
 
 static const int MAX_TOKEN_LEN_ON_DEVICE = 255;   // deeper nodes never occur: depth is a uint8
-static const int CHUNK_RANKS = 32;                // one lane walks the nodes of 32 strings = one word
 static const int CHUNK_ANC = 16;                  // ancestors stored per chunk (longer paths use parent links)
 
-// Immutable per-engine tables in device memory.
+// Immutable per-engine tables in device memory.  Every array is padded to a multiple of 16 bytes
+// so that a block can stage it into LDS with 4-byte copies.
 struct DeviceTables {
-    const uint16_t *sym;        // [P]
-    const uint16_t *end_pos;    // [N] position whose sym is END|X
+    const uint16_t *sym;        // [P] symbol after the dot
+    const uint32_t *advpq;      // [P] the (position | DFA state << 16) word to insert when the dot arrives at p
     const uint8_t *cls;         // [256] byte -> class
-    const uint16_t *delta;      // [Q][n_cls]
-    const uint8_t *qflags;      // [Q]
-    const uint16_t *term_start; // [T]
+    const uint32_t *qinfo;      // [Q]
     const uint32_t *scan_off;   // [N*n_cls+1] CSR into scan_list
-    const uint32_t *scan_list;  // p | q' << 16
     const uint32_t *comp_off;   // [N*N+1] CSR into comp_list
+    const uint16_t *delta;      // [dense rows][n_cls]
+    const uint32_t *scan_list;  // p | q' << 16
     const uint16_t *comp_list;  // advanced positions
+    uint32_t small_bytes[6];    // padded byte sizes of sym .. comp_off (always staged into LDS when they fit)
+    uint32_t big_bytes[3];      // padded byte sizes of delta, scan_list, comp_list
     const TrieNode *nodes;      // [n_nodes]
     const uint32_t *parent;     // [n_nodes] parent node index, 0xFFFFFFFF for depth-1 nodes
     const uint32_t *chunk_begin; // [n_chunks] first node of the chunk
     const uint32_t *chunk_end;   // [n_chunks] one past the last string node of the chunk
     const uint32_t *chunk_anc;   // [n_chunks][CHUNK_ANC] ancestors of the chunk's first node, depth 1 first
     const uint32_t *rank_of;    // [V] rank of token v's string, 0xFFFFFFFF for the empty token
-    int32_t N, n_cls, n_nodes, n_chunks, n_strings, V, W, Wr;
+    int32_t N, n_cls, end_base, n_nodes, n_chunks, n_strings, V, W;
+    int32_t chunk_ranks;        // strings per chunk: 8, 16 or 32
+    int32_t Wr;                 // 32-bit words per row of the rank-ordered verdict bitmap
 };
 
 // Per-row header of the uploaded chart.  Items of set k: items[item_base + set_off[set_base+k] ..

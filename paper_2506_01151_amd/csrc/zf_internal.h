@@ -36,6 +36,10 @@ struct Tables {
     uint8_t cls[256];
     std::vector<uint16_t> delta;      // [Q*n_cls]
     std::vector<uint8_t> qflags;      // [Q]
+    std::vector<uint32_t> advpq;      // [P] word to insert when the dot arrives at p
+    std::vector<uint32_t> qinfo;      // [Q] flags | literal byte << 8 | dense row << 16
+    std::vector<uint16_t> delta_dense; // rows of the non-literal states only
+    int end_base = 0;                 // end_pos[X] == end_base + X
     std::vector<uint16_t> term_start; // [T]
     std::vector<uint32_t> scan_off, scan_list;
     std::vector<uint32_t> comp_off;
@@ -54,8 +58,9 @@ struct Trie {
     std::vector<uint32_t> chunk_begin, chunk_end, chunk_anc;
     std::vector<uint32_t> rank_of;    // [V]
     int n_strings = 0;
+    int chunk_ranks = 32;
 };
-void build_trie(const zf_vocab_desc *v, Trie &t);
+void build_trie(const zf_vocab_desc *v, int chunk_ranks, Trie &t);
 
 // ---- chart --------------------------------------------------------------------------------------
 struct Chart {

@@ -1,137 +1,220 @@
-// HIP kernels for gfx950: the vocabulary-mask kernel (main pass + exact fallback pass), the
-// rank-order -> token-order bit permutation, and the logit-masking kernel.
+// HIP kernels for gfx950: the vocabulary-mask kernel (main pass + two exact fallback levels),
+// the rank-order -> token-order bit permutation, and the logit-masking kernel.
 //
 // Mask kernel.  The vocabulary trie is stored in preorder, so a depth-first walk is a linear
 // scan in which a dead subtree is left through the node's skip pointer and a shared prefix is
-// scanned once per lane.  Every lane owns the nodes of CHUNK_RANKS consecutive strings (one
-// 32-bit word of verdicts).  It first replays the ancestors of its first node, then walks its
-// nodes; per node it performs one Earley byte step (Scan + Complete with tabulated Predict,
-// paper Section 3.2) on a private item list kept in LDS, interleaved by lane so that lanes
-// never collide on a bank.  The list holds one set per trie depth of the current path; moving
-// to a shallower node simply truncates it.  A lane whose list would outgrow its budget (or
-// whose path is too deep) reports its chunk to the fallback pass, which repeats the same walk
-// with the list in a global-memory arena.
+// scanned once per lane.  Every lane owns the nodes of `chunk_ranks` consecutive strings.  It
+// first replays the ancestors of its first node, then walks its nodes; per node it performs
+// one Earley byte step (Scan + Complete with tabulated Predict, paper Section 3.2) on a private
+// item list kept in LDS, interleaved by lane so that lanes never collide on a bank.  The list
+// holds one set per trie depth of the current path; moving to a shallower node truncates it.
+// The grammar tables (and the row's chart when it is small) are staged into LDS once per
+// block, so a byte step is a chain of LDS look-ups; only the trie nodes stream from L2.
+// A lane whose list would outgrow its budget (or whose path is too deep) hands its chunk to the
+// fallback: level 2 repeats the walk with one lane per wavefront and a 2,048-item list in LDS,
+// level 3 with the list in a global-memory arena.
 #include <hip/hip_runtime.h>
 #include "zf_launch.h"
 
 namespace zf {
 namespace {
 
-struct LdsStore {
-    uint2 *items;     // this lane's column of the block's item array (stride 64)
-    uint8_t *ss;      // this lane's column of the set-start array (stride 64)
+// Table view used by the device code; the pointers lead into LDS or global memory.
+struct TV {
+    const uint16_t *sym;
+    const uint32_t *advpq;
+    const uint8_t *cls;
+    const uint32_t *qinfo;
+    const uint32_t *scan_off;
+    const uint32_t *comp_off;
+    const uint16_t *delta;
+    const uint32_t *scan_list;
+    const uint16_t *comp_list;
+    uint32_t N, ncls, end_base;
+};
+
+__device__ __forceinline__ void copy16(void *dst, const void *src, uint32_t bytes, uint32_t tid, uint32_t nthreads) {
+    const uint4 *s = reinterpret_cast<const uint4 *>(src);
+    uint4 *d = reinterpret_cast<uint4 *>(dst);
+    for (uint32_t i = tid; i < bytes / 16; i += nthreads) d[i] = s[i];
+}
+
+// Stage the tables the MODE asks for into LDS at smem and build the view.  Returns the bytes used.
+// The caller must put a barrier between this and the first use.
+template <int MODE>
+__device__ __forceinline__ uint32_t stage_tables(const DeviceTables &D, uint8_t *smem, TV &tv, uint32_t tid, uint32_t nthreads) {
+    tv.N = D.N; tv.ncls = D.n_cls; tv.end_base = D.end_base;
+    uint32_t off = 0;
+    if (MODE <= 1) {
+        const void *src[6] = {D.sym, D.advpq, D.cls, D.qinfo, D.scan_off, D.comp_off};
+        uint32_t at[6];
+#pragma unroll
+        for (int k = 0; k < 6; k++) { at[k] = off; copy16(smem + off, src[k], D.small_bytes[k], tid, nthreads); off += D.small_bytes[k]; }
+        tv.sym = reinterpret_cast<const uint16_t *>(smem + at[0]);
+        tv.advpq = reinterpret_cast<const uint32_t *>(smem + at[1]);
+        tv.cls = smem + at[2];
+        tv.qinfo = reinterpret_cast<const uint32_t *>(smem + at[3]);
+        tv.scan_off = reinterpret_cast<const uint32_t *>(smem + at[4]);
+        tv.comp_off = reinterpret_cast<const uint32_t *>(smem + at[5]);
+    } else {
+        tv.sym = D.sym; tv.advpq = D.advpq; tv.cls = D.cls; tv.qinfo = D.qinfo; tv.scan_off = D.scan_off; tv.comp_off = D.comp_off;
+    }
+    if (MODE == 0) {
+        const void *src[3] = {D.delta, D.scan_list, D.comp_list};
+        uint32_t at[3];
+#pragma unroll
+        for (int k = 0; k < 3; k++) { at[k] = off; copy16(smem + off, src[k], D.big_bytes[k], tid, nthreads); off += D.big_bytes[k]; }
+        tv.delta = reinterpret_cast<const uint16_t *>(smem + at[0]);
+        tv.scan_list = reinterpret_cast<const uint32_t *>(smem + at[1]);
+        tv.comp_list = reinterpret_cast<const uint16_t *>(smem + at[2]);
+    } else {
+        tv.delta = D.delta; tv.scan_list = D.scan_list; tv.comp_list = D.comp_list;
+    }
+    return off;
+}
+
+// ---- item-list storage policies ---------------------------------------------------------
+// An item is (pq, o): pq = dotted position | DFA state << 16, o = origin set.
+struct LaneLdsStore {          // main kernel: one list per lane, interleaved by lane
+    uint32_t *pq;              // column of this lane, stride 64
+    uint16_t *org;
+    uint8_t *ss;
     uint32_t cap;
     static constexpr int max_depth = LANE_DEPTH_MAX;
-    __device__ __forceinline__ uint2 get(uint32_t i) const { return items[i * 64]; }
-    __device__ __forceinline__ void put(uint32_t i, uint2 v) { items[i * 64] = v; }
+    __device__ __forceinline__ void get(uint32_t i, uint32_t &p, uint32_t &o) const { p = pq[i * 64]; o = org[i * 64]; }
+    __device__ __forceinline__ void put(uint32_t i, uint32_t p, uint32_t o) { pq[i * 64] = p; org[i * 64] = (uint16_t)o; }
     __device__ __forceinline__ uint32_t start(int d) const { return ss[d * 64]; }
     __device__ __forceinline__ void set_start(int d, uint32_t v) { ss[d * 64] = (uint8_t)v; }
 };
-
-struct GlobalStore {
-    uint2 *items;     // this lane's column of the arena (stride FB_LANES)
+struct WaveLdsStore {          // fallback level 2: the whole wavefront's LDS serves one lane
+    uint32_t *pq;
+    uint32_t *org;
+    uint16_t *ss;
+    uint32_t cap;
+    static constexpr int max_depth = FB_DEPTH_MAX;
+    __device__ __forceinline__ void get(uint32_t i, uint32_t &p, uint32_t &o) const { p = pq[i]; o = org[i]; }
+    __device__ __forceinline__ void put(uint32_t i, uint32_t p, uint32_t o) { pq[i] = p; org[i] = o; }
+    __device__ __forceinline__ uint32_t start(int d) const { return ss[d]; }
+    __device__ __forceinline__ void set_start(int d, uint32_t v) { ss[d] = (uint16_t)v; }
+};
+struct GlobalStore {           // fallback level 3: arena in global memory, interleaved by lane
+    uint2 *items;
     uint32_t *ss;
     uint32_t cap;
     static constexpr int max_depth = FB_DEPTH_MAX;
-    __device__ __forceinline__ uint2 get(uint32_t i) const { return items[(size_t)i * FB_LANES]; }
-    __device__ __forceinline__ void put(uint32_t i, uint2 v) { items[(size_t)i * FB_LANES] = v; }
-    __device__ __forceinline__ uint32_t start(int d) const { return ss[(size_t)d * FB_LANES]; }
-    __device__ __forceinline__ void set_start(int d, uint32_t v) { ss[(size_t)d * FB_LANES] = v; }
+    __device__ __forceinline__ void get(uint32_t i, uint32_t &p, uint32_t &o) const { uint2 x = items[(size_t)i * FB3_LANES]; p = x.x; o = x.y; }
+    __device__ __forceinline__ void put(uint32_t i, uint32_t p, uint32_t o) { items[(size_t)i * FB3_LANES] = make_uint2(p, o); }
+    __device__ __forceinline__ uint32_t start(int d) const { return ss[(size_t)d * FB3_LANES]; }
+    __device__ __forceinline__ void set_start(int d, uint32_t v) { ss[(size_t)d * FB3_LANES] = v; }
 };
 
-// items are uint2: x = dotted position | DFA state << 16, y = origin set
+// "each state set maintains only unique states" (Section 3.2)
 template <class S>
 __device__ __forceinline__ bool insert_unique(S &st, uint32_t set_begin, uint32_t &cnt, uint32_t pq, uint32_t o) {
     for (uint32_t i = set_begin; i < cnt; i++) {
-        uint2 x = st.get(i);
-        if (x.x == pq && x.y == o) return true;
+        uint32_t xp, xo;
+        st.get(i, xp, xo);
+        if (xp == pq && xo == o) return true;
     }
     if (cnt >= st.cap) return false;
-    st.put(cnt++, make_uint2(pq, o));
+    st.put(cnt++, pq, o);
     return true;
 }
 
-// Add the item with the dot at position p; skip nullable postdot nonterminals; record a dot at
-// the end of a rule as the canonical "lhs complete since o" item.
+// Add the item with the dot at position p; skip nullable postdot nonterminals; a dot at the end
+// of a rule becomes the canonical "lhs complete since o" item (positions >= end_base).
 template <class S>
-__device__ __forceinline__ bool add_advanced(const DeviceTables &T, S &st, uint32_t set_begin, uint32_t &cnt, uint32_t p, uint32_t o) {
+__device__ __forceinline__ bool add_advanced(const TV &T, S &st, uint32_t set_begin, uint32_t &cnt, uint32_t p, uint32_t o) {
     for (;;) {
-        uint32_t code = T.sym[p];
-        uint32_t k = code >> SYM_KIND_SHIFT;
-        if (k == SYM_END) return insert_unique(st, set_begin, cnt, T.end_pos[code & SYM_ID_MASK], o);
-        if (k == SYM_TERM) return insert_unique(st, set_begin, cnt, p | ((uint32_t)T.term_start[code & SYM_ID_MASK] << 16), o);
-        if (!insert_unique(st, set_begin, cnt, p, o)) return false;
-        if (!(code & SYM_NULLABLE_BIT)) return true;
+        const uint32_t code = T.sym[p];
+        if (!insert_unique(st, set_begin, cnt, T.advpq[p], o)) return false;
+        if ((code >> SYM_KIND_SHIFT) != SYM_NT || !(code & SYM_NULLABLE_BIT)) return true;
         p++;
     }
 }
 
+__device__ __forceinline__ uint32_t dfa_next(const TV &T, uint32_t q, uint32_t byte, uint32_t cl) {
+    const uint32_t info = T.qinfo[q];
+    if (info & QF_LITERAL) return (((info >> 8) & 0xFFu) == byte && (info & QF_CONT)) ? q + 1 : (uint32_t)DFA_DEAD;
+    return T.delta[(info >> 16) * T.ncls + cl];
+}
+
 enum { STEP_ALIVE = 1, STEP_KERNEL = 2, STEP_OVERFLOW = 4 };
+
+struct Base {                  // the row's uploaded chart (LDS copy or global)
+    const uint32_t *so;        // set offsets, so[k] .. so[k+1]
+    const uint2 *it;           // items: x = p | q << 16, y = origin
+    uint32_t m;                // number of sets; set m-1 is the current one
+    uint32_t last_lo, last_hi; // so[m-1], so[m]
+};
 
 // One Earley byte step at trie depth d (1-based).  The source set is the row's current set for
 // d == 1, else the lane's set of depth d-1.  On entry cnt == st.start(d).
 template <class S>
-__device__ int earley_step(const DeviceTables &T, const uint32_t *__restrict__ bso, const uint2 *__restrict__ bit,
-                           uint32_t m, S &st, int d, uint32_t byte, uint32_t &cnt) {
+__device__ __forceinline__ int earley_step(const TV &T, const Base &B, S &st, int d, uint32_t byte, uint32_t &cnt) {
     const uint32_t nb = cnt;
-    const uint32_t ncls = T.n_cls, cl = T.cls[byte];
-    const uint32_t cur = m - 1 + (uint32_t)(d - 1);   // index of the source set
-    const uint32_t SP = (uint32_t)T.N - 1;
+    const uint32_t cl = T.cls[byte];
+    const uint32_t cur = B.m - 1 + (uint32_t)(d - 1);   // index of the source set
     bool ok = true;
     const bool from_base = d == 1;
-    uint32_t sb = from_base ? bso[m - 1] : st.start(d - 1);
-    uint32_t se = from_base ? bso[m] : nb;
+    const uint32_t sb = from_base ? B.last_lo : st.start(d - 1);
+    const uint32_t se = from_base ? B.last_hi : nb;
+    // Scan
     for (uint32_t i = sb; i < se && ok; i++) {
-        uint2 it = from_base ? bit[i] : st.get(i);
-        uint32_t p = it.x & 0xFFFFu, q = it.x >> 16;
-        uint32_t code = T.sym[p];
-        uint32_t k = code >> SYM_KIND_SHIFT;
-        if (k == SYM_TERM) {
-            uint32_t q2 = T.delta[q * ncls + cl];
+        uint32_t pq, o;
+        if (from_base) { uint2 x = B.it[i]; pq = x.x; o = x.y; } else st.get(i, pq, o);
+        const uint32_t p = pq & 0xFFFFu;
+        if (p >= T.end_base) continue;                  // completed item kept in an unpruned chart
+        const uint32_t code = T.sym[p];
+        if ((code >> SYM_KIND_SHIFT) == SYM_TERM) {
+            const uint32_t q2 = dfa_next(T, pq >> 16, byte, cl);
             if (q2 == DFA_DEAD) continue;
-            uint32_t f = T.qflags[q2];
-            if (f & QF_CONT) ok = insert_unique(st, nb, cnt, p | (q2 << 16), it.y);
-            if (ok && (f & QF_ACCEPT)) ok = add_advanced(T, st, nb, cnt, p + 1, it.y);
-        } else if (k == SYM_NT) {
-            uint32_t Y = code & SYM_ID_MASK_NT;
-            uint32_t k0 = T.scan_off[Y * ncls + cl], k1 = T.scan_off[Y * ncls + cl + 1];
+            const uint32_t f = T.qinfo[q2];
+            if (f & QF_CONT) ok = insert_unique(st, nb, cnt, p | (q2 << 16), o);   // no longest match: keep matching ...
+            if (ok && (f & QF_ACCEPT)) ok = add_advanced(T, st, nb, cnt, p + 1, o);   // ... and also finish here
+        } else {
+            const uint32_t Y = code & SYM_ID_MASK_NT;   // stands for every predicted item of I(Y)
+            const uint32_t k0 = T.scan_off[Y * T.ncls + cl], k1 = T.scan_off[Y * T.ncls + cl + 1];
             for (uint32_t e = k0; e < k1 && ok; e++) {
-                uint32_t ent = T.scan_list[e];
-                uint32_t p0 = ent & 0xFFFFu, q2 = ent >> 16;
-                uint32_t f = T.qflags[q2];
-                if (f & QF_CONT) ok = insert_unique(st, nb, cnt, p0 | (q2 << 16), cur);
-                if (ok && (f & QF_ACCEPT)) ok = add_advanced(T, st, nb, cnt, p0 + 1, cur);
+                const uint32_t ent = T.scan_list[e];
+                const uint32_t f = T.qinfo[ent >> 16];
+                if (f & QF_CONT) ok = insert_unique(st, nb, cnt, ent, cur);
+                if (ok && (f & QF_ACCEPT)) ok = add_advanced(T, st, nb, cnt, (ent & 0xFFFFu) + 1, cur);
             }
         }
     }
-    bool accepted = false;
+    // Complete
     for (uint32_t i = nb; i < cnt && ok; i++) {
-        uint2 it = st.get(i);
-        uint32_t code = T.sym[it.x & 0xFFFFu];
-        if ((code >> SYM_KIND_SHIFT) != SYM_END) continue;
-        uint32_t X = code & SYM_ID_MASK;
-        if (X == SP) { accepted = true; continue; }
-        uint32_t o = it.y;
-        const bool in_base = o < m;
+        uint32_t pq, o;
+        st.get(i, pq, o);
+        const uint32_t p = pq & 0xFFFFu;
+        if (p < T.end_base) continue;
+        const uint32_t X = p - T.end_base;
+        if (X == T.N - 1) continue;                     // the start rule is complete: the prefix is a sentence
+        const bool in_base = o < B.m;
         uint32_t jb, je;
-        if (in_base) { jb = bso[o]; je = bso[o + 1]; }
-        else { int dj = (int)(o - (m - 1)); jb = st.start(dj); je = st.start(dj + 1); }
+        if (in_base) { jb = B.so[o]; je = B.so[o + 1]; }
+        else { const int dj = (int)(o - (B.m - 1)); jb = st.start(dj); je = st.start(dj + 1); }
         for (uint32_t j = jb; j < je && ok; j++) {
-            uint2 y = in_base ? bit[j] : st.get(j);
-            uint32_t yc = T.sym[y.x & 0xFFFFu];
+            uint32_t ypq, yo;
+            if (in_base) { uint2 y = B.it[j]; ypq = y.x; yo = y.y; } else st.get(j, ypq, yo);
+            const uint32_t yp = ypq & 0xFFFFu;
+            if (yp >= T.end_base) continue;
+            const uint32_t yc = T.sym[yp];
             if ((yc >> SYM_KIND_SHIFT) != SYM_NT) continue;
-            uint32_t Y = yc & SYM_ID_MASK_NT;
-            uint32_t c0 = T.comp_off[Y * T.N + X], c1 = T.comp_off[Y * T.N + X + 1];
+            const uint32_t Y = yc & SYM_ID_MASK_NT;
+            const uint32_t c0 = T.comp_off[Y * T.N + X], c1 = T.comp_off[Y * T.N + X + 1];
             for (uint32_t e = c0; e < c1 && ok; e++) ok = add_advanced(T, st, nb, cnt, T.comp_list[e], o);
-            if (ok && Y == X) ok = add_advanced(T, st, nb, cnt, (y.x & 0xFFFFu) + 1, y.y);
+            if (ok && Y == X) ok = add_advanced(T, st, nb, cnt, yp + 1, yo);
         }
     }
     if (!ok) return STEP_OVERFLOW;
-    const bool alive = cnt > nb || accepted;
+    const bool alive = cnt > nb;
     uint32_t w = nb;   // completed items are needed only while their own set is processed
     for (uint32_t i = nb; i < cnt; i++) {
-        uint2 it = st.get(i);
-        if ((T.sym[it.x & 0xFFFFu] >> SYM_KIND_SHIFT) != SYM_END) { if (w != i) st.put(w, it); w++; }
+        uint32_t pq, o;
+        st.get(i, pq, o);
+        if ((pq & 0xFFFFu) < T.end_base) { if (w != i) st.put(w, pq, o); w++; }
     }
     cnt = w;
     st.set_start(d + 1, cnt);
@@ -139,99 +222,189 @@ __device__ int earley_step(const DeviceTables &T, const uint32_t *__restrict__ b
 }
 
 // Walk the nodes of one chunk.  anc(j) gives the node index of the first node's ancestor at
-// depth j+1.  Returns false on overflow; otherwise *bits holds the 32 verdicts.
+// depth j+1.  Returns false on overflow; otherwise *bits_out holds the chunk's verdicts.
 template <class S, class Anc>
-__device__ bool walk_chunk(const DeviceTables &T, const uint32_t *bso, const uint2 *bit, uint32_t m, S &st,
-                           uint32_t chunk, Anc anc, uint32_t *bits_out) {
-    uint32_t i = T.chunk_begin[chunk];
-    const uint32_t end = T.chunk_end[chunk];
-    const uint32_t rank0 = chunk * CHUNK_RANKS;
+__device__ __forceinline__ bool walk_chunk(const DeviceTables &D, const TV &T, const Base &B, S &st, uint32_t chunk, Anc anc, uint32_t *bits_out) {
+    uint32_t i = D.chunk_begin[chunk];
+    const uint32_t end = D.chunk_end[chunk];
+    const uint32_t rank0 = chunk * (uint32_t)D.chunk_ranks;
     uint32_t bits = 0, cnt = 0;
     st.set_start(1, 0);
-    const int d0 = T.nodes[i].depth;
+    TrieNode nd = D.nodes[i];
+    const int d0 = nd.depth;
     if (d0 > S::max_depth) return false;
     for (int j = 0; j + 1 < d0; j++) {   // replay the path above the chunk's first node
-        TrieNode an = T.nodes[anc(j)];
-        int r = earley_step(T, bso, bit, m, st, j + 1, an.byte, cnt);
+        const TrieNode an = D.nodes[anc(j)];
+        const int r = earley_step(T, B, st, j + 1, an.byte, cnt);
         if (r & STEP_OVERFLOW) return false;
-        if (!(r & STEP_KERNEL)) { i = an.skip; cnt = st.start(j + 1); break; }   // that whole subtree is dead
+        if (!(r & STEP_KERNEL)) {        // that whole subtree is dead
+            i = an.skip; cnt = st.start(j + 1);
+            if (i < end) nd = D.nodes[i];
+            break;
+        }
     }
     while (i < end) {
-        TrieNode nd = T.nodes[i];
-        int d = nd.depth;
+        const uint32_t nxt = i + 1;
+        TrieNode nx = nd;
+        if (nxt < end) nx = D.nodes[nxt];                // issued before the step so that it overlaps it
+        const int d = nd.depth;
         if (d > S::max_depth) return false;
-        cnt = st.start(d);   // forget the sets of the deeper path we came from
-        int r = earley_step(T, bso, bit, m, st, d, nd.byte, cnt);
+        cnt = st.start(d);                               // forget the sets of the deeper path we came from
+        const int r = earley_step(T, B, st, d, nd.byte, cnt);
         if (r & STEP_OVERFLOW) return false;
         if (nd.has_string && (r & STEP_ALIVE)) bits |= 1u << (nd.rank - rank0);
-        i = (r & STEP_KERNEL) ? i + 1 : nd.skip;
+        const uint32_t ni = (r & STEP_KERNEL) ? nxt : nd.skip;
+        if (ni == nxt) nd = nx;
+        else if (ni < end) nd = D.nodes[ni];
+        i = ni;
     }
     *bits_out = bits;
     return true;
 }
 
-__global__ __launch_bounds__(64) void mask_main_kernel(MaskArgs a) {
-    __shared__ uint2 lds_items[LANE_CAP_MAX * 64];
-    __shared__ uint8_t lds_ss[(LANE_DEPTH_MAX + 2) * 64];
-    const DeviceTables &T = a.tab;
-    const uint32_t lane = threadIdx.x, chunk = blockIdx.x * 64 + lane, row = blockIdx.y;
-    if (chunk >= (uint32_t)T.n_chunks) return;
+__device__ __forceinline__ void store_bits(const DeviceTables &D, uint32_t *rank_mask, uint32_t row, uint32_t chunk, uint32_t bits) {
+    uint8_t *rowp = reinterpret_cast<uint8_t *>(rank_mask + (size_t)row * D.Wr);
+    if (D.chunk_ranks == 32) reinterpret_cast<uint32_t *>(rowp)[chunk] = bits;
+    else if (D.chunk_ranks == 16) reinterpret_cast<uint16_t *>(rowp)[chunk] = (uint16_t)bits;
+    else rowp[chunk] = (uint8_t)bits;
+}
+
+__device__ __forceinline__ uint32_t lane_region_bytes(uint32_t cap) { return cap * 64 * 6 + (LANE_DEPTH_MAX + 2) * 64; }
+static const uint32_t BASE_LDS_BYTES = (BASE_SETS_LDS + 1) * 4 + BASE_ITEMS_LDS * 8;
+
+template <int MODE>
+__global__ __launch_bounds__(MAIN_BLOCK) void mask_main_kernel(MaskArgs a) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    const DeviceTables &D = a.tab;
+    const uint32_t tid = threadIdx.x, row = blockIdx.y;
+    TV T;
+    uint32_t off = stage_tables<MODE>(D, smem, T, tid, MAIN_BLOCK);
+    // the row's chart: LDS copy when small
     const RowChart rc = a.rows[row];
-    const uint32_t *bso = a.set_off + rc.set_base;
-    const uint2 *bit = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
-    LdsStore st{lds_items + lane, lds_ss + lane, (uint32_t)a.lane_cap};
-    const uint32_t *anc_row = T.chunk_anc + (size_t)chunk * CHUNK_ANC;
+    const uint32_t *g_so = a.set_off + rc.set_base;
+    const uint2 *g_it = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
+    const uint32_t n_items = g_so[rc.n_sets];
+    Base B;
+    B.m = rc.n_sets;
+    B.last_lo = g_so[rc.n_sets - 1];
+    B.last_hi = n_items;
+    if (rc.n_sets <= BASE_SETS_LDS && n_items <= BASE_ITEMS_LDS) {
+        uint32_t *l_so = reinterpret_cast<uint32_t *>(smem + off);
+        uint2 *l_it = reinterpret_cast<uint2 *>(smem + off + (BASE_SETS_LDS + 1) * 4);
+        for (uint32_t k = tid; k <= rc.n_sets; k += MAIN_BLOCK) l_so[k] = g_so[k];
+        for (uint32_t k = tid; k < n_items; k += MAIN_BLOCK) l_it[k] = g_it[k];
+        B.so = l_so; B.it = l_it;
+    } else { B.so = g_so; B.it = g_it; }
+    off += BASE_LDS_BYTES;
+    __syncthreads();
+    const uint32_t chunk = blockIdx.x * MAIN_BLOCK + tid;
+    if (chunk >= (uint32_t)D.n_chunks) return;
+    const uint32_t wave = tid >> 6, lane = tid & 63;
+    const uint32_t cap = (uint32_t)a.lane_cap;
+    uint8_t *region = smem + off + wave * lane_region_bytes(cap);
+    LaneLdsStore st;
+    st.pq = reinterpret_cast<uint32_t *>(region) + lane;
+    st.org = reinterpret_cast<uint16_t *>(region + cap * 64 * 4) + lane;
+    st.ss = region + cap * 64 * 6 + lane;
+    st.cap = cap;
+    const uint32_t *anc_row = D.chunk_anc + (size_t)chunk * CHUNK_ANC;
     uint32_t bits = 0;
-    bool ok = walk_chunk(T, bso, bit, rc.n_sets, st, chunk, [&](int j) { return anc_row[j]; }, &bits);
+    bool ok = cap > 0 && B.m + LANE_DEPTH_MAX < 0xFFFFu &&
+              walk_chunk(D, T, B, st, chunk, [&](int j) { return anc_row[j]; }, &bits);
     if (!ok) {
-        uint32_t slot = atomicAdd(&a.counters[0], 1u);
+        const uint32_t slot = atomicAdd(&a.counters[0], 1u);
         if (slot < a.overflow_cap) a.overflow_list[slot] = make_uint2(row, chunk);
         bits = 0;
     }
-    a.rank_mask[(size_t)row * T.Wr + chunk] = bits;
+    store_bits(D, a.rank_mask, row, chunk, bits);
 }
 
-// Exact fallback: the same walk, one lane per reported chunk, item list in global memory.
-__global__ __launch_bounds__(64) void mask_fallback_kernel(MaskArgs a) {
-    const DeviceTables &T = a.tab;
-    const uint32_t gid = blockIdx.x * 64 + threadIdx.x;
+struct ParentAnc {             // ancestor at depth j+1 through the parent links
+    const uint32_t *parent; uint32_t first; int d0;
+    __device__ __forceinline__ uint32_t operator()(int j) const {
+        uint32_t x = first;
+        for (int k = d0; k > j + 1; k--) x = parent[x];
+        return x;
+    }
+};
+
+__device__ __forceinline__ Base global_base(const MaskArgs &a, uint32_t row) {
+    const RowChart rc = a.rows[row];
+    Base B;
+    B.so = a.set_off + rc.set_base;
+    B.it = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
+    B.m = rc.n_sets;
+    B.last_lo = B.so[rc.n_sets - 1];
+    B.last_hi = B.so[rc.n_sets];
+    return B;
+}
+
+// Fallback level 2: one chunk per wavefront, walked by lane 0 with a 2,048-item list in LDS.
+template <int MODE>
+__global__ __launch_bounds__(64) void mask_fallback2_kernel(MaskArgs a) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    const DeviceTables &D = a.tab;
+    TV T;
+    uint32_t off = stage_tables<MODE>(D, smem, T, threadIdx.x, 64);
+    __syncthreads();
     uint32_t n = a.counters[0];
-    if (n > a.overflow_cap) { if (gid == 0) atomicAdd(&a.counters[1], n - a.overflow_cap); n = a.overflow_cap; }
-    GlobalStore st{a.fb_items + gid, a.fb_set_start + gid, (uint32_t)FB_ITEMS_PER_LANE};
-    for (uint32_t e = gid; e < n; e += FB_LANES) {
+    if (n > a.overflow_cap) { if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&a.counters[2], n - a.overflow_cap); n = a.overflow_cap; }
+    if (threadIdx.x != 0) return;
+    WaveLdsStore st;
+    st.pq = reinterpret_cast<uint32_t *>(smem + off);
+    st.org = st.pq + FB2_CAP;
+    st.ss = reinterpret_cast<uint16_t *>(st.org + FB2_CAP);
+    st.cap = (uint32_t)a.fb2_cap;
+    for (uint32_t e = blockIdx.x; e < n; e += gridDim.x) {
         const uint2 ent = a.overflow_list[e];
-        const uint32_t row = ent.x, chunk = ent.y;
-        const RowChart rc = a.rows[row];
-        const uint32_t *bso = a.set_off + rc.set_base;
-        const uint2 *bit = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
-        const uint32_t first = T.chunk_begin[chunk];
-        const int d0 = T.nodes[first].depth;
-        auto anc = [&](int j) {   // ancestor at depth j+1 through the parent links
-            uint32_t x = first;
-            for (int k = d0; k > j + 1; k--) x = T.parent[x];
-            return x;
-        };
+        const Base B = global_base(a, ent.x);
+        const uint32_t first = D.chunk_begin[ent.y];
+        ParentAnc anc{D.parent, first, D.nodes[first].depth};
         uint32_t bits = 0;
-        if (!walk_chunk(T, bso, bit, rc.n_sets, st, chunk, anc, &bits)) { atomicAdd(&a.counters[1], 1u); bits = 0; }
-        a.rank_mask[(size_t)row * T.Wr + chunk] = bits;
+        if (!walk_chunk(D, T, B, st, ent.y, anc, &bits)) {
+            const uint32_t slot = atomicAdd(&a.counters[1], 1u);
+            if (slot < a.overflow_cap) a.overflow_list2[slot] = ent;
+            bits = 0;
+        }
+        store_bits(D, a.rank_mask, ent.x, ent.y, bits);
+    }
+}
+
+// Fallback level 3: one lane per remaining chunk, item list in a global-memory arena.
+__global__ __launch_bounds__(64) void mask_fallback3_kernel(MaskArgs a) {
+    const DeviceTables &D = a.tab;
+    TV T;
+    stage_tables<2>(D, nullptr, T, 0, 1);
+    const uint32_t gid = blockIdx.x * 64 + threadIdx.x;
+    uint32_t n = a.counters[1];
+    if (n > a.overflow_cap) { if (gid == 0) atomicAdd(&a.counters[2], n - a.overflow_cap); n = a.overflow_cap; }
+    GlobalStore st{a.fb_items + gid, a.fb_set_start + gid, (uint32_t)FB3_ITEMS_PER_LANE};
+    for (uint32_t e = gid; e < n; e += FB3_LANES) {
+        const uint2 ent = a.overflow_list2[e];
+        const Base B = global_base(a, ent.x);
+        const uint32_t first = D.chunk_begin[ent.y];
+        ParentAnc anc{D.parent, first, D.nodes[first].depth};
+        uint32_t bits = 0;
+        if (!walk_chunk(D, T, B, st, ent.y, anc, &bits)) { atomicAdd(&a.counters[2], 1u); bits = 0; }
+        store_bits(D, a.rank_mask, ent.x, ent.y, bits);
     }
 }
 
 // Verdicts are produced in trie order; the caller wants bit v at word v >> 5.  One lane per
 // token looks its bit up and a wavefront ballot packs 64 of them into two words.
 __global__ __launch_bounds__(256) void permute_kernel(MaskArgs a) {
-    const DeviceTables &T = a.tab;
+    const DeviceTables &D = a.tab;
     const uint32_t v = blockIdx.x * 256 + threadIdx.x, row = blockIdx.y;
     uint32_t bit = 0;
-    if (v < (uint32_t)T.V) {
-        uint32_t r = T.rank_of[v];
-        if (r != 0xFFFFFFFFu) bit = (a.rank_mask[(size_t)row * T.Wr + (r >> 5)] >> (r & 31)) & 1u;
+    if (v < (uint32_t)D.V) {
+        const uint32_t r = D.rank_of[v];
+        if (r != 0xFFFFFFFFu) bit = (a.rank_mask[(size_t)row * D.Wr + (r >> 5)] >> (r & 31)) & 1u;
     }
-    unsigned long long b = __ballot(bit);
+    const unsigned long long b = __ballot(bit);
     const uint32_t lane = threadIdx.x & 63;
     if ((lane & 31) == 0) {
-        uint32_t w = v >> 5;
-        if (w < (uint32_t)T.W) a.out_mask[(size_t)row * T.W + w] = (uint32_t)(b >> lane);
+        const uint32_t w = v >> 5;
+        if (w < (uint32_t)D.W) a.out_mask[(size_t)row * D.W + w] = (uint32_t)(b >> lane);
     }
 }
 
@@ -272,15 +445,48 @@ __global__ __launch_bounds__(256) void apply_mask_scalar_kernel(const ElemT *__r
     }
 }
 
+uint32_t table_bytes(const DeviceTables &t, int mode) {
+    uint32_t n = 0;
+    if (mode <= 1) for (int k = 0; k < 6; k++) n += t.small_bytes[k];
+    if (mode == 0) for (int k = 0; k < 3; k++) n += t.big_bytes[k];
+    return n;
+}
+
 }  // namespace
 
+int choose_table_mode(const DeviceTables &t) {
+    if (table_bytes(t, 0) <= (uint32_t)TABLE_LDS_BUDGET) return 0;
+    if (table_bytes(t, 1) <= (uint32_t)TABLE_LDS_BUDGET) return 1;
+    return 2;
+}
+
+hipError_t prepare_kernels() {
+    const int max_lds = 160 * 1024;
+    hipError_t e;
+#define SET_ATTR(k) if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k), hipFuncAttributeMaxDynamicSharedMemorySize, max_lds)) != hipSuccess) return e
+    SET_ATTR(mask_main_kernel<0>); SET_ATTR(mask_main_kernel<1>); SET_ATTR(mask_main_kernel<2>);
+    SET_ATTR(mask_fallback2_kernel<0>); SET_ATTR(mask_fallback2_kernel<1>); SET_ATTR(mask_fallback2_kernel<2>);
+#undef SET_ATTR
+    return hipSuccess;
+}
+
 hipError_t launch_mask_main(const MaskArgs &a, hipStream_t s) {
-    dim3 grid((a.tab.n_chunks + 63) / 64, a.batch);
-    hipLaunchKernelGGL(mask_main_kernel, grid, dim3(64), 0, s, a);
+    dim3 grid((a.tab.n_chunks + MAIN_BLOCK - 1) / MAIN_BLOCK, a.batch);
+    const uint32_t lds = table_bytes(a.tab, a.mode) + BASE_LDS_BYTES + (MAIN_BLOCK / 64) * ((uint32_t)a.lane_cap * 64 * 6 + (LANE_DEPTH_MAX + 2) * 64);
+    if (a.mode == 0) hipLaunchKernelGGL(mask_main_kernel<0>, grid, dim3(MAIN_BLOCK), lds, s, a);
+    else if (a.mode == 1) hipLaunchKernelGGL(mask_main_kernel<1>, grid, dim3(MAIN_BLOCK), lds, s, a);
+    else hipLaunchKernelGGL(mask_main_kernel<2>, grid, dim3(MAIN_BLOCK), lds, s, a);
     return hipGetLastError();
 }
-hipError_t launch_mask_fallback(const MaskArgs &a, hipStream_t s) {
-    hipLaunchKernelGGL(mask_fallback_kernel, dim3(FB_LANES / 64), dim3(64), 0, s, a);
+hipError_t launch_mask_fallback2(const MaskArgs &a, hipStream_t s) {
+    const uint32_t lds = table_bytes(a.tab, a.mode) + FB2_CAP * 8 + (FB_DEPTH_MAX + 2) * 2 + 16;
+    if (a.mode == 0) hipLaunchKernelGGL(mask_fallback2_kernel<0>, dim3(FB2_BLOCKS), dim3(64), lds, s, a);
+    else if (a.mode == 1) hipLaunchKernelGGL(mask_fallback2_kernel<1>, dim3(FB2_BLOCKS), dim3(64), lds, s, a);
+    else hipLaunchKernelGGL(mask_fallback2_kernel<2>, dim3(FB2_BLOCKS), dim3(64), lds, s, a);
+    return hipGetLastError();
+}
+hipError_t launch_mask_fallback3(const MaskArgs &a, hipStream_t s) {
+    hipLaunchKernelGGL(mask_fallback3_kernel, dim3(FB3_LANES / 64), dim3(64), 0, s, a);
     return hipGetLastError();
 }
 hipError_t launch_permute(const MaskArgs &a, hipStream_t s) {

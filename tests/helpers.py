@@ -4,6 +4,15 @@ from workloads import vocab as wvocab
 from workloads.configs import pick_set_bit
 
 
+def load_trajectory(idx, rows, steps):
+    """Token ids per step and row from tests/golden/trajectory_cfgN.txt (-1 = reset)."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", f"trajectory_cfg{idx}.txt")
+    traj = [[int(x) for x in line.split()] for line in open(path) if line.strip() and not line.startswith("#")]
+    assert len(traj) >= steps and len(traj[0]) >= rows, "trajectory file too small for this test"
+    return [t[:rows] for t in traj[:steps]]
+
+
 def popcount(words) -> int:
     return int(np.unpackbits(np.ascontiguousarray(words).view(np.uint8)).sum())
 

@@ -4,7 +4,8 @@ import pytest
 
 from workloads import grammars, configs
 from workloads.rng import stream
-from tests.helpers import OracleRun, popcount
+from tests.helpers import OracleRun, popcount, load_trajectory
+from workloads import vocab as wvocab
 
 pytestmark = pytest.mark.gpu
 
@@ -59,12 +60,124 @@ def test_config2_json_v32k(torch_cuda, oracle_lib):
     _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(), cfg.batch, cfg.steps, cfg.seed)
 
 
-@pytest.mark.parametrize("cap", [1, 2, 4])
-def test_forced_overflow_gives_same_bits(cap, torch_cuda, oracle_lib):
+@pytest.mark.parametrize("cap,cap2", [(1, 0), (2, 0), (4, 0), (1, 1), (2, 3), (4, 8)])
+def test_forced_overflow_gives_same_bits(cap, cap2, torch_cuda, oracle_lib):
+    """Tiny item budgets push chunks to the LDS fallback (cap) and on to the global-memory
+    level (cap2); the bits must not change."""
     import paper_2506_01151_amd as zf
     cfg = configs.CONFIGS[1]
-    ov = _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(), 2, 24, cfg.seed + 77, lane_item_cap=cap)
+    ov = _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(), 2, 24, cfg.seed + 77,
+                     lane_item_cap=cap, fallback_item_cap=cap2)
     assert ov > 0, "the cap was meant to force the fallback pass"
+
+
+@pytest.mark.parametrize("chunk", [8, 16, 32])
+def test_chunk_sizes(chunk, torch_cuda, oracle_lib):
+    import paper_2506_01151_amd as zf
+    cfg = configs.CONFIGS[1]
+    _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(2048 - 37), 3, 32, cfg.seed + 5, chunk_strings=chunk)
+
+
+REPLAY = [  # config, rows, steps, check every, rows compared with the oracle per check, pruning
+    (3, 16, 512, 37, 16, True),
+    (4, 64, 256, 31, 12, True),
+    (5, 8, 192, 23, 8, True),
+    (5, 8, 192, 47, 8, False),
+]
+
+
+@pytest.mark.parametrize("idx,rows,steps,every,n_cmp,pruning", REPLAY, ids=[f"cfg{r[0]}-pruning{int(r[5])}" for r in REPLAY])
+def test_full_size_configs_replay(idx, rows, steps, every, n_cmp, pruning, torch_cuda, oracle_lib):
+    """Full vocabulary and batch of configurations 3-5 in the launch shape the benchmark uses:
+    replay the oracle-sampled trajectory on both sides; at sampled steps one compute_mask call
+    covers every row and sampled rows are compared bit for bit with the oracle's masks."""
+    import paper_2506_01151_amd as zf
+    torch = torch_cuda
+    cfg = configs.CONFIGS[idx]
+    toks = cfg.vocab()
+    off, data = wvocab.vocab_csr(toks)
+    traj = load_trajectory(idx, rows, steps)
+    g = cfg.grammar()
+    eng = zf.Engine(g, toks, device=0, pruning=pruning)
+    orc = oracle_lib.Oracle(g)
+    so = [orc.new_state() for _ in range(rows)]
+    ss = [eng.new_state() for _ in range(rows)]
+    d_mask = torch.empty((rows, eng.W), dtype=torch.int32, device="cuda")
+    pick = stream(cfg.seed, "parity-rows")
+    n_checked = 0
+    for step, ids in enumerate(traj):
+        for b, t in enumerate(ids):
+            if t < 0:
+                so[b] = orc.new_state()
+                ss[b].reset()
+            else:
+                assert so[b].feed_bytes(toks[t])
+                ss[b].advance(t)
+        if step % every == 0 or step == steps - 1:
+            d_mask.fill_(-1)
+            zf.compute_mask(eng, ss, d_mask)
+            got = d_mask.cpu().numpy().view(np.uint32)
+            cmp_rows = range(rows) if n_cmp >= rows else sorted({pick.below(rows) for _ in range(n_cmp)})
+            for b in cmp_rows:
+                want = so[b].mask(off, data, 16)
+                assert (got[b] == want).all(), f"cfg{idx} step {step} row {b}"
+                n_checked += 1
+    assert n_checked >= 8
+
+
+def test_edge_cases(torch_cuda, oracle_lib):
+    """Empty tokens, duplicates, a vocabulary smaller than one word, rows in different states,
+    a finished sentence (empty mask), V not a multiple of 32."""
+    import paper_2506_01151_amd as zf
+    torch = torch_cuda
+    g = grammars.json_grammar()
+    orc = oracle_lib.Oracle(g)
+    for toks in ([b"", b"1", b"1", b"", b"[", b"]", b"[]", b" ", b"x"],
+                 [b'"', b""] * 20 + [bytes([c]) for c in range(256)] + [b"tru", b"true", b"e", b'{"a":1}', b"}"]):
+        off, data = wvocab.vocab_csr(toks)
+        eng = zf.Engine(g, toks, device=0)
+        prefixes = [b"", b"[", b"[1", b"[]", b'{"a":1}', b"tr", b'{"k":"\\u12']
+        so, ss = [], []
+        for p in prefixes:
+            a, b = orc.new_state(), eng.new_state()
+            assert a.feed_bytes(p)
+            b.advance_bytes(p)
+            so.append(a)
+            ss.append(b)
+        d_mask = torch.full((len(prefixes), eng.W), -1, dtype=torch.int32, device="cuda")
+        zf.compute_mask(eng, ss, d_mask)
+        got = d_mask.cpu().numpy().view(np.uint32)
+        for i, a in enumerate(so):
+            assert (got[i] == a.mask(off, data, 1)).all(), (toks[:4], prefixes[i])
+    # a grammar whose sentence cannot be extended: after the last byte the mask is all zero
+    g2 = grammars.w2_grammar()
+    toks = [b"a", b"b", b"ab"]
+    eng = zf.Engine(g2, toks, device=0)
+    s = eng.new_state()
+    s.advance(2)
+    d_mask = torch.full((1, eng.W), -1, dtype=torch.int32, device="cuda")
+    zf.compute_mask(eng, [s], d_mask)
+    assert d_mask.cpu().numpy().view(np.uint32).tolist() == [[0]] and s.accepting()
+
+
+def test_apply_mask_full_size_bf16(torch_cuda, oracle_lib):
+    """Configuration 3's logits shape [16, 128256] bf16, mask from a real state."""
+    import paper_2506_01151_amd as zf
+    from oracle.frontend import apply_mask as oracle_apply
+    torch = torch_cuda
+    cfg = configs.CONFIGS[3]
+    eng = zf.Engine(cfg.grammar(), cfg.vocab(), device=0)
+    rng = np.random.default_rng(5)
+    mask = rng.integers(0, 2**32, size=(cfg.batch, eng.W), dtype=np.uint32)
+    mask[3] = 0
+    mask[4] = 0xFFFFFFFF
+    logits = configs.make_logits(cfg, 1, device="cuda")
+    d_mask = torch.from_numpy(mask.view(np.int32)).cuda()
+    out = torch.empty_like(logits)
+    zf.apply_mask(eng, logits, d_mask, out=out)
+    bits = logits.view(torch.int16).cpu().numpy().view(np.uint16)
+    want = oracle_apply(bits, mask)
+    assert out.view(torch.int16).cpu().numpy().view(np.uint16).tobytes() == want.tobytes()
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])

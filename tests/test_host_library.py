@@ -1,0 +1,236 @@
+"""CPU tests of the library's host side: the C boundary loads and exports what the header
+declares, error paths, and the host logic (grammar compiler, DFAs, trie, Earley advance,
+ZapFormat compaction) checked against the oracle through the host walk of the compiled tables.
+No GPU is touched: engines are compiled with device = -1."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from workloads import grammars, configs, vocab as wvocab
+from workloads.grammar import Grammar, Lit, Rx
+from workloads.rng import SplitMix64, stream
+from tests.helpers import OracleRun, popcount, load_trajectory
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def zf():
+    import paper_2506_01151_amd as zf
+    zf.load_library()
+    return zf
+
+
+def test_library_exports_every_declared_symbol(zf):
+    header = open(os.path.join(ROOT, "include", "zapformat.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(zf_[a-z0-9_]+)\s*\(", header))
+    assert len(declared) >= 20
+    lib = zf.load_library()
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} is declared in zapformat.h but not exported"
+    from paper_2506_01151_amd.binding import EXPORTS
+    assert declared == set(EXPORTS)
+
+
+def _all_strings(alphabet, max_len):
+    import itertools
+    for n in range(1, max_len + 1):
+        for tup in itertools.product(alphabet, repeat=n):
+            yield bytes(tup)
+
+
+SMALL = [(grammars.w1_grammar, b"ab"), (grammars.w2_grammar, b"ab"), (grammars.w3_grammar, b"ac+bd"),
+         (grammars.parens_grammar, b"()"), (grammars.anbn_grammar, b"ab"), (grammars.palindrome_grammar, b"ab"),
+         (grammars.nullable_chain_grammar, b"abcd"), (grammars.useless_grammar, b"abcux"),
+         (grammars.multibyte_literal_grammar, b"abc()"), (grammars.expr_grammar, b"a1+*()")]
+
+
+@pytest.mark.parametrize("pruning", [True, False])
+@pytest.mark.parametrize("gram,alphabet", SMALL, ids=[s[0].__name__ for s in SMALL])
+def test_small_grammars_every_prefix_every_token(gram, alphabet, pruning, zf, oracle_lib):
+    """Vocabulary = every string up to length 3 over the alphabet (+ an empty token); the host
+    walk must give the oracle's mask after every viable prefix up to length 4, and advance must
+    succeed exactly on the allowed tokens, for pruning on and off."""
+    g = gram()
+    toks = [b""] + list(_all_strings(alphabet, 3 if len(alphabet) <= 4 else 2))
+    off, data = wvocab.vocab_csr(toks)
+    eng = zf.Engine(g, toks, device=-1, pruning=pruning)
+    orc = oracle_lib.Oracle(g)
+    n_checked = 0
+    for p in [b""] + list(_all_strings(alphabet, 4 if len(alphabet) <= 4 else 3)):
+        so = orc.new_state()
+        s = eng.new_state()
+        ok = so.feed_bytes(p)
+        rc = s.try_advance_bytes(p)
+        assert (rc == zf.ZF_OK) == ok, p
+        if not ok:
+            assert rc == zf.ZF_ERR_REJECTED
+            continue
+        assert s.accepting() == so.accepting(), p
+        want = so.mask(off, data, 1)
+        got = s.debug_host_mask()
+        assert (got == want).all(), (p, [toks[v] for v in range(len(toks)) if ((int(got[v >> 5]) ^ int(want[v >> 5])) >> (v & 31)) & 1])
+        n_checked += 1
+        for v in range(0, len(toks), 3):       # advance(t) succeeds <=> bit t was 1; failure leaves the state alone
+            c = s.clone()
+            before = c.chart()
+            rc = c.try_advance(v)
+            bit = (int(want[v >> 5]) >> (v & 31)) & 1
+            assert (rc == zf.ZF_OK) == bool(bit), (p, toks[v])
+            if rc != zf.ZF_OK:
+                assert c.chart() == before and c.accepting() == s.accepting()
+    assert n_checked >= 3
+
+
+REGEXES = [grammars.NUMBER_RX.pattern, grammars.STRING_RX.pattern, rb"(ab|a)(bc|c)*", rb"a{2,4}b?", rb"[^a]+|a{3}",
+           rb"(a|)b{2,}", rb"x[0-9a-f]{2}\.\x41", rb"[ \t\n\r]+", rb"(a*b|ac)+d?"]
+
+
+@pytest.mark.parametrize("pattern", REGEXES, ids=[r.decode("latin1")[:30] for r in REGEXES])
+def test_regex_dfa_against_oracle_rules(pattern, zf, oracle_lib):
+    """The library turns a regex into a DFA, the oracle into grammar rules: the two must accept
+    and reject the same random strings (drawn from the pattern's own alphabet plus noise)."""
+    g = grammars.regex_only_grammar(pattern)
+    eng = zf.Engine(g, [b"a"], device=-1)
+    orc = oracle_lib.Oracle(g)
+    alphabet = sorted(set(pattern) | set(b'ab01."\\e-+\xc3\xa9\xe2\x82\xac\xf0\x9f\x98\x80 \n'))
+    rs = SplitMix64(99)
+    for _ in range(1500):
+        w = bytes(alphabet[rs.below(len(alphabet))] for _ in range(rs.below(9)))
+        so, s = orc.new_state(), eng.new_state()
+        ok = so.feed_bytes(w)
+        assert (s.try_advance_bytes(w) == zf.ZF_OK) == ok, w
+        if ok:
+            assert s.accepting() == so.accepting(), w
+
+
+def test_grammar_errors(zf):
+    def expect(code, g, toks=(b"a",)):
+        with pytest.raises(zf.ZfError) as ei:
+            zf.Engine(g, list(toks), device=-1)
+        assert ei.value.code == code, ei.value
+
+    g = Grammar(); g.set_start("S"); g.rule("S", [Rx(rb"a*")])            # terminal matches the empty string
+    expect(zf.ZF_ERR_GRAMMAR, g)
+    g = Grammar(); g.set_start("S"); g.rule("S", [Rx(rb"a[^\x00-\xff]")])  # empty language
+    expect(zf.ZF_ERR_GRAMMAR, g)
+    g = Grammar(); g.set_start("S"); g.rule("S", [Rx(rb"(ab")])            # syntax error
+    expect(zf.ZF_ERR_GRAMMAR, g)
+    g = Grammar(); g.set_start("S"); g.rule("S", [b"a", "S"])              # start derives nothing
+    expect(zf.ZF_ERR_GRAMMAR, g)
+    g = grammars.w2_grammar(); g.rules.append((0, [17]))                   # bad symbol id
+    expect(zf.ZF_ERR_GRAMMAR, g)
+    expect(zf.ZF_ERR_INVALID_ARG, grammars.w2_grammar(), [b"x" * 300])     # token longer than 255 bytes
+
+
+def test_state_errors_and_device_less_engine(zf):
+    eng = zf.Engine(grammars.w2_grammar(), [b"a", b"b", b"", b"ab"], device=-1)
+    s = eng.new_state()
+    assert s.try_advance(7) == zf.ZF_ERR_RANGE and s.try_advance(-1) == zf.ZF_ERR_RANGE
+    assert s.try_advance(2) == zf.ZF_ERR_REJECTED          # the empty token
+    assert s.try_advance(1) == zf.ZF_ERR_REJECTED
+    assert s.stats().bytes_fed == 0
+    s.advance(3)
+    assert s.accepting() and s.stats().bytes_fed == 2
+    s.reset()
+    assert not s.accepting() and s.stats().bytes_fed == 0
+    with pytest.raises(zf.ZfError) as ei:                    # no CPU substitute for the mask kernels
+        eng.compute_mask([s], 16)
+    assert ei.value.code == zf.ZF_ERR_DEVICE
+    with pytest.raises(zf.ZfError) as ei:
+        eng.apply_mask(16, 16, 0, 1, 8, 16)
+    assert ei.value.code == zf.ZF_ERR_DEVICE
+    lib = zf.load_library()
+    assert lib.zf_strerror(zf.ZF_ERR_REJECTED) and lib.zf_compute_mask(None, None, 1, None, None) == zf.ZF_ERR_INVALID_ARG
+
+
+def _lib_items(eng, state, names):
+    """Chart of a library state as {(set, lhs name, rule, dot, origin)} for user rules."""
+    items, n_sets = state.chart()
+    out = set()
+    for k, p, o, q in items:
+        lhs, rule, dot = eng.position_info(p)
+        if rule >= 0:
+            out.add((k, names[lhs], rule, dot, o))
+    return out, n_sets
+
+
+def test_w1_pruned_chart_is_constant_and_unpruned_grows(zf):
+    """Section 1 example, grammar A -> A B | B ; B -> a: with pruning the completed (B -> a .)
+    disappears as soon as its set is done and nothing but the start set and the current set
+    survives, however long the input; without pruning one set per byte is kept."""
+    g = grammars.w1_grammar()
+    pr = zf.Engine(g, [b"a"], device=-1, pruning=True)
+    un = zf.Engine(g, [b"a"], device=-1, pruning=False)
+    sp, su = pr.new_state(), un.new_state()
+    sizes = []
+    for n in range(1, 40):
+        sp.advance(0)
+        su.advance(0)
+        assert sp.accepting() and su.accepting()
+        st = sp.stats()
+        sizes.append((st.n_sets, st.n_items))
+        assert su.stats().n_sets == n + 1
+        items, _ = _lib_items(pr, sp, g.nonterminals)
+        # rule 0 is A -> A B: the only user item that must survive is (A -> A . B, origin 0) in the last set
+        assert (st.n_sets - 1, "A", 0, 1, 0) in items
+        assert not any(dot == 1 and lhs == "B" for _, lhs, _, dot, _ in items)      # (B -> a .) is gone
+    assert len(set(sizes)) == 1 and sizes[0][0] <= 2, sizes
+    assert su.stats().n_items > 5 * sp.stats().n_items
+
+
+def test_hrr_only_grammar_keeps_chart_bounded(zf):
+    """Rules of the forms A -> c, A -> B a, A -> eps only (Section 4.1, high-level regular rules):
+    the pruned chart must not grow with the input."""
+    g = Grammar(); g.set_start("L")
+    g.alts("L", [], ["L", "I"])             # list of items: L -> eps | L I
+    g.alts("I", [b"x"], ["P", b";"])        # I -> c | B a
+    g.alts("P", [b"y"], ["P", b"y"])
+    eng = zf.Engine(g, [b"x", b"y", b";"], device=-1)
+    s = eng.new_state()
+    rs = SplitMix64(5)
+    sizes = []
+    text = b""
+    for _ in range(300):
+        m = s.debug_host_mask()
+        allowed = [v for v in range(3) if (int(m[0]) >> v) & 1]
+        v = allowed[rs.below(len(allowed))]
+        s.advance(v)
+        sizes.append(s.stats().n_items)
+    assert max(sizes) <= 8, max(sizes)
+
+
+@pytest.mark.parametrize("idx,rows,steps,every", [(1, 1, 64, 1), (2, 1, 256, 8), (3, 2, 200, 25), (4, 2, 120, 20), (5, 2, 96, 12)])
+def test_config_trajectories_host_walk_matches_oracle(idx, rows, steps, every, zf, oracle_lib):
+    """Replay the oracle-sampled trajectory of each configuration; at sampled steps the host walk
+    of the compiled tables (pruning on and off) must reproduce the oracle's mask bit for bit, and
+    advance must accept exactly the tokens the oracle fed."""
+    cfg = configs.CONFIGS[idx]
+    toks = cfg.vocab()
+    traj = load_trajectory(idx, rows, steps)
+    off, data = wvocab.vocab_csr(toks)
+    g = cfg.grammar()
+    orc = oracle_lib.Oracle(g)
+    engines = [zf.Engine(g, toks, device=-1, pruning=True), zf.Engine(g, toks, device=-1, pruning=False)]
+    for b in range(rows):
+        so = orc.new_state()
+        ss = [e.new_state() for e in engines]
+        for step, ids in enumerate(traj):
+            t = ids[b]
+            if t < 0:
+                so = orc.new_state()
+                for s in ss:
+                    s.reset()
+            else:
+                assert so.feed_bytes(toks[t])
+                for s in ss:
+                    s.advance(t)
+            if step % every == 0:
+                want = so.mask(off, data, 8)
+                for s in ss:
+                    assert (s.debug_host_mask() == want).all(), (idx, b, step)
+                    assert s.accepting() == so.accepting()
+        assert ss[0].stats().n_items <= ss[1].stats().n_items
