@@ -72,6 +72,8 @@ typedef struct {
     int32_t chunk_strings; /* vocabulary strings walked by one lane: 8, 16 or 32; 0 = default */
     int32_t fallback_item_cap; /* item budget of the LDS fallback level, 0 = default (2048); tests
                                   set it low to force the last, global-memory level */
+    int32_t disable_token_mask_cache; /* 1 = every token goes through the parser walk (Section 4.3
+                                  optimisation off); masks are identical either way */
 } zf_options;
 
 typedef struct {
@@ -148,6 +150,10 @@ int zf_debug_host_mask(zf_engine *e, const zf_state *s, uint32_t *mask /* host [
  * live set, largest item count of one trie path, largest single set, chunks whose path
  * outgrows lane_item_cap (an estimate of what the fallback pass receives). */
 int zf_debug_host_mask_stats(zf_engine *e, const zf_state *s, uint32_t *mask /* host [W] */, int64_t *stats);
+/* Diagnostic: host walk that first merges the context-independent token-mask cache (Section
+ * 4.3) of the current set's items and sends only the undecided strings through the parser, as
+ * the kernel does.  stats[0..2] (host, may be null): byte steps, undecided strings, cache rows. */
+int zf_debug_host_mask_cached(zf_engine *e, const zf_state *s, uint32_t *mask /* host [W] */, int64_t *stats);
 
 #ifdef __cplusplus
 }

@@ -86,10 +86,12 @@ int setup_device(zf_engine *e) {
     UP(delta, t.delta_dense, &T.big_bytes[0]); UP(scan_list, t.scan_list, &T.big_bytes[1]); UP(comp_list, t.comp_list, &T.big_bytes[2]);
     UP(nodes, tr.nodes, nullptr); UP(parent, tr.parent, nullptr); UP(chunk_begin, tr.chunk_begin, nullptr); UP(chunk_end, tr.chunk_end, nullptr);
     UP(chunk_anc, tr.chunk_anc, nullptr); UP(rank_of, tr.rank_of, nullptr);
+    UP(ci_valid, tr.ci_valid, nullptr); UP(ci_cd, tr.ci_cd, nullptr);
+    T.Q = t.Q;
 #undef UP
     T.N = t.N; T.n_cls = t.n_cls; T.end_base = t.end_base; T.n_nodes = (int)tr.nodes.size(); T.n_chunks = (int)tr.chunk_begin.size();
     T.n_strings = tr.n_strings; T.V = e->V; T.W = e->W; T.chunk_ranks = tr.chunk_ranks;
-    T.Wr = (T.n_chunks * tr.chunk_ranks + 31) / 32;
+    T.Wr = tr.Wr;
     d->mode = choose_table_mode(T);
     HIP_TRY(prepare_kernels());
     HIP_TRY(hipMalloc((void **)&d->d_counters, 16));
@@ -97,6 +99,23 @@ int setup_device(zf_engine *e) {
     HIP_TRY(hipMalloc((void **)&d->d_fb_items, (size_t)FB3_ITEMS_PER_LANE * FB3_LANES * sizeof(uint2)));
     HIP_TRY(hipMalloc((void **)&d->d_fb_ss, (size_t)(FB_DEPTH_MAX + 2) * FB3_LANES * sizeof(uint32_t)));
     return ZF_OK;
+}
+
+// Rows of the token-mask cache that the items of the current set select: the DFA state of an
+// item that stands inside (or before) a terminal, Q + Y for an item that waits for nonterminal Y.
+uint32_t current_set_entries(const Tables &t, const Chart &c, uint32_t *out) {
+    uint32_t n = 0;
+    for (uint32_t i = c.set_off[c.n_sets() - 1]; i < c.set_off[c.n_sets()]; i++) {
+        uint16_t code = t.sym[c.items[i].p];
+        uint32_t row;
+        if ((code >> SYM_KIND_SHIFT) == SYM_TERM) row = c.items[i].q;
+        else if ((code >> SYM_KIND_SHIFT) == SYM_NT) row = (uint32_t)t.Q + (code & SYM_ID_MASK_NT);
+        else continue;
+        bool dup = false;
+        for (uint32_t k = 0; k < n && !dup; k++) dup = out[k] == row;
+        if (!dup) out[n++] = row;
+    }
+    return n;
 }
 
 int feed_token_bytes(zf_state *s, const uint8_t *bytes, int64_t n) {
@@ -151,7 +170,7 @@ int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_option
     }
     zf_engine *e = new (std::nothrow) zf_engine();
     if (!e) return fail(ZF_ERR_OOM, "out of memory");
-    e->opt = opt ? *opt : zf_options{1, 0, 0, 0, 0};
+    e->opt = opt ? *opt : zf_options{1, 0, 0, 0, 0, 0};
     if (e->opt.lane_item_cap <= 0) e->opt.lane_item_cap = LANE_CAP_DEFAULT;
     if (e->opt.lane_item_cap > LANE_CAP_MAX) e->opt.lane_item_cap = LANE_CAP_MAX;
     if (e->opt.fallback_item_cap <= 0 || e->opt.fallback_item_cap > FB2_CAP) e->opt.fallback_item_cap = FB2_CAP;
@@ -162,6 +181,7 @@ int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_option
         e->voc_off.assign(v->off, v->off + v->V + 1);
         e->voc_bytes.assign(v->bytes, v->bytes + v->off[v->V]);
         build_trie(v, e->opt.chunk_strings, e->trie);
+        build_token_mask_cache(e->tab, e->trie);
     } catch (const std::bad_alloc &) { delete e; return fail(ZF_ERR_OOM, "out of memory"); }
     if (e->opt.device >= 0) {
         int rc = setup_device(e);
@@ -269,6 +289,39 @@ int zf_position_info(const zf_engine *e, int32_t p, int32_t *lhs, int32_t *rule,
 
 int zf_debug_host_mask(zf_engine *e, const zf_state *s, uint32_t *mask) { return zf_debug_host_mask_stats(e, s, mask, nullptr); }
 
+int zf_debug_host_mask_cached(zf_engine *e, const zf_state *s, uint32_t *mask, int64_t *stats) {
+    if (!e || !s || !mask || s->eng != e) return fail(ZF_ERR_INVALID_ARG, "bad argument");
+    const Tables &t = e->tab;
+    const Trie &tr = e->trie;
+    Chart c = s->chart;
+    const uint32_t m0 = c.n_sets();
+    std::vector<uint32_t> ents(c.set_off[m0] - c.set_off[m0 - 1] + 1);
+    const uint32_t n_ent = current_set_entries(t, c, ents.data());
+    std::vector<uint32_t> valid(tr.Wr, 0), want(tr.Wr, 0);
+    for (uint32_t k = 0; k < n_ent; k++)
+        for (int w = 0; w < tr.Wr; w++) { valid[w] |= tr.ci_valid[(size_t)ents[k] * tr.Wr + w]; want[w] |= tr.ci_cd[(size_t)ents[k] * tr.Wr + w]; }
+    for (int w = 0; w < tr.Wr; w++) want[w] &= ~valid[w];
+    auto any_in = [&](uint32_t lo, uint32_t hi) { for (uint32_t r = lo; r < hi; r++) if ((want[r >> 5] >> (r & 31)) & 1) return true; return false; };
+    int64_t n_steps = 0, n_wanted = 0;
+    for (int w = 0; w < tr.Wr; w++) n_wanted += __builtin_popcount(want[w]);
+    for (uint32_t i = 0; i < tr.nodes.size();) {
+        const TrieNode &nd = tr.nodes[i];
+        if (!any_in(nd.rank, nd.rank + nd.n_sub)) { i = nd.skip; continue; }
+        c.truncate(m0 + nd.depth - 1);
+        StepResult r = earley_step(t, c, nd.byte, false, nullptr);
+        n_steps++;
+        if (nd.has_string && r.alive && ((want[nd.rank >> 5] >> (nd.rank & 31)) & 1)) valid[nd.rank >> 5] |= 1u << (nd.rank & 31);
+        i = r.kernel_nonempty ? i + 1 : nd.skip;
+    }
+    memset(mask, 0, sizeof(uint32_t) * e->W);
+    for (int v = 0; v < e->V; v++) {
+        uint32_t r = tr.rank_of[v];
+        if (r != 0xFFFFFFFFu && ((valid[r >> 5] >> (r & 31)) & 1)) mask[v >> 5] |= 1u << (v & 31);
+    }
+    if (stats) { stats[0] = n_steps; stats[1] = n_wanted; stats[2] = n_ent; }
+    return ZF_OK;
+}
+
 int zf_debug_host_mask_stats(zf_engine *e, const zf_state *s, uint32_t *mask, int64_t *stats) {
     if (!e || !s || !mask || s->eng != e) return fail(ZF_ERR_INVALID_ARG, "bad argument");
     int64_t n_steps = 0, n_alive = 0, max_path = 0, max_set = 0, chunks_over = 0;
@@ -308,15 +361,19 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     hipStream_t stream = (hipStream_t)hip_stream;
     HIP_TRY(hipSetDevice(d->device));
     // ---- pack the charts: [RowChart x batch][set offsets][items] ----
-    size_t n_off = 0, n_items = 0;
+    size_t n_off = 0, n_items = 0, n_ent = 0;
+    const bool use_cache = !e->opt.disable_token_mask_cache;
     for (int b = 0; b < batch; b++) {
         if (!states[b] || states[b]->eng != e) return fail(ZF_ERR_INVALID_ARG, "state " + std::to_string(b) + " is null or belongs to another engine");
-        n_off += states[b]->chart.set_off.size();
-        n_items += states[b]->chart.items.size();
+        const Chart &c = states[b]->chart;
+        n_off += c.set_off.size();
+        n_items += c.items.size();
+        if (use_cache) n_ent += c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1];
     }
     auto align16 = [](size_t x) { return (x + 15) & ~(size_t)15; };
     const size_t off_rows = 0, off_so = align16(sizeof(RowChart) * batch), off_items = align16(off_so + 4 * n_off);
-    const size_t total = off_items + sizeof(Item) * n_items + 16;
+    const size_t off_ent = align16(off_items + sizeof(Item) * n_items);
+    const size_t total = off_ent + 4 * n_ent + 16;
     if (total > d->stage_cap) {
         if (d->h_stage) (void)hipHostFree(d->h_stage);
         if (d->d_chart) (void)hipFree(d->d_chart);
@@ -331,10 +388,13 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
         RowChart *rows = (RowChart *)(h + off_rows);
         uint32_t *so = (uint32_t *)(h + off_so);
         Item *items = (Item *)(h + off_items);
-        uint32_t so_at = 0, it_at = 0;
+        uint32_t *ents = (uint32_t *)(h + off_ent);
+        uint32_t so_at = 0, it_at = 0, en_at = 0;
         for (int b = 0; b < batch; b++) {
             const Chart &c = states[b]->chart;
-            rows[b] = RowChart{c.n_sets(), so_at, it_at, 0};
+            rows[b] = RowChart{c.n_sets(), so_at, it_at, en_at, 0, {0, 0, 0}};
+            if (use_cache) rows[b].n_ent = current_set_entries(e->tab, c, ents + en_at);
+            en_at += rows[b].n_ent;
             memcpy(so + so_at, c.set_off.data(), 4 * c.set_off.size());
             if (!c.items.empty()) memcpy(items + it_at, c.items.data(), sizeof(Item) * c.items.size());
             so_at += (uint32_t)c.set_off.size(); it_at += (uint32_t)c.items.size();
@@ -358,6 +418,7 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     a.rows = (const RowChart *)((uint8_t *)d->d_chart + off_rows);
     a.set_off = (const uint32_t *)((uint8_t *)d->d_chart + off_so);
     a.items = (const Item *)((uint8_t *)d->d_chart + off_items);
+    a.entries = (const uint32_t *)((uint8_t *)d->d_chart + off_ent);
     a.rank_mask = d->d_rank_mask;
     a.out_mask = d_mask;
     a.counters = d->d_counters;

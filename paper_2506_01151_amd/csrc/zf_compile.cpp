@@ -198,6 +198,7 @@ bool build_tables(const zf_grammar_desc *g, Tables &t) {
             if (s < 0 || !nullable[s]) break;
         }
     t.reach.assign((size_t)N * N, 0);
+    t.first_terms.assign(N, {});
     t.scan_off.assign((size_t)N * t.n_cls + 1, 0);
     t.comp_off.assign((size_t)N * N + 1, 0);
     t.scan_list.clear(); t.comp_list.clear();
@@ -223,6 +224,8 @@ bool build_tables(const zf_grammar_desc *g, Tables &t) {
             uint16_t code = t.sym[p];
             if ((code >> SYM_KIND_SHIFT) == SYM_TERM) {
                 int term = code & SYM_ID_MASK;
+                if (std::find(t.first_terms[Y].begin(), t.first_terms[Y].end(), (uint16_t)term) == t.first_terms[Y].end())
+                    t.first_terms[Y].push_back((uint16_t)term);
                 for (int c = 0; c < t.n_cls; c++) {
                     uint16_t to = t.delta[(size_t)t.term_start[term] * t.n_cls + c];
                     if (to != DFA_DEAD) scan_tmp[Y][c].push_back((uint32_t)p | ((uint32_t)to << 16));
@@ -295,6 +298,10 @@ void build_trie(const zf_vocab_desc *v, int CHUNK_RANKS, Trie &t) {
             open.push_back(i);
         }
         for (uint32_t i : open) t.nodes[i].skip = n;
+        for (uint32_t i = 0; i < n; i++) {
+            uint32_t end_rank = t.nodes[i].skip < n ? t.nodes[t.nodes[i].skip].rank : (uint32_t)t.n_strings;
+            t.nodes[i].n_sub = end_rank - t.nodes[i].rank;
+        }
     }
     // chunks of CHUNK_RANKS strings: [node that carries rank 32c, node that carries the chunk's last rank + 1)
     int n_chunks = (t.n_strings + CHUNK_RANKS - 1) / CHUNK_RANKS;
@@ -304,6 +311,7 @@ void build_trie(const zf_vocab_desc *v, int CHUNK_RANKS, Trie &t) {
         if (r % CHUNK_RANKS == 0) t.chunk_begin[r / CHUNK_RANKS] = i;
         t.chunk_end[r / CHUNK_RANKS] = i + 1;
     }
+    t.Wr = (n_chunks * CHUNK_RANKS + 31) / 32;
     // ancestors of each chunk's first node (top down), for the lanes that start in mid-trie
     t.chunk_anc.assign((size_t)n_chunks * CHUNK_ANC, 0);
     for (int c = 0; c < n_chunks; c++) {
@@ -312,6 +320,56 @@ void build_trie(const zf_vocab_desc *v, int CHUNK_RANKS, Trie &t) {
         for (uint32_t a = t.parent[i]; a != 0xFFFFFFFFu; a = t.parent[a]) {
             d--;
             if (d - 1 < CHUNK_ANC) t.chunk_anc[(size_t)c * CHUNK_ANC + d - 1] = a;
+        }
+    }
+}
+
+}  // namespace zf
+
+namespace zf {
+
+// For every DFA state q: run the DFA alone from q down the trie.  A string the DFA survives is
+// valid whatever the context (the in-progress terminal item survives or has just completed).  A
+// string on which the DFA dies is hopeless for this item unless the DFA passed an accepting state
+// first -- then the terminal may end there and what follows depends on the parser.  Rows of
+// nonterminals are the union over the terminals that can begin them.
+void build_token_mask_cache(const Tables &t, Trie &tr) {
+    const int Wr = tr.Wr, rows = t.Q + t.N;
+    tr.ci_valid.assign((size_t)rows * Wr, 0);
+    tr.ci_cd.assign((size_t)rows * Wr, 0);
+    const uint32_t n = (uint32_t)tr.nodes.size();
+    auto fill = [](uint32_t *bits, uint32_t lo, uint32_t hi) {   // set bits [lo, hi)
+        while (lo < hi) {
+            uint32_t w = lo >> 5, b = lo & 31, cnt = std::min<uint32_t>(32 - b, hi - lo);
+            bits[w] |= (cnt == 32 ? 0xFFFFFFFFu : ((1u << cnt) - 1)) << b;
+            lo += cnt;
+        }
+    };
+    std::vector<uint16_t> st(MAX_TOKEN_LEN_ON_DEVICE + 2);
+    std::vector<uint8_t> acc(MAX_TOKEN_LEN_ON_DEVICE + 2);
+    for (int q = 0; q < t.Q; q++) {
+        if (!(t.qflags[q] & QF_CONT)) continue;   // no item ever waits in a state without outgoing edges
+        uint32_t *V = &tr.ci_valid[(size_t)q * Wr], *C = &tr.ci_cd[(size_t)q * Wr];
+        st[0] = (uint16_t)q; acc[0] = 0;
+        for (uint32_t i = 0; i < n;) {
+            const TrieNode &nd = tr.nodes[i];
+            const int d = nd.depth;
+            uint16_t s2 = t.delta[(size_t)st[d - 1] * t.n_cls + t.cls[nd.byte]];
+            if (s2 == DFA_DEAD) {
+                if (acc[d - 1]) fill(C, nd.rank, nd.rank + nd.n_sub);
+                i = nd.skip;
+            } else {
+                st[d] = s2; acc[d] = acc[d - 1] | (t.qflags[s2] & QF_ACCEPT);
+                if (nd.has_string) V[nd.rank >> 5] |= 1u << (nd.rank & 31);
+                i++;
+            }
+        }
+    }
+    for (int Y = 0; Y < t.N; Y++) {
+        uint32_t *V = &tr.ci_valid[(size_t)(t.Q + Y) * Wr], *C = &tr.ci_cd[(size_t)(t.Q + Y) * Wr];
+        for (uint16_t term : t.first_terms[Y]) {
+            const uint32_t *v = &tr.ci_valid[(size_t)t.term_start[term] * Wr], *c = &tr.ci_cd[(size_t)t.term_start[term] * Wr];
+            for (int w = 0; w < Wr; w++) { V[w] |= v[w]; C[w] |= c[w]; }
         }
     }
 }

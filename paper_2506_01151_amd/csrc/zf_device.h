@@ -34,7 +34,7 @@ struct TrieNode {
     uint32_t skip;
     uint32_t rank;
     uint8_t byte, depth, has_string, pad;
-    uint32_t pad2;
+    uint32_t n_sub;      // strings carried by this node's subtree (itself included)
 };
 
 static const int MAX_TOKEN_LEN_ON_DEVICE = 255;   // deeper nodes never occur: depth is a uint8
@@ -60,6 +60,11 @@ struct DeviceTables {
     const uint32_t *chunk_end;   // [n_chunks] one past the last string node of the chunk
     const uint32_t *chunk_anc;   // [n_chunks][CHUNK_ANC] ancestors of the chunk's first node, depth 1 first
     const uint32_t *rank_of;    // [V] rank of token v's string, 0xFFFFFFFF for the empty token
+    // Context-independent token-mask cache (paper Section 4.3), one bitset row of Wr words per DFA
+    // state q (row q) and per nonterminal Y (row Q + Y), in string-rank order:
+    const uint32_t *ci_valid;   // strings a terminal entered in state q swallows whole
+    const uint32_t *ci_cd;      // strings on which that terminal dies after passing an accepting state
+    int32_t Q;
     int32_t N, n_cls, end_base, n_nodes, n_chunks, n_strings, V, W;
     int32_t chunk_ranks;        // strings per chunk: 8, 16 or 32
     int32_t Wr;                 // 32-bit words per row of the rank-ordered verdict bitmap
@@ -71,7 +76,9 @@ struct RowChart {
     uint32_t n_sets;     // m; the last set (m-1) is the current one
     uint32_t set_base;   // index into the shared set_off array
     uint32_t item_base;  // index into the shared item array
-    uint32_t pad;
+    uint32_t ent_base;   // index into the shared entry array: bitset rows of the current set's items
+    uint32_t n_ent;      // 0 = token-mask cache not used for this row
+    uint32_t pad[3];
 };
 
 }  // namespace zf

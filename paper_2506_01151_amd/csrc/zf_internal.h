@@ -40,6 +40,7 @@ struct Tables {
     std::vector<uint32_t> qinfo;      // [Q] flags | literal byte << 8 | dense row << 16
     std::vector<uint16_t> delta_dense; // rows of the non-literal states only
     int end_base = 0;                 // end_pos[X] == end_base + X
+    std::vector<std::vector<uint16_t>> first_terms;   // [N] terminals that can begin a derivation of Y
     std::vector<uint16_t> term_start; // [T]
     std::vector<uint32_t> scan_off, scan_list;
     std::vector<uint32_t> comp_off;
@@ -59,7 +60,12 @@ struct Trie {
     std::vector<uint32_t> rank_of;    // [V]
     int n_strings = 0;
     int chunk_ranks = 32;
+    int Wr = 0;                       // words per row of a rank-ordered bitmap
+    std::vector<uint32_t> ci_valid, ci_cd;   // [(Q + N) * Wr]
 };
+// Context-independent token-mask cache (Section 4.3): per DFA state and per nonterminal, which
+// strings are decided by the terminal alone and which need the parser.
+void build_token_mask_cache(const Tables &t, Trie &tr);
 void build_trie(const zf_vocab_desc *v, int chunk_ranks, Trie &t);
 
 // ---- chart --------------------------------------------------------------------------------------

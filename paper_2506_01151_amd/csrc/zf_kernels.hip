@@ -223,8 +223,10 @@ __device__ __forceinline__ int earley_step(const TV &T, const Base &B, S &st, in
 
 // Walk the nodes of one chunk.  anc(j) gives the node index of the first node's ancestor at
 // depth j+1.  Returns false on overflow; otherwise *bits_out holds the chunk's verdicts.
+// `want` marks the strings of the chunk that still need a verdict (the others are decided by the
+// token-mask cache); subtrees without such a string are skipped without a byte step.
 template <class S, class Anc>
-__device__ __forceinline__ bool walk_chunk(const DeviceTables &D, const TV &T, const Base &B, S &st, uint32_t chunk, Anc anc, uint32_t *bits_out) {
+__device__ __forceinline__ bool walk_chunk(const DeviceTables &D, const TV &T, const Base &B, S &st, uint32_t chunk, uint32_t want, Anc anc, uint32_t *bits_out) {
     uint32_t i = D.chunk_begin[chunk];
     const uint32_t end = D.chunk_end[chunk];
     const uint32_t rank0 = chunk * (uint32_t)D.chunk_ranks;
@@ -248,6 +250,17 @@ __device__ __forceinline__ bool walk_chunk(const DeviceTables &D, const TV &T, c
         TrieNode nx = nd;
         if (nxt < end) nx = D.nodes[nxt];                // issued before the step so that it overlaps it
         const int d = nd.depth;
+        {
+            const uint32_t rel = nd.rank - rank0;
+            const uint32_t span = (nd.n_sub >= 32u ? 0xFFFFFFFFu : ((1u << nd.n_sub) - 1u)) << rel;
+            if (!(span & want)) {                        // nothing to decide below this node
+                const uint32_t ni = nd.skip;
+                if (ni == nxt) nd = nx;
+                else if (ni < end) nd = D.nodes[ni];
+                i = ni;
+                continue;
+            }
+        }
         if (d > S::max_depth) return false;
         cnt = st.start(d);                               // forget the sets of the deeper path we came from
         const int r = earley_step(T, B, st, d, nd.byte, cnt);
@@ -260,6 +273,27 @@ __device__ __forceinline__ bool walk_chunk(const DeviceTables &D, const TV &T, c
     }
     *bits_out = bits;
     return true;
+}
+
+__device__ __forceinline__ uint32_t load_bits(const DeviceTables &D, const uint32_t *bitmap_row, uint32_t chunk) {
+    const uint8_t *rowp = reinterpret_cast<const uint8_t *>(bitmap_row);
+    if (D.chunk_ranks == 32) return reinterpret_cast<const uint32_t *>(rowp)[chunk];
+    if (D.chunk_ranks == 16) return reinterpret_cast<const uint16_t *>(rowp)[chunk];
+    return rowp[chunk];
+}
+
+// Token-mask cache (Section 4.3): merge the cached bitsets of every item of the row's current set.
+// valid: strings some terminal swallows whole; want: strings that need the parser.
+__device__ __forceinline__ void cached_verdicts(const MaskArgs &a, const RowChart &rc, uint32_t chunk, uint32_t &valid, uint32_t &want) {
+    const DeviceTables &D = a.tab;
+    if (rc.n_ent == 0) { valid = 0; want = D.chunk_ranks == 32 ? 0xFFFFFFFFu : ((1u << D.chunk_ranks) - 1u); return; }
+    uint32_t v = 0, c = 0;
+    for (uint32_t k = 0; k < rc.n_ent; k++) {
+        const size_t r = (size_t)a.entries[rc.ent_base + k] * D.Wr;
+        v |= load_bits(D, D.ci_valid + r, chunk);
+        c |= load_bits(D, D.ci_cd + r, chunk);
+    }
+    valid = v; want = c & ~v;
 }
 
 __device__ __forceinline__ void store_bits(const DeviceTables &D, uint32_t *rank_mask, uint32_t row, uint32_t chunk, uint32_t bits) {
@@ -299,6 +333,9 @@ __global__ __launch_bounds__(MAIN_BLOCK) void mask_main_kernel(MaskArgs a) {
     __syncthreads();
     const uint32_t chunk = blockIdx.x * MAIN_BLOCK + tid;
     if (chunk >= (uint32_t)D.n_chunks) return;
+    uint32_t valid, want;
+    cached_verdicts(a, rc, chunk, valid, want);
+    if (!want) { store_bits(D, a.rank_mask, row, chunk, valid); return; }
     const uint32_t wave = tid >> 6, lane = tid & 63;
     const uint32_t cap = (uint32_t)a.lane_cap;
     uint8_t *region = smem + off + wave * lane_region_bytes(cap);
@@ -310,13 +347,13 @@ __global__ __launch_bounds__(MAIN_BLOCK) void mask_main_kernel(MaskArgs a) {
     const uint32_t *anc_row = D.chunk_anc + (size_t)chunk * CHUNK_ANC;
     uint32_t bits = 0;
     bool ok = cap > 0 && B.m + LANE_DEPTH_MAX < 0xFFFFu &&
-              walk_chunk(D, T, B, st, chunk, [&](int j) { return anc_row[j]; }, &bits);
+              walk_chunk(D, T, B, st, chunk, want, [&](int j) { return anc_row[j]; }, &bits);
     if (!ok) {
         const uint32_t slot = atomicAdd(&a.counters[0], 1u);
         if (slot < a.overflow_cap) a.overflow_list[slot] = make_uint2(row, chunk);
         bits = 0;
     }
-    store_bits(D, a.rank_mask, row, chunk, bits);
+    store_bits(D, a.rank_mask, row, chunk, valid | (bits & want));
 }
 
 struct ParentAnc {             // ancestor at depth j+1 through the parent links
@@ -360,13 +397,14 @@ __global__ __launch_bounds__(64) void mask_fallback2_kernel(MaskArgs a) {
         const Base B = global_base(a, ent.x);
         const uint32_t first = D.chunk_begin[ent.y];
         ParentAnc anc{D.parent, first, D.nodes[first].depth};
-        uint32_t bits = 0;
-        if (!walk_chunk(D, T, B, st, ent.y, anc, &bits)) {
+        uint32_t bits = 0, valid, want;
+        cached_verdicts(a, a.rows[ent.x], ent.y, valid, want);
+        if (!walk_chunk(D, T, B, st, ent.y, want, anc, &bits)) {
             const uint32_t slot = atomicAdd(&a.counters[1], 1u);
             if (slot < a.overflow_cap) a.overflow_list2[slot] = ent;
             bits = 0;
         }
-        store_bits(D, a.rank_mask, ent.x, ent.y, bits);
+        store_bits(D, a.rank_mask, ent.x, ent.y, valid | (bits & want));
     }
 }
 
@@ -384,9 +422,10 @@ __global__ __launch_bounds__(64) void mask_fallback3_kernel(MaskArgs a) {
         const Base B = global_base(a, ent.x);
         const uint32_t first = D.chunk_begin[ent.y];
         ParentAnc anc{D.parent, first, D.nodes[first].depth};
-        uint32_t bits = 0;
-        if (!walk_chunk(D, T, B, st, ent.y, anc, &bits)) { atomicAdd(&a.counters[2], 1u); bits = 0; }
-        store_bits(D, a.rank_mask, ent.x, ent.y, bits);
+        uint32_t bits = 0, valid, want;
+        cached_verdicts(a, a.rows[ent.x], ent.y, valid, want);
+        if (!walk_chunk(D, T, B, st, ent.y, want, anc, &bits)) { atomicAdd(&a.counters[2], 1u); bits = 0; }
+        store_bits(D, a.rank_mask, ent.x, ent.y, valid | (bits & want));
     }
 }
 

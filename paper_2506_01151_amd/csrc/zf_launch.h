@@ -23,6 +23,7 @@ struct MaskArgs {
     const RowChart *rows;      // [batch]
     const uint32_t *set_off;   // shared CSR offsets of all rows' sets
     const Item *items;         // shared item array of all rows
+    const uint32_t *entries;   // shared array of token-mask-cache rows (see RowChart)
     uint32_t *rank_mask;       // [batch][Wr] verdicts in trie (rank) order
     uint32_t *out_mask;        // [batch][W] verdicts in token-id order
     uint32_t *counters;        // [0] chunks passed to level 2, [1] chunks passed to level 3, [2] unresolved

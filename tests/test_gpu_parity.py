@@ -48,10 +48,11 @@ def _run_parity(torch, zf, Oracle, grammar, tokens, batch, steps, seed, check_ev
     return overflow
 
 
-def test_config1_json_v2k_all_steps(torch_cuda, oracle_lib):
+@pytest.mark.parametrize("cache", [True, False], ids=["token-mask-cache", "parser-only"])
+def test_config1_json_v2k_all_steps(cache, torch_cuda, oracle_lib):
     import paper_2506_01151_amd as zf
     cfg = configs.CONFIGS[1]
-    _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(), cfg.batch, cfg.steps, cfg.seed)
+    _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(), cfg.batch, cfg.steps, cfg.seed, token_mask_cache=cache)
 
 
 def test_config2_json_v32k(torch_cuda, oracle_lib):
@@ -83,10 +84,11 @@ REPLAY = [  # config, rows, steps, check every, rows compared with the oracle pe
     (4, 64, 256, 31, 12, True),
     (5, 8, 192, 23, 8, True),
     (5, 8, 192, 47, 8, False),
+    (3, 16, 512, 61, 16, None),    # None: pruning on, token-mask cache off (every token through the parser)
 ]
 
 
-@pytest.mark.parametrize("idx,rows,steps,every,n_cmp,pruning", REPLAY, ids=[f"cfg{r[0]}-pruning{int(r[5])}" for r in REPLAY])
+@pytest.mark.parametrize("idx,rows,steps,every,n_cmp,pruning", REPLAY, ids=[f"cfg{r[0]}-" + {True: "pruned", False: "unpruned", None: "parser-only"}[r[5]] for r in REPLAY])
 def test_full_size_configs_replay(idx, rows, steps, every, n_cmp, pruning, torch_cuda, oracle_lib):
     """Full vocabulary and batch of configurations 3-5 in the launch shape the benchmark uses:
     replay the oracle-sampled trajectory on both sides; at sampled steps one compute_mask call
@@ -98,7 +100,7 @@ def test_full_size_configs_replay(idx, rows, steps, every, n_cmp, pruning, torch
     off, data = wvocab.vocab_csr(toks)
     traj = load_trajectory(idx, rows, steps)
     g = cfg.grammar()
-    eng = zf.Engine(g, toks, device=0, pruning=pruning)
+    eng = zf.Engine(g, toks, device=0, pruning=pruning is not False, token_mask_cache=pruning is not None)
     orc = oracle_lib.Oracle(g)
     so = [orc.new_state() for _ in range(rows)]
     ss = [eng.new_state() for _ in range(rows)]

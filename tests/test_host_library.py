@@ -71,6 +71,7 @@ def test_small_grammars_every_prefix_every_token(gram, alphabet, pruning, zf, or
             continue
         assert s.accepting() == so.accepting(), p
         want = so.mask(off, data, 1)
+        assert (s.debug_host_mask_cached()[0] == want).all(), (p, "token-mask cache")
         got = s.debug_host_mask()
         assert (got == want).all(), (p, [toks[v] for v in range(len(toks)) if ((int(got[v >> 5]) ^ int(want[v >> 5])) >> (v & 31)) & 1])
         n_checked += 1
@@ -232,5 +233,6 @@ def test_config_trajectories_host_walk_matches_oracle(idx, rows, steps, every, z
                 want = so.mask(off, data, 8)
                 for s in ss:
                     assert (s.debug_host_mask() == want).all(), (idx, b, step)
+                    assert (s.debug_host_mask_cached()[0] == want).all(), (idx, b, step, "token-mask cache")
                     assert s.accepting() == so.accepting()
         assert ss[0].stats().n_items <= ss[1].stats().n_items
