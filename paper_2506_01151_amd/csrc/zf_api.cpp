@@ -22,7 +22,8 @@ struct DeviceSide {
     void *d_chart = nullptr; size_t chart_cap = 0;
     void *h_stage = nullptr; size_t stage_cap = 0;   // pinned
     uint32_t *d_rank_mask = nullptr; size_t rank_cap = 0;
-    uint2 *d_overflow = nullptr, *d_overflow2 = nullptr; size_t overflow_cap = 0;
+    uint4 *d_overflow = nullptr, *d_overflow2 = nullptr; size_t overflow_cap = 0;
+    uint2 *d_work = nullptr;
     int mode = 2;
     uint32_t *d_counters = nullptr;
     uint32_t *h_counters = nullptr;      // pinned
@@ -34,6 +35,8 @@ struct DeviceSide {
 };
 
 namespace {
+
+const int MAX_BATCH = 4096;   // rows per zf_compute_mask call
 
 int fail(int code, const std::string &m) { set_error(m); return code; }
 #define HIP_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return fail(ZF_ERR_DEVICE, std::string(#expr) + ": " + hipGetErrorString(e_)); } while (0)
@@ -61,6 +64,7 @@ void free_device(DeviceSide *d) {
     if (d->d_rank_mask) (void)hipFree(d->d_rank_mask);
     if (d->d_overflow) (void)hipFree(d->d_overflow);
     if (d->d_overflow2) (void)hipFree(d->d_overflow2);
+    if (d->d_work) (void)hipFree(d->d_work);
     if (d->d_counters) (void)hipFree(d->d_counters);
     if (d->h_counters) (void)hipHostFree(d->h_counters);
     if (d->d_fb_items) (void)hipFree(d->d_fb_items);
@@ -81,9 +85,9 @@ int setup_device(zf_engine *e) {
     int rc;
     std::vector<uint8_t> cls(t.cls, t.cls + 256);
 #define UP(field, vec, bytes) if ((rc = upload(d, vec, &T.field, bytes)) != ZF_OK) return rc
-    UP(sym, t.sym, &T.small_bytes[0]); UP(advpq, t.advpq, &T.small_bytes[1]); UP(cls, cls, &T.small_bytes[2]);
-    UP(qinfo, t.qinfo, &T.small_bytes[3]); UP(scan_off, t.scan_off, &T.small_bytes[4]); UP(comp_off, t.comp_off, &T.small_bytes[5]);
-    UP(delta, t.delta_dense, &T.big_bytes[0]); UP(scan_list, t.scan_list, &T.big_bytes[1]); UP(comp_list, t.comp_list, &T.big_bytes[2]);
+    UP(advpq, t.advpq, &T.small_bytes[0]); UP(cls, cls, &T.small_bytes[1]);
+    UP(qinfo, t.qinfo, &T.small_bytes[2]); UP(scan_off, t.scan_off, &T.small_bytes[3]); UP(comp_off, t.comp_off, &T.small_bytes[4]);
+    UP(delta, t.delta_dense, &T.big_bytes[0]); UP(scan_list, t.dev_scan_list, &T.big_bytes[1]); UP(comp_list, t.comp_list, &T.big_bytes[2]);
     UP(nodes, tr.nodes, nullptr); UP(parent, tr.parent, nullptr); UP(chunk_begin, tr.chunk_begin, nullptr); UP(chunk_end, tr.chunk_end, nullptr);
     UP(chunk_anc, tr.chunk_anc, nullptr); UP(rank_of, tr.rank_of, nullptr);
     UP(ci_valid, tr.ci_valid, nullptr); UP(ci_cd, tr.ci_cd, nullptr);
@@ -94,7 +98,7 @@ int setup_device(zf_engine *e) {
     T.Wr = tr.Wr;
     d->mode = choose_table_mode(T);
     HIP_TRY(prepare_kernels());
-    HIP_TRY(hipMalloc((void **)&d->d_counters, 16));
+    HIP_TRY(hipMalloc((void **)&d->d_counters, 16 + 4 * MAX_BATCH));
     HIP_TRY(hipHostMalloc((void **)&d->h_counters, 16, hipHostMallocDefault));
     HIP_TRY(hipMalloc((void **)&d->d_fb_items, (size_t)FB3_ITEMS_PER_LANE * FB3_LANES * sizeof(uint2)));
     HIP_TRY(hipMalloc((void **)&d->d_fb_ss, (size_t)(FB_DEPTH_MAX + 2) * FB3_LANES * sizeof(uint32_t)));
@@ -355,7 +359,7 @@ int zf_debug_host_mask_stats(zf_engine *e, const zf_state *s, uint32_t *mask, in
 }
 
 int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream) {
-    if (!e || !states || batch <= 0 || !d_mask) return fail(ZF_ERR_INVALID_ARG, "bad argument");
+    if (!e || !states || batch <= 0 || batch > MAX_BATCH || !d_mask) return fail(ZF_ERR_INVALID_ARG, "bad argument (batch must be 1..4096)");
     DeviceSide *d = e->dev;
     if (!d) return fail(ZF_ERR_DEVICE, "engine was compiled without a device (device = -1)");
     hipStream_t stream = (hipStream_t)hip_stream;
@@ -387,7 +391,7 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
         uint8_t *h = (uint8_t *)d->h_stage;
         RowChart *rows = (RowChart *)(h + off_rows);
         uint32_t *so = (uint32_t *)(h + off_so);
-        Item *items = (Item *)(h + off_items);
+        uint32_t *dev_items = (uint32_t *)(h + off_items);
         uint32_t *ents = (uint32_t *)(h + off_ent);
         uint32_t so_at = 0, it_at = 0, en_at = 0;
         for (int b = 0; b < batch; b++) {
@@ -396,7 +400,12 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
             if (use_cache) rows[b].n_ent = current_set_entries(e->tab, c, ents + en_at);
             en_at += rows[b].n_ent;
             memcpy(so + so_at, c.set_off.data(), 4 * c.set_off.size());
-            if (!c.items.empty()) memcpy(items + it_at, c.items.data(), sizeof(Item) * c.items.size());
+            for (size_t i = 0; i < c.items.size(); i++) {   // host item -> device item word + origin
+                const uint32_t aw = e->tab.advpq[c.items[i].p];
+                const uint32_t w = (aw & IW_TERM) ? ((aw & 0xFFFFu) | ((uint32_t)c.items[i].q << 16)) : aw;
+                dev_items[2 * (it_at + i)] = w;
+                dev_items[2 * (it_at + i) + 1] = c.items[i].o;
+            }
             so_at += (uint32_t)c.set_off.size(); it_at += (uint32_t)c.items.size();
         }
     }
@@ -407,10 +416,12 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
         if (d->d_rank_mask) (void)hipFree(d->d_rank_mask);
         if (d->d_overflow) (void)hipFree(d->d_overflow);
         if (d->d_overflow2) (void)hipFree(d->d_overflow2);
-        d->d_rank_mask = nullptr; d->d_overflow = d->d_overflow2 = nullptr; d->rank_cap = d->overflow_cap = 0;
+        if (d->d_work) (void)hipFree(d->d_work);
+        d->d_rank_mask = nullptr; d->d_overflow = d->d_overflow2 = nullptr; d->d_work = nullptr; d->rank_cap = d->overflow_cap = 0;
         HIP_TRY(hipMalloc((void **)&d->d_rank_mask, need_rank * 4 + 16));
-        HIP_TRY(hipMalloc((void **)&d->d_overflow, need_ovf * sizeof(uint2) + 16));
-        HIP_TRY(hipMalloc((void **)&d->d_overflow2, need_ovf * sizeof(uint2) + 16));
+        HIP_TRY(hipMalloc((void **)&d->d_overflow, need_ovf * sizeof(uint4) + 16));
+        HIP_TRY(hipMalloc((void **)&d->d_overflow2, need_ovf * sizeof(uint4) + 16));
+        HIP_TRY(hipMalloc((void **)&d->d_work, need_ovf * sizeof(uint2) + 16));
         d->rank_cap = need_rank; d->overflow_cap = need_ovf;
     }
     MaskArgs a{};
@@ -422,6 +433,8 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     a.rank_mask = d->d_rank_mask;
     a.out_mask = d_mask;
     a.counters = d->d_counters;
+    a.row_count = d->d_counters + 4;
+    a.work = d->d_work;
     a.overflow_list = d->d_overflow;
     a.overflow_list2 = d->d_overflow2;
     a.mode = d->mode;
@@ -431,8 +444,9 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     a.fb_set_start = d->d_fb_ss;
     a.batch = batch;
     a.lane_cap = e->opt.lane_item_cap;
-    HIP_TRY(hipMemsetAsync(d->d_counters, 0, 16, stream));
+    HIP_TRY(hipMemsetAsync(d->d_counters, 0, 16 + 4 * (size_t)batch, stream));
     const bool prof = d->profiling;
+    if (d->tab.n_chunks > 0) HIP_TRY(launch_cache_merge(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
     if (d->tab.n_chunks > 0) HIP_TRY(launch_mask_main(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));

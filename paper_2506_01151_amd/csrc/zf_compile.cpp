@@ -158,15 +158,15 @@ bool build_tables(const zf_grammar_desc *g, Tables &t) {
         t.pos_rule.push_back(-1); t.pos_dot.push_back(-1); t.pos_lhs_orig.push_back(orig_of_new[a]);
     }
     t.P = (int)t.sym.size();
-    if (t.P >= 0xFFFF) { set_error("grammar: too many dotted positions"); return false; }
+    if (t.P > (int)MAX_POSITIONS) { set_error("grammar: too many dotted positions"); return false; }
     t.end_base = t.end_pos[0];
     t.advpq.assign(t.P, 0);
     for (int p = 0; p < t.P; p++) {
         uint16_t code = t.sym[p];
         int k = code >> SYM_KIND_SHIFT;
-        if (k == SYM_END) t.advpq[p] = t.end_pos[code & SYM_ID_MASK];
-        else if (k == SYM_TERM) t.advpq[p] = (uint32_t)p | ((uint32_t)t.term_start[code & SYM_ID_MASK] << 16);
-        else t.advpq[p] = (uint32_t)p;
+        if (k == SYM_END) t.advpq[p] = (uint32_t)t.end_pos[code & SYM_ID_MASK] | IW_END;
+        else if (k == SYM_TERM) t.advpq[p] = (uint32_t)p | IW_TERM | ((uint32_t)t.term_start[code & SYM_ID_MASK] << 16);
+        else t.advpq[p] = (uint32_t)p | ((code & SYM_NULLABLE_BIT) ? (uint32_t)IW_NT_NULLABLE : 0u) | ((uint32_t)(code & SYM_ID_MASK_NT) << IW_NT_SHIFT);
     }
     // hybrid DFA encoding for the device: literal chains carry their byte, other states a dense row
     t.qinfo.assign(Q, 0);
@@ -245,6 +245,8 @@ bool build_tables(const zf_grammar_desc *g, Tables &t) {
         t.comp_list.insert(t.comp_list.end(), comp_tmp[Y][X].begin(), comp_tmp[Y][X].end());
     }
     t.comp_off[(size_t)N * N] = (uint32_t)t.comp_list.size();
+    t.dev_scan_list.resize(t.scan_list.size());
+    for (size_t k = 0; k < t.scan_list.size(); k++) t.dev_scan_list[k] = t.scan_list[k] | IW_TERM;
     return true;
 }
 

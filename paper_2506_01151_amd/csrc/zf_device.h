@@ -15,6 +15,14 @@ enum : uint16_t {
     SYM_ID_MASK = (1u << 14) - 1,
     DFA_DEAD = 0xFFFF,
 };
+// Item word used on the device: bits 0-13 dotted position, bit 14 = completed ("lhs complete since
+// origin"), bit 15 = the postdot symbol is a terminal and bits 16-31 hold its DFA state; for an item
+// that waits for a nonterminal Y: bit 16 = Y is nullable, bits 17-29 = Y.
+enum : uint32_t {
+    IW_POS_MASK = 0x3FFF, IW_END = 0x4000, IW_TERM = 0x8000,
+    IW_NT_NULLABLE = 1u << 16, IW_NT_SHIFT = 17, IW_NT_MASK = 0x1FFF,
+    MAX_POSITIONS = 0x3FFF,
+};
 // Per-DFA-state word: flags | expected byte << 8 | dense transition row << 16.  States of a
 // literal terminal form a chain (one expected byte, next state = q + 1) and need no table row.
 enum : uint8_t { QF_ACCEPT = 1, QF_CONT = 2, QF_LITERAL = 4 };
@@ -43,16 +51,15 @@ static const int CHUNK_ANC = 16;                  // ancestors stored per chunk 
 // Immutable per-engine tables in device memory.  Every array is padded to a multiple of 16 bytes
 // so that a block can stage it into LDS with 4-byte copies.
 struct DeviceTables {
-    const uint16_t *sym;        // [P] symbol after the dot
-    const uint32_t *advpq;      // [P] the (position | DFA state << 16) word to insert when the dot arrives at p
+    const uint32_t *advpq;      // [P] the item word to insert when the dot arrives at position p
     const uint8_t *cls;         // [256] byte -> class
     const uint32_t *qinfo;      // [Q]
     const uint32_t *scan_off;   // [N*n_cls+1] CSR into scan_list
     const uint32_t *comp_off;   // [N*N+1] CSR into comp_list
     const uint16_t *delta;      // [dense rows][n_cls]
-    const uint32_t *scan_list;  // p | q' << 16
+    const uint32_t *scan_list;  // item words (terminal already stepped once)
     const uint16_t *comp_list;  // advanced positions
-    uint32_t small_bytes[6];    // padded byte sizes of sym .. comp_off (always staged into LDS when they fit)
+    uint32_t small_bytes[5];    // padded byte sizes of advpq .. comp_off (always staged into LDS when they fit)
     uint32_t big_bytes[3];      // padded byte sizes of delta, scan_list, comp_list
     const TrieNode *nodes;      // [n_nodes]
     const uint32_t *parent;     // [n_nodes] parent node index, 0xFFFFFFFF for depth-1 nodes

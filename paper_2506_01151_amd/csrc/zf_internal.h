@@ -36,7 +36,8 @@ struct Tables {
     uint8_t cls[256];
     std::vector<uint16_t> delta;      // [Q*n_cls]
     std::vector<uint8_t> qflags;      // [Q]
-    std::vector<uint32_t> advpq;      // [P] word to insert when the dot arrives at p
+    std::vector<uint32_t> advpq;      // [P] device item word to insert when the dot arrives at p
+    std::vector<uint32_t> dev_scan_list;  // scan_list as device item words
     std::vector<uint32_t> qinfo;      // [Q] flags | literal byte << 8 | dense row << 16
     std::vector<uint16_t> delta_dense; // rows of the non-literal states only
     int end_base = 0;                 // end_pos[X] == end_base + X

@@ -21,7 +21,6 @@ namespace {
 
 // Table view used by the device code; the pointers lead into LDS or global memory.
 struct TV {
-    const uint16_t *sym;
     const uint32_t *advpq;
     const uint8_t *cls;
     const uint32_t *qinfo;
@@ -46,18 +45,17 @@ __device__ __forceinline__ uint32_t stage_tables(const DeviceTables &D, uint8_t 
     tv.N = D.N; tv.ncls = D.n_cls; tv.end_base = D.end_base;
     uint32_t off = 0;
     if (MODE <= 1) {
-        const void *src[6] = {D.sym, D.advpq, D.cls, D.qinfo, D.scan_off, D.comp_off};
-        uint32_t at[6];
+        const void *src[5] = {D.advpq, D.cls, D.qinfo, D.scan_off, D.comp_off};
+        uint32_t at[5];
 #pragma unroll
-        for (int k = 0; k < 6; k++) { at[k] = off; copy16(smem + off, src[k], D.small_bytes[k], tid, nthreads); off += D.small_bytes[k]; }
-        tv.sym = reinterpret_cast<const uint16_t *>(smem + at[0]);
-        tv.advpq = reinterpret_cast<const uint32_t *>(smem + at[1]);
-        tv.cls = smem + at[2];
-        tv.qinfo = reinterpret_cast<const uint32_t *>(smem + at[3]);
-        tv.scan_off = reinterpret_cast<const uint32_t *>(smem + at[4]);
-        tv.comp_off = reinterpret_cast<const uint32_t *>(smem + at[5]);
+        for (int k = 0; k < 5; k++) { at[k] = off; copy16(smem + off, src[k], D.small_bytes[k], tid, nthreads); off += D.small_bytes[k]; }
+        tv.advpq = reinterpret_cast<const uint32_t *>(smem + at[0]);
+        tv.cls = smem + at[1];
+        tv.qinfo = reinterpret_cast<const uint32_t *>(smem + at[2]);
+        tv.scan_off = reinterpret_cast<const uint32_t *>(smem + at[3]);
+        tv.comp_off = reinterpret_cast<const uint32_t *>(smem + at[4]);
     } else {
-        tv.sym = D.sym; tv.advpq = D.advpq; tv.cls = D.cls; tv.qinfo = D.qinfo; tv.scan_off = D.scan_off; tv.comp_off = D.comp_off;
+        tv.advpq = D.advpq; tv.cls = D.cls; tv.qinfo = D.qinfo; tv.scan_off = D.scan_off; tv.comp_off = D.comp_off;
     }
     if (MODE == 0) {
         const void *src[3] = {D.delta, D.scan_list, D.comp_list};
@@ -74,7 +72,7 @@ __device__ __forceinline__ uint32_t stage_tables(const DeviceTables &D, uint8_t 
 }
 
 // ---- item-list storage policies ---------------------------------------------------------
-// An item is (pq, o): pq = dotted position | DFA state << 16, o = origin set.
+// An item is (w, o): w = item word (see IW_* in zf_device.h), o = origin set.
 struct LaneLdsStore {          // main kernel: one list per lane, interleaved by lane
     uint32_t *pq;              // column of this lane, stride 64
     uint16_t *org;
@@ -108,27 +106,30 @@ struct GlobalStore {           // fallback level 3: arena in global memory, inte
     __device__ __forceinline__ void set_start(int d, uint32_t v) { ss[(size_t)d * FB3_LANES] = v; }
 };
 
+enum { ADD_OK = 1, ADD_END = 2 };   // result bits of the insert helpers (0 = list full)
+
 // "each state set maintains only unique states" (Section 3.2)
 template <class S>
-__device__ __forceinline__ bool insert_unique(S &st, uint32_t set_begin, uint32_t &cnt, uint32_t pq, uint32_t o) {
+__device__ __forceinline__ bool insert_unique(S &st, uint32_t set_begin, uint32_t &cnt, uint32_t w, uint32_t o) {
     for (uint32_t i = set_begin; i < cnt; i++) {
-        uint32_t xp, xo;
-        st.get(i, xp, xo);
-        if (xp == pq && xo == o) return true;
+        uint32_t xw, xo;
+        st.get(i, xw, xo);
+        if (xw == w && xo == o) return true;
     }
     if (cnt >= st.cap) return false;
-    st.put(cnt++, pq, o);
+    st.put(cnt++, w, o);
     return true;
 }
 
 // Add the item with the dot at position p; skip nullable postdot nonterminals; a dot at the end
-// of a rule becomes the canonical "lhs complete since o" item (positions >= end_base).
+// of a rule becomes the canonical "lhs complete since o" item.  Returns ADD_* bits.
 template <class S>
-__device__ __forceinline__ bool add_advanced(const TV &T, S &st, uint32_t set_begin, uint32_t &cnt, uint32_t p, uint32_t o) {
+__device__ __forceinline__ uint32_t add_advanced(const TV &T, S &st, uint32_t set_begin, uint32_t &cnt, uint32_t p, uint32_t o) {
     for (;;) {
-        const uint32_t code = T.sym[p];
-        if (!insert_unique(st, set_begin, cnt, T.advpq[p], o)) return false;
-        if ((code >> SYM_KIND_SHIFT) != SYM_NT || !(code & SYM_NULLABLE_BIT)) return true;
+        const uint32_t w = T.advpq[p];
+        if (!insert_unique(st, set_begin, cnt, w, o)) return 0;
+        if (w & IW_END) return ADD_OK | ADD_END;
+        if ((w & IW_TERM) || !(w & IW_NT_NULLABLE)) return ADD_OK;
         p++;
     }
 }
@@ -143,7 +144,7 @@ enum { STEP_ALIVE = 1, STEP_KERNEL = 2, STEP_OVERFLOW = 4 };
 
 struct Base {                  // the row's uploaded chart (LDS copy or global)
     const uint32_t *so;        // set offsets, so[k] .. so[k+1]
-    const uint2 *it;           // items: x = p | q << 16, y = origin
+    const uint2 *it;           // items: x = item word, y = origin
     uint32_t m;                // number of sets; set m-1 is the current one
     uint32_t last_lo, last_hi; // so[m-1], so[m]
 };
@@ -155,70 +156,71 @@ __device__ __forceinline__ int earley_step(const TV &T, const Base &B, S &st, in
     const uint32_t nb = cnt;
     const uint32_t cl = T.cls[byte];
     const uint32_t cur = B.m - 1 + (uint32_t)(d - 1);   // index of the source set
-    bool ok = true;
+    uint32_t acc = ADD_OK;                               // AND of ok bits, OR of END bits
     const bool from_base = d == 1;
     const uint32_t sb = from_base ? B.last_lo : st.start(d - 1);
     const uint32_t se = from_base ? B.last_hi : nb;
     // Scan
-    for (uint32_t i = sb; i < se && ok; i++) {
-        uint32_t pq, o;
-        if (from_base) { uint2 x = B.it[i]; pq = x.x; o = x.y; } else st.get(i, pq, o);
-        const uint32_t p = pq & 0xFFFFu;
-        if (p >= T.end_base) continue;                  // completed item kept in an unpruned chart
-        const uint32_t code = T.sym[p];
-        if ((code >> SYM_KIND_SHIFT) == SYM_TERM) {
-            const uint32_t q2 = dfa_next(T, pq >> 16, byte, cl);
+    for (uint32_t i = sb; i < se; i++) {
+        uint32_t w, o;
+        if (from_base) { uint2 x = B.it[i]; w = x.x; o = x.y; } else st.get(i, w, o);
+        if (w & IW_TERM) {
+            const uint32_t q2 = dfa_next(T, w >> 16, byte, cl);
             if (q2 == DFA_DEAD) continue;
             const uint32_t f = T.qinfo[q2];
-            if (f & QF_CONT) ok = insert_unique(st, nb, cnt, p | (q2 << 16), o);   // no longest match: keep matching ...
-            if (ok && (f & QF_ACCEPT)) ok = add_advanced(T, st, nb, cnt, p + 1, o);   // ... and also finish here
-        } else {
-            const uint32_t Y = code & SYM_ID_MASK_NT;   // stands for every predicted item of I(Y)
+            uint32_t r = ADD_OK;
+            if (f & QF_CONT) r = insert_unique(st, nb, cnt, (w & 0xFFFFu) | (q2 << 16), o) ? ADD_OK : 0;   // no longest match: keep matching ...
+            if (r && (f & QF_ACCEPT)) r = add_advanced(T, st, nb, cnt, (w & IW_POS_MASK) + 1, o);        // ... and also finish here
+            if (!r) return STEP_OVERFLOW;
+            acc |= r;
+        } else if (!(w & IW_END)) {                      // waits for nonterminal Y: stands for every predicted item of I(Y)
+            const uint32_t Y = (w >> IW_NT_SHIFT) & IW_NT_MASK;
             const uint32_t k0 = T.scan_off[Y * T.ncls + cl], k1 = T.scan_off[Y * T.ncls + cl + 1];
-            for (uint32_t e = k0; e < k1 && ok; e++) {
+            for (uint32_t e = k0; e < k1; e++) {
                 const uint32_t ent = T.scan_list[e];
                 const uint32_t f = T.qinfo[ent >> 16];
-                if (f & QF_CONT) ok = insert_unique(st, nb, cnt, ent, cur);
-                if (ok && (f & QF_ACCEPT)) ok = add_advanced(T, st, nb, cnt, (ent & 0xFFFFu) + 1, cur);
+                uint32_t r = ADD_OK;
+                if (f & QF_CONT) r = insert_unique(st, nb, cnt, ent, cur) ? ADD_OK : 0;
+                if (r && (f & QF_ACCEPT)) r = add_advanced(T, st, nb, cnt, (ent & IW_POS_MASK) + 1, cur);
+                if (!r) return STEP_OVERFLOW;
+                acc |= r;
             }
         }
     }
+    if (!(acc & ADD_END)) {                              // nothing completed: no Complete phase, nothing to drop
+        st.set_start(d + 1, cnt);
+        return cnt > nb ? (STEP_ALIVE | STEP_KERNEL) : 0;
+    }
     // Complete
-    for (uint32_t i = nb; i < cnt && ok; i++) {
-        uint32_t pq, o;
-        st.get(i, pq, o);
-        const uint32_t p = pq & 0xFFFFu;
-        if (p < T.end_base) continue;
-        const uint32_t X = p - T.end_base;
+    for (uint32_t i = nb; i < cnt; i++) {
+        uint32_t w, o;
+        st.get(i, w, o);
+        if (!(w & IW_END)) continue;
+        const uint32_t X = (w & IW_POS_MASK) - T.end_base;
         if (X == T.N - 1) continue;                     // the start rule is complete: the prefix is a sentence
         const bool in_base = o < B.m;
         uint32_t jb, je;
         if (in_base) { jb = B.so[o]; je = B.so[o + 1]; }
         else { const int dj = (int)(o - (B.m - 1)); jb = st.start(dj); je = st.start(dj + 1); }
-        for (uint32_t j = jb; j < je && ok; j++) {
-            uint32_t ypq, yo;
-            if (in_base) { uint2 y = B.it[j]; ypq = y.x; yo = y.y; } else st.get(j, ypq, yo);
-            const uint32_t yp = ypq & 0xFFFFu;
-            if (yp >= T.end_base) continue;
-            const uint32_t yc = T.sym[yp];
-            if ((yc >> SYM_KIND_SHIFT) != SYM_NT) continue;
-            const uint32_t Y = yc & SYM_ID_MASK_NT;
+        for (uint32_t j = jb; j < je; j++) {
+            uint32_t yw, yo;
+            if (in_base) { uint2 y = B.it[j]; yw = y.x; yo = y.y; } else st.get(j, yw, yo);
+            if (yw & (IW_TERM | IW_END)) continue;
+            const uint32_t Y = (yw >> IW_NT_SHIFT) & IW_NT_MASK;
             const uint32_t c0 = T.comp_off[Y * T.N + X], c1 = T.comp_off[Y * T.N + X + 1];
-            for (uint32_t e = c0; e < c1 && ok; e++) ok = add_advanced(T, st, nb, cnt, T.comp_list[e], o);
-            if (ok && Y == X) ok = add_advanced(T, st, nb, cnt, yp + 1, yo);
+            for (uint32_t e = c0; e < c1; e++) if (!add_advanced(T, st, nb, cnt, T.comp_list[e], o)) return STEP_OVERFLOW;
+            if (Y == X && !add_advanced(T, st, nb, cnt, (yw & IW_POS_MASK) + 1, yo)) return STEP_OVERFLOW;
         }
     }
-    if (!ok) return STEP_OVERFLOW;
-    const bool alive = cnt > nb;
-    uint32_t w = nb;   // completed items are needed only while their own set is processed
+    uint32_t wpos = nb;   // completed items are needed only while their own set is processed
     for (uint32_t i = nb; i < cnt; i++) {
-        uint32_t pq, o;
-        st.get(i, pq, o);
-        if ((pq & 0xFFFFu) < T.end_base) { if (w != i) st.put(w, pq, o); w++; }
+        uint32_t w, o;
+        st.get(i, w, o);
+        if (!(w & IW_END)) { if (wpos != i) st.put(wpos, w, o); wpos++; }
     }
-    cnt = w;
+    cnt = wpos;
     st.set_start(d + 1, cnt);
-    return (alive ? STEP_ALIVE : 0) | (cnt > nb ? STEP_KERNEL : 0);
+    return STEP_ALIVE | (cnt > nb ? STEP_KERNEL : 0);
 }
 
 // Walk the nodes of one chunk.  anc(j) gives the node index of the first node's ancestor at
@@ -250,23 +252,18 @@ __device__ __forceinline__ bool walk_chunk(const DeviceTables &D, const TV &T, c
         TrieNode nx = nd;
         if (nxt < end) nx = D.nodes[nxt];                // issued before the step so that it overlaps it
         const int d = nd.depth;
-        {
-            const uint32_t rel = nd.rank - rank0;
-            const uint32_t span = (nd.n_sub >= 32u ? 0xFFFFFFFFu : ((1u << nd.n_sub) - 1u)) << rel;
-            if (!(span & want)) {                        // nothing to decide below this node
-                const uint32_t ni = nd.skip;
-                if (ni == nxt) nd = nx;
-                else if (ni < end) nd = D.nodes[ni];
-                i = ni;
-                continue;
-            }
+        uint32_t ni;
+        const uint32_t rel = nd.rank - rank0;
+        const uint32_t span = (nd.n_sub >= 32u ? 0xFFFFFFFFu : ((1u << nd.n_sub) - 1u)) << rel;
+        if (!(span & want)) ni = nd.skip;                // nothing to decide below this node
+        else {
+            if (d > S::max_depth) return false;
+            cnt = st.start(d);                           // forget the sets of the deeper path we came from
+            const int r = earley_step(T, B, st, d, nd.byte, cnt);
+            if (r & STEP_OVERFLOW) return false;
+            if (nd.has_string && (r & STEP_ALIVE)) bits |= 1u << rel;
+            ni = (r & STEP_KERNEL) ? nxt : nd.skip;
         }
-        if (d > S::max_depth) return false;
-        cnt = st.start(d);                               // forget the sets of the deeper path we came from
-        const int r = earley_step(T, B, st, d, nd.byte, cnt);
-        if (r & STEP_OVERFLOW) return false;
-        if (nd.has_string && (r & STEP_ALIVE)) bits |= 1u << (nd.rank - rank0);
-        const uint32_t ni = (r & STEP_KERNEL) ? nxt : nd.skip;
         if (ni == nxt) nd = nx;
         else if (ni < end) nd = D.nodes[ni];
         i = ni;
@@ -282,35 +279,60 @@ __device__ __forceinline__ uint32_t load_bits(const DeviceTables &D, const uint3
     return rowp[chunk];
 }
 
-// Token-mask cache (Section 4.3): merge the cached bitsets of every item of the row's current set.
-// valid: strings some terminal swallows whole; want: strings that need the parser.
-__device__ __forceinline__ void cached_verdicts(const MaskArgs &a, const RowChart &rc, uint32_t chunk, uint32_t &valid, uint32_t &want) {
-    const DeviceTables &D = a.tab;
-    if (rc.n_ent == 0) { valid = 0; want = D.chunk_ranks == 32 ? 0xFFFFFFFFu : ((1u << D.chunk_ranks) - 1u); return; }
-    uint32_t v = 0, c = 0;
-    for (uint32_t k = 0; k < rc.n_ent; k++) {
-        const size_t r = (size_t)a.entries[rc.ent_base + k] * D.Wr;
-        v |= load_bits(D, D.ci_valid + r, chunk);
-        c |= load_bits(D, D.ci_cd + r, chunk);
-    }
-    valid = v; want = c & ~v;
-}
-
 __device__ __forceinline__ void store_bits(const DeviceTables &D, uint32_t *rank_mask, uint32_t row, uint32_t chunk, uint32_t bits) {
     uint8_t *rowp = reinterpret_cast<uint8_t *>(rank_mask + (size_t)row * D.Wr);
     if (D.chunk_ranks == 32) reinterpret_cast<uint32_t *>(rowp)[chunk] = bits;
     else if (D.chunk_ranks == 16) reinterpret_cast<uint16_t *>(rowp)[chunk] = (uint16_t)bits;
     else rowp[chunk] = (uint8_t)bits;
 }
+// the chunk's bits are owned by one lane at a time (kernels are stream ordered): plain read-modify-write
+__device__ __forceinline__ void or_bits(const DeviceTables &D, uint32_t *rank_mask, uint32_t row, uint32_t chunk, uint32_t bits) {
+    if (bits) store_bits(D, rank_mask, row, chunk, bits | load_bits(D, rank_mask + (size_t)row * D.Wr, chunk));
+}
+
+// Token-mask cache (Section 4.3): merge the cached bitsets of every item of the row's current set,
+// store the strings some terminal swallows whole, and queue the chunks that hold strings which
+// need the parser.  One lane per (row, chunk); wavefront-aggregated queue append.
+__global__ __launch_bounds__(256) void cache_merge_kernel(MaskArgs a) {
+    const DeviceTables &D = a.tab;
+    const uint32_t chunk = blockIdx.x * 256 + threadIdx.x, row = blockIdx.y;
+    const RowChart rc = a.rows[row];
+    uint32_t valid = 0, want = 0;
+    if (chunk < (uint32_t)D.n_chunks) {
+        if (rc.n_ent == 0) want = D.chunk_ranks == 32 ? 0xFFFFFFFFu : ((1u << D.chunk_ranks) - 1u);
+        else {
+            uint32_t c = 0;
+            for (uint32_t k = 0; k < rc.n_ent; k++) {
+                const size_t r = (size_t)a.entries[rc.ent_base + k] * D.Wr;
+                valid |= load_bits(D, D.ci_valid + r, chunk);
+                c |= load_bits(D, D.ci_cd + r, chunk);
+            }
+            want = c & ~valid;
+        }
+        store_bits(D, a.rank_mask, row, chunk, valid);
+    }
+    const unsigned long long b = __ballot(want != 0);
+    if (b) {
+        const uint32_t lane = threadIdx.x & 63;
+        const uint32_t leader = (uint32_t)__ffsll((long long)b) - 1;
+        uint32_t base = 0;
+        if (lane == leader) base = atomicAdd(&a.row_count[row], (uint32_t)__popcll(b));
+        base = __shfl(base, leader);
+        if (want) a.work[(size_t)row * D.n_chunks + base + __popcll(b & ((1ull << lane) - 1ull))] = make_uint2(chunk, want);
+    }
+}
 
 __device__ __forceinline__ uint32_t lane_region_bytes(uint32_t cap) { return cap * 64 * 6 + (LANE_DEPTH_MAX + 2) * 64; }
 static const uint32_t BASE_LDS_BYTES = (BASE_SETS_LDS + 1) * 4 + BASE_ITEMS_LDS * 8;
 
+// The parser walk: one lane per queued chunk of the block's row.
 template <int MODE>
 __global__ __launch_bounds__(MAIN_BLOCK) void mask_main_kernel(MaskArgs a) {
     extern __shared__ __align__(16) uint8_t smem[];
     const DeviceTables &D = a.tab;
     const uint32_t tid = threadIdx.x, row = blockIdx.y;
+    const uint32_t n_work = a.row_count[row];
+    if (blockIdx.x * MAIN_BLOCK >= n_work) return;      // uniform: the queue of this row is shorter
     TV T;
     uint32_t off = stage_tables<MODE>(D, smem, T, tid, MAIN_BLOCK);
     // the row's chart: LDS copy when small
@@ -331,11 +353,10 @@ __global__ __launch_bounds__(MAIN_BLOCK) void mask_main_kernel(MaskArgs a) {
     } else { B.so = g_so; B.it = g_it; }
     off += BASE_LDS_BYTES;
     __syncthreads();
-    const uint32_t chunk = blockIdx.x * MAIN_BLOCK + tid;
-    if (chunk >= (uint32_t)D.n_chunks) return;
-    uint32_t valid, want;
-    cached_verdicts(a, rc, chunk, valid, want);
-    if (!want) { store_bits(D, a.rank_mask, row, chunk, valid); return; }
+    const uint32_t e = blockIdx.x * MAIN_BLOCK + tid;
+    if (e >= n_work) return;
+    const uint2 item = a.work[(size_t)row * D.n_chunks + e];
+    const uint32_t chunk = item.x, want = item.y;
     const uint32_t wave = tid >> 6, lane = tid & 63;
     const uint32_t cap = (uint32_t)a.lane_cap;
     uint8_t *region = smem + off + wave * lane_region_bytes(cap);
@@ -350,10 +371,10 @@ __global__ __launch_bounds__(MAIN_BLOCK) void mask_main_kernel(MaskArgs a) {
               walk_chunk(D, T, B, st, chunk, want, [&](int j) { return anc_row[j]; }, &bits);
     if (!ok) {
         const uint32_t slot = atomicAdd(&a.counters[0], 1u);
-        if (slot < a.overflow_cap) a.overflow_list[slot] = make_uint2(row, chunk);
-        bits = 0;
+        if (slot < a.overflow_cap) a.overflow_list[slot] = make_uint4(row, chunk, want, 0);
+        return;
     }
-    store_bits(D, a.rank_mask, row, chunk, valid | (bits & want));
+    or_bits(D, a.rank_mask, row, chunk, bits & want);
 }
 
 struct ParentAnc {             // ancestor at depth j+1 through the parent links
@@ -393,18 +414,17 @@ __global__ __launch_bounds__(64) void mask_fallback2_kernel(MaskArgs a) {
     st.ss = reinterpret_cast<uint16_t *>(st.org + FB2_CAP);
     st.cap = (uint32_t)a.fb2_cap;
     for (uint32_t e = blockIdx.x; e < n; e += gridDim.x) {
-        const uint2 ent = a.overflow_list[e];
+        const uint4 ent = a.overflow_list[e];
         const Base B = global_base(a, ent.x);
         const uint32_t first = D.chunk_begin[ent.y];
         ParentAnc anc{D.parent, first, D.nodes[first].depth};
-        uint32_t bits = 0, valid, want;
-        cached_verdicts(a, a.rows[ent.x], ent.y, valid, want);
-        if (!walk_chunk(D, T, B, st, ent.y, want, anc, &bits)) {
+        uint32_t bits = 0;
+        if (!walk_chunk(D, T, B, st, ent.y, ent.z, anc, &bits)) {
             const uint32_t slot = atomicAdd(&a.counters[1], 1u);
             if (slot < a.overflow_cap) a.overflow_list2[slot] = ent;
-            bits = 0;
+            continue;
         }
-        store_bits(D, a.rank_mask, ent.x, ent.y, valid | (bits & want));
+        or_bits(D, a.rank_mask, ent.x, ent.y, bits & ent.z);
     }
 }
 
@@ -418,14 +438,13 @@ __global__ __launch_bounds__(64) void mask_fallback3_kernel(MaskArgs a) {
     if (n > a.overflow_cap) { if (gid == 0) atomicAdd(&a.counters[2], n - a.overflow_cap); n = a.overflow_cap; }
     GlobalStore st{a.fb_items + gid, a.fb_set_start + gid, (uint32_t)FB3_ITEMS_PER_LANE};
     for (uint32_t e = gid; e < n; e += FB3_LANES) {
-        const uint2 ent = a.overflow_list2[e];
+        const uint4 ent = a.overflow_list2[e];
         const Base B = global_base(a, ent.x);
         const uint32_t first = D.chunk_begin[ent.y];
         ParentAnc anc{D.parent, first, D.nodes[first].depth};
-        uint32_t bits = 0, valid, want;
-        cached_verdicts(a, a.rows[ent.x], ent.y, valid, want);
-        if (!walk_chunk(D, T, B, st, ent.y, want, anc, &bits)) { atomicAdd(&a.counters[2], 1u); bits = 0; }
-        store_bits(D, a.rank_mask, ent.x, ent.y, valid | (bits & want));
+        uint32_t bits = 0;
+        if (!walk_chunk(D, T, B, st, ent.y, ent.z, anc, &bits)) { atomicAdd(&a.counters[2], 1u); continue; }
+        or_bits(D, a.rank_mask, ent.x, ent.y, bits & ent.z);
     }
 }
 
@@ -486,7 +505,7 @@ __global__ __launch_bounds__(256) void apply_mask_scalar_kernel(const ElemT *__r
 
 uint32_t table_bytes(const DeviceTables &t, int mode) {
     uint32_t n = 0;
-    if (mode <= 1) for (int k = 0; k < 6; k++) n += t.small_bytes[k];
+    if (mode <= 1) for (int k = 0; k < 5; k++) n += t.small_bytes[k];
     if (mode == 0) for (int k = 0; k < 3; k++) n += t.big_bytes[k];
     return n;
 }
@@ -509,6 +528,11 @@ hipError_t prepare_kernels() {
     return hipSuccess;
 }
 
+hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s) {
+    dim3 grid((a.tab.n_chunks + 255) / 256, a.batch);
+    hipLaunchKernelGGL(cache_merge_kernel, grid, dim3(256), 0, s, a);
+    return hipGetLastError();
+}
 hipError_t launch_mask_main(const MaskArgs &a, hipStream_t s) {
     dim3 grid((a.tab.n_chunks + MAIN_BLOCK - 1) / MAIN_BLOCK, a.batch);
     const uint32_t lds = table_bytes(a.tab, a.mode) + BASE_LDS_BYTES + (MAIN_BLOCK / 64) * ((uint32_t)a.lane_cap * 64 * 6 + (LANE_DEPTH_MAX + 2) * 64);

@@ -27,8 +27,10 @@ struct MaskArgs {
     uint32_t *rank_mask;       // [batch][Wr] verdicts in trie (rank) order
     uint32_t *out_mask;        // [batch][W] verdicts in token-id order
     uint32_t *counters;        // [0] chunks passed to level 2, [1] chunks passed to level 3, [2] unresolved
-    uint2 *overflow_list;      // (row, chunk) for level 2
-    uint2 *overflow_list2;     // (row, chunk) for level 3
+    uint32_t *row_count;       // [batch] length of each row's queue of chunks that need the parser walk
+    uint2 *work;               // [batch][n_chunks] (chunk, undecided strings) queue per row
+    uint4 *overflow_list;      // (row, chunk, undecided strings, -) for level 2
+    uint4 *overflow_list2;     // same for level 3
     uint32_t overflow_cap;
     uint2 *fb_items;           // [FB3_ITEMS_PER_LANE][FB3_LANES] interleaved
     uint32_t *fb_set_start;    // [FB_DEPTH_MAX + 2][FB3_LANES]
@@ -40,6 +42,7 @@ struct MaskArgs {
 
 int choose_table_mode(const DeviceTables &t);
 hipError_t prepare_kernels();   // one-time function attributes (dynamic LDS above 64 KB)
+hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_main(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_fallback2(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_fallback3(const MaskArgs &a, hipStream_t s);
