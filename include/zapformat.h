@@ -66,12 +66,12 @@ typedef struct {
 
 typedef struct {
     int32_t pruning;       /* 1 = ZapFormat Compact phase on (Section 4.2), 0 = keep every item */
-    int32_t lane_item_cap; /* per-lane Earley item budget of the mask kernel, 0 = default;
-                              anything that does not fit goes to the exact fallback pass */
+    int32_t lane_item_cap; /* Earley item budget (LDS) of one walking wavefront of the mask kernel,
+                              0 = default (256); what does not fit goes to the exact fallback pass */
     int32_t device;        /* HIP device ordinal, or -1 = host tables only (no mask calls) */
     int32_t chunk_strings; /* vocabulary strings walked by one lane: 8, 16 or 32; 0 = default */
-    int32_t fallback_item_cap; /* item budget of the LDS fallback level, 0 = default (2048); tests
-                                  set it low to force the last, global-memory level */
+    int32_t fallback_item_cap; /* item budget of a fallback lane (global memory), 0 = default
+                                  (16384); tests set it low to provoke ZF_ERR_OVERFLOW */
     int32_t disable_token_mask_cache; /* 1 = every token goes through the parser walk (Section 4.3
                                   optimisation off); masks are identical either way */
 } zf_options;
@@ -93,7 +93,6 @@ typedef struct {
 
 typedef struct {               /* facts about the last zf_compute_mask, for reporting only */
     int64_t overflow_chunks;   /* trie chunks handed to the fallback pass in the last call */
-    int64_t overflow_chunks_level3; /* of those, chunks that also outgrew the LDS fallback */
     int64_t chart_bytes;       /* bytes uploaded for the last call */
     float main_ms, fallback_ms, permute_ms; /* kernel durations from HIP events on the call's
                                                stream; 0 unless zf_engine_set_profiling is on */

@@ -43,7 +43,7 @@ class EngineInfo(ctypes.Structure):
 
 
 class MaskReport(ctypes.Structure):
-    _fields_ = [("overflow_chunks", c_i64), ("overflow_chunks_level3", c_i64), ("chart_bytes", c_i64), ("main_ms", ctypes.c_float),
+    _fields_ = [("overflow_chunks", c_i64), ("chart_bytes", c_i64), ("main_ms", ctypes.c_float),
                 ("fallback_ms", ctypes.c_float), ("permute_ms", ctypes.c_float)]
 
 

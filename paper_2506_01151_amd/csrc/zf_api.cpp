@@ -22,7 +22,7 @@ struct DeviceSide {
     void *d_chart = nullptr; size_t chart_cap = 0;
     void *h_stage = nullptr; size_t stage_cap = 0;   // pinned
     uint32_t *d_rank_mask = nullptr; size_t rank_cap = 0;
-    uint4 *d_overflow = nullptr, *d_overflow2 = nullptr; size_t overflow_cap = 0;
+    uint4 *d_overflow = nullptr; size_t overflow_cap = 0;
     uint2 *d_work = nullptr;
     int mode = 2;
     uint32_t *d_counters = nullptr;
@@ -63,7 +63,6 @@ void free_device(DeviceSide *d) {
     if (d->h_stage) (void)hipHostFree(d->h_stage);
     if (d->d_rank_mask) (void)hipFree(d->d_rank_mask);
     if (d->d_overflow) (void)hipFree(d->d_overflow);
-    if (d->d_overflow2) (void)hipFree(d->d_overflow2);
     if (d->d_work) (void)hipFree(d->d_work);
     if (d->d_counters) (void)hipFree(d->d_counters);
     if (d->h_counters) (void)hipHostFree(d->h_counters);
@@ -177,7 +176,7 @@ int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_option
     e->opt = opt ? *opt : zf_options{1, 0, 0, 0, 0, 0};
     if (e->opt.lane_item_cap <= 0) e->opt.lane_item_cap = LANE_CAP_DEFAULT;
     if (e->opt.lane_item_cap > LANE_CAP_MAX) e->opt.lane_item_cap = LANE_CAP_MAX;
-    if (e->opt.fallback_item_cap <= 0 || e->opt.fallback_item_cap > FB2_CAP) e->opt.fallback_item_cap = FB2_CAP;
+    if (e->opt.fallback_item_cap <= 0 || e->opt.fallback_item_cap > FB3_ITEMS_PER_LANE) e->opt.fallback_item_cap = FB3_ITEMS_PER_LANE;
     if (e->opt.chunk_strings != 8 && e->opt.chunk_strings != 16 && e->opt.chunk_strings != 32) e->opt.chunk_strings = 8;
     try {
         if (!build_tables(g, e->tab)) { delete e; return ZF_ERR_GRAMMAR; }
@@ -415,12 +414,10 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     if (need_rank > d->rank_cap || need_ovf > d->overflow_cap) {
         if (d->d_rank_mask) (void)hipFree(d->d_rank_mask);
         if (d->d_overflow) (void)hipFree(d->d_overflow);
-        if (d->d_overflow2) (void)hipFree(d->d_overflow2);
         if (d->d_work) (void)hipFree(d->d_work);
-        d->d_rank_mask = nullptr; d->d_overflow = d->d_overflow2 = nullptr; d->d_work = nullptr; d->rank_cap = d->overflow_cap = 0;
+        d->d_rank_mask = nullptr; d->d_overflow = nullptr; d->d_work = nullptr; d->rank_cap = d->overflow_cap = 0;
         HIP_TRY(hipMalloc((void **)&d->d_rank_mask, need_rank * 4 + 16));
         HIP_TRY(hipMalloc((void **)&d->d_overflow, need_ovf * sizeof(uint4) + 16));
-        HIP_TRY(hipMalloc((void **)&d->d_overflow2, need_ovf * sizeof(uint4) + 16));
         HIP_TRY(hipMalloc((void **)&d->d_work, need_ovf * sizeof(uint2) + 16));
         d->rank_cap = need_rank; d->overflow_cap = need_ovf;
     }
@@ -436,9 +433,8 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     a.row_count = d->d_counters + 4;
     a.work = d->d_work;
     a.overflow_list = d->d_overflow;
-    a.overflow_list2 = d->d_overflow2;
     a.mode = d->mode;
-    a.fb2_cap = e->opt.fallback_item_cap;
+    a.fb_cap = e->opt.fallback_item_cap;
     a.overflow_cap = (uint32_t)d->overflow_cap;
     a.fb_items = d->d_fb_items;
     a.fb_set_start = d->d_fb_ss;
@@ -448,9 +444,9 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     const bool prof = d->profiling;
     if (d->tab.n_chunks > 0) HIP_TRY(launch_cache_merge(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
-    if (d->tab.n_chunks > 0) HIP_TRY(launch_mask_main(a, stream));
+    if (d->tab.n_chunks > 0) HIP_TRY(launch_mask_walk(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));
-    if (d->tab.n_chunks > 0) { HIP_TRY(launch_mask_fallback2(a, stream)); HIP_TRY(launch_mask_fallback3(a, stream)); }
+    if (d->tab.n_chunks > 0) HIP_TRY(launch_mask_fallback(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[2], stream));
     HIP_TRY(launch_permute(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[3], stream));
@@ -463,7 +459,6 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
         HIP_TRY(hipEventElapsedTime(&d->report.permute_ms, d->ev[2], d->ev[3]));
     }
     d->report.overflow_chunks = d->h_counters[0];
-    d->report.overflow_chunks_level3 = d->h_counters[1];
     d->report.chart_bytes = (int64_t)total;
     if (d->h_counters[2]) return fail(ZF_ERR_OVERFLOW, std::to_string(d->h_counters[2]) + " trie chunks exceeded the fallback arena");
     return ZF_OK;

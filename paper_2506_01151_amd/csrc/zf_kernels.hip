@@ -1,18 +1,23 @@
 // HIP kernels for gfx950: the vocabulary-mask kernel (main pass + two exact fallback levels),
 // the rank-order -> token-order bit permutation, and the logit-masking kernel.
 //
-// Mask kernel.  The vocabulary trie is stored in preorder, so a depth-first walk is a linear
-// scan in which a dead subtree is left through the node's skip pointer and a shared prefix is
-// scanned once per lane.  Every lane owns the nodes of `chunk_ranks` consecutive strings.  It
-// first replays the ancestors of its first node, then walks its nodes; per node it performs
-// one Earley byte step (Scan + Complete with tabulated Predict, paper Section 3.2) on a private
-// item list kept in LDS, interleaved by lane so that lanes never collide on a bank.  The list
-// holds one set per trie depth of the current path; moving to a shallower node truncates it.
-// The grammar tables (and the row's chart when it is small) are staged into LDS once per
-// block, so a byte step is a chain of LDS look-ups; only the trie nodes stream from L2.
-// A lane whose list would outgrow its budget (or whose path is too deep) hands its chunk to the
-// fallback: level 2 repeats the walk with one lane per wavefront and a 2,048-item list in LDS,
-// level 3 with the list in a global-memory arena.
+// Mask path.  The vocabulary trie is stored in preorder, so a depth-first walk is a linear scan
+// in which a dead subtree is left through the node's skip pointer and a shared prefix is scanned
+// once.  A chunk is the node range of `chunk_ranks` consecutive strings.
+//   1. cache_merge_kernel: per (row, chunk) merge the context-independent token-mask cache
+//      (Section 4.3) of the row's current Earley set; strings a terminal swallows whole are valid
+//      at once; chunks that hold strings which need the parser go to the row's work queue.
+//   2. mask_walk_kernel: one wavefront per queued chunk.  The 64 lanes first pull the chunk's trie
+//      nodes and the ancestors of its first node into LDS; then ONE lane replays the ancestors and
+//      walks the nodes, one Earley byte step (Scan + Complete with tabulated Predict, Section 3.2)
+//      per node, on an item list in LDS that holds one set per trie depth of the current path.
+//      Earley steps are nests of short data-dependent loops; run on 64 lanes at once they pay for
+//      the longest trip count of every loop level at every step (measured: ~12,000 cycles per
+//      step per wavefront), so a single-lane walk per wavefront with many wavefronts in flight
+//      is the faster mapping on this hardware.  Grammar tables and the row's chart are staged
+//      in LDS once per block of 8 wavefronts.
+//   3. mask_fallback_kernel: chunks whose list outgrew LDS repeat the walk with the list in a
+//      global-memory arena.
 #include <hip/hip_runtime.h>
 #include "zf_launch.h"
 
@@ -73,18 +78,7 @@ __device__ __forceinline__ uint32_t stage_tables(const DeviceTables &D, uint8_t 
 
 // ---- item-list storage policies ---------------------------------------------------------
 // An item is (w, o): w = item word (see IW_* in zf_device.h), o = origin set.
-struct LaneLdsStore {          // main kernel: one list per lane, interleaved by lane
-    uint32_t *pq;              // column of this lane, stride 64
-    uint16_t *org;
-    uint8_t *ss;
-    uint32_t cap;
-    static constexpr int max_depth = LANE_DEPTH_MAX;
-    __device__ __forceinline__ void get(uint32_t i, uint32_t &p, uint32_t &o) const { p = pq[i * 64]; o = org[i * 64]; }
-    __device__ __forceinline__ void put(uint32_t i, uint32_t p, uint32_t o) { pq[i * 64] = p; org[i * 64] = (uint16_t)o; }
-    __device__ __forceinline__ uint32_t start(int d) const { return ss[d * 64]; }
-    __device__ __forceinline__ void set_start(int d, uint32_t v) { ss[d * 64] = (uint8_t)v; }
-};
-struct WaveLdsStore {          // fallback level 2: the whole wavefront's LDS serves one lane
+struct WaveLdsStore {          // walk kernel: the wavefront's list in LDS, used by its walking lane
     uint32_t *pq;
     uint32_t *org;
     uint16_t *ss;
@@ -95,7 +89,7 @@ struct WaveLdsStore {          // fallback level 2: the whole wavefront's LDS se
     __device__ __forceinline__ uint32_t start(int d) const { return ss[d]; }
     __device__ __forceinline__ void set_start(int d, uint32_t v) { ss[d] = (uint16_t)v; }
 };
-struct GlobalStore {           // fallback level 3: arena in global memory, interleaved by lane
+struct GlobalStore {           // fallback: arena in global memory, interleaved by lane
     uint2 *items;
     uint32_t *ss;
     uint32_t cap;
@@ -227,30 +221,30 @@ __device__ __forceinline__ int earley_step(const TV &T, const Base &B, S &st, in
 // depth j+1.  Returns false on overflow; otherwise *bits_out holds the chunk's verdicts.
 // `want` marks the strings of the chunk that still need a verdict (the others are decided by the
 // token-mask cache); subtrees without such a string are skipped without a byte step.
-template <class S, class Anc>
-__device__ __forceinline__ bool walk_chunk(const DeviceTables &D, const TV &T, const Base &B, S &st, uint32_t chunk, uint32_t want, Anc anc, uint32_t *bits_out) {
-    uint32_t i = D.chunk_begin[chunk];
-    const uint32_t end = D.chunk_end[chunk];
+template <class S, class Anc, class Nodes>
+__device__ __forceinline__ bool walk_chunk(const DeviceTables &D, const TV &T, const Base &B, S &st, uint32_t chunk, uint32_t want,
+                                           uint32_t begin, uint32_t end, Anc anc, Nodes node, uint32_t *bits_out) {
+    uint32_t i = begin;
     const uint32_t rank0 = chunk * (uint32_t)D.chunk_ranks;
     uint32_t bits = 0, cnt = 0;
     st.set_start(1, 0);
-    TrieNode nd = D.nodes[i];
+    TrieNode nd = node(i);
     const int d0 = nd.depth;
     if (d0 > S::max_depth) return false;
     for (int j = 0; j + 1 < d0; j++) {   // replay the path above the chunk's first node
-        const TrieNode an = D.nodes[anc(j)];
+        const TrieNode an = anc(j);
         const int r = earley_step(T, B, st, j + 1, an.byte, cnt);
         if (r & STEP_OVERFLOW) return false;
         if (!(r & STEP_KERNEL)) {        // that whole subtree is dead
             i = an.skip; cnt = st.start(j + 1);
-            if (i < end) nd = D.nodes[i];
+            if (i < end) nd = node(i);
             break;
         }
     }
     while (i < end) {
         const uint32_t nxt = i + 1;
         TrieNode nx = nd;
-        if (nxt < end) nx = D.nodes[nxt];                // issued before the step so that it overlaps it
+        if (nxt < end) nx = node(nxt);                   // issued before the step so that it overlaps it
         const int d = nd.depth;
         uint32_t ni;
         const uint32_t rel = nd.rank - rank0;
@@ -265,7 +259,7 @@ __device__ __forceinline__ bool walk_chunk(const DeviceTables &D, const TV &T, c
             ni = (r & STEP_KERNEL) ? nxt : nd.skip;
         }
         if (ni == nxt) nd = nx;
-        else if (ni < end) nd = D.nodes[ni];
+        else if (ni < end) nd = node(ni);
         i = ni;
     }
     *bits_out = bits;
@@ -322,67 +316,18 @@ __global__ __launch_bounds__(256) void cache_merge_kernel(MaskArgs a) {
     }
 }
 
-__device__ __forceinline__ uint32_t lane_region_bytes(uint32_t cap) { return cap * 64 * 6 + (LANE_DEPTH_MAX + 2) * 64; }
 static const uint32_t BASE_LDS_BYTES = (BASE_SETS_LDS + 1) * 4 + BASE_ITEMS_LDS * 8;
-
-// The parser walk: one lane per queued chunk of the block's row.
-template <int MODE>
-__global__ __launch_bounds__(MAIN_BLOCK) void mask_main_kernel(MaskArgs a) {
-    extern __shared__ __align__(16) uint8_t smem[];
-    const DeviceTables &D = a.tab;
-    const uint32_t tid = threadIdx.x, row = blockIdx.y;
-    const uint32_t n_work = a.row_count[row];
-    if (blockIdx.x * MAIN_BLOCK >= n_work) return;      // uniform: the queue of this row is shorter
-    TV T;
-    uint32_t off = stage_tables<MODE>(D, smem, T, tid, MAIN_BLOCK);
-    // the row's chart: LDS copy when small
-    const RowChart rc = a.rows[row];
-    const uint32_t *g_so = a.set_off + rc.set_base;
-    const uint2 *g_it = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
-    const uint32_t n_items = g_so[rc.n_sets];
-    Base B;
-    B.m = rc.n_sets;
-    B.last_lo = g_so[rc.n_sets - 1];
-    B.last_hi = n_items;
-    if (rc.n_sets <= BASE_SETS_LDS && n_items <= BASE_ITEMS_LDS) {
-        uint32_t *l_so = reinterpret_cast<uint32_t *>(smem + off);
-        uint2 *l_it = reinterpret_cast<uint2 *>(smem + off + (BASE_SETS_LDS + 1) * 4);
-        for (uint32_t k = tid; k <= rc.n_sets; k += MAIN_BLOCK) l_so[k] = g_so[k];
-        for (uint32_t k = tid; k < n_items; k += MAIN_BLOCK) l_it[k] = g_it[k];
-        B.so = l_so; B.it = l_it;
-    } else { B.so = g_so; B.it = g_it; }
-    off += BASE_LDS_BYTES;
-    __syncthreads();
-    const uint32_t e = blockIdx.x * MAIN_BLOCK + tid;
-    if (e >= n_work) return;
-    const uint2 item = a.work[(size_t)row * D.n_chunks + e];
-    const uint32_t chunk = item.x, want = item.y;
-    const uint32_t wave = tid >> 6, lane = tid & 63;
-    const uint32_t cap = (uint32_t)a.lane_cap;
-    uint8_t *region = smem + off + wave * lane_region_bytes(cap);
-    LaneLdsStore st;
-    st.pq = reinterpret_cast<uint32_t *>(region) + lane;
-    st.org = reinterpret_cast<uint16_t *>(region + cap * 64 * 4) + lane;
-    st.ss = region + cap * 64 * 6 + lane;
-    st.cap = cap;
-    const uint32_t *anc_row = D.chunk_anc + (size_t)chunk * CHUNK_ANC;
-    uint32_t bits = 0;
-    bool ok = cap > 0 && B.m + LANE_DEPTH_MAX < 0xFFFFu &&
-              walk_chunk(D, T, B, st, chunk, want, [&](int j) { return anc_row[j]; }, &bits);
-    if (!ok) {
-        const uint32_t slot = atomicAdd(&a.counters[0], 1u);
-        if (slot < a.overflow_cap) a.overflow_list[slot] = make_uint4(row, chunk, want, 0);
-        return;
-    }
-    or_bits(D, a.rank_mask, row, chunk, bits & want);
+__host__ __device__ inline uint32_t wave_region_bytes(uint32_t cap) {
+    // prefetched nodes, ancestor nodes, item words, origins, set starts (uint16); a multiple of 16
+    return (WALK_NODES_LDS + CHUNK_ANC) * 16 + (cap * 8 + (FB_DEPTH_MAX + 2) * 2 + 15) / 16 * 16;
 }
 
-struct ParentAnc {             // ancestor at depth j+1 through the parent links
-    const uint32_t *parent; uint32_t first; int d0;
-    __device__ __forceinline__ uint32_t operator()(int j) const {
+struct ParentAnc {             // ancestor node at depth j+1 through the parent links
+    const TrieNode *nodes; const uint32_t *parent; uint32_t first; int d0;
+    __device__ __forceinline__ TrieNode operator()(int j) const {
         uint32_t x = first;
         for (int k = d0; k > j + 1; k--) x = parent[x];
-        return x;
+        return nodes[x];
     }
 };
 
@@ -397,53 +342,87 @@ __device__ __forceinline__ Base global_base(const MaskArgs &a, uint32_t row) {
     return B;
 }
 
-// Fallback level 2: one chunk per wavefront, walked by lane 0 with a 2,048-item list in LDS.
+// The parser walk: one wavefront per queued chunk of the block's row.
 template <int MODE>
-__global__ __launch_bounds__(64) void mask_fallback2_kernel(MaskArgs a) {
+__global__ __launch_bounds__(WALK_BLOCK) void mask_walk_kernel(MaskArgs a) {
     extern __shared__ __align__(16) uint8_t smem[];
     const DeviceTables &D = a.tab;
+    const uint32_t tid = threadIdx.x, row = blockIdx.y;
+    const uint32_t n_work = a.row_count[row];
+    if (blockIdx.x * WALK_WAVES >= n_work) return;      // uniform: the queue of this row is shorter
     TV T;
-    uint32_t off = stage_tables<MODE>(D, smem, T, threadIdx.x, 64);
-    __syncthreads();
-    uint32_t n = a.counters[0];
-    if (n > a.overflow_cap) { if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&a.counters[2], n - a.overflow_cap); n = a.overflow_cap; }
-    if (threadIdx.x != 0) return;
-    WaveLdsStore st;
-    st.pq = reinterpret_cast<uint32_t *>(smem + off);
-    st.org = st.pq + FB2_CAP;
-    st.ss = reinterpret_cast<uint16_t *>(st.org + FB2_CAP);
-    st.cap = (uint32_t)a.fb2_cap;
-    for (uint32_t e = blockIdx.x; e < n; e += gridDim.x) {
-        const uint4 ent = a.overflow_list[e];
-        const Base B = global_base(a, ent.x);
-        const uint32_t first = D.chunk_begin[ent.y];
-        ParentAnc anc{D.parent, first, D.nodes[first].depth};
-        uint32_t bits = 0;
-        if (!walk_chunk(D, T, B, st, ent.y, ent.z, anc, &bits)) {
-            const uint32_t slot = atomicAdd(&a.counters[1], 1u);
-            if (slot < a.overflow_cap) a.overflow_list2[slot] = ent;
-            continue;
+    uint32_t off = stage_tables<MODE>(D, smem, T, tid, WALK_BLOCK);
+    // the row's chart: LDS copy when small
+    const RowChart rc = a.rows[row];
+    const uint32_t *g_so = a.set_off + rc.set_base;
+    const uint2 *g_it = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
+    const uint32_t n_items = g_so[rc.n_sets];
+    Base B;
+    B.m = rc.n_sets;
+    B.last_lo = g_so[rc.n_sets - 1];
+    B.last_hi = n_items;
+    if (rc.n_sets <= BASE_SETS_LDS && n_items <= BASE_ITEMS_LDS) {
+        uint32_t *l_so = reinterpret_cast<uint32_t *>(smem + off);
+        uint2 *l_it = reinterpret_cast<uint2 *>(smem + off + (BASE_SETS_LDS + 1) * 4);
+        for (uint32_t k = tid; k <= rc.n_sets; k += WALK_BLOCK) l_so[k] = g_so[k];
+        for (uint32_t k = tid; k < n_items; k += WALK_BLOCK) l_it[k] = g_it[k];
+        B.so = l_so; B.it = l_it;
+    } else { B.so = g_so; B.it = g_it; }
+    off += BASE_LDS_BYTES;
+    const uint32_t wave = tid >> 6, lane = tid & 63;
+    const uint32_t e = blockIdx.x * WALK_WAVES + wave;
+    const uint32_t cap = (uint32_t)a.lane_cap;
+    uint8_t *region = smem + off + wave * wave_region_bytes(cap);
+    TrieNode *l_nodes = reinterpret_cast<TrieNode *>(region);
+    TrieNode *l_anc = l_nodes + WALK_NODES_LDS;
+    uint32_t chunk = 0, want = 0, begin = 0, end = 0;
+    if (e < n_work) {                                    // all lanes pull the chunk's nodes and ancestors into LDS
+        const uint2 item = a.work[(size_t)row * D.n_chunks + e];
+        chunk = item.x; want = item.y;
+        begin = D.chunk_begin[chunk]; end = D.chunk_end[chunk];
+        for (uint32_t k = lane; k < end - begin && k < (uint32_t)WALK_NODES_LDS; k += 64) l_nodes[k] = D.nodes[begin + k];
+        if (lane < CHUNK_ANC) {
+            const uint32_t ai = D.chunk_anc[(size_t)chunk * CHUNK_ANC + lane];   // unused slots hold node 0
+            l_anc[lane] = D.nodes[ai];
         }
-        or_bits(D, a.rank_mask, ent.x, ent.y, bits & ent.z);
     }
+    __syncthreads();
+    if (e >= n_work || lane != 0) return;
+    WaveLdsStore st;
+    st.pq = reinterpret_cast<uint32_t *>(region + (WALK_NODES_LDS + CHUNK_ANC) * 16);
+    st.org = st.pq + cap;
+    st.ss = reinterpret_cast<uint16_t *>(st.org + cap);
+    st.cap = cap;
+    const int d0 = l_nodes[0].depth;
+    ParentAnc deep{D.nodes, D.parent, begin, d0};
+    uint32_t bits = 0;
+    const bool ok = cap > 0 && walk_chunk(D, T, B, st, chunk, want, begin, end,
+        [&](int j) { return d0 - 1 <= CHUNK_ANC ? l_anc[j] : deep(j); },
+        [&](uint32_t i) { return i - begin < (uint32_t)WALK_NODES_LDS ? l_nodes[i - begin] : D.nodes[i]; }, &bits);
+    if (!ok) {
+        const uint32_t slot = atomicAdd(&a.counters[0], 1u);
+        if (slot < a.overflow_cap) a.overflow_list[slot] = make_uint4(row, chunk, want, 0);
+        return;
+    }
+    or_bits(D, a.rank_mask, row, chunk, bits & want);
 }
 
-// Fallback level 3: one lane per remaining chunk, item list in a global-memory arena.
-__global__ __launch_bounds__(64) void mask_fallback3_kernel(MaskArgs a) {
+// Fallback: one lane per chunk that outgrew LDS, item list in a global-memory arena.
+__global__ __launch_bounds__(64) void mask_fallback_kernel(MaskArgs a) {
     const DeviceTables &D = a.tab;
     TV T;
     stage_tables<2>(D, nullptr, T, 0, 1);
     const uint32_t gid = blockIdx.x * 64 + threadIdx.x;
-    uint32_t n = a.counters[1];
+    uint32_t n = a.counters[0];
     if (n > a.overflow_cap) { if (gid == 0) atomicAdd(&a.counters[2], n - a.overflow_cap); n = a.overflow_cap; }
-    GlobalStore st{a.fb_items + gid, a.fb_set_start + gid, (uint32_t)FB3_ITEMS_PER_LANE};
+    GlobalStore st{a.fb_items + gid, a.fb_set_start + gid, (uint32_t)a.fb_cap};
     for (uint32_t e = gid; e < n; e += FB3_LANES) {
-        const uint4 ent = a.overflow_list2[e];
+        const uint4 ent = a.overflow_list[e];
         const Base B = global_base(a, ent.x);
-        const uint32_t first = D.chunk_begin[ent.y];
-        ParentAnc anc{D.parent, first, D.nodes[first].depth};
+        const uint32_t begin = D.chunk_begin[ent.y], end = D.chunk_end[ent.y];
+        ParentAnc anc{D.nodes, D.parent, begin, D.nodes[begin].depth};
         uint32_t bits = 0;
-        if (!walk_chunk(D, T, B, st, ent.y, ent.z, anc, &bits)) { atomicAdd(&a.counters[2], 1u); continue; }
+        if (!walk_chunk(D, T, B, st, ent.y, ent.z, begin, end, anc, [&](uint32_t i) { return D.nodes[i]; }, &bits)) { atomicAdd(&a.counters[2], 1u); continue; }
         or_bits(D, a.rank_mask, ent.x, ent.y, bits & ent.z);
     }
 }
@@ -522,8 +501,7 @@ hipError_t prepare_kernels() {
     const int max_lds = 160 * 1024;
     hipError_t e;
 #define SET_ATTR(k) if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k), hipFuncAttributeMaxDynamicSharedMemorySize, max_lds)) != hipSuccess) return e
-    SET_ATTR(mask_main_kernel<0>); SET_ATTR(mask_main_kernel<1>); SET_ATTR(mask_main_kernel<2>);
-    SET_ATTR(mask_fallback2_kernel<0>); SET_ATTR(mask_fallback2_kernel<1>); SET_ATTR(mask_fallback2_kernel<2>);
+    SET_ATTR(mask_walk_kernel<0>); SET_ATTR(mask_walk_kernel<1>); SET_ATTR(mask_walk_kernel<2>);
 #undef SET_ATTR
     return hipSuccess;
 }
@@ -533,23 +511,16 @@ hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s) {
     hipLaunchKernelGGL(cache_merge_kernel, grid, dim3(256), 0, s, a);
     return hipGetLastError();
 }
-hipError_t launch_mask_main(const MaskArgs &a, hipStream_t s) {
-    dim3 grid((a.tab.n_chunks + MAIN_BLOCK - 1) / MAIN_BLOCK, a.batch);
-    const uint32_t lds = table_bytes(a.tab, a.mode) + BASE_LDS_BYTES + (MAIN_BLOCK / 64) * ((uint32_t)a.lane_cap * 64 * 6 + (LANE_DEPTH_MAX + 2) * 64);
-    if (a.mode == 0) hipLaunchKernelGGL(mask_main_kernel<0>, grid, dim3(MAIN_BLOCK), lds, s, a);
-    else if (a.mode == 1) hipLaunchKernelGGL(mask_main_kernel<1>, grid, dim3(MAIN_BLOCK), lds, s, a);
-    else hipLaunchKernelGGL(mask_main_kernel<2>, grid, dim3(MAIN_BLOCK), lds, s, a);
+hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s) {
+    dim3 grid((a.tab.n_chunks + WALK_WAVES - 1) / WALK_WAVES, a.batch);
+    const uint32_t lds = table_bytes(a.tab, a.mode) + BASE_LDS_BYTES + WALK_WAVES * wave_region_bytes((uint32_t)a.lane_cap);
+    if (a.mode == 0) hipLaunchKernelGGL(mask_walk_kernel<0>, grid, dim3(WALK_BLOCK), lds, s, a);
+    else if (a.mode == 1) hipLaunchKernelGGL(mask_walk_kernel<1>, grid, dim3(WALK_BLOCK), lds, s, a);
+    else hipLaunchKernelGGL(mask_walk_kernel<2>, grid, dim3(WALK_BLOCK), lds, s, a);
     return hipGetLastError();
 }
-hipError_t launch_mask_fallback2(const MaskArgs &a, hipStream_t s) {
-    const uint32_t lds = table_bytes(a.tab, a.mode) + FB2_CAP * 8 + (FB_DEPTH_MAX + 2) * 2 + 16;
-    if (a.mode == 0) hipLaunchKernelGGL(mask_fallback2_kernel<0>, dim3(FB2_BLOCKS), dim3(64), lds, s, a);
-    else if (a.mode == 1) hipLaunchKernelGGL(mask_fallback2_kernel<1>, dim3(FB2_BLOCKS), dim3(64), lds, s, a);
-    else hipLaunchKernelGGL(mask_fallback2_kernel<2>, dim3(FB2_BLOCKS), dim3(64), lds, s, a);
-    return hipGetLastError();
-}
-hipError_t launch_mask_fallback3(const MaskArgs &a, hipStream_t s) {
-    hipLaunchKernelGGL(mask_fallback3_kernel, dim3(FB3_LANES / 64), dim3(64), 0, s, a);
+hipError_t launch_mask_fallback(const MaskArgs &a, hipStream_t s) {
+    hipLaunchKernelGGL(mask_fallback_kernel, dim3(FB3_LANES / 64), dim3(64), 0, s, a);
     return hipGetLastError();
 }
 hipError_t launch_permute(const MaskArgs &a, hipStream_t s) {

@@ -61,15 +61,26 @@ def test_config2_json_v32k(torch_cuda, oracle_lib):
     _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(), cfg.batch, cfg.steps, cfg.seed)
 
 
-@pytest.mark.parametrize("cap,cap2", [(1, 0), (2, 0), (4, 0), (1, 1), (2, 3), (4, 8)])
-def test_forced_overflow_gives_same_bits(cap, cap2, torch_cuda, oracle_lib):
-    """Tiny item budgets push chunks to the LDS fallback (cap) and on to the global-memory
-    level (cap2); the bits must not change."""
+@pytest.mark.parametrize("cap", [1, 2, 4, 7])
+def test_forced_overflow_gives_same_bits(cap, torch_cuda, oracle_lib):
+    """A tiny LDS item budget pushes chunks to the global-memory fallback; the bits must not change."""
     import paper_2506_01151_amd as zf
     cfg = configs.CONFIGS[1]
-    ov = _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(), 2, 24, cfg.seed + 77,
-                     lane_item_cap=cap, fallback_item_cap=cap2)
+    ov = _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(), 2, 24, cfg.seed + 77, lane_item_cap=cap)
     assert ov > 0, "the cap was meant to force the fallback pass"
+
+
+def test_overflow_beyond_the_fallback_is_an_error(torch_cuda):
+    """When even the fallback arena is too small the call must fail loudly (no silent wrong mask)."""
+    import paper_2506_01151_amd as zf
+    cfg = configs.CONFIGS[1]
+    eng = zf.Engine(cfg.grammar(), cfg.vocab(), device=0, lane_item_cap=1, fallback_item_cap=1)
+    s = eng.new_state()
+    s.advance_bytes(b'{"a": [1')
+    d_mask = torch_cuda.empty((1, eng.W), dtype=torch_cuda.int32, device="cuda")
+    with pytest.raises(zf.ZfError) as ei:
+        zf.compute_mask(eng, [s], d_mask)
+    assert ei.value.code == zf.ZF_ERR_OVERFLOW
 
 
 @pytest.mark.parametrize("chunk", [8, 16, 32])
