@@ -23,7 +23,8 @@ struct DeviceSide {
     void *h_stage = nullptr; size_t stage_cap = 0;   // pinned
     uint32_t *d_rank_mask = nullptr; size_t rank_cap = 0;
     uint4 *d_overflow = nullptr; size_t overflow_cap = 0;
-    uint2 *d_work = nullptr;
+    uint4 *d_work = nullptr;
+    int walk_blocks = 256;
     int mode = 2;
     uint32_t *d_counters = nullptr;
     uint32_t *h_counters = nullptr;      // pinned
@@ -97,7 +98,16 @@ int setup_device(zf_engine *e) {
     T.Wr = tr.Wr;
     d->mode = choose_table_mode(T);
     HIP_TRY(prepare_kernels());
-    HIP_TRY(hipMalloc((void **)&d->d_counters, 16 + 4 * MAX_BATCH));
+    {   // the persistent walk grid: as many blocks as fit on the chip at once (LDS is the limit)
+        int cus = 0;
+        HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, d->device));
+        const uint32_t lds = walk_lds_bytes(T, d->mode, e->opt.lane_item_cap);
+        if (lds > 160u * 1024u) return fail(ZF_ERR_INVALID_ARG, "lane_item_cap and the grammar tables do not fit the 160 KB of LDS");
+        int per_cu = (int)(160u * 1024u / lds);
+        if (per_cu > 4) per_cu = 4;      // 4 blocks x 8 wavefronts = 8 wavefronts per SIMD
+        d->walk_blocks = std::max(1, cus) * std::max(1, per_cu);
+    }
+    HIP_TRY(hipMalloc((void **)&d->d_counters, 16));
     HIP_TRY(hipHostMalloc((void **)&d->h_counters, 16, hipHostMallocDefault));
     HIP_TRY(hipMalloc((void **)&d->d_fb_items, (size_t)FB3_ITEMS_PER_LANE * FB3_LANES * sizeof(uint2)));
     HIP_TRY(hipMalloc((void **)&d->d_fb_ss, (size_t)(FB_DEPTH_MAX + 2) * FB3_LANES * sizeof(uint32_t)));
@@ -183,7 +193,7 @@ int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_option
         e->V = v->V; e->W = (v->V + 31) / 32;
         e->voc_off.assign(v->off, v->off + v->V + 1);
         e->voc_bytes.assign(v->bytes, v->bytes + v->off[v->V]);
-        build_trie(v, e->opt.chunk_strings, e->trie);
+        build_trie(v, e->opt.chunk_strings, e->tab.cls, e->trie);
         build_token_mask_cache(e->tab, e->trie);
     } catch (const std::bad_alloc &) { delete e; return fail(ZF_ERR_OOM, "out of memory"); }
     if (e->opt.device >= 0) {
@@ -395,7 +405,7 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
         uint32_t so_at = 0, it_at = 0, en_at = 0;
         for (int b = 0; b < batch; b++) {
             const Chart &c = states[b]->chart;
-            rows[b] = RowChart{c.n_sets(), so_at, it_at, en_at, 0, {0, 0, 0}};
+            rows[b] = RowChart{c.n_sets(), so_at, it_at, en_at, 0, (uint32_t)c.items.size(), {0, 0}};
             if (use_cache) rows[b].n_ent = current_set_entries(e->tab, c, ents + en_at);
             en_at += rows[b].n_ent;
             memcpy(so + so_at, c.set_off.data(), 4 * c.set_off.size());
@@ -418,7 +428,7 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
         d->d_rank_mask = nullptr; d->d_overflow = nullptr; d->d_work = nullptr; d->rank_cap = d->overflow_cap = 0;
         HIP_TRY(hipMalloc((void **)&d->d_rank_mask, need_rank * 4 + 16));
         HIP_TRY(hipMalloc((void **)&d->d_overflow, need_ovf * sizeof(uint4) + 16));
-        HIP_TRY(hipMalloc((void **)&d->d_work, need_ovf * sizeof(uint2) + 16));
+        HIP_TRY(hipMalloc((void **)&d->d_work, need_ovf * sizeof(uint4) + 16));
         d->rank_cap = need_rank; d->overflow_cap = need_ovf;
     }
     MaskArgs a{};
@@ -430,17 +440,17 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     a.rank_mask = d->d_rank_mask;
     a.out_mask = d_mask;
     a.counters = d->d_counters;
-    a.row_count = d->d_counters + 4;
     a.work = d->d_work;
     a.overflow_list = d->d_overflow;
     a.mode = d->mode;
+    a.walk_blocks = d->walk_blocks;
     a.fb_cap = e->opt.fallback_item_cap;
     a.overflow_cap = (uint32_t)d->overflow_cap;
     a.fb_items = d->d_fb_items;
     a.fb_set_start = d->d_fb_ss;
     a.batch = batch;
     a.lane_cap = e->opt.lane_item_cap;
-    HIP_TRY(hipMemsetAsync(d->d_counters, 0, 16 + 4 * (size_t)batch, stream));
+    HIP_TRY(hipMemsetAsync(d->d_counters, 0, 16, stream));
     const bool prof = d->profiling;
     if (d->tab.n_chunks > 0) HIP_TRY(launch_cache_merge(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));

@@ -180,9 +180,13 @@ bool build_tables(const zf_grammar_desc *g, Tables &t) {
                 int b = 0;
                 for (int x = 0; x < 256; x++) if (dfas[k].trans[s * 256 + x] >= 0) b = x;
                 info |= QF_LITERAL | ((uint32_t)b << 8);
+                if (s + 1 < dfas[k].n_states()) info |= (uint32_t)t.qflags[q + 1] << 16;
             } else {
                 uint32_t row = (uint32_t)(t.delta_dense.size() / t.n_cls);
-                t.delta_dense.insert(t.delta_dense.end(), t.delta.begin() + (size_t)q * t.n_cls, t.delta.begin() + (size_t)(q + 1) * t.n_cls);
+                for (int c = 0; c < t.n_cls; c++) {
+                    uint16_t to = t.delta[(size_t)q * t.n_cls + c];
+                    t.delta_dense.push_back(to == DFA_DEAD ? (uint32_t)DFA_DEAD : ((uint32_t)to | ((uint32_t)t.qflags[to] << 16)));
+                }
                 info |= row << 16;
             }
             t.qinfo[q] = info;
@@ -245,13 +249,16 @@ bool build_tables(const zf_grammar_desc *g, Tables &t) {
         t.comp_list.insert(t.comp_list.end(), comp_tmp[Y][X].begin(), comp_tmp[Y][X].end());
     }
     t.comp_off[(size_t)N * N] = (uint32_t)t.comp_list.size();
-    t.dev_scan_list.resize(t.scan_list.size());
-    for (size_t k = 0; k < t.scan_list.size(); k++) t.dev_scan_list[k] = t.scan_list[k] | IW_TERM;
+    t.dev_scan_list.resize(2 * t.scan_list.size());
+    for (size_t k = 0; k < t.scan_list.size(); k++) {
+        t.dev_scan_list[2 * k] = t.scan_list[k] | IW_TERM;
+        t.dev_scan_list[2 * k + 1] = t.qflags[t.scan_list[k] >> 16];
+    }
     return true;
 }
 
 // ---- vocabulary -> flattened prefix trie ---------------------------------------------------
-void build_trie(const zf_vocab_desc *v, int CHUNK_RANKS, Trie &t) {
+void build_trie(const zf_vocab_desc *v, int CHUNK_RANKS, const uint8_t *cls, Trie &t) {
     t.chunk_ranks = CHUNK_RANKS;
     const int V = v->V;
     std::vector<int> order;
@@ -282,7 +289,7 @@ void build_trie(const zf_vocab_desc *v, int CHUNK_RANKS, Trie &t) {
         path.resize(common); path_bytes.resize(common);
         for (size_t d = common; d < n; d++) {
             TrieNode nd{};
-            nd.byte = p[d]; nd.depth = (uint8_t)(d + 1); nd.has_string = (d + 1 == n); nd.rank = rank; nd.skip = 0;
+            nd.byte = p[d]; nd.cls = cls[p[d]]; nd.depth = (uint8_t)(d + 1); nd.has_string = (d + 1 == n); nd.rank = rank; nd.skip = 0;
             t.parent.push_back(d == 0 ? 0xFFFFFFFFu : path[d - 1]);
             path.push_back((uint32_t)t.nodes.size()); path_bytes.push_back(p[d]);
             t.nodes.push_back(nd);
@@ -315,13 +322,13 @@ void build_trie(const zf_vocab_desc *v, int CHUNK_RANKS, Trie &t) {
     }
     t.Wr = (n_chunks * CHUNK_RANKS + 31) / 32;
     // ancestors of each chunk's first node (top down), for the lanes that start in mid-trie
-    t.chunk_anc.assign((size_t)n_chunks * CHUNK_ANC, 0);
+    t.chunk_anc.assign((size_t)n_chunks * CHUNK_ANC, TrieNode{});
     for (int c = 0; c < n_chunks; c++) {
         uint32_t i = t.chunk_begin[c];
         int d = t.nodes[i].depth;
         for (uint32_t a = t.parent[i]; a != 0xFFFFFFFFu; a = t.parent[a]) {
             d--;
-            if (d - 1 < CHUNK_ANC) t.chunk_anc[(size_t)c * CHUNK_ANC + d - 1] = a;
+            if (d - 1 < CHUNK_ANC) t.chunk_anc[(size_t)c * CHUNK_ANC + d - 1] = t.nodes[a];
         }
     }
 }

@@ -23,8 +23,9 @@ enum : uint32_t {
     IW_NT_NULLABLE = 1u << 16, IW_NT_SHIFT = 17, IW_NT_MASK = 0x1FFF,
     MAX_POSITIONS = 0x3FFF,
 };
-// Per-DFA-state word: flags | expected byte << 8 | dense transition row << 16.  States of a
-// literal terminal form a chain (one expected byte, next state = q + 1) and need no table row.
+// Per-DFA-state word.  States of a literal terminal form a chain (one expected byte, next state
+// q + 1) and need no table row: flags | QF_LITERAL | expected byte << 8 | flags of state q+1 << 16.
+// Other states: flags | dense transition row << 16; a row entry is next state | its flags << 16.
 enum : uint8_t { QF_ACCEPT = 1, QF_CONT = 2, QF_LITERAL = 4 };
 
 // One Earley item.  p: dotted position (index into sym[]); q: DFA state when the postdot
@@ -41,7 +42,7 @@ struct Item {
 struct TrieNode {
     uint32_t skip;
     uint32_t rank;
-    uint8_t byte, depth, has_string, pad;
+    uint8_t byte, depth, has_string, cls;   // cls = byte equivalence class of `byte`
     uint32_t n_sub;      // strings carried by this node's subtree (itself included)
 };
 
@@ -56,8 +57,8 @@ struct DeviceTables {
     const uint32_t *qinfo;      // [Q]
     const uint32_t *scan_off;   // [N*n_cls+1] CSR into scan_list
     const uint32_t *comp_off;   // [N*N+1] CSR into comp_list
-    const uint16_t *delta;      // [dense rows][n_cls]
-    const uint32_t *scan_list;  // item words (terminal already stepped once)
+    const uint32_t *delta;      // [dense rows][n_cls] next state | flags << 16, DFA_DEAD in the low half = no edge
+    const uint32_t *scan_list;  // pairs: item word (terminal already stepped once), flags of its DFA state
     const uint16_t *comp_list;  // advanced positions
     uint32_t small_bytes[5];    // padded byte sizes of advpq .. comp_off (always staged into LDS when they fit)
     uint32_t big_bytes[3];      // padded byte sizes of delta, scan_list, comp_list
@@ -65,7 +66,7 @@ struct DeviceTables {
     const uint32_t *parent;     // [n_nodes] parent node index, 0xFFFFFFFF for depth-1 nodes
     const uint32_t *chunk_begin; // [n_chunks] first node of the chunk
     const uint32_t *chunk_end;   // [n_chunks] one past the last string node of the chunk
-    const uint32_t *chunk_anc;   // [n_chunks][CHUNK_ANC] ancestors of the chunk's first node, depth 1 first
+    const TrieNode *chunk_anc;   // [n_chunks][CHUNK_ANC] copies of the ancestors of the chunk's first node, depth 1 first
     const uint32_t *rank_of;    // [V] rank of token v's string, 0xFFFFFFFF for the empty token
     // Context-independent token-mask cache (paper Section 4.3), one bitset row of Wr words per DFA
     // state q (row q) and per nonterminal Y (row Q + Y), in string-rank order:
@@ -85,7 +86,8 @@ struct RowChart {
     uint32_t item_base;  // index into the shared item array
     uint32_t ent_base;   // index into the shared entry array: bitset rows of the current set's items
     uint32_t n_ent;      // 0 = token-mask cache not used for this row
-    uint32_t pad[3];
+    uint32_t n_items;    // items of the row's chart
+    uint32_t pad[2];
 };
 
 }  // namespace zf

@@ -37,9 +37,9 @@ struct Tables {
     std::vector<uint16_t> delta;      // [Q*n_cls]
     std::vector<uint8_t> qflags;      // [Q]
     std::vector<uint32_t> advpq;      // [P] device item word to insert when the dot arrives at p
-    std::vector<uint32_t> dev_scan_list;  // scan_list as device item words
+    std::vector<uint32_t> dev_scan_list;  // scan_list for the device: (item word, flags) pairs
     std::vector<uint32_t> qinfo;      // [Q] flags | literal byte << 8 | dense row << 16
-    std::vector<uint16_t> delta_dense; // rows of the non-literal states only
+    std::vector<uint32_t> delta_dense; // rows of the non-literal states only: next state | flags << 16
     int end_base = 0;                 // end_pos[X] == end_base + X
     std::vector<std::vector<uint16_t>> first_terms;   // [N] terminals that can begin a derivation of Y
     std::vector<uint16_t> term_start; // [T]
@@ -57,7 +57,8 @@ bool build_tables(const zf_grammar_desc *g, Tables &t);
 struct Trie {
     std::vector<TrieNode> nodes;      // preorder
     std::vector<uint32_t> parent;
-    std::vector<uint32_t> chunk_begin, chunk_end, chunk_anc;
+    std::vector<uint32_t> chunk_begin, chunk_end;
+    std::vector<TrieNode> chunk_anc;   // [n_chunks][CHUNK_ANC]
     std::vector<uint32_t> rank_of;    // [V]
     int n_strings = 0;
     int chunk_ranks = 32;
@@ -67,7 +68,7 @@ struct Trie {
 // Context-independent token-mask cache (Section 4.3): per DFA state and per nonterminal, which
 // strings are decided by the terminal alone and which need the parser.
 void build_token_mask_cache(const Tables &t, Trie &tr);
-void build_trie(const zf_vocab_desc *v, int chunk_ranks, Trie &t);
+void build_trie(const zf_vocab_desc *v, int chunk_ranks, const uint8_t *cls, Trie &t);
 
 // ---- chart --------------------------------------------------------------------------------------
 struct Chart {

@@ -6,16 +6,17 @@
 // once.  A chunk is the node range of `chunk_ranks` consecutive strings.
 //   1. cache_merge_kernel: per (row, chunk) merge the context-independent token-mask cache
 //      (Section 4.3) of the row's current Earley set; strings a terminal swallows whole are valid
-//      at once; chunks that hold strings which need the parser go to the row's work queue.
-//   2. mask_walk_kernel: one wavefront per queued chunk.  The 64 lanes first pull the chunk's trie
+//      at once; chunks that hold strings which need the parser go to the work queue.
+//   2. mask_walk_kernel: a persistent grid (as many blocks as the chip holds at once) whose
+//      wavefronts take queued chunks in turn.  The 64 lanes first pull the chunk's trie
 //      nodes and the ancestors of its first node into LDS; then ONE lane replays the ancestors and
 //      walks the nodes, one Earley byte step (Scan + Complete with tabulated Predict, Section 3.2)
 //      per node, on an item list in LDS that holds one set per trie depth of the current path.
 //      Earley steps are nests of short data-dependent loops; run on 64 lanes at once they pay for
 //      the longest trip count of every loop level at every step (measured: ~12,000 cycles per
 //      step per wavefront), so a single-lane walk per wavefront with many wavefronts in flight
-//      is the faster mapping on this hardware.  Grammar tables and the row's chart are staged
-//      in LDS once per block of 8 wavefronts.
+//      is the faster mapping on this hardware.  Grammar tables are staged in LDS once per block of
+//      8 wavefronts, the row's chart (when small) once per chunk.
 //   3. mask_fallback_kernel: chunks whose list outgrew LDS repeat the walk with the list in a
 //      global-memory arena.
 #include <hip/hip_runtime.h>
@@ -31,8 +32,8 @@ struct TV {
     const uint32_t *qinfo;
     const uint32_t *scan_off;
     const uint32_t *comp_off;
-    const uint16_t *delta;
-    const uint32_t *scan_list;
+    const uint32_t *delta;
+    const uint2 *scan_list;
     const uint16_t *comp_list;
     uint32_t N, ncls, end_base;
 };
@@ -67,11 +68,11 @@ __device__ __forceinline__ uint32_t stage_tables(const DeviceTables &D, uint8_t 
         uint32_t at[3];
 #pragma unroll
         for (int k = 0; k < 3; k++) { at[k] = off; copy16(smem + off, src[k], D.big_bytes[k], tid, nthreads); off += D.big_bytes[k]; }
-        tv.delta = reinterpret_cast<const uint16_t *>(smem + at[0]);
-        tv.scan_list = reinterpret_cast<const uint32_t *>(smem + at[1]);
+        tv.delta = reinterpret_cast<const uint32_t *>(smem + at[0]);
+        tv.scan_list = reinterpret_cast<const uint2 *>(smem + at[1]);
         tv.comp_list = reinterpret_cast<const uint16_t *>(smem + at[2]);
     } else {
-        tv.delta = D.delta; tv.scan_list = D.scan_list; tv.comp_list = D.comp_list;
+        tv.delta = D.delta; tv.scan_list = reinterpret_cast<const uint2 *>(D.scan_list); tv.comp_list = D.comp_list;
     }
     return off;
 }
@@ -128,27 +129,29 @@ __device__ __forceinline__ uint32_t add_advanced(const TV &T, S &st, uint32_t se
     }
 }
 
+// One DFA step: returns next state | flags of the next state << 16, or DFA_DEAD in the low half.
 __device__ __forceinline__ uint32_t dfa_next(const TV &T, uint32_t q, uint32_t byte, uint32_t cl) {
     const uint32_t info = T.qinfo[q];
-    if (info & QF_LITERAL) return (((info >> 8) & 0xFFu) == byte && (info & QF_CONT)) ? q + 1 : (uint32_t)DFA_DEAD;
+    if (info & QF_LITERAL) return (((info >> 8) & 0xFFu) == byte && (info & QF_CONT)) ? ((q + 1) | (info & 0xFFFF0000u)) : (uint32_t)DFA_DEAD;
     return T.delta[(info >> 16) * T.ncls + cl];
 }
 
 enum { STEP_ALIVE = 1, STEP_KERNEL = 2, STEP_OVERFLOW = 4 };
 
+template <class SoPtr, class ItPtr>
 struct Base {                  // the row's uploaded chart (LDS copy or global)
-    const uint32_t *so;        // set offsets, so[k] .. so[k+1]
-    const uint2 *it;           // items: x = item word, y = origin
+    SoPtr so;                  // set offsets, so[k] .. so[k+1]
+    ItPtr it;                  // items: x = item word, y = origin
     uint32_t m;                // number of sets; set m-1 is the current one
     uint32_t last_lo, last_hi; // so[m-1], so[m]
 };
+typedef Base<const uint32_t *, const uint2 *> BaseG;
 
 // One Earley byte step at trie depth d (1-based).  The source set is the row's current set for
 // d == 1, else the lane's set of depth d-1.  On entry cnt == st.start(d).
-template <class S>
-__device__ __forceinline__ int earley_step(const TV &T, const Base &B, S &st, int d, uint32_t byte, uint32_t &cnt) {
+template <class S, class BaseT>
+__device__ __forceinline__ int earley_step(const TV &T, const BaseT &B, S &st, int d, uint32_t byte, uint32_t cl, uint32_t &cnt) {
     const uint32_t nb = cnt;
-    const uint32_t cl = T.cls[byte];
     const uint32_t cur = B.m - 1 + (uint32_t)(d - 1);   // index of the source set
     uint32_t acc = ADD_OK;                               // AND of ok bits, OR of END bits
     const bool from_base = d == 1;
@@ -159,9 +162,9 @@ __device__ __forceinline__ int earley_step(const TV &T, const Base &B, S &st, in
         uint32_t w, o;
         if (from_base) { uint2 x = B.it[i]; w = x.x; o = x.y; } else st.get(i, w, o);
         if (w & IW_TERM) {
-            const uint32_t q2 = dfa_next(T, w >> 16, byte, cl);
+            const uint32_t nx = dfa_next(T, w >> 16, byte, cl);
+            const uint32_t q2 = nx & 0xFFFFu, f = nx >> 16;
             if (q2 == DFA_DEAD) continue;
-            const uint32_t f = T.qinfo[q2];
             uint32_t r = ADD_OK;
             if (f & QF_CONT) r = insert_unique(st, nb, cnt, (w & 0xFFFFu) | (q2 << 16), o) ? ADD_OK : 0;   // no longest match: keep matching ...
             if (r && (f & QF_ACCEPT)) r = add_advanced(T, st, nb, cnt, (w & IW_POS_MASK) + 1, o);        // ... and also finish here
@@ -171,8 +174,8 @@ __device__ __forceinline__ int earley_step(const TV &T, const Base &B, S &st, in
             const uint32_t Y = (w >> IW_NT_SHIFT) & IW_NT_MASK;
             const uint32_t k0 = T.scan_off[Y * T.ncls + cl], k1 = T.scan_off[Y * T.ncls + cl + 1];
             for (uint32_t e = k0; e < k1; e++) {
-                const uint32_t ent = T.scan_list[e];
-                const uint32_t f = T.qinfo[ent >> 16];
+                const uint2 ef = T.scan_list[e];
+                const uint32_t ent = ef.x, f = ef.y;
                 uint32_t r = ADD_OK;
                 if (f & QF_CONT) r = insert_unique(st, nb, cnt, ent, cur) ? ADD_OK : 0;
                 if (r && (f & QF_ACCEPT)) r = add_advanced(T, st, nb, cnt, (ent & IW_POS_MASK) + 1, cur);
@@ -221,8 +224,8 @@ __device__ __forceinline__ int earley_step(const TV &T, const Base &B, S &st, in
 // depth j+1.  Returns false on overflow; otherwise *bits_out holds the chunk's verdicts.
 // `want` marks the strings of the chunk that still need a verdict (the others are decided by the
 // token-mask cache); subtrees without such a string are skipped without a byte step.
-template <class S, class Anc, class Nodes>
-__device__ __forceinline__ bool walk_chunk(const DeviceTables &D, const TV &T, const Base &B, S &st, uint32_t chunk, uint32_t want,
+template <class S, class BaseT, class Anc, class Nodes>
+__device__ __forceinline__ bool walk_chunk(const DeviceTables &D, const TV &T, const BaseT &B, S &st, uint32_t chunk, uint32_t want,
                                            uint32_t begin, uint32_t end, Anc anc, Nodes node, uint32_t *bits_out) {
     uint32_t i = begin;
     const uint32_t rank0 = chunk * (uint32_t)D.chunk_ranks;
@@ -233,7 +236,7 @@ __device__ __forceinline__ bool walk_chunk(const DeviceTables &D, const TV &T, c
     if (d0 > S::max_depth) return false;
     for (int j = 0; j + 1 < d0; j++) {   // replay the path above the chunk's first node
         const TrieNode an = anc(j);
-        const int r = earley_step(T, B, st, j + 1, an.byte, cnt);
+        const int r = earley_step(T, B, st, j + 1, an.byte, an.cls, cnt);
         if (r & STEP_OVERFLOW) return false;
         if (!(r & STEP_KERNEL)) {        // that whole subtree is dead
             i = an.skip; cnt = st.start(j + 1);
@@ -253,7 +256,7 @@ __device__ __forceinline__ bool walk_chunk(const DeviceTables &D, const TV &T, c
         else {
             if (d > S::max_depth) return false;
             cnt = st.start(d);                           // forget the sets of the deeper path we came from
-            const int r = earley_step(T, B, st, d, nd.byte, cnt);
+            const int r = earley_step(T, B, st, d, nd.byte, nd.cls, cnt);
             if (r & STEP_OVERFLOW) return false;
             if (nd.has_string && (r & STEP_ALIVE)) bits |= 1u << rel;
             ni = (r & STEP_KERNEL) ? nxt : nd.skip;
@@ -310,16 +313,19 @@ __global__ __launch_bounds__(256) void cache_merge_kernel(MaskArgs a) {
         const uint32_t lane = threadIdx.x & 63;
         const uint32_t leader = (uint32_t)__ffsll((long long)b) - 1;
         uint32_t base = 0;
-        if (lane == leader) base = atomicAdd(&a.row_count[row], (uint32_t)__popcll(b));
+        if (lane == leader) base = atomicAdd(&a.counters[1], (uint32_t)__popcll(b));
         base = __shfl(base, leader);
-        if (want) a.work[(size_t)row * D.n_chunks + base + __popcll(b & ((1ull << lane) - 1ull))] = make_uint2(chunk, want);
+        if (want) {
+            const uint32_t begin = D.chunk_begin[chunk], n_nodes = D.chunk_end[chunk] - begin;
+            a.work[base + __popcll(b & ((1ull << lane) - 1ull))] = make_uint4(row | (n_nodes > 0xFFFFu ? 0xFFFF0000u : n_nodes << 16), chunk, want, begin);
+        }
     }
 }
 
 static const uint32_t BASE_LDS_BYTES = (BASE_SETS_LDS + 1) * 4 + BASE_ITEMS_LDS * 8;
 __host__ __device__ inline uint32_t wave_region_bytes(uint32_t cap) {
-    // prefetched nodes, ancestor nodes, item words, origins, set starts (uint16); a multiple of 16
-    return (WALK_NODES_LDS + CHUNK_ANC) * 16 + (cap * 8 + (FB_DEPTH_MAX + 2) * 2 + 15) / 16 * 16;
+    // prefetched nodes, ancestor nodes, the row's chart, item words, origins, set starts (uint16); a multiple of 16
+    return (WALK_NODES_LDS + CHUNK_ANC) * 16 + BASE_LDS_BYTES + (cap * 8 + (FB_DEPTH_MAX + 2) * 2 + 15) / 16 * 16;
 }
 
 struct ParentAnc {             // ancestor node at depth j+1 through the parent links
@@ -331,9 +337,9 @@ struct ParentAnc {             // ancestor node at depth j+1 through the parent 
     }
 };
 
-__device__ __forceinline__ Base global_base(const MaskArgs &a, uint32_t row) {
+__device__ __forceinline__ BaseG global_base(const MaskArgs &a, uint32_t row) {
     const RowChart rc = a.rows[row];
-    Base B;
+    BaseG B;
     B.so = a.set_off + rc.set_base;
     B.it = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
     B.m = rc.n_sets;
@@ -342,69 +348,72 @@ __device__ __forceinline__ Base global_base(const MaskArgs &a, uint32_t row) {
     return B;
 }
 
-// The parser walk: one wavefront per queued chunk of the block's row.
+// The parser walk.  Persistent blocks; every wavefront takes queued chunks g, g + stride, ...
 template <int MODE>
 __global__ __launch_bounds__(WALK_BLOCK) void mask_walk_kernel(MaskArgs a) {
     extern __shared__ __align__(16) uint8_t smem[];
     const DeviceTables &D = a.tab;
-    const uint32_t tid = threadIdx.x, row = blockIdx.y;
-    const uint32_t n_work = a.row_count[row];
-    if (blockIdx.x * WALK_WAVES >= n_work) return;      // uniform: the queue of this row is shorter
+    const uint32_t tid = threadIdx.x;
+    const uint32_t n_work = a.counters[1];
+    if (blockIdx.x * WALK_WAVES >= n_work) return;      // uniform
     TV T;
-    uint32_t off = stage_tables<MODE>(D, smem, T, tid, WALK_BLOCK);
-    // the row's chart: LDS copy when small
-    const RowChart rc = a.rows[row];
-    const uint32_t *g_so = a.set_off + rc.set_base;
-    const uint2 *g_it = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
-    const uint32_t n_items = g_so[rc.n_sets];
-    Base B;
-    B.m = rc.n_sets;
-    B.last_lo = g_so[rc.n_sets - 1];
-    B.last_hi = n_items;
-    if (rc.n_sets <= BASE_SETS_LDS && n_items <= BASE_ITEMS_LDS) {
-        uint32_t *l_so = reinterpret_cast<uint32_t *>(smem + off);
-        uint2 *l_it = reinterpret_cast<uint2 *>(smem + off + (BASE_SETS_LDS + 1) * 4);
-        for (uint32_t k = tid; k <= rc.n_sets; k += WALK_BLOCK) l_so[k] = g_so[k];
-        for (uint32_t k = tid; k < n_items; k += WALK_BLOCK) l_it[k] = g_it[k];
-        B.so = l_so; B.it = l_it;
-    } else { B.so = g_so; B.it = g_it; }
-    off += BASE_LDS_BYTES;
+    const uint32_t off = stage_tables<MODE>(D, smem, T, tid, WALK_BLOCK);
+    __syncthreads();                                     // the only block-wide barrier; below, wavefronts run on their own
     const uint32_t wave = tid >> 6, lane = tid & 63;
-    const uint32_t e = blockIdx.x * WALK_WAVES + wave;
     const uint32_t cap = (uint32_t)a.lane_cap;
     uint8_t *region = smem + off + wave * wave_region_bytes(cap);
     TrieNode *l_nodes = reinterpret_cast<TrieNode *>(region);
     TrieNode *l_anc = l_nodes + WALK_NODES_LDS;
-    uint32_t chunk = 0, want = 0, begin = 0, end = 0;
-    if (e < n_work) {                                    // all lanes pull the chunk's nodes and ancestors into LDS
-        const uint2 item = a.work[(size_t)row * D.n_chunks + e];
-        chunk = item.x; want = item.y;
-        begin = D.chunk_begin[chunk]; end = D.chunk_end[chunk];
-        for (uint32_t k = lane; k < end - begin && k < (uint32_t)WALK_NODES_LDS; k += 64) l_nodes[k] = D.nodes[begin + k];
-        if (lane < CHUNK_ANC) {
-            const uint32_t ai = D.chunk_anc[(size_t)chunk * CHUNK_ANC + lane];   // unused slots hold node 0
-            l_anc[lane] = D.nodes[ai];
-        }
-    }
-    __syncthreads();
-    if (e >= n_work || lane != 0) return;
+    uint32_t *l_so = reinterpret_cast<uint32_t *>(region + (WALK_NODES_LDS + CHUNK_ANC) * 16);
+    uint2 *l_it = reinterpret_cast<uint2 *>(l_so + BASE_SETS_LDS + 1);
     WaveLdsStore st;
-    st.pq = reinterpret_cast<uint32_t *>(region + (WALK_NODES_LDS + CHUNK_ANC) * 16);
+    st.pq = reinterpret_cast<uint32_t *>(l_it + BASE_ITEMS_LDS);
     st.org = st.pq + cap;
     st.ss = reinterpret_cast<uint16_t *>(st.org + cap);
     st.cap = cap;
-    const int d0 = l_nodes[0].depth;
-    ParentAnc deep{D.nodes, D.parent, begin, d0};
-    uint32_t bits = 0;
-    const bool ok = cap > 0 && walk_chunk(D, T, B, st, chunk, want, begin, end,
-        [&](int j) { return d0 - 1 <= CHUNK_ANC ? l_anc[j] : deep(j); },
-        [&](uint32_t i) { return i - begin < (uint32_t)WALK_NODES_LDS ? l_nodes[i - begin] : D.nodes[i]; }, &bits);
-    if (!ok) {
-        const uint32_t slot = atomicAdd(&a.counters[0], 1u);
-        if (slot < a.overflow_cap) a.overflow_list[slot] = make_uint4(row, chunk, want, 0);
-        return;
+    for (uint32_t g = blockIdx.x * WALK_WAVES + wave; g < n_work; g += gridDim.x * WALK_WAVES) {
+        const uint4 item = a.work[g];                   // row | node count << 16, chunk, undecided strings, first node
+        const uint32_t row = item.x & 0xFFFFu, n_nodes = item.x >> 16, chunk = item.y, want = item.z, begin = item.w;
+        const RowChart rc = a.rows[row];
+        const uint32_t *g_so = a.set_off + rc.set_base;
+        const uint2 *g_it = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
+        const bool base_fits = rc.n_sets <= BASE_SETS_LDS && rc.n_items <= BASE_ITEMS_LDS;
+        // all 64 lanes pull the chunk's nodes, the ancestors of its first node and the row's chart into LDS
+        if (n_nodes <= (uint32_t)WALK_NODES_LDS)
+            for (uint32_t k = lane; k < n_nodes; k += 64) l_nodes[k] = D.nodes[begin + k];
+        if (lane < CHUNK_ANC) l_anc[lane] = D.chunk_anc[(size_t)chunk * CHUNK_ANC + lane];
+        if (base_fits) {
+            for (uint32_t k = lane; k <= rc.n_sets; k += 64) l_so[k] = g_so[k];
+            for (uint32_t k = lane; k < rc.n_items; k += 64) l_it[k] = g_it[k];
+        }
+        // lane 0 reads what the other lanes of its own wavefront wrote: LDS serves one wavefront's
+        // accesses in issue order; the fences keep the compiler from moving accesses across
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (lane == 0) {
+            uint32_t bits = 0;
+            bool ok = cap > 0 && n_nodes <= (uint32_t)WALK_NODES_LDS && l_nodes[0].depth - 1 <= CHUNK_ANC;
+            if (ok) {
+                auto anc = [&](int j) { return l_anc[j]; };
+                auto node = [&](uint32_t i) { return l_nodes[i - begin]; };
+                if (base_fits) {
+                    const Base<const uint32_t *, const uint2 *> B{l_so, l_it, rc.n_sets, l_so[rc.n_sets - 1], rc.n_items};
+                    ok = walk_chunk(D, T, B, st, chunk, want, begin, begin + n_nodes, anc, node, &bits);
+                } else {
+                    const Base<const uint32_t *, const uint2 *> B{g_so, g_it, rc.n_sets, g_so[rc.n_sets - 1], rc.n_items};
+                    ok = walk_chunk(D, T, B, st, chunk, want, begin, begin + n_nodes, anc, node, &bits);
+                }
+            }
+            if (!ok) {
+                const uint32_t slot = atomicAdd(&a.counters[0], 1u);
+                if (slot < a.overflow_cap) a.overflow_list[slot] = make_uint4(row, chunk, want, 0);
+            } else or_bits(D, a.rank_mask, row, chunk, bits & want);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the next round overwrites the staged data
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
-    or_bits(D, a.rank_mask, row, chunk, bits & want);
 }
 
 // Fallback: one lane per chunk that outgrew LDS, item list in a global-memory arena.
@@ -418,7 +427,7 @@ __global__ __launch_bounds__(64) void mask_fallback_kernel(MaskArgs a) {
     GlobalStore st{a.fb_items + gid, a.fb_set_start + gid, (uint32_t)a.fb_cap};
     for (uint32_t e = gid; e < n; e += FB3_LANES) {
         const uint4 ent = a.overflow_list[e];
-        const Base B = global_base(a, ent.x);
+        const BaseG B = global_base(a, ent.x);
         const uint32_t begin = D.chunk_begin[ent.y], end = D.chunk_end[ent.y];
         ParentAnc anc{D.nodes, D.parent, begin, D.nodes[begin].depth};
         uint32_t bits = 0;
@@ -511,9 +520,12 @@ hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s) {
     hipLaunchKernelGGL(cache_merge_kernel, grid, dim3(256), 0, s, a);
     return hipGetLastError();
 }
+uint32_t walk_lds_bytes(const DeviceTables &t, int mode, int lane_cap) {
+    return table_bytes(t, mode) + WALK_WAVES * wave_region_bytes((uint32_t)lane_cap);
+}
 hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s) {
-    dim3 grid((a.tab.n_chunks + WALK_WAVES - 1) / WALK_WAVES, a.batch);
-    const uint32_t lds = table_bytes(a.tab, a.mode) + BASE_LDS_BYTES + WALK_WAVES * wave_region_bytes((uint32_t)a.lane_cap);
+    const uint32_t lds = walk_lds_bytes(a.tab, a.mode, a.lane_cap);
+    dim3 grid(a.walk_blocks);
     if (a.mode == 0) hipLaunchKernelGGL(mask_walk_kernel<0>, grid, dim3(WALK_BLOCK), lds, s, a);
     else if (a.mode == 1) hipLaunchKernelGGL(mask_walk_kernel<1>, grid, dim3(WALK_BLOCK), lds, s, a);
     else hipLaunchKernelGGL(mask_walk_kernel<2>, grid, dim3(WALK_BLOCK), lds, s, a);

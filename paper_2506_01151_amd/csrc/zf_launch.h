@@ -25,9 +25,8 @@ struct MaskArgs {
     const uint32_t *entries;   // shared array of token-mask-cache rows (see RowChart)
     uint32_t *rank_mask;       // [batch][Wr] verdicts in trie (rank) order
     uint32_t *out_mask;        // [batch][W] verdicts in token-id order
-    uint32_t *counters;        // [0] chunks passed to the fallback, [2] chunks nobody could resolve
-    uint32_t *row_count;       // [batch] length of each row's queue of chunks that need the parser walk
-    uint2 *work;               // [batch][n_chunks] (chunk, undecided strings) queue per row
+    uint32_t *counters;        // [0] chunks passed to the fallback, [1] length of the work queue, [2] chunks nobody could resolve
+    uint4 *work;               // queue of (row, chunk, undecided strings, -) that need the parser walk
     uint4 *overflow_list;      // (row, chunk, undecided strings, -) for the fallback
     uint32_t overflow_cap;
     uint2 *fb_items;           // [FB3_ITEMS_PER_LANE][FB3_LANES] interleaved
@@ -35,10 +34,12 @@ struct MaskArgs {
     int32_t batch;
     int32_t lane_cap;          // item budget of a walking wavefront
     int32_t fb_cap;            // item budget of a fallback lane (<= FB3_ITEMS_PER_LANE)
+    int32_t walk_blocks;       // blocks of the persistent walk grid (what the chip holds at once)
     int32_t mode;              // 0: all tables staged in LDS, 1: the small ones only, 2: none
 };
 
 int choose_table_mode(const DeviceTables &t);
+uint32_t walk_lds_bytes(const DeviceTables &t, int mode, int lane_cap);   // dynamic LDS of one block of the walk kernel
 hipError_t prepare_kernels();   // one-time function attributes (dynamic LDS above 64 KB)
 hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s);
