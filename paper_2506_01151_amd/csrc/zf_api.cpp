@@ -442,14 +442,14 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     a.counters = d->d_counters;
     a.work = d->d_work;
     a.overflow_list = d->d_overflow;
-    a.mode = d->mode;
-    a.walk_blocks = d->walk_blocks;
-    a.fb_cap = e->opt.fallback_item_cap;
     a.overflow_cap = (uint32_t)d->overflow_cap;
     a.fb_items = d->d_fb_items;
     a.fb_set_start = d->d_fb_ss;
     a.batch = batch;
     a.lane_cap = e->opt.lane_item_cap;
+    a.fb_cap = e->opt.fallback_item_cap;
+    a.mode = d->mode;
+    a.walk_blocks = d->walk_blocks;
     HIP_TRY(hipMemsetAsync(d->d_counters, 0, 16, stream));
     const bool prof = d->profiling;
     if (d->tab.n_chunks > 0) HIP_TRY(launch_cache_merge(a, stream));

@@ -282,9 +282,11 @@ __device__ __forceinline__ void store_bits(const DeviceTables &D, uint32_t *rank
     else if (D.chunk_ranks == 16) reinterpret_cast<uint16_t *>(rowp)[chunk] = (uint16_t)bits;
     else rowp[chunk] = (uint8_t)bits;
 }
-// the chunk's bits are owned by one lane at a time (kernels are stream ordered): plain read-modify-write
+// several walks may add verdicts to the same word of the rank-ordered bitmap: atomic OR
 __device__ __forceinline__ void or_bits(const DeviceTables &D, uint32_t *rank_mask, uint32_t row, uint32_t chunk, uint32_t bits) {
-    if (bits) store_bits(D, rank_mask, row, chunk, bits | load_bits(D, rank_mask + (size_t)row * D.Wr, chunk));
+    if (!bits) return;
+    const uint32_t byte_off = chunk * ((uint32_t)D.chunk_ranks >> 3);
+    atomicOr(rank_mask + (size_t)row * D.Wr + (byte_off >> 2), bits << ((byte_off & 3u) * 8u));
 }
 
 // Token-mask cache (Section 4.3): merge the cached bitsets of every item of the row's current set,
