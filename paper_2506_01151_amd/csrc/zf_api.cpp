@@ -104,7 +104,7 @@ int setup_device(zf_engine *e) {
         const uint32_t lds = walk_lds_bytes(T, d->mode, e->opt.lane_item_cap);
         if (lds > 160u * 1024u) return fail(ZF_ERR_INVALID_ARG, "lane_item_cap and the grammar tables do not fit the 160 KB of LDS");
         int per_cu = (int)(160u * 1024u / lds);
-        if (per_cu > 4) per_cu = 4;      // 4 blocks x 8 wavefronts = 8 wavefronts per SIMD
+        if (per_cu > 32 / WALK_WAVES) per_cu = 32 / WALK_WAVES;      // 32 wavefronts per CU = 8 per SIMD
         d->walk_blocks = std::max(1, cus) * std::max(1, per_cu);
     }
     HIP_TRY(hipMalloc((void **)&d->d_counters, 16));

@@ -9,14 +9,15 @@
 //      at once; chunks that hold strings which need the parser go to the work queue.
 //   2. mask_walk_kernel: a persistent grid (as many blocks as the chip holds at once) whose
 //      wavefronts take queued chunks in turn.  The 64 lanes first pull the chunk's trie
-//      nodes and the ancestors of its first node into LDS; then ONE lane replays the ancestors and
-//      walks the nodes, one Earley byte step (Scan + Complete with tabulated Predict, Section 3.2)
-//      per node, on an item list in LDS that holds one set per trie depth of the current path.
-//      Earley steps are nests of short data-dependent loops; run on 64 lanes at once they pay for
-//      the longest trip count of every loop level at every step (measured: ~12,000 cycles per
-//      step per wavefront), so a single-lane walk per wavefront with many wavefronts in flight
-//      is the faster mapping on this hardware.  Grammar tables are staged in LDS once per block of
-//      8 wavefronts, the row's chart (when small) once per chunk.
+//      nodes, the ancestors of its first node and the row's chart into LDS; then the wavefront
+//      replays the ancestors and walks the nodes, one Earley byte step (Scan + Complete with
+//      tabulated Predict, Section 3.2) per node, on an item list in LDS that holds one set per
+//      trie depth of the current path.  The step is wavefront-cooperative with uniform control
+//      flow (wave_step): items of a set are spread over the lanes, the set under construction is
+//      held in registers, duplicate tests are ballots.  (Giving every lane its own chunk was
+//      measured first: the nests of short data-dependent loops of an Earley step then cost
+//      ~12,000 cycles per step per wavefront because every loop level runs for its longest
+//      trip count over the 64 lanes.)  Grammar tables are staged in LDS once per block.
 //   3. mask_fallback_kernel: chunks whose list outgrew LDS repeat the walk with the list in a
 //      global-memory arena.
 #include <hip/hip_runtime.h>
@@ -84,7 +85,7 @@ struct WaveLdsStore {          // walk kernel: the wavefront's list in LDS, used
     uint32_t *org;
     uint16_t *ss;
     uint32_t cap;
-    static constexpr int max_depth = FB_DEPTH_MAX;
+    static constexpr int max_depth = WALK_DEPTH_MAX;
     __device__ __forceinline__ void get(uint32_t i, uint32_t &p, uint32_t &o) const { p = pq[i]; o = org[i]; }
     __device__ __forceinline__ void put(uint32_t i, uint32_t p, uint32_t o) { pq[i] = p; org[i] = o; }
     __device__ __forceinline__ uint32_t start(int d) const { return ss[d]; }
@@ -157,6 +158,22 @@ __device__ __forceinline__ int earley_step(const TV &T, const BaseT &B, S &st, i
     const bool from_base = d == 1;
     const uint32_t sb = from_base ? B.last_lo : st.start(d - 1);
     const uint32_t se = from_base ? B.last_hi : nb;
+    if (se - sb == 1) {   // the common case inside a terminal: one item, the DFA moves on and does not accept
+        uint32_t w, o;
+        if (from_base) { uint2 x = B.it[sb]; w = x.x; o = x.y; } else st.get(sb, w, o);
+        if (w & IW_TERM) {
+            const uint32_t nx = dfa_next(T, w >> 16, byte, cl);
+            const uint32_t q2 = nx & 0xFFFFu;
+            if (q2 == DFA_DEAD) { st.set_start(d + 1, nb); return 0; }
+            if (!((nx >> 16) & QF_ACCEPT)) {
+                if (nb >= st.cap) return STEP_OVERFLOW;
+                st.put(nb, (w & 0xFFFFu) | (q2 << 16), o);
+                cnt = nb + 1;
+                st.set_start(d + 1, cnt);
+                return STEP_ALIVE | STEP_KERNEL;
+            }
+        }
+    }
     // Scan
     for (uint32_t i = sb; i < se; i++) {
         uint32_t w, o;
@@ -220,12 +237,114 @@ __device__ __forceinline__ int earley_step(const TV &T, const BaseT &B, S &st, i
     return STEP_ALIVE | (cnt > nb ? STEP_KERNEL : 0);
 }
 
+// The same byte step done by a whole wavefront with uniform control flow.  All 64 lanes call it
+// with identical arguments.  Lane i loads source item i, the DFA transitions of all items run in
+// parallel, the set under construction lives in registers (lane j holds new item j) so that the
+// duplicate test is one compare + ballot, and Complete loads S[origin] 64 items at a time.  Sets
+// of more than 64 items are reported as overflow (the fallback handles them).
+template <class BaseT>
+__device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsStore &st, int d, uint32_t byte, uint32_t cl, uint32_t &cnt, uint32_t lane) {
+    const uint32_t nb = cnt;
+    const uint32_t cur = B.m - 1 + (uint32_t)(d - 1);
+    const bool from_base = d == 1;
+    const uint32_t sb = from_base ? B.last_lo : st.start(d - 1);
+    const uint32_t ns = (from_base ? B.last_hi : nb) - sb;
+    if (ns > 64) return STEP_OVERFLOW;
+    uint32_t sw = IW_END, so = 0;                        // lanes beyond the set hold an inert item
+    if (lane < ns) { if (from_base) { const uint2 x = B.it[sb + lane]; sw = x.x; so = x.y; } else st.get(sb + lane, sw, so); }
+    uint32_t nw = 0, no = 0, nnew = 0;                   // the set under construction, one item per lane
+    bool saw_end = false;
+    auto insert = [&](uint32_t w, uint32_t o) -> bool {  // uniform arguments
+        if (__ballot(lane < nnew && nw == w && no == o)) return true;
+        if (nnew >= 64 || nb + nnew >= st.cap) return false;
+        if (lane == nnew) { nw = w; no = o; }
+        nnew++;
+        return true;
+    };
+    auto advance = [&](uint32_t p, uint32_t o) -> bool { // dot arrives at p: skip nullable nonterminals, canonical END item
+        for (;;) {
+            const uint32_t w = T.advpq[p];
+            if (!insert(w, o)) return false;
+            if (w & IW_END) { saw_end = true; return true; }
+            if ((w & IW_TERM) || !(w & IW_NT_NULLABLE)) return true;
+            p++;
+        }
+    };
+    // Scan, terminal items: all DFA steps at once, then the survivors one after the other
+    uint32_t nx = DFA_DEAD;
+    if (sw & IW_TERM) nx = dfa_next(T, sw >> 16, byte, cl);
+    unsigned long long m = __ballot((nx & 0xFFFFu) != DFA_DEAD);
+    while (m) {
+        const int l = __ffsll((long long)m) - 1;
+        m &= m - 1;
+        const uint32_t lw = __builtin_amdgcn_readlane(sw, l), lo = __builtin_amdgcn_readlane(so, l), lnx = __builtin_amdgcn_readlane(nx, l);
+        if ((lnx >> 16) & QF_CONT) if (!insert((lw & 0xFFFFu) | (lnx << 16), lo)) return STEP_OVERFLOW;   // no longest match: keep matching ...
+        if ((lnx >> 16) & QF_ACCEPT) if (!advance((lw & IW_POS_MASK) + 1, lo)) return STEP_OVERFLOW;      // ... and also finish here
+    }
+    // Scan, items that wait for a nonterminal Y: the tabulated first steps of every terminal that can begin Y
+    m = __ballot(!(sw & (IW_TERM | IW_END)));
+    while (m) {
+        const int l = __ffsll((long long)m) - 1;
+        m &= m - 1;
+        const uint32_t Y = (__builtin_amdgcn_readlane(sw, l) >> IW_NT_SHIFT) & IW_NT_MASK;
+        const uint32_t k0 = T.scan_off[Y * T.ncls + cl], k1 = T.scan_off[Y * T.ncls + cl + 1];
+        for (uint32_t e0 = k0; e0 < k1; e0 += 64) {
+            uint2 ef = make_uint2(0, 0);
+            if (e0 + lane < k1) ef = T.scan_list[e0 + lane];
+            const uint32_t n_e = k1 - e0 < 64 ? k1 - e0 : 64;
+            for (uint32_t t = 0; t < n_e; t++) {
+                const uint32_t ent = __builtin_amdgcn_readlane(ef.x, t), f = __builtin_amdgcn_readlane(ef.y, t);
+                if (f & QF_CONT) if (!insert(ent, cur)) return STEP_OVERFLOW;
+                if (f & QF_ACCEPT) if (!advance((ent & IW_POS_MASK) + 1, cur)) return STEP_OVERFLOW;
+            }
+        }
+    }
+    if (saw_end) {
+        // Complete: new items are visited in order; completing may append more
+        for (uint32_t i = 0; i < nnew; i++) {
+            const uint32_t w = __builtin_amdgcn_readlane(nw, i);
+            if (!(w & IW_END)) continue;
+            const uint32_t X = (w & IW_POS_MASK) - T.end_base;
+            if (X == T.N - 1) continue;                 // the start rule is complete: the prefix is a sentence
+            const uint32_t o = __builtin_amdgcn_readlane(no, i);
+            const bool in_base = o < B.m;
+            uint32_t jb, je;
+            if (in_base) { jb = B.so[o]; je = B.so[o + 1]; }
+            else { const int dj = (int)(o - (B.m - 1)); jb = st.start(dj); je = st.start(dj + 1); }
+            for (uint32_t j0 = jb; j0 < je; j0 += 64) {
+                uint32_t yw = IW_END, yo = 0;
+                if (j0 + lane < je) { if (in_base) { const uint2 y = B.it[j0 + lane]; yw = y.x; yo = y.y; } else st.get(j0 + lane, yw, yo); }
+                const bool nt = !(yw & (IW_TERM | IW_END));
+                const uint32_t Y = (yw >> IW_NT_SHIFT) & IW_NT_MASK;
+                uint32_t c0 = 0, c1 = 0;
+                if (nt) { c0 = T.comp_off[Y * T.N + X]; c1 = T.comp_off[Y * T.N + X + 1]; }
+                unsigned long long mm = __ballot(nt && (c1 > c0 || Y == X));
+                while (mm) {
+                    const int l = __ffsll((long long)mm) - 1;
+                    mm &= mm - 1;
+                    const uint32_t lc0 = __builtin_amdgcn_readlane(c0, l), lc1 = __builtin_amdgcn_readlane(c1, l);
+                    for (uint32_t e = lc0; e < lc1; e++) if (!advance(T.comp_list[e], o)) return STEP_OVERFLOW;
+                    if (__builtin_amdgcn_readlane(Y, l) == X)
+                        if (!advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l))) return STEP_OVERFLOW;
+                }
+            }
+        }
+    }
+    // completed items are needed only while their own set is processed: store the others
+    const bool keep = lane < nnew && !(nw & IW_END);
+    const unsigned long long kb = __ballot(keep);
+    if (keep) st.put(nb + __popcll(kb & ((1ull << lane) - 1ull)), nw, no);
+    cnt = nb + (uint32_t)__popcll(kb);
+    st.set_start(d + 1, cnt);
+    return (nnew ? STEP_ALIVE : 0) | (kb ? STEP_KERNEL : 0);
+}
+
 // Walk the nodes of one chunk.  anc(j) gives the node index of the first node's ancestor at
 // depth j+1.  Returns false on overflow; otherwise *bits_out holds the chunk's verdicts.
 // `want` marks the strings of the chunk that still need a verdict (the others are decided by the
 // token-mask cache); subtrees without such a string are skipped without a byte step.
-template <class S, class BaseT, class Anc, class Nodes>
-__device__ __forceinline__ bool walk_chunk(const DeviceTables &D, const TV &T, const BaseT &B, S &st, uint32_t chunk, uint32_t want,
+template <class S, class Step, class Anc, class Nodes>
+__device__ __forceinline__ bool walk_chunk(const DeviceTables &D, S &st, Step step, uint32_t chunk, uint32_t want,
                                            uint32_t begin, uint32_t end, Anc anc, Nodes node, uint32_t *bits_out) {
     uint32_t i = begin;
     const uint32_t rank0 = chunk * (uint32_t)D.chunk_ranks;
@@ -236,7 +355,7 @@ __device__ __forceinline__ bool walk_chunk(const DeviceTables &D, const TV &T, c
     if (d0 > S::max_depth) return false;
     for (int j = 0; j + 1 < d0; j++) {   // replay the path above the chunk's first node
         const TrieNode an = anc(j);
-        const int r = earley_step(T, B, st, j + 1, an.byte, an.cls, cnt);
+        const int r = step(j + 1, an.byte, an.cls, cnt);
         if (r & STEP_OVERFLOW) return false;
         if (!(r & STEP_KERNEL)) {        // that whole subtree is dead
             i = an.skip; cnt = st.start(j + 1);
@@ -256,7 +375,7 @@ __device__ __forceinline__ bool walk_chunk(const DeviceTables &D, const TV &T, c
         else {
             if (d > S::max_depth) return false;
             cnt = st.start(d);                           // forget the sets of the deeper path we came from
-            const int r = earley_step(T, B, st, d, nd.byte, nd.cls, cnt);
+            const int r = step(d, nd.byte, nd.cls, cnt);
             if (r & STEP_OVERFLOW) return false;
             if (nd.has_string && (r & STEP_ALIVE)) bits |= 1u << rel;
             ni = (r & STEP_KERNEL) ? nxt : nd.skip;
@@ -327,7 +446,7 @@ __global__ __launch_bounds__(256) void cache_merge_kernel(MaskArgs a) {
 static const uint32_t BASE_LDS_BYTES = (BASE_SETS_LDS + 1) * 4 + BASE_ITEMS_LDS * 8;
 __host__ __device__ inline uint32_t wave_region_bytes(uint32_t cap) {
     // prefetched nodes, ancestor nodes, the row's chart, item words, origins, set starts (uint16); a multiple of 16
-    return (WALK_NODES_LDS + CHUNK_ANC) * 16 + BASE_LDS_BYTES + (cap * 8 + (FB_DEPTH_MAX + 2) * 2 + 15) / 16 * 16;
+    return (WALK_NODES_LDS + CHUNK_ANC) * 16 + BASE_LDS_BYTES + (cap * 8 + (WALK_DEPTH_MAX + 2) * 2 + 15) / 16 * 16;
 }
 
 struct ParentAnc {             // ancestor node at depth j+1 through the parent links
@@ -352,7 +471,7 @@ __device__ __forceinline__ BaseG global_base(const MaskArgs &a, uint32_t row) {
 
 // The parser walk.  Persistent blocks; every wavefront takes queued chunks g, g + stride, ...
 template <int MODE>
-__global__ __launch_bounds__(WALK_BLOCK) void mask_walk_kernel(MaskArgs a) {
+__global__ __launch_bounds__(WALK_BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8))) void mask_walk_kernel(MaskArgs a) {
     extern __shared__ __align__(16) uint8_t smem[];
     const DeviceTables &D = a.tab;
     const uint32_t tid = threadIdx.x;
@@ -393,7 +512,7 @@ __global__ __launch_bounds__(WALK_BLOCK) void mask_walk_kernel(MaskArgs a) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        if (lane == 0) {
+        {
             uint32_t bits = 0;
             bool ok = cap > 0 && n_nodes <= (uint32_t)WALK_NODES_LDS && l_nodes[0].depth - 1 <= CHUNK_ANC;
             if (ok) {
@@ -401,16 +520,20 @@ __global__ __launch_bounds__(WALK_BLOCK) void mask_walk_kernel(MaskArgs a) {
                 auto node = [&](uint32_t i) { return l_nodes[i - begin]; };
                 if (base_fits) {
                     const Base<const uint32_t *, const uint2 *> B{l_so, l_it, rc.n_sets, l_so[rc.n_sets - 1], rc.n_items};
-                    ok = walk_chunk(D, T, B, st, chunk, want, begin, begin + n_nodes, anc, node, &bits);
+                    ok = walk_chunk(D, st, [&](int d, uint32_t byte, uint32_t cl, uint32_t &cnt) { return wave_step(T, B, st, d, byte, cl, cnt, lane); },
+                                    chunk, want, begin, begin + n_nodes, anc, node, &bits);
                 } else {
                     const Base<const uint32_t *, const uint2 *> B{g_so, g_it, rc.n_sets, g_so[rc.n_sets - 1], rc.n_items};
-                    ok = walk_chunk(D, T, B, st, chunk, want, begin, begin + n_nodes, anc, node, &bits);
+                    ok = walk_chunk(D, st, [&](int d, uint32_t byte, uint32_t cl, uint32_t &cnt) { return wave_step(T, B, st, d, byte, cl, cnt, lane); },
+                                    chunk, want, begin, begin + n_nodes, anc, node, &bits);
                 }
             }
-            if (!ok) {
-                const uint32_t slot = atomicAdd(&a.counters[0], 1u);
-                if (slot < a.overflow_cap) a.overflow_list[slot] = make_uint4(row, chunk, want, 0);
-            } else or_bits(D, a.rank_mask, row, chunk, bits & want);
+            if (lane == 0) {
+                if (!ok) {
+                    const uint32_t slot = atomicAdd(&a.counters[0], 1u);
+                    if (slot < a.overflow_cap) a.overflow_list[slot] = make_uint4(row, chunk, want, 0);
+                } else or_bits(D, a.rank_mask, row, chunk, bits & want);
+            }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the next round overwrites the staged data
         __builtin_amdgcn_wave_barrier();
@@ -433,7 +556,8 @@ __global__ __launch_bounds__(64) void mask_fallback_kernel(MaskArgs a) {
         const uint32_t begin = D.chunk_begin[ent.y], end = D.chunk_end[ent.y];
         ParentAnc anc{D.nodes, D.parent, begin, D.nodes[begin].depth};
         uint32_t bits = 0;
-        if (!walk_chunk(D, T, B, st, ent.y, ent.z, begin, end, anc, [&](uint32_t i) { return D.nodes[i]; }, &bits)) { atomicAdd(&a.counters[2], 1u); continue; }
+        if (!walk_chunk(D, st, [&](int d, uint32_t byte, uint32_t cl, uint32_t &cnt) { return earley_step(T, B, st, d, byte, cl, cnt); },
+                        ent.y, ent.z, begin, end, anc, [&](uint32_t i) { return D.nodes[i]; }, &bits)) { atomicAdd(&a.counters[2], 1u); continue; }
         or_bits(D, a.rank_mask, ent.x, ent.y, bits & ent.z);
     }
 }

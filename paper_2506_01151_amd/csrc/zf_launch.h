@@ -6,12 +6,13 @@
 namespace zf {
 
 static const int LANE_CAP_MAX = 1024;      // upper limit of the walk kernel's item budget per wavefront (LDS)
-static const int LANE_CAP_DEFAULT = 256;
+static const int LANE_CAP_DEFAULT = 64;
 static const int WALK_WAVES = 8;           // wavefronts (= queued chunks) per block of the walk kernel; they share the staged tables
 static const int WALK_BLOCK = WALK_WAVES * 64;
-static const int WALK_NODES_LDS = 144;     // trie nodes of a chunk prefetched into LDS (8 strings x 16 bytes fit; longer ranges read L2)
-static const int BASE_SETS_LDS = 63;       // a row's chart is staged into LDS when it has at most this many sets ...
-static const int BASE_ITEMS_LDS = 192;     // ... and items
+static const int WALK_NODES_LDS = 80;      // trie nodes of a chunk the walk kernel stages in LDS (bigger chunks go to the fallback)
+static const int WALK_DEPTH_MAX = 32;      // trie depth the walk kernel follows (deeper paths go to the fallback)
+static const int BASE_SETS_LDS = 31;       // a row's chart is staged into LDS when it has at most this many sets ...
+static const int BASE_ITEMS_LDS = 96;      // ... and items
 static const int TABLE_LDS_BUDGET = 56 * 1024;
 static const int FB_DEPTH_MAX = 256;
 static const int FB3_LANES = 2048;         // lanes of the fallback grid
