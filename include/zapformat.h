@@ -67,11 +67,11 @@ typedef struct {
 typedef struct {
     int32_t pruning;       /* 1 = ZapFormat Compact phase on (Section 4.2), 0 = keep every item */
     int32_t lane_item_cap; /* Earley item budget (LDS) of one walking wavefront of the mask kernel,
-                              0 = default (256); what does not fit goes to the exact fallback pass */
+                              0 = automatic (128, more when the current sets are large); what does not fit goes to the exact fallback pass */
     int32_t device;        /* HIP device ordinal, or -1 = host tables only (no mask calls) */
     int32_t chunk_strings; /* vocabulary strings walked by one lane: 8, 16 or 32; 0 = default */
-    int32_t fallback_item_cap; /* item budget of a fallback lane (global memory), 0 = default
-                                  (16384); tests set it low to provoke ZF_ERR_OVERFLOW */
+    int32_t fallback_item_cap; /* item budget of a fallback wavefront (global memory), 0 = default
+                                  (65536); tests set it low to provoke ZF_ERR_OVERFLOW */
     int32_t disable_token_mask_cache; /* 1 = every token goes through the parser walk (Section 4.3
                                   optimisation off); masks are identical either way */
 } zf_options;

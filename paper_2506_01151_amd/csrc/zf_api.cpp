@@ -24,7 +24,7 @@ struct DeviceSide {
     uint32_t *d_rank_mask = nullptr; size_t rank_cap = 0;
     uint4 *d_overflow = nullptr; size_t overflow_cap = 0;
     uint4 *d_work = nullptr;
-    int walk_blocks = 256;
+    int cus = 256;
     int mode = 2;
     uint32_t *d_counters = nullptr;
     uint32_t *h_counters = nullptr;      // pinned
@@ -98,19 +98,13 @@ int setup_device(zf_engine *e) {
     T.Wr = tr.Wr;
     d->mode = choose_table_mode(T);
     HIP_TRY(prepare_kernels());
-    {   // the persistent walk grid: as many blocks as fit on the chip at once (LDS is the limit)
-        int cus = 0;
-        HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, d->device));
-        const uint32_t lds = walk_lds_bytes(T, d->mode, e->opt.lane_item_cap);
-        if (lds > 160u * 1024u) return fail(ZF_ERR_INVALID_ARG, "lane_item_cap and the grammar tables do not fit the 160 KB of LDS");
-        int per_cu = (int)(160u * 1024u / lds);
-        if (per_cu > 32 / WALK_WAVES) per_cu = 32 / WALK_WAVES;      // 32 wavefronts per CU = 8 per SIMD
-        d->walk_blocks = std::max(1, cus) * std::max(1, per_cu);
-    }
+    HIP_TRY(hipDeviceGetAttribute(&d->cus, hipDeviceAttributeMultiprocessorCount, d->device));
+    if (walk_lds_bytes(T, d->mode, e->opt.lane_item_cap) > 160u * 1024u)
+        return fail(ZF_ERR_INVALID_ARG, "lane_item_cap and the grammar tables do not fit the 160 KB of LDS");
     HIP_TRY(hipMalloc((void **)&d->d_counters, 16));
     HIP_TRY(hipHostMalloc((void **)&d->h_counters, 16, hipHostMallocDefault));
-    HIP_TRY(hipMalloc((void **)&d->d_fb_items, (size_t)FB3_ITEMS_PER_LANE * FB3_LANES * sizeof(uint2)));
-    HIP_TRY(hipMalloc((void **)&d->d_fb_ss, (size_t)(FB_DEPTH_MAX + 2) * FB3_LANES * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc((void **)&d->d_fb_items, (size_t)FB_ITEMS_PER_WAVE * FB_WAVES * sizeof(uint2)));
+    HIP_TRY(hipMalloc((void **)&d->d_fb_ss, (size_t)(FB_DEPTH_MAX + 2) * FB_WAVES * sizeof(uint32_t)));
     return ZF_OK;
 }
 
@@ -184,9 +178,10 @@ int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_option
     zf_engine *e = new (std::nothrow) zf_engine();
     if (!e) return fail(ZF_ERR_OOM, "out of memory");
     e->opt = opt ? *opt : zf_options{1, 0, 0, 0, 0, 0};
+    e->lane_cap_auto = e->opt.lane_item_cap <= 0;
     if (e->opt.lane_item_cap <= 0) e->opt.lane_item_cap = LANE_CAP_DEFAULT;
     if (e->opt.lane_item_cap > LANE_CAP_MAX) e->opt.lane_item_cap = LANE_CAP_MAX;
-    if (e->opt.fallback_item_cap <= 0 || e->opt.fallback_item_cap > FB3_ITEMS_PER_LANE) e->opt.fallback_item_cap = FB3_ITEMS_PER_LANE;
+    if (e->opt.fallback_item_cap <= 0 || e->opt.fallback_item_cap > FB_ITEMS_PER_WAVE) e->opt.fallback_item_cap = FB_ITEMS_PER_WAVE;
     if (e->opt.chunk_strings != 8 && e->opt.chunk_strings != 16 && e->opt.chunk_strings != 32) e->opt.chunk_strings = 8;
     try {
         if (!build_tables(g, e->tab)) { delete e; return ZF_ERR_GRAMMAR; }
@@ -446,10 +441,27 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     a.fb_items = d->d_fb_items;
     a.fb_set_start = d->d_fb_ss;
     a.batch = batch;
+    // Item budget of a walking wavefront: the configured one, raised for this call when the rows'
+    // current sets are large (ambiguous grammars) so that such rows do not all end in the fallback.
     a.lane_cap = e->opt.lane_item_cap;
+    if (e->lane_cap_auto) {
+        size_t widest = 0;
+        for (int b = 0; b < batch; b++) {
+            const Chart &c = states[b]->chart;
+            widest = std::max<size_t>(widest, c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1]);
+        }
+        size_t want_cap = (8 * widest + 64 + 127) / 128 * 128;
+        while (want_cap > (size_t)a.lane_cap && walk_lds_bytes(d->tab, d->mode, (int)std::min<size_t>(want_cap, LANE_CAP_MAX)) > 160u * 1024u) want_cap -= 128;
+        if (want_cap > (size_t)a.lane_cap) a.lane_cap = (int)std::min<size_t>(want_cap, LANE_CAP_MAX);
+    }
+    {   // the persistent walk grid: as many blocks as the chip holds at once (LDS is the limit)
+        const uint32_t lds = walk_lds_bytes(d->tab, d->mode, a.lane_cap);
+        int per_cu = (int)(160u * 1024u / lds);
+        if (per_cu > 32 / WALK_WAVES) per_cu = 32 / WALK_WAVES;      // 32 wavefronts per CU = 8 per SIMD
+        a.walk_blocks = std::max(1, d->cus) * std::max(1, per_cu);
+    }
     a.fb_cap = e->opt.fallback_item_cap;
     a.mode = d->mode;
-    a.walk_blocks = d->walk_blocks;
     HIP_TRY(hipMemsetAsync(d->d_counters, 0, 16, stream));
     const bool prof = d->profiling;
     if (d->tab.n_chunks > 0) HIP_TRY(launch_cache_merge(a, stream));

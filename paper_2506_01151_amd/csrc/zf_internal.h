@@ -96,6 +96,7 @@ struct zf_engine {
     std::vector<int64_t> voc_off;
     std::vector<uint8_t> voc_bytes;
     bool start_nullable = false;
+    bool lane_cap_auto = true;          // no explicit lane_item_cap: the budget follows the rows' set sizes
     struct DeviceSide *dev = nullptr;   // null when compiled with device = -1
 };
 

@@ -18,8 +18,8 @@
 //      measured first: the nests of short data-dependent loops of an Earley step then cost
 //      ~12,000 cycles per step per wavefront because every loop level runs for its longest
 //      trip count over the 64 lanes.)  Grammar tables are staged in LDS once per block.
-//   3. mask_fallback_kernel: chunks whose list outgrew LDS repeat the walk with the list in a
-//      global-memory arena.
+//   3. mask_fallback_kernel: chunks whose list outgrew LDS repeat the walk, one wavefront each,
+//      with the list in a global-memory arena.
 #include <hip/hip_runtime.h>
 #include "zf_launch.h"
 
@@ -91,44 +91,16 @@ struct WaveLdsStore {          // walk kernel: the wavefront's list in LDS, used
     __device__ __forceinline__ uint32_t start(int d) const { return ss[d]; }
     __device__ __forceinline__ void set_start(int d, uint32_t v) { ss[d] = (uint16_t)v; }
 };
-struct GlobalStore {           // fallback: arena in global memory, interleaved by lane
+struct GlobalStore {           // fallback: the wavefront's list in a global-memory arena
     uint2 *items;
     uint32_t *ss;
     uint32_t cap;
     static constexpr int max_depth = FB_DEPTH_MAX;
-    __device__ __forceinline__ void get(uint32_t i, uint32_t &p, uint32_t &o) const { uint2 x = items[(size_t)i * FB3_LANES]; p = x.x; o = x.y; }
-    __device__ __forceinline__ void put(uint32_t i, uint32_t p, uint32_t o) { items[(size_t)i * FB3_LANES] = make_uint2(p, o); }
-    __device__ __forceinline__ uint32_t start(int d) const { return ss[(size_t)d * FB3_LANES]; }
-    __device__ __forceinline__ void set_start(int d, uint32_t v) { ss[(size_t)d * FB3_LANES] = v; }
+    __device__ __forceinline__ void get(uint32_t i, uint32_t &p, uint32_t &o) const { const uint2 x = items[i]; p = x.x; o = x.y; }
+    __device__ __forceinline__ void put(uint32_t i, uint32_t p, uint32_t o) { items[i] = make_uint2(p, o); }
+    __device__ __forceinline__ uint32_t start(int d) const { return ss[d]; }
+    __device__ __forceinline__ void set_start(int d, uint32_t v) { ss[d] = v; }
 };
-
-enum { ADD_OK = 1, ADD_END = 2 };   // result bits of the insert helpers (0 = list full)
-
-// "each state set maintains only unique states" (Section 3.2)
-template <class S>
-__device__ __forceinline__ bool insert_unique(S &st, uint32_t set_begin, uint32_t &cnt, uint32_t w, uint32_t o) {
-    for (uint32_t i = set_begin; i < cnt; i++) {
-        uint32_t xw, xo;
-        st.get(i, xw, xo);
-        if (xw == w && xo == o) return true;
-    }
-    if (cnt >= st.cap) return false;
-    st.put(cnt++, w, o);
-    return true;
-}
-
-// Add the item with the dot at position p; skip nullable postdot nonterminals; a dot at the end
-// of a rule becomes the canonical "lhs complete since o" item.  Returns ADD_* bits.
-template <class S>
-__device__ __forceinline__ uint32_t add_advanced(const TV &T, S &st, uint32_t set_begin, uint32_t &cnt, uint32_t p, uint32_t o) {
-    for (;;) {
-        const uint32_t w = T.advpq[p];
-        if (!insert_unique(st, set_begin, cnt, w, o)) return 0;
-        if (w & IW_END) return ADD_OK | ADD_END;
-        if ((w & IW_TERM) || !(w & IW_NT_NULLABLE)) return ADD_OK;
-        p++;
-    }
-}
 
 // One DFA step: returns next state | flags of the next state << 16, or DFA_DEAD in the low half.
 __device__ __forceinline__ uint32_t dfa_next(const TV &T, uint32_t q, uint32_t byte, uint32_t cl) {
@@ -137,7 +109,7 @@ __device__ __forceinline__ uint32_t dfa_next(const TV &T, uint32_t q, uint32_t b
     return T.delta[(info >> 16) * T.ncls + cl];
 }
 
-enum { STEP_ALIVE = 1, STEP_KERNEL = 2, STEP_OVERFLOW = 4 };
+enum { STEP_ALIVE = 1, STEP_KERNEL = 2, STEP_OVERFLOW = 4, STEP_WIDE = 8 /* a set wider than 64 items: redo with wave_step_big */ };
 
 template <class SoPtr, class ItPtr>
 struct Base {                  // the row's uploaded chart (LDS copy or global)
@@ -148,97 +120,10 @@ struct Base {                  // the row's uploaded chart (LDS copy or global)
 };
 typedef Base<const uint32_t *, const uint2 *> BaseG;
 
-// One Earley byte step at trie depth d (1-based).  The source set is the row's current set for
-// d == 1, else the lane's set of depth d-1.  On entry cnt == st.start(d).
-template <class S, class BaseT>
-__device__ __forceinline__ int earley_step(const TV &T, const BaseT &B, S &st, int d, uint32_t byte, uint32_t cl, uint32_t &cnt) {
-    const uint32_t nb = cnt;
-    const uint32_t cur = B.m - 1 + (uint32_t)(d - 1);   // index of the source set
-    uint32_t acc = ADD_OK;                               // AND of ok bits, OR of END bits
-    const bool from_base = d == 1;
-    const uint32_t sb = from_base ? B.last_lo : st.start(d - 1);
-    const uint32_t se = from_base ? B.last_hi : nb;
-    if (se - sb == 1) {   // the common case inside a terminal: one item, the DFA moves on and does not accept
-        uint32_t w, o;
-        if (from_base) { uint2 x = B.it[sb]; w = x.x; o = x.y; } else st.get(sb, w, o);
-        if (w & IW_TERM) {
-            const uint32_t nx = dfa_next(T, w >> 16, byte, cl);
-            const uint32_t q2 = nx & 0xFFFFu;
-            if (q2 == DFA_DEAD) { st.set_start(d + 1, nb); return 0; }
-            if (!((nx >> 16) & QF_ACCEPT)) {
-                if (nb >= st.cap) return STEP_OVERFLOW;
-                st.put(nb, (w & 0xFFFFu) | (q2 << 16), o);
-                cnt = nb + 1;
-                st.set_start(d + 1, cnt);
-                return STEP_ALIVE | STEP_KERNEL;
-            }
-        }
-    }
-    // Scan
-    for (uint32_t i = sb; i < se; i++) {
-        uint32_t w, o;
-        if (from_base) { uint2 x = B.it[i]; w = x.x; o = x.y; } else st.get(i, w, o);
-        if (w & IW_TERM) {
-            const uint32_t nx = dfa_next(T, w >> 16, byte, cl);
-            const uint32_t q2 = nx & 0xFFFFu, f = nx >> 16;
-            if (q2 == DFA_DEAD) continue;
-            uint32_t r = ADD_OK;
-            if (f & QF_CONT) r = insert_unique(st, nb, cnt, (w & 0xFFFFu) | (q2 << 16), o) ? ADD_OK : 0;   // no longest match: keep matching ...
-            if (r && (f & QF_ACCEPT)) r = add_advanced(T, st, nb, cnt, (w & IW_POS_MASK) + 1, o);        // ... and also finish here
-            if (!r) return STEP_OVERFLOW;
-            acc |= r;
-        } else if (!(w & IW_END)) {                      // waits for nonterminal Y: stands for every predicted item of I(Y)
-            const uint32_t Y = (w >> IW_NT_SHIFT) & IW_NT_MASK;
-            const uint32_t k0 = T.scan_off[Y * T.ncls + cl], k1 = T.scan_off[Y * T.ncls + cl + 1];
-            for (uint32_t e = k0; e < k1; e++) {
-                const uint2 ef = T.scan_list[e];
-                const uint32_t ent = ef.x, f = ef.y;
-                uint32_t r = ADD_OK;
-                if (f & QF_CONT) r = insert_unique(st, nb, cnt, ent, cur) ? ADD_OK : 0;
-                if (r && (f & QF_ACCEPT)) r = add_advanced(T, st, nb, cnt, (ent & IW_POS_MASK) + 1, cur);
-                if (!r) return STEP_OVERFLOW;
-                acc |= r;
-            }
-        }
-    }
-    if (!(acc & ADD_END)) {                              // nothing completed: no Complete phase, nothing to drop
-        st.set_start(d + 1, cnt);
-        return cnt > nb ? (STEP_ALIVE | STEP_KERNEL) : 0;
-    }
-    // Complete
-    for (uint32_t i = nb; i < cnt; i++) {
-        uint32_t w, o;
-        st.get(i, w, o);
-        if (!(w & IW_END)) continue;
-        const uint32_t X = (w & IW_POS_MASK) - T.end_base;
-        if (X == T.N - 1) continue;                     // the start rule is complete: the prefix is a sentence
-        const bool in_base = o < B.m;
-        uint32_t jb, je;
-        if (in_base) { jb = B.so[o]; je = B.so[o + 1]; }
-        else { const int dj = (int)(o - (B.m - 1)); jb = st.start(dj); je = st.start(dj + 1); }
-        for (uint32_t j = jb; j < je; j++) {
-            uint32_t yw, yo;
-            if (in_base) { uint2 y = B.it[j]; yw = y.x; yo = y.y; } else st.get(j, yw, yo);
-            if (yw & (IW_TERM | IW_END)) continue;
-            const uint32_t Y = (yw >> IW_NT_SHIFT) & IW_NT_MASK;
-            const uint32_t c0 = T.comp_off[Y * T.N + X], c1 = T.comp_off[Y * T.N + X + 1];
-            for (uint32_t e = c0; e < c1; e++) if (!add_advanced(T, st, nb, cnt, T.comp_list[e], o)) return STEP_OVERFLOW;
-            if (Y == X && !add_advanced(T, st, nb, cnt, (yw & IW_POS_MASK) + 1, yo)) return STEP_OVERFLOW;
-        }
-    }
-    uint32_t wpos = nb;   // completed items are needed only while their own set is processed
-    for (uint32_t i = nb; i < cnt; i++) {
-        uint32_t w, o;
-        st.get(i, w, o);
-        if (!(w & IW_END)) { if (wpos != i) st.put(wpos, w, o); wpos++; }
-    }
-    cnt = wpos;
-    st.set_start(d + 1, cnt);
-    return STEP_ALIVE | (cnt > nb ? STEP_KERNEL : 0);
-}
-
-// The same byte step done by a whole wavefront with uniform control flow.  All 64 lanes call it
-// with identical arguments.  Lane i loads source item i, the DFA transitions of all items run in
+// One Earley byte step at trie depth d (1-based) is done by a whole wavefront with uniform control
+// flow.  The source set is the row's current set for d == 1, else the wavefront's set of depth
+// d-1.  On entry cnt == st.start(d); on exit the new set is stored at [cnt_in, cnt_out).
+// All 64 lanes call it with identical arguments.  Lane i loads source item i, the DFA transitions of all items run in
 // parallel, the set under construction lives in registers (lane j holds new item j) so that the
 // duplicate test is one compare + ballot, and Complete loads S[origin] 64 items at a time.  Sets
 // of more than 64 items are reported as overflow (the fallback handles them).
@@ -249,14 +134,15 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
     const bool from_base = d == 1;
     const uint32_t sb = from_base ? B.last_lo : st.start(d - 1);
     const uint32_t ns = (from_base ? B.last_hi : nb) - sb;
-    if (ns > 64) return STEP_OVERFLOW;
+    if (ns > 64) return STEP_WIDE;
     uint32_t sw = IW_END, so = 0;                        // lanes beyond the set hold an inert item
     if (lane < ns) { if (from_base) { const uint2 x = B.it[sb + lane]; sw = x.x; so = x.y; } else st.get(sb + lane, sw, so); }
     uint32_t nw = 0, no = 0, nnew = 0;                   // the set under construction, one item per lane
-    bool saw_end = false;
+    bool saw_end = false, wide = false;
     auto insert = [&](uint32_t w, uint32_t o) -> bool {  // uniform arguments
         if (__ballot(lane < nnew && nw == w && no == o)) return true;
-        if (nnew >= 64 || nb + nnew >= st.cap) return false;
+        if (nnew >= 64) { wide = true; return false; }
+        if (nb + nnew >= st.cap) return false;
         if (lane == nnew) { nw = w; no = o; }
         nnew++;
         return true;
@@ -278,8 +164,8 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
         const int l = __ffsll((long long)m) - 1;
         m &= m - 1;
         const uint32_t lw = __builtin_amdgcn_readlane(sw, l), lo = __builtin_amdgcn_readlane(so, l), lnx = __builtin_amdgcn_readlane(nx, l);
-        if ((lnx >> 16) & QF_CONT) if (!insert((lw & 0xFFFFu) | (lnx << 16), lo)) return STEP_OVERFLOW;   // no longest match: keep matching ...
-        if ((lnx >> 16) & QF_ACCEPT) if (!advance((lw & IW_POS_MASK) + 1, lo)) return STEP_OVERFLOW;      // ... and also finish here
+        if ((lnx >> 16) & QF_CONT) if (!insert((lw & 0xFFFFu) | (lnx << 16), lo)) return wide ? STEP_WIDE : STEP_OVERFLOW;   // no longest match: keep matching ...
+        if ((lnx >> 16) & QF_ACCEPT) if (!advance((lw & IW_POS_MASK) + 1, lo)) return wide ? STEP_WIDE : STEP_OVERFLOW;      // ... and also finish here
     }
     // Scan, items that wait for a nonterminal Y: the tabulated first steps of every terminal that can begin Y
     m = __ballot(!(sw & (IW_TERM | IW_END)));
@@ -294,8 +180,8 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
             const uint32_t n_e = k1 - e0 < 64 ? k1 - e0 : 64;
             for (uint32_t t = 0; t < n_e; t++) {
                 const uint32_t ent = __builtin_amdgcn_readlane(ef.x, t), f = __builtin_amdgcn_readlane(ef.y, t);
-                if (f & QF_CONT) if (!insert(ent, cur)) return STEP_OVERFLOW;
-                if (f & QF_ACCEPT) if (!advance((ent & IW_POS_MASK) + 1, cur)) return STEP_OVERFLOW;
+                if (f & QF_CONT) if (!insert(ent, cur)) return wide ? STEP_WIDE : STEP_OVERFLOW;
+                if (f & QF_ACCEPT) if (!advance((ent & IW_POS_MASK) + 1, cur)) return wide ? STEP_WIDE : STEP_OVERFLOW;
             }
         }
     }
@@ -323,9 +209,9 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
                     const int l = __ffsll((long long)mm) - 1;
                     mm &= mm - 1;
                     const uint32_t lc0 = __builtin_amdgcn_readlane(c0, l), lc1 = __builtin_amdgcn_readlane(c1, l);
-                    for (uint32_t e = lc0; e < lc1; e++) if (!advance(T.comp_list[e], o)) return STEP_OVERFLOW;
+                    for (uint32_t e = lc0; e < lc1; e++) if (!advance(T.comp_list[e], o)) return wide ? STEP_WIDE : STEP_OVERFLOW;
                     if (__builtin_amdgcn_readlane(Y, l) == X)
-                        if (!advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l))) return STEP_OVERFLOW;
+                        if (!advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l))) return wide ? STEP_WIDE : STEP_OVERFLOW;
                 }
             }
         }
@@ -337,6 +223,109 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
     cnt = nb + (uint32_t)__popcll(kb);
     st.set_start(d + 1, cnt);
     return (nnew ? STEP_ALIVE : 0) | (kb ? STEP_KERNEL : 0);
+}
+
+// The wavefront step for large sets (ambiguous grammars make sets of hundreds of items): same
+// structure, but the set under construction lives in LDS only and every loop over items runs in
+// strips of 64.  Slower per item than wave_step, used only when a set does not fit 64 lanes.
+template <class BaseT, class S>
+__device__ __forceinline__ int wave_step_big(const TV &T, const BaseT &B, S &st, int d, uint32_t byte, uint32_t cl, uint32_t &cnt, uint32_t lane) {
+    const uint32_t nb = cnt;
+    const uint32_t cur = B.m - 1 + (uint32_t)(d - 1);
+    const bool from_base = d == 1;
+    const uint32_t sb = from_base ? B.last_lo : st.start(d - 1);
+    const uint32_t se = from_base ? B.last_hi : nb;
+    uint32_t nnew = 0;
+    bool saw_end = false;
+    auto insert = [&](uint32_t w, uint32_t o) -> bool {
+        for (uint32_t s0 = 0; s0 < nnew; s0 += 64) {
+            uint32_t xw = 0, xo = 0xFFFFFFFFu;
+            if (s0 + lane < nnew) st.get(nb + s0 + lane, xw, xo);
+            if (__ballot(s0 + lane < nnew && xw == w && xo == o)) return true;
+        }
+        if (nb + nnew >= st.cap) return false;
+        if (lane == 0) st.put(nb + nnew, w, o);
+        nnew++;
+        return true;
+    };
+    auto advance = [&](uint32_t p, uint32_t o) -> bool {
+        for (;;) {
+            const uint32_t w = T.advpq[p];
+            if (!insert(w, o)) return false;
+            if (w & IW_END) { saw_end = true; return true; }
+            if ((w & IW_TERM) || !(w & IW_NT_NULLABLE)) return true;
+            p++;
+        }
+    };
+    for (uint32_t s0 = sb; s0 < se; s0 += 64) {
+        uint32_t sw = IW_END, so = 0;
+        if (s0 + lane < se) { if (from_base) { const uint2 x = B.it[s0 + lane]; sw = x.x; so = x.y; } else st.get(s0 + lane, sw, so); }
+        uint32_t nx = DFA_DEAD;
+        if (sw & IW_TERM) nx = dfa_next(T, sw >> 16, byte, cl);
+        unsigned long long m = __ballot((nx & 0xFFFFu) != DFA_DEAD);
+        while (m) {
+            const int l = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const uint32_t lw = __builtin_amdgcn_readlane(sw, l), lo = __builtin_amdgcn_readlane(so, l), lnx = __builtin_amdgcn_readlane(nx, l);
+            if ((lnx >> 16) & QF_CONT) if (!insert((lw & 0xFFFFu) | (lnx << 16), lo)) return STEP_OVERFLOW;
+            if ((lnx >> 16) & QF_ACCEPT) if (!advance((lw & IW_POS_MASK) + 1, lo)) return STEP_OVERFLOW;
+        }
+        m = __ballot(!(sw & (IW_TERM | IW_END)));
+        while (m) {
+            const int l = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const uint32_t Y = (__builtin_amdgcn_readlane(sw, l) >> IW_NT_SHIFT) & IW_NT_MASK;
+            const uint32_t k0 = T.scan_off[Y * T.ncls + cl], k1 = T.scan_off[Y * T.ncls + cl + 1];
+            for (uint32_t e = k0; e < k1; e++) {
+                const uint2 ef = T.scan_list[e];
+                if (ef.y & QF_CONT) if (!insert(ef.x, cur)) return STEP_OVERFLOW;
+                if (ef.y & QF_ACCEPT) if (!advance((ef.x & IW_POS_MASK) + 1, cur)) return STEP_OVERFLOW;
+            }
+        }
+    }
+    if (saw_end) {
+        for (uint32_t i = 0; i < nnew; i++) {
+            uint32_t w, o;
+            st.get(nb + i, w, o);                        // every lane reads the same item
+            if (!(w & IW_END)) continue;
+            const uint32_t X = (w & IW_POS_MASK) - T.end_base;
+            if (X == T.N - 1) continue;
+            const bool in_base = o < B.m;
+            uint32_t jb, je;
+            if (in_base) { jb = B.so[o]; je = B.so[o + 1]; }
+            else { const int dj = (int)(o - (B.m - 1)); jb = st.start(dj); je = st.start(dj + 1); }
+            for (uint32_t j0 = jb; j0 < je; j0 += 64) {
+                uint32_t yw = IW_END, yo = 0;
+                if (j0 + lane < je) { if (in_base) { const uint2 y = B.it[j0 + lane]; yw = y.x; yo = y.y; } else st.get(j0 + lane, yw, yo); }
+                const bool nt = !(yw & (IW_TERM | IW_END));
+                const uint32_t Y = (yw >> IW_NT_SHIFT) & IW_NT_MASK;
+                uint32_t c0 = 0, c1 = 0;
+                if (nt) { c0 = T.comp_off[Y * T.N + X]; c1 = T.comp_off[Y * T.N + X + 1]; }
+                unsigned long long mm = __ballot(nt && (c1 > c0 || Y == X));
+                while (mm) {
+                    const int l = __ffsll((long long)mm) - 1;
+                    mm &= mm - 1;
+                    const uint32_t lc0 = __builtin_amdgcn_readlane(c0, l), lc1 = __builtin_amdgcn_readlane(c1, l);
+                    for (uint32_t e = lc0; e < lc1; e++) if (!advance(T.comp_list[e], o)) return STEP_OVERFLOW;
+                    if (__builtin_amdgcn_readlane(Y, l) == X)
+                        if (!advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l))) return STEP_OVERFLOW;
+                }
+            }
+        }
+    }
+    // drop the completed items: forward compaction, strip by strip (a strip is read before it is written)
+    uint32_t kept = 0;
+    for (uint32_t s0 = 0; s0 < nnew; s0 += 64) {
+        uint32_t w = IW_END, o = 0;
+        if (s0 + lane < nnew) st.get(nb + s0 + lane, w, o);
+        const bool keep = !(w & IW_END);
+        const unsigned long long kb = __ballot(keep);
+        if (keep) st.put(nb + kept + __popcll(kb & ((1ull << lane) - 1ull)), w, o);
+        kept += (uint32_t)__popcll(kb);
+    }
+    cnt = nb + kept;
+    st.set_start(d + 1, cnt);
+    return (nnew ? STEP_ALIVE : 0) | (kept ? STEP_KERNEL : 0);
 }
 
 // Walk the nodes of one chunk.  anc(j) gives the node index of the first node's ancestor at
@@ -520,11 +509,19 @@ __global__ __launch_bounds__(WALK_BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8
                 auto node = [&](uint32_t i) { return l_nodes[i - begin]; };
                 if (base_fits) {
                     const Base<const uint32_t *, const uint2 *> B{l_so, l_it, rc.n_sets, l_so[rc.n_sets - 1], rc.n_items};
-                    ok = walk_chunk(D, st, [&](int d, uint32_t byte, uint32_t cl, uint32_t &cnt) { return wave_step(T, B, st, d, byte, cl, cnt, lane); },
+                    ok = walk_chunk(D, st, [&](int d, uint32_t byte, uint32_t cl, uint32_t &cnt) {
+                                        const uint32_t keep = cnt;
+                                        int r = wave_step(T, B, st, d, byte, cl, cnt, lane);
+                                        if (r & STEP_WIDE) { cnt = keep; r = wave_step_big(T, B, st, d, byte, cl, cnt, lane); }
+                                        return r; },
                                     chunk, want, begin, begin + n_nodes, anc, node, &bits);
                 } else {
                     const Base<const uint32_t *, const uint2 *> B{g_so, g_it, rc.n_sets, g_so[rc.n_sets - 1], rc.n_items};
-                    ok = walk_chunk(D, st, [&](int d, uint32_t byte, uint32_t cl, uint32_t &cnt) { return wave_step(T, B, st, d, byte, cl, cnt, lane); },
+                    ok = walk_chunk(D, st, [&](int d, uint32_t byte, uint32_t cl, uint32_t &cnt) {
+                                        const uint32_t keep = cnt;
+                                        int r = wave_step(T, B, st, d, byte, cl, cnt, lane);
+                                        if (r & STEP_WIDE) { cnt = keep; r = wave_step_big(T, B, st, d, byte, cl, cnt, lane); }
+                                        return r; },
                                     chunk, want, begin, begin + n_nodes, anc, node, &bits);
                 }
             }
@@ -541,24 +538,32 @@ __global__ __launch_bounds__(WALK_BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8
     }
 }
 
-// Fallback: one lane per chunk that outgrew LDS, item list in a global-memory arena.
+// Fallback: one wavefront per chunk that outgrew LDS; same walk with the strip-wise step and the
+// item list in a global-memory arena.
 __global__ __launch_bounds__(64) void mask_fallback_kernel(MaskArgs a) {
     const DeviceTables &D = a.tab;
     TV T;
     stage_tables<2>(D, nullptr, T, 0, 1);
-    const uint32_t gid = blockIdx.x * 64 + threadIdx.x;
+    const uint32_t lane = threadIdx.x;
     uint32_t n = a.counters[0];
-    if (n > a.overflow_cap) { if (gid == 0) atomicAdd(&a.counters[2], n - a.overflow_cap); n = a.overflow_cap; }
-    GlobalStore st{a.fb_items + gid, a.fb_set_start + gid, (uint32_t)a.fb_cap};
-    for (uint32_t e = gid; e < n; e += FB3_LANES) {
+    if (n > a.overflow_cap) { if (blockIdx.x == 0 && lane == 0) atomicAdd(&a.counters[2], n - a.overflow_cap); n = a.overflow_cap; }
+    GlobalStore st{a.fb_items + (size_t)blockIdx.x * FB_ITEMS_PER_WAVE, a.fb_set_start + (size_t)blockIdx.x * (FB_DEPTH_MAX + 2), (uint32_t)a.fb_cap};
+    for (uint32_t e = blockIdx.x; e < n; e += gridDim.x) {
         const uint4 ent = a.overflow_list[e];
         const BaseG B = global_base(a, ent.x);
         const uint32_t begin = D.chunk_begin[ent.y], end = D.chunk_end[ent.y];
         ParentAnc anc{D.nodes, D.parent, begin, D.nodes[begin].depth};
         uint32_t bits = 0;
-        if (!walk_chunk(D, st, [&](int d, uint32_t byte, uint32_t cl, uint32_t &cnt) { return earley_step(T, B, st, d, byte, cl, cnt); },
-                        ent.y, ent.z, begin, end, anc, [&](uint32_t i) { return D.nodes[i]; }, &bits)) { atomicAdd(&a.counters[2], 1u); continue; }
-        or_bits(D, a.rank_mask, ent.x, ent.y, bits & ent.z);
+        const bool ok = walk_chunk(D, st, [&](int d, uint32_t byte, uint32_t cl, uint32_t &cnt) { return wave_step_big(T, B, st, d, byte, cl, cnt, lane); },
+                                   ent.y, ent.z, begin, end, anc, [&](uint32_t i) { return D.nodes[i]; }, &bits);
+        if (lane == 0) {
+            if (!ok) atomicAdd(&a.counters[2], 1u);
+            else or_bits(D, a.rank_mask, ent.x, ent.y, bits & ent.z);
+        }
+        // lanes write the arena, lane-uniform reads follow in the next round: keep the order
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
 }
 
@@ -658,7 +663,7 @@ hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s) {
     return hipGetLastError();
 }
 hipError_t launch_mask_fallback(const MaskArgs &a, hipStream_t s) {
-    hipLaunchKernelGGL(mask_fallback_kernel, dim3(FB3_LANES / 64), dim3(64), 0, s, a);
+    hipLaunchKernelGGL(mask_fallback_kernel, dim3(FB_WAVES), dim3(64), 0, s, a);
     return hipGetLastError();
 }
 hipError_t launch_permute(const MaskArgs &a, hipStream_t s) {

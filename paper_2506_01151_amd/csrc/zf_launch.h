@@ -5,8 +5,8 @@
 
 namespace zf {
 
-static const int LANE_CAP_MAX = 1024;      // upper limit of the walk kernel's item budget per wavefront (LDS)
-static const int LANE_CAP_DEFAULT = 64;
+static const int LANE_CAP_MAX = 2048;      // upper limit of the walk kernel's item budget per wavefront (LDS)
+static const int LANE_CAP_DEFAULT = 128;
 static const int WALK_WAVES = 8;           // wavefronts (= queued chunks) per block of the walk kernel; they share the staged tables
 static const int WALK_BLOCK = WALK_WAVES * 64;
 static const int WALK_NODES_LDS = 80;      // trie nodes of a chunk the walk kernel stages in LDS (bigger chunks go to the fallback)
@@ -15,8 +15,8 @@ static const int BASE_SETS_LDS = 31;       // a row's chart is staged into LDS w
 static const int BASE_ITEMS_LDS = 96;      // ... and items
 static const int TABLE_LDS_BUDGET = 56 * 1024;
 static const int FB_DEPTH_MAX = 256;
-static const int FB3_LANES = 2048;         // lanes of the fallback grid
-static const int FB3_ITEMS_PER_LANE = 16384; // its arena in global memory: items per lane
+static const int FB_WAVES = 512;           // wavefronts of the fallback grid
+static const int FB_ITEMS_PER_WAVE = 65536; // its arena in global memory: items per wavefront (256 MB in all)
 
 struct MaskArgs {
     DeviceTables tab;
@@ -30,11 +30,11 @@ struct MaskArgs {
     uint4 *work;               // queue of (row, chunk, undecided strings, -) that need the parser walk
     uint4 *overflow_list;      // (row, chunk, undecided strings, -) for the fallback
     uint32_t overflow_cap;
-    uint2 *fb_items;           // [FB3_ITEMS_PER_LANE][FB3_LANES] interleaved
-    uint32_t *fb_set_start;    // [FB_DEPTH_MAX + 2][FB3_LANES]
+    uint2 *fb_items;           // [FB_WAVES][FB_ITEMS_PER_WAVE]
+    uint32_t *fb_set_start;    // [FB_WAVES][FB_DEPTH_MAX + 2]
     int32_t batch;
     int32_t lane_cap;          // item budget of a walking wavefront
-    int32_t fb_cap;            // item budget of a fallback lane (<= FB3_ITEMS_PER_LANE)
+    int32_t fb_cap;            // item budget of a fallback wavefront (<= FB_ITEMS_PER_WAVE)
     int32_t walk_blocks;       // blocks of the persistent walk grid (what the chip holds at once)
     int32_t mode;              // 0: all tables staged in LDS, 1: the small ones only, 2: none
 };
