@@ -67,7 +67,7 @@ typedef struct {
 typedef struct {
     int32_t pruning;       /* 1 = ZapFormat Compact phase on (Section 4.2), 0 = keep every item */
     int32_t lane_item_cap; /* Earley item budget (LDS) of one walking wavefront of the mask kernel,
-                              0 = automatic (128, more when the current sets are large); what does not fit goes to the exact fallback pass */
+                              0 = automatic (96, more when the current sets are large); what does not fit goes to the exact fallback pass */
     int32_t device;        /* HIP device ordinal, or -1 = host tables only (no mask calls) */
     int32_t chunk_strings; /* vocabulary strings walked by one lane: 8, 16 or 32; 0 = default */
     int32_t fallback_item_cap; /* item budget of a fallback wavefront (global memory), 0 = default

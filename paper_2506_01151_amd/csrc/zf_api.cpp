@@ -31,6 +31,7 @@ struct DeviceSide {
     uint2 *d_fb_items = nullptr;
     uint32_t *d_fb_ss = nullptr;
     zf_mask_report report{};
+    uint32_t call_parity = 0;            // which of the two counter sets the next call uses
     bool profiling = false;
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
 };
@@ -101,7 +102,8 @@ int setup_device(zf_engine *e) {
     HIP_TRY(hipDeviceGetAttribute(&d->cus, hipDeviceAttributeMultiprocessorCount, d->device));
     if (walk_lds_bytes(T, d->mode, e->opt.lane_item_cap) > 160u * 1024u)
         return fail(ZF_ERR_INVALID_ARG, "lane_item_cap and the grammar tables do not fit the 160 KB of LDS");
-    HIP_TRY(hipMalloc((void **)&d->d_counters, 16));
+    HIP_TRY(hipMalloc((void **)&d->d_counters, 32));
+    HIP_TRY(hipMemset(d->d_counters, 0, 32));
     HIP_TRY(hipHostMalloc((void **)&d->h_counters, 16, hipHostMallocDefault));
     HIP_TRY(hipMalloc((void **)&d->d_fb_items, (size_t)FB_ITEMS_PER_WAVE * FB_WAVES * sizeof(uint2)));
     HIP_TRY(hipMalloc((void **)&d->d_fb_ss, (size_t)(FB_DEPTH_MAX + 2) * FB_WAVES * sizeof(uint32_t)));
@@ -434,7 +436,9 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     a.entries = (const uint32_t *)((uint8_t *)d->d_chart + off_ent);
     a.rank_mask = d->d_rank_mask;
     a.out_mask = d_mask;
-    a.counters = d->d_counters;
+    a.counters = d->d_counters + 4 * d->call_parity;
+    a.counters_next = d->d_counters + 4 * (d->call_parity ^ 1u);
+    d->call_parity ^= 1u;
     a.work = d->d_work;
     a.overflow_list = d->d_overflow;
     a.overflow_cap = (uint32_t)d->overflow_cap;
@@ -450,35 +454,41 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
             const Chart &c = states[b]->chart;
             widest = std::max<size_t>(widest, c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1]);
         }
-        size_t want_cap = (8 * widest + 64 + 127) / 128 * 128;
-        while (want_cap > (size_t)a.lane_cap && walk_lds_bytes(d->tab, d->mode, (int)std::min<size_t>(want_cap, LANE_CAP_MAX)) > 160u * 1024u) want_cap -= 128;
+        size_t want_cap = (8 * widest + 64 + 31) / 32 * 32;
+        while (want_cap > (size_t)a.lane_cap && walk_lds_bytes(d->tab, d->mode, (int)std::min<size_t>(want_cap, LANE_CAP_MAX)) > 160u * 1024u) want_cap -= 32;
         if (want_cap > (size_t)a.lane_cap) a.lane_cap = (int)std::min<size_t>(want_cap, LANE_CAP_MAX);
     }
     {   // the persistent walk grid: as many blocks as the chip holds at once (LDS is the limit)
         const uint32_t lds = walk_lds_bytes(d->tab, d->mode, a.lane_cap);
         int per_cu = (int)(160u * 1024u / lds);
-        if (per_cu > 32 / WALK_WAVES) per_cu = 32 / WALK_WAVES;      // 32 wavefronts per CU = 8 per SIMD
+        if (per_cu > 32 / WALK_WAVES) per_cu = 32 / WALK_WAVES;      // at most 32 wavefronts per CU (8 per SIMD)
         a.walk_blocks = std::max(1, d->cus) * std::max(1, per_cu);
     }
     a.fb_cap = e->opt.fallback_item_cap;
     a.mode = d->mode;
-    HIP_TRY(hipMemsetAsync(d->d_counters, 0, 16, stream));
     const bool prof = d->profiling;
     if (d->tab.n_chunks > 0) HIP_TRY(launch_cache_merge(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
     if (d->tab.n_chunks > 0) HIP_TRY(launch_mask_walk(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));
-    if (d->tab.n_chunks > 0) HIP_TRY(launch_mask_fallback(a, stream));
-    if (prof) HIP_TRY(hipEventRecord(d->ev[2], stream));
     HIP_TRY(launch_permute(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[3], stream));
-    HIP_TRY(hipMemcpyAsync(d->h_counters, d->d_counters, 16, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipMemcpyAsync(d->h_counters, a.counters, 16, hipMemcpyDeviceToHost, stream));
     HIP_TRY(hipStreamSynchronize(stream));
     d->report.main_ms = d->report.fallback_ms = d->report.permute_ms = 0.f;
     if (prof) {
         HIP_TRY(hipEventElapsedTime(&d->report.main_ms, d->ev[0], d->ev[1]));
-        HIP_TRY(hipEventElapsedTime(&d->report.fallback_ms, d->ev[1], d->ev[2]));
-        HIP_TRY(hipEventElapsedTime(&d->report.permute_ms, d->ev[2], d->ev[3]));
+        HIP_TRY(hipEventElapsedTime(&d->report.permute_ms, d->ev[1], d->ev[3]));
+    }
+    if (d->h_counters[0] && !d->h_counters[2]) {
+        // rare: some chunks outgrew LDS.  Run the fallback pass on them and permute again.
+        if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));
+        HIP_TRY(launch_mask_fallback(a, stream));
+        if (prof) HIP_TRY(hipEventRecord(d->ev[2], stream));
+        HIP_TRY(launch_permute(a, stream));
+        HIP_TRY(hipMemcpyAsync(d->h_counters, a.counters, 16, hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+        if (prof) HIP_TRY(hipEventElapsedTime(&d->report.fallback_ms, d->ev[1], d->ev[2]));
     }
     d->report.overflow_chunks = d->h_counters[0];
     d->report.chart_bytes = (int64_t)total;

@@ -6,13 +6,13 @@
 namespace zf {
 
 static const int LANE_CAP_MAX = 2048;      // upper limit of the walk kernel's item budget per wavefront (LDS)
-static const int LANE_CAP_DEFAULT = 128;
+static const int LANE_CAP_DEFAULT = 96; 
 static const int WALK_WAVES = 8;           // wavefronts (= queued chunks) per block of the walk kernel; they share the staged tables
 static const int WALK_BLOCK = WALK_WAVES * 64;
 static const int WALK_NODES_LDS = 80;      // trie nodes of a chunk the walk kernel stages in LDS (bigger chunks go to the fallback)
 static const int WALK_DEPTH_MAX = 32;      // trie depth the walk kernel follows (deeper paths go to the fallback)
 static const int BASE_SETS_LDS = 31;       // a row's chart is staged into LDS when it has at most this many sets ...
-static const int BASE_ITEMS_LDS = 96;      // ... and items
+static const int BASE_ITEMS_LDS = 64;      // ... and items
 static const int TABLE_LDS_BUDGET = 56 * 1024;
 static const int FB_DEPTH_MAX = 256;
 static const int FB_WAVES = 512;           // wavefronts of the fallback grid
@@ -27,6 +27,7 @@ struct MaskArgs {
     uint32_t *rank_mask;       // [batch][Wr] verdicts in trie (rank) order
     uint32_t *out_mask;        // [batch][W] verdicts in token-id order
     uint32_t *counters;        // [0] chunks passed to the fallback, [1] length of the work queue, [2] chunks nobody could resolve
+    uint32_t *counters_next;   // the next call's counters: cleared by this call's last kernel (no separate memset)
     uint4 *work;               // queue of (row, chunk, undecided strings, -) that need the parser walk
     uint4 *overflow_list;      // (row, chunk, undecided strings, -) for the fallback
     uint32_t overflow_cap;
