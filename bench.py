@@ -99,6 +99,9 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pruning", type=int, default=1)
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="only run apply_mask with an all-ones mask on a [1024, V] tensor three times: a plain copy of known "
+                         "size, used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("this build runs on one GPU only: rows and vocabulary ranges would shard without any exchange, "
@@ -122,6 +125,16 @@ def main():
     if len(traj) < need:
         traj_src = f"oracle-sampled file ({len(traj)} steps) extended by the library"
         traj = extend_trajectory(zf, eng, cfg, traj, B, need)
+
+    if args.traffic_calibration:
+        x = torch.zeros((1024, V), dtype=torch.bfloat16, device="cuda")
+        y = torch.empty_like(x)
+        ones = torch.full((1024, W), -1, dtype=torch.int32, device="cuda")
+        for _ in range(3):
+            zf.apply_mask(eng, x, ones, out=y)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration_copy_bytes_read": x.numel() * 2 + ones.numel() * 4, "calibration_copy_bytes_written": y.numel() * 2}))
+        return
 
     n_logit_bufs = 4
     logits = [configs.make_logits(cfg, i, device="cuda") for i in range(n_logit_bufs)]
@@ -196,7 +209,7 @@ def main():
         "kernel_ms": {k: statistics.fmean(v) for k, v in kern.items()},
         "kernel_ms_p50": {k: pct(v, 0.5) for k, v in kern.items()},
         "overflow_chunks_per_step": ovf / K,
-        "roofline": {"bound": "hbm", "kernel": "mask_main_kernel", "achieved": mask_bytes / (main_ms * 1e-3) / 1e9,
+        "roofline": {"bound": "hbm", "kernel": "mask_walk_kernel", "achieved": mask_bytes / (main_ms * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": mask_bytes / (main_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "traffic": None, "algorithmic_bytes": mask_bytes,
                      "note": "integer trie walk; bound by dependent LDS/L2 look-ups, far below the HBM roof"},

@@ -460,7 +460,7 @@ __device__ __forceinline__ BaseG global_base(const MaskArgs &a, uint32_t row) {
 
 // The parser walk.  Persistent blocks; every wavefront takes queued chunks g, g + stride, ...
 template <int MODE>
-__global__ __launch_bounds__(WALK_BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8))) void mask_walk_kernel(MaskArgs a) {
+__global__ __launch_bounds__(WALK_BLOCK) void mask_walk_kernel(MaskArgs a) {
     extern __shared__ __align__(16) uint8_t smem[];
     const DeviceTables &D = a.tab;
     const uint32_t tid = threadIdx.x;
