@@ -131,6 +131,14 @@ int zf_position_info(const zf_engine *e, int32_t position, int32_t *lhs, int32_t
  * stream); the call waits for its own kernels so that ZF_ERR_OVERFLOW can be reported. */
 int zf_compute_mask(zf_engine *e, zf_state *const *states /* host array */, int32_t batch,
                     uint32_t *d_mask, void *hip_stream);
+/* The same, without waiting: the kernels (the fallback pass included) are only enqueued on
+ * hip_stream, so that the caller's next launches (zf_apply_mask, the sampler) queue up right
+ * behind them.  ZF_ERR_OVERFLOW, if any, is reported by zf_mask_wait, which synchronises the
+ * stream.  At most 4 calls may be in flight between two zf_mask_wait calls; calls on one engine
+ * must all use the same stream and must not overlap from several host threads. */
+int zf_compute_mask_async(zf_engine *e, zf_state *const *states /* host array */, int32_t batch,
+                          uint32_t *d_mask, void *hip_stream);
+int zf_mask_wait(zf_engine *e, void *hip_stream);
 int zf_last_mask_report(const zf_engine *e, zf_mask_report *out);
 /* on != 0: zf_compute_mask brackets each of its kernels with HIP events (a few microseconds
  * of extra host time per call) and zf_last_mask_report returns their durations. */

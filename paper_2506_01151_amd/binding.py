@@ -50,7 +50,7 @@ class MaskReport(ctypes.Structure):
 EXPORTS = ["zf_strerror", "zf_last_error", "zf_compile", "zf_engine_destroy", "zf_engine_get_info",
            "zf_state_new", "zf_state_clone", "zf_state_reset", "zf_state_destroy", "zf_advance",
            "zf_advance_bytes", "zf_is_accepting", "zf_state_stats", "zf_state_chart", "zf_position_info",
-           "zf_compute_mask", "zf_last_mask_report", "zf_engine_set_profiling", "zf_apply_mask", "zf_debug_host_mask", "zf_debug_host_mask_stats", "zf_debug_host_mask_cached"]
+           "zf_compute_mask", "zf_compute_mask_async", "zf_mask_wait", "zf_last_mask_report", "zf_engine_set_profiling", "zf_apply_mask", "zf_debug_host_mask", "zf_debug_host_mask_stats", "zf_debug_host_mask_cached"]
 
 
 class ZfError(RuntimeError):
@@ -85,6 +85,8 @@ def load_library():
     L.zf_state_chart.argtypes = [c_vp, c_vp, c_vp]
     L.zf_position_info.argtypes = [c_vp, c_i32, ctypes.POINTER(c_i32), ctypes.POINTER(c_i32), ctypes.POINTER(c_i32)]
     L.zf_compute_mask.argtypes = [c_vp, c_vp, c_i32, c_vp, c_vp]
+    L.zf_compute_mask_async.argtypes = [c_vp, c_vp, c_i32, c_vp, c_vp]
+    L.zf_mask_wait.argtypes = [c_vp, c_vp]
     L.zf_last_mask_report.argtypes = [c_vp, c_vp]
     L.zf_engine_set_profiling.argtypes = [c_vp, c_i32]
     L.zf_apply_mask.argtypes = [c_vp, c_vp, c_vp, c_i32, c_i32, c_i64, c_vp, c_vp]
@@ -214,6 +216,13 @@ class Engine:
         arr = (c_vp * len(states))(*[s.h for s in states])
         _check(_lib.zf_compute_mask(self.h, arr, len(states), d_mask_ptr, stream))
 
+    def compute_mask_async(self, states, d_mask_ptr: int, stream: int = 0):
+        arr = (c_vp * len(states))(*[s.h for s in states])
+        _check(_lib.zf_compute_mask_async(self.h, arr, len(states), d_mask_ptr, stream))
+
+    def mask_wait(self, stream: int = 0):
+        _check(_lib.zf_mask_wait(self.h, stream))
+
     def set_profiling(self, on: bool):
         _check(_lib.zf_engine_set_profiling(self.h, int(on)))
 
@@ -243,6 +252,20 @@ def compute_mask(engine: Engine, states, mask_tensor):
     assert tuple(mask_tensor.shape) == (len(states), engine.W)
     engine.compute_mask(states, mask_tensor.data_ptr(), torch.cuda.current_stream().cuda_stream)
     return mask_tensor
+
+
+def compute_mask_async(engine: Engine, states, mask_tensor):
+    """Enqueue only; pair with mask_wait(engine) before reading the mask on the host."""
+    import torch
+    assert mask_tensor.is_cuda and mask_tensor.is_contiguous() and mask_tensor.dtype == torch.int32
+    assert tuple(mask_tensor.shape) == (len(states), engine.W)
+    engine.compute_mask_async(states, mask_tensor.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    return mask_tensor
+
+
+def mask_wait(engine: Engine):
+    import torch
+    engine.mask_wait(torch.cuda.current_stream().cuda_stream)
 
 
 def apply_mask(engine: Engine, logits, mask_tensor, out=None):

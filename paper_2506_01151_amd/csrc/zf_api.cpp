@@ -20,14 +20,17 @@ struct DeviceSide {
     std::vector<void *> owned;           // table allocations
     // per-call buffers, grown on demand
     void *d_chart = nullptr; size_t chart_cap = 0;
-    void *h_stage = nullptr; size_t stage_cap = 0;   // pinned
+    static const int N_SLOTS = 4;                    // calls that may be in flight before zf_mask_wait
+    void *h_stage[N_SLOTS] = {nullptr, nullptr, nullptr, nullptr}; size_t stage_cap[N_SLOTS] = {0, 0, 0, 0};   // pinned
+    hipEvent_t stage_done[N_SLOTS] = {nullptr, nullptr, nullptr, nullptr};   // the slot's upload has been consumed
+    uint32_t *h_status = nullptr;                    // pinned, [N_SLOTS][4]: counters written by each call's last kernel
+    uint32_t next_slot = 0, pending = 0;
     uint32_t *d_rank_mask = nullptr; size_t rank_cap = 0;
     uint4 *d_overflow = nullptr; size_t overflow_cap = 0;
     uint4 *d_work = nullptr;
     int cus = 256;
     int mode = 2;
     uint32_t *d_counters = nullptr;
-    uint32_t *h_counters = nullptr;      // pinned
     uint2 *d_fb_items = nullptr;
     uint32_t *d_fb_ss = nullptr;
     zf_mask_report report{};
@@ -62,12 +65,12 @@ void free_device(DeviceSide *d) {
     (void)hipSetDevice(d->device);
     for (void *p : d->owned) (void)hipFree(p);
     if (d->d_chart) (void)hipFree(d->d_chart);
-    if (d->h_stage) (void)hipHostFree(d->h_stage);
+    for (int k = 0; k < DeviceSide::N_SLOTS; k++) { if (d->h_stage[k]) (void)hipHostFree(d->h_stage[k]); if (d->stage_done[k]) (void)hipEventDestroy(d->stage_done[k]); }
+    if (d->h_status) (void)hipHostFree(d->h_status);
     if (d->d_rank_mask) (void)hipFree(d->d_rank_mask);
     if (d->d_overflow) (void)hipFree(d->d_overflow);
     if (d->d_work) (void)hipFree(d->d_work);
     if (d->d_counters) (void)hipFree(d->d_counters);
-    if (d->h_counters) (void)hipHostFree(d->h_counters);
     if (d->d_fb_items) (void)hipFree(d->d_fb_items);
     if (d->d_fb_ss) (void)hipFree(d->d_fb_ss);
     for (auto &ev : d->ev) if (ev) (void)hipEventDestroy(ev);
@@ -104,7 +107,9 @@ int setup_device(zf_engine *e) {
         return fail(ZF_ERR_INVALID_ARG, "lane_item_cap and the grammar tables do not fit the 160 KB of LDS");
     HIP_TRY(hipMalloc((void **)&d->d_counters, 32));
     HIP_TRY(hipMemset(d->d_counters, 0, 32));
-    HIP_TRY(hipHostMalloc((void **)&d->h_counters, 16, hipHostMallocDefault));
+    HIP_TRY(hipHostMalloc((void **)&d->h_status, 16 * DeviceSide::N_SLOTS, hipHostMallocDefault));
+    memset(d->h_status, 0, 16 * DeviceSide::N_SLOTS);
+    for (auto &ev : d->stage_done) HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
     HIP_TRY(hipMalloc((void **)&d->d_fb_items, (size_t)FB_ITEMS_PER_WAVE * FB_WAVES * sizeof(uint2)));
     HIP_TRY(hipMalloc((void **)&d->d_fb_ss, (size_t)(FB_DEPTH_MAX + 2) * FB_WAVES * sizeof(uint32_t)));
     return ZF_OK;
@@ -364,12 +369,19 @@ int zf_debug_host_mask_stats(zf_engine *e, const zf_state *s, uint32_t *mask, in
     return ZF_OK;
 }
 
-int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream) {
+// Pack and upload the charts and enqueue the kernels of one compute_mask call.  wait = true: the
+// fallback pass is launched only if the walk reported overflow (one extra host round trip in that
+// rare case) and the call returns the final status; wait = false: the fallback pass is always
+// enqueued and the status is left for zf_mask_wait.
+static int enqueue_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait) {
     if (!e || !states || batch <= 0 || batch > MAX_BATCH || !d_mask) return fail(ZF_ERR_INVALID_ARG, "bad argument (batch must be 1..4096)");
     DeviceSide *d = e->dev;
     if (!d) return fail(ZF_ERR_DEVICE, "engine was compiled without a device (device = -1)");
     hipStream_t stream = (hipStream_t)hip_stream;
     HIP_TRY(hipSetDevice(d->device));
+    if (d->pending >= (uint32_t)DeviceSide::N_SLOTS) return fail(ZF_ERR_INVALID_ARG, "too many asynchronous mask calls in flight: call zf_mask_wait");
+    const uint32_t slot = d->next_slot;
+    HIP_TRY(hipEventSynchronize(d->stage_done[slot]));   // the slot's previous upload has left the staging buffer
     // ---- pack the charts: [RowChart x batch][set offsets][items] ----
     size_t n_off = 0, n_items = 0, n_ent = 0;
     const bool use_cache = !e->opt.disable_token_mask_cache;
@@ -384,17 +396,23 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     const size_t off_rows = 0, off_so = align16(sizeof(RowChart) * batch), off_items = align16(off_so + 4 * n_off);
     const size_t off_ent = align16(off_items + sizeof(Item) * n_items);
     const size_t total = off_ent + 4 * n_ent + 16;
-    if (total > d->stage_cap) {
-        if (d->h_stage) (void)hipHostFree(d->h_stage);
-        if (d->d_chart) (void)hipFree(d->d_chart);
-        d->h_stage = nullptr; d->d_chart = nullptr; d->stage_cap = d->chart_cap = 0;
+    if (total > d->stage_cap[slot]) {
+        if (d->h_stage[slot]) (void)hipHostFree(d->h_stage[slot]);
+        d->h_stage[slot] = nullptr; d->stage_cap[slot] = 0;
         size_t cap = total * 2 + 4096;
-        HIP_TRY(hipHostMalloc(&d->h_stage, cap, hipHostMallocDefault));
+        HIP_TRY(hipHostMalloc(&d->h_stage[slot], cap, hipHostMallocDefault));
+        d->stage_cap[slot] = cap;
+    }
+    if (total > d->chart_cap) {
+        HIP_TRY(hipStreamSynchronize(stream));            // earlier calls may still read the old buffer
+        if (d->d_chart) (void)hipFree(d->d_chart);
+        d->d_chart = nullptr; d->chart_cap = 0;
+        size_t cap = total * 2 + 4096;
         HIP_TRY(hipMalloc(&d->d_chart, cap));
-        d->stage_cap = d->chart_cap = cap;
+        d->chart_cap = cap;
     }
     {
-        uint8_t *h = (uint8_t *)d->h_stage;
+        uint8_t *h = (uint8_t *)d->h_stage[slot];
         RowChart *rows = (RowChart *)(h + off_rows);
         uint32_t *so = (uint32_t *)(h + off_so);
         uint32_t *dev_items = (uint32_t *)(h + off_items);
@@ -415,10 +433,12 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
             so_at += (uint32_t)c.set_off.size(); it_at += (uint32_t)c.items.size();
         }
     }
-    HIP_TRY(hipMemcpyAsync(d->d_chart, d->h_stage, total, hipMemcpyHostToDevice, stream));
+    HIP_TRY(hipMemcpyAsync(d->d_chart, d->h_stage[slot], total, hipMemcpyHostToDevice, stream));
+    HIP_TRY(hipEventRecord(d->stage_done[slot], stream));
     // ---- per-call device buffers ----
     const size_t need_rank = (size_t)batch * d->tab.Wr, need_ovf = (size_t)batch * d->tab.n_chunks;
     if (need_rank > d->rank_cap || need_ovf > d->overflow_cap) {
+        HIP_TRY(hipStreamSynchronize(stream));
         if (d->d_rank_mask) (void)hipFree(d->d_rank_mask);
         if (d->d_overflow) (void)hipFree(d->d_overflow);
         if (d->d_work) (void)hipFree(d->d_work);
@@ -440,6 +460,7 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     a.counters_next = d->d_counters + 4 * (d->call_parity ^ 1u);
     d->call_parity ^= 1u;
     a.work = d->d_work;
+    a.host_status = d->h_status + 4 * slot;
     a.overflow_list = d->d_overflow;
     a.overflow_cap = (uint32_t)d->overflow_cap;
     a.fb_items = d->d_fb_items;
@@ -467,32 +488,60 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     a.fb_cap = e->opt.fallback_item_cap;
     a.mode = d->mode;
     const bool prof = d->profiling;
+    d->report.chart_bytes = (int64_t)total;
+    d->report.main_ms = d->report.fallback_ms = d->report.permute_ms = 0.f;
     if (d->tab.n_chunks > 0) HIP_TRY(launch_cache_merge(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
     if (d->tab.n_chunks > 0) HIP_TRY(launch_mask_walk(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));
-    HIP_TRY(launch_permute(a, stream));
+    if (!wait && d->tab.n_chunks > 0) HIP_TRY(launch_mask_fallback(a, stream));
+    if (prof) HIP_TRY(hipEventRecord(d->ev[2], stream));
+    HIP_TRY(launch_permute(a, stream));                   // also hands the counters to the host and clears the next call's
     if (prof) HIP_TRY(hipEventRecord(d->ev[3], stream));
-    HIP_TRY(hipMemcpyAsync(d->h_counters, a.counters, 16, hipMemcpyDeviceToHost, stream));
+    d->next_slot = (slot + 1) % DeviceSide::N_SLOTS;
+    d->pending++;
+    if (!wait) return ZF_OK;
     HIP_TRY(hipStreamSynchronize(stream));
-    d->report.main_ms = d->report.fallback_ms = d->report.permute_ms = 0.f;
-    if (prof) {
-        HIP_TRY(hipEventElapsedTime(&d->report.main_ms, d->ev[0], d->ev[1]));
-        HIP_TRY(hipEventElapsedTime(&d->report.permute_ms, d->ev[1], d->ev[3]));
-    }
-    if (d->h_counters[0] && !d->h_counters[2]) {
+    volatile uint32_t *st = d->h_status + 4 * slot;
+    if (st[0] && !st[2] && d->tab.n_chunks > 0) {
         // rare: some chunks outgrew LDS.  Run the fallback pass on them and permute again.
         if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));
         HIP_TRY(launch_mask_fallback(a, stream));
         if (prof) HIP_TRY(hipEventRecord(d->ev[2], stream));
         HIP_TRY(launch_permute(a, stream));
-        HIP_TRY(hipMemcpyAsync(d->h_counters, a.counters, 16, hipMemcpyDeviceToHost, stream));
+        if (prof) HIP_TRY(hipEventRecord(d->ev[3], stream));
         HIP_TRY(hipStreamSynchronize(stream));
-        if (prof) HIP_TRY(hipEventElapsedTime(&d->report.fallback_ms, d->ev[1], d->ev[2]));
     }
-    d->report.overflow_chunks = d->h_counters[0];
-    d->report.chart_bytes = (int64_t)total;
-    if (d->h_counters[2]) return fail(ZF_ERR_OVERFLOW, std::to_string(d->h_counters[2]) + " trie chunks exceeded the fallback arena");
+    return zf_mask_wait(e, hip_stream);
+}
+
+int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream) {
+    return enqueue_mask(e, states, batch, d_mask, hip_stream, true);
+}
+
+int zf_compute_mask_async(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream) {
+    return enqueue_mask(e, states, batch, d_mask, hip_stream, false);
+}
+
+int zf_mask_wait(zf_engine *e, void *hip_stream) {
+    if (!e || !e->dev) return fail(ZF_ERR_INVALID_ARG, "bad argument");
+    DeviceSide *d = e->dev;
+    HIP_TRY(hipSetDevice(d->device));
+    HIP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));
+    uint32_t unresolved = 0;
+    volatile uint32_t *st = d->h_status;
+    for (int k = 0; k < DeviceSide::N_SLOTS; k++) {
+        unresolved += st[4 * k + 2];
+        if (st[4 * k + 0] || st[4 * k + 1]) d->report.overflow_chunks = st[4 * k + 0];
+        st[4 * k + 0] = st[4 * k + 1] = st[4 * k + 2] = st[4 * k + 3] = 0;
+    }
+    if (d->pending && d->profiling) {
+        (void)hipEventElapsedTime(&d->report.main_ms, d->ev[0], d->ev[1]);
+        (void)hipEventElapsedTime(&d->report.fallback_ms, d->ev[1], d->ev[2]);
+        (void)hipEventElapsedTime(&d->report.permute_ms, d->ev[2], d->ev[3]);
+    }
+    d->pending = 0;
+    if (unresolved) return fail(ZF_ERR_OVERFLOW, std::to_string(unresolved) + " trie chunks exceeded the fallback arena");
     return ZF_OK;
 }
 

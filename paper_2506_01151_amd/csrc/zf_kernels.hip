@@ -572,7 +572,10 @@ __global__ __launch_bounds__(64) void mask_fallback_kernel(MaskArgs a) {
 __global__ __launch_bounds__(256) void permute_kernel(MaskArgs a) {
     const DeviceTables &D = a.tab;
     const uint32_t v = blockIdx.x * 256 + threadIdx.x, row = blockIdx.y;
-    if (v < 4 && row == 0) a.counters_next[v] = 0;   // this call's counters are read back after this kernel; the next call uses the other set
+    if (v < 4 && row == 0) {                          // the last kernel of the call: hand the counters to the host, clear the next call's set
+        a.host_status[v] = a.counters[v];
+        a.counters_next[v] = 0;
+    }
     uint32_t bit = 0;
     if (v < (uint32_t)D.V) {
         const uint32_t r = D.rank_of[v];

@@ -27,6 +27,7 @@ struct MaskArgs {
     uint32_t *rank_mask;       // [batch][Wr] verdicts in trie (rank) order
     uint32_t *out_mask;        // [batch][W] verdicts in token-id order
     uint32_t *counters;        // [0] chunks passed to the fallback, [1] length of the work queue, [2] chunks nobody could resolve
+    uint32_t *host_status;     // pinned host memory: this call's counters, written by its last kernel
     uint32_t *counters_next;   // the next call's counters: cleared by this call's last kernel (no separate memset)
     uint4 *work;               // queue of (row, chunk, undecided strings, -) that need the parser walk
     uint4 *overflow_list;      // (row, chunk, undecided strings, -) for the fallback

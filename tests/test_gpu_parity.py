@@ -138,6 +138,51 @@ def test_full_size_configs_replay(idx, rows, steps, every, n_cmp, pruning, torch
     assert n_checked >= 8
 
 
+def test_async_calls_match_the_waiting_call(torch_cuda, oracle_lib):
+    """compute_mask_async + mask_wait: several calls in flight on one stream, apply_mask queued right
+    behind each; results equal the waiting call's and the oracle's; a fifth call in flight is refused;
+    an overflow beyond the fallback arena surfaces in mask_wait."""
+    import paper_2506_01151_amd as zf
+    from oracle.frontend import apply_mask as oracle_apply
+    torch = torch_cuda
+    cfg = configs.CONFIGS[2]
+    toks = cfg.vocab()
+    off, data = wvocab.vocab_csr(toks)
+    g = cfg.grammar()
+    eng = zf.Engine(g, toks, device=0)
+    orc = oracle_lib.Oracle(g)
+    prefixes = [b'{"a', b'[1, 2', b' {"k": "\\', b"tr"]
+    so, ss = [], []
+    for p in prefixes:
+        a, b = orc.new_state(), eng.new_state()
+        assert a.feed_bytes(p)
+        b.advance_bytes(p)
+        so.append(a)
+        ss.append(b)
+    masks = [torch.full((1, eng.W), -1, dtype=torch.int32, device="cuda") for _ in prefixes]
+    logits = configs.make_logits(cfg, 3, device="cuda", batch=1)
+    outs = [torch.empty_like(logits) for _ in prefixes]
+    for i in range(4):
+        zf.compute_mask_async(eng, [ss[i]], masks[i])
+        zf.apply_mask(eng, logits, masks[i], out=outs[i])
+    with pytest.raises(zf.ZfError) as ei:
+        zf.compute_mask_async(eng, [ss[0]], masks[0])
+    assert ei.value.code == zf.ZF_ERR_INVALID_ARG
+    zf.mask_wait(eng)
+    lbits = logits.view(torch.int32).cpu().numpy().view(np.uint32)
+    for i in range(4):
+        want = so[i].mask(off, data, 4)
+        assert (masks[i].cpu().numpy().view(np.uint32)[0] == want).all(), prefixes[i]
+        assert outs[i].view(torch.int32).cpu().numpy().view(np.uint32).tobytes() == oracle_apply(lbits, want[None, :]).tobytes()
+    tiny = zf.Engine(g, toks, device=0, lane_item_cap=1, fallback_item_cap=1)
+    s = tiny.new_state()
+    s.advance_bytes(b'{"a": [1')
+    zf.compute_mask_async(tiny, [s], masks[0])
+    with pytest.raises(zf.ZfError) as ei:
+        zf.mask_wait(tiny)
+    assert ei.value.code == zf.ZF_ERR_OVERFLOW
+
+
 def test_edge_cases(torch_cuda, oracle_lib):
     """Empty tokens, duplicates, a vocabulary smaller than one word, rows in different states,
     a finished sentence (empty mask), V not a multiple of 32."""
