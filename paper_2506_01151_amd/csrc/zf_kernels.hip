@@ -465,9 +465,12 @@ __global__ __launch_bounds__(WALK_BLOCK) void mask_walk_kernel(MaskArgs a) {
     const DeviceTables &D = a.tab;
     const uint32_t tid = threadIdx.x;
     const uint32_t n_work = a.counters[1];
-    if (blockIdx.x * WALK_WAVES >= n_work) return;      // uniform
+    if (blockIdx.x * WALK_TILE >= n_work) return;       // uniform: not even the block's first tile exists
     TV T;
-    const uint32_t off = stage_tables<MODE>(D, smem, T, tid, WALK_BLOCK);
+    uint32_t off = stage_tables<MODE>(D, smem, T, tid, WALK_BLOCK);
+    uint32_t *next_item = reinterpret_cast<uint32_t *>(smem + off);   // the block's counter of items handed out
+    off += 16;
+    if (tid == 0) *next_item = 0;
     __syncthreads();                                     // the only block-wide barrier; below, wavefronts run on their own
     const uint32_t wave = tid >> 6, lane = tid & 63;
     const uint32_t cap = (uint32_t)a.lane_cap;
@@ -481,7 +484,16 @@ __global__ __launch_bounds__(WALK_BLOCK) void mask_walk_kernel(MaskArgs a) {
     st.org = st.pq + cap;
     st.ss = reinterpret_cast<uint16_t *>(st.org + cap);
     st.cap = cap;
-    for (uint32_t g = blockIdx.x * WALK_WAVES + wave; g < n_work; g += gridDim.x * WALK_WAVES) {
+    // The queue is dealt to the blocks in tiles of WALK_TILE consecutive items, round robin; inside a
+    // block the wavefronts take the next item of the block's share whenever they are free (LDS
+    // counter), so that one long walk does not hold up the items behind it.
+    for (;;) {
+        uint32_t k = 0;
+        if (lane == 0) k = atomicAdd(next_item, 1u);
+        k = (uint32_t)__builtin_amdgcn_readfirstlane((int)k);
+        const uint32_t g = ((k / WALK_TILE) * gridDim.x + blockIdx.x) * WALK_TILE + k % WALK_TILE;
+        if ((k / WALK_TILE) * gridDim.x * WALK_TILE >= n_work) break;   // every later tile of this block lies beyond the queue
+        if (g >= n_work) continue;
         const uint4 item = a.work[g];                   // row | node count << 16, chunk, undecided strings, first node
         const uint32_t row = item.x & 0xFFFFu, n_nodes = item.x >> 16, chunk = item.y, want = item.z, begin = item.w;
         const RowChart rc = a.rows[row];
@@ -656,7 +668,7 @@ hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s) {
     return hipGetLastError();
 }
 uint32_t walk_lds_bytes(const DeviceTables &t, int mode, int lane_cap) {
-    return table_bytes(t, mode) + WALK_WAVES * wave_region_bytes((uint32_t)lane_cap);
+    return table_bytes(t, mode) + 16 + WALK_WAVES * wave_region_bytes((uint32_t)lane_cap);
 }
 hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s) {
     const uint32_t lds = walk_lds_bytes(a.tab, a.mode, a.lane_cap);
