@@ -340,35 +340,41 @@ __device__ __forceinline__ bool walk_chunk(const DeviceTables &D, S &st, Step st
     uint32_t bits = 0, cnt = 0;
     st.set_start(1, 0);
     TrieNode nd = node(i);
-    const int d0 = nd.depth;
-    if (d0 > S::max_depth) return false;
-    for (int j = 0; j + 1 < d0; j++) {   // replay the path above the chunk's first node
-        const TrieNode an = anc(j);
-        const int r = step(j + 1, an.byte, an.cls, cnt);
-        if (r & STEP_OVERFLOW) return false;
-        if (!(r & STEP_KERNEL)) {        // that whole subtree is dead
-            i = an.skip; cnt = st.start(j + 1);
-            if (i < end) nd = node(i);
-            break;
-        }
-    }
-    while (i < end) {
+    const int n_anc = nd.depth - 1;                      // first the path above the chunk's first node is replayed
+    if (nd.depth > S::max_depth) return false;
+    int j = 0;
+    for (;;) {                                           // one loop, one call site of the byte step (keeps the code small)
+        const bool warm = j < n_anc;
         const uint32_t nxt = i + 1;
-        TrieNode nx = nd;
-        if (nxt < end) nx = node(nxt);                   // issued before the step so that it overlaps it
-        const int d = nd.depth;
-        uint32_t ni;
-        const uint32_t rel = nd.rank - rank0;
-        const uint32_t span = (nd.n_sub >= 32u ? 0xFFFFFFFFu : ((1u << nd.n_sub) - 1u)) << rel;
-        if (!(span & want)) ni = nd.skip;                // nothing to decide below this node
+        TrieNode cur, nx = nd;
+        uint32_t rel = 0;
+        bool do_step = true;
+        if (warm) cur = anc(j);
         else {
-            if (d > S::max_depth) return false;
-            cnt = st.start(d);                           // forget the sets of the deeper path we came from
-            const int r = step(d, nd.byte, nd.cls, cnt);
-            if (r & STEP_OVERFLOW) return false;
-            if (nd.has_string && (r & STEP_ALIVE)) bits |= 1u << rel;
-            ni = (r & STEP_KERNEL) ? nxt : nd.skip;
+            if (i >= end) break;
+            cur = nd;
+            if (nxt < end) nx = node(nxt);               // issued before the step so that it overlaps it
+            rel = cur.rank - rank0;
+            const uint32_t span = (cur.n_sub >= 32u ? 0xFFFFFFFFu : ((1u << cur.n_sub) - 1u)) << rel;
+            do_step = (span & want) != 0;                // nothing to decide below this node: skip it without a step
+            if (do_step) {
+                if (cur.depth > S::max_depth) return false;
+                cnt = st.start(cur.depth);               // forget the sets of the deeper path we came from
+            }
         }
+        int r = 0;
+        if (do_step) {
+            r = step(warm ? j + 1 : (int)cur.depth, cur.byte, cur.cls, cnt);
+            if (r & STEP_OVERFLOW) return false;
+        }
+        if (warm) {
+            if (r & STEP_KERNEL) { j++; continue; }
+            i = cur.skip; cnt = st.start(j + 1); j = n_anc;   // that whole subtree is dead
+            if (i < end) nd = node(i);
+            continue;
+        }
+        if (cur.has_string && (r & STEP_ALIVE)) bits |= 1u << rel;
+        const uint32_t ni = (r & STEP_KERNEL) ? nxt : cur.skip;
         if (ni == nxt) nd = nx;
         else if (ni < end) nd = node(ni);
         i = ni;
@@ -519,23 +525,16 @@ __global__ __launch_bounds__(WALK_BLOCK) void mask_walk_kernel(MaskArgs a) {
             if (ok) {
                 auto anc = [&](int j) { return l_anc[j]; };
                 auto node = [&](uint32_t i) { return l_nodes[i - begin]; };
-                if (base_fits) {
-                    const Base<const uint32_t *, const uint2 *> B{l_so, l_it, rc.n_sets, l_so[rc.n_sets - 1], rc.n_items};
-                    ok = walk_chunk(D, st, [&](int d, uint32_t byte, uint32_t cl, uint32_t &cnt) {
+                // the row's chart through generic pointers: its LDS copy when it was staged, else global memory
+                const uint32_t *b_so = base_fits ? l_so : g_so;
+                const uint2 *b_it = base_fits ? l_it : g_it;
+                const BaseG B{b_so, b_it, rc.n_sets, b_so[rc.n_sets - 1], rc.n_items};
+                ok = walk_chunk(D, st, [&](int d, uint32_t byte, uint32_t cl, uint32_t &cnt) {
                                         const uint32_t keep = cnt;
                                         int r = wave_step(T, B, st, d, byte, cl, cnt, lane);
                                         if (r & STEP_WIDE) { cnt = keep; r = wave_step_big(T, B, st, d, byte, cl, cnt, lane); }
                                         return r; },
-                                    chunk, want, begin, begin + n_nodes, anc, node, &bits);
-                } else {
-                    const Base<const uint32_t *, const uint2 *> B{g_so, g_it, rc.n_sets, g_so[rc.n_sets - 1], rc.n_items};
-                    ok = walk_chunk(D, st, [&](int d, uint32_t byte, uint32_t cl, uint32_t &cnt) {
-                                        const uint32_t keep = cnt;
-                                        int r = wave_step(T, B, st, d, byte, cl, cnt, lane);
-                                        if (r & STEP_WIDE) { cnt = keep; r = wave_step_big(T, B, st, d, byte, cl, cnt, lane); }
-                                        return r; },
-                                    chunk, want, begin, begin + n_nodes, anc, node, &bits);
-                }
+                                chunk, want, begin, begin + n_nodes, anc, node, &bits);
             }
             if (lane == 0) {
                 if (!ok) {
