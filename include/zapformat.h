@@ -72,6 +72,8 @@ typedef struct {
     int32_t chunk_strings; /* vocabulary strings walked by one lane: 8, 16 or 32; 0 = default */
     int32_t fallback_item_cap; /* item budget of a fallback wavefront (global memory), 0 = default
                                   (65536); tests set it low to provoke ZF_ERR_OVERFLOW */
+    int32_t state_cache_entries; /* state cache (Section 5.2): finished mask rows kept on the device,
+                                  keyed by the row's pruned chart; 0 = default (2048 rows), -1 = off */
     int32_t disable_token_mask_cache; /* 1 = every token goes through the parser walk (Section 4.3
                                   optimisation off); masks are identical either way */
 } zf_options;
@@ -94,6 +96,7 @@ typedef struct {
 typedef struct {               /* facts about the last zf_compute_mask, for reporting only */
     int64_t overflow_chunks;   /* trie chunks handed to the fallback pass in the last call */
     int64_t chart_bytes;       /* bytes uploaded for the last call */
+    int32_t cache_hits, cache_misses; /* rows of the last call served from / added to the state cache */
     float main_ms, fallback_ms, permute_ms; /* kernel durations from HIP events on the call's
                                                stream; 0 unless zf_engine_set_profiling is on */
 } zf_mask_report;
@@ -140,6 +143,8 @@ int zf_compute_mask_async(zf_engine *e, zf_state *const *states /* host array */
                           uint32_t *d_mask, void *hip_stream);
 int zf_mask_wait(zf_engine *e, void *hip_stream);
 int zf_last_mask_report(const zf_engine *e, zf_mask_report *out);
+/* Forget every cached mask row (benchmarks call it to start cold). */
+int zf_engine_clear_state_cache(zf_engine *e);
 /* on != 0: zf_compute_mask brackets each of its kernels with HIP events (a few microseconds
  * of extra host time per call) and zf_last_mask_report returns their durations. */
 int zf_engine_set_profiling(zf_engine *e, int32_t on);

@@ -29,7 +29,7 @@ class VocabDesc(ctypes.Structure):
 
 
 class Options(ctypes.Structure):
-    _fields_ = [("pruning", c_i32), ("lane_item_cap", c_i32), ("device", c_i32), ("chunk_strings", c_i32), ("fallback_item_cap", c_i32), ("disable_token_mask_cache", c_i32)]
+    _fields_ = [("pruning", c_i32), ("lane_item_cap", c_i32), ("device", c_i32), ("chunk_strings", c_i32), ("fallback_item_cap", c_i32), ("state_cache_entries", c_i32), ("disable_token_mask_cache", c_i32)]
 
 
 class Stats(ctypes.Structure):
@@ -43,14 +43,14 @@ class EngineInfo(ctypes.Structure):
 
 
 class MaskReport(ctypes.Structure):
-    _fields_ = [("overflow_chunks", c_i64), ("chart_bytes", c_i64), ("main_ms", ctypes.c_float),
+    _fields_ = [("overflow_chunks", c_i64), ("chart_bytes", c_i64), ("cache_hits", c_i32), ("cache_misses", c_i32), ("main_ms", ctypes.c_float),
                 ("fallback_ms", ctypes.c_float), ("permute_ms", ctypes.c_float)]
 
 
 EXPORTS = ["zf_strerror", "zf_last_error", "zf_compile", "zf_engine_destroy", "zf_engine_get_info",
            "zf_state_new", "zf_state_clone", "zf_state_reset", "zf_state_destroy", "zf_advance",
            "zf_advance_bytes", "zf_is_accepting", "zf_state_stats", "zf_state_chart", "zf_position_info",
-           "zf_compute_mask", "zf_compute_mask_async", "zf_mask_wait", "zf_last_mask_report", "zf_engine_set_profiling", "zf_apply_mask", "zf_debug_host_mask", "zf_debug_host_mask_stats", "zf_debug_host_mask_cached"]
+           "zf_compute_mask", "zf_compute_mask_async", "zf_mask_wait", "zf_last_mask_report", "zf_engine_clear_state_cache", "zf_engine_set_profiling", "zf_apply_mask", "zf_debug_host_mask", "zf_debug_host_mask_stats", "zf_debug_host_mask_cached"]
 
 
 class ZfError(RuntimeError):
@@ -89,6 +89,7 @@ def load_library():
     L.zf_mask_wait.argtypes = [c_vp, c_vp]
     L.zf_last_mask_report.argtypes = [c_vp, c_vp]
     L.zf_engine_set_profiling.argtypes = [c_vp, c_i32]
+    L.zf_engine_clear_state_cache.argtypes = [c_vp]
     L.zf_apply_mask.argtypes = [c_vp, c_vp, c_vp, c_i32, c_i32, c_i64, c_vp, c_vp]
     L.zf_debug_host_mask.argtypes = [c_vp, c_vp, c_vp]
     L.zf_debug_host_mask_stats.argtypes = [c_vp, c_vp, c_vp, c_vp]
@@ -176,7 +177,7 @@ class State:
 class Engine:
     """compile(grammar rules, vocab byte strings)."""
 
-    def __init__(self, grammar, vocab_tokens, *, pruning=True, lane_item_cap=0, device=0, chunk_strings=0, fallback_item_cap=0, token_mask_cache=True):
+    def __init__(self, grammar, vocab_tokens, *, pruning=True, lane_item_cap=0, device=0, chunk_strings=0, fallback_item_cap=0, token_mask_cache=True, state_cache_entries=0):
         load_library()
         csr = grammar.csr()
         self._keep = csr
@@ -188,7 +189,7 @@ class Engine:
         np.cumsum([len(t) for t in vocab_tokens], out=off[1:])
         data = np.frombuffer(b"".join(vocab_tokens) or b"\0", dtype=np.uint8).copy()
         vd = VocabDesc(len(vocab_tokens), off.ctypes.data, data.ctypes.data)
-        opt = Options(int(bool(pruning)), lane_item_cap, device, chunk_strings, fallback_item_cap, int(not token_mask_cache))
+        opt = Options(int(bool(pruning)), lane_item_cap, device, chunk_strings, fallback_item_cap, state_cache_entries, int(not token_mask_cache))
         h = c_vp()
         self.h = None
         _check(_lib.zf_compile(ctypes.byref(gd), ctypes.byref(vd), ctypes.byref(opt), ctypes.byref(h)))
@@ -222,6 +223,9 @@ class Engine:
 
     def mask_wait(self, stream: int = 0):
         _check(_lib.zf_mask_wait(self.h, stream))
+
+    def clear_state_cache(self):
+        _check(_lib.zf_engine_clear_state_cache(self.h))
 
     def set_profiling(self, on: bool):
         _check(_lib.zf_engine_set_profiling(self.h, int(on)))

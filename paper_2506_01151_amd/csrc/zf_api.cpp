@@ -2,6 +2,7 @@
 // upload, kernel launches.
 #include <hip/hip_runtime_api.h>
 #include <cstring>
+#include <unordered_map>
 #include <new>
 #include "zf_internal.h"
 #include "zf_launch.h"
@@ -25,6 +26,12 @@ struct DeviceSide {
     hipEvent_t stage_done[N_SLOTS] = {nullptr, nullptr, nullptr, nullptr};   // the slot's upload has been consumed
     uint32_t *h_status = nullptr;                    // pinned, [N_SLOTS][4]: counters written by each call's last kernel
     uint32_t next_slot = 0, pending = 0;
+    // State cache (paper Section 5.2): finished token-order mask rows keyed by the row's packed chart.
+    struct CacheEntry { uint64_t hash = 0; std::vector<uint32_t> key; uint32_t stamp = 0; bool used = false; };
+    std::vector<CacheEntry> cache;                   // one per pool slot
+    std::unordered_multimap<uint64_t, uint32_t> cache_index;
+    uint32_t *d_pool = nullptr;                      // [cache.size()][W]
+    uint32_t cache_victim = 0, cache_call = 0;
     uint32_t *d_rank_mask = nullptr; size_t rank_cap = 0;
     uint4 *d_overflow = nullptr; size_t overflow_cap = 0;
     uint4 *d_work = nullptr;
@@ -67,6 +74,7 @@ void free_device(DeviceSide *d) {
     if (d->d_chart) (void)hipFree(d->d_chart);
     for (int k = 0; k < DeviceSide::N_SLOTS; k++) { if (d->h_stage[k]) (void)hipHostFree(d->h_stage[k]); if (d->stage_done[k]) (void)hipEventDestroy(d->stage_done[k]); }
     if (d->h_status) (void)hipHostFree(d->h_status);
+    if (d->d_pool) (void)hipFree(d->d_pool);
     if (d->d_rank_mask) (void)hipFree(d->d_rank_mask);
     if (d->d_overflow) (void)hipFree(d->d_overflow);
     if (d->d_work) (void)hipFree(d->d_work);
@@ -103,6 +111,10 @@ int setup_device(zf_engine *e) {
     d->mode = choose_table_mode(T);
     HIP_TRY(prepare_kernels());
     HIP_TRY(hipDeviceGetAttribute(&d->cus, hipDeviceAttributeMultiprocessorCount, d->device));
+    if (e->opt.state_cache_entries > 0 && e->W > 0) {
+        d->cache.resize(e->opt.state_cache_entries);
+        HIP_TRY(hipMalloc((void **)&d->d_pool, (size_t)e->opt.state_cache_entries * e->W * 4));
+    }
     if (walk_lds_bytes(T, d->mode, e->opt.lane_item_cap) > 160u * 1024u)
         return fail(ZF_ERR_INVALID_ARG, "lane_item_cap and the grammar tables do not fit the 160 KB of LDS");
     HIP_TRY(hipMalloc((void **)&d->d_counters, 32));
@@ -184,11 +196,14 @@ int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_option
     }
     zf_engine *e = new (std::nothrow) zf_engine();
     if (!e) return fail(ZF_ERR_OOM, "out of memory");
-    e->opt = opt ? *opt : zf_options{1, 0, 0, 0, 0, 0};
+    e->opt = opt ? *opt : zf_options{1, 0, 0, 0, 0, 0, 0};
     e->lane_cap_auto = e->opt.lane_item_cap <= 0;
     if (e->opt.lane_item_cap <= 0) e->opt.lane_item_cap = LANE_CAP_DEFAULT;
     if (e->opt.lane_item_cap > LANE_CAP_MAX) e->opt.lane_item_cap = LANE_CAP_MAX;
     if (e->opt.fallback_item_cap <= 0 || e->opt.fallback_item_cap > FB_ITEMS_PER_WAVE) e->opt.fallback_item_cap = FB_ITEMS_PER_WAVE;
+    if (e->opt.state_cache_entries == 0) e->opt.state_cache_entries = 2048;
+    if (e->opt.state_cache_entries < 0) e->opt.state_cache_entries = 0;
+    if (e->opt.state_cache_entries > 65536) e->opt.state_cache_entries = 65536;
     if (e->opt.chunk_strings != 8 && e->opt.chunk_strings != 16 && e->opt.chunk_strings != 32) e->opt.chunk_strings = 8;
     try {
         if (!build_tables(g, e->tab)) { delete e; return ZF_ERR_GRAMMAR; }
@@ -373,7 +388,7 @@ int zf_debug_host_mask_stats(zf_engine *e, const zf_state *s, uint32_t *mask, in
 // fallback pass is launched only if the walk reported overflow (one extra host round trip in that
 // rare case) and the call returns the final status; wait = false: the fallback pass is always
 // enqueued and the status is left for zf_mask_wait.
-static int enqueue_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait) {
+static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait) {
     if (!e || !states || batch <= 0 || batch > MAX_BATCH || !d_mask) return fail(ZF_ERR_INVALID_ARG, "bad argument (batch must be 1..4096)");
     DeviceSide *d = e->dev;
     if (!d) return fail(ZF_ERR_DEVICE, "engine was compiled without a device (device = -1)");
@@ -382,20 +397,71 @@ static int enqueue_mask(zf_engine *e, zf_state *const *states, int32_t batch, ui
     if (d->pending >= (uint32_t)DeviceSide::N_SLOTS) return fail(ZF_ERR_INVALID_ARG, "too many asynchronous mask calls in flight: call zf_mask_wait");
     const uint32_t slot = d->next_slot;
     HIP_TRY(hipEventSynchronize(d->stage_done[slot]));   // the slot's previous upload has left the staging buffer
-    // ---- pack the charts: [RowChart x batch][set offsets][items] ----
+    for (int b = 0; b < batch; b++)
+        if (!states[b] || states[b]->eng != e) return fail(ZF_ERR_INVALID_ARG, "state " + std::to_string(b) + " is null or belongs to another engine");
+    // ---- the packed form of every row: [n_sets][set offsets][item word, origin]... (also the cache key) ----
+    static thread_local std::vector<std::vector<uint32_t>> packed;
+    if ((int)packed.size() < batch) packed.resize(batch);
+    for (int b = 0; b < batch; b++) {
+        const Chart &c = states[b]->chart;
+        std::vector<uint32_t> &k = packed[b];
+        k.clear();
+        k.push_back(c.n_sets());
+        k.insert(k.end(), c.set_off.begin(), c.set_off.end());
+        for (const Item &it : c.items) {   // host item -> device item word + origin
+            const uint32_t aw = e->tab.advpq[it.p];
+            k.push_back((aw & IW_TERM) ? ((aw & 0xFFFFu) | ((uint32_t)it.q << 16)) : aw);
+            k.push_back(it.o);
+        }
+    }
+    // ---- state cache: rows whose chart has been seen before only need their finished mask copied ----
+    const bool sc = !d->cache.empty() && (size_t)batch * 2 <= d->cache.size();
+    static thread_local std::vector<uint32_t> row_slot, miss_rows;
+    row_slot.assign(batch, 0);
+    miss_rows.clear();
+    int n_hits = 0;
+    if (sc) {
+        const uint32_t call = ++d->cache_call;
+        for (int b = 0; b < batch; b++) {
+            const std::vector<uint32_t> &k = packed[b];
+            uint64_t h = 0xCBF29CE484222325ull;
+            for (uint32_t w : k) { h ^= w; h *= 0x100000001B3ull; h ^= h >> 29; }
+            uint32_t found = 0xFFFFFFFFu;
+            auto range = d->cache_index.equal_range(h);
+            for (auto it = range.first; it != range.second; ++it) if (d->cache[it->second].key == k) { found = it->second; break; }
+            if (found == 0xFFFFFFFFu) {
+                while (d->cache[d->cache_victim].used && d->cache[d->cache_victim].stamp == call) d->cache_victim = (d->cache_victim + 1) % d->cache.size();
+                found = d->cache_victim;
+                d->cache_victim = (d->cache_victim + 1) % d->cache.size();
+                DeviceSide::CacheEntry &ce = d->cache[found];
+                if (ce.used) {   // evict
+                    auto r2 = d->cache_index.equal_range(ce.hash);
+                    for (auto it = r2.first; it != r2.second; ++it) if (it->second == found) { d->cache_index.erase(it); break; }
+                }
+                ce.hash = h; ce.key = k; ce.used = true;
+                d->cache_index.emplace(h, found);
+                miss_rows.push_back((uint32_t)b);
+            } else n_hits++;
+            d->cache[found].stamp = call;
+            row_slot[b] = found;
+        }
+    } else for (int b = 0; b < batch; b++) miss_rows.push_back((uint32_t)b);
+    const int nb = (int)miss_rows.size();                // rows that go through the kernels
+    d->report.cache_hits = n_hits; d->report.cache_misses = sc ? nb : 0;
+    // ---- upload: [RowChart x nb][set offsets][items][cache rows of the token-mask cache][dst slot x nb][row slot x batch] ----
     size_t n_off = 0, n_items = 0, n_ent = 0;
     const bool use_cache = !e->opt.disable_token_mask_cache;
-    for (int b = 0; b < batch; b++) {
-        if (!states[b] || states[b]->eng != e) return fail(ZF_ERR_INVALID_ARG, "state " + std::to_string(b) + " is null or belongs to another engine");
-        const Chart &c = states[b]->chart;
+    for (int r = 0; r < nb; r++) {
+        const Chart &c = states[miss_rows[r]]->chart;
         n_off += c.set_off.size();
         n_items += c.items.size();
         if (use_cache) n_ent += c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1];
     }
     auto align16 = [](size_t x) { return (x + 15) & ~(size_t)15; };
-    const size_t off_rows = 0, off_so = align16(sizeof(RowChart) * batch), off_items = align16(off_so + 4 * n_off);
+    const size_t off_rows = 0, off_so = align16(sizeof(RowChart) * nb), off_items = align16(off_so + 4 * n_off);
     const size_t off_ent = align16(off_items + sizeof(Item) * n_items);
-    const size_t total = off_ent + 4 * n_ent + 16;
+    const size_t off_dst = align16(off_ent + 4 * n_ent), off_rowslot = align16(off_dst + 4 * (size_t)nb);
+    const size_t total = off_rowslot + 4 * (size_t)batch + 16;
     if (total > d->stage_cap[slot]) {
         if (d->h_stage[slot]) (void)hipHostFree(d->h_stage[slot]);
         d->h_stage[slot] = nullptr; d->stage_cap[slot] = 0;
@@ -417,26 +483,25 @@ static int enqueue_mask(zf_engine *e, zf_state *const *states, int32_t batch, ui
         uint32_t *so = (uint32_t *)(h + off_so);
         uint32_t *dev_items = (uint32_t *)(h + off_items);
         uint32_t *ents = (uint32_t *)(h + off_ent);
+        uint32_t *dst = (uint32_t *)(h + off_dst);
+        memcpy(h + off_rowslot, row_slot.data(), 4 * (size_t)batch);
         uint32_t so_at = 0, it_at = 0, en_at = 0;
-        for (int b = 0; b < batch; b++) {
-            const Chart &c = states[b]->chart;
-            rows[b] = RowChart{c.n_sets(), so_at, it_at, en_at, 0, (uint32_t)c.items.size(), {0, 0}};
-            if (use_cache) rows[b].n_ent = current_set_entries(e->tab, c, ents + en_at);
-            en_at += rows[b].n_ent;
-            memcpy(so + so_at, c.set_off.data(), 4 * c.set_off.size());
-            for (size_t i = 0; i < c.items.size(); i++) {   // host item -> device item word + origin
-                const uint32_t aw = e->tab.advpq[c.items[i].p];
-                const uint32_t w = (aw & IW_TERM) ? ((aw & 0xFFFFu) | ((uint32_t)c.items[i].q << 16)) : aw;
-                dev_items[2 * (it_at + i)] = w;
-                dev_items[2 * (it_at + i) + 1] = c.items[i].o;
-            }
+        for (int r = 0; r < nb; r++) {
+            const Chart &c = states[miss_rows[r]]->chart;
+            const std::vector<uint32_t> &k = packed[miss_rows[r]];
+            rows[r] = RowChart{c.n_sets(), so_at, it_at, en_at, 0, (uint32_t)c.items.size(), {0, 0}};
+            if (use_cache) rows[r].n_ent = current_set_entries(e->tab, c, ents + en_at);
+            en_at += rows[r].n_ent;
+            memcpy(so + so_at, k.data() + 1, 4 * c.set_off.size());
+            memcpy(dev_items + 2 * (size_t)it_at, k.data() + 1 + c.set_off.size(), 8 * c.items.size());
             so_at += (uint32_t)c.set_off.size(); it_at += (uint32_t)c.items.size();
+            dst[r] = sc ? row_slot[miss_rows[r]] : miss_rows[r];
         }
     }
     HIP_TRY(hipMemcpyAsync(d->d_chart, d->h_stage[slot], total, hipMemcpyHostToDevice, stream));
     HIP_TRY(hipEventRecord(d->stage_done[slot], stream));
     // ---- per-call device buffers ----
-    const size_t need_rank = (size_t)batch * d->tab.Wr, need_ovf = (size_t)batch * d->tab.n_chunks;
+    const size_t need_rank = (size_t)std::max(nb, 1) * d->tab.Wr, need_ovf = (size_t)std::max(nb, 1) * d->tab.n_chunks;
     if (need_rank > d->rank_cap || need_ovf > d->overflow_cap) {
         HIP_TRY(hipStreamSynchronize(stream));
         if (d->d_rank_mask) (void)hipFree(d->d_rank_mask);
@@ -455,7 +520,12 @@ static int enqueue_mask(zf_engine *e, zf_state *const *states, int32_t batch, ui
     a.items = (const Item *)((uint8_t *)d->d_chart + off_items);
     a.entries = (const uint32_t *)((uint8_t *)d->d_chart + off_ent);
     a.rank_mask = d->d_rank_mask;
-    a.out_mask = d_mask;
+    a.out_mask = sc ? d->d_pool : d_mask;                 // with the state cache the rows are finished in their pool slots
+    a.dst_row = (const uint32_t *)((uint8_t *)d->d_chart + off_dst);
+    a.row_slot = (const uint32_t *)((uint8_t *)d->d_chart + off_rowslot);
+    a.user_mask = d_mask;
+    a.user_batch = batch;
+    a.handoff_in_permute = sc ? 0 : 1;
     a.counters = d->d_counters + 4 * d->call_parity;
     a.counters_next = d->d_counters + 4 * (d->call_parity ^ 1u);
     d->call_parity ^= 1u;
@@ -465,14 +535,14 @@ static int enqueue_mask(zf_engine *e, zf_state *const *states, int32_t batch, ui
     a.overflow_cap = (uint32_t)d->overflow_cap;
     a.fb_items = d->d_fb_items;
     a.fb_set_start = d->d_fb_ss;
-    a.batch = batch;
+    a.batch = nb;
     // Item budget of a walking wavefront: the configured one, raised for this call when the rows'
     // current sets are large (ambiguous grammars) so that such rows do not all end in the fallback.
     a.lane_cap = e->opt.lane_item_cap;
     if (e->lane_cap_auto) {
         size_t widest = 0;
-        for (int b = 0; b < batch; b++) {
-            const Chart &c = states[b]->chart;
+        for (int r = 0; r < nb; r++) {
+            const Chart &c = states[miss_rows[r]]->chart;
             widest = std::max<size_t>(widest, c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1]);
         }
         size_t want_cap = (8 * widest + 64 + 31) / 32 * 32;
@@ -490,13 +560,15 @@ static int enqueue_mask(zf_engine *e, zf_state *const *states, int32_t batch, ui
     const bool prof = d->profiling;
     d->report.chart_bytes = (int64_t)total;
     d->report.main_ms = d->report.fallback_ms = d->report.permute_ms = 0.f;
-    if (d->tab.n_chunks > 0) HIP_TRY(launch_cache_merge(a, stream));
+    const bool run_kernels = nb > 0;
+    if (run_kernels && d->tab.n_chunks > 0) HIP_TRY(launch_cache_merge(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
-    if (d->tab.n_chunks > 0) HIP_TRY(launch_mask_walk(a, stream));
+    if (run_kernels && d->tab.n_chunks > 0) HIP_TRY(launch_mask_walk(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));
-    if (!wait && d->tab.n_chunks > 0) HIP_TRY(launch_mask_fallback(a, stream));
+    if (run_kernels && !wait && d->tab.n_chunks > 0) HIP_TRY(launch_mask_fallback(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[2], stream));
-    HIP_TRY(launch_permute(a, stream));                   // also hands the counters to the host and clears the next call's
+    if (run_kernels) HIP_TRY(launch_permute(a, stream));  // the call's last kernel also hands the counters to the host and clears the next call's
+    if (sc) HIP_TRY(launch_gather(a, stream));            // every row's finished mask from its pool slot to the caller's tensor
     if (prof) HIP_TRY(hipEventRecord(d->ev[3], stream));
     d->next_slot = (slot + 1) % DeviceSide::N_SLOTS;
     d->pending++;
@@ -509,10 +581,23 @@ static int enqueue_mask(zf_engine *e, zf_state *const *states, int32_t batch, ui
         HIP_TRY(launch_mask_fallback(a, stream));
         if (prof) HIP_TRY(hipEventRecord(d->ev[2], stream));
         HIP_TRY(launch_permute(a, stream));
+        if (sc) HIP_TRY(launch_gather(a, stream));
         if (prof) HIP_TRY(hipEventRecord(d->ev[3], stream));
         HIP_TRY(hipStreamSynchronize(stream));
     }
     return zf_mask_wait(e, hip_stream);
+}
+
+static void forget_cached_masks(DeviceSide *d) {
+    d->cache_index.clear();
+    for (auto &ce : d->cache) ce.used = false;
+}
+
+// A call that fails part-way may have registered cache slots whose masks were never written.
+static int enqueue_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait) {
+    const int rc = enqueue_mask_impl(e, states, batch, d_mask, hip_stream, wait);
+    if (rc != ZF_OK && e && e->dev) forget_cached_masks(e->dev);
+    return rc;
 }
 
 int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream) {
@@ -541,7 +626,14 @@ int zf_mask_wait(zf_engine *e, void *hip_stream) {
         (void)hipEventElapsedTime(&d->report.permute_ms, d->ev[2], d->ev[3]);
     }
     d->pending = 0;
+    if (unresolved) forget_cached_masks(d);               // masks written by the failed call must not be served from the cache
     if (unresolved) return fail(ZF_ERR_OVERFLOW, std::to_string(unresolved) + " trie chunks exceeded the fallback arena");
+    return ZF_OK;
+}
+
+int zf_engine_clear_state_cache(zf_engine *e) {
+    if (!e) return fail(ZF_ERR_INVALID_ARG, "null argument");
+    if (e->dev) forget_cached_masks(e->dev);
     return ZF_OK;
 }
 

@@ -583,7 +583,7 @@ __global__ __launch_bounds__(64) void mask_fallback_kernel(MaskArgs a) {
 __global__ __launch_bounds__(256) void permute_kernel(MaskArgs a) {
     const DeviceTables &D = a.tab;
     const uint32_t v = blockIdx.x * 256 + threadIdx.x, row = blockIdx.y;
-    if (v < 4 && row == 0) {                          // the last kernel of the call: hand the counters to the host, clear the next call's set
+    if (a.handoff_in_permute && v < 4 && row == 0) {  // the last kernel of the call: hand the counters to the host, clear the next call's set
         a.host_status[v] = a.counters[v];
         a.counters_next[v] = 0;
     }
@@ -596,8 +596,19 @@ __global__ __launch_bounds__(256) void permute_kernel(MaskArgs a) {
     const uint32_t lane = threadIdx.x & 63;
     if ((lane & 31) == 0) {
         const uint32_t w = v >> 5;
-        if (w < (uint32_t)D.W) a.out_mask[(size_t)row * D.W + w] = (uint32_t)(b >> lane);
+        if (w < (uint32_t)D.W) a.out_mask[(size_t)a.dst_row[row] * D.W + w] = (uint32_t)(b >> lane);
     }
+}
+
+// State cache (Section 5.2): copy every row's finished mask from its pool slot to the caller's
+// tensor.  When the cache is on this is the call's last kernel.
+__global__ __launch_bounds__(256) void gather_kernel(MaskArgs a) {
+    const uint32_t w = blockIdx.x * 256 + threadIdx.x, row = blockIdx.y, W = (uint32_t)a.tab.W;
+    if (w < 4 && row == 0) {
+        a.host_status[w] = a.counters[w];
+        a.counters_next[w] = 0;
+    }
+    if (w < W) a.user_mask[(size_t)row * W + w] = a.out_mask[(size_t)a.row_slot[row] * W + w];
 }
 
 // Logit masking (Section 3.3): pure copy-or-(-inf).  16-byte accesses, consecutive lanes on
@@ -684,6 +695,12 @@ hipError_t launch_mask_fallback(const MaskArgs &a, hipStream_t s) {
 hipError_t launch_permute(const MaskArgs &a, hipStream_t s) {
     dim3 grid((a.tab.V + 255) / 256, a.batch);
     hipLaunchKernelGGL(permute_kernel, grid, dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather(const MaskArgs &a, hipStream_t s) {
+    dim3 grid((a.tab.W + 255) / 256 > 0 ? (a.tab.W + 255) / 256 : 1, a.user_batch);
+    hipLaunchKernelGGL(gather_kernel, grid, dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

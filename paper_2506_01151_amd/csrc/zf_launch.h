@@ -26,7 +26,12 @@ struct MaskArgs {
     const Item *items;         // shared item array of all rows
     const uint32_t *entries;   // shared array of token-mask-cache rows (see RowChart)
     uint32_t *rank_mask;       // [batch][Wr] verdicts in trie (rank) order
-    uint32_t *out_mask;        // [batch][W] verdicts in token-id order
+    uint32_t *out_mask;        // token-order rows: the caller's tensor, or the state cache's pool
+    const uint32_t *dst_row;   // [batch] row of out_mask that row r of this launch is written to
+    const uint32_t *row_slot;  // [user_batch] pool slot that holds the finished mask of each of the caller's rows
+    uint32_t *user_mask;       // the caller's [user_batch][W] tensor (target of the gather)
+    int32_t user_batch;
+    int32_t handoff_in_permute; // 1: permute is the call's last kernel (state cache off), else the gather is
     uint32_t *counters;        // [0] chunks passed to the fallback, [1] length of the work queue, [2] chunks nobody could resolve
     uint32_t *host_status;     // pinned host memory: this call's counters, written by its last kernel
     uint32_t *counters_next;   // the next call's counters: cleared by this call's last kernel (no separate memset)
@@ -49,6 +54,7 @@ hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_fallback(const MaskArgs &a, hipStream_t s);
 hipError_t launch_permute(const MaskArgs &a, hipStream_t s);
+hipError_t launch_gather(const MaskArgs &a, hipStream_t s);
 hipError_t launch_apply_mask(const void *logits, void *out, int dtype, int batch, int64_t row_stride, int V, int W,
                              const uint32_t *mask, hipStream_t s);
 

@@ -18,6 +18,7 @@ def torch_cuda():
 
 
 def _run_parity(torch, zf, Oracle, grammar, tokens, batch, steps, seed, check_every=1, **engine_kw):
+    engine_kw.setdefault("state_cache_entries", -1)      # every step through the kernels unless a test asks for the state cache
     eng = zf.Engine(grammar, tokens, device=0, **engine_kw)
     orc = Oracle(grammar)
     run = OracleRun(orc, tokens, [stream(seed, f"sample[{b}]") for b in range(batch)])
@@ -111,7 +112,7 @@ def test_full_size_configs_replay(idx, rows, steps, every, n_cmp, pruning, torch
     off, data = wvocab.vocab_csr(toks)
     traj = load_trajectory(idx, rows, steps)
     g = cfg.grammar()
-    eng = zf.Engine(g, toks, device=0, pruning=pruning is not False, token_mask_cache=pruning is not None)
+    eng = zf.Engine(g, toks, device=0, pruning=pruning is not False, token_mask_cache=pruning is not None, state_cache_entries=-1)
     orc = oracle_lib.Oracle(g)
     so = [orc.new_state() for _ in range(rows)]
     ss = [eng.new_state() for _ in range(rows)]
@@ -136,6 +137,92 @@ def test_full_size_configs_replay(idx, rows, steps, every, n_cmp, pruning, torch
                 assert (got[b] == want).all(), f"cfg{idx} step {step} row {b}"
                 n_checked += 1
     assert n_checked >= 8
+
+
+STATE_CACHE = [  # config, rows, steps, compare every, cache rows (0 = default), expect the cache to be used
+    (3, 16, 512, 29, 0, True),
+    (3, 16, 512, 41, 32, True),     # the smallest cache a batch of 16 may use: constant eviction
+    (3, 16, 128, 17, 16, False),    # too small for the batch: bypassed
+    (4, 64, 256, 37, 256, True),
+]
+
+
+@pytest.mark.parametrize("idx,rows,steps,every,entries,used", STATE_CACHE, ids=[f"cfg{r[0]}-{r[4] or 'default'}" for r in STATE_CACHE])
+def test_state_cache_replay(idx, rows, steps, every, entries, used, torch_cuda, oracle_lib):
+    """State cache (Section 5.2) on: compute_mask at every step of the trajectory, so that rows are
+    served from cached masks as in real decoding; at sampled steps every row equals the oracle."""
+    import paper_2506_01151_amd as zf
+    torch = torch_cuda
+    cfg = configs.CONFIGS[idx]
+    toks = cfg.vocab()
+    off, data = wvocab.vocab_csr(toks)
+    traj = load_trajectory(idx, rows, steps)
+    g = cfg.grammar()
+    eng = zf.Engine(g, toks, device=0, state_cache_entries=entries)
+    orc = oracle_lib.Oracle(g)
+    so = [orc.new_state() for _ in range(rows)]
+    ss = [eng.new_state() for _ in range(rows)]
+    d_mask = torch.empty((rows, eng.W), dtype=torch.int32, device="cuda")
+    hits = misses = 0
+    for step, ids in enumerate(traj):
+        for b, t in enumerate(ids):
+            if t < 0:
+                so[b] = orc.new_state()
+                ss[b].reset()
+            else:
+                assert so[b].feed_bytes(toks[t])
+                ss[b].advance(t)
+        d_mask.fill_(0x33333333)
+        zf.compute_mask(eng, ss, d_mask)
+        r = eng.mask_report()
+        assert r.cache_hits + r.cache_misses == (rows if used else 0)
+        hits += r.cache_hits
+        misses += r.cache_misses
+        if step % every == 0 or step == steps - 1:
+            got = d_mask.cpu().numpy().view(np.uint32)
+            for b in range(rows):
+                want = so[b].mask(off, data, 16)
+                assert (got[b] == want).all(), f"cfg{idx} step {step} row {b} (hits so far {hits}, misses {misses})"
+    if used:
+        assert hits > misses > 0
+
+
+def test_state_cache_rows_in_one_call_and_clearing(torch_cuda, oracle_lib):
+    """Equal rows of one call are computed once; clearing the cache makes the next call start cold;
+    a failed call leaves nothing behind that a later call could be served from."""
+    import paper_2506_01151_amd as zf
+    torch = torch_cuda
+    cfg = configs.CONFIGS[2]
+    toks = cfg.vocab()
+    off, data = wvocab.vocab_csr(toks)
+    g = cfg.grammar()
+    eng = zf.Engine(g, toks, device=0)
+    orc = oracle_lib.Oracle(g)
+    o = orc.new_state()
+    assert o.feed_bytes(b'{"key": [1, {"x": "a')
+    want = o.mask(off, data, 4)
+    ss = [eng.new_state() for _ in range(8)]
+    for s in ss:
+        s.advance_bytes(b'{"key": [1, {"x": "a')
+    d_mask = torch.empty((8, eng.W), dtype=torch.int32, device="cuda")
+    for expect in [(7, 1), (8, 0), None, (7, 1)]:
+        if expect is None:
+            eng.clear_state_cache()
+            continue
+        d_mask.fill_(0)
+        zf.compute_mask(eng, ss, d_mask)
+        r = eng.mask_report()
+        assert (r.cache_hits, r.cache_misses) == expect
+        assert (d_mask.cpu().numpy().view(np.uint32) == want[None, :]).all()
+    # same prefix through an engine whose budgets are too small: the error must not poison its cache
+    tiny = zf.Engine(g, toks, device=0, lane_item_cap=1, fallback_item_cap=1)
+    t = tiny.new_state()
+    t.advance_bytes(b'{"a": [1')
+    for _ in range(2):
+        with pytest.raises(zf.ZfError) as ei:
+            zf.compute_mask(tiny, [t], d_mask[:1])
+        assert ei.value.code == zf.ZF_ERR_OVERFLOW
+        assert tiny.mask_report().cache_misses == 1
 
 
 def test_async_calls_match_the_waiting_call(torch_cuda, oracle_lib):
