@@ -92,6 +92,34 @@ def cpu_baseline(cfg, toks, traj, budget_s=15.0):
             "sample": f"{n_masks} masks: all {rows} rows at {len(sample_steps)} steps (every {stride}th) of the same trajectory, {spent:.1f} s"}
 
 
+def apply_mask_sweep(zf, eng, torch, dtype, batches=(16, 64, 256, 1024), launches=24):
+    """apply_mask alone at growing batch: each launch works on rows it has not touched for more than
+    1.5 GB of traffic (input and output rotate through 3072-row tensors), so nothing is served from
+    the last-level cache.  HIP events on the launch stream around `launches` back-to-back calls."""
+    V, W = eng.V, eng.W
+    R = 3072
+    x = torch.randn((R, V), dtype=torch.float32, device="cuda").to(dtype) if dtype != torch.float32 else torch.randn((R, V), device="cuda")
+    y = torch.empty_like(x)
+    m = torch.randint(-2**31, 2**31 - 1, (R, W), dtype=torch.int32, device="cuda")
+    esz = x.element_size()
+    rows = []
+    for B in batches:
+        at = 0
+        for timed in (False, True):
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(launches):
+                zf.apply_mask(eng, x[at:at + B], m[at:at + B], out=y[at:at + B])
+                at = (at + B) % R
+            e1.record()
+            torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / launches
+        nbytes = 2 * B * V * esz + B * W * 4
+        rows.append({"batch": B, "us_per_launch": us, "GB/s": nbytes / us / 1e3, "frac": nbytes / us / 1e3 / HBM_PEAK_GBS})
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -100,6 +128,9 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pruning", type=int, default=1)
+    ap.add_argument("--headline-only", action="store_true",
+                    help="run the warm-up and timed steps of the headline pass and nothing else (for hardware-counter runs, "
+                         "where every dispatch of a kernel should belong to the same workload); prints a short JSON line")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="only run apply_mask with an all-ones mask on a [1024, V] tensor three times: a plain copy of known "
                          "size, used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -187,6 +218,9 @@ def main():
         return total, lat, adv, kern, ovf, eng.mask_report().chart_bytes, hits
 
     total, lat, adv, _, _, _, _ = run(eng, Wm, K, False)
+    if args.headline_only:
+        print(json.dumps({"headline_only": True, "steps": K, "warmup": Wm, "ms_per_step": total / K * 1e3, "value": B * V * K / total}))
+        return
     _, _, _, kern, ovf, chart_bytes, _ = run(eng, Wm, K, True)     # same steps again with HIP events around each kernel
     # the same steps with the state cache (Section 5.2) on, starting cold: reported beside the headline
     eng_sc = zf.Engine(cfg.grammar(), toks, device=0, pruning=bool(args.pruning))
@@ -228,6 +262,8 @@ def main():
                                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": apply_bytes / (apply_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                 "traffic": None, "algorithmic_bytes": apply_bytes},
     }
+    result["apply_mask_sweep"] = {"dtype": str(logits[0].dtype).replace("torch.", ""), "V": V, "bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                  "rows": apply_mask_sweep(zf, eng, torch, logits[0].dtype)}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, toks, traj[:K])
     print(json.dumps(result))

@@ -95,6 +95,7 @@ typedef struct {
 
 typedef struct {               /* facts about the last zf_compute_mask, for reporting only */
     int64_t overflow_chunks;   /* trie chunks handed to the fallback pass in the last call */
+    int64_t walk_chunks;       /* trie chunks the token-mask cache left undecided: walked by the parser kernel */
     int64_t chart_bytes;       /* bytes uploaded for the last call */
     int32_t cache_hits, cache_misses; /* rows of the last call served from / added to the state cache */
     float main_ms, fallback_ms, permute_ms; /* kernel durations from HIP events on the call's
@@ -164,7 +165,8 @@ int zf_debug_host_mask(zf_engine *e, const zf_state *s, uint32_t *mask /* host [
 int zf_debug_host_mask_stats(zf_engine *e, const zf_state *s, uint32_t *mask /* host [W] */, int64_t *stats);
 /* Diagnostic: host walk that first merges the context-independent token-mask cache (Section
  * 4.3) of the current set's items and sends only the undecided strings through the parser, as
- * the kernel does.  stats[0..2] (host, may be null): byte steps, undecided strings, cache rows. */
+ * the kernel does.  stats[0..4] (host, may be null): byte steps, undecided strings, cache rows,
+ * byte steps the chunk-wise kernel adds by replaying the path above each chunk, chunks walked. */
 int zf_debug_host_mask_cached(zf_engine *e, const zf_state *s, uint32_t *mask /* host [W] */, int64_t *stats);
 
 #ifdef __cplusplus

@@ -43,7 +43,7 @@ class EngineInfo(ctypes.Structure):
 
 
 class MaskReport(ctypes.Structure):
-    _fields_ = [("overflow_chunks", c_i64), ("chart_bytes", c_i64), ("cache_hits", c_i32), ("cache_misses", c_i32), ("main_ms", ctypes.c_float),
+    _fields_ = [("overflow_chunks", c_i64), ("walk_chunks", c_i64), ("chart_bytes", c_i64), ("cache_hits", c_i32), ("cache_misses", c_i32), ("main_ms", ctypes.c_float),
                 ("fallback_ms", ctypes.c_float), ("permute_ms", ctypes.c_float)]
 
 
@@ -166,7 +166,7 @@ class State:
         out = np.zeros(self.engine.W, dtype=np.uint32)
         st = np.zeros(8, dtype=np.int64)
         _check(_lib.zf_debug_host_mask_cached(self.engine.h, self.h, out.ctypes.data, st.ctypes.data))
-        return out, dict(steps=int(st[0]), undecided=int(st[1]), cache_rows=int(st[2]))
+        return out, dict(steps=int(st[0]), undecided=int(st[1]), cache_rows=int(st[2]), replay_steps=int(st[3]), chunks=int(st[4]))
 
     def debug_host_mask(self) -> np.ndarray:
         out = np.zeros(self.engine.W, dtype=np.uint32)

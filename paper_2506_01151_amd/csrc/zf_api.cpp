@@ -99,7 +99,7 @@ int setup_device(zf_engine *e) {
 #define UP(field, vec, bytes) if ((rc = upload(d, vec, &T.field, bytes)) != ZF_OK) return rc
     UP(advpq, t.advpq, &T.small_bytes[0]); UP(cls, cls, &T.small_bytes[1]);
     UP(qinfo, t.qinfo, &T.small_bytes[2]); UP(scan_off, t.scan_off, &T.small_bytes[3]); UP(comp_off, t.comp_off, &T.small_bytes[4]);
-    UP(delta, t.delta_dense, &T.big_bytes[0]); UP(scan_list, t.dev_scan_list, &T.big_bytes[1]); UP(comp_list, t.comp_list, &T.big_bytes[2]);
+    UP(delta, t.delta_dense, &T.big_bytes[0]); UP(scan_list, t.dev_scan_list, &T.big_bytes[1]); UP(comp_list, t.dev_comp_list, &T.big_bytes[2]);
     UP(nodes, tr.nodes, nullptr); UP(parent, tr.parent, nullptr); UP(chunk_begin, tr.chunk_begin, nullptr); UP(chunk_end, tr.chunk_end, nullptr);
     UP(chunk_anc, tr.chunk_anc, nullptr); UP(rank_of, tr.rank_of, nullptr);
     UP(ci_valid, tr.ci_valid, nullptr); UP(ci_cd, tr.ci_cd, nullptr);
@@ -332,11 +332,18 @@ int zf_debug_host_mask_cached(zf_engine *e, const zf_state *s, uint32_t *mask, i
         for (int w = 0; w < tr.Wr; w++) { valid[w] |= tr.ci_valid[(size_t)ents[k] * tr.Wr + w]; want[w] |= tr.ci_cd[(size_t)ents[k] * tr.Wr + w]; }
     for (int w = 0; w < tr.Wr; w++) want[w] &= ~valid[w];
     auto any_in = [&](uint32_t lo, uint32_t hi) { for (uint32_t r = lo; r < hi; r++) if ((want[r >> 5] >> (r & 31)) & 1) return true; return false; };
-    int64_t n_steps = 0, n_wanted = 0;
+    int64_t n_steps = 0, n_wanted = 0, n_replay = 0, n_queued = 0;
     for (int w = 0; w < tr.Wr; w++) n_wanted += __builtin_popcount(want[w]);
+    size_t chunk = 0;
+    int64_t last_counted = -1;
     for (uint32_t i = 0; i < tr.nodes.size();) {
         const TrieNode &nd = tr.nodes[i];
         if (!any_in(nd.rank, nd.rank + nd.n_sub)) { i = nd.skip; continue; }
+        while (chunk + 1 < tr.chunk_begin.size() && tr.chunk_end[chunk] <= i) chunk++;
+        if ((int64_t)chunk != last_counted) {    // the kernel walks chunk by chunk and replays the path above each chunk's first node
+            last_counted = (int64_t)chunk; n_queued++;
+            n_replay += tr.nodes[tr.chunk_begin[chunk]].depth - 1;
+        }
         c.truncate(m0 + nd.depth - 1);
         StepResult r = earley_step(t, c, nd.byte, false, nullptr);
         n_steps++;
@@ -348,7 +355,7 @@ int zf_debug_host_mask_cached(zf_engine *e, const zf_state *s, uint32_t *mask, i
         uint32_t r = tr.rank_of[v];
         if (r != 0xFFFFFFFFu && ((valid[r >> 5] >> (r & 31)) & 1)) mask[v >> 5] |= 1u << (v & 31);
     }
-    if (stats) { stats[0] = n_steps; stats[1] = n_wanted; stats[2] = n_ent; }
+    if (stats) { stats[0] = n_steps; stats[1] = n_wanted; stats[2] = n_ent; stats[3] = n_replay; stats[4] = n_queued; }
     return ZF_OK;
 }
 
@@ -560,6 +567,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     const bool prof = d->profiling;
     d->report.chart_bytes = (int64_t)total;
     d->report.main_ms = d->report.fallback_ms = d->report.permute_ms = 0.f;
+    d->report.overflow_chunks = d->report.walk_chunks = 0;
     const bool run_kernels = nb > 0;
     if (run_kernels && d->tab.n_chunks > 0) HIP_TRY(launch_cache_merge(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
@@ -617,7 +625,7 @@ int zf_mask_wait(zf_engine *e, void *hip_stream) {
     volatile uint32_t *st = d->h_status;
     for (int k = 0; k < DeviceSide::N_SLOTS; k++) {
         unresolved += st[4 * k + 2];
-        if (st[4 * k + 0] || st[4 * k + 1]) d->report.overflow_chunks = st[4 * k + 0];
+        if (st[4 * k + 0] || st[4 * k + 1]) { d->report.overflow_chunks = st[4 * k + 0]; d->report.walk_chunks = st[4 * k + 1]; }
         st[4 * k + 0] = st[4 * k + 1] = st[4 * k + 2] = st[4 * k + 3] = 0;
     }
     if (d->pending && d->profiling) {

@@ -11,7 +11,12 @@
 //   I(Y)     = dotted positions (Z -> alpha . beta) with Z in PRED(Y) and alpha nullable;
 //   SCAN(Y,c)= for positions of I(Y) that stand before a terminal t: (position, delta_t(start, c))
 //              for every byte class c the terminal can start with;
-//   COMP(Y,X)= positions of I(Y) that stand before nonterminal X, already advanced over X.
+//   COMP(Y,X)= what the completion of X does to the predicted items of I(Y): the positions that
+//              stand behind X in I(Y), with nullable symbols skipped -- and, where such a
+//              position is the end of its rule, its left-hand side counts as completed too (same
+//              origin, the set that predicted it) and is followed up here, at compile time.  The
+//              list holds the resulting items and, if Y itself is among the completed
+//              nonterminals, a marker that tells the recognizer to advance the waiting item.
 // Nullable nonterminals are handled when an item is added: the item is also added with the dot
 // moved over the nullable symbol (Aycock-Horspool), so no epsilon rule survives at run time.
 #include <algorithm>
@@ -246,9 +251,33 @@ bool build_tables(const zf_grammar_desc *g, Tables &t) {
     t.scan_off[(size_t)N * t.n_cls] = (uint32_t)t.scan_list.size();
     for (int Y = 0; Y < N; Y++) for (int X = 0; X < N; X++) {
         t.comp_off[(size_t)Y * N + X] = (uint32_t)t.comp_list.size();
-        t.comp_list.insert(t.comp_list.end(), comp_tmp[Y][X].begin(), comp_tmp[Y][X].end());
+        if (!t.reach[(size_t)Y * N + X]) continue;       // no item predicted by Y waits for X or for anything X leads to
+        std::vector<uint8_t> completed(N, 0);
+        std::vector<int> work{X};
+        std::vector<uint16_t> out;
+        completed[X] = 1;
+        bool y_completes = false;
+        while (!work.empty()) {
+            const int C = work.back(); work.pop_back();
+            if (C == Y) y_completes = true;
+            for (uint16_t p1 : comp_tmp[Y][C]) {
+                for (int p = p1;; p++) {                   // the dot arrives at p: same walk as the recognizer's add step
+                    const uint16_t code = t.sym[p];
+                    const int k = code >> SYM_KIND_SHIFT;
+                    if (k == SYM_END) { const int L = code & SYM_ID_MASK; if (!completed[L]) { completed[L] = 1; work.push_back(L); } break; }
+                    if (std::find(out.begin(), out.end(), (uint16_t)p) == out.end()) out.push_back((uint16_t)p);
+                    if (k == SYM_TERM || !(code & SYM_NULLABLE_BIT)) break;
+                }
+            }
+        }
+        std::sort(out.begin(), out.end());
+        t.comp_list.insert(t.comp_list.end(), out.begin(), out.end());
+        if (y_completes) t.comp_list.push_back(COMP_ADVANCE_WAITING);
     }
     t.comp_off[(size_t)N * N] = (uint32_t)t.comp_list.size();
+    t.dev_comp_list.resize(t.comp_list.size());
+    for (size_t k = 0; k < t.comp_list.size(); k++)
+        t.dev_comp_list[k] = t.comp_list[k] == COMP_ADVANCE_WAITING ? 0xFFFFFFFFu : t.advpq[t.comp_list[k]];
     t.dev_scan_list.resize(2 * t.scan_list.size());
     for (size_t k = 0; k < t.scan_list.size(); k++) {
         t.dev_scan_list[2 * k] = t.scan_list[k] | IW_TERM;

@@ -22,6 +22,7 @@ enum : uint32_t {
     IW_POS_MASK = 0x3FFF, IW_END = 0x4000, IW_TERM = 0x8000,
     IW_NT_NULLABLE = 1u << 16, IW_NT_SHIFT = 17, IW_NT_MASK = 0x1FFF,
     MAX_POSITIONS = 0x3FFF,
+    COMP_ADVANCE_WAITING = 0xFFFF,   // entry of the completion lists (host form)
 };
 // Per-DFA-state word.  States of a literal terminal form a chain (one expected byte, next state
 // q + 1) and need no table row: flags | QF_LITERAL | expected byte << 8 | flags of state q+1 << 16.
@@ -59,7 +60,7 @@ struct DeviceTables {
     const uint32_t *comp_off;   // [N*N+1] CSR into comp_list
     const uint32_t *delta;      // [dense rows][n_cls] next state | flags << 16, DFA_DEAD in the low half = no edge
     const uint32_t *scan_list;  // pairs: item word (terminal already stepped once), flags of its DFA state
-    const uint16_t *comp_list;  // advanced positions
+    const uint32_t *comp_list;  // item words the completion adds; 0xFFFFFFFF: advance the waiting item itself
     uint32_t small_bytes[5];    // padded byte sizes of advpq .. comp_off (always staged into LDS when they fit)
     uint32_t big_bytes[3];      // padded byte sizes of delta, scan_list, comp_list
     const TrieNode *nodes;      // [n_nodes]

@@ -69,6 +69,8 @@ StepResult earley_step(const Tables &t, Chart &c, uint8_t byte, bool keep_comple
     }
     // Complete: "X complete since o" advances every item of S[o] that waits for X -- the kernel
     // item itself when its postdot symbol is X, and the predicted items of I(Y) that wait for X.
+    // COMP(Y, X) already holds the outcome for the predicted items, including the completions
+    // of their own left-hand sides that follow at the same origin.
     for (size_t i = nb; i < c.items.size(); i++) {
         Item it = c.items[i];
         uint16_t code = t.sym[it.p];
@@ -81,9 +83,11 @@ StepResult earley_step(const Tables &t, Chart &c, uint8_t byte, bool keep_comple
             uint16_t yc = t.sym[y.p];
             if (kind(yc) != SYM_NT) continue;
             int Y = yc & SYM_ID_MASK_NT;
-            for (uint32_t k = t.comp_off[(size_t)Y * t.N + X]; k < t.comp_off[(size_t)Y * t.N + X + 1]; k++)
-                add_advanced(t, c, nb, t.comp_list[k], o, created);
-            if (Y == X) add_advanced(t, c, nb, y.p + 1u, y.o, created);
+            for (uint32_t k = t.comp_off[(size_t)Y * t.N + X]; k < t.comp_off[(size_t)Y * t.N + X + 1]; k++) {
+                const uint16_t p = t.comp_list[k];
+                if (p == COMP_ADVANCE_WAITING) add_advanced(t, c, nb, y.p + 1u, y.o, created);   // Y itself is complete since y's set
+                else insert(c, nb, Item{p, kind(t.sym[p]) == SYM_TERM ? t.term_start[t.sym[p] & SYM_ID_MASK] : (uint16_t)0, o}, created);
+            }
         }
     }
     res.alive = c.items.size() > nb;

@@ -45,7 +45,8 @@ struct Tables {
     std::vector<uint16_t> term_start; // [T]
     std::vector<uint32_t> scan_off, scan_list;
     std::vector<uint32_t> comp_off;
-    std::vector<uint16_t> comp_list;
+    std::vector<uint16_t> comp_list;      // positions, COMP_ADVANCE_WAITING = "advance the waiting item itself"
+    std::vector<uint32_t> dev_comp_list;  // the same as device item words (0xFFFFFFFF for the marker)
     std::vector<uint8_t> reach;       // [N*N] reach[Y*N+X] = 1 iff X can be a left corner of Y (X in PRED(Y))
     // for zf_position_info: original rule index / lhs / dot of each position (-1 for added ones)
     std::vector<int32_t> pos_rule, pos_dot, pos_lhs_orig;

@@ -35,7 +35,7 @@ struct TV {
     const uint32_t *comp_off;
     const uint32_t *delta;
     const uint2 *scan_list;
-    const uint16_t *comp_list;
+    const uint32_t *comp_list;
     uint32_t N, ncls, end_base;
 };
 
@@ -71,7 +71,7 @@ __device__ __forceinline__ uint32_t stage_tables(const DeviceTables &D, uint8_t 
         for (int k = 0; k < 3; k++) { at[k] = off; copy16(smem + off, src[k], D.big_bytes[k], tid, nthreads); off += D.big_bytes[k]; }
         tv.delta = reinterpret_cast<const uint32_t *>(smem + at[0]);
         tv.scan_list = reinterpret_cast<const uint2 *>(smem + at[1]);
-        tv.comp_list = reinterpret_cast<const uint16_t *>(smem + at[2]);
+        tv.comp_list = reinterpret_cast<const uint32_t *>(smem + at[2]);
     } else {
         tv.delta = D.delta; tv.scan_list = reinterpret_cast<const uint2 *>(D.scan_list); tv.comp_list = D.comp_list;
     }
@@ -204,14 +204,16 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
                 const uint32_t Y = (yw >> IW_NT_SHIFT) & IW_NT_MASK;
                 uint32_t c0 = 0, c1 = 0;
                 if (nt) { c0 = T.comp_off[Y * T.N + X]; c1 = T.comp_off[Y * T.N + X + 1]; }
-                unsigned long long mm = __ballot(nt && (c1 > c0 || Y == X));
+                unsigned long long mm = __ballot(nt && c1 > c0);
                 while (mm) {
                     const int l = __ffsll((long long)mm) - 1;
                     mm &= mm - 1;
                     const uint32_t lc0 = __builtin_amdgcn_readlane(c0, l), lc1 = __builtin_amdgcn_readlane(c1, l);
-                    for (uint32_t e = lc0; e < lc1; e++) if (!advance(T.comp_list[e], o)) return wide ? STEP_WIDE : STEP_OVERFLOW;
-                    if (__builtin_amdgcn_readlane(Y, l) == X)
-                        if (!advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l))) return wide ? STEP_WIDE : STEP_OVERFLOW;
+                    for (uint32_t e = lc0; e < lc1; e++) {
+                        const uint32_t cw = T.comp_list[e];
+                        if (cw != 0xFFFFFFFFu) { if (!insert(cw, o)) return wide ? STEP_WIDE : STEP_OVERFLOW; }
+                        else if (!advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l))) return wide ? STEP_WIDE : STEP_OVERFLOW;   // Y itself is complete: the waiting item moves on
+                    }
                 }
             }
         }
@@ -301,14 +303,16 @@ __device__ __forceinline__ int wave_step_big(const TV &T, const BaseT &B, S &st,
                 const uint32_t Y = (yw >> IW_NT_SHIFT) & IW_NT_MASK;
                 uint32_t c0 = 0, c1 = 0;
                 if (nt) { c0 = T.comp_off[Y * T.N + X]; c1 = T.comp_off[Y * T.N + X + 1]; }
-                unsigned long long mm = __ballot(nt && (c1 > c0 || Y == X));
+                unsigned long long mm = __ballot(nt && c1 > c0);
                 while (mm) {
                     const int l = __ffsll((long long)mm) - 1;
                     mm &= mm - 1;
                     const uint32_t lc0 = __builtin_amdgcn_readlane(c0, l), lc1 = __builtin_amdgcn_readlane(c1, l);
-                    for (uint32_t e = lc0; e < lc1; e++) if (!advance(T.comp_list[e], o)) return STEP_OVERFLOW;
-                    if (__builtin_amdgcn_readlane(Y, l) == X)
-                        if (!advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l))) return STEP_OVERFLOW;
+                    for (uint32_t e = lc0; e < lc1; e++) {
+                        const uint32_t cw = T.comp_list[e];
+                        if (cw != 0xFFFFFFFFu) { if (!insert(cw, o)) return STEP_OVERFLOW; }
+                        else if (!advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l))) return STEP_OVERFLOW;
+                    }
                 }
             }
         }
@@ -328,21 +332,46 @@ __device__ __forceinline__ int wave_step_big(const TV &T, const BaseT &B, S &st,
     return (nnew ? STEP_ALIVE : 0) | (kept ? STEP_KERNEL : 0);
 }
 
-// Walk the nodes of one chunk.  anc(j) gives the node index of the first node's ancestor at
-// depth j+1.  Returns false on overflow; otherwise *bits_out holds the chunk's verdicts.
+// What a wavefront remembers between two chunks of the same row: which trie path its stored sets
+// belong to.  A node is named by (depth, rank of its first string).  Consecutive chunks share most
+// of the path above their first node, so the next walk replays only what differs.
+struct PathMemo {
+    uint32_t rank_at;          // lane d: the node whose live set is stored at depth d (valid for 1 <= d <= valid)
+    int valid;                 // depths 1..valid hold live sets of one root path
+    int dead_depth;            // the node (dead_depth, dead_rank) below that path is known to leave no item: its subtree is dead
+    uint32_t dead_rank;
+    __device__ __forceinline__ void reset() { rank_at = 0; valid = 0; dead_depth = 0; dead_rank = 0; }
+    __device__ __forceinline__ void note(int d, uint32_t rank, bool live, uint32_t lane) {   // a step was taken at depth d
+        if (live) { valid = d; dead_depth = 0; if ((int)lane == d) rank_at = rank; }
+        else { valid = d - 1; dead_depth = d; dead_rank = rank; }
+    }
+};
+
+// Walk the nodes of one chunk.  anc(j) gives the first node's ancestor at depth j+1.  Returns
+// false on overflow (the memo is then unusable); otherwise *bits_out holds the chunk's verdicts.
 // `want` marks the strings of the chunk that still need a verdict (the others are decided by the
 // token-mask cache); subtrees without such a string are skipped without a byte step.
 template <class S, class Step, class Anc, class Nodes>
 __device__ __forceinline__ bool walk_chunk(const DeviceTables &D, S &st, Step step, uint32_t chunk, uint32_t want,
-                                           uint32_t begin, uint32_t end, Anc anc, Nodes node, uint32_t *bits_out) {
+                                           uint32_t begin, uint32_t end, Anc anc, Nodes node, uint32_t *bits_out,
+                                           PathMemo &memo, uint32_t lane) {
     uint32_t i = begin;
     const uint32_t rank0 = chunk * (uint32_t)D.chunk_ranks;
     uint32_t bits = 0, cnt = 0;
     st.set_start(1, 0);
     TrieNode nd = node(i);
-    const int n_anc = nd.depth - 1;                      // first the path above the chunk's first node is replayed
+    const int n_anc = nd.depth - 1;                      // the path above the chunk's first node: reused or replayed
     if (nd.depth > S::max_depth) return false;
     int j = 0;
+    while (j < n_anc && j < memo.valid && (uint32_t)__builtin_amdgcn_readlane((int)memo.rank_at, j + 1) == anc(j).rank) j++;
+    if (j < n_anc && memo.dead_depth == j + 1 && j == memo.valid) {
+        const TrieNode dn = anc(j);
+        if (dn.rank == memo.dead_rank) {                 // the chunk starts inside a subtree known to be dead
+            i = dn.skip; j = n_anc;
+            if (i < end) nd = node(i);
+        }
+    } else if (j < memo.valid) { memo.valid = j; memo.dead_depth = 0; }
+    cnt = st.start(j + 1);
     for (;;) {                                           // one loop, one call site of the byte step (keeps the code small)
         const bool warm = j < n_anc;
         const uint32_t nxt = i + 1;
@@ -364,8 +393,10 @@ __device__ __forceinline__ bool walk_chunk(const DeviceTables &D, S &st, Step st
         }
         int r = 0;
         if (do_step) {
-            r = step(warm ? j + 1 : (int)cur.depth, cur.byte, cur.cls, cnt);
+            const int d = warm ? j + 1 : (int)cur.depth;
+            r = step(d, cur.byte, cur.cls, cnt);
             if (r & STEP_OVERFLOW) return false;
+            memo.note(d, cur.rank, (r & STEP_KERNEL) != 0, lane);
         }
         if (warm) {
             if (r & STEP_KERNEL) { j++; continue; }
@@ -405,36 +436,44 @@ __device__ __forceinline__ void or_bits(const DeviceTables &D, uint32_t *rank_ma
 
 // Token-mask cache (Section 4.3): merge the cached bitsets of every item of the row's current set,
 // store the strings some terminal swallows whole, and queue the chunks that hold strings which
-// need the parser.  One lane per (row, chunk); wavefront-aggregated queue append.
+// need the parser.  One lane per 64 ranks (two words of the rank-ordered bitmap, 64 / chunk_ranks
+// chunks); a wavefront appends its chunks to the queue in chunk order with one atomic, so that
+// neighbours in the queue are mostly neighbours in the trie (the walk reuses shared paths).
 __global__ __launch_bounds__(256) void cache_merge_kernel(MaskArgs a) {
     const DeviceTables &D = a.tab;
-    const uint32_t chunk = blockIdx.x * 256 + threadIdx.x, row = blockIdx.y;
+    const uint32_t t = blockIdx.x * 256 + threadIdx.x, row = blockIdx.y, lane = threadIdx.x & 63;
     const RowChart rc = a.rows[row];
-    uint32_t valid = 0, want = 0;
-    if (chunk < (uint32_t)D.n_chunks) {
-        if (rc.n_ent == 0) want = D.chunk_ranks == 32 ? 0xFFFFFFFFu : ((1u << D.chunk_ranks) - 1u);
-        else {
-            uint32_t c = 0;
-            for (uint32_t k = 0; k < rc.n_ent; k++) {
-                const size_t r = (size_t)a.entries[rc.ent_base + k] * D.Wr;
-                valid |= load_bits(D, D.ci_valid + r, chunk);
-                c |= load_bits(D, D.ci_cd + r, chunk);
-            }
-            want = c & ~valid;
+    const uint32_t w0 = 2 * t, Wr = (uint32_t)D.Wr, cr = (uint32_t)D.chunk_ranks;
+    const bool has0 = w0 < Wr, has1 = w0 + 1 < Wr;
+    uint32_t v0 = 0, v1 = 0, c0 = 0, c1 = 0;
+    if (has0) {
+        if (rc.n_ent == 0) { c0 = 0xFFFFFFFFu; c1 = has1 ? 0xFFFFFFFFu : 0u; }
+        for (uint32_t k = 0; k < rc.n_ent; k++) {
+            const size_t r = (size_t)a.entries[rc.ent_base + k] * Wr + w0;
+            v0 |= D.ci_valid[r]; c0 |= D.ci_cd[r];
+            if (has1) { v1 |= D.ci_valid[r + 1]; c1 |= D.ci_cd[r + 1]; }
         }
-        store_bits(D, a.rank_mask, row, chunk, valid);
+        a.rank_mask[(size_t)row * Wr + w0] = v0;
+        if (has1) a.rank_mask[(size_t)row * Wr + w0 + 1] = v1;
     }
-    const unsigned long long b = __ballot(want != 0);
-    if (b) {
-        const uint32_t lane = threadIdx.x & 63;
-        const uint32_t leader = (uint32_t)__ffsll((long long)b) - 1;
-        uint32_t base = 0;
-        if (lane == leader) base = atomicAdd(&a.counters[1], (uint32_t)__popcll(b));
-        base = __shfl(base, leader);
-        if (want) {
-            const uint32_t begin = D.chunk_begin[chunk], n_nodes = D.chunk_end[chunk] - begin;
-            a.work[base + __popcll(b & ((1ull << lane) - 1ull))] = make_uint4(row | (n_nodes > 0xFFFFu ? 0xFFFF0000u : n_nodes << 16), chunk, want, begin);
-        }
+    const unsigned long long want = ((unsigned long long)(c1 & ~v1) << 32) | (c0 & ~v0);
+    const uint32_t per_lane = 64u / cr, chunk0 = t * per_lane;
+    const unsigned long long cm = cr == 32 ? 0xFFFFFFFFull : ((1ull << cr) - 1ull);
+    uint32_t n_mine = 0;
+    for (uint32_t k = 0; k < per_lane; k++) n_mine += ((want >> (k * cr)) & cm) != 0 && chunk0 + k < (uint32_t)D.n_chunks;
+    if (!__ballot(n_mine != 0)) return;
+    uint32_t incl = n_mine;                                  // inclusive prefix sum over the lanes
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) { const uint32_t up = __shfl_up(incl, d); if ((int)lane >= d) incl += up; }
+    uint32_t base = 0;
+    if (lane == 63) base = atomicAdd(&a.counters[1], incl);
+    base = __shfl(base, 63);
+    uint32_t at = base + incl - n_mine;
+    for (uint32_t k = 0; k < per_lane; k++) {
+        const uint32_t wk = (uint32_t)((want >> (k * cr)) & cm), chunk = chunk0 + k;
+        if (!wk || chunk >= (uint32_t)D.n_chunks) continue;
+        const uint32_t begin = D.chunk_begin[chunk], n_nodes = D.chunk_end[chunk] - begin;
+        a.work[at++] = make_uint4(row | (n_nodes > 0xFFFFu ? 0xFFFF0000u : n_nodes << 16), chunk, wk, begin);
     }
 }
 
@@ -466,12 +505,20 @@ __device__ __forceinline__ BaseG global_base(const MaskArgs &a, uint32_t row) {
 
 // The parser walk.  Persistent blocks; every wavefront takes queued chunks g, g + stride, ...
 template <int MODE>
-__global__ __launch_bounds__(WALK_BLOCK) void mask_walk_kernel(MaskArgs a) {
+__global__ __launch_bounds__(WALK_BLOCK) __attribute__((amdgpu_waves_per_eu(6))) void mask_walk_kernel(MaskArgs a) {
     extern __shared__ __align__(16) uint8_t smem[];
     const DeviceTables &D = a.tab;
     const uint32_t tid = threadIdx.x;
     const uint32_t n_work = a.counters[1];
-    if (blockIdx.x * WALK_TILE >= n_work) return;       // uniform: not even the block's first tile exists
+    // The queue is dealt to the blocks in tiles, round robin; a tile is WALK_WAVES runs of `run`
+    // consecutive items, and inside a block the wavefronts take the next run of the block's share
+    // whenever they are free (LDS counter), so that one long walk does not hold up the items behind
+    // it.  Items of a run are mostly neighbouring chunks of one row: the wavefront keeps its path
+    // (PathMemo) from one to the next.  Short queues are dealt item by item so that all wavefronts work.
+    uint32_t run = n_work / (gridDim.x * WALK_WAVES);
+    run = run < 1 ? 1 : (run > WALK_RUN_MAX ? WALK_RUN_MAX : run);
+    const uint32_t tile = run * WALK_WAVES;
+    if (blockIdx.x * tile >= n_work) return;            // uniform: not even the block's first tile exists
     TV T;
     uint32_t off = stage_tables<MODE>(D, smem, T, tid, WALK_BLOCK);
     uint32_t *next_item = reinterpret_cast<uint32_t *>(smem + off);   // the block's counter of items handed out
@@ -490,62 +537,69 @@ __global__ __launch_bounds__(WALK_BLOCK) void mask_walk_kernel(MaskArgs a) {
     st.org = st.pq + cap;
     st.ss = reinterpret_cast<uint16_t *>(st.org + cap);
     st.cap = cap;
-    // The queue is dealt to the blocks in tiles of WALK_TILE consecutive items, round robin; inside a
-    // block the wavefronts take the next item of the block's share whenever they are free (LDS
-    // counter), so that one long walk does not hold up the items behind it.
+    PathMemo memo;
+    memo.reset();
+    uint32_t memo_row = 0xFFFFFFFFu;
     for (;;) {
         uint32_t k = 0;
         if (lane == 0) k = atomicAdd(next_item, 1u);
         k = (uint32_t)__builtin_amdgcn_readfirstlane((int)k);
-        const uint32_t g = ((k / WALK_TILE) * gridDim.x + blockIdx.x) * WALK_TILE + k % WALK_TILE;
-        if ((k / WALK_TILE) * gridDim.x * WALK_TILE >= n_work) break;   // every later tile of this block lies beyond the queue
-        if (g >= n_work) continue;
-        const uint4 item = a.work[g];                   // row | node count << 16, chunk, undecided strings, first node
-        const uint32_t row = item.x & 0xFFFFu, n_nodes = item.x >> 16, chunk = item.y, want = item.z, begin = item.w;
-        const RowChart rc = a.rows[row];
-        const uint32_t *g_so = a.set_off + rc.set_base;
-        const uint2 *g_it = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
-        const bool base_fits = rc.n_sets <= BASE_SETS_LDS && rc.n_items <= BASE_ITEMS_LDS;
-        // all 64 lanes pull the chunk's nodes, the ancestors of its first node and the row's chart into LDS
-        if (n_nodes <= (uint32_t)WALK_NODES_LDS)
-            for (uint32_t k = lane; k < n_nodes; k += 64) l_nodes[k] = D.nodes[begin + k];
-        if (lane < CHUNK_ANC) l_anc[lane] = D.chunk_anc[(size_t)chunk * CHUNK_ANC + lane];
-        if (base_fits) {
-            for (uint32_t k = lane; k <= rc.n_sets; k += 64) l_so[k] = g_so[k];
-            for (uint32_t k = lane; k < rc.n_items; k += 64) l_it[k] = g_it[k];
-        }
-        // lane 0 reads what the other lanes of its own wavefront wrote: LDS serves one wavefront's
-        // accesses in issue order; the fences keep the compiler from moving accesses across
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        {
-            uint32_t bits = 0;
-            bool ok = cap > 0 && n_nodes <= (uint32_t)WALK_NODES_LDS && l_nodes[0].depth - 1 <= CHUNK_ANC;
-            if (ok) {
-                auto anc = [&](int j) { return l_anc[j]; };
-                auto node = [&](uint32_t i) { return l_nodes[i - begin]; };
-                // the row's chart through generic pointers: its LDS copy when it was staged, else global memory
-                const uint32_t *b_so = base_fits ? l_so : g_so;
-                const uint2 *b_it = base_fits ? l_it : g_it;
-                const BaseG B{b_so, b_it, rc.n_sets, b_so[rc.n_sets - 1], rc.n_items};
-                ok = walk_chunk(D, st, [&](int d, uint32_t byte, uint32_t cl, uint32_t &cnt) {
-                                        const uint32_t keep = cnt;
-                                        int r = wave_step(T, B, st, d, byte, cl, cnt, lane);
-                                        if (r & STEP_WIDE) { cnt = keep; r = wave_step_big(T, B, st, d, byte, cl, cnt, lane); }
-                                        return r; },
-                                chunk, want, begin, begin + n_nodes, anc, node, &bits);
+        const uint32_t t_base = ((k / WALK_WAVES) * gridDim.x + blockIdx.x) * tile;
+        if (t_base >= n_work) break;                    // this and every later tile of this block lie beyond the queue
+        const uint32_t g0 = t_base + (k % WALK_WAVES) * run;
+        for (uint32_t g = g0; g < g0 + run && g < n_work; g++) {
+            const uint4 item = a.work[g];               // row | node count << 16, chunk, undecided strings, first node
+            const uint32_t row = item.x & 0xFFFFu, n_nodes = item.x >> 16, chunk = item.y, want = item.z, begin = item.w;
+            const RowChart rc = a.rows[row];
+            const uint32_t *g_so = a.set_off + rc.set_base;
+            const uint2 *g_it = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
+            const bool base_fits = rc.n_sets <= BASE_SETS_LDS && rc.n_items <= BASE_ITEMS_LDS;
+            // all 64 lanes pull the chunk's nodes, the ancestors of its first node and the row's chart into LDS
+            if (n_nodes <= (uint32_t)WALK_NODES_LDS)
+                for (uint32_t k2 = lane; k2 < n_nodes; k2 += 64) l_nodes[k2] = D.nodes[begin + k2];
+            if (lane < CHUNK_ANC) l_anc[lane] = D.chunk_anc[(size_t)chunk * CHUNK_ANC + lane];
+            if (row != memo_row) {                       // another row: its chart, and no path to reuse
+                memo.reset();
+                memo_row = row;
+                if (base_fits) {
+                    for (uint32_t k2 = lane; k2 <= rc.n_sets; k2 += 64) l_so[k2] = g_so[k2];
+                    for (uint32_t k2 = lane; k2 < rc.n_items; k2 += 64) l_it[k2] = g_it[k2];
+                }
             }
-            if (lane == 0) {
-                if (!ok) {
-                    const uint32_t slot = atomicAdd(&a.counters[0], 1u);
-                    if (slot < a.overflow_cap) a.overflow_list[slot] = make_uint4(row, chunk, want, 0);
-                } else or_bits(D, a.rank_mask, row, chunk, bits & want);
+            // lanes read what other lanes of their own wavefront wrote: LDS serves one wavefront's
+            // accesses in issue order; the fences keep the compiler from moving accesses across
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            {
+                uint32_t bits = 0;
+                bool ok = cap > 0 && n_nodes <= (uint32_t)WALK_NODES_LDS && l_nodes[0].depth - 1 <= CHUNK_ANC;
+                if (ok) {
+                    auto anc = [&](int j) { return l_anc[j]; };
+                    auto node = [&](uint32_t i) { return l_nodes[i - begin]; };
+                    // the row's chart through generic pointers: its LDS copy when it was staged, else global memory
+                    const uint32_t *b_so = base_fits ? l_so : g_so;
+                    const uint2 *b_it = base_fits ? l_it : g_it;
+                    const BaseG B{b_so, b_it, rc.n_sets, b_so[rc.n_sets - 1], rc.n_items};
+                    ok = walk_chunk(D, st, [&](int d, uint32_t byte, uint32_t cl, uint32_t &cnt) {
+                                            const uint32_t keep = cnt;
+                                            int r = wave_step(T, B, st, d, byte, cl, cnt, lane);
+                                            if (r & STEP_WIDE) { cnt = keep; r = wave_step_big(T, B, st, d, byte, cl, cnt, lane); }
+                                            return r; },
+                                    chunk, want, begin, begin + n_nodes, anc, node, &bits, memo, lane);
+                }
+                if (!ok) memo.reset();
+                if (lane == 0) {
+                    if (!ok) {
+                        const uint32_t slot = atomicAdd(&a.counters[0], 1u);
+                        if (slot < a.overflow_cap) a.overflow_list[slot] = make_uint4(row, chunk, want, 0);
+                    } else or_bits(D, a.rank_mask, row, chunk, bits & want);
+                }
             }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the next round overwrites the staged data
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the next round overwrites the staged data
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
 }
 
@@ -565,8 +619,10 @@ __global__ __launch_bounds__(64) void mask_fallback_kernel(MaskArgs a) {
         const uint32_t begin = D.chunk_begin[ent.y], end = D.chunk_end[ent.y];
         ParentAnc anc{D.nodes, D.parent, begin, D.nodes[begin].depth};
         uint32_t bits = 0;
+        PathMemo memo;
+        memo.reset();
         const bool ok = walk_chunk(D, st, [&](int d, uint32_t byte, uint32_t cl, uint32_t &cnt) { return wave_step_big(T, B, st, d, byte, cl, cnt, lane); },
-                                   ent.y, ent.z, begin, end, anc, [&](uint32_t i) { return D.nodes[i]; }, &bits);
+                                   ent.y, ent.z, begin, end, anc, [&](uint32_t i) { return D.nodes[i]; }, &bits, memo, lane);
         if (lane == 0) {
             if (!ok) atomicAdd(&a.counters[2], 1u);
             else or_bits(D, a.rank_mask, ent.x, ent.y, bits & ent.z);
@@ -613,6 +669,8 @@ __global__ __launch_bounds__(256) void gather_kernel(MaskArgs a) {
 
 // Logit masking (Section 3.3): pure copy-or-(-inf).  16-byte accesses, consecutive lanes on
 // consecutive 16-byte pieces; the mask words come from L2.
+static const int APPLY_UNROLL = 4;   // 16-byte pieces per thread
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 template <typename VecT, int EPV /* elements per 16 bytes */, typename ElemT>
 __global__ __launch_bounds__(256) void apply_mask_vec_kernel(const ElemT *__restrict__ in, ElemT *__restrict__ out, int64_t stride,
                                                              int V, int W, const uint32_t *__restrict__ mask, ElemT neg_inf) {
@@ -621,14 +679,24 @@ __global__ __launch_bounds__(256) void apply_mask_vec_kernel(const ElemT *__rest
     ElemT *dst = out + (size_t)row * stride;
     const uint32_t *mrow = mask + (size_t)row * W;
     const int n_vec = V / EPV;
-    for (int g = blockIdx.x * 256 + threadIdx.x; g < n_vec; g += gridDim.x * 256) {
-        VecT x = reinterpret_cast<const VecT *>(src)[g];
+    // a block covers APPLY_UNROLL * 256 consecutive pieces: all loads of a thread are issued before its first store
+    const int g0 = blockIdx.x * (256 * APPLY_UNROLL) + threadIdx.x;
+    VecT x[APPLY_UNROLL];
+#pragma unroll
+    for (int u = 0; u < APPLY_UNROLL; u++) {
+        const int g = g0 + u * 256;
+        if (g < n_vec) x[u] = __builtin_nontemporal_load(reinterpret_cast<const VecT *>(src) + g);
+    }
+#pragma unroll
+    for (int u = 0; u < APPLY_UNROLL; u++) {
+        const int g = g0 + u * 256;
+        if (g >= n_vec) break;
         const int v0 = g * EPV;
         const uint32_t mb = mrow[v0 >> 5] >> (v0 & 31);
-        ElemT *e = reinterpret_cast<ElemT *>(&x);
+        ElemT *e = reinterpret_cast<ElemT *>(&x[u]);
 #pragma unroll
         for (int k = 0; k < EPV; k++) if (!((mb >> k) & 1u)) e[k] = neg_inf;
-        reinterpret_cast<VecT *>(dst)[g] = x;
+        __builtin_nontemporal_store(x[u], reinterpret_cast<VecT *>(dst) + g);
     }
     // ragged tail of the row
     const int t = n_vec * EPV + blockIdx.x * 256 + threadIdx.x;
@@ -673,7 +741,7 @@ hipError_t prepare_kernels() {
 }
 
 hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s) {
-    dim3 grid((a.tab.n_chunks + 255) / 256, a.batch);
+    dim3 grid(((a.tab.Wr + 1) / 2 + 255) / 256, a.batch);
     hipLaunchKernelGGL(cache_merge_kernel, grid, dim3(256), 0, s, a);
     return hipGetLastError();
 }
@@ -709,16 +777,16 @@ hipError_t launch_apply_mask(const void *logits, void *out, int dtype, int batch
     const size_t esz = dtype == 0 ? 4 : 2;
     const bool aligned = ((uintptr_t)logits % 16 == 0) && ((uintptr_t)out % 16 == 0) && ((row_stride * esz) % 16 == 0);
     const int epv = (int)(16 / esz);
-    int blocks_x = aligned ? (V / epv + 255) / 256 : (V + 255) / 256;
+    int blocks_x = aligned ? (V / epv + 256 * APPLY_UNROLL - 1) / (256 * APPLY_UNROLL) : (V + 255) / 256;
     if (blocks_x < 1) blocks_x = 1;
     dim3 grid(blocks_x, batch);
     if (dtype == 0) {
         const uint32_t ninf = 0xFF800000u;
-        if (aligned) hipLaunchKernelGGL((apply_mask_vec_kernel<uint4, 4, uint32_t>), grid, dim3(256), 0, s, (const uint32_t *)logits, (uint32_t *)out, row_stride, V, W, mask, ninf);
+        if (aligned) hipLaunchKernelGGL((apply_mask_vec_kernel<u32x4, 4, uint32_t>), grid, dim3(256), 0, s, (const uint32_t *)logits, (uint32_t *)out, row_stride, V, W, mask, ninf);
         else hipLaunchKernelGGL((apply_mask_scalar_kernel<uint32_t>), grid, dim3(256), 0, s, (const uint32_t *)logits, (uint32_t *)out, row_stride, V, W, mask, ninf);
     } else {
         const uint16_t ninf = 0xFF80u;
-        if (aligned) hipLaunchKernelGGL((apply_mask_vec_kernel<uint4, 8, uint16_t>), grid, dim3(256), 0, s, (const uint16_t *)logits, (uint16_t *)out, row_stride, V, W, mask, ninf);
+        if (aligned) hipLaunchKernelGGL((apply_mask_vec_kernel<u32x4, 8, uint16_t>), grid, dim3(256), 0, s, (const uint16_t *)logits, (uint16_t *)out, row_stride, V, W, mask, ninf);
         else hipLaunchKernelGGL((apply_mask_scalar_kernel<uint16_t>), grid, dim3(256), 0, s, (const uint16_t *)logits, (uint16_t *)out, row_stride, V, W, mask, ninf);
     }
     return hipGetLastError();
