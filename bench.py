@@ -178,7 +178,7 @@ def main():
     def run(eng, n_warm, n_timed, profile):
         eng.set_profiling(profile)
         states = [eng.new_state() for _ in range(B)]
-        lat, adv, kern, ovf, hits = [], [], {"main": [], "fallback": [], "permute": [], "apply": []}, 0, 0
+        lat, adv, kern, ovf, hits, queued = [], [], {"main": [], "fallback": [], "permute": [], "apply": []}, 0, 0, 0
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_timed)] if profile else None
         t_begin = None
         for i in range(n_warm + n_timed):
@@ -211,20 +211,31 @@ def main():
                     kern["fallback"].append(r.fallback_ms)
                     kern["permute"].append(r.permute_ms)
                     ovf += r.overflow_chunks
+                    queued += r.walk_chunks
         torch.cuda.synchronize()
         total = time.perf_counter() - t_begin
         if profile:
             kern["apply"] = [a.elapsed_time(b) for a, b in evs]
-        return total, lat, adv, kern, ovf, eng.mask_report().chart_bytes, hits
+        return total, lat, adv, kern, ovf, eng.mask_report().chart_bytes, hits, queued
 
-    total, lat, adv, _, _, _, _ = run(eng, Wm, K, False)
+    total, lat, adv, _, _, _, _, _ = run(eng, Wm, K, False)
     if args.headline_only:
         print(json.dumps({"headline_only": True, "steps": K, "warmup": Wm, "ms_per_step": total / K * 1e3, "value": B * V * K / total}))
         return
-    _, _, _, kern, ovf, chart_bytes, _ = run(eng, Wm, K, True)     # same steps again with HIP events around each kernel
+    _, _, _, kern, ovf, chart_bytes, _, queued = run(eng, Wm, K, True)     # same steps again with HIP events around each kernel
     # the same steps with the state cache (Section 5.2) on, starting cold: reported beside the headline
     eng_sc = zf.Engine(cfg.grammar(), toks, device=0, pruning=bool(args.pruning))
-    sc_total, sc_lat, _, _, _, _, sc_hits = run(eng_sc, Wm, K, False)
+    sc_total, sc_lat, _, _, _, _, sc_hits, _ = run(eng_sc, Wm, K, False)
+    # live trie nodes (Earley byte steps) per mask from the host twin of the kernel, on every 16th step
+    live = {"steps": 0, "replay_steps": 0, "undecided": 0, "masks": 0}
+    tw = [eng.new_state() for _ in range(B)]
+    for i, ids in enumerate(traj[:K]):
+        for b in range(B):
+            tw[b].reset() if ids[b] < 0 else tw[b].advance(ids[b])
+        if i % 16 == 0:
+            for b in range(B):
+                _, st = tw[b].debug_host_mask_cached()
+                live["steps"] += st["steps"]; live["replay_steps"] += st["replay_steps"]; live["undecided"] += st["undecided"]; live["masks"] += 1
 
     ms_per_step = total / K * 1e3
     value = B * V * K / total
@@ -250,6 +261,10 @@ def main():
         "kernel_ms": {k: statistics.fmean(v) for k, v in kern.items()},
         "kernel_ms_p50": {k: pct(v, 0.5) for k, v in kern.items()},
         "overflow_chunks_per_step": ovf / K,
+        "walk_chunks_per_step": queued / K,
+        "live_trie_nodes_per_mask": live["steps"] / live["masks"], "undecided_strings_per_mask": live["undecided"] / live["masks"],
+        "replayed_path_nodes_per_mask_upper_bound": live["replay_steps"] / live["masks"],
+        "live_trie_nodes_per_s": live["steps"] / live["masks"] * B * K / total,
         "with_state_cache": {"value": B * V * K / sc_total, "ms_per_step": sc_total / K * 1e3,
                              "p50_mask_apply_latency_us": pct(sc_lat, 0.5) * 1e6, "p99_mask_apply_latency_us": pct(sc_lat, 0.99) * 1e6,
                              "row_hit_rate": sc_hits / (B * K),

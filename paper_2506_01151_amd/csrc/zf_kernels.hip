@@ -137,10 +137,10 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
     if (ns > 64) return STEP_WIDE;
     uint32_t sw = IW_END, so = 0;                        // lanes beyond the set hold an inert item
     if (lane < ns) { if (from_base) { const uint2 x = B.it[sb + lane]; sw = x.x; so = x.y; } else st.get(sb + lane, sw, so); }
-    uint32_t nw = 0, no = 0, nnew = 0;                   // the set under construction, one item per lane
+    uint32_t nw = 0xFFFFFFFFu, no = 0, nnew = 0;         // the set under construction, one item per lane (no item word is all ones)
     bool saw_end = false, wide = false;
     auto insert = [&](uint32_t w, uint32_t o) -> bool {  // uniform arguments
-        if (__ballot(lane < nnew && nw == w && no == o)) return true;
+        if (__ballot(nw == w && no == o)) return true;
         if (nnew >= 64) { wide = true; return false; }
         if (nb + nnew >= st.cap) return false;
         if (lane == nnew) { nw = w; no = o; }
@@ -157,15 +157,21 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
         }
     };
     // Scan, terminal items: all DFA steps at once, then the survivors one after the other
-    uint32_t nx = DFA_DEAD;
+    uint32_t nx = DFA_DEAD, aw = 0;
     if (sw & IW_TERM) nx = dfa_next(T, sw >> 16, byte, cl);
+    if ((nx & 0xFFFFu) != DFA_DEAD && ((nx >> 16) & QF_ACCEPT)) aw = T.advpq[(sw & IW_POS_MASK) + 1];   // every lane looks up its own item behind the terminal
     unsigned long long m = __ballot((nx & 0xFFFFu) != DFA_DEAD);
     while (m) {
         const int l = __ffsll((long long)m) - 1;
         m &= m - 1;
         const uint32_t lw = __builtin_amdgcn_readlane(sw, l), lo = __builtin_amdgcn_readlane(so, l), lnx = __builtin_amdgcn_readlane(nx, l);
         if ((lnx >> 16) & QF_CONT) if (!insert((lw & 0xFFFFu) | (lnx << 16), lo)) return wide ? STEP_WIDE : STEP_OVERFLOW;   // no longest match: keep matching ...
-        if ((lnx >> 16) & QF_ACCEPT) if (!advance((lw & IW_POS_MASK) + 1, lo)) return wide ? STEP_WIDE : STEP_OVERFLOW;      // ... and also finish here
+        if ((lnx >> 16) & QF_ACCEPT) {                                                                                        // ... and also finish here
+            const uint32_t law = __builtin_amdgcn_readlane(aw, l);
+            if (!insert(law, lo)) return wide ? STEP_WIDE : STEP_OVERFLOW;
+            if (law & IW_END) saw_end = true;
+            else if (!(law & IW_TERM) && (law & IW_NT_NULLABLE)) if (!advance((lw & IW_POS_MASK) + 2, lo)) return wide ? STEP_WIDE : STEP_OVERFLOW;
+        }
     }
     // Scan, items that wait for a nonterminal Y: the tabulated first steps of every terminal that can begin Y
     m = __ballot(!(sw & (IW_TERM | IW_END)));
@@ -202,15 +208,16 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
                 if (j0 + lane < je) { if (in_base) { const uint2 y = B.it[j0 + lane]; yw = y.x; yo = y.y; } else st.get(j0 + lane, yw, yo); }
                 const bool nt = !(yw & (IW_TERM | IW_END));
                 const uint32_t Y = (yw >> IW_NT_SHIFT) & IW_NT_MASK;
-                uint32_t c0 = 0, c1 = 0;
+                uint32_t c0 = 0, c1 = 0, cw0 = 0;
                 if (nt) { c0 = T.comp_off[Y * T.N + X]; c1 = T.comp_off[Y * T.N + X + 1]; }
+                if (c1 > c0) cw0 = T.comp_list[c0];     // every lane fetches the first entry of its own list
                 unsigned long long mm = __ballot(nt && c1 > c0);
                 while (mm) {
                     const int l = __ffsll((long long)mm) - 1;
                     mm &= mm - 1;
                     const uint32_t lc0 = __builtin_amdgcn_readlane(c0, l), lc1 = __builtin_amdgcn_readlane(c1, l);
                     for (uint32_t e = lc0; e < lc1; e++) {
-                        const uint32_t cw = T.comp_list[e];
+                        const uint32_t cw = e == lc0 ? (uint32_t)__builtin_amdgcn_readlane(cw0, l) : T.comp_list[e];
                         if (cw != 0xFFFFFFFFu) { if (!insert(cw, o)) return wide ? STEP_WIDE : STEP_OVERFLOW; }
                         else if (!advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l))) return wide ? STEP_WIDE : STEP_OVERFLOW;   // Y itself is complete: the waiting item moves on
                     }
