@@ -177,7 +177,7 @@ def main():
 
     def run(eng, n_warm, n_timed, profile):
         eng.set_profiling(profile)
-        states = [eng.new_state() for _ in range(B)]
+        states = zf.StateBatch([eng.new_state() for _ in range(B)])
         lat, adv, kern, ovf, hits, queued = [], [], {"main": [], "fallback": [], "permute": [], "apply": []}, 0, 0, 0
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_timed)] if profile else None
         t_begin = None
@@ -190,8 +190,7 @@ def main():
                 t_begin = time.perf_counter()
             ids = traj[i if i < n_warm else i - n_warm]
             t0 = time.perf_counter()
-            for b in range(B):
-                states[b].reset() if ids[b] < 0 else states[b].advance(ids[b])
+            states.advance(ids)                             # every row by its token (a negative id starts the row over)
             t1 = time.perf_counter()
             zf.compute_mask_async(eng, states, d_mask)      # enqueue only: apply_mask queues right behind the mask kernels
             if profile and i >= n_warm:

@@ -118,6 +118,12 @@ void zf_state_destroy(zf_state *s);
  * Predict (Sections 3.2, 4.2).  All or nothing: on ZF_ERR_REJECTED the state is unchanged. */
 int zf_advance(zf_state *s, int32_t token_id);
 int zf_advance_bytes(zf_state *s, const uint8_t *bytes /* host */, int64_t n);
+/* One decode step of a whole batch (the generation loop of Section 3.3 applied to every row):
+ * row b is advanced by token_ids[b], or reset to the empty prefix when token_ids[b] < 0.
+ * states and token_ids are host arrays of n entries; status (host, n entries, may be null)
+ * receives each row's return code.  Every row is processed; the return value is the first
+ * code that is not ZF_OK.  A rejected row is left unchanged, as with zf_advance. */
+int zf_advance_batch(zf_state *const *states, const int32_t *token_ids, int32_t n, int32_t *status);
 int zf_is_accepting(const zf_state *s, int32_t *out); /* is the prefix a sentence of the grammar? */
 int zf_state_stats(const zf_state *s, zf_stats *out);
 /* Copy the chart out for inspection: items as int32 triples (dotted position, origin set, DFA

@@ -49,7 +49,7 @@ class MaskReport(ctypes.Structure):
 
 EXPORTS = ["zf_strerror", "zf_last_error", "zf_compile", "zf_engine_destroy", "zf_engine_get_info",
            "zf_state_new", "zf_state_clone", "zf_state_reset", "zf_state_destroy", "zf_advance",
-           "zf_advance_bytes", "zf_is_accepting", "zf_state_stats", "zf_state_chart", "zf_position_info",
+           "zf_advance_bytes", "zf_advance_batch", "zf_is_accepting", "zf_state_stats", "zf_state_chart", "zf_position_info",
            "zf_compute_mask", "zf_compute_mask_async", "zf_mask_wait", "zf_last_mask_report", "zf_engine_clear_state_cache", "zf_engine_set_profiling", "zf_apply_mask", "zf_debug_host_mask", "zf_debug_host_mask_stats", "zf_debug_host_mask_cached"]
 
 
@@ -88,6 +88,7 @@ def load_library():
     L.zf_compute_mask_async.argtypes = [c_vp, c_vp, c_i32, c_vp, c_vp]
     L.zf_mask_wait.argtypes = [c_vp, c_vp]
     L.zf_last_mask_report.argtypes = [c_vp, c_vp]
+    L.zf_advance_batch.argtypes = [c_vp, c_vp, c_i32, c_vp]
     L.zf_engine_set_profiling.argtypes = [c_vp, c_i32]
     L.zf_engine_clear_state_cache.argtypes = [c_vp]
     L.zf_apply_mask.argtypes = [c_vp, c_vp, c_vp, c_i32, c_i32, c_i64, c_vp, c_vp]
@@ -174,6 +175,34 @@ class State:
         return out
 
 
+class StateBatch:
+    """The rows of one batch with their handle array marshalled once: pass it wherever a list of
+    states is accepted; advance() moves every row by one token in a single library call."""
+
+    def __init__(self, states):
+        self.states = list(states)
+        self.arr = (c_vp * max(1, len(self.states)))(*[s.h for s in self.states])
+        self._ids = (c_i32 * max(1, len(self.states)))()
+
+    def __len__(self):
+        return len(self.states)
+
+    def __getitem__(self, i):
+        return self.states[i]
+
+    def __iter__(self):
+        return iter(self.states)
+
+    def advance(self, token_ids):
+        """token_ids[b] < 0 resets row b."""
+        self._ids[:len(self.states)] = token_ids
+        _check(_lib.zf_advance_batch(self.arr, self._ids, len(self.states), None))
+
+
+def _handles(states):
+    return states.arr if isinstance(states, StateBatch) else (c_vp * len(states))(*[s.h for s in states])
+
+
 class Engine:
     """compile(grammar rules, vocab byte strings)."""
 
@@ -214,12 +243,10 @@ class Engine:
         return a.value, b.value, c.value
 
     def compute_mask(self, states, d_mask_ptr: int, stream: int = 0):
-        arr = (c_vp * len(states))(*[s.h for s in states])
-        _check(_lib.zf_compute_mask(self.h, arr, len(states), d_mask_ptr, stream))
+        _check(_lib.zf_compute_mask(self.h, _handles(states), len(states), d_mask_ptr, stream))
 
     def compute_mask_async(self, states, d_mask_ptr: int, stream: int = 0):
-        arr = (c_vp * len(states))(*[s.h for s in states])
-        _check(_lib.zf_compute_mask_async(self.h, arr, len(states), d_mask_ptr, stream))
+        _check(_lib.zf_compute_mask_async(self.h, _handles(states), len(states), d_mask_ptr, stream))
 
     def mask_wait(self, stream: int = 0):
         _check(_lib.zf_mask_wait(self.h, stream))

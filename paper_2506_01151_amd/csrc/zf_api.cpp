@@ -26,6 +26,8 @@ struct DeviceSide {
     hipEvent_t stage_done[N_SLOTS] = {nullptr, nullptr, nullptr, nullptr};   // the slot's upload has been consumed
     uint32_t *h_status = nullptr;                    // pinned, [N_SLOTS][4]: counters written by each call's last kernel
     uint32_t next_slot = 0, pending = 0;
+    uint32_t occ_lds = 0;                            // LDS size the cached occupancy answer belongs to
+    int occ_blocks = 1;
     // State cache (paper Section 5.2): finished token-order mask rows keyed by the row's packed chart.
     struct CacheEntry { uint64_t hash = 0; std::vector<uint32_t> key; uint32_t stamp = 0; bool used = false; };
     std::vector<CacheEntry> cache;                   // one per pool slot
@@ -279,6 +281,17 @@ int zf_advance(zf_state *s, int32_t token) {
     const zf_engine *e = s->eng;
     if (token < 0 || token >= e->V) return fail(ZF_ERR_RANGE, "token id out of range");
     return feed_token_bytes(s, e->voc_bytes.data() + e->voc_off[token], e->voc_off[token + 1] - e->voc_off[token]);
+}
+
+int zf_advance_batch(zf_state *const *states, const int32_t *token_ids, int32_t n, int32_t *status) {
+    if (!states || !token_ids || n < 0) return fail(ZF_ERR_INVALID_ARG, "null argument");
+    int first = ZF_OK;
+    for (int32_t b = 0; b < n; b++) {
+        const int rc = token_ids[b] < 0 ? zf_state_reset(states[b]) : zf_advance(states[b], token_ids[b]);
+        if (status) status[b] = rc;
+        if (rc != ZF_OK && first == ZF_OK) first = rc;
+    }
+    return first;
 }
 
 int zf_advance_bytes(zf_state *s, const uint8_t *bytes, int64_t n) {
@@ -558,9 +571,14 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     }
     {   // the persistent walk grid: as many blocks as the chip holds at once (LDS is the limit)
         const uint32_t lds = walk_lds_bytes(d->tab, d->mode, a.lane_cap);
-        int per_cu = (int)(160u * 1024u / lds);
-        if (per_cu > 32 / WALK_WAVES) per_cu = 32 / WALK_WAVES;      // at most 32 wavefronts per CU (8 per SIMD)
-        a.walk_blocks = std::max(1, d->cus) * std::max(1, per_cu);
+        if (lds != d->occ_lds) {                          // ask the runtime once per LDS size
+            HIP_TRY(walk_blocks_per_cu(d->mode, lds, &d->occ_blocks));
+            d->occ_lds = lds;
+        }
+        // half as many blocks again as the chip holds at once: the surplus blocks take the places of
+        // blocks whose share of the queue was light (measured: exactly-resident grids are ~10 % slower,
+        // larger surpluses bring nothing more)
+        a.walk_blocks = std::max(1, d->cus) * d->occ_blocks * 3 / 2;
     }
     a.fb_cap = e->opt.fallback_item_cap;
     a.mode = d->mode;

@@ -755,6 +755,17 @@ hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s) {
 uint32_t walk_lds_bytes(const DeviceTables &t, int mode, int lane_cap) {
     return table_bytes(t, mode) + 16 + WALK_WAVES * wave_region_bytes((uint32_t)lane_cap);
 }
+// Blocks of the walk kernel one compute unit holds at once (registers and LDS both limit it): the
+// persistent grid must not be larger, or the surplus blocks would start only after others finish.
+hipError_t walk_blocks_per_cu(int mode, uint32_t lds_bytes, int *out) {
+    int n = 0;
+    hipError_t e;
+    if (mode == 0) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, mask_walk_kernel<0>, WALK_BLOCK, lds_bytes);
+    else if (mode == 1) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, mask_walk_kernel<1>, WALK_BLOCK, lds_bytes);
+    else e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, mask_walk_kernel<2>, WALK_BLOCK, lds_bytes);
+    *out = n < 1 ? 1 : n;
+    return e;
+}
 hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s) {
     const uint32_t lds = walk_lds_bytes(a.tab, a.mode, a.lane_cap);
     dim3 grid(a.walk_blocks);

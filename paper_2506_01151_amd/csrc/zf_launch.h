@@ -43,12 +43,13 @@ struct MaskArgs {
     int32_t batch;
     int32_t lane_cap;          // item budget of a walking wavefront
     int32_t fb_cap;            // item budget of a fallback wavefront (<= FB_ITEMS_PER_WAVE)
-    int32_t walk_blocks;       // blocks of the persistent walk grid (what the chip holds at once)
+    int32_t walk_blocks;       // blocks of the walk grid (one and a half times what the chip holds at once)
     int32_t mode;              // 0: all tables staged in LDS, 1: the small ones only, 2: none
 };
 
 int choose_table_mode(const DeviceTables &t);
 uint32_t walk_lds_bytes(const DeviceTables &t, int mode, int lane_cap);   // dynamic LDS of one block of the walk kernel
+hipError_t walk_blocks_per_cu(int mode, uint32_t lds_bytes, int *out);   // resident blocks of the walk kernel per compute unit
 hipError_t prepare_kernels();   // one-time function attributes (dynamic LDS above 64 KB)
 hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s);

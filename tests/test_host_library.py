@@ -236,3 +236,32 @@ def test_config_trajectories_host_walk_matches_oracle(idx, rows, steps, every, z
                     assert (s.debug_host_mask_cached()[0] == want).all(), (idx, b, step, "token-mask cache")
                     assert s.accepting() == so.accepting()
         assert ss[0].stats().n_items <= ss[1].stats().n_items
+
+
+def test_advance_batch_equals_row_by_row():
+    """zf_advance_batch: same charts as advancing every row on its own; negative ids reset a row;
+    a rejected row is reported, left unchanged, and does not stop the others."""
+    import paper_2506_01151_amd as zf
+    cfg = configs.CONFIGS[1]
+    toks = cfg.vocab()
+    eng = zf.Engine(cfg.grammar(), toks, device=-1)
+    traj = load_trajectory(1, 1, 40)
+    one, many = eng.new_state(), zf.StateBatch([eng.new_state() for _ in range(3)])
+    for ids in traj:
+        t = ids[0]
+        one.reset() if t < 0 else one.advance(t)
+        many.advance([t, t, t])
+        for s in many:
+            assert s.chart() == one.chart() and s.accepting() == one.accepting()
+    before = many[1].chart()
+    bad = next(v for v in range(len(toks)) if one.clone().try_advance(v) == zf.ZF_ERR_REJECTED)
+    good = traj[0][0]
+    with pytest.raises(zf.ZfError) as ei:
+        many.advance([-1, bad, -1])
+    assert ei.value.code == zf.ZF_ERR_REJECTED
+    assert many[1].chart() == before
+    fresh = eng.new_state()
+    assert many[0].chart() == fresh.chart() and many[2].chart() == fresh.chart()
+    many.advance([good, -1, good])
+    fresh.advance(good)
+    assert many[0].chart() == fresh.chart() and many[2].chart() == fresh.chart()
