@@ -466,6 +466,12 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
             row_slot[b] = found;
         }
     } else for (int b = 0; b < batch; b++) miss_rows.push_back((uint32_t)b);
+    // rows with a wide current set first: their chunks are the expensive ones, and work that starts early does not
+    // end up as the kernel's tail
+    std::stable_sort(miss_rows.begin(), miss_rows.end(), [&](uint32_t x, uint32_t y) {
+        const Chart &cx = states[x]->chart, &cy = states[y]->chart;
+        return cx.set_off[cx.n_sets()] - cx.set_off[cx.n_sets() - 1] > cy.set_off[cy.n_sets()] - cy.set_off[cy.n_sets() - 1];
+    });
     const int nb = (int)miss_rows.size();                // rows that go through the kernels
     d->report.cache_hits = n_hits; d->report.cache_misses = sc ? nb : 0;
     // ---- upload: [RowChart x nb][set offsets][items][cache rows of the token-mask cache][dst slot x nb][row slot x batch] ----

@@ -9,7 +9,7 @@ static const int LANE_CAP_MAX = 2048;      // upper limit of the walk kernel's i
 static const int LANE_CAP_DEFAULT = 96; 
 static const int WALK_WAVES = 8;           // wavefronts (= queued chunks) per block of the walk kernel; they share the staged tables
 static const int WALK_BLOCK = WALK_WAVES * 64;
-static const int WALK_RUN_MAX = 8;         // consecutive queue items a wavefront takes at a time (fewer when the queue is short)
+static const int WALK_RUN_MAX = 2;         // consecutive queue items a wavefront takes at a time (one when the queue is short)
 static const int WALK_NODES_LDS = 80;      // trie nodes of a chunk the walk kernel stages in LDS (bigger chunks go to the fallback)
 static const int WALK_DEPTH_MAX = 32;      // trie depth the walk kernel follows (deeper paths go to the fallback)
 static const int BASE_SETS_LDS = 31;       // a row's chart is staged into LDS when it has at most this many sets ...
