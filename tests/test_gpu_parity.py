@@ -71,6 +71,19 @@ def test_forced_overflow_gives_same_bits(cap, torch_cuda, oracle_lib):
     assert ov > 0, "the cap was meant to force the fallback pass"
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_grammars(seed, torch_cuda, oracle_lib):
+    """Seeded random grammars (empty rules, unit cycles, all kinds of recursion, ambiguity): kernels
+    against the oracle at every step, once with the default item budget and once with a budget of
+    three items that sends most chunks through the fallback pass."""
+    import paper_2506_01151_amd as zf
+    from workloads import random_grammars
+    g = random_grammars.random_grammar(seed)
+    toks = random_grammars.random_vocab(seed, 400)
+    _run_parity(torch_cuda, zf, oracle_lib.Oracle, g, toks, 3, 20, 1000 + seed)
+    _run_parity(torch_cuda, zf, oracle_lib.Oracle, g, toks, 2, 12, 2000 + seed, lane_item_cap=3, token_mask_cache=seed % 2 == 0)
+
+
 def test_overflow_beyond_the_fallback_is_an_error(torch_cuda):
     """When even the fallback arena is too small the call must fail loudly (no silent wrong mask)."""
     import paper_2506_01151_amd as zf

@@ -265,3 +265,27 @@ def test_advance_batch_equals_row_by_row():
     many.advance([good, -1, good])
     fresh.advance(good)
     assert many[0].chart() == fresh.chart() and many[2].chart() == fresh.chart()
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_grammars_host_walk_equals_oracle(seed, zf, oracle_lib):
+    """Differential test on seeded random grammars (empty rules, unit cycles, recursion of every
+    kind, ambiguity): along an oracle-sampled trajectory the host walk of the compiled tables,
+    with and without the token-mask cache and with pruning on and off, gives the oracle's mask,
+    and advance/accepting agree."""
+    from workloads import random_grammars
+    g = random_grammars.random_grammar(seed)
+    toks = random_grammars.random_vocab(seed)
+    orc = oracle_lib.Oracle(g)
+    run = OracleRun(orc, toks, [stream(seed, "random-walk")], n_threads=1)
+    engines = [zf.Engine(g, toks, device=-1, pruning=p) for p in (True, False)]
+    states = [e.new_state() for e in engines]
+    for step in range(24):
+        want = run.masks()[0]
+        for s in states:
+            assert (s.debug_host_mask() == want).all(), (seed, step)
+            assert (s.debug_host_mask_cached()[0] == want).all(), (seed, step, "token-mask cache")
+            assert s.accepting() == run.states[0].accepting(), (seed, step)
+        t = run.step(want[None, :])[0]
+        for s in states:
+            s.reset() if t < 0 else s.advance(t)
