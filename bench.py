@@ -26,8 +26,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic of one mask_walk_kernel launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # scaled by a plain copy of known size (profiles/mask_walk_kernel_cfg3_hbm_traffic.txt).  It describes the kernel
 # sources with the digest below; once they change the figure is reported as null until it is measured again.
-MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 6539800, "apply_bytes_per_launch": 8508900,
-                    "kernel_sources_sha256": "5f8cd22526874de16c60cc66bae9a30238ebc942f97397a3361f395aaf6880e9"}
+MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 6531100, "apply_bytes_per_launch": 8508700,
+                    "kernel_sources_sha256": "8a46ca59297a0cb9566cf86de509e6061a9b77fdeccff8fb542ae8a30aa65f52"}
 
 
 def kernel_sources_digest():
