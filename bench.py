@@ -151,7 +151,7 @@ def main():
                          "size, used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("this build runs on one GPU only: rows and vocabulary ranges would shard without any exchange, "
+        print("this benchmark runs on one GPU only: rows and vocabulary ranges would shard without any exchange, "
               "but no multi-GPU path is part of it; run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
@@ -287,7 +287,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "mask_walk_kernel", "achieved": mask_bytes / (main_ms * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": mask_bytes / (main_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC["bytes_per_launch"] if traffic_ok else None, "algorithmic_bytes": mask_bytes,
-                     "note": "integer trie walk; bound by the latency of short dependent instruction chains (about 570 instructions "
+                     "note": "integer trie walk; bound by the latency of short dependent instruction chains (about 690 instructions "
                              "per Earley byte step), far below the HBM roof; the event pair also spans the dispatch gap before the kernel"},
         "roofline_apply_mask": {"bound": "hbm", "kernel": "apply_mask_vec_kernel", "achieved": apply_bytes / (apply_ms * 1e-3) / 1e9,
                                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": apply_bytes / (apply_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
