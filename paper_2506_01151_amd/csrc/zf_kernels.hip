@@ -138,21 +138,26 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
     uint32_t sw = IW_END, so = 0;                        // lanes beyond the set hold an inert item
     if (lane < ns) { if (from_base) { const uint2 x = B.it[sb + lane]; sw = x.x; so = x.y; } else st.get(sb + lane, sw, so); }
     uint32_t nw = 0xFFFFFFFFu, no = 0, nnew = 0;         // the set under construction, one item per lane (no item word is all ones)
-    bool saw_end = false, wide = false;
-    auto insert = [&](uint32_t w, uint32_t o) -> bool {  // uniform arguments
-        if (__ballot(nw == w && no == o)) return true;
-        if (nnew >= 64) { wide = true; return false; }
-        if (nb + nnew >= st.cap) return false;
-        if (lane == nnew) { nw = w; no = o; }
-        nnew++;
-        return true;
+    bool saw_end = false;
+    uint32_t failed = 0;                                 // sticky: 1 = the set needs more than 64 lanes, 2 = the item budget is used up
+    // No branch in here: an item that does not fit leaves `failed` set and the set as it is; the
+    // step runs on (every loop below is bounded by the tables and by 64 items) and reports at its end.
+    auto insert = [&](uint32_t w, uint32_t o) {          // uniform arguments
+        const bool fresh = __ballot(nw == w && no == o) == 0;
+        const bool lanes_left = nnew < 64, budget_left = nb + nnew < st.cap;
+        const bool add = fresh && lanes_left && budget_left;
+        failed |= (fresh && !lanes_left ? 1u : 0u) | (fresh && lanes_left && !budget_left ? 2u : 0u);
+        const bool mine = add && lane == nnew;
+        nw = mine ? w : nw;
+        no = mine ? o : no;
+        nnew += add ? 1u : 0u;
     };
-    auto advance = [&](uint32_t p, uint32_t o) -> bool { // dot arrives at p: skip nullable nonterminals, canonical END item
+    auto advance = [&](uint32_t p, uint32_t o) {         // dot arrives at p: skip nullable nonterminals, canonical END item
         for (;;) {
             const uint32_t w = T.advpq[p];
-            if (!insert(w, o)) return false;
-            if (w & IW_END) { saw_end = true; return true; }
-            if ((w & IW_TERM) || !(w & IW_NT_NULLABLE)) return true;
+            insert(w, o);
+            if (w & IW_END) { saw_end = true; return; }
+            if ((w & IW_TERM) || !(w & IW_NT_NULLABLE)) return;
             p++;
         }
     };
@@ -165,12 +170,12 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
         const int l = __ffsll((long long)m) - 1;
         m &= m - 1;
         const uint32_t lw = __builtin_amdgcn_readlane(sw, l), lo = __builtin_amdgcn_readlane(so, l), lnx = __builtin_amdgcn_readlane(nx, l);
-        if ((lnx >> 16) & QF_CONT) if (!insert((lw & 0xFFFFu) | (lnx << 16), lo)) return wide ? STEP_WIDE : STEP_OVERFLOW;   // no longest match: keep matching ...
+        if ((lnx >> 16) & QF_CONT) insert((lw & 0xFFFFu) | (lnx << 16), lo);   // no longest match: keep matching ...
         if ((lnx >> 16) & QF_ACCEPT) {                                                                                        // ... and also finish here
             const uint32_t law = __builtin_amdgcn_readlane(aw, l);
-            if (!insert(law, lo)) return wide ? STEP_WIDE : STEP_OVERFLOW;
+            insert(law, lo);
             if (law & IW_END) saw_end = true;
-            else if (!(law & IW_TERM) && (law & IW_NT_NULLABLE)) if (!advance((lw & IW_POS_MASK) + 2, lo)) return wide ? STEP_WIDE : STEP_OVERFLOW;
+            else if (!(law & IW_TERM) && (law & IW_NT_NULLABLE)) advance((lw & IW_POS_MASK) + 2, lo);
         }
     }
     // Scan, items that wait for a nonterminal Y: the tabulated first steps of every terminal that can begin Y
@@ -186,8 +191,8 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
             const uint32_t n_e = k1 - e0 < 64 ? k1 - e0 : 64;
             for (uint32_t t = 0; t < n_e; t++) {
                 const uint32_t ent = __builtin_amdgcn_readlane(ef.x, t), f = __builtin_amdgcn_readlane(ef.y, t);
-                if (f & QF_CONT) if (!insert(ent, cur)) return wide ? STEP_WIDE : STEP_OVERFLOW;
-                if (f & QF_ACCEPT) if (!advance((ent & IW_POS_MASK) + 1, cur)) return wide ? STEP_WIDE : STEP_OVERFLOW;
+                if (f & QF_CONT) insert(ent, cur);
+                if (f & QF_ACCEPT) advance((ent & IW_POS_MASK) + 1, cur);
             }
         }
     }
@@ -218,13 +223,14 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
                     const uint32_t lc0 = __builtin_amdgcn_readlane(c0, l), lc1 = __builtin_amdgcn_readlane(c1, l);
                     for (uint32_t e = lc0; e < lc1; e++) {
                         const uint32_t cw = e == lc0 ? (uint32_t)__builtin_amdgcn_readlane(cw0, l) : T.comp_list[e];
-                        if (cw != 0xFFFFFFFFu) { if (!insert(cw, o)) return wide ? STEP_WIDE : STEP_OVERFLOW; }
-                        else if (!advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l))) return wide ? STEP_WIDE : STEP_OVERFLOW;   // Y itself is complete: the waiting item moves on
+                        if (cw != 0xFFFFFFFFu) insert(cw, o);
+                        else advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l));   // Y itself is complete: the waiting item moves on
                     }
                 }
             }
         }
     }
+    if (failed) return (failed & 1u) ? STEP_WIDE : STEP_OVERFLOW;
     // completed items are needed only while their own set is processed: store the others
     const bool keep = lane < nnew && !(nw & IW_END);
     const unsigned long long kb = __ballot(keep);
