@@ -179,12 +179,16 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
         }
     }
     // Scan, items that wait for a nonterminal Y: the tabulated first steps of every terminal that can begin Y
-    m = __ballot(!(sw & (IW_TERM | IW_END)));
+    uint32_t sk0 = 0, sk1 = 0;                           // every lane looks up the list of its own nonterminal
+    if (!(sw & (IW_TERM | IW_END))) {
+        const uint32_t Y = (sw >> IW_NT_SHIFT) & IW_NT_MASK;
+        sk0 = T.scan_off[Y * T.ncls + cl]; sk1 = T.scan_off[Y * T.ncls + cl + 1];
+    }
+    m = __ballot(sk1 > sk0);
     while (m) {
         const int l = __ffsll((long long)m) - 1;
         m &= m - 1;
-        const uint32_t Y = (__builtin_amdgcn_readlane(sw, l) >> IW_NT_SHIFT) & IW_NT_MASK;
-        const uint32_t k0 = T.scan_off[Y * T.ncls + cl], k1 = T.scan_off[Y * T.ncls + cl + 1];
+        const uint32_t k0 = __builtin_amdgcn_readlane(sk0, l), k1 = __builtin_amdgcn_readlane(sk1, l);
         for (uint32_t e0 = k0; e0 < k1; e0 += 64) {
             uint2 ef = make_uint2(0, 0);
             if (e0 + lane < k1) ef = T.scan_list[e0 + lane];
@@ -198,9 +202,13 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
     }
     if (saw_end) {
         // Complete: new items are visited in order; completing may append more
-        for (uint32_t i = 0; i < nnew; i++) {
+        unsigned long long visited = 0;
+        for (;;) {
+            const unsigned long long todo = __ballot(lane < nnew && (nw & IW_END)) & ~visited;
+            if (!todo) break;
+            const int i = __ffsll((long long)todo) - 1;
+            visited |= 1ull << i;
             const uint32_t w = __builtin_amdgcn_readlane(nw, i);
-            if (!(w & IW_END)) continue;
             const uint32_t X = (w & IW_POS_MASK) - T.end_base;
             if (X == T.N - 1) continue;                 // the start rule is complete: the prefix is a sentence
             const uint32_t o = __builtin_amdgcn_readlane(no, i);
