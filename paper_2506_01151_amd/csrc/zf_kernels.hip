@@ -259,24 +259,25 @@ __device__ __forceinline__ int wave_step_big(const TV &T, const BaseT &B, S &st,
     const uint32_t sb = from_base ? B.last_lo : st.start(d - 1);
     const uint32_t se = from_base ? B.last_hi : nb;
     uint32_t nnew = 0;
-    bool saw_end = false;
-    auto insert = [&](uint32_t w, uint32_t o) -> bool {
+    bool saw_end = false, failed = false;                // failed: the item budget is used up (sticky; the step runs on and reports at its end)
+    auto insert = [&](uint32_t w, uint32_t o) {
+        unsigned long long dup = 0;
         for (uint32_t s0 = 0; s0 < nnew; s0 += 64) {
             uint32_t xw = 0, xo = 0xFFFFFFFFu;
             if (s0 + lane < nnew) st.get(nb + s0 + lane, xw, xo);
-            if (__ballot(s0 + lane < nnew && xw == w && xo == o)) return true;
+            dup |= __ballot(s0 + lane < nnew && xw == w && xo == o);
         }
-        if (nb + nnew >= st.cap) return false;
-        if (lane == 0) st.put(nb + nnew, w, o);
-        nnew++;
-        return true;
+        const bool add = !dup && nb + nnew < st.cap;
+        failed |= !dup && !add;
+        if (add && lane == 0) st.put(nb + nnew, w, o);
+        nnew += add ? 1u : 0u;
     };
-    auto advance = [&](uint32_t p, uint32_t o) -> bool {
+    auto advance = [&](uint32_t p, uint32_t o) {
         for (;;) {
             const uint32_t w = T.advpq[p];
-            if (!insert(w, o)) return false;
-            if (w & IW_END) { saw_end = true; return true; }
-            if ((w & IW_TERM) || !(w & IW_NT_NULLABLE)) return true;
+            insert(w, o);
+            if (w & IW_END) { saw_end = true; return; }
+            if ((w & IW_TERM) || !(w & IW_NT_NULLABLE)) return;
             p++;
         }
     };
@@ -290,8 +291,8 @@ __device__ __forceinline__ int wave_step_big(const TV &T, const BaseT &B, S &st,
             const int l = __ffsll((long long)m) - 1;
             m &= m - 1;
             const uint32_t lw = __builtin_amdgcn_readlane(sw, l), lo = __builtin_amdgcn_readlane(so, l), lnx = __builtin_amdgcn_readlane(nx, l);
-            if ((lnx >> 16) & QF_CONT) if (!insert((lw & 0xFFFFu) | (lnx << 16), lo)) return STEP_OVERFLOW;
-            if ((lnx >> 16) & QF_ACCEPT) if (!advance((lw & IW_POS_MASK) + 1, lo)) return STEP_OVERFLOW;
+            if ((lnx >> 16) & QF_CONT) insert((lw & 0xFFFFu) | (lnx << 16), lo);
+            if ((lnx >> 16) & QF_ACCEPT) advance((lw & IW_POS_MASK) + 1, lo);
         }
         m = __ballot(!(sw & (IW_TERM | IW_END)));
         while (m) {
@@ -301,8 +302,8 @@ __device__ __forceinline__ int wave_step_big(const TV &T, const BaseT &B, S &st,
             const uint32_t k0 = T.scan_off[Y * T.ncls + cl], k1 = T.scan_off[Y * T.ncls + cl + 1];
             for (uint32_t e = k0; e < k1; e++) {
                 const uint2 ef = T.scan_list[e];
-                if (ef.y & QF_CONT) if (!insert(ef.x, cur)) return STEP_OVERFLOW;
-                if (ef.y & QF_ACCEPT) if (!advance((ef.x & IW_POS_MASK) + 1, cur)) return STEP_OVERFLOW;
+                if (ef.y & QF_CONT) insert(ef.x, cur);
+                if (ef.y & QF_ACCEPT) advance((ef.x & IW_POS_MASK) + 1, cur);
             }
         }
     }
@@ -331,13 +332,14 @@ __device__ __forceinline__ int wave_step_big(const TV &T, const BaseT &B, S &st,
                     const uint32_t lc0 = __builtin_amdgcn_readlane(c0, l), lc1 = __builtin_amdgcn_readlane(c1, l);
                     for (uint32_t e = lc0; e < lc1; e++) {
                         const uint32_t cw = T.comp_list[e];
-                        if (cw != 0xFFFFFFFFu) { if (!insert(cw, o)) return STEP_OVERFLOW; }
-                        else if (!advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l))) return STEP_OVERFLOW;
+                        if (cw != 0xFFFFFFFFu) insert(cw, o);
+                        else advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l));
                     }
                 }
             }
         }
     }
+    if (failed) return STEP_OVERFLOW;
     // drop the completed items: forward compaction, strip by strip (a strip is read before it is written)
     uint32_t kept = 0;
     for (uint32_t s0 = 0; s0 < nnew; s0 += 64) {
