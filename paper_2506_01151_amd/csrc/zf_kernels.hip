@@ -163,8 +163,10 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
     };
     // Scan, terminal items: all DFA steps at once, then the survivors one after the other
     uint32_t nx = DFA_DEAD, aw = 0;
-    if (sw & IW_TERM) nx = dfa_next(T, sw >> 16, byte, cl);
-    if ((nx & 0xFFFFu) != DFA_DEAD && ((nx >> 16) & QF_ACCEPT)) aw = T.advpq[(sw & IW_POS_MASK) + 1];   // every lane looks up its own item behind the terminal
+    if (sw & IW_TERM) {
+        aw = T.advpq[(sw & IW_POS_MASK) + 1];            // the item behind the terminal, fetched alongside the DFA step in case the terminal ends here
+        nx = dfa_next(T, sw >> 16, byte, cl);
+    }
     unsigned long long m = __ballot((nx & 0xFFFFu) != DFA_DEAD);
     while (m) {
         const int l = __ffsll((long long)m) - 1;
