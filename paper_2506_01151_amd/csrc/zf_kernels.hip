@@ -80,16 +80,17 @@ __device__ __forceinline__ uint32_t stage_tables(const DeviceTables &D, uint8_t 
 
 // ---- item-list storage policies ---------------------------------------------------------
 // An item is (w, o): w = item word (see IW_* in zf_device.h), o = origin set.
-struct WaveLdsStore {          // walk kernel: the wavefront's list in LDS, used by its walking lane
+struct WaveLdsStore {          // walk kernel: the wavefront's list in LDS; set starts in a register (lane d holds the start of depth d)
     uint32_t *pq;
     uint32_t *org;
-    uint16_t *ss;
+    uint32_t ss_reg;
+    uint32_t lane;
     uint32_t cap;
     static constexpr int max_depth = WALK_DEPTH_MAX;
     __device__ __forceinline__ void get(uint32_t i, uint32_t &p, uint32_t &o) const { p = pq[i]; o = org[i]; }
     __device__ __forceinline__ void put(uint32_t i, uint32_t p, uint32_t o) { pq[i] = p; org[i] = o; }
-    __device__ __forceinline__ uint32_t start(int d) const { return ss[d]; }
-    __device__ __forceinline__ void set_start(int d, uint32_t v) { ss[d] = (uint16_t)v; }
+    __device__ __forceinline__ uint32_t start(int d) const { return (uint32_t)__builtin_amdgcn_readlane((int)ss_reg, __builtin_amdgcn_readfirstlane(d)); }
+    __device__ __forceinline__ void set_start(int d, uint32_t v) { if ((int)lane == d) ss_reg = v; }
 };
 struct GlobalStore {           // fallback: the wavefront's list in a global-memory arena
     uint2 *items;
@@ -504,8 +505,8 @@ __global__ __launch_bounds__(256) void cache_merge_kernel(MaskArgs a) {
 
 static const uint32_t BASE_LDS_BYTES = (BASE_SETS_LDS + 1) * 4 + BASE_ITEMS_LDS * 8;
 __host__ __device__ inline uint32_t wave_region_bytes(uint32_t cap) {
-    // prefetched nodes, ancestor nodes, the row's chart, item words, origins, set starts (uint16); a multiple of 16
-    return (WALK_NODES_LDS + CHUNK_ANC) * 16 + BASE_LDS_BYTES + (cap * 8 + (WALK_DEPTH_MAX + 2) * 2 + 15) / 16 * 16;
+    // prefetched nodes, ancestor nodes, the row's chart, item words, origins; a multiple of 16
+    return (WALK_NODES_LDS + CHUNK_ANC) * 16 + BASE_LDS_BYTES + (cap * 8 + 15) / 16 * 16;
 }
 
 struct ParentAnc {             // ancestor node at depth j+1 through the parent links
@@ -560,7 +561,8 @@ __global__ __launch_bounds__(WALK_BLOCK) __attribute__((amdgpu_waves_per_eu(6)))
     WaveLdsStore st;
     st.pq = reinterpret_cast<uint32_t *>(l_it + BASE_ITEMS_LDS);
     st.org = st.pq + cap;
-    st.ss = reinterpret_cast<uint16_t *>(st.org + cap);
+    st.ss_reg = 0;
+    st.lane = lane;
     st.cap = cap;
     PathMemo memo;
     memo.reset();
