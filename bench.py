@@ -26,8 +26,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic of one mask_walk_kernel launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # scaled by a plain copy of known size (profiles/mask_walk_kernel_cfg3_hbm_traffic.txt).  It describes the kernel
 # sources with the digest below; once they change the figure is reported as null until it is measured again.
-MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 6524100, "apply_bytes_per_launch": 8493700,
-                    "kernel_sources_sha256": "747c4c85575bde0d4627e627f024df89300dc9eff23cd5b69eef89754cc9fbb0"}
+MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 6509200, "apply_bytes_per_launch": 8501700,
+                    "kernel_sources_sha256": "3ce98567bc9f34f9274df838c4ac1ecda3fb2ca465bebeca1764de4b82f30bec"}
 
 
 def kernel_sources_digest():
@@ -287,7 +287,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "mask_walk_kernel", "achieved": mask_bytes / (main_ms * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": mask_bytes / (main_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC["bytes_per_launch"] if traffic_ok else None, "algorithmic_bytes": mask_bytes,
-                     "note": "integer trie walk; bound by the latency of short dependent instruction chains (about 490 instructions "
+                     "note": "integer trie walk; bound by the latency of short dependent instruction chains (about 470 instructions "
                              "per Earley byte step), far below the HBM roof; the event pair also spans the dispatch gap before the kernel"},
         "roofline_apply_mask": {"bound": "hbm", "kernel": "apply_mask_vec_kernel", "achieved": apply_bytes / (apply_ms * 1e-3) / 1e9,
                                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": apply_bytes / (apply_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
