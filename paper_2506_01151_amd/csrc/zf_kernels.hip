@@ -140,14 +140,14 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
     if (lane < ns) { if (from_base) { const uint2 x = B.it[sb + lane]; sw = x.x; so = x.y; } else st.get(sb + lane, sw, so); }
     uint32_t nw = 0xFFFFFFFFu, no = 0, nnew = 0;         // the set under construction, one item per lane (no item word is all ones)
     bool saw_end = false;
-    uint32_t failed = 0;                                 // sticky: 1 = the set needs more than 64 lanes, 2 = the item budget is used up
+    bool failed = false;                                 // sticky: an item found no room (64 lanes, or the item budget)
+    const uint32_t room = st.cap - nb < 64u ? st.cap - nb : 64u;   // nb <= cap always
     // No branch in here: an item that does not fit leaves `failed` set and the set as it is; the
     // step runs on (every loop below is bounded by the tables and by 64 items) and reports at its end.
     auto insert = [&](uint32_t w, uint32_t o) {          // uniform arguments
         const bool fresh = __ballot(nw == w && no == o) == 0;
-        const bool lanes_left = nnew < 64, budget_left = nb + nnew < st.cap;
-        const bool add = fresh && lanes_left && budget_left;
-        failed |= (fresh && !lanes_left ? 1u : 0u) | (fresh && lanes_left && !budget_left ? 2u : 0u);
+        const bool add = fresh && nnew < room;
+        failed |= fresh && !add;
         const bool mine = add && lane == nnew;
         nw = mine ? w : nw;
         no = mine ? o : no;
@@ -241,7 +241,7 @@ __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsSto
             }
         }
     }
-    if (failed) return (failed & 1u) ? STEP_WIDE : STEP_OVERFLOW;
+    if (failed) return nnew >= 64u ? STEP_WIDE : STEP_OVERFLOW;   // all lanes taken: the strip-wise step may still fit; else the budget is used up
     // completed items are needed only while their own set is processed: store the others
     const bool keep = lane < nnew && !(nw & IW_END);
     const unsigned long long kb = __ballot(keep);
