@@ -524,8 +524,6 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
             dst[r] = sc ? row_slot[miss_rows[r]] : miss_rows[r];
         }
     }
-    HIP_TRY(hipMemcpyAsync(d->d_chart, d->h_stage[slot], total, hipMemcpyHostToDevice, stream));
-    HIP_TRY(hipEventRecord(d->stage_done[slot], stream));
     // ---- per-call device buffers ----
     const size_t need_rank = (size_t)std::max(nb, 1) * d->tab.Wr, need_ovf = (size_t)std::max(nb, 1) * d->tab.n_chunks;
     if (need_rank > d->rank_cap || need_ovf > d->overflow_cap) {
@@ -592,6 +590,8 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     d->report.chart_bytes = (int64_t)total;
     d->report.main_ms = d->report.fallback_ms = d->report.permute_ms = 0.f;
     d->report.overflow_chunks = d->report.walk_chunks = 0;
+    // everything the host has to work out is done: enqueue the upload and the kernels back to back
+    HIP_TRY(launch_upload(d->h_stage[slot], d->d_chart, total, stream));
     const bool run_kernels = nb > 0;
     if (run_kernels && d->tab.n_chunks > 0) HIP_TRY(launch_cache_merge(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
@@ -602,6 +602,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     if (run_kernels) HIP_TRY(launch_permute(a, stream));  // the call's last kernel also hands the counters to the host and clears the next call's
     if (sc) HIP_TRY(launch_gather(a, stream));            // every row's finished mask from its pool slot to the caller's tensor
     if (prof) HIP_TRY(hipEventRecord(d->ev[3], stream));
+    HIP_TRY(hipEventRecord(d->stage_done[slot], stream));   // the staging slot is free again once this point of the stream is reached
     d->next_slot = (slot + 1) % DeviceSide::N_SLOTS;
     d->pending++;
     if (!wait) return ZF_OK;

@@ -503,6 +503,13 @@ __global__ __launch_bounds__(256) void cache_merge_kernel(MaskArgs a) {
     }
 }
 
+// The packed charts of a call, a few KB, from pinned host memory to device memory: launched like
+// the kernels behind it (the runtime's copy path costs the host several times as long per call).
+__global__ __launch_bounds__(256) void upload_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, uint32_t n16) {
+    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n16) dst[i] = src[i];
+}
+
 static const uint32_t BASE_LDS_BYTES = (BASE_SETS_LDS + 1) * 4 + BASE_ITEMS_LDS * 8;
 __host__ __device__ inline uint32_t wave_region_bytes(uint32_t cap) {
     // prefetched nodes, ancestor nodes, the row's chart, item words, origins; a multiple of 16
@@ -767,6 +774,11 @@ hipError_t prepare_kernels() {
     return hipSuccess;
 }
 
+hipError_t launch_upload(const void *pinned_src, void *dst, size_t bytes, hipStream_t s) {
+    const uint32_t n16 = (uint32_t)((bytes + 15) / 16);
+    hipLaunchKernelGGL(upload_kernel, dim3((n16 + 255) / 256), dim3(256), 0, s, (const uint4 *)pinned_src, (uint4 *)dst, n16);
+    return hipGetLastError();
+}
 hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s) {
     dim3 grid(((a.tab.Wr + 1) / 2 + 255) / 256, a.batch);
     hipLaunchKernelGGL(cache_merge_kernel, grid, dim3(256), 0, s, a);
