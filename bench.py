@@ -26,8 +26,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic of one mask_walk_kernel launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # scaled by a plain copy of known size (profiles/mask_walk_kernel_cfg3_hbm_traffic.txt).  It describes the kernel
 # sources with the digest below; once they change the figure is reported as null until it is measured again.
-MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 6509200, "apply_bytes_per_launch": 8501700,
-                    "kernel_sources_sha256": "3ce98567bc9f34f9274df838c4ac1ecda3fb2ca465bebeca1764de4b82f30bec"}
+MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 6518000, "apply_bytes_per_launch": 8493700,
+                    "kernel_sources_sha256": "7b22b335517ce682b333e977f76f6689aeaaf82379a72d613f59e634e03e4898"}
 
 
 def kernel_sources_digest():
