@@ -76,6 +76,10 @@ typedef struct {
                                   keyed by the row's pruned chart; 0 = default (2048 rows), -1 = off */
     int32_t disable_token_mask_cache; /* 1 = every token goes through the parser walk (Section 4.3
                                   optimisation off); masks are identical either way */
+    int32_t walk_mode;     /* which mask kernel checks the tokens the token-mask cache leaves undecided:
+                              0 = mask automaton (a block builds the row's automaton of Earley sets over
+                              byte classes lazily in LDS; one lane per token string), 1 = trie walk (one
+                              wavefront per chunk of the vocabulary trie).  Masks are identical. */
 } zf_options;
 
 typedef struct {
@@ -95,11 +99,13 @@ typedef struct {
 
 typedef struct {               /* facts about the last zf_compute_mask, for reporting only */
     int64_t overflow_chunks;   /* trie chunks handed to the fallback pass in the last call */
-    int64_t walk_chunks;       /* trie chunks the token-mask cache left undecided: walked by the parser kernel */
+    int64_t walk_chunks;       /* work the token-mask cache left to the parser kernel: undecided strings (mask
+                                  automaton) or trie chunks that hold such strings (trie walk) */
     int64_t chart_bytes;       /* bytes uploaded for the last call */
     int32_t cache_hits, cache_misses; /* rows of the last call served from / added to the state cache */
     float main_ms, fallback_ms, permute_ms; /* kernel durations from HIP events on the call's
                                                stream; 0 unless zf_engine_set_profiling is on */
+    int32_t parser_steps;      /* Earley byte steps the mask-automaton kernel took in the last call (all blocks) */
 } zf_mask_report;
 
 /* compile(grammar rules, vocab byte strings): clean the grammar (useless rules, nullable
@@ -174,6 +180,13 @@ int zf_debug_host_mask_stats(zf_engine *e, const zf_state *s, uint32_t *mask /* 
  * the kernel does.  stats[0..4] (host, may be null): byte steps, undecided strings, cache rows,
  * byte steps the chunk-wise kernel adds by replaying the path above each chunk, chunks walked. */
 int zf_debug_host_mask_cached(zf_engine *e, const zf_state *s, uint32_t *mask /* host [W] */, int64_t *stats);
+/* Diagnostic: host twin of the mask-automaton kernel.  The Earley sets met while checking one
+ * row's tokens are the states of a deterministic automaton over byte classes; a transition is
+ * computed by one Earley byte step (Section 3.2) the first time a token needs it and looked up
+ * afterwards, sets are interned by content (the state-cache idea of Section 5.2 inside one
+ * mask).  stats[0..4] (host, may be null): automaton states created, Earley byte steps taken,
+ * transition look-ups, undecided strings, largest set. */
+int zf_debug_host_mask_automaton(zf_engine *e, const zf_state *s, uint32_t *mask /* host [W] */, int64_t *stats);
 
 #ifdef __cplusplus
 }

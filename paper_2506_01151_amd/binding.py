@@ -29,7 +29,7 @@ class VocabDesc(ctypes.Structure):
 
 
 class Options(ctypes.Structure):
-    _fields_ = [("pruning", c_i32), ("lane_item_cap", c_i32), ("device", c_i32), ("chunk_strings", c_i32), ("fallback_item_cap", c_i32), ("state_cache_entries", c_i32), ("disable_token_mask_cache", c_i32)]
+    _fields_ = [("pruning", c_i32), ("lane_item_cap", c_i32), ("device", c_i32), ("chunk_strings", c_i32), ("fallback_item_cap", c_i32), ("state_cache_entries", c_i32), ("disable_token_mask_cache", c_i32), ("walk_mode", c_i32)]
 
 
 class Stats(ctypes.Structure):
@@ -44,13 +44,13 @@ class EngineInfo(ctypes.Structure):
 
 class MaskReport(ctypes.Structure):
     _fields_ = [("overflow_chunks", c_i64), ("walk_chunks", c_i64), ("chart_bytes", c_i64), ("cache_hits", c_i32), ("cache_misses", c_i32), ("main_ms", ctypes.c_float),
-                ("fallback_ms", ctypes.c_float), ("permute_ms", ctypes.c_float)]
+                ("fallback_ms", ctypes.c_float), ("permute_ms", ctypes.c_float), ("parser_steps", c_i32)]
 
 
 EXPORTS = ["zf_strerror", "zf_last_error", "zf_compile", "zf_engine_destroy", "zf_engine_get_info",
            "zf_state_new", "zf_state_clone", "zf_state_reset", "zf_state_destroy", "zf_advance",
            "zf_advance_bytes", "zf_advance_batch", "zf_is_accepting", "zf_state_stats", "zf_state_chart", "zf_position_info",
-           "zf_compute_mask", "zf_compute_mask_async", "zf_mask_wait", "zf_last_mask_report", "zf_engine_clear_state_cache", "zf_engine_set_profiling", "zf_apply_mask", "zf_debug_host_mask", "zf_debug_host_mask_stats", "zf_debug_host_mask_cached"]
+           "zf_compute_mask", "zf_compute_mask_async", "zf_mask_wait", "zf_last_mask_report", "zf_engine_clear_state_cache", "zf_engine_set_profiling", "zf_apply_mask", "zf_debug_host_mask", "zf_debug_host_mask_stats", "zf_debug_host_mask_cached", "zf_debug_host_mask_automaton"]
 
 
 class ZfError(RuntimeError):
@@ -95,6 +95,7 @@ def load_library():
     L.zf_debug_host_mask.argtypes = [c_vp, c_vp, c_vp]
     L.zf_debug_host_mask_stats.argtypes = [c_vp, c_vp, c_vp, c_vp]
     L.zf_debug_host_mask_cached.argtypes = [c_vp, c_vp, c_vp, c_vp]
+    L.zf_debug_host_mask_automaton.argtypes = [c_vp, c_vp, c_vp, c_vp]
     _lib = L
     return L
 
@@ -169,6 +170,12 @@ class State:
         _check(_lib.zf_debug_host_mask_cached(self.engine.h, self.h, out.ctypes.data, st.ctypes.data))
         return out, dict(steps=int(st[0]), undecided=int(st[1]), cache_rows=int(st[2]), replay_steps=int(st[3]), chunks=int(st[4]))
 
+    def debug_host_mask_automaton(self):
+        out = np.zeros(self.engine.W, dtype=np.uint32)
+        st = np.zeros(8, dtype=np.int64)
+        _check(_lib.zf_debug_host_mask_automaton(self.engine.h, self.h, out.ctypes.data, st.ctypes.data))
+        return out, dict(states=int(st[0]), steps=int(st[1]), lookups=int(st[2]), undecided=int(st[3]), max_set=int(st[4]))
+
     def debug_host_mask(self) -> np.ndarray:
         out = np.zeros(self.engine.W, dtype=np.uint32)
         _check(_lib.zf_debug_host_mask(self.engine.h, self.h, out.ctypes.data))
@@ -206,7 +213,7 @@ def _handles(states):
 class Engine:
     """compile(grammar rules, vocab byte strings)."""
 
-    def __init__(self, grammar, vocab_tokens, *, pruning=True, lane_item_cap=0, device=0, chunk_strings=0, fallback_item_cap=0, token_mask_cache=True, state_cache_entries=0):
+    def __init__(self, grammar, vocab_tokens, *, pruning=True, lane_item_cap=0, device=0, chunk_strings=0, fallback_item_cap=0, token_mask_cache=True, state_cache_entries=0, walk_mode=0):
         load_library()
         csr = grammar.csr()
         self._keep = csr
@@ -218,7 +225,7 @@ class Engine:
         np.cumsum([len(t) for t in vocab_tokens], out=off[1:])
         data = np.frombuffer(b"".join(vocab_tokens) or b"\0", dtype=np.uint8).copy()
         vd = VocabDesc(len(vocab_tokens), off.ctypes.data, data.ctypes.data)
-        opt = Options(int(bool(pruning)), lane_item_cap, device, chunk_strings, fallback_item_cap, state_cache_entries, int(not token_mask_cache))
+        opt = Options(int(bool(pruning)), lane_item_cap, device, chunk_strings, fallback_item_cap, state_cache_entries, int(not token_mask_cache), walk_mode)
         h = c_vp()
         self.h = None
         _check(_lib.zf_compile(ctypes.byref(gd), ctypes.byref(vd), ctypes.byref(opt), ctypes.byref(h)))

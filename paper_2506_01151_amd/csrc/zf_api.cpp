@@ -105,6 +105,19 @@ int setup_device(zf_engine *e) {
     UP(nodes, tr.nodes, nullptr); UP(parent, tr.parent, nullptr); UP(chunk_begin, tr.chunk_begin, nullptr); UP(chunk_end, tr.chunk_end, nullptr);
     UP(chunk_anc, tr.chunk_anc, nullptr); UP(rank_of, tr.rank_of, nullptr);
     UP(ci_valid, tr.ci_valid, nullptr); UP(ci_cd, tr.ci_cd, nullptr);
+    {   // the strings as class strings for the mask-automaton kernel
+        std::vector<uint8_t> str_cls(tr.str_bytes.size()), rep(std::max(t.n_cls, 1), 0);
+        for (size_t k = 0; k < tr.str_bytes.size(); k++) str_cls[k] = t.cls[tr.str_bytes[k]];
+        for (int b = 255; b >= 0; b--) rep[t.cls[b]] = (uint8_t)b;
+        std::vector<Str16> str16((size_t)std::max(tr.n_strings, 1), Str16{{0, 0, 0, 0}});
+        for (int r = 0; r < tr.n_strings; r++) {
+            uint8_t first[16] = {0};
+            const uint32_t n = std::min<uint32_t>(16, tr.str_off[r + 1] - tr.str_off[r]);
+            memcpy(first, str_cls.data() + tr.str_off[r], n);
+            memcpy(&str16[r], first, 16);
+        }
+        UP(str_off, tr.str_off, nullptr); UP(str_cls, str_cls, nullptr); UP(str16, str16, nullptr); UP(cls_rep, rep, nullptr);
+    }
     T.Q = t.Q;
 #undef UP
     T.N = t.N; T.n_cls = t.n_cls; T.end_base = t.end_base; T.n_nodes = (int)tr.nodes.size(); T.n_chunks = (int)tr.chunk_begin.size();
@@ -198,7 +211,7 @@ int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_option
     }
     zf_engine *e = new (std::nothrow) zf_engine();
     if (!e) return fail(ZF_ERR_OOM, "out of memory");
-    e->opt = opt ? *opt : zf_options{1, 0, 0, 0, 0, 0, 0};
+    e->opt = opt ? *opt : zf_options{1, 0, 0, 0, 0, 0, 0, 0};
     e->lane_cap_auto = e->opt.lane_item_cap <= 0;
     if (e->opt.lane_item_cap <= 0) e->opt.lane_item_cap = LANE_CAP_DEFAULT;
     if (e->opt.lane_item_cap > LANE_CAP_MAX) e->opt.lane_item_cap = LANE_CAP_MAX;
@@ -525,7 +538,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
         }
     }
     // ---- per-call device buffers ----
-    const size_t need_rank = (size_t)std::max(nb, 1) * d->tab.Wr, need_ovf = (size_t)std::max(nb, 1) * d->tab.n_chunks;
+    const size_t need_rank = (size_t)std::max(nb, 1) * d->tab.Wr, need_ovf = 2 * (size_t)std::max(nb, 1) * d->tab.n_chunks;   // the automaton kernel may name a chunk in two entries
     if (need_rank > d->rank_cap || need_ovf > d->overflow_cap) {
         HIP_TRY(hipStreamSynchronize(stream));
         if (d->d_rank_mask) (void)hipFree(d->d_rank_mask);
@@ -586,16 +599,37 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     }
     a.fb_cap = e->opt.fallback_item_cap;
     a.mode = d->mode;
+    const bool automaton = e->opt.walk_mode != 1;
+    if (automaton) {
+        // LDS budgets of one block's automaton.  The set under construction gets the configured item
+        // budget (tests set it tiny to force the fallback pass), else room for sets a few times as wide
+        // as the widest current set; states and the item arena share what the tables leave of 160 KB.
+        size_t widest = 0;
+        for (int r = 0; r < nb; r++) {
+            const Chart &c = states[miss_rows[r]]->chart;
+            widest = std::max<size_t>(widest, c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1]);
+        }
+        int scratch = e->lane_cap_auto ? (int)std::min<size_t>(LANE_CAP_MAX, (4 * widest + 128 + 31) / 32 * 32) : e->opt.lane_item_cap;
+        int n_states = AUT_STATES_DEFAULT, arena = std::max(1024, 8 * scratch);
+        const uint32_t lds_max = 160u * 1024u;
+        while (automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch) > lds_max && arena > 2 * scratch) arena /= 2;
+        while (automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch) > lds_max && n_states > 8) n_states /= 2;
+        while (automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch) > lds_max && scratch > 32) { scratch /= 2; arena = std::max(arena / 2, 2 * scratch); }
+        if (automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch) > lds_max) return fail(ZF_ERR_INVALID_ARG, "the grammar tables leave no LDS for the mask automaton");
+        a.aut_states = n_states; a.aut_arena = arena; a.aut_scratch = scratch;
+        const int n_sub = (d->tab.Wr + AUT_SUB_WORDS - 1) / AUT_SUB_WORDS;
+        a.aut_parts = std::max(1, std::min(n_sub, (2 * std::max(1, d->cus) + std::max(nb, 1) - 1) / std::max(nb, 1)));
+    }
     const bool prof = d->profiling;
     d->report.chart_bytes = (int64_t)total;
     d->report.main_ms = d->report.fallback_ms = d->report.permute_ms = 0.f;
-    d->report.overflow_chunks = d->report.walk_chunks = 0;
+    d->report.overflow_chunks = d->report.walk_chunks = d->report.parser_steps = 0;
     // everything the host has to work out is done: enqueue the upload and the kernels back to back
     HIP_TRY(launch_upload(d->h_stage[slot], d->d_chart, total, stream));
     const bool run_kernels = nb > 0;
-    if (run_kernels && d->tab.n_chunks > 0) HIP_TRY(launch_cache_merge(a, stream));
+    if (run_kernels && d->tab.n_chunks > 0 && !automaton) HIP_TRY(launch_cache_merge(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
-    if (run_kernels && d->tab.n_chunks > 0) HIP_TRY(launch_mask_walk(a, stream));
+    if (run_kernels && d->tab.n_chunks > 0) HIP_TRY(automaton ? launch_mask_automaton(a, stream) : launch_mask_walk(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));
     if (run_kernels && !wait && d->tab.n_chunks > 0) HIP_TRY(launch_mask_fallback(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[2], stream));
@@ -650,7 +684,7 @@ int zf_mask_wait(zf_engine *e, void *hip_stream) {
     volatile uint32_t *st = d->h_status;
     for (int k = 0; k < DeviceSide::N_SLOTS; k++) {
         unresolved += st[4 * k + 2];
-        if (st[4 * k + 0] || st[4 * k + 1]) { d->report.overflow_chunks = st[4 * k + 0]; d->report.walk_chunks = st[4 * k + 1]; }
+        if (st[4 * k + 0] || st[4 * k + 1]) { d->report.overflow_chunks = st[4 * k + 0]; d->report.walk_chunks = st[4 * k + 1]; d->report.parser_steps = st[4 * k + 3]; }
         st[4 * k + 0] = st[4 * k + 1] = st[4 * k + 2] = st[4 * k + 3] = 0;
     }
     if (d->pending && d->profiling) {

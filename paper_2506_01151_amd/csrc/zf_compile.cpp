@@ -302,6 +302,7 @@ void build_trie(const zf_vocab_desc *v, int CHUNK_RANKS, const uint8_t *cls, Tri
         return a < b;
     });
     t.nodes.clear(); t.parent.clear(); t.rank_of.assign(V, 0xFFFFFFFFu);
+    t.str_off.clear(); t.str_bytes.clear();
     // Walk the sorted strings; the stack holds the node indices of the current path.
     std::vector<uint32_t> path;       // path[d-1] = node index at depth d
     std::vector<uint8_t> path_bytes;
@@ -324,8 +325,11 @@ void build_trie(const zf_vocab_desc *v, int CHUNK_RANKS, const uint8_t *cls, Tri
             t.nodes.push_back(nd);
         }
         t.rank_of[id] = rank++;
+        t.str_off.push_back((uint32_t)t.str_bytes.size());
+        t.str_bytes.insert(t.str_bytes.end(), p, p + n);
         prev = p; prev_n = n;
     }
+    t.str_off.push_back((uint32_t)t.str_bytes.size());
     t.n_strings = (int)rank;
     // skip pointers: next node in preorder whose depth is <= this node's depth
     {

@@ -47,6 +47,8 @@ struct TrieNode {
     uint32_t n_sub;      // strings carried by this node's subtree (itself included)
 };
 
+struct alignas(16) Str16 { uint32_t w[4]; };       // 16 one-byte symbols, first symbol in the low byte of w[0]
+
 static const int MAX_TOKEN_LEN_ON_DEVICE = 255;   // deeper nodes never occur: depth is a uint8
 static const int CHUNK_ANC = 16;                  // ancestors stored per chunk (longer paths use parent links)
 
@@ -69,6 +71,12 @@ struct DeviceTables {
     const uint32_t *chunk_end;   // [n_chunks] one past the last string node of the chunk
     const TrieNode *chunk_anc;   // [n_chunks][CHUNK_ANC] copies of the ancestors of the chunk's first node, depth 1 first
     const uint32_t *rank_of;    // [V] rank of token v's string, 0xFFFFFFFF for the empty token
+    // The distinct strings in rank order as strings of byte classes (the mask-automaton kernel reads
+    // a string front to back, one lane per string):
+    const uint32_t *str_off;    // [n_strings + 1] offsets into str_cls
+    const uint8_t *str_cls;     // classes of the strings' bytes, flat
+    const Str16 *str16;         // [n_strings] the first 16 classes of each string (zero padded), one aligned load
+    const uint8_t *cls_rep;     // [n_cls] one byte of each class (every DFA treats the bytes of a class alike)
     // Context-independent token-mask cache (paper Section 4.3), one bitset row of Wr words per DFA
     // state q (row q) and per nonterminal Y (row Q + Y), in string-rank order:
     const uint32_t *ci_valid;   // strings a terminal entered in state q swallows whole

@@ -61,6 +61,8 @@ struct Trie {
     std::vector<uint32_t> chunk_begin, chunk_end;
     std::vector<TrieNode> chunk_anc;   // [n_chunks][CHUNK_ANC]
     std::vector<uint32_t> rank_of;    // [V]
+    std::vector<uint32_t> str_off;    // [n_strings + 1] the distinct strings in rank order, flat: string r is
+    std::vector<uint8_t> str_bytes;   //   str_bytes[str_off[r] .. str_off[r+1])
     int n_strings = 0;
     int chunk_ranks = 32;
     int Wr = 0;                       // words per row of a rank-ordered bitmap

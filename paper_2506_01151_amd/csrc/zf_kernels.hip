@@ -668,6 +668,365 @@ __global__ __launch_bounds__(64) void mask_fallback_kernel(MaskArgs a) {
     }
 }
 
+// ---- mask automaton ------------------------------------------------------------------------------
+// The Earley set reached after a byte is a function of the set it came from, of the sets that
+// set's items point back to, and of the byte's equivalence class -- not of the token that is
+// being checked.  So the sets met while checking one row's tokens are the states of a
+// deterministic automaton over byte classes, and with a pruned chart (Section 4.2) it is tiny: a
+// few states, a few dozen transitions, while thousands of tokens need a verdict (Section 4.1).
+// A block builds the automaton of its row lazily in LDS: a transition is computed by one
+// wavefront-cooperative Earley byte step (Scan + Complete, tabulated Predict: Section 3.2) the
+// first time a string needs it and looked up from then on; sets are interned by content, so a
+// terminal that loops in place is a self loop (the state-cache idea of Section 5.2 inside one
+// mask).  Every lane then walks its own string through the transition table.
+//
+// An item of a state is (item word, origin reference); an origin reference is the index of a set
+// of the row's chart, or AUT_REF | id of another state of this automaton.  State 0 is the row's
+// current set and is read from the chart.
+static const uint32_t AUT_REF = 0x80000000u;
+enum : uint32_t { AT_NONE = 0xFFFFFFFFu,   // not computed yet
+                  AT_DEAD = 0xFFFFFFFEu,   // the byte leaves no item
+                  AT_SINK = 0xFFFFFFFDu,   // only completed items: the string may end here, nothing can follow
+                  AT_BUSY = 0xFFFFFFFCu,   // a wavefront is computing it
+                  AT_FAIL = 0xFFFFFFFBu }; // does not fit this block's budgets: such strings go to the fallback pass
+
+struct Aut {               // one block's automaton; every pointer leads into LDS
+    uint32_t *trans;       // [states_cap][ncls] next state or AT_*
+    uint2 *hdr;            // [states_cap] (first item in arena, item count); count 0xFFFFFFFF = not written yet
+    uint32_t *hash;        // [states_cap] content hash (filter for the interning compare)
+    uint2 *arena;          // [arena_cap] items of all states
+    uint32_t *ctl;         // [0] states handed out, [1] arena items handed out, [2] next batch of the string list, [3] length of the list
+    uint32_t states_cap, arena_cap, ncls;
+};
+
+__device__ __forceinline__ uint32_t lds_load(const uint32_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+__device__ __forceinline__ void lds_store(uint32_t *p, uint32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+
+// One Earley byte step from state s on byte class cl, done by a whole wavefront with uniform
+// control flow (all lanes call it with identical arguments).  The set under construction lives in
+// the wavefront's scratch (sc_w, sc_o); source sets of any size are read in strips of 64 items.
+// Returns the id of the (new or already known) state that holds the resulting set, or AT_DEAD /
+// AT_SINK / AT_FAIL.
+template <class BaseT>
+__device__ __forceinline__ uint32_t aut_transition(const TV &T, const BaseT &B, const Aut &A, uint32_t *sc_w, uint32_t *sc_o, uint32_t sc_cap,
+                                                   uint32_t s, uint32_t byte, uint32_t cl, uint32_t lane) {
+    auto view = [&](uint32_t ref, const uint2 *&p, uint32_t &n) {   // the items of the set an origin reference names
+        if (ref & AUT_REF) { const uint2 h = A.hdr[ref & ~AUT_REF]; p = A.arena + h.x; n = h.y; }
+        else { const uint32_t lo = B.so[ref]; p = B.it + lo; n = B.so[ref + 1] - lo; }
+    };
+    const uint32_t cur = s == 0 ? B.m - 1 : (AUT_REF | s);   // what items predicted in the source set get as origin
+    const uint2 *src;
+    uint32_t ns;
+    view(cur, src, ns);
+    uint32_t nnew = 0;
+    bool saw_end = false, failed = false;                    // failed: no room left in the scratch (sticky; the step runs on and reports at its end)
+    auto insert = [&](uint32_t w, uint32_t o) {              // uniform arguments
+        unsigned long long dup = 0;
+        for (uint32_t s0 = 0; s0 < nnew; s0 += 64) {
+            const bool in = s0 + lane < nnew;
+            uint32_t xw = 0, xo = 0;
+            if (in) { xw = sc_w[s0 + lane]; xo = sc_o[s0 + lane]; }
+            dup |= __ballot(in && xw == w && xo == o);
+        }
+        const bool add = !dup && nnew < sc_cap;
+        failed |= !dup && !add;
+        if (add && lane == 0) { sc_w[nnew] = w; sc_o[nnew] = o; }
+        nnew += add ? 1u : 0u;
+    };
+    auto advance = [&](uint32_t p, uint32_t o) {             // dot arrives at p: skip nullable nonterminals, canonical END item
+        for (;;) {
+            const uint32_t w = T.advpq[p];
+            insert(w, o);
+            if (w & IW_END) { saw_end = true; return; }
+            if ((w & IW_TERM) || !(w & IW_NT_NULLABLE)) return;
+            p++;
+        }
+    };
+    for (uint32_t s0 = 0; s0 < ns; s0 += 64) {
+        uint32_t sw = IW_END, so = 0;                        // lanes beyond the set hold an inert item
+        if (s0 + lane < ns) { const uint2 x = src[s0 + lane]; sw = x.x; so = x.y; }
+        // Scan, terminal items: all DFA steps at once, then the survivors one after the other
+        uint32_t nx = DFA_DEAD;
+        if (sw & IW_TERM) nx = dfa_next(T, sw >> 16, byte, cl);
+        unsigned long long m = __ballot((nx & 0xFFFFu) != DFA_DEAD);
+        while (m) {
+            const int l = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const uint32_t lw = __builtin_amdgcn_readlane(sw, l), lo = __builtin_amdgcn_readlane(so, l), lnx = __builtin_amdgcn_readlane(nx, l);
+            if ((lnx >> 16) & QF_CONT) insert((lw & 0xFFFFu) | (lnx << 16), lo);   // no longest match: keep matching ...
+            if ((lnx >> 16) & QF_ACCEPT) advance((lw & IW_POS_MASK) + 1, lo);      // ... and also finish here
+        }
+        // Scan, items that wait for a nonterminal Y: the tabulated first steps of every terminal that can begin Y
+        uint32_t sk0 = 0, sk1 = 0;
+        if (!(sw & (IW_TERM | IW_END))) {
+            const uint32_t Y = (sw >> IW_NT_SHIFT) & IW_NT_MASK;
+            sk0 = T.scan_off[Y * T.ncls + cl]; sk1 = T.scan_off[Y * T.ncls + cl + 1];
+        }
+        m = __ballot(sk1 > sk0);
+        while (m) {
+            const int l = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const uint32_t k0 = __builtin_amdgcn_readlane(sk0, l), k1 = __builtin_amdgcn_readlane(sk1, l);
+            for (uint32_t e0 = k0; e0 < k1; e0 += 64) {
+                uint2 ef = make_uint2(0, 0);
+                if (e0 + lane < k1) ef = T.scan_list[e0 + lane];
+                const uint32_t n_e = k1 - e0 < 64 ? k1 - e0 : 64;
+                for (uint32_t t = 0; t < n_e; t++) {
+                    const uint32_t ent = __builtin_amdgcn_readlane(ef.x, t), f = __builtin_amdgcn_readlane(ef.y, t);
+                    if (f & QF_CONT) insert(ent, cur);
+                    if (f & QF_ACCEPT) advance((ent & IW_POS_MASK) + 1, cur);
+                }
+            }
+        }
+    }
+    if (saw_end) {
+        // Complete: the new items are visited in order; completing may append more
+        for (uint32_t i = 0; i < nnew; i++) {
+            const uint32_t w = sc_w[i], o = sc_o[i];         // every lane reads the same item
+            if (!(w & IW_END)) continue;
+            const uint32_t X = (w & IW_POS_MASK) - T.end_base;
+            if (X == T.N - 1) continue;                      // the start rule is complete: the prefix is a sentence
+            const uint2 *yp;
+            uint32_t yn;
+            view(o, yp, yn);
+            for (uint32_t j0 = 0; j0 < yn; j0 += 64) {
+                uint32_t yw = IW_END, yo = 0;
+                if (j0 + lane < yn) { const uint2 y = yp[j0 + lane]; yw = y.x; yo = y.y; }
+                const bool nt = !(yw & (IW_TERM | IW_END));
+                const uint32_t Y = (yw >> IW_NT_SHIFT) & IW_NT_MASK;
+                uint32_t c0 = 0, c1 = 0;
+                if (nt) { c0 = T.comp_off[Y * T.N + X]; c1 = T.comp_off[Y * T.N + X + 1]; }
+                unsigned long long mm = __ballot(nt && c1 > c0);
+                while (mm) {
+                    const int l = __ffsll((long long)mm) - 1;
+                    mm &= mm - 1;
+                    const uint32_t lc0 = __builtin_amdgcn_readlane(c0, l), lc1 = __builtin_amdgcn_readlane(c1, l);
+                    for (uint32_t e = lc0; e < lc1; e++) {
+                        const uint32_t cw = T.comp_list[e];
+                        if (cw != 0xFFFFFFFFu) insert(cw, o);
+                        else advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l));   // Y itself is complete: the waiting item moves on
+                    }
+                }
+            }
+        }
+    }
+    if (failed) return AT_FAIL;
+    if (nnew == 0) return AT_DEAD;
+    // completed items are needed only while their own set is processed: drop them (forward compaction, a strip is read before it is written)
+    uint32_t kept = 0;
+    for (uint32_t s0 = 0; s0 < nnew; s0 += 64) {
+        uint32_t w = IW_END, o = 0;
+        if (s0 + lane < nnew) { w = sc_w[s0 + lane]; o = sc_o[s0 + lane]; }
+        const bool keep = !(w & IW_END);
+        const unsigned long long kb = __ballot(keep);
+        if (keep) { const uint32_t at = kept + __popcll(kb & ((1ull << lane) - 1ull)); sc_w[at] = w; sc_o[at] = o; }
+        kept += (uint32_t)__popcll(kb);
+    }
+    if (kept == 0) return AT_SINK;
+    // intern by content: the same items in the same order are the same state
+    uint32_t h = 0;
+    for (uint32_t i0 = 0; i0 < kept; i0 += 64)
+        if (i0 + lane < kept) h += ((sc_w[i0 + lane] * 0x9E3779B1u) ^ (sc_o[i0 + lane] * 0x85EBCA77u)) + (i0 + lane) * 0xC2B2AE3Du;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) h += __shfl_xor(h, d);
+    uint32_t n_st = lds_load(&A.ctl[0]);
+    n_st = n_st < A.states_cap ? n_st : A.states_cap;
+    for (uint32_t j0 = 1; j0 < n_st; j0 += 64) {
+        const uint32_t j = j0 + lane;
+        bool cand = false;
+        if (j < n_st) { const uint2 hj = A.hdr[j]; cand = hj.y == kept && A.hash[j] == h; }   // a state that is still being written has count 0xFFFFFFFF
+        unsigned long long m = __ballot(cand);
+        while (m) {
+            const int l = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const uint32_t id = j0 + (uint32_t)l;
+            const uint2 hj = A.hdr[id];
+            unsigned long long diff = 0;
+            for (uint32_t i0 = 0; i0 < kept; i0 += 64) {
+                bool ne = false;
+                if (i0 + lane < kept) { const uint2 x = A.arena[hj.x + i0 + lane]; ne = x.x != sc_w[i0 + lane] || x.y != sc_o[i0 + lane]; }
+                diff |= __ballot(ne);
+            }
+            if (!diff) return id;
+        }
+    }
+    uint32_t id = 0, at = 0;
+    if (lane == 0) { id = atomicAdd(&A.ctl[0], 1u); at = atomicAdd(&A.ctl[1], kept); }
+    id = (uint32_t)__builtin_amdgcn_readfirstlane((int)id);
+    at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+    if (id >= A.states_cap || at + kept > A.arena_cap) return AT_FAIL;
+    for (uint32_t i0 = 0; i0 < kept; i0 += 64)
+        if (i0 + lane < kept) A.arena[at + i0 + lane] = make_uint2(sc_w[i0 + lane], sc_o[i0 + lane]);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // items before the hash, the hash before the header that makes the state visible
+    if (lane == 0) A.hash[id] = h;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    if (lane == 0) A.hdr[id] = make_uint2(at, kept);
+    return id;
+}
+
+__host__ __device__ inline uint32_t aut_round16(uint32_t x) { return (x + 15u) & ~15u; }
+
+// Grid (parts, rows).  A block takes slices of AUT_SUB_WORDS words of its row's rank-ordered bitmap in
+// turn: it merges the token-mask cache rows of the row's current set (Section 4.3: strings a terminal
+// swallows whole are valid at once), lists the strings that need the parser, and its wavefronts
+// take the list in batches of 64 strings, one lane per string.  The verdicts of a slice are
+// collected in LDS and stored once: no atomics on global memory and nothing to clear beforehand.
+template <int MODE>
+__global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    const DeviceTables &D = a.tab;
+    const uint32_t tid = threadIdx.x, row = blockIdx.y, wave = tid >> 6, lane = tid & 63;
+    const uint32_t Wr = (uint32_t)D.Wr, n_sub = (Wr + AUT_SUB_WORDS - 1) / AUT_SUB_WORDS, n_strings = (uint32_t)D.n_strings;
+    if (blockIdx.x >= n_sub) return;
+    TV T;
+    uint32_t off = stage_tables<MODE>(D, smem, T, tid, AUT_BLOCK);
+    Aut A;
+    A.ncls = (uint32_t)D.n_cls; A.states_cap = (uint32_t)a.aut_states; A.arena_cap = (uint32_t)a.aut_arena;
+    const uint32_t sc_cap = (uint32_t)a.aut_scratch;
+    A.trans = reinterpret_cast<uint32_t *>(smem + off); off += aut_round16(A.states_cap * A.ncls * 4);
+    A.hdr = reinterpret_cast<uint2 *>(smem + off); off += aut_round16(A.states_cap * 8);
+    A.hash = reinterpret_cast<uint32_t *>(smem + off); off += aut_round16(A.states_cap * 4);
+    A.ctl = reinterpret_cast<uint32_t *>(smem + off); off += 16;
+    uint32_t *l_so = reinterpret_cast<uint32_t *>(smem + off); off += aut_round16((BASE_SETS_LDS + 1) * 4);
+    uint2 *l_it = reinterpret_cast<uint2 *>(smem + off); off += BASE_ITEMS_LDS * 8;
+    uint32_t *vslice = reinterpret_cast<uint32_t *>(smem + off); off += AUT_SUB_WORDS * 4;
+    uint16_t *list = reinterpret_cast<uint16_t *>(smem + off); off += AUT_SUB_WORDS * 32 * 2;
+    A.arena = reinterpret_cast<uint2 *>(smem + off); off += aut_round16(A.arena_cap * 8);
+    uint32_t *sc_w = reinterpret_cast<uint32_t *>(smem + off) + (size_t)wave * 2 * sc_cap;
+    uint32_t *sc_o = sc_w + sc_cap;
+    // the row's chart: its LDS copy when it is small, else global memory (generic pointers either way)
+    const RowChart rc = a.rows[row];
+    const uint32_t *g_so = a.set_off + rc.set_base;
+    const uint2 *g_it = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
+    const bool base_fits = rc.n_sets <= BASE_SETS_LDS && rc.n_items <= BASE_ITEMS_LDS;
+    if (base_fits) {
+        for (uint32_t k = tid; k <= rc.n_sets; k += AUT_BLOCK) l_so[k] = g_so[k];
+        for (uint32_t k = tid; k < rc.n_items; k += AUT_BLOCK) l_it[k] = g_it[k];
+    }
+    for (uint32_t k = tid; k < A.states_cap * A.ncls; k += AUT_BLOCK) A.trans[k] = AT_NONE;
+    for (uint32_t k = tid; k < A.states_cap; k += AUT_BLOCK) A.hdr[k] = make_uint2(0, 0xFFFFFFFFu);
+    if (tid == 0) { A.ctl[0] = 1; A.ctl[1] = 0; }
+    const uint32_t *b_so = base_fits ? l_so : g_so;
+    const uint2 *b_it = base_fits ? l_it : g_it;
+    uint32_t steps = 0;
+    const uint32_t cr = (uint32_t)D.chunk_ranks;
+    for (uint32_t g = blockIdx.x; g < n_sub; g += gridDim.x) {
+        const uint32_t w_base = g * AUT_SUB_WORDS;
+        if (tid == 0) { A.ctl[2] = 0; A.ctl[3] = 0; }
+        __syncthreads();                                     // also: tables, chart and automaton set-up are in place
+        // ---- merge the token-mask cache rows, list the undecided strings of the slice ----
+        if (tid < AUT_SUB_WORDS) {                           // whole wavefronts
+            const uint32_t w = w_base + tid;
+            uint32_t v = 0, c = 0;
+            if (w < Wr) {
+                if (rc.n_ent == 0) c = 0xFFFFFFFFu;
+                for (uint32_t k = 0; k < rc.n_ent; k++) {
+                    const size_t r = (size_t)a.entries[rc.ent_base + k] * Wr + w;
+                    v |= D.ci_valid[r]; c |= D.ci_cd[r];
+                }
+            }
+            uint32_t want = c & ~v;
+            const uint32_t r0 = w * 32u;                     // strings beyond the last one do not exist
+            if (r0 >= n_strings) want = 0;
+            else if (n_strings - r0 < 32u) want &= (1u << (n_strings - r0)) - 1u;
+            vslice[tid] = v;
+            const uint32_t cnt = (uint32_t)__popc(want);
+            uint32_t incl = cnt;                             // inclusive prefix sum over the lanes
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) { const uint32_t up = __shfl_up(incl, d); if ((int)lane >= d) incl += up; }
+            uint32_t base = 0;
+            if (lane == 63) base = atomicAdd(&A.ctl[3], incl);
+            base = __shfl(base, 63);
+            uint32_t at = base + incl - cnt;
+            while (want) { const uint32_t b = (uint32_t)__ffs((int)want) - 1u; want &= want - 1u; list[at++] = (uint16_t)(tid * 32u + b); }
+        }
+        __syncthreads();
+        const uint32_t n_list = A.ctl[3];
+        if (tid == 0 && n_list) atomicAdd(&a.counters[1], n_list);
+        const BaseG B{b_so, b_it, rc.n_sets, b_so[rc.n_sets - 1], rc.n_items};
+        // ---- one lane per string through the automaton ----
+        for (;;) {
+            uint32_t b = 0;
+            if (lane == 0) b = atomicAdd(&A.ctl[2], 1u);
+            b = (uint32_t)__builtin_amdgcn_readfirstlane((int)b);
+            if (b * 64u >= n_list) break;
+            const uint32_t idx = b * 64u + lane;
+            bool live = idx < n_list;
+            const uint32_t rel = live ? list[idx] : 0u;
+            const uint32_t rank = w_base * 32u + rel;
+            uint32_t soff = 0, len = 0;
+            Str16 c16{{0, 0, 0, 0}};
+            if (live) { soff = D.str_off[rank]; len = D.str_off[rank + 1] - soff; c16 = D.str16[rank]; }
+            live = live && len > 0;
+            uint32_t s = 0, pos = 0, c = 0, spins = 0;
+            bool ok = false, fail = false;
+            for (;;) {
+                while (live) {                               // every lane follows its own string as far as the table goes
+                    if (pos < 16u) {
+                        const uint32_t q = pos >> 2;
+                        const uint32_t word = q == 0 ? c16.w[0] : (q == 1 ? c16.w[1] : (q == 2 ? c16.w[2] : c16.w[3]));
+                        c = (word >> ((pos & 3u) * 8u)) & 0xFFu;
+                    } else c = D.str_cls[soff + pos];
+                    const uint32_t t = lds_load(&A.trans[s * A.ncls + c]);
+                    if (t < AT_FAIL) { s = t; pos++; if (pos == len) { ok = true; live = false; } }
+                    else if (t == AT_DEAD) live = false;
+                    else if (t == AT_SINK) { ok = pos + 1 == len; live = false; }
+                    else if (t == AT_FAIL) { fail = true; live = false; }
+                    else break;                              // not there yet
+                }
+                const unsigned long long pend = __ballot(live);
+                if (!pend) break;
+                // take one missing transition that nobody is computing yet and compute it
+                unsigned long long m = pend;
+                bool progress = false;
+                while (m) {
+                    const int l = __ffsll((long long)m) - 1;
+                    const uint32_t ls = __builtin_amdgcn_readlane(s, l), lc = __builtin_amdgcn_readlane(c, l);
+                    m &= ~__ballot(live && s == ls && c == lc);
+                    uint32_t *slot = &A.trans[ls * A.ncls + lc];
+                    uint32_t old = 0;
+                    if (lane == 0) old = atomicCAS(slot, (uint32_t)AT_NONE, (uint32_t)AT_BUSY);
+                    old = (uint32_t)__builtin_amdgcn_readfirstlane((int)old);
+                    if (old == AT_NONE) {
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");   // the states this step reads were published by other wavefronts
+                        const uint32_t r = aut_transition(T, B, A, sc_w, sc_o, sc_cap, ls, D.cls_rep[lc], lc, lane);
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the new state before the transition that leads to it
+                        if (lane == 0) lds_store(slot, r);
+                        steps++;
+                        progress = true;
+                        break;
+                    }
+                    if (old != AT_BUSY) { progress = true; break; }   // it has just been published
+                }
+                if (!progress) {                             // everything this wavefront waits for is being computed by others
+                    __builtin_amdgcn_s_sleep(4);
+                    if (++spins > (uint32_t)AUT_SPIN_LIMIT) { fail = fail || live; live = false; }   // bounded wait: hand the strings to the fallback
+                }
+            }
+            if (ok) atomicOr(&vslice[rel >> 5], 1u << (rel & 31u));
+            // strings this block could not decide: one fallback entry per trie chunk
+            unsigned long long fm = __ballot(fail);
+            const uint32_t my_chunk = rank / cr;
+            while (fm) {
+                const int l = __ffsll((long long)fm) - 1;
+                const uint32_t ch = __builtin_amdgcn_readlane(my_chunk, l);
+                const bool same = fail && my_chunk == ch;
+                fm &= ~__ballot(same);
+                uint32_t bits = same ? 1u << (rank % cr) : 0u;
+#pragma unroll
+                for (int d = 32; d >= 1; d >>= 1) bits |= __shfl_xor(bits, d);
+                if (lane == 0) {
+                    const uint32_t slot = atomicAdd(&a.counters[0], 1u);
+                    if (slot < a.overflow_cap) a.overflow_list[slot] = make_uint4(row, ch, bits, 0);
+                }
+            }
+        }
+        __syncthreads();
+        if (tid < AUT_SUB_WORDS && w_base + tid < Wr) a.rank_mask[(size_t)row * Wr + w_base + tid] = vslice[tid];
+    }
+    if (lane == 0 && steps) atomicAdd(&a.counters[3], steps);
+}
+
 // Verdicts are produced in trie order; the caller wants bit v at word v >> 5.  One lane per
 // token looks its bit up and a wavefront ballot packs 64 of them into two words.
 __global__ __launch_bounds__(256) void permute_kernel(MaskArgs a) {
@@ -770,6 +1129,7 @@ hipError_t prepare_kernels() {
     hipError_t e;
 #define SET_ATTR(k) if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k), hipFuncAttributeMaxDynamicSharedMemorySize, max_lds)) != hipSuccess) return e
     SET_ATTR(mask_walk_kernel<0>); SET_ATTR(mask_walk_kernel<1>); SET_ATTR(mask_walk_kernel<2>);
+    SET_ATTR(mask_automaton_kernel<0>); SET_ATTR(mask_automaton_kernel<1>); SET_ATTR(mask_automaton_kernel<2>);
 #undef SET_ATTR
     return hipSuccess;
 }
@@ -804,6 +1164,19 @@ hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s) {
     if (a.mode == 0) hipLaunchKernelGGL(mask_walk_kernel<0>, grid, dim3(WALK_BLOCK), lds, s, a);
     else if (a.mode == 1) hipLaunchKernelGGL(mask_walk_kernel<1>, grid, dim3(WALK_BLOCK), lds, s, a);
     else hipLaunchKernelGGL(mask_walk_kernel<2>, grid, dim3(WALK_BLOCK), lds, s, a);
+    return hipGetLastError();
+}
+uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int arena, int scratch) {
+    return table_bytes(t, mode) + aut_round16((uint32_t)states * (uint32_t)t.n_cls * 4) + aut_round16((uint32_t)states * 8) + aut_round16((uint32_t)states * 4) + 16 +
+           aut_round16((BASE_SETS_LDS + 1) * 4) + BASE_ITEMS_LDS * 8 + AUT_SUB_WORDS * 4 + AUT_SUB_WORDS * 32 * 2 + aut_round16((uint32_t)arena * 8) +
+           AUT_WAVES * (uint32_t)scratch * 8;
+}
+hipError_t launch_mask_automaton(const MaskArgs &a, hipStream_t s) {
+    const uint32_t lds = automaton_lds_bytes(a.tab, a.mode, a.aut_states, a.aut_arena, a.aut_scratch);
+    dim3 grid(a.aut_parts, a.batch);
+    if (a.mode == 0) hipLaunchKernelGGL(mask_automaton_kernel<0>, grid, dim3(AUT_BLOCK), lds, s, a);
+    else if (a.mode == 1) hipLaunchKernelGGL(mask_automaton_kernel<1>, grid, dim3(AUT_BLOCK), lds, s, a);
+    else hipLaunchKernelGGL(mask_automaton_kernel<2>, grid, dim3(AUT_BLOCK), lds, s, a);
     return hipGetLastError();
 }
 hipError_t launch_mask_fallback(const MaskArgs &a, hipStream_t s) {

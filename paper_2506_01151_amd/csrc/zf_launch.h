@@ -15,6 +15,11 @@ static const int WALK_DEPTH_MAX = 32;      // trie depth the walk kernel follows
 static const int BASE_SETS_LDS = 31;       // a row's chart is staged into LDS when it has at most this many sets ...
 static const int BASE_ITEMS_LDS = 64;      // ... and items
 static const int TABLE_LDS_BUDGET = 56 * 1024;
+static const int AUT_WAVES = 8;            // wavefronts per block of the mask-automaton kernel
+static const int AUT_BLOCK = AUT_WAVES * 64;
+static const int AUT_SUB_WORDS = 128;      // words of the rank-ordered bitmap (32 strings each) a block merges and checks at a time
+static const int AUT_STATES_DEFAULT = 64;  // automaton states a block can hold (more when LDS allows and the grammar is small)
+static const int AUT_SPIN_LIMIT = 1 << 16; // polls of a transition another wavefront is computing before giving the strings to the fallback
 static const int FB_DEPTH_MAX = 256;
 static const int FB_WAVES = 512;           // wavefronts of the fallback grid
 static const int FB_ITEMS_PER_WAVE = 65536; // its arena in global memory: items per wavefront (256 MB in all)
@@ -45,6 +50,11 @@ struct MaskArgs {
     int32_t fb_cap;            // item budget of a fallback wavefront (<= FB_ITEMS_PER_WAVE)
     int32_t walk_blocks;       // blocks of the walk grid (one and a half times what the chip holds at once)
     int32_t mode;              // 0: all tables staged in LDS, 1: the small ones only, 2: none
+    // mask-automaton kernel: capacities of one block's automaton in LDS
+    int32_t aut_states;        // states (rows of the transition table)
+    int32_t aut_arena;         // items of all states together
+    int32_t aut_scratch;       // items of one set under construction (per wavefront)
+    int32_t aut_parts;         // blocks per row (grid.x)
 };
 
 int choose_table_mode(const DeviceTables &t);
@@ -54,6 +64,8 @@ hipError_t prepare_kernels();   // one-time function attributes (dynamic LDS abo
 hipError_t launch_upload(const void *pinned_src, void *dst, size_t bytes, hipStream_t s);   // bytes rounded up to 16: both buffers must hold that much
 hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s);
+uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int arena, int scratch);
+hipError_t launch_mask_automaton(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_fallback(const MaskArgs &a, hipStream_t s);
 hipError_t launch_permute(const MaskArgs &a, hipStream_t s);
 hipError_t launch_gather(const MaskArgs &a, hipStream_t s);

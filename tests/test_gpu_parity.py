@@ -49,39 +49,46 @@ def _run_parity(torch, zf, Oracle, grammar, tokens, batch, steps, seed, check_ev
     return overflow
 
 
+MODES = {"automaton": 0, "trie-walk": 1}     # zf_options.walk_mode: both mask kernels must give the oracle's bits
+
+
+@pytest.mark.parametrize("mode", list(MODES))
 @pytest.mark.parametrize("cache", [True, False], ids=["token-mask-cache", "parser-only"])
-def test_config1_json_v2k_all_steps(cache, torch_cuda, oracle_lib):
+def test_config1_json_v2k_all_steps(cache, mode, torch_cuda, oracle_lib):
     import paper_2506_01151_amd as zf
     cfg = configs.CONFIGS[1]
-    _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(), cfg.batch, cfg.steps, cfg.seed, token_mask_cache=cache)
+    _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(), cfg.batch, cfg.steps, cfg.seed, token_mask_cache=cache, walk_mode=MODES[mode])
 
 
-def test_config2_json_v32k(torch_cuda, oracle_lib):
+@pytest.mark.parametrize("mode", list(MODES))
+def test_config2_json_v32k(mode, torch_cuda, oracle_lib):
     import paper_2506_01151_amd as zf
     cfg = configs.CONFIGS[2]
-    _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(), cfg.batch, cfg.steps, cfg.seed)
+    _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(), cfg.batch, cfg.steps, cfg.seed, walk_mode=MODES[mode])
 
 
-@pytest.mark.parametrize("cap", [1, 2, 4, 7])
-def test_forced_overflow_gives_same_bits(cap, torch_cuda, oracle_lib):
-    """A tiny LDS item budget pushes chunks to the global-memory fallback; the bits must not change."""
+# the item budget bounds one set under construction (automaton) or the sets of one trie path (trie walk)
+@pytest.mark.parametrize("mode,cap", [("automaton", 1), ("automaton", 2), ("automaton", 3), ("trie-walk", 1), ("trie-walk", 2), ("trie-walk", 4), ("trie-walk", 7)])
+def test_forced_overflow_gives_same_bits(mode, cap, torch_cuda, oracle_lib):
+    """A tiny LDS item budget pushes work to the global-memory fallback; the bits must not change."""
     import paper_2506_01151_amd as zf
     cfg = configs.CONFIGS[1]
-    ov = _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(), 2, 24, cfg.seed + 77, lane_item_cap=cap)
+    ov = _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(), 2, 24, cfg.seed + 77, lane_item_cap=cap, walk_mode=MODES[mode])
     assert ov > 0, "the cap was meant to force the fallback pass"
 
 
 @pytest.mark.parametrize("seed", range(16))
 def test_random_grammars(seed, torch_cuda, oracle_lib):
-    """Seeded random grammars (empty rules, unit cycles, all kinds of recursion, ambiguity): kernels
-    against the oracle at every step, once with the default item budget and once with a budget of
-    three items that sends most chunks through the fallback pass."""
+    """Seeded random grammars (empty rules, unit cycles, all kinds of recursion, ambiguity): both mask
+    kernels against the oracle at every step, once with the default item budget and once with a
+    budget of two or three items that sends much of the work through the fallback pass."""
     import paper_2506_01151_amd as zf
     from workloads import random_grammars
     g = random_grammars.random_grammar(seed)
     toks = random_grammars.random_vocab(seed, 400)
-    _run_parity(torch_cuda, zf, oracle_lib.Oracle, g, toks, 3, 20, 1000 + seed)
-    _run_parity(torch_cuda, zf, oracle_lib.Oracle, g, toks, 2, 12, 2000 + seed, lane_item_cap=3, token_mask_cache=seed % 2 == 0)
+    for mode in MODES.values():
+        _run_parity(torch_cuda, zf, oracle_lib.Oracle, g, toks, 3, 20, 1000 + seed, walk_mode=mode)
+        _run_parity(torch_cuda, zf, oracle_lib.Oracle, g, toks, 2, 12, 2000 + seed, lane_item_cap=3 - mode, token_mask_cache=seed % 2 == 0, walk_mode=mode)
 
 
 def test_overflow_beyond_the_fallback_is_an_error(torch_cuda):
@@ -104,17 +111,22 @@ def test_chunk_sizes(chunk, torch_cuda, oracle_lib):
     _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(2048 - 37), 3, 32, cfg.seed + 5, chunk_strings=chunk)
 
 
-REPLAY = [  # config, rows, steps, check every, rows compared with the oracle per check, pruning
-    (3, 16, 512, 37, 16, True),
-    (4, 64, 256, 31, 12, True),
-    (5, 8, 192, 23, 8, True),
-    (5, 8, 192, 47, 8, False),
-    (3, 16, 512, 61, 16, None),    # None: pruning on, token-mask cache off (every token through the parser)
+REPLAY = [  # config, rows, steps, check every, rows compared with the oracle per check, pruning, mask kernel
+    (3, 16, 512, 37, 16, True, "automaton"),
+    (4, 64, 256, 31, 12, True, "automaton"),
+    (5, 8, 192, 23, 8, True, "automaton"),
+    (5, 8, 192, 47, 8, False, "automaton"),
+    (3, 16, 512, 61, 16, None, "automaton"),    # None: pruning on, token-mask cache off (every token through the parser)
+    (3, 16, 512, 43, 16, True, "trie-walk"),
+    (4, 64, 256, 53, 12, True, "trie-walk"),
+    (5, 8, 192, 59, 8, True, "trie-walk"),
+    (3, 16, 512, 127, 16, None, "trie-walk"),
 ]
 
 
-@pytest.mark.parametrize("idx,rows,steps,every,n_cmp,pruning", REPLAY, ids=[f"cfg{r[0]}-" + {True: "pruned", False: "unpruned", None: "parser-only"}[r[5]] for r in REPLAY])
-def test_full_size_configs_replay(idx, rows, steps, every, n_cmp, pruning, torch_cuda, oracle_lib):
+@pytest.mark.parametrize("idx,rows,steps,every,n_cmp,pruning,mode", REPLAY,
+                         ids=[f"cfg{r[0]}-" + {True: "pruned", False: "unpruned", None: "parser-only"}[r[5]] + "-" + r[6] for r in REPLAY])
+def test_full_size_configs_replay(idx, rows, steps, every, n_cmp, pruning, mode, torch_cuda, oracle_lib):
     """Full vocabulary and batch of configurations 3-5 in the launch shape the benchmark uses:
     replay the oracle-sampled trajectory on both sides; at sampled steps one compute_mask call
     covers every row and sampled rows are compared bit for bit with the oracle's masks."""
@@ -125,7 +137,7 @@ def test_full_size_configs_replay(idx, rows, steps, every, n_cmp, pruning, torch
     off, data = wvocab.vocab_csr(toks)
     traj = load_trajectory(idx, rows, steps)
     g = cfg.grammar()
-    eng = zf.Engine(g, toks, device=0, pruning=pruning is not False, token_mask_cache=pruning is not None, state_cache_entries=-1)
+    eng = zf.Engine(g, toks, device=0, pruning=pruning is not False, token_mask_cache=pruning is not None, state_cache_entries=-1, walk_mode=MODES[mode])
     orc = oracle_lib.Oracle(g)
     so = [orc.new_state() for _ in range(rows)]
     ss = [eng.new_state() for _ in range(rows)]
