@@ -99,9 +99,29 @@ int setup_device(zf_engine *e) {
     int rc;
     std::vector<uint8_t> cls(t.cls, t.cls + 256);
 #define UP(field, vec, bytes) if ((rc = upload(d, vec, &T.field, bytes)) != ZF_OK) return rc
-    UP(advpq, t.advpq, &T.small_bytes[0]); UP(cls, cls, &T.small_bytes[1]);
-    UP(qinfo, t.qinfo, &T.small_bytes[2]); UP(scan_off, t.scan_off, &T.small_bytes[3]); UP(comp_off, t.comp_off, &T.small_bytes[4]);
-    UP(delta, t.delta_dense, &T.big_bytes[0]); UP(scan_list, t.dev_scan_list, &T.big_bytes[1]); UP(comp_list, t.dev_comp_list, &T.big_bytes[2]);
+    {   // the grammar tables in one allocation, in the order the kernels lay them out in LDS, each padded
+        // to 16 bytes: a block stages whatever prefix fits with one flat copy
+        std::vector<uint8_t> blob;
+        size_t at[8];
+        auto add = [&](const void *p, size_t bytes, uint32_t *padded, int k) {
+            at[k] = blob.size();
+            const size_t pad = (std::max<size_t>(bytes, 16) + 15) & ~(size_t)15;
+            blob.resize(blob.size() + pad, 0);
+            if (bytes) memcpy(blob.data() + at[k], p, bytes);
+            *padded = (uint32_t)pad;
+        };
+        add(t.advpq.data(), t.advpq.size() * 4, &T.small_bytes[0], 0); add(cls.data(), cls.size(), &T.small_bytes[1], 1);
+        add(t.qinfo.data(), t.qinfo.size() * 4, &T.small_bytes[2], 2); add(t.scan_off.data(), t.scan_off.size() * 4, &T.small_bytes[3], 3);
+        add(t.comp_off.data(), t.comp_off.size() * 4, &T.small_bytes[4], 4);
+        add(t.delta_dense.data(), t.delta_dense.size() * 4, &T.big_bytes[0], 5); add(t.dev_scan_list.data(), t.dev_scan_list.size() * 4, &T.big_bytes[1], 6);
+        add(t.dev_comp_list.data(), t.dev_comp_list.size() * 4, &T.big_bytes[2], 7);
+        const uint8_t *dev = nullptr;
+        if ((rc = upload(d, blob, &dev)) != ZF_OK) return rc;
+        T.table_blob = dev;
+        T.advpq = (const uint32_t *)(dev + at[0]); T.cls = dev + at[1]; T.qinfo = (const uint32_t *)(dev + at[2]);
+        T.scan_off = (const uint32_t *)(dev + at[3]); T.comp_off = (const uint32_t *)(dev + at[4]); T.delta = (const uint32_t *)(dev + at[5]);
+        T.scan_list = (const uint32_t *)(dev + at[6]); T.comp_list = (const uint32_t *)(dev + at[7]);
+    }
     UP(nodes, tr.nodes, nullptr); UP(parent, tr.parent, nullptr); UP(chunk_begin, tr.chunk_begin, nullptr); UP(chunk_end, tr.chunk_end, nullptr);
     UP(chunk_anc, tr.chunk_anc, nullptr); UP(rank_of, tr.rank_of, nullptr);
     UP(ci_valid, tr.ci_valid, nullptr); UP(ci_cd, tr.ci_cd, nullptr);
@@ -617,6 +637,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
         while (automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch) > lds_max && scratch > 32) { scratch /= 2; arena = std::max(arena / 2, 2 * scratch); }
         if (automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch) > lds_max) return fail(ZF_ERR_INVALID_ARG, "the grammar tables leave no LDS for the mask automaton");
         a.aut_states = n_states; a.aut_arena = arena; a.aut_scratch = scratch;
+        // blocks per row: enough to fill the chip about once, at most one block per pass of AUT_SUB_WORDS words
         const int n_sub = (d->tab.Wr + AUT_SUB_WORDS - 1) / AUT_SUB_WORDS;
         a.aut_parts = std::max(1, std::min(n_sub, (2 * std::max(1, d->cus) + std::max(nb, 1) - 1) / std::max(nb, 1)));
     }

@@ -63,6 +63,7 @@ struct DeviceTables {
     const uint32_t *delta;      // [dense rows][n_cls] next state | flags << 16, DFA_DEAD in the low half = no edge
     const uint32_t *scan_list;  // pairs: item word (terminal already stepped once), flags of its DFA state
     const uint32_t *comp_list;  // item words the completion adds; 0xFFFFFFFF: advance the waiting item itself
+    const uint8_t *table_blob;  // the eight tables above are one allocation in this order, each padded to 16 bytes
     uint32_t small_bytes[5];    // padded byte sizes of advpq .. comp_off (always staged into LDS when they fit)
     uint32_t big_bytes[3];      // padded byte sizes of delta, scan_list, comp_list
     const TrieNode *nodes;      // [n_nodes]

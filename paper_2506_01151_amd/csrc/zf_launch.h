@@ -17,7 +17,10 @@ static const int BASE_ITEMS_LDS = 64;      // ... and items
 static const int TABLE_LDS_BUDGET = 56 * 1024;
 static const int AUT_WAVES = 8;            // wavefronts per block of the mask-automaton kernel
 static const int AUT_BLOCK = AUT_WAVES * 64;
-static const int AUT_SUB_WORDS = 128;      // words of the rank-ordered bitmap (32 strings each) a block merges and checks at a time
+static const int AUT_SUB_WORDS = 128;      // words of the rank-ordered bitmap (32 strings each) a block merges and checks per pass ...
+static const int AUT_GROUP_WORDS = 8;      // ... taken from the row in groups of this many neighbouring words, dealt to the blocks round robin
+static const int AUT_ENT_LDS = 64;         // token-mask-cache rows of the row's current set kept in LDS (more are read from global memory)
+static const int AUT_TABLE_LOADS = (TABLE_LDS_BUDGET + AUT_BLOCK * 16 - 1) / (AUT_BLOCK * 16);   // 16-byte pieces of the staged tables per thread
 static const int AUT_STATES_DEFAULT = 64;  // automaton states a block can hold (more when LDS allows and the grammar is small)
 static const int AUT_SPIN_LIMIT = 1 << 16; // polls of a transition another wavefront is computing before giving the strings to the fallback
 static const int FB_DEPTH_MAX = 256;
