@@ -718,7 +718,9 @@ struct Aut {               // one block's automaton; every pointer leads into LD
     uint2 *hdr;            // [states_cap] (first item in arena, item count); count 0xFFFFFFFF = not written yet
     uint32_t *hash;        // [states_cap] signature of the content (filter for the interning compare)
     uint2 *arena;          // [arena_cap] items of all states
-    uint32_t *ctl;         // [0] states handed out, [1] arena items handed out, [2] next batch of the string list, [3] length of the list
+    uint32_t *ctl;         // [0] states handed out, [1] arena items handed out, [2] next batch of strings, [3] number of batches,
+                           // [4] help-queue places handed out, [5] help-queue places taken, [6] batches finished
+    uint32_t *hq;          // [AUT_HELP_QUEUE] transitions that wait for a free wavefront: HQ_VALID | state << 8 | class
     const uint8_t *rep;    // [ncls] one byte of each class
     uint32_t states_cap, arena_cap, ncls;
 };
@@ -752,6 +754,8 @@ __device__ __forceinline__ void aut_mark_dead(const TV &T, const Aut &A, ItemWor
         if (!alive) A.trans[id * A.ncls + c] = AT_DEAD;
     }
 }
+
+static const uint32_t HQ_VALID = 0x80000000u;
 
 __device__ __forceinline__ uint32_t lds_load(const uint32_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
 __device__ __forceinline__ void lds_store(uint32_t *p, uint32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
@@ -1056,6 +1060,40 @@ __device__ __forceinline__ uint32_t aut_transition(const TV &T, const BaseT &B, 
     return id;
 }
 
+// Compute the transition of state s on class cl (the caller owns it: its entry is AT_BUSY) and publish it.
+template <class BaseT>
+__device__ __forceinline__ void aut_resolve(const TV &T, const BaseT &B, const Aut &A, uint32_t *sc_w, uint32_t *sc_o, uint32_t sc_cap,
+                                            uint32_t s, uint32_t cl, uint32_t lane) {
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");   // the states this step reads were published by other wavefronts
+    const uint32_t r = aut_transition(T, B, A, sc_w, sc_o, sc_cap, s, A.rep[cl], cl, lane);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the new state before the transition that leads to it
+    if (lane == 0) lds_store(&A.trans[s * A.ncls + cl], r);
+}
+
+// A wavefront whose strings miss several transitions at once computes one and leaves the others in
+// the help queue; wavefronts that wait or have run out of strings take them from there.  Serves one
+// request if there is one; returns false when the queue is empty.  Uniform over the wavefront.
+template <class BaseT>
+__device__ __forceinline__ bool aut_help(const TV &T, const BaseT &B, const Aut &A, uint32_t *sc_w, uint32_t *sc_o, uint32_t sc_cap, uint32_t lane, uint32_t &steps) {
+    uint32_t tail = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&A.ctl[4]));
+    tail = tail < (uint32_t)AUT_HELP_QUEUE ? tail : (uint32_t)AUT_HELP_QUEUE;
+    const uint32_t head = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&A.ctl[5]));
+    if (head >= tail) return false;
+    uint32_t got = 0;
+    if (lane == 0) got = atomicCAS(&A.ctl[5], head, head + 1u) == head ? 1u : 0u;
+    if (!__builtin_amdgcn_readfirstlane((int)got)) return true;            // another wavefront took it: look again
+    uint32_t e = 0;
+    for (int tries = 0; tries < AUT_SPIN_LIMIT; tries++) {    // the entry is written right after its place was handed out
+        e = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&A.hq[head]));
+        if (e & HQ_VALID) break;
+        __builtin_amdgcn_s_sleep(1);
+    }
+    if (!(e & HQ_VALID) || (e & 0x7FFFFF00u) == 0x7FFFFF00u) return true;   // a place whose request was settled before it was queued
+    aut_resolve(T, B, A, sc_w, sc_o, sc_cap, (e & ~HQ_VALID) >> 8, e & 0xFFu, lane);
+    steps++;
+    return true;
+}
+
 __host__ __device__ inline uint32_t aut_round16(uint32_t x) { return (x + 15u) & ~15u; }
 
 // Grid (parts, rows).  A block takes slices of AUT_SUB_WORDS words of its row's rank-ordered bitmap in
@@ -1087,7 +1125,8 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
     A.trans = reinterpret_cast<uint32_t *>(smem + off); off += aut_round16(A.states_cap * A.ncls * 4);
     A.hdr = reinterpret_cast<uint2 *>(smem + off); off += aut_round16(A.states_cap * 8);
     A.hash = reinterpret_cast<uint32_t *>(smem + off); off += aut_round16(A.states_cap * 4);
-    A.ctl = reinterpret_cast<uint32_t *>(smem + off); off += 16;
+    A.ctl = reinterpret_cast<uint32_t *>(smem + off); off += 32;
+    A.hq = reinterpret_cast<uint32_t *>(smem + off); off += AUT_HELP_QUEUE * 4;
     uint32_t *l_so = reinterpret_cast<uint32_t *>(smem + off); off += aut_round16((BASE_SETS_LDS + 1) * 4);
     uint2 *l_it = reinterpret_cast<uint2 *>(smem + off); off += BASE_ITEMS_LDS * 8;
     uint32_t *l_ent = reinterpret_cast<uint32_t *>(smem + off); off += AUT_ENT_LDS * 4;
@@ -1123,7 +1162,8 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
     if (tid < 256) l_rep[tid] = rep_v;
     for (uint32_t k = tid; k < A.states_cap * A.ncls; k += AUT_BLOCK) A.trans[k] = AT_NONE;
     for (uint32_t k = tid; k < A.states_cap; k += AUT_BLOCK) A.hdr[k] = make_uint2(0, 0xFFFFFFFFu);
-    if (tid == 0) { A.ctl[0] = 1; A.ctl[1] = 0; }
+    for (uint32_t k = tid; k < (uint32_t)AUT_HELP_QUEUE; k += AUT_BLOCK) A.hq[k] = 0;
+    if (tid == 0) { A.ctl[0] = 1; A.ctl[1] = 0; A.ctl[4] = 0; A.ctl[5] = 0; }
     const uint32_t *b_ent = ent_fits ? l_ent : g_ent;
     const uint32_t *b_so = base_fits ? l_so : g_so;
     const uint2 *b_it = base_fits ? l_it : g_it;
@@ -1138,7 +1178,7 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
             const uint32_t grp = blockIdx.x + (j0 + t / AUT_GROUP_WORDS) * gridDim.x;
             return grp < n_groups ? grp * AUT_GROUP_WORDS + t % AUT_GROUP_WORDS : 0xFFFFFF00u;
         };
-        if (tid == 0) { A.ctl[2] = 0; A.ctl[3] = 0; }
+        if (tid == 0) { A.ctl[2] = 0; A.ctl[3] = 0; A.ctl[6] = 0; }
         if (tid < AUT_SUB_WORDS) { vslice[tid] = 0; cslice[tid] = rc.n_ent == 0 ? 0xFFFFFFFFu : 0u; }
         __syncthreads();                                     // also: tables, chart and automaton set-up are in place
         // ---- merge the token-mask cache rows (all threads: word slot tid % SUB, cache rows tid / SUB, + 4, ...) ----
@@ -1208,33 +1248,38 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
                 }
                 const unsigned long long pend = __ballot(live);
                 if (!pend) break;
-                // take one missing transition that nobody is computing yet and compute it
+                // Claim the missing transitions that nobody is computing yet: the first one is computed here,
+                // the others are left in the help queue for wavefronts that have nothing to do.
                 unsigned long long m = pend;
-                bool progress = false;
+                bool progress = false, mine = false;
+                uint32_t ms = 0, mc = 0;
                 while (m) {
                     const int l = __ffsll((long long)m) - 1;
                     const uint32_t ls = __builtin_amdgcn_readlane(s, l), lc = __builtin_amdgcn_readlane(c, l);
                     m &= ~__ballot(live && s == ls && c == lc);
                     uint32_t *slot = &A.trans[ls * A.ncls + lc];
                     uint32_t old = 0;
-                    if (lane == 0) old = atomicCAS(slot, (uint32_t)AT_NONE, (uint32_t)AT_BUSY);
+                    if (lane == 0) {
+                        bool room = true;
+                        uint32_t at = 0;
+                        if (mine) { at = atomicAdd(&A.ctl[4], 1u); room = at < (uint32_t)AUT_HELP_QUEUE; }   // a place in the queue first ...
+                        old = room ? atomicCAS(slot, (uint32_t)AT_NONE, (uint32_t)AT_BUSY) : (uint32_t)AT_BUSY;
+                        // ... which is filled in any case: with the request, or with one that is already settled (takers find it done)
+                        if (mine && room) lds_store(&A.hq[at], HQ_VALID | (old == AT_NONE ? (ls << 8) | lc : 0x7FFFFF00u));
+                    }
                     old = (uint32_t)__builtin_amdgcn_readfirstlane((int)old);
                     if (old == AT_NONE) {
-                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");   // the states this step reads were published by other wavefronts
-                        const uint32_t r = aut_transition(T, B, A, sc_w, sc_o, sc_cap, ls, l_rep[lc], lc, lane);
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the new state before the transition that leads to it
-                        if (lane == 0) lds_store(slot, r);
-                        steps++;
+                        if (!mine) { mine = true; ms = ls; mc = lc; }
                         progress = true;
-                        break;
-                    }
-                    if (old != AT_BUSY) { progress = true; break; }   // it has just been published
+                    } else if (old != AT_BUSY) progress = true;      // it has just been published
                 }
-                if (!progress) {                             // everything this wavefront waits for is being computed by others
+                if (mine) { aut_resolve(T, B, A, sc_w, sc_o, sc_cap, ms, mc, lane); steps++; }
+                if (!progress && !aut_help(T, B, A, sc_w, sc_o, sc_cap, lane, steps)) {   // everything this wavefront waits for is being computed by others
                     __builtin_amdgcn_s_sleep(4);
                     if (++spins > (uint32_t)AUT_SPIN_LIMIT) { fail = fail || live; live = false; }   // bounded wait: hand the strings to the fallback
                 }
             }
+            if (lane == 0) atomicAdd(&A.ctl[6], 1u);
             const unsigned long long okb = __ballot(ok);     // this wavefront is the only one that touches the pair's two words
             if (lane == 0 && okb) { vslice[2 * pair] |= (uint32_t)okb; vslice[2 * pair + 1] |= (uint32_t)(okb >> 32); }
             // strings this block could not decide: one fallback entry per trie chunk
@@ -1254,6 +1299,12 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
                 }
             }
         }
+        // out of strings: serve the help queue until every batch of the block is finished
+        for (uint32_t idle = 0; (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&A.ctl[6])) < n_pairs && idle < (uint32_t)AUT_SPIN_LIMIT;) {
+            if (aut_help(T, B, A, sc_w, sc_o, sc_cap, lane, steps)) idle = 0;
+            else { __builtin_amdgcn_s_sleep(4); idle++; }
+        }
+        while (aut_help(T, B, A, sc_w, sc_o, sc_cap, lane, steps)) {}       // nothing may stay marked as being computed
         __syncthreads();
         if (tid < AUT_SUB_WORDS) { const uint32_t w = word_of(tid); if (w < Wr) a.rank_mask[(size_t)row * Wr + w] = vslice[tid]; }
     }
@@ -1400,7 +1451,7 @@ hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s) {
     return hipGetLastError();
 }
 uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int arena, int scratch) {
-    return table_bytes(t, mode) + aut_round16((uint32_t)states * (uint32_t)t.n_cls * 4) + aut_round16((uint32_t)states * 8) + aut_round16((uint32_t)states * 4) + 16 +
+    return table_bytes(t, mode) + aut_round16((uint32_t)states * (uint32_t)t.n_cls * 4) + aut_round16((uint32_t)states * 8) + aut_round16((uint32_t)states * 4) + 32 + AUT_HELP_QUEUE * 4 +
            aut_round16((BASE_SETS_LDS + 1) * 4) + BASE_ITEMS_LDS * 8 + AUT_ENT_LDS * 4 + 256 + 2 * AUT_SUB_WORDS * 4 + AUT_SUB_WORDS / 2 + aut_round16((uint32_t)arena * 8) +
            AUT_WAVES * (uint32_t)scratch * 8;
 }
