@@ -2,7 +2,7 @@
 """Benchmark of the per-decode-step vocabulary mask on one MI355X.
 
 A "step" is one pass of the whole hot path over one batch: advance every row by its next
-token (host Earley + ZapFormat compaction), compute_mask (chart pack + upload, trie-walk
+token (host Earley + ZapFormat compaction), compute_mask (chart pack + upload, mask-automaton
 kernel, fallback pass, bit permutation; enqueued with compute_mask_async), apply_mask on that
 step's logits, and mask_wait (stream synchronisation + deferred error check).  The token
 trajectory is fixed beforehand (tests/golden/trajectory_cfgN.txt, sampled by the CPU oracle;
@@ -23,8 +23,8 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM traffic of one mask_walk_kernel launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
-# scaled by a plain copy of known size (profiles/mask_walk_kernel_cfg3_hbm_traffic.txt).  It describes the kernel
+# HBM traffic of one mask_automaton_kernel launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+# scaled by a plain copy of known size (profiles/mask_automaton_kernel_cfg3_hbm_traffic.txt).  It describes the kernel
 # sources with the digest below; once they change the figure is reported as null until it is measured again.
 MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 6518000, "apply_bytes_per_launch": 8493700,
                     "kernel_sources_sha256": "7b22b335517ce682b333e977f76f6689aeaaf82379a72d613f59e634e03e4898"}
@@ -143,6 +143,7 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pruning", type=int, default=1)
+    ap.add_argument("--walk-mode", type=int, default=0, help="mask kernel of the headline pass: 0 = mask automaton (default), 1 = trie walk")
     ap.add_argument("--headline-only", action="store_true",
                     help="run the warm-up and timed steps of the headline pass and nothing else (for hardware-counter runs, "
                          "where every dispatch of a kernel should belong to the same workload); prints a short JSON line")
@@ -165,7 +166,7 @@ def main():
     B, K, Wm = cfg.batch, args.steps, args.warmup
     toks = cfg.vocab()
     # headline engine: state cache off, so every row of every step goes through the mask kernels
-    eng = zf.Engine(cfg.grammar(), toks, device=0, pruning=bool(args.pruning), state_cache_entries=-1)
+    eng = zf.Engine(cfg.grammar(), toks, device=0, pruning=bool(args.pruning), state_cache_entries=-1, walk_mode=args.walk_mode)
     V, W = eng.V, eng.W
     need = max(K, Wm)
     traj = load_trajectory(args.config, B, need)
@@ -194,6 +195,7 @@ def main():
         eng.set_profiling(profile)
         states = zf.StateBatch([eng.new_state() for _ in range(B)])
         lat, adv, kern, ovf, hits, queued = [], [], {"main": [], "fallback": [], "permute": [], "apply": []}, 0, 0, 0
+        psteps = crows = 0
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_timed)] if profile else None
         t_begin = None
         for i in range(n_warm + n_timed):
@@ -226,30 +228,40 @@ def main():
                     kern["permute"].append(r.permute_ms)
                     ovf += r.overflow_chunks
                     queued += r.walk_chunks
+                    psteps += r.parser_steps
+                    crows += r.cache_rows
         torch.cuda.synchronize()
         total = time.perf_counter() - t_begin
         if profile:
             kern["apply"] = [a.elapsed_time(b) for a, b in evs]
-        return total, lat, adv, kern, ovf, eng.mask_report().chart_bytes, hits, queued
+        return total, lat, adv, kern, ovf, eng.mask_report().chart_bytes, hits, (queued, psteps, crows)
 
     total, lat, adv, _, _, _, _, _ = run(eng, Wm, K, False)
     if args.headline_only:
         print(json.dumps({"headline_only": True, "steps": K, "warmup": Wm, "ms_per_step": total / K * 1e3, "value": B * V * K / total}))
         return
-    _, _, _, kern, ovf, chart_bytes, _, queued = run(eng, Wm, K, True)     # same steps again with HIP events around each kernel
+    _, _, _, kern, ovf, chart_bytes, _, (queued, psteps, crows) = run(eng, Wm, K, True)     # same steps again with HIP events around each kernel
     # the same steps with the state cache (Section 5.2) on, starting cold: reported beside the headline
-    eng_sc = zf.Engine(cfg.grammar(), toks, device=0, pruning=bool(args.pruning))
+    eng_sc = zf.Engine(cfg.grammar(), toks, device=0, pruning=bool(args.pruning), walk_mode=args.walk_mode)
     sc_total, sc_lat, _, _, _, _, sc_hits, _ = run(eng_sc, Wm, K, False)
-    # live trie nodes (Earley byte steps) per mask from the host twin of the kernel, on every 16th step
-    live = {"steps": 0, "replay_steps": 0, "undecided": 0, "masks": 0}
+    del eng_sc
+    # and with the other mask kernel (trie walk when the headline runs the mask automaton), state cache off
+    eng_alt = zf.Engine(cfg.grammar(), toks, device=0, pruning=bool(args.pruning), state_cache_entries=-1, walk_mode=1 - args.walk_mode)
+    alt_total, alt_lat, _, _, _, _, _, _ = run(eng_alt, Wm, K, False)
+    del eng_alt
+    # what one row's automaton looks like, from the host twin of the kernel on every 16th step (the kernel
+    # builds a row's automaton once per block, so its own step count is a multiple of this)
+    live = {"states": 0, "steps": 0, "lookups": 0, "undecided": 0, "masks": 0}
     tw = [eng.new_state() for _ in range(B)]
     for i, ids in enumerate(traj[:K]):
         for b in range(B):
             tw[b].reset() if ids[b] < 0 else tw[b].advance(ids[b])
         if i % 16 == 0:
             for b in range(B):
-                _, st = tw[b].debug_host_mask_cached()
-                live["steps"] += st["steps"]; live["replay_steps"] += st["replay_steps"]; live["undecided"] += st["undecided"]; live["masks"] += 1
+                _, st = tw[b].debug_host_mask_automaton()
+                for k in ("states", "steps", "lookups", "undecided"):
+                    live[k] += st[k]
+                live["masks"] += 1
 
     ms_per_step = total / K * 1e3
     value = B * V * K / total
@@ -257,38 +269,50 @@ def main():
     info = eng.info
     main_ms = statistics.fmean(kern["main"])
     apply_ms = statistics.fmean(kern["apply"])
-    # algorithmic bytes of one mask-kernel launch: the trie (nodes 16 B + three 4-byte chunk tables and the
-    # ancestor table per 32 strings), the uploaded charts, and the rank-ordered verdict words written
-    n_chunks = (info.n_strings + 31) // 32
-    mask_bytes = info.n_trie_nodes * 16 + n_chunks * (8 + 64) + chart_bytes + B * n_chunks * 4
+    # algorithmic bytes of one mask-kernel launch (mask automaton): the token-mask-cache rows merged (two bitsets of
+    # Wr words per selected row), the rank-ordered verdict words written, 24 bytes per undecided string (its first 16
+    # byte classes and two offsets) and the uploaded charts.  (Trie walk: the trie nodes and chunk tables instead.)
+    Wr = (info.n_strings + 31) // 32
+    if args.walk_mode == 0:
+        mask_bytes = int(crows / K * Wr * 8 + B * Wr * 4 + queued / K * 24 + chart_bytes)
+    else:
+        n_chunks = (info.n_strings + 31) // 32
+        mask_bytes = info.n_trie_nodes * 16 + n_chunks * (8 + 64) + chart_bytes + B * n_chunks * 4
     apply_bytes = 2 * B * V * esz + B * W * 4
-    traffic_ok = args.config == MEASURED_TRAFFIC["config"] and args.pruning == 1 and kernel_sources_digest() == MEASURED_TRAFFIC["kernel_sources_sha256"]
+    traffic_ok = (args.config == MEASURED_TRAFFIC["config"] and args.pruning == 1 and args.walk_mode == 0
+                  and kernel_sources_digest() == MEASURED_TRAFFIC["kernel_sources_sha256"])
+    kname = "mask_automaton_kernel" if args.walk_mode == 0 else "mask_walk_kernel"
     result = {
         "metric": "vocab tokens checked/sec + p50 mask+apply latency per step (V=128k, B=16)",
         "value": value, "unit": "vocab tokens checked/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32", "data": "synthetic",
         "config": {"workload": f"configs[{args.config - 1}] {cfg.name}: grammar={cfg.grammar().name} V={V} batch={B} "
-                               f"logits={cfg.dtype} pruning={'on' if args.pruning else 'off'}", "trajectory": traj_src},
+                               f"logits={cfg.dtype} pruning={'on' if args.pruning else 'off'}", "trajectory": traj_src,
+                   "mask_kernel": kname},
         "p50_mask_apply_latency_us": pct(lat, 0.5) * 1e6, "p90_mask_apply_latency_us": pct(lat, 0.9) * 1e6,
         "p99_mask_apply_latency_us": pct(lat, 0.99) * 1e6,
         "mean_advance_us_per_step": statistics.fmean(adv) * 1e6,
         "kernel_ms": {k: statistics.fmean(v) for k, v in kern.items()},
         "kernel_ms_p50": {k: pct(v, 0.5) for k, v in kern.items()},
         "overflow_chunks_per_step": ovf / K,
-        "walk_chunks_per_step": queued / K,
-        "live_trie_nodes_per_mask": live["steps"] / live["masks"], "undecided_strings_per_mask": live["undecided"] / live["masks"],
-        "replayed_path_nodes_per_mask_upper_bound": live["replay_steps"] / live["masks"],
-        "live_trie_nodes_per_s": live["steps"] / live["masks"] * B * K / total,
+        "undecided_strings_per_step" if args.walk_mode == 0 else "walk_chunks_per_step": queued / K,
+        "earley_steps_per_launch": psteps / K,
+        "token_mask_cache_rows_per_step": crows / K,
+        "automaton_per_mask_host_twin": {"states": live["states"] / live["masks"], "earley_steps": live["steps"] / live["masks"],
+                                         "transition_lookups": live["lookups"] / live["masks"], "undecided_strings": live["undecided"] / live["masks"]},
         "with_state_cache": {"value": B * V * K / sc_total, "ms_per_step": sc_total / K * 1e3,
                              "p50_mask_apply_latency_us": pct(sc_lat, 0.5) * 1e6, "p99_mask_apply_latency_us": pct(sc_lat, 0.99) * 1e6,
                              "row_hit_rate": sc_hits / (B * K),
                              "note": "cache cleared when the timed steps start; the headline value runs with it off"},
-        "roofline": {"bound": "hbm", "kernel": "mask_walk_kernel", "achieved": mask_bytes / (main_ms * 1e-3) / 1e9,
+        "other_mask_kernel": {"kernel": "mask_walk_kernel" if args.walk_mode == 0 else "mask_automaton_kernel", "value": B * V * K / alt_total,
+                              "ms_per_step": alt_total / K * 1e3, "p50_mask_apply_latency_us": pct(alt_lat, 0.5) * 1e6},
+        "roofline": {"bound": "hbm", "kernel": kname, "achieved": mask_bytes / (main_ms * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": mask_bytes / (main_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC["bytes_per_launch"] if traffic_ok else None, "algorithmic_bytes": mask_bytes,
-                     "note": "integer trie walk; bound by the latency of short dependent instruction chains (about 470 instructions "
-                             "per Earley byte step), far below the HBM roof; the event pair also spans the dispatch gap before the kernel"},
+                     "note": "integer work: lazily built automaton of Earley sets + table look-ups per string; bound by the latency of the "
+                             "dependent chain of Earley byte steps a block has to take (a few microseconds each), far below the HBM roof; "
+                             "the event pair also spans the dispatch gap before the kernel"},
         "roofline_apply_mask": {"bound": "hbm", "kernel": "apply_mask_vec_kernel", "achieved": apply_bytes / (apply_ms * 1e-3) / 1e9,
                                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": apply_bytes / (apply_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                 "traffic": MEASURED_TRAFFIC["apply_bytes_per_launch"] if traffic_ok else None, "algorithmic_bytes": apply_bytes,

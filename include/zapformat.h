@@ -106,6 +106,7 @@ typedef struct {               /* facts about the last zf_compute_mask, for repo
     float main_ms, fallback_ms, permute_ms; /* kernel durations from HIP events on the call's
                                                stream; 0 unless zf_engine_set_profiling is on */
     int32_t parser_steps;      /* Earley byte steps the mask-automaton kernel took in the last call (all blocks) */
+    int32_t cache_rows;        /* token-mask-cache bitset rows merged in the last call (sum over its rows) */
 } zf_mask_report;
 
 /* compile(grammar rules, vocab byte strings): clean the grammar (useless rules, nullable

@@ -44,7 +44,7 @@ class EngineInfo(ctypes.Structure):
 
 class MaskReport(ctypes.Structure):
     _fields_ = [("overflow_chunks", c_i64), ("walk_chunks", c_i64), ("chart_bytes", c_i64), ("cache_hits", c_i32), ("cache_misses", c_i32), ("main_ms", ctypes.c_float),
-                ("fallback_ms", ctypes.c_float), ("permute_ms", ctypes.c_float), ("parser_steps", c_i32)]
+                ("fallback_ms", ctypes.c_float), ("permute_ms", ctypes.c_float), ("parser_steps", c_i32), ("cache_rows", c_i32)]
 
 
 EXPORTS = ["zf_strerror", "zf_last_error", "zf_compile", "zf_engine_destroy", "zf_engine_get_info",

@@ -643,6 +643,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     }
     const bool prof = d->profiling;
     d->report.chart_bytes = (int64_t)total;
+    d->report.cache_rows = (int32_t)n_ent;
     d->report.main_ms = d->report.fallback_ms = d->report.permute_ms = 0.f;
     d->report.overflow_chunks = d->report.walk_chunks = d->report.parser_steps = 0;
     // everything the host has to work out is done: enqueue the upload and the kernels back to back

@@ -1,25 +1,29 @@
-// HIP kernels for gfx950: the vocabulary-mask kernel (main pass + two exact fallback levels),
+// HIP kernels for gfx950: the vocabulary-mask kernels (mask automaton, trie walk, exact fallback),
 // the rank-order -> token-order bit permutation, and the logit-masking kernel.
 //
-// Mask path.  The vocabulary trie is stored in preorder, so a depth-first walk is a linear scan
-// in which a dead subtree is left through the node's skip pointer and a shared prefix is scanned
-// once.  A chunk is the node range of `chunk_ranks` consecutive strings.
-//   1. cache_merge_kernel: per (row, chunk) merge the context-independent token-mask cache
-//      (Section 4.3) of the row's current Earley set; strings a terminal swallows whole are valid
-//      at once; chunks that hold strings which need the parser go to the work queue.
-//   2. mask_walk_kernel: a persistent grid (as many blocks as the chip holds at once) whose
-//      wavefronts take queued chunks in turn.  The 64 lanes first pull the chunk's trie
-//      nodes, the ancestors of its first node and the row's chart into LDS; then the wavefront
-//      replays the ancestors and walks the nodes, one Earley byte step (Scan + Complete with
-//      tabulated Predict, Section 3.2) per node, on an item list in LDS that holds one set per
-//      trie depth of the current path.  The step is wavefront-cooperative with uniform control
-//      flow (wave_step): items of a set are spread over the lanes, the set under construction is
-//      held in registers, duplicate tests are ballots.  (Giving every lane its own chunk was
-//      measured first: the nests of short data-dependent loops of an Earley step then cost
-//      ~12,000 cycles per step per wavefront because every loop level runs for its longest
-//      trip count over the 64 lanes.)  Grammar tables are staged in LDS once per block.
-//   3. mask_fallback_kernel: chunks whose list outgrew LDS repeat the walk, one wavefront each,
-//      with the list in a global-memory arena.
+// Mask path.  The distinct vocabulary strings are numbered in sorted order (their rank); verdicts
+// are first produced in rank order.  The context-independent token-mask cache (Section 4.3) settles
+// most strings from the terminals of the row's current Earley set alone; the strings it leaves
+// undecided need the parser.  Two kernels can do that part (zf_options.walk_mode), both exact:
+//   mask_automaton_kernel (default): the Earley sets met while checking one row's strings are the
+//      states of a small deterministic automaton over byte classes.  A block merges the cache rows
+//      of a slice of its row's bitmap, builds the automaton lazily in LDS (one wavefront-cooperative
+//      Earley byte step per missing transition: Scan + Complete with tabulated Predict, Section 3.2)
+//      and walks every undecided string through the transition table, one lane per string.
+//   cache_merge_kernel + mask_walk_kernel: the vocabulary trie is stored in preorder, so a
+//      depth-first walk is a linear scan in which a dead subtree is left through the node's skip
+//      pointer and a shared prefix is scanned once.  A chunk is the node range of `chunk_ranks`
+//      consecutive strings; the merge kernel queues the chunks that hold undecided strings, and a
+//      persistent grid of wavefronts walks them, one Earley byte step per live trie node, on an item
+//      list in LDS that holds one set per trie depth of the current path.  The step is
+//      wavefront-cooperative with uniform control flow (wave_step): items of a set are spread over
+//      the lanes, the set under construction is held in registers, duplicate tests are ballots.
+//      (Giving every lane its own chunk was measured first: the nests of short data-dependent loops
+//      of an Earley step then cost ~12,000 cycles per step per wavefront because every loop level
+//      runs for its longest trip count over the 64 lanes.)  Grammar tables are staged in LDS once
+//      per block.
+//   mask_fallback_kernel: whatever did not fit the LDS budgets of either kernel repeats the trie
+//      walk, one wavefront per chunk, with the item list in a global-memory arena.
 #include <hip/hip_runtime.h>
 #include "zf_launch.h"
 

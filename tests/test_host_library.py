@@ -72,6 +72,7 @@ def test_small_grammars_every_prefix_every_token(gram, alphabet, pruning, zf, or
         assert s.accepting() == so.accepting(), p
         want = so.mask(off, data, 1)
         assert (s.debug_host_mask_cached()[0] == want).all(), (p, "token-mask cache")
+        assert (s.debug_host_mask_automaton()[0] == want).all(), (p, "mask automaton")
         got = s.debug_host_mask()
         assert (got == want).all(), (p, [toks[v] for v in range(len(toks)) if ((int(got[v >> 5]) ^ int(want[v >> 5])) >> (v & 31)) & 1])
         n_checked += 1
@@ -234,6 +235,9 @@ def test_config_trajectories_host_walk_matches_oracle(idx, rows, steps, every, z
                 for s in ss:
                     assert (s.debug_host_mask() == want).all(), (idx, b, step)
                     assert (s.debug_host_mask_cached()[0] == want).all(), (idx, b, step, "token-mask cache")
+                    got, st = s.debug_host_mask_automaton()
+                    assert (got == want).all(), (idx, b, step, "mask automaton")
+                    assert st["steps"] <= st["lookups"] and st["states"] <= st["steps"]   # at most one Earley step per new transition
                     assert s.accepting() == so.accepting()
         assert ss[0].stats().n_items <= ss[1].stats().n_items
 
@@ -285,6 +289,7 @@ def test_random_grammars_host_walk_equals_oracle(seed, zf, oracle_lib):
         for s in states:
             assert (s.debug_host_mask() == want).all(), (seed, step)
             assert (s.debug_host_mask_cached()[0] == want).all(), (seed, step, "token-mask cache")
+            assert (s.debug_host_mask_automaton()[0] == want).all(), (seed, step, "mask automaton")
             assert s.accepting() == run.states[0].accepting(), (seed, step)
         t = run.step(want[None, :])[0]
         for s in states:
