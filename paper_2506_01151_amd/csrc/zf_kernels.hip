@@ -1117,12 +1117,12 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
     TV T;
     uint32_t off = table_view<MODE>(D, smem, T);
     const uint32_t n16 = off / 16;
-    uint4 tb[AUT_TABLE_LOADS];
-#pragma unroll
-    for (int u = 0; u < AUT_TABLE_LOADS; u++) {
-        const uint32_t i = tid + (uint32_t)u * AUT_BLOCK;
-        if (i < n16) tb[u] = reinterpret_cast<const uint4 *>(D.table_blob)[i];
-    }
+    static_assert(AUT_TABLE_LOADS <= 7, "the staging below holds at most seven 16-byte pieces per thread");
+    const uint4 *blob = reinterpret_cast<const uint4 *>(D.table_blob);
+    uint4 tb0 = make_uint4(0, 0, 0, 0), tb1 = tb0, tb2 = tb0, tb3 = tb0, tb4 = tb0, tb5 = tb0, tb6 = tb0;   // named registers: an indexed array ends up in scratch memory
+#define ZF_STAGE_LOAD(u) if (tid + (u) * AUT_BLOCK < n16) tb##u = blob[tid + (u) * AUT_BLOCK];
+    ZF_STAGE_LOAD(0) ZF_STAGE_LOAD(1) ZF_STAGE_LOAD(2) ZF_STAGE_LOAD(3) ZF_STAGE_LOAD(4) ZF_STAGE_LOAD(5) ZF_STAGE_LOAD(6)
+#undef ZF_STAGE_LOAD
     Aut A;
     A.ncls = (uint32_t)D.n_cls; A.states_cap = (uint32_t)a.aut_states; A.arena_cap = (uint32_t)a.aut_arena;
     const uint32_t sc_cap = (uint32_t)a.aut_scratch;
@@ -1155,11 +1155,9 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
     if (base_fits && tid < rc.n_items) it_v = g_it[tid];
     if (ent_fits && tid < rc.n_ent) ent_v = g_ent[tid];
     const uint8_t rep_v = tid < A.ncls ? D.cls_rep[tid] : (uint8_t)0;
-#pragma unroll
-    for (int u = 0; u < AUT_TABLE_LOADS; u++) {
-        const uint32_t i = tid + (uint32_t)u * AUT_BLOCK;
-        if (i < n16) reinterpret_cast<uint4 *>(smem)[i] = tb[u];
-    }
+#define ZF_STAGE_STORE(u) if (tid + (u) * AUT_BLOCK < n16) reinterpret_cast<uint4 *>(smem)[tid + (u) * AUT_BLOCK] = tb##u;
+    ZF_STAGE_STORE(0) ZF_STAGE_STORE(1) ZF_STAGE_STORE(2) ZF_STAGE_STORE(3) ZF_STAGE_STORE(4) ZF_STAGE_STORE(5) ZF_STAGE_STORE(6)
+#undef ZF_STAGE_STORE
     if (base_fits && tid <= rc.n_sets) l_so[tid] = so_v;
     if (base_fits && tid < rc.n_items) l_it[tid] = it_v;
     if (ent_fits && tid < rc.n_ent) l_ent[tid] = ent_v;
