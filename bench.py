@@ -26,8 +26,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic of one mask_automaton_kernel launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # scaled by a plain copy of known size (profiles/mask_automaton_kernel_cfg3_hbm_traffic.txt).  It describes the kernel
 # sources with the digest below; once they change the figure is reported as null until it is measured again.
-MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 6518000, "apply_bytes_per_launch": 8493700,
-                    "kernel_sources_sha256": "7b22b335517ce682b333e977f76f6689aeaaf82379a72d613f59e634e03e4898"}
+MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 3538500, "apply_bytes_per_launch": 8508700,
+                    "kernel_sources_sha256": "7b88eb3a7d1a2a44b8935e781f3b76ea84ba182389b3b6495b02f4ae5cf96497"}
 
 
 def kernel_sources_digest():
