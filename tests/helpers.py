@@ -47,3 +47,23 @@ class OracleRun:
             assert s.feed_bytes(self.tokens[t])
             out.append(t)
         return out
+
+
+def edge_vocab_json(seed: int = 7):
+    """A JSON vocabulary that exercises the long and deep ends: every byte, tokens of 17-60 bytes (beyond the
+    16 bytes a lane of the mask-automaton kernel fetches at once), and runs of up to 120 opening brackets
+    (every nesting depth is another Earley set: more automaton states than a block keeps in LDS)."""
+    from workloads.rng import stream
+    rs = stream(seed, "edge-vocab")
+    toks = [bytes([c]) for c in range(256)]
+    alphabet = b'abcxyz019 ,:"[]{}-.e\\tn'
+    for _ in range(300):
+        n = 17 + rs.below(44)
+        toks.append(bytes(alphabet[rs.below(len(alphabet))] for _ in range(n)))
+    for k in range(1, 121):
+        toks.append(b"[" * k)
+        if k % 3 == 0:
+            toks.append(b"[" * k + b"1,")
+            toks.append(b"[" * (k // 2) + b'{"a":' + b"[" * (k // 2))
+    toks += [b'"' + b"a" * 30 + b'"', b'"' + b"a" * 30 + b'":', b"1" * 40, b"1" * 20 + b"." + b"5" * 20 + b"e-" + b"3" * 10, b" " * 50, b'{"k":"' + b"v" * 25 + b'"}']
+    return toks

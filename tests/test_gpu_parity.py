@@ -330,6 +330,39 @@ def test_edge_cases(torch_cuda, oracle_lib):
     assert d_mask.cpu().numpy().view(np.uint32).tolist() == [[0]] and s.accepting()
 
 
+@pytest.mark.parametrize("mode", list(MODES))
+def test_long_tokens_deep_nesting_many_classes(mode, torch_cuda, oracle_lib):
+    """Tokens longer than the 16 bytes a lane fetches at once, nesting deeper than the automaton's state budget
+    (those strings must come back through the fallback pass), and a grammar with more than 64 byte classes."""
+    import paper_2506_01151_amd as zf
+    from tests.helpers import edge_vocab_json
+    torch = torch_cuda
+    g = grammars.json_grammar()
+    toks = edge_vocab_json()
+    off, data = wvocab.vocab_csr(toks)
+    orc = oracle_lib.Oracle(g)
+    eng = zf.Engine(g, toks, device=0, state_cache_entries=-1, walk_mode=MODES[mode])
+    prefixes = [b"", b"[", b'{"k":"', b"[1,", b'[[{"a":[', b'{"k":"v', b"[1", b'["\\']
+    so, ss = [], []
+    for p in prefixes:
+        a, b = orc.new_state(), eng.new_state()
+        assert a.feed_bytes(p)
+        b.advance_bytes(p)
+        so.append(a)
+        ss.append(b)
+    d_mask = torch.full((len(prefixes), eng.W), -1, dtype=torch.int32, device="cuda")
+    zf.compute_mask(eng, ss, d_mask)
+    got = d_mask.cpu().numpy().view(np.uint32)
+    for i, a in enumerate(so):
+        assert (got[i] == a.mask(off, data, 4)).all(), prefixes[i]
+    if mode == "automaton":
+        assert eng.mask_report().overflow_chunks > 0, "runs of 120 brackets were meant to outgrow the state budget"
+    g2 = grammars.many_classes_grammar(100)
+    toks2 = [bytes([c]) for c in range(256)] + [bytes([32 + c, 32 + (c * 7 + 3) % 100]) for c in range(100)] + [bytes([32 + c, 32 + (c * 7 + 3) % 100, 32 + (c * 5) % 100]) for c in range(100)]
+    assert zf.Engine(g2, toks2, device=-1).info.n_byte_classes > 64
+    _run_parity(torch, zf, oracle_lib.Oracle, g2, toks2, 3, 12, 4242, walk_mode=MODES[mode])
+
+
 def test_apply_mask_full_size_bf16(torch_cuda, oracle_lib):
     """Configuration 3's logits shape [16, 128256] bf16, mask from a real state."""
     import paper_2506_01151_amd as zf

@@ -294,3 +294,33 @@ def test_random_grammars_host_walk_equals_oracle(seed, zf, oracle_lib):
         t = run.step(want[None, :])[0]
         for s in states:
             s.reset() if t < 0 else s.advance(t)
+
+
+def test_automaton_twin_long_tokens_deep_nesting_many_classes(zf, oracle_lib):
+    """The mask automaton's host twin on the inputs that stress its ends: tokens longer than 16 bytes, nesting
+    deeper than any state budget, more than 64 byte classes."""
+    from tests.helpers import edge_vocab_json
+    g = grammars.json_grammar()
+    toks = edge_vocab_json()
+    off, data = wvocab.vocab_csr(toks)
+    orc = oracle_lib.Oracle(g)
+    eng = zf.Engine(g, toks, device=-1)
+    for p in [b"", b"[", b'{"k":"', b"[1,", b'[[{"a":[', b'{"k":"v', b"[1", b'["\\']:
+        o, s = orc.new_state(), eng.new_state()
+        assert o.feed_bytes(p)
+        s.advance_bytes(p)
+        got, st = s.debug_host_mask_automaton()
+        assert (got == o.mask(off, data, 4)).all(), p
+        if p == b"[":
+            assert st["states"] > 64      # every nesting depth is a state of its own
+    g2 = grammars.many_classes_grammar(100)
+    toks2 = [bytes([c]) for c in range(256)] + [bytes([32 + c, 32 + (c * 7 + 3) % 100]) for c in range(100)] + [bytes([32 + c, 32 + (c * 7 + 3) % 100, 32 + (c * 5) % 100]) for c in range(100)]
+    off2, data2 = wvocab.vocab_csr(toks2)
+    orc2 = oracle_lib.Oracle(g2)
+    eng2 = zf.Engine(g2, toks2, device=-1)
+    assert eng2.info.n_byte_classes > 64
+    for p in [b"", bytes([40]), bytes([40, 32 + (8 * 7 + 3) % 100]), bytes([41, 32 + (9 * 7 + 3) % 100, 50])]:
+        o, s = orc2.new_state(), eng2.new_state()
+        assert o.feed_bytes(p)
+        s.advance_bytes(p)
+        assert (s.debug_host_mask_automaton()[0] == o.mask(off2, data2, 4)).all(), p

@@ -224,3 +224,15 @@ def multibyte_literal_grammar() -> Grammar:
     g.alts("S", ["K", "S"], ["K"])
     g.alts("K", [b"ab"], [b"abc"], [b"c"], [Rx(rb'ab*')], [b"(", "S", b")"])
     return g
+
+
+def many_classes_grammar(n: int = 100) -> Grammar:
+    """S -> T S | T ; T -> one of n two-byte literals whose first bytes are all different, so that the
+    terminals' automata tell more than 64 byte classes apart."""
+    g = Grammar(name=f"many_classes_{n}")
+    g.set_start("S")
+    g.rule("S", ["T", "S"])
+    g.rule("S", ["T"])
+    for c in range(n):
+        g.rule("T", [bytes([32 + c, 32 + (c * 7 + 3) % n])])
+    return g
