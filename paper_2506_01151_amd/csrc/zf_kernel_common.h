@@ -1,0 +1,120 @@
+// Device-side pieces shared by the mask kernels: the view of the grammar tables (in LDS or in global
+// memory), their staging, one DFA step, and the row's uploaded chart.
+#pragma once
+#include <hip/hip_runtime.h>
+#include "zf_launch.h"
+
+namespace zf {
+namespace {
+
+// Table view used by the device code; the pointers lead into LDS or global memory.
+struct TV {
+    const uint32_t *advpq;
+    const uint8_t *cls;
+    const uint32_t *qinfo;
+    const uint32_t *scan_off;
+    const uint32_t *comp_off;
+    const uint32_t *delta;
+    const uint2 *scan_list;
+    const uint32_t *comp_list;
+    uint32_t N, ncls, end_base;
+};
+
+__device__ __forceinline__ void copy16(void *dst, const void *src, uint32_t bytes, uint32_t tid, uint32_t nthreads) {
+    const uint4 *s = reinterpret_cast<const uint4 *>(src);
+    uint4 *d = reinterpret_cast<uint4 *>(dst);
+    for (uint32_t i = tid; i < bytes / 16; i += nthreads) d[i] = s[i];
+}
+
+// Stage the tables the MODE asks for into LDS at smem and build the view.  Returns the bytes used.
+// The caller must put a barrier between this and the first use.
+template <int MODE>
+__device__ __forceinline__ uint32_t stage_tables(const DeviceTables &D, uint8_t *smem, TV &tv, uint32_t tid, uint32_t nthreads) {
+    tv.N = D.N; tv.ncls = D.n_cls; tv.end_base = D.end_base;
+    uint32_t off = 0;
+    if (MODE <= 1) {
+        const void *src[5] = {D.advpq, D.cls, D.qinfo, D.scan_off, D.comp_off};
+        uint32_t at[5];
+#pragma unroll
+        for (int k = 0; k < 5; k++) { at[k] = off; copy16(smem + off, src[k], D.small_bytes[k], tid, nthreads); off += D.small_bytes[k]; }
+        tv.advpq = reinterpret_cast<const uint32_t *>(smem + at[0]);
+        tv.cls = smem + at[1];
+        tv.qinfo = reinterpret_cast<const uint32_t *>(smem + at[2]);
+        tv.scan_off = reinterpret_cast<const uint32_t *>(smem + at[3]);
+        tv.comp_off = reinterpret_cast<const uint32_t *>(smem + at[4]);
+    } else {
+        tv.advpq = D.advpq; tv.cls = D.cls; tv.qinfo = D.qinfo; tv.scan_off = D.scan_off; tv.comp_off = D.comp_off;
+    }
+    if (MODE == 0) {
+        const void *src[3] = {D.delta, D.scan_list, D.comp_list};
+        uint32_t at[3];
+#pragma unroll
+        for (int k = 0; k < 3; k++) { at[k] = off; copy16(smem + off, src[k], D.big_bytes[k], tid, nthreads); off += D.big_bytes[k]; }
+        tv.delta = reinterpret_cast<const uint32_t *>(smem + at[0]);
+        tv.scan_list = reinterpret_cast<const uint2 *>(smem + at[1]);
+        tv.comp_list = reinterpret_cast<const uint32_t *>(smem + at[2]);
+    } else {
+        tv.delta = D.delta; tv.scan_list = reinterpret_cast<const uint2 *>(D.scan_list); tv.comp_list = D.comp_list;
+    }
+    return off;
+}
+
+// The same view without the copy: the tables of the MODE are expected at the start of smem in the
+// order of DeviceTables::table_blob (the caller copies that prefix).  Returns the bytes they take.
+template <int MODE>
+__device__ __forceinline__ uint32_t table_view(const DeviceTables &D, uint8_t *smem, TV &tv) {
+    tv.N = D.N; tv.ncls = D.n_cls; tv.end_base = D.end_base;
+    tv.advpq = D.advpq; tv.cls = D.cls; tv.qinfo = D.qinfo; tv.scan_off = D.scan_off; tv.comp_off = D.comp_off;
+    tv.delta = D.delta; tv.scan_list = reinterpret_cast<const uint2 *>(D.scan_list); tv.comp_list = D.comp_list;
+    uint32_t off = 0;
+    if (MODE <= 1) {
+        tv.advpq = reinterpret_cast<const uint32_t *>(smem + off); off += D.small_bytes[0];
+        tv.cls = smem + off; off += D.small_bytes[1];
+        tv.qinfo = reinterpret_cast<const uint32_t *>(smem + off); off += D.small_bytes[2];
+        tv.scan_off = reinterpret_cast<const uint32_t *>(smem + off); off += D.small_bytes[3];
+        tv.comp_off = reinterpret_cast<const uint32_t *>(smem + off); off += D.small_bytes[4];
+    }
+    if (MODE == 0) {
+        tv.delta = reinterpret_cast<const uint32_t *>(smem + off); off += D.big_bytes[0];
+        tv.scan_list = reinterpret_cast<const uint2 *>(smem + off); off += D.big_bytes[1];
+        tv.comp_list = reinterpret_cast<const uint32_t *>(smem + off); off += D.big_bytes[2];
+    }
+    return off;
+}
+
+// One DFA step: returns next state | flags of the next state << 16, or DFA_DEAD in the low half.
+__device__ __forceinline__ uint32_t dfa_next(const TV &T, uint32_t q, uint32_t byte, uint32_t cl) {
+    const uint32_t info = T.qinfo[q];
+    if (info & QF_LITERAL) return (((info >> 8) & 0xFFu) == byte && (info & QF_CONT)) ? ((q + 1) | (info & 0xFFFF0000u)) : (uint32_t)DFA_DEAD;
+    return T.delta[(info >> 16) * T.ncls + cl];
+}
+
+template <class SoPtr, class ItPtr>
+struct Base {                  // the row's uploaded chart (LDS copy or global)
+    SoPtr so;                  // set offsets, so[k] .. so[k+1]
+    ItPtr it;                  // items: x = item word, y = origin
+    uint32_t m;                // number of sets; set m-1 is the current one
+    uint32_t last_lo, last_hi; // so[m-1], so[m]
+};
+typedef Base<const uint32_t *, const uint2 *> BaseG;
+
+__device__ __forceinline__ BaseG global_base(const MaskArgs &a, uint32_t row) {
+    const RowChart rc = a.rows[row];
+    BaseG B;
+    B.so = a.set_off + rc.set_base;
+    B.it = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
+    B.m = rc.n_sets;
+    B.last_lo = B.so[rc.n_sets - 1];
+    B.last_hi = B.so[rc.n_sets];
+    return B;
+}
+
+inline uint32_t table_bytes(const DeviceTables &t, int mode) {
+    uint32_t n = 0;
+    if (mode <= 1) for (int k = 0; k < 5; k++) n += t.small_bytes[k];
+    if (mode == 0) for (int k = 0; k < 3; k++) n += t.big_bytes[k];
+    return n;
+}
+
+}  // namespace
+}  // namespace zf

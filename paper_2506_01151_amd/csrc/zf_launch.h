@@ -64,7 +64,9 @@ struct MaskArgs {
 int choose_table_mode(const DeviceTables &t);
 uint32_t walk_lds_bytes(const DeviceTables &t, int mode, int lane_cap);   // dynamic LDS of one block of the walk kernel
 hipError_t walk_blocks_per_cu(int mode, uint32_t lds_bytes, int *out);   // resident blocks of the walk kernel per compute unit
-hipError_t prepare_kernels();   // one-time function attributes (dynamic LDS above 64 KB)
+hipError_t prepare_kernels();   // one-time function attributes (dynamic LDS above 64 KB) of all kernels:
+hipError_t prepare_walk_kernels();
+hipError_t prepare_automaton_kernels();
 hipError_t launch_upload(const void *pinned_src, void *dst, size_t bytes, hipStream_t s);   // bytes rounded up to 16: both buffers must hold that much
 hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s);

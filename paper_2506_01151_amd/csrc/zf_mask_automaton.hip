@@ -1,0 +1,650 @@
+// Mask kernel, default (zf_options.walk_mode = 0): mask_automaton_kernel.  What does not fit its LDS budgets goes to
+// mask_fallback_kernel (zf_mask_walk.hip).
+#include "zf_kernel_common.h"
+
+namespace zf {
+namespace {
+
+//
+// The Earley set reached after a byte is a function of the set it came from, of the sets that
+// set's items point back to, and of the byte's equivalence class -- not of the token that is
+// being checked.  So the sets met while checking one row's tokens are the states of a
+// deterministic automaton over byte classes, and with a pruned chart (Section 4.2) it is tiny: a
+// few states, a few dozen transitions, while thousands of tokens need a verdict (Section 4.1).
+// A block builds the automaton of its row lazily in LDS: a transition is computed by one
+// wavefront-cooperative Earley byte step (Scan + Complete, tabulated Predict: Section 3.2) the
+// first time a string needs it and looked up from then on; sets are interned by content, so a
+// terminal that loops in place is a self loop (the state-cache idea of Section 5.2 inside one
+// mask).  Every lane then walks its own string through the transition table.
+//
+// An item of a state is (item word, origin reference); an origin reference is the index of a set
+// of the row's chart, or AUT_REF | id of another state of this automaton.  State 0 is the row's
+// current set and is read from the chart.
+static const uint32_t AUT_REF = 0x80000000u;
+enum : uint32_t { AT_NONE = 0xFFFFFFFFu,   // not computed yet
+                  AT_DEAD = 0xFFFFFFFEu,   // the byte leaves no item
+                  AT_SINK = 0xFFFFFFFDu,   // only completed items: the string may end here, nothing can follow
+                  AT_BUSY = 0xFFFFFFFCu,   // a wavefront is computing it
+                  AT_FAIL = 0xFFFFFFFBu }; // does not fit this block's budgets: such strings go to the fallback pass
+
+struct Aut {               // one block's automaton; every pointer leads into LDS
+    uint32_t *trans;       // [states_cap][ncls] next state or AT_*
+    uint2 *hdr;            // [states_cap] (first item in arena, item count); count 0xFFFFFFFF = not written yet
+    uint32_t *hash;        // [states_cap] signature of the content (filter for the interning compare)
+    uint2 *arena;          // [arena_cap] items of all states
+    uint32_t *ctl;         // [0] states handed out, [1] arena items handed out, [2] next batch of strings, [3] number of batches,
+                           // [4] help-queue places handed out, [5] help-queue places taken, [6] batches finished
+    uint32_t *hq;          // [AUT_HELP_QUEUE] transitions that wait for a free wavefront: HQ_VALID | state << 8 | class
+    const uint8_t *rep;    // [ncls] one byte of each class
+    uint32_t states_cap, arena_cap, ncls;
+};
+
+// Transitions of state `id` that leave no item at all are settled when the state is made, for all
+// byte classes at once (lane = class): an item before a terminal survives a class iff its DFA has
+// an edge, an item that waits for a nonterminal iff some terminal that can begin it has one.  What
+// remains for the byte step proper are the few classes that lead somewhere.  item(i) is uniform.
+template <class ItemWord>
+__device__ __forceinline__ void aut_mark_dead(const TV &T, const Aut &A, ItemWord item, uint32_t n, uint32_t id, uint32_t lane) {
+    auto survives = [&](uint32_t w, uint32_t byte, uint32_t c) -> bool {   // no branch: both kinds of look-up are made, with safe indices
+        const bool term = (w & IW_TERM) != 0, end = (w & IW_END) != 0;
+        const uint32_t info = T.qinfo[term ? w >> 16 : 0u];
+        const bool lit = (info & QF_LITERAL) != 0;
+        const uint32_t d = T.delta[(lit ? 0u : info >> 16) * T.ncls + c];
+        const bool a_term = lit ? (((info >> 8) & 0xFFu) == byte && (info & QF_CONT)) : (d & 0xFFFFu) != DFA_DEAD;
+        const uint32_t Y = term || end ? 0u : (w >> IW_NT_SHIFT) & IW_NT_MASK;
+        const bool a_nt = T.scan_off[Y * T.ncls + c + 1] > T.scan_off[Y * T.ncls + c];
+        return !end && (term ? a_term : a_nt);
+    };
+    for (uint32_t c0 = 0; c0 < A.ncls; c0 += 64) {
+        const uint32_t c = c0 + lane < A.ncls ? c0 + lane : A.ncls - 1;   // surplus lanes repeat the last class
+        const uint32_t byte = A.rep[c];
+        bool alive = false;
+        for (uint32_t i = 0; i < n; i += 4) {                // four items at a time: their look-ups are independent of each other
+            const uint32_t w0 = item(i), w1 = i + 1 < n ? item(i + 1) : (uint32_t)IW_END, w2 = i + 2 < n ? item(i + 2) : (uint32_t)IW_END,
+                           w3 = i + 3 < n ? item(i + 3) : (uint32_t)IW_END;
+            const bool a0 = survives(w0, byte, c), a1 = survives(w1, byte, c), a2 = survives(w2, byte, c), a3 = survives(w3, byte, c);
+            alive |= a0 | a1 | a2 | a3;
+        }
+        if (!alive) A.trans[id * A.ncls + c] = AT_DEAD;
+    }
+}
+
+static const uint32_t HQ_VALID = 0x80000000u;
+
+__device__ __forceinline__ uint32_t lds_load(const uint32_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+__device__ __forceinline__ void lds_store(uint32_t *p, uint32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+
+// One Earley byte step from state s on byte class cl is done by a whole wavefront with uniform
+// control flow (all lanes call these functions with identical arguments).  Both variants leave the
+// new set, completed items dropped, in the wavefront's scratch (sc_w, sc_o) and return AUT_OK,
+// AUT_WIDE (narrow variant only: more than 64 new items) or AUT_OVER (no room).
+enum { AUT_OK = 0, AUT_WIDE = 1, AUT_OVER = 2 };
+
+template <class BaseT>
+struct AutSets {           // resolves origin references
+    const BaseT &B;
+    const Aut &A;
+    __device__ __forceinline__ void view(uint32_t ref, const uint2 *&p, uint32_t &n) const {
+        if (ref & AUT_REF) { const uint2 h = A.hdr[ref & ~AUT_REF]; p = A.arena + h.x; n = h.y; }
+        else { const uint32_t lo = B.so[ref]; p = B.it + lo; n = B.so[ref + 1] - lo; }
+    }
+};
+
+// Narrow variant: the set under construction lives in registers (lane j holds new item j), so the
+// duplicate test is one compare + ballot; the source set is read in strips of 64 items.
+template <class BaseT>
+__device__ __forceinline__ int aut_step_narrow(const TV &T, const AutSets<BaseT> &S, uint32_t *sc_w, uint32_t *sc_o, uint32_t sc_cap,
+                                               uint32_t cur, uint32_t byte, uint32_t cl, uint32_t lane, uint32_t &nnew_out, uint32_t &kept_out) {
+    const uint2 *src;
+    uint32_t ns;
+    S.view(cur, src, ns);
+    uint32_t nw = 0xFFFFFFFFu, no = 0, nnew = 0;             // no item word is all ones
+    bool saw_end = false, failed = false;                    // failed is sticky: the step runs on and reports at its end
+    const uint32_t room = sc_cap < 64u ? sc_cap : 64u;
+    auto insert = [&](uint32_t w, uint32_t o) {              // uniform arguments; no branch
+        const bool fresh = __ballot(nw == w && no == o) == 0;
+        const bool add = fresh && nnew < room;
+        failed |= fresh && !add;
+        const bool mine = add && lane == nnew;
+        nw = mine ? w : nw;
+        no = mine ? o : no;
+        nnew += add ? 1u : 0u;
+    };
+    auto advance = [&](uint32_t p, uint32_t o) {             // dot arrives at p: skip nullable nonterminals, canonical END item
+        for (;;) {
+            const uint32_t w = T.advpq[p];
+            insert(w, o);
+            if (w & IW_END) { saw_end = true; return; }
+            if ((w & IW_TERM) || !(w & IW_NT_NULLABLE)) return;
+            p++;
+        }
+    };
+    for (uint32_t s0 = 0; s0 < ns; s0 += 64) {
+        uint32_t sw = IW_END, so = 0;                        // lanes beyond the set hold an inert item
+        if (s0 + lane < ns) { const uint2 x = src[s0 + lane]; sw = x.x; so = x.y; }
+        // Scan, terminal items: all DFA steps at once, then the survivors one after the other
+        uint32_t nx = DFA_DEAD, aw = 0;
+        if (sw & IW_TERM) {
+            aw = T.advpq[(sw & IW_POS_MASK) + 1];            // the item behind the terminal, fetched alongside the DFA step
+            nx = dfa_next(T, sw >> 16, byte, cl);
+        }
+        unsigned long long m = __ballot((nx & 0xFFFFu) != DFA_DEAD);
+        while (m) {
+            const int l = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const uint32_t lw = __builtin_amdgcn_readlane(sw, l), lo = __builtin_amdgcn_readlane(so, l), lnx = __builtin_amdgcn_readlane(nx, l);
+            if ((lnx >> 16) & QF_CONT) insert((lw & 0xFFFFu) | (lnx << 16), lo);   // no longest match: keep matching ...
+            if ((lnx >> 16) & QF_ACCEPT) {                                         // ... and also finish here
+                const uint32_t law = __builtin_amdgcn_readlane(aw, l);
+                insert(law, lo);
+                if (law & IW_END) saw_end = true;
+                else if (!(law & IW_TERM) && (law & IW_NT_NULLABLE)) advance((lw & IW_POS_MASK) + 2, lo);
+            }
+        }
+        // Scan, items that wait for a nonterminal Y: the tabulated first steps of every terminal that can begin Y
+        uint32_t sk0 = 0, sk1 = 0;
+        if (!(sw & (IW_TERM | IW_END))) {
+            const uint32_t Y = (sw >> IW_NT_SHIFT) & IW_NT_MASK;
+            sk0 = T.scan_off[Y * T.ncls + cl]; sk1 = T.scan_off[Y * T.ncls + cl + 1];
+        }
+        m = __ballot(sk1 > sk0);
+        while (m) {
+            const int l = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const uint32_t k0 = __builtin_amdgcn_readlane(sk0, l), k1 = __builtin_amdgcn_readlane(sk1, l);
+            for (uint32_t e0 = k0; e0 < k1; e0 += 64) {
+                uint2 ef = make_uint2(0, 0);
+                if (e0 + lane < k1) ef = T.scan_list[e0 + lane];
+                const uint32_t n_e = k1 - e0 < 64 ? k1 - e0 : 64;
+                for (uint32_t t = 0; t < n_e; t++) {
+                    const uint32_t ent = __builtin_amdgcn_readlane(ef.x, t), f = __builtin_amdgcn_readlane(ef.y, t);
+                    if (f & QF_CONT) insert(ent, cur);
+                    if (f & QF_ACCEPT) advance((ent & IW_POS_MASK) + 1, cur);
+                }
+            }
+        }
+    }
+    if (saw_end) {
+        // Complete: new items are visited in order; completing may append more
+        unsigned long long visited = 0;
+        for (;;) {
+            const unsigned long long todo = __ballot(lane < nnew && (nw & IW_END)) & ~visited;
+            if (!todo) break;
+            const int i = __ffsll((long long)todo) - 1;
+            visited |= 1ull << i;
+            const uint32_t w = __builtin_amdgcn_readlane(nw, i);
+            const uint32_t X = (w & IW_POS_MASK) - T.end_base;
+            if (X == T.N - 1) continue;                      // the start rule is complete: the prefix is a sentence
+            const uint32_t o = __builtin_amdgcn_readlane(no, i);
+            const uint2 *yp;
+            uint32_t yn;
+            S.view(o, yp, yn);
+            for (uint32_t j0 = 0; j0 < yn; j0 += 64) {
+                uint32_t yw = IW_END, yo = 0;
+                if (j0 + lane < yn) { const uint2 y = yp[j0 + lane]; yw = y.x; yo = y.y; }
+                const bool nt = !(yw & (IW_TERM | IW_END));
+                const uint32_t Y = (yw >> IW_NT_SHIFT) & IW_NT_MASK;
+                uint32_t c0 = 0, c1 = 0, cw0 = 0;
+                if (nt) { c0 = T.comp_off[Y * T.N + X]; c1 = T.comp_off[Y * T.N + X + 1]; }
+                if (c1 > c0) cw0 = T.comp_list[c0];          // every lane fetches the first entry of its own list
+                unsigned long long mm = __ballot(nt && c1 > c0);
+                while (mm) {
+                    const int l = __ffsll((long long)mm) - 1;
+                    mm &= mm - 1;
+                    const uint32_t lc0 = __builtin_amdgcn_readlane(c0, l), lc1 = __builtin_amdgcn_readlane(c1, l);
+                    for (uint32_t e = lc0; e < lc1; e++) {
+                        const uint32_t cw = e == lc0 ? (uint32_t)__builtin_amdgcn_readlane(cw0, l) : T.comp_list[e];
+                        if (cw != 0xFFFFFFFFu) insert(cw, o);
+                        else advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l));   // Y itself is complete: the waiting item moves on
+                    }
+                }
+            }
+        }
+    }
+    if (failed) return nnew >= 64u ? AUT_WIDE : AUT_OVER;
+    // completed items are needed only while their own set is processed: store the others
+    const bool keep = lane < nnew && !(nw & IW_END);
+    const unsigned long long kb = __ballot(keep);
+    if (keep) { const uint32_t at = (uint32_t)__popcll(kb & ((1ull << lane) - 1ull)); sc_w[at] = nw; sc_o[at] = no; }
+    nnew_out = nnew;
+    kept_out = (uint32_t)__popcll(kb);
+    return AUT_OK;
+}
+
+// Wide variant (ambiguous grammars make sets of hundreds of items): the set under construction lives
+// in the scratch and every loop over its items runs in strips of 64.
+template <class BaseT>
+__device__ __forceinline__ int aut_step_wide(const TV &T, const AutSets<BaseT> &S, uint32_t *sc_w, uint32_t *sc_o, uint32_t sc_cap,
+                                             uint32_t cur, uint32_t byte, uint32_t cl, uint32_t lane, uint32_t &nnew_out, uint32_t &kept_out) {
+    const uint2 *src;
+    uint32_t ns;
+    S.view(cur, src, ns);
+    uint32_t nnew = 0;
+    bool saw_end = false, failed = false;
+    auto insert = [&](uint32_t w, uint32_t o) {              // uniform arguments
+        unsigned long long dup = 0;
+        for (uint32_t s0 = 0; s0 < nnew; s0 += 64) {
+            const bool in = s0 + lane < nnew;
+            uint32_t xw = 0, xo = 0;
+            if (in) { xw = sc_w[s0 + lane]; xo = sc_o[s0 + lane]; }
+            dup |= __ballot(in && xw == w && xo == o);
+        }
+        const bool add = !dup && nnew < sc_cap;
+        failed |= !dup && !add;
+        if (add && lane == 0) { sc_w[nnew] = w; sc_o[nnew] = o; }
+        nnew += add ? 1u : 0u;
+    };
+    auto advance = [&](uint32_t p, uint32_t o) {
+        for (;;) {
+            const uint32_t w = T.advpq[p];
+            insert(w, o);
+            if (w & IW_END) { saw_end = true; return; }
+            if ((w & IW_TERM) || !(w & IW_NT_NULLABLE)) return;
+            p++;
+        }
+    };
+    for (uint32_t s0 = 0; s0 < ns; s0 += 64) {
+        uint32_t sw = IW_END, so = 0;
+        if (s0 + lane < ns) { const uint2 x = src[s0 + lane]; sw = x.x; so = x.y; }
+        uint32_t nx = DFA_DEAD;
+        if (sw & IW_TERM) nx = dfa_next(T, sw >> 16, byte, cl);
+        unsigned long long m = __ballot((nx & 0xFFFFu) != DFA_DEAD);
+        while (m) {
+            const int l = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const uint32_t lw = __builtin_amdgcn_readlane(sw, l), lo = __builtin_amdgcn_readlane(so, l), lnx = __builtin_amdgcn_readlane(nx, l);
+            if ((lnx >> 16) & QF_CONT) insert((lw & 0xFFFFu) | (lnx << 16), lo);
+            if ((lnx >> 16) & QF_ACCEPT) advance((lw & IW_POS_MASK) + 1, lo);
+        }
+        uint32_t sk0 = 0, sk1 = 0;
+        if (!(sw & (IW_TERM | IW_END))) {
+            const uint32_t Y = (sw >> IW_NT_SHIFT) & IW_NT_MASK;
+            sk0 = T.scan_off[Y * T.ncls + cl]; sk1 = T.scan_off[Y * T.ncls + cl + 1];
+        }
+        m = __ballot(sk1 > sk0);
+        while (m) {
+            const int l = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const uint32_t k0 = __builtin_amdgcn_readlane(sk0, l), k1 = __builtin_amdgcn_readlane(sk1, l);
+            for (uint32_t e = k0; e < k1; e++) {
+                const uint2 ef = T.scan_list[e];
+                if (ef.y & QF_CONT) insert(ef.x, cur);
+                if (ef.y & QF_ACCEPT) advance((ef.x & IW_POS_MASK) + 1, cur);
+            }
+        }
+    }
+    if (saw_end) {
+        for (uint32_t i = 0; i < nnew; i++) {
+            const uint32_t w = sc_w[i], o = sc_o[i];         // every lane reads the same item
+            if (!(w & IW_END)) continue;
+            const uint32_t X = (w & IW_POS_MASK) - T.end_base;
+            if (X == T.N - 1) continue;
+            const uint2 *yp;
+            uint32_t yn;
+            S.view(o, yp, yn);
+            for (uint32_t j0 = 0; j0 < yn; j0 += 64) {
+                uint32_t yw = IW_END, yo = 0;
+                if (j0 + lane < yn) { const uint2 y = yp[j0 + lane]; yw = y.x; yo = y.y; }
+                const bool nt = !(yw & (IW_TERM | IW_END));
+                const uint32_t Y = (yw >> IW_NT_SHIFT) & IW_NT_MASK;
+                uint32_t c0 = 0, c1 = 0;
+                if (nt) { c0 = T.comp_off[Y * T.N + X]; c1 = T.comp_off[Y * T.N + X + 1]; }
+                unsigned long long mm = __ballot(nt && c1 > c0);
+                while (mm) {
+                    const int l = __ffsll((long long)mm) - 1;
+                    mm &= mm - 1;
+                    const uint32_t lc0 = __builtin_amdgcn_readlane(c0, l), lc1 = __builtin_amdgcn_readlane(c1, l);
+                    for (uint32_t e = lc0; e < lc1; e++) {
+                        const uint32_t cw = T.comp_list[e];
+                        if (cw != 0xFFFFFFFFu) insert(cw, o);
+                        else advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l));
+                    }
+                }
+            }
+        }
+    }
+    if (failed) return AUT_OVER;
+    // drop the completed items: forward compaction, strip by strip (a strip is read before it is written)
+    uint32_t kept = 0;
+    for (uint32_t s0 = 0; s0 < nnew; s0 += 64) {
+        uint32_t w = IW_END, o = 0;
+        if (s0 + lane < nnew) { w = sc_w[s0 + lane]; o = sc_o[s0 + lane]; }
+        const bool keep = !(w & IW_END);
+        const unsigned long long kb = __ballot(keep);
+        if (keep) { const uint32_t at = kept + (uint32_t)__popcll(kb & ((1ull << lane) - 1ull)); sc_w[at] = w; sc_o[at] = o; }
+        kept += (uint32_t)__popcll(kb);
+    }
+    nnew_out = nnew;
+    kept_out = kept;
+    return AUT_OK;
+}
+
+// The transition of state s on class cl: take the byte step, then find the state that holds the
+// resulting set (sets are interned by content: the same items in the same order are the same
+// state) or make a new one.  Returns a state id or AT_DEAD / AT_SINK / AT_FAIL.
+template <class BaseT>
+__device__ __forceinline__ uint32_t aut_transition(const TV &T, const BaseT &B, const Aut &A, uint32_t *sc_w, uint32_t *sc_o, uint32_t sc_cap,
+                                                   uint32_t s, uint32_t byte, uint32_t cl, uint32_t lane) {
+    const AutSets<BaseT> S{B, A};
+    const uint32_t cur = s == 0 ? B.m - 1 : (AUT_REF | s);   // the source set; also what items predicted in it get as origin
+    uint32_t nnew = 0, kept = 0;
+    const uint2 *src_p;
+    uint32_t src_n;
+    S.view(cur, src_p, src_n);
+    int st = src_n > 48u ? AUT_WIDE : aut_step_narrow(T, S, sc_w, sc_o, sc_cap, cur, byte, cl, lane, nnew, kept);   // a wide source set rarely leaves a narrow one
+    if (st == AUT_WIDE) st = aut_step_wide(T, S, sc_w, sc_o, sc_cap, cur, byte, cl, lane, nnew, kept);
+    if (st != AUT_OK) return AT_FAIL;
+    if (nnew == 0) return AT_DEAD;
+    if (kept == 0) return AT_SINK;
+    // a cheap signature (first and last item) filters the candidates of the content compare
+    const uint32_t h = (sc_w[0] * 0x9E3779B1u) ^ (sc_o[0] * 0x85EBCA77u) ^ (sc_w[kept - 1] * 0xC2B2AE3Du) ^ sc_o[kept - 1];
+    uint32_t n_st = lds_load(&A.ctl[0]);
+    n_st = n_st < A.states_cap ? n_st : A.states_cap;
+    for (uint32_t j0 = 1; j0 < n_st; j0 += 64) {
+        const uint32_t j = j0 + lane;
+        bool cand = false;
+        if (j < n_st) { const uint2 hj = A.hdr[j]; cand = hj.y == kept && A.hash[j] == h; }   // a state that is still being written has count 0xFFFFFFFF
+        unsigned long long m = __ballot(cand);
+        while (m) {
+            const int l = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const uint32_t id = j0 + (uint32_t)l;
+            const uint2 hj = A.hdr[id];
+            unsigned long long diff = 0;
+            for (uint32_t i0 = 0; i0 < kept; i0 += 64) {
+                bool ne = false;
+                if (i0 + lane < kept) { const uint2 x = A.arena[hj.x + i0 + lane]; ne = x.x != sc_w[i0 + lane] || x.y != sc_o[i0 + lane]; }
+                diff |= __ballot(ne);
+            }
+            if (!diff) return id;
+        }
+    }
+    uint32_t id = 0, at = 0;
+    if (lane == 0) { id = atomicAdd(&A.ctl[0], 1u); at = atomicAdd(&A.ctl[1], kept); }
+    id = (uint32_t)__builtin_amdgcn_readfirstlane((int)id);
+    at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+    if (id >= A.states_cap || at + kept > A.arena_cap) return AT_FAIL;
+    for (uint32_t i0 = 0; i0 < kept; i0 += 64)
+        if (i0 + lane < kept) A.arena[at + i0 + lane] = make_uint2(sc_w[i0 + lane], sc_o[i0 + lane]);
+    aut_mark_dead(T, A, [&](uint32_t i) { return sc_w[i]; }, kept, id, lane);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // items before the hash, the hash before the header that makes the state visible
+    if (lane == 0) A.hash[id] = h;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    if (lane == 0) A.hdr[id] = make_uint2(at, kept);
+    return id;
+}
+
+// Compute the transition of state s on class cl (the caller owns it: its entry is AT_BUSY) and publish it.
+template <class BaseT>
+__device__ __forceinline__ void aut_resolve(const TV &T, const BaseT &B, const Aut &A, uint32_t *sc_w, uint32_t *sc_o, uint32_t sc_cap,
+                                            uint32_t s, uint32_t cl, uint32_t lane) {
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");   // the states this step reads were published by other wavefronts
+    const uint32_t r = aut_transition(T, B, A, sc_w, sc_o, sc_cap, s, A.rep[cl], cl, lane);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the new state before the transition that leads to it
+    if (lane == 0) lds_store(&A.trans[s * A.ncls + cl], r);
+}
+
+// A wavefront whose strings miss several transitions at once computes one and leaves the others in
+// the help queue; wavefronts that wait or have run out of strings take them from there.  Serves one
+// request if there is one; returns false when the queue is empty.  Uniform over the wavefront.
+template <class BaseT>
+__device__ __forceinline__ bool aut_help(const TV &T, const BaseT &B, const Aut &A, uint32_t *sc_w, uint32_t *sc_o, uint32_t sc_cap, uint32_t lane, uint32_t &steps) {
+    uint32_t tail = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&A.ctl[4]));
+    tail = tail < (uint32_t)AUT_HELP_QUEUE ? tail : (uint32_t)AUT_HELP_QUEUE;
+    const uint32_t head = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&A.ctl[5]));
+    if (head >= tail) return false;
+    uint32_t got = 0;
+    if (lane == 0) got = atomicCAS(&A.ctl[5], head, head + 1u) == head ? 1u : 0u;
+    if (!__builtin_amdgcn_readfirstlane((int)got)) return true;            // another wavefront took it: look again
+    uint32_t e = 0;
+    for (int tries = 0; tries < AUT_SPIN_LIMIT; tries++) {    // the entry is written right after its place was handed out
+        e = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&A.hq[head]));
+        if (e & HQ_VALID) break;
+        __builtin_amdgcn_s_sleep(1);
+    }
+    if (!(e & HQ_VALID) || (e & 0x7FFFFF00u) == 0x7FFFFF00u) return true;   // a place whose request was settled before it was queued
+    aut_resolve(T, B, A, sc_w, sc_o, sc_cap, (e & ~HQ_VALID) >> 8, e & 0xFFu, lane);
+    steps++;
+    return true;
+}
+
+__host__ __device__ inline uint32_t aut_round16(uint32_t x) { return (x + 15u) & ~15u; }
+
+// Grid (parts, rows).  A block takes slices of AUT_SUB_WORDS words of its row's rank-ordered bitmap in
+// turn: it merges the token-mask cache rows of the row's current set (Section 4.3: strings a terminal
+// swallows whole are valid at once), lists the strings that need the parser, and its wavefronts
+// take the list in batches of 64 strings, one lane per string.  The verdicts of a slice are
+// collected in LDS and stored once: no atomics on global memory and nothing to clear beforehand.
+template <int MODE>
+__global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    const DeviceTables &D = a.tab;
+    const uint32_t tid = threadIdx.x, row = blockIdx.y, wave = tid >> 6, lane = tid & 63;
+    const uint32_t Wr = (uint32_t)D.Wr, n_strings = (uint32_t)D.n_strings;
+    if (blockIdx.x >= (Wr + AUT_GROUP_WORDS - 1) / AUT_GROUP_WORDS) return;
+    // Everything a block needs from global memory before it can start is requested at once (tables,
+    // the row's chart, its token-mask-cache rows) and written to LDS afterwards: one memory latency.
+    TV T;
+    uint32_t off = table_view<MODE>(D, smem, T);
+    const uint32_t n16 = off / 16;
+    static_assert(AUT_TABLE_LOADS <= 7, "the staging below holds at most seven 16-byte pieces per thread");
+    const uint4 *blob = reinterpret_cast<const uint4 *>(D.table_blob);
+    uint4 tb0 = make_uint4(0, 0, 0, 0), tb1 = tb0, tb2 = tb0, tb3 = tb0, tb4 = tb0, tb5 = tb0, tb6 = tb0;   // named registers: an indexed array ends up in scratch memory
+#define ZF_STAGE_LOAD(u) if (tid + (u) * AUT_BLOCK < n16) tb##u = blob[tid + (u) * AUT_BLOCK];
+    ZF_STAGE_LOAD(0) ZF_STAGE_LOAD(1) ZF_STAGE_LOAD(2) ZF_STAGE_LOAD(3) ZF_STAGE_LOAD(4) ZF_STAGE_LOAD(5) ZF_STAGE_LOAD(6)
+#undef ZF_STAGE_LOAD
+    Aut A;
+    A.ncls = (uint32_t)D.n_cls; A.states_cap = (uint32_t)a.aut_states; A.arena_cap = (uint32_t)a.aut_arena;
+    const uint32_t sc_cap = (uint32_t)a.aut_scratch;
+    A.trans = reinterpret_cast<uint32_t *>(smem + off); off += aut_round16(A.states_cap * A.ncls * 4);
+    A.hdr = reinterpret_cast<uint2 *>(smem + off); off += aut_round16(A.states_cap * 8);
+    A.hash = reinterpret_cast<uint32_t *>(smem + off); off += aut_round16(A.states_cap * 4);
+    A.ctl = reinterpret_cast<uint32_t *>(smem + off); off += 32;
+    A.hq = reinterpret_cast<uint32_t *>(smem + off); off += AUT_HELP_QUEUE * 4;
+    uint32_t *l_so = reinterpret_cast<uint32_t *>(smem + off); off += aut_round16((BASE_SETS_LDS + 1) * 4);
+    uint2 *l_it = reinterpret_cast<uint2 *>(smem + off); off += BASE_ITEMS_LDS * 8;
+    uint32_t *l_ent = reinterpret_cast<uint32_t *>(smem + off); off += AUT_ENT_LDS * 4;
+    uint8_t *l_rep = smem + off; off += 256;
+    A.rep = l_rep;
+    uint32_t *vslice = reinterpret_cast<uint32_t *>(smem + off); off += AUT_SUB_WORDS * 4;
+    uint32_t *cslice = reinterpret_cast<uint32_t *>(smem + off); off += AUT_SUB_WORDS * 4;
+    uint8_t *pairs = smem + off; off += AUT_SUB_WORDS / 2;   // slots of the word pairs that hold undecided strings
+    A.arena = reinterpret_cast<uint2 *>(smem + off); off += aut_round16(A.arena_cap * 8);
+    uint32_t *sc_w = reinterpret_cast<uint32_t *>(smem + off) + (size_t)wave * 2 * sc_cap;
+    uint32_t *sc_o = sc_w + sc_cap;
+    // the row's chart: its LDS copy when it is small, else global memory (generic pointers either way)
+    const RowChart rc = a.rows[row];
+    const uint32_t *g_so = a.set_off + rc.set_base;
+    const uint2 *g_it = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
+    const uint32_t *g_ent = a.entries + rc.ent_base;
+    const bool base_fits = rc.n_sets <= BASE_SETS_LDS && rc.n_items <= BASE_ITEMS_LDS;   // both limits are below the block size
+    const bool ent_fits = rc.n_ent <= AUT_ENT_LDS;
+    uint32_t so_v = 0, ent_v = 0;
+    uint2 it_v = make_uint2(0, 0);
+    if (base_fits && tid <= rc.n_sets) so_v = g_so[tid];
+    if (base_fits && tid < rc.n_items) it_v = g_it[tid];
+    if (ent_fits && tid < rc.n_ent) ent_v = g_ent[tid];
+    const uint8_t rep_v = tid < A.ncls ? D.cls_rep[tid] : (uint8_t)0;
+#define ZF_STAGE_STORE(u) if (tid + (u) * AUT_BLOCK < n16) reinterpret_cast<uint4 *>(smem)[tid + (u) * AUT_BLOCK] = tb##u;
+    ZF_STAGE_STORE(0) ZF_STAGE_STORE(1) ZF_STAGE_STORE(2) ZF_STAGE_STORE(3) ZF_STAGE_STORE(4) ZF_STAGE_STORE(5) ZF_STAGE_STORE(6)
+#undef ZF_STAGE_STORE
+    if (base_fits && tid <= rc.n_sets) l_so[tid] = so_v;
+    if (base_fits && tid < rc.n_items) l_it[tid] = it_v;
+    if (ent_fits && tid < rc.n_ent) l_ent[tid] = ent_v;
+    if (tid < 256) l_rep[tid] = rep_v;
+    for (uint32_t k = tid; k < A.states_cap * A.ncls; k += AUT_BLOCK) A.trans[k] = AT_NONE;
+    for (uint32_t k = tid; k < A.states_cap; k += AUT_BLOCK) A.hdr[k] = make_uint2(0, 0xFFFFFFFFu);
+    for (uint32_t k = tid; k < (uint32_t)AUT_HELP_QUEUE; k += AUT_BLOCK) A.hq[k] = 0;
+    if (tid == 0) { A.ctl[0] = 1; A.ctl[1] = 0; A.ctl[4] = 0; A.ctl[5] = 0; }
+    const uint32_t *b_ent = ent_fits ? l_ent : g_ent;
+    const uint32_t *b_so = base_fits ? l_so : g_so;
+    const uint2 *b_it = base_fits ? l_it : g_it;
+    uint32_t steps = 0;
+    const uint32_t cr = (uint32_t)D.chunk_ranks;
+    // The words of the row's bitmap are dealt to the blocks in groups of AUT_GROUP_WORDS, round robin:
+    // undecided strings come in runs of thousands of neighbouring ranks (everything that begins
+    // with a quote, say), and every block should get its share of each run.
+    const uint32_t n_groups = (Wr + AUT_GROUP_WORDS - 1) / AUT_GROUP_WORDS, groups_per_pass = AUT_SUB_WORDS / AUT_GROUP_WORDS;
+    for (uint32_t j0 = 0; blockIdx.x + j0 * gridDim.x < n_groups; j0 += groups_per_pass) {
+        auto word_of = [&](uint32_t t) -> uint32_t {         // the bitmap word slot t of this pass stands for, or Wr and more if none
+            const uint32_t grp = blockIdx.x + (j0 + t / AUT_GROUP_WORDS) * gridDim.x;
+            return grp < n_groups ? grp * AUT_GROUP_WORDS + t % AUT_GROUP_WORDS : 0xFFFFFF00u;
+        };
+        if (tid == 0) { A.ctl[2] = 0; A.ctl[3] = 0; A.ctl[6] = 0; }
+        if (tid < AUT_SUB_WORDS) { vslice[tid] = 0; cslice[tid] = rc.n_ent == 0 ? 0xFFFFFFFFu : 0u; }
+        __syncthreads();                                     // also: tables, chart and automaton set-up are in place
+        // ---- merge the token-mask cache rows (all threads: word slot tid % SUB, cache rows tid / SUB, + 4, ...) ----
+        {
+            const uint32_t t = tid % AUT_SUB_WORDS, w = word_of(t);
+            uint32_t v = 0, c = 0;
+            if (w < Wr)
+                for (uint32_t k = tid / AUT_SUB_WORDS; k < rc.n_ent; k += AUT_BLOCK / AUT_SUB_WORDS) {
+                    const size_t r = (size_t)b_ent[k] * Wr + w;
+                    v |= D.ci_valid[r]; c |= D.ci_cd[r];
+                }
+            if (v) atomicOr(&vslice[t], v);
+            if (c) atomicOr(&cslice[t], c);
+        }
+        __syncthreads();
+        // ---- the undecided strings, and the word pairs (64 ranks) that hold any: one wavefront, one ballot ----
+        if (tid < AUT_SUB_WORDS / 2) {                       // the first wavefront
+            uint32_t want[2];
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const uint32_t w = word_of(2 * tid + h), r0 = w * 32u;
+                want[h] = cslice[2 * tid + h] & ~vslice[2 * tid + h];
+                if (w >= Wr || r0 >= n_strings) want[h] = 0;                 // strings beyond the last one do not exist
+                else if (n_strings - r0 < 32u) want[h] &= (1u << (n_strings - r0)) - 1u;
+                cslice[2 * tid + h] = want[h];
+            }
+            const unsigned long long nz = __ballot((want[0] | want[1]) != 0);
+            if (want[0] | want[1]) pairs[__popcll(nz & ((1ull << lane) - 1ull))] = (uint8_t)tid;
+            uint32_t cnt = (uint32_t)(__popc(want[0]) + __popc(want[1]));
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d);
+            if (lane == 0) { A.ctl[3] = (uint32_t)__popcll(nz); if (cnt) atomicAdd(&a.counters[1], cnt); }
+        }
+        const BaseG B{b_so, b_it, rc.n_sets, b_so[rc.n_sets - 1], rc.n_items};
+        if (j0 == 0 && wave == AUT_WAVES - 1)                // meanwhile the last wavefront settles the dead transitions of the row's current set
+            aut_mark_dead(T, A, [&](uint32_t i) { return B.it[B.last_lo + i].x; }, B.last_hi - B.last_lo, 0u, lane);
+        __syncthreads();
+        const uint32_t n_pairs = A.ctl[3];
+        // ---- one lane per string through the automaton, 64 neighbouring ranks at a time ----
+        for (;;) {
+            uint32_t b = 0;
+            if (lane == 0) b = atomicAdd(&A.ctl[2], 1u);
+            b = (uint32_t)__builtin_amdgcn_readfirstlane((int)b);
+            if (b >= n_pairs) break;
+            const uint32_t pair = pairs[b];
+            const uint32_t rank = word_of(2 * pair) * 32u + lane;            // a pair lies inside one group: consecutive ranks
+            bool live = (cslice[2 * pair + (lane >> 5)] >> (lane & 31u)) & 1u;
+            uint32_t soff = 0, len = 0;
+            Str16 c16{{0, 0, 0, 0}};
+            if (live) { soff = D.str_off[rank]; len = D.str_off[rank + 1] - soff; c16 = D.str16[rank]; }
+            live = live && len > 0;
+            uint32_t s = 0, pos = 0, c = 0, spins = 0;
+            bool ok = false, fail = false;
+            for (;;) {
+                while (live) {                               // every lane follows its own string as far as the table goes
+                    if (pos < 16u) {
+                        const uint32_t q = pos >> 2;
+                        const uint32_t word = q == 0 ? c16.w[0] : (q == 1 ? c16.w[1] : (q == 2 ? c16.w[2] : c16.w[3]));
+                        c = (word >> ((pos & 3u) * 8u)) & 0xFFu;
+                    } else c = D.str_cls[soff + pos];
+                    const uint32_t t = lds_load(&A.trans[s * A.ncls + c]);
+                    if (t < AT_FAIL) { s = t; pos++; if (pos == len) { ok = true; live = false; } }
+                    else if (t == AT_DEAD) live = false;
+                    else if (t == AT_SINK) { ok = pos + 1 == len; live = false; }
+                    else if (t == AT_FAIL) { fail = true; live = false; }
+                    else break;                              // not there yet
+                }
+                const unsigned long long pend = __ballot(live);
+                if (!pend) break;
+                // Claim the missing transitions that nobody is computing yet: the first one is computed here,
+                // the others are left in the help queue for wavefronts that have nothing to do.
+                unsigned long long m = pend;
+                bool progress = false, mine = false;
+                uint32_t ms = 0, mc = 0;
+                while (m) {
+                    const int l = __ffsll((long long)m) - 1;
+                    const uint32_t ls = __builtin_amdgcn_readlane(s, l), lc = __builtin_amdgcn_readlane(c, l);
+                    m &= ~__ballot(live && s == ls && c == lc);
+                    uint32_t *slot = &A.trans[ls * A.ncls + lc];
+                    uint32_t old = 0;
+                    if (lane == 0) {
+                        bool room = true;
+                        uint32_t at = 0;
+                        if (mine) { at = atomicAdd(&A.ctl[4], 1u); room = at < (uint32_t)AUT_HELP_QUEUE; }   // a place in the queue first ...
+                        old = room ? atomicCAS(slot, (uint32_t)AT_NONE, (uint32_t)AT_BUSY) : (uint32_t)AT_BUSY;
+                        // ... which is filled in any case: with the request, or with one that is already settled (takers find it done)
+                        if (mine && room) lds_store(&A.hq[at], HQ_VALID | (old == AT_NONE ? (ls << 8) | lc : 0x7FFFFF00u));
+                    }
+                    old = (uint32_t)__builtin_amdgcn_readfirstlane((int)old);
+                    if (old == AT_NONE) {
+                        if (!mine) { mine = true; ms = ls; mc = lc; }
+                        progress = true;
+                    } else if (old != AT_BUSY) progress = true;      // it has just been published
+                }
+                if (mine) { aut_resolve(T, B, A, sc_w, sc_o, sc_cap, ms, mc, lane); steps++; }
+                if (!progress && !aut_help(T, B, A, sc_w, sc_o, sc_cap, lane, steps)) {   // everything this wavefront waits for is being computed by others
+                    __builtin_amdgcn_s_sleep(4);
+                    if (++spins > (uint32_t)AUT_SPIN_LIMIT) { fail = fail || live; live = false; }   // bounded wait: hand the strings to the fallback
+                }
+            }
+            if (lane == 0) atomicAdd(&A.ctl[6], 1u);
+            const unsigned long long okb = __ballot(ok);     // this wavefront is the only one that touches the pair's two words
+            if (lane == 0 && okb) { vslice[2 * pair] |= (uint32_t)okb; vslice[2 * pair + 1] |= (uint32_t)(okb >> 32); }
+            // strings this block could not decide: one fallback entry per trie chunk
+            unsigned long long fm = __ballot(fail);
+            const uint32_t my_chunk = rank / cr;
+            while (fm) {
+                const int l = __ffsll((long long)fm) - 1;
+                const uint32_t ch = __builtin_amdgcn_readlane(my_chunk, l);
+                const bool same = fail && my_chunk == ch;
+                fm &= ~__ballot(same);
+                uint32_t bits = same ? 1u << (rank % cr) : 0u;
+#pragma unroll
+                for (int d = 32; d >= 1; d >>= 1) bits |= __shfl_xor(bits, d);
+                if (lane == 0) {
+                    const uint32_t slot = atomicAdd(&a.counters[0], 1u);
+                    if (slot < a.overflow_cap) a.overflow_list[slot] = make_uint4(row, ch, bits, 0);
+                }
+            }
+        }
+        // out of strings: serve the help queue until every batch of the block is finished
+        for (uint32_t idle = 0; (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&A.ctl[6])) < n_pairs && idle < (uint32_t)AUT_SPIN_LIMIT;) {
+            if (aut_help(T, B, A, sc_w, sc_o, sc_cap, lane, steps)) idle = 0;
+            else { __builtin_amdgcn_s_sleep(4); idle++; }
+        }
+        while (aut_help(T, B, A, sc_w, sc_o, sc_cap, lane, steps)) {}       // nothing may stay marked as being computed
+        __syncthreads();
+        if (tid < AUT_SUB_WORDS) { const uint32_t w = word_of(tid); if (w < Wr) a.rank_mask[(size_t)row * Wr + w] = vslice[tid]; }
+    }
+    if (lane == 0 && steps) atomicAdd(&a.counters[3], steps);
+}
+
+}  // namespace
+
+hipError_t prepare_automaton_kernels() {
+    const int max_lds = 160 * 1024;
+    hipError_t e;
+#define SET_ATTR(k) if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k), hipFuncAttributeMaxDynamicSharedMemorySize, max_lds)) != hipSuccess) return e
+    SET_ATTR(mask_automaton_kernel<0>); SET_ATTR(mask_automaton_kernel<1>); SET_ATTR(mask_automaton_kernel<2>);
+#undef SET_ATTR
+    return hipSuccess;
+}
+
+uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int arena, int scratch) {
+    return table_bytes(t, mode) + aut_round16((uint32_t)states * (uint32_t)t.n_cls * 4) + aut_round16((uint32_t)states * 8) + aut_round16((uint32_t)states * 4) + 32 + AUT_HELP_QUEUE * 4 +
+           aut_round16((BASE_SETS_LDS + 1) * 4) + BASE_ITEMS_LDS * 8 + AUT_ENT_LDS * 4 + 256 + 2 * AUT_SUB_WORDS * 4 + AUT_SUB_WORDS / 2 + aut_round16((uint32_t)arena * 8) +
+           AUT_WAVES * (uint32_t)scratch * 8;
+}
+hipError_t launch_mask_automaton(const MaskArgs &a, hipStream_t s) {
+    const uint32_t lds = automaton_lds_bytes(a.tab, a.mode, a.aut_states, a.aut_arena, a.aut_scratch);
+    dim3 grid(a.aut_parts, a.batch);
+    if (a.mode == 0) hipLaunchKernelGGL(mask_automaton_kernel<0>, grid, dim3(AUT_BLOCK), lds, s, a);
+    else if (a.mode == 1) hipLaunchKernelGGL(mask_automaton_kernel<1>, grid, dim3(AUT_BLOCK), lds, s, a);
+    else hipLaunchKernelGGL(mask_automaton_kernel<2>, grid, dim3(AUT_BLOCK), lds, s, a);
+    return hipGetLastError();
+}
+}  // namespace zf
