@@ -363,6 +363,36 @@ def test_long_tokens_deep_nesting_many_classes(mode, torch_cuda, oracle_lib):
     _run_parity(torch, zf, oracle_lib.Oracle, g2, toks2, 3, 12, 4242, walk_mode=MODES[mode])
 
 
+@pytest.mark.parametrize("mode", list(MODES))
+def test_many_rows_and_longest_token(mode, torch_cuda, oracle_lib):
+    """A batch larger than the number of compute units (one block per row and less) and tokens of the
+    maximum length the library takes (255 bytes), valid and invalid ones."""
+    import paper_2506_01151_amd as zf
+    torch = torch_cuda
+    cfg = configs.CONFIGS[1]
+    g = cfg.grammar()
+    toks = cfg.vocab(600) + [b'"' + b"x" * 253 + b'"', b"[" * 255, b"1" * 255, b'"' + b"y" * 254, b" " * 254 + b"}", b"a" * 255]
+    off, data = wvocab.vocab_csr(toks)
+    orc = oracle_lib.Oracle(g)
+    eng = zf.Engine(g, toks, device=0, state_cache_entries=-1, walk_mode=MODES[mode])
+    rows = 300
+    rs = stream(cfg.seed, "many-rows")
+    pieces = [b"", b"[", b'{"a":', b'{"a": "', b"[1, 2", b'[{"k": [', b"tr", b'"abc', b"[[[", b'{"k":"v"', b"-1.5e", b'["\\u00']
+    so, ss = [], []
+    for r in range(rows):
+        p = pieces[rs.below(len(pieces))]
+        a, b = orc.new_state(), eng.new_state()
+        assert a.feed_bytes(p)
+        b.advance_bytes(p)
+        so.append(a)
+        ss.append(b)
+    d_mask = torch.full((rows, eng.W), -1, dtype=torch.int32, device="cuda")
+    zf.compute_mask(eng, ss, d_mask)
+    got = d_mask.cpu().numpy().view(np.uint32)
+    for r in range(rows):
+        assert (got[r] == so[r].mask(off, data, 4)).all(), r
+
+
 def test_apply_mask_full_size_bf16(torch_cuda, oracle_lib):
     """Configuration 3's logits shape [16, 128256] bf16, mask from a real state."""
     import paper_2506_01151_amd as zf
