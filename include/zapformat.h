@@ -95,6 +95,8 @@ typedef struct {
     int32_t n_dfa_states, n_byte_classes;
     int32_t n_trie_nodes, n_strings; /* distinct non-empty token strings */
     int32_t lane_item_cap, device;
+    int32_t table_lds_mode;       /* grammar tables the mask kernels keep in LDS: 0 = all, 1 = the small ones, 2 = none;
+                                     -1 when the engine has no device */
 } zf_engine_info;
 
 typedef struct {               /* facts about the last zf_compute_mask, for reporting only */

@@ -39,7 +39,7 @@ class Stats(ctypes.Structure):
 
 class EngineInfo(ctypes.Structure):
     _fields_ = [(n, c_i32) for n in ("V", "W", "n_nonterminals", "n_rules", "n_positions", "n_dfa_states",
-                                     "n_byte_classes", "n_trie_nodes", "n_strings", "lane_item_cap", "device")]
+                                     "n_byte_classes", "n_trie_nodes", "n_strings", "lane_item_cap", "device", "table_lds_mode")]
 
 
 class MaskReport(ctypes.Structure):

@@ -267,6 +267,7 @@ int zf_engine_get_info(const zf_engine *e, zf_engine_info *o) {
     o->V = e->V; o->W = e->W; o->n_nonterminals = e->tab.N; o->n_rules = e->tab.n_rules_kept; o->n_positions = e->tab.P;
     o->n_dfa_states = e->tab.Q; o->n_byte_classes = e->tab.n_cls; o->n_trie_nodes = (int)e->trie.nodes.size();
     o->n_strings = e->trie.n_strings; o->lane_item_cap = e->opt.lane_item_cap; o->device = e->opt.device;
+    o->table_lds_mode = e->dev ? e->dev->mode : -1;
     return ZF_OK;
 }
 

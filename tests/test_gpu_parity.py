@@ -393,6 +393,26 @@ def test_many_rows_and_longest_token(mode, torch_cuda, oracle_lib):
         assert (got[r] == so[r].mask(off, data, 4)).all(), r
 
 
+@pytest.mark.parametrize("mode", list(MODES))
+@pytest.mark.parametrize("n_words,word_len,lds_mode", [(1500, 5, 1), (1500, 8, 2)])
+def test_grammar_tables_beyond_the_lds_budget(n_words, word_len, lds_mode, mode, torch_cuda, oracle_lib):
+    """Grammars whose tables do not fit the kernels' LDS budget: only the small tables staged (mode 1) or
+    none (mode 2); the kernels then read the rest from global memory."""
+    import paper_2506_01151_amd as zf
+    g = grammars.big_tables_grammar(n_words, word_len)
+    words = [bytes(t.data) for t in g.terminals if len(t.data) == word_len]
+    rs = stream(77, "big-tables-vocab")
+    toks = [bytes([c]) for c in range(256)]
+    for _ in range(400):
+        w = words[rs.below(len(words))]
+        k = rs.below(4)
+        toks.append(w if k == 0 else (w[:1 + rs.below(word_len - 1)] if k == 1 else (w + b" " if k == 2 else w[2:] + b" " + words[rs.below(len(words))][:3])))
+    eng = zf.Engine(g, toks, device=0, state_cache_entries=-1, walk_mode=MODES[mode])
+    assert eng.info.table_lds_mode == lds_mode
+    del eng
+    _run_parity(torch_cuda, zf, oracle_lib.Oracle, g, toks, 3, 6, 31337, walk_mode=MODES[mode])
+
+
 def test_apply_mask_full_size_bf16(torch_cuda, oracle_lib):
     """Configuration 3's logits shape [16, 128256] bf16, mask from a real state."""
     import paper_2506_01151_amd as zf

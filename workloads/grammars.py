@@ -236,3 +236,19 @@ def many_classes_grammar(n: int = 100) -> Grammar:
     for c in range(n):
         g.rule("T", [bytes([32 + c, 32 + (c * 7 + 3) % n])])
     return g
+
+
+def big_tables_grammar(n_words: int, word_len: int, seed: int = 11) -> Grammar:
+    """S -> W | W ' ' S ; W -> one of n_words seeded lowercase literals of word_len letters: as many DFA
+    states and tabulated scan entries as a test needs to outgrow the kernels' LDS budget for grammar tables."""
+    rs = stream(seed, f"big-tables[{n_words},{word_len}]")
+    words = set()
+    while len(words) < n_words:
+        words.add(bytes(97 + rs.below(26) for _ in range(word_len)))
+    g = Grammar(name=f"big_tables_{n_words}x{word_len}")
+    g.set_start("S")
+    g.rule("S", ["W"])
+    g.rule("S", ["W", b" ", "S"])
+    for w in sorted(words):
+        g.rule("W", [w])
+    return g
