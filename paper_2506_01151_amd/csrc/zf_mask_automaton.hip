@@ -402,7 +402,7 @@ __device__ __forceinline__ bool aut_help(const TV &T, const BaseT &B, const Aut 
         if (e & HQ_VALID) break;
         __builtin_amdgcn_s_sleep(1);
     }
-    if (!(e & HQ_VALID) || (e & 0x7FFFFF00u) == 0x7FFFFF00u) return true;   // a place whose request was settled before it was queued
+    if (!(e & HQ_VALID)) return true;                        // cannot happen: places below the end of the queue are always filled
     aut_resolve(T, B, A, sc_w, sc_o, sc_cap, (e & ~HQ_VALID) >> 8, e & 0xFFu, lane);
     steps++;
     return true;
@@ -560,32 +560,29 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
                 }
                 const unsigned long long pend = __ballot(live);
                 if (!pend) break;
-                // Claim the missing transitions that nobody is computing yet: the first one is computed here,
-                // the others are left in the help queue for wavefronts that have nothing to do.
-                unsigned long long m = pend;
-                bool progress = false, mine = false;
-                uint32_t ms = 0, mc = 0;
-                while (m) {
-                    const int l = __ffsll((long long)m) - 1;
-                    const uint32_t ls = __builtin_amdgcn_readlane(s, l), lc = __builtin_amdgcn_readlane(c, l);
-                    m &= ~__ballot(live && s == ls && c == lc);
-                    uint32_t *slot = &A.trans[ls * A.ncls + lc];
-                    uint32_t old = 0;
-                    if (lane == 0) {
-                        bool room = true;
+                // Every waiting lane tries to claim the transition it misses, all at once (among lanes that miss
+                // the same one, one wins).  The first claim is computed here, the others are left in the
+                // help queue for wavefronts that have nothing to do.
+                uint32_t old = AT_BUSY;
+                if (live) old = atomicCAS(&A.trans[s * A.ncls + c], (uint32_t)AT_NONE, (uint32_t)AT_BUSY);
+                const unsigned long long won = __ballot(live && old == AT_NONE);
+                const bool progress = won != 0 || __ballot(live && old != AT_NONE && old != AT_BUSY) != 0;   // claimed, or published meanwhile
+                if (won) {
+                    const int first = __ffsll((long long)won) - 1;
+                    const unsigned long long rest = won & ~(1ull << first);
+                    if (rest) {
                         uint32_t at = 0;
-                        if (mine) { at = atomicAdd(&A.ctl[4], 1u); room = at < (uint32_t)AUT_HELP_QUEUE; }   // a place in the queue first ...
-                        old = room ? atomicCAS(slot, (uint32_t)AT_NONE, (uint32_t)AT_BUSY) : (uint32_t)AT_BUSY;
-                        // ... which is filled in any case: with the request, or with one that is already settled (takers find it done)
-                        if (mine && room) lds_store(&A.hq[at], HQ_VALID | (old == AT_NONE ? (ls << 8) | lc : 0x7FFFFF00u));
+                        if (lane == 0) at = atomicAdd(&A.ctl[4], (uint32_t)__popcll(rest));
+                        at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+                        if ((rest >> lane) & 1ull) {
+                            const uint32_t k = at + (uint32_t)__popcll(rest & ((1ull << lane) - 1ull));
+                            if (k < (uint32_t)AUT_HELP_QUEUE) lds_store(&A.hq[k], HQ_VALID | (s << 8) | c);
+                            else lds_store(&A.trans[s * A.ncls + c], (uint32_t)AT_NONE);   // no room in the queue: the claim is given back
+                        }
                     }
-                    old = (uint32_t)__builtin_amdgcn_readfirstlane((int)old);
-                    if (old == AT_NONE) {
-                        if (!mine) { mine = true; ms = ls; mc = lc; }
-                        progress = true;
-                    } else if (old != AT_BUSY) progress = true;      // it has just been published
+                    aut_resolve(T, B, A, sc_w, sc_o, sc_cap, (uint32_t)__builtin_amdgcn_readlane((int)s, first), (uint32_t)__builtin_amdgcn_readlane((int)c, first), lane);
+                    steps++;
                 }
-                if (mine) { aut_resolve(T, B, A, sc_w, sc_o, sc_cap, ms, mc, lane); steps++; }
                 if (!progress && !aut_help(T, B, A, sc_w, sc_o, sc_cap, lane, steps)) {   // everything this wavefront waits for is being computed by others
                     __builtin_amdgcn_s_sleep(4);
                     if (++spins > (uint32_t)AUT_SPIN_LIMIT) { fail = fail || live; live = false; }   // bounded wait: hand the strings to the fallback
