@@ -26,10 +26,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic of one mask_automaton_kernel launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # scaled by a plain copy of known size (profiles/mask_automaton_kernel_cfg3_hbm_traffic.txt).  It describes the kernel
 # sources with the digest below; once they change the figure is reported as null until it is measured again.
-# (Digest renewed after the kernel file was split in three and the permutation kernel changed: the code of the two
-# kernels the figures belong to is the same as when the counters were read.)
-MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 3538500, "apply_bytes_per_launch": 8508700,
-                    "kernel_sources_sha256": "9e4f2c990ed5eb3b950f8732712a0b00e6fb2574b8cb6130903ef6155f4e14c3"}
+MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 3535600, "apply_bytes_per_launch": 8508700,
+                    "kernel_sources_sha256": "18a4f132b4c0fd7c3c0fcccf4b9e16db3226c1c394c6ca312cf52b787797509a"}
 
 
 def kernel_sources_digest():

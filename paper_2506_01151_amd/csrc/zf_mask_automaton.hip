@@ -542,7 +542,7 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
             Str16 c16{{0, 0, 0, 0}};
             if (live) { soff = D.str_off[rank]; len = D.str_off[rank + 1] - soff; c16 = D.str16[rank]; }
             live = live && len > 0;
-            uint32_t s = 0, pos = 0, c = 0, spins = 0;
+            uint32_t s = 0, pos = 0, c = 0, spins = 0, t = AT_BUSY;
             bool ok = false, fail = false;
             for (;;) {
                 while (live) {                               // every lane follows its own string as far as the table goes
@@ -551,7 +551,7 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
                         const uint32_t word = q == 0 ? c16.w[0] : (q == 1 ? c16.w[1] : (q == 2 ? c16.w[2] : c16.w[3]));
                         c = (word >> ((pos & 3u) * 8u)) & 0xFFu;
                     } else c = D.str_cls[soff + pos];
-                    const uint32_t t = lds_load(&A.trans[s * A.ncls + c]);
+                    t = lds_load(&A.trans[s * A.ncls + c]);
                     if (t < AT_FAIL) { s = t; pos++; if (pos == len) { ok = true; live = false; } }
                     else if (t == AT_DEAD) live = false;
                     else if (t == AT_SINK) { ok = pos + 1 == len; live = false; }
@@ -563,8 +563,8 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
                 // Every waiting lane tries to claim the transition it misses, all at once (among lanes that miss
                 // the same one, one wins).  The first claim is computed here, the others are left in the
                 // help queue for wavefronts that have nothing to do.
-                uint32_t old = AT_BUSY;
-                if (live) old = atomicCAS(&A.trans[s * A.ncls + c], (uint32_t)AT_NONE, (uint32_t)AT_BUSY);
+                uint32_t old = AT_BUSY;                      // lanes that found the transition being computed need not ask again
+                if (live && t == AT_NONE) old = atomicCAS(&A.trans[s * A.ncls + c], (uint32_t)AT_NONE, (uint32_t)AT_BUSY);
                 const unsigned long long won = __ballot(live && old == AT_NONE);
                 const bool progress = won != 0 || __ballot(live && old != AT_NONE && old != AT_BUSY) != 0;   // claimed, or published meanwhile
                 if (won) {
