@@ -537,6 +537,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
         HIP_TRY(hipMalloc(&d->d_chart, cap));
         d->chart_cap = cap;
     }
+    uint32_t n_cache_rows = 0;                            // distinct rows of the token-mask cache, summed over the rows of the call
     {
         uint8_t *h = (uint8_t *)d->h_stage[slot];
         RowChart *rows = (RowChart *)(h + off_rows);
@@ -557,6 +558,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
             so_at += (uint32_t)c.set_off.size(); it_at += (uint32_t)c.items.size();
             dst[r] = sc ? row_slot[miss_rows[r]] : miss_rows[r];
         }
+        n_cache_rows = en_at;
     }
     // ---- per-call device buffers ----
     const size_t need_rank = (size_t)std::max(nb, 1) * d->tab.Wr, need_ovf = 2 * (size_t)std::max(nb, 1) * d->tab.n_chunks;   // the automaton kernel may name a chunk in two entries
@@ -625,26 +627,40 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
         // LDS budgets of one block's automaton.  The set under construction gets the configured item
         // budget (tests set it tiny to force the fallback pass), else room for sets a few times as wide
         // as the widest current set; states and the item arena share what the tables leave of 160 KB.
-        size_t widest = 0;
+        size_t widest = 0, most_sets = 0, most_items = 0;
         for (int r = 0; r < nb; r++) {
             const Chart &c = states[miss_rows[r]]->chart;
             widest = std::max<size_t>(widest, c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1]);
+            most_sets = std::max<size_t>(most_sets, c.n_sets());
+            most_items = std::max<size_t>(most_items, c.set_off[c.n_sets()]);
         }
         int scratch = e->lane_cap_auto ? (int)std::min<size_t>(LANE_CAP_MAX, (4 * widest + 128 + 31) / 32 * 32) : e->opt.lane_item_cap;
         int n_states = AUT_STATES_DEFAULT, arena = std::max(1024, 8 * scratch);
+        int base_sets = BASE_SETS_LDS, base_items = BASE_ITEMS_LDS;
         const uint32_t lds_max = 160u * 1024u;
-        while (automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch) > lds_max && arena > 2 * scratch) arena /= 2;
-        while (automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch) > lds_max && n_states > 8) n_states /= 2;
-        while (automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch) > lds_max && scratch > 32) { scratch /= 2; arena = std::max(arena / 2, 2 * scratch); }
-        if (automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch) > lds_max) return fail(ZF_ERR_INVALID_ARG, "the grammar tables leave no LDS for the mask automaton");
+        auto lds_now = [&]() { return automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch, base_sets, base_items); };
+        while (lds_now() > lds_max && arena > 2 * scratch) arena /= 2;
+        while (lds_now() > lds_max && n_states > 8) n_states /= 2;
+        while (lds_now() > lds_max && scratch > 32) { scratch /= 2; arena = std::max(arena / 2, 2 * scratch); }
+        if (lds_now() > lds_max) return fail(ZF_ERR_INVALID_ARG, "the grammar tables leave no LDS for the mask automaton");
+        // the rows' charts are read over and over by Complete: keep them in LDS too when the longest one fits in what is left
+        if (most_sets > (size_t)BASE_SETS_LDS || most_items > (size_t)BASE_ITEMS_LDS) {
+            const int want_sets = (int)std::max<size_t>(BASE_SETS_LDS, (most_sets + 32) / 32 * 32 - 1);
+            const int want_items = (int)std::max<size_t>(BASE_ITEMS_LDS, (most_items + 63) / 64 * 64);
+            if (want_sets <= AUT_BASE_SETS_MAX && want_items <= AUT_BASE_ITEMS_MAX &&
+                automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch, want_sets, want_items) <= lds_max) {
+                base_sets = want_sets; base_items = want_items;
+            }
+        }
         a.aut_states = n_states; a.aut_arena = arena; a.aut_scratch = scratch;
+        a.aut_base_sets = base_sets; a.aut_base_items = base_items;
         // blocks per row: enough to fill the chip about once, at most one block per pass of AUT_SUB_WORDS words
         const int n_sub = (d->tab.Wr + AUT_SUB_WORDS - 1) / AUT_SUB_WORDS;
         a.aut_parts = std::max(1, std::min(n_sub, (2 * std::max(1, d->cus) + std::max(nb, 1) - 1) / std::max(nb, 1)));
     }
     const bool prof = d->profiling;
     d->report.chart_bytes = (int64_t)total;
-    d->report.cache_rows = (int32_t)n_ent;
+    d->report.cache_rows = (int32_t)n_cache_rows;
     d->report.main_ms = d->report.fallback_ms = d->report.permute_ms = 0.f;
     d->report.overflow_chunks = d->report.walk_chunks = d->report.parser_steps = 0;
     // everything the host has to work out is done: enqueue the upload and the kernels back to back

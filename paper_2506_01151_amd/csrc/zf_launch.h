@@ -13,7 +13,9 @@ static const int WALK_RUN_MAX = 2;         // consecutive queue items a wavefron
 static const int WALK_NODES_LDS = 80;      // trie nodes of a chunk the walk kernel stages in LDS (bigger chunks go to the fallback)
 static const int WALK_DEPTH_MAX = 32;      // trie depth the walk kernel follows (deeper paths go to the fallback)
 static const int BASE_SETS_LDS = 31;       // a row's chart is staged into LDS when it has at most this many sets ...
-static const int BASE_ITEMS_LDS = 64;      // ... and items
+static const int BASE_ITEMS_LDS = 64;      // ... and items (the mask-automaton kernel takes larger limits from the host when LDS allows)
+static const int AUT_BASE_SETS_MAX = 1023; // the largest limits the host asks for
+static const int AUT_BASE_ITEMS_MAX = 4096;
 static const int TABLE_LDS_BUDGET = 56 * 1024;
 static const int AUT_WAVES = 8;            // wavefronts per block of the mask-automaton kernel
 static const int AUT_BLOCK = AUT_WAVES * 64;
@@ -59,6 +61,8 @@ struct MaskArgs {
     int32_t aut_arena;         // items of all states together
     int32_t aut_scratch;       // items of one set under construction (per wavefront)
     int32_t aut_parts;         // blocks per row (grid.x)
+    int32_t aut_base_sets;     // a row's chart is staged into LDS when it has at most this many sets ...
+    int32_t aut_base_items;    // ... and items (both at least BASE_SETS_LDS / BASE_ITEMS_LDS)
 };
 
 int choose_table_mode(const DeviceTables &t);
@@ -70,7 +74,7 @@ hipError_t prepare_automaton_kernels();
 hipError_t launch_upload(const void *pinned_src, void *dst, size_t bytes, hipStream_t s);   // bytes rounded up to 16: both buffers must hold that much
 hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s);
-uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int arena, int scratch);
+uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int arena, int scratch, int base_sets, int base_items);
 hipError_t launch_mask_automaton(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_fallback(const MaskArgs &a, hipStream_t s);
 hipError_t launch_permute(const MaskArgs &a, hipStream_t s);

@@ -42,7 +42,7 @@ struct Aut {               // one block's automaton; every pointer leads into LD
 // Transitions of state `id` that leave no item at all are settled when the state is made, for all
 // byte classes at once (lane = class): an item before a terminal survives a class iff its DFA has
 // an edge, an item that waits for a nonterminal iff some terminal that can begin it has one.  What
-// remains for the byte step proper are the few classes that lead somewhere.  item(i) is uniform.
+// remains for the byte step proper are the few classes that lead somewhere.
 template <class ItemWord>
 __device__ __forceinline__ void aut_mark_dead(const TV &T, const Aut &A, ItemWord item, uint32_t n, uint32_t id, uint32_t lane) {
     auto survives = [&](uint32_t w, uint32_t byte, uint32_t c) -> bool {   // no branch: both kinds of look-up are made, with safe indices
@@ -55,6 +55,25 @@ __device__ __forceinline__ void aut_mark_dead(const TV &T, const Aut &A, ItemWor
         const bool a_nt = T.scan_off[Y * T.ncls + c + 1] > T.scan_off[Y * T.ncls + c];
         return !end && (term ? a_term : a_nt);
     };
+    if (n > 16u) {                                           // a wide set: one item per lane, the classes in turn
+        for (uint32_t c0 = 0; c0 < A.ncls; c0 += 64) {
+            const uint32_t nc = A.ncls - c0 < 64u ? A.ncls - c0 : 64u;
+            uint32_t lo = 0, hi = 0;                         // bit k: some item of this lane survives class c0 + k
+            for (uint32_t i0 = 0; i0 < n; i0 += 64) {
+                const uint32_t w = i0 + lane < n ? item(i0 + lane) : (uint32_t)IW_END;
+                for (uint32_t k = 0; k < nc; k++) {
+                    const bool al = survives(w, A.rep[c0 + k], c0 + k);
+                    lo |= (al && k < 32u) ? 1u << (k & 31u) : 0u;
+                    hi |= (al && k >= 32u) ? 1u << (k & 31u) : 0u;
+                }
+            }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) { lo |= __shfl_xor(lo, d); hi |= __shfl_xor(hi, d); }
+            const uint32_t mine = lane < 32u ? lo >> lane : hi >> (lane - 32u);
+            if (lane < nc && !(mine & 1u)) A.trans[id * A.ncls + c0 + lane] = AT_DEAD;
+        }
+        return;
+    }
     for (uint32_t c0 = 0; c0 < A.ncls; c0 += 64) {
         const uint32_t c = c0 + lane < A.ncls ? c0 + lane : A.ncls - 1;   // surplus lanes repeat the last class
         const uint32_t byte = A.rep[c];
@@ -77,8 +96,9 @@ __device__ __forceinline__ void lds_store(uint32_t *p, uint32_t v) { __hip_atomi
 // One Earley byte step from state s on byte class cl is done by a whole wavefront with uniform
 // control flow (all lanes call these functions with identical arguments).  Both variants leave the
 // new set, completed items dropped, in the wavefront's scratch (sc_w, sc_o) and return AUT_OK,
-// AUT_WIDE (narrow variant only: more than 64 new items) or AUT_OVER (no room).
+// AUT_WIDE (narrow variant only: more than 64 new items, or too many candidates) or AUT_OVER (no room).
 enum { AUT_OK = 0, AUT_WIDE = 1, AUT_OVER = 2 };
+static const int AUT_NARROW_TRIES = 96;   // insert attempts after which the narrow variant hands the step to the wide one
 
 template <class BaseT>
 struct AutSets {           // resolves origin references
@@ -98,10 +118,11 @@ __device__ __forceinline__ int aut_step_narrow(const TV &T, const AutSets<BaseT>
     const uint2 *src;
     uint32_t ns;
     S.view(cur, src, ns);
-    uint32_t nw = 0xFFFFFFFFu, no = 0, nnew = 0;             // no item word is all ones
+    uint32_t nw = 0xFFFFFFFFu, no = 0, nnew = 0, tries = 0;  // no item word is all ones
     bool saw_end = false, failed = false;                    // failed is sticky: the step runs on and reports at its end
     const uint32_t room = sc_cap < 64u ? sc_cap : 64u;
     auto insert = [&](uint32_t w, uint32_t o) {              // uniform arguments; no branch
+        tries++;
         const bool fresh = __ballot(nw == w && no == o) == 0;
         const bool add = fresh && nnew < room;
         failed |= fresh && !add;
@@ -170,6 +191,7 @@ __device__ __forceinline__ int aut_step_narrow(const TV &T, const AutSets<BaseT>
         for (;;) {
             const unsigned long long todo = __ballot(lane < nnew && (nw & IW_END)) & ~visited;
             if (!todo) break;
+            if (tries > (uint32_t)AUT_NARROW_TRIES) return AUT_WIDE;   // candidates come one at a time here: an ambiguous grammar makes hundreds, mostly duplicates
             const int i = __ffsll((long long)todo) - 1;
             visited |= 1ull << i;
             const uint32_t w = __builtin_amdgcn_readlane(nw, i);
@@ -212,95 +234,146 @@ __device__ __forceinline__ int aut_step_narrow(const TV &T, const AutSets<BaseT>
 }
 
 // Wide variant (ambiguous grammars make sets of hundreds of items): the set under construction lives
-// in the scratch and every loop over its items runs in strips of 64.
+// in the scratch, with an open-addressing hash table over it (sc_h: 0 = free, else item index + 1;
+// at least twice as many places as items).  The lanes make candidates in parallel -- one source
+// item per lane in Scan, one waiting item of the completed nonterminal's origin set per lane in
+// Complete -- and 64 candidates are entered at a time.  The order of the new set is fixed by strip,
+// round and lane number, so the same source set always yields the same sequence of items.
+__host__ __device__ inline uint32_t aut_hash_places(uint32_t sc_cap) {
+    uint32_t n = 64;
+    while (n < 2 * sc_cap) n <<= 1;
+    return n;
+}
 template <class BaseT>
-__device__ __forceinline__ int aut_step_wide(const TV &T, const AutSets<BaseT> &S, uint32_t *sc_w, uint32_t *sc_o, uint32_t sc_cap,
+__device__ __forceinline__ int aut_step_wide(const TV &T, const AutSets<BaseT> &S, uint32_t *sc_w, uint32_t *sc_o, uint32_t *sc_h, uint32_t sc_cap,
                                              uint32_t cur, uint32_t byte, uint32_t cl, uint32_t lane, uint32_t &nnew_out, uint32_t &kept_out) {
     const uint2 *src;
     uint32_t ns;
     S.view(cur, src, ns);
+    const uint32_t places = aut_hash_places(sc_cap), pmask = places - 1u;
+    for (uint32_t k = lane; k < places; k += 64) lds_store(&sc_h[k], 0u);
     uint32_t nnew = 0;
     bool saw_end = false, failed = false;
-    auto insert = [&](uint32_t w, uint32_t o) {              // uniform arguments
-        unsigned long long dup = 0;
-        for (uint32_t s0 = 0; s0 < nnew; s0 += 64) {
-            const bool in = s0 + lane < nnew;
-            uint32_t xw = 0, xo = 0;
-            if (in) { xw = sc_w[s0 + lane]; xo = sc_o[s0 + lane]; }
-            dup |= __ballot(in && xw == w && xo == o);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    auto insert = [&](bool has, uint32_t w, uint32_t o) {    // per-lane arguments: every lane with `has` brings a candidate
+        if (failed || !__ballot(has)) return;
+        uint32_t h = (w * 0x9E3779B1u) ^ (o * 0x85EBCA77u);
+        h ^= h >> 15; h *= 0x2C1B3C6Du; h ^= h >> 13;
+        uint32_t slot = h & pmask;
+        bool fresh = has;
+        while (fresh) {                                      // in the set already?  (the table always has free places: the probe ends)
+            const uint32_t v = lds_load(&sc_h[slot]);
+            if (v == 0u) break;
+            if (lds_load(&sc_w[v - 1u]) == w && lds_load(&sc_o[v - 1u]) == o) fresh = false;
+            else slot = (slot + 1u) & pmask;
         }
-        const bool add = !dup && nnew < sc_cap;
-        failed |= !dup && !add;
-        if (add && lane == 0) { sc_w[nnew] = w; sc_o[nnew] = o; }
-        nnew += add ? 1u : 0u;
+        unsigned long long f = __ballot(fresh);
+        if (__popcll(f) > 1) {                               // the same candidate on several lanes: the lowest lane keeps it
+            unsigned long long todo = f;
+            while (todo) {
+                const int l = __ffsll((long long)todo) - 1;
+                const uint32_t lw = __builtin_amdgcn_readlane(w, l), lo = __builtin_amdgcn_readlane(o, l);
+                const bool same = fresh && w == lw && o == lo;           // lane l itself included
+                todo &= ~__ballot(same);
+                if (same && lane != (uint32_t)l) fresh = false;
+            }
+            f = __ballot(fresh);
+        }
+        const uint32_t n_f = (uint32_t)__popcll(f);
+        if (n_f > sc_cap - nnew) { failed = true; return; }
+        if (fresh) {                                         // places in lane order; then into the table (distinct keys: any order will do)
+            const uint32_t idx = nnew + (uint32_t)__popcll(f & below);
+            lds_store(&sc_w[idx], w);
+            lds_store(&sc_o[idx], o);
+            while (atomicCAS(&sc_h[slot], 0u, idx + 1u) != 0u) slot = (slot + 1u) & pmask;
+        }
+        nnew += n_f;
+        saw_end = saw_end || __ballot(fresh && (w & IW_END)) != 0;
     };
-    auto advance = [&](uint32_t p, uint32_t o) {
-        for (;;) {
-            const uint32_t w = T.advpq[p];
-            insert(w, o);
-            if (w & IW_END) { saw_end = true; return; }
-            if ((w & IW_TERM) || !(w & IW_NT_NULLABLE)) return;
+    auto chain = [&](bool on, uint32_t p, uint32_t o) {     // per lane: the dot arrives at p; skip nullable nonterminals, canonical END item
+        while (__ballot(on)) {
+            uint32_t w = 0;
+            if (on) w = T.advpq[p];
+            insert(on, w, o);
+            on = on && !(w & (IW_END | IW_TERM)) && (w & IW_NT_NULLABLE);
             p++;
         }
     };
-    for (uint32_t s0 = 0; s0 < ns; s0 += 64) {
-        uint32_t sw = IW_END, so = 0;
+    for (uint32_t s0 = 0; s0 < ns && !failed; s0 += 64) {
+        uint32_t sw = IW_END, so = 0;                        // lanes beyond the set hold an inert item
         if (s0 + lane < ns) { const uint2 x = src[s0 + lane]; sw = x.x; so = x.y; }
+        // Scan, terminal items
         uint32_t nx = DFA_DEAD;
         if (sw & IW_TERM) nx = dfa_next(T, sw >> 16, byte, cl);
-        unsigned long long m = __ballot((nx & 0xFFFFu) != DFA_DEAD);
-        while (m) {
-            const int l = __ffsll((long long)m) - 1;
-            m &= m - 1;
-            const uint32_t lw = __builtin_amdgcn_readlane(sw, l), lo = __builtin_amdgcn_readlane(so, l), lnx = __builtin_amdgcn_readlane(nx, l);
-            if ((lnx >> 16) & QF_CONT) insert((lw & 0xFFFFu) | (lnx << 16), lo);
-            if ((lnx >> 16) & QF_ACCEPT) advance((lw & IW_POS_MASK) + 1, lo);
-        }
+        const bool hit = (nx & 0xFFFFu) != DFA_DEAD;
+        insert(hit && ((nx >> 16) & QF_CONT), (sw & 0xFFFFu) | (nx << 16), so);        // no longest match: keep matching ...
+        chain(hit && ((nx >> 16) & QF_ACCEPT), (sw & IW_POS_MASK) + 1, so);             // ... and also finish here
+        // Scan, items that wait for a nonterminal Y: the tabulated first steps of every terminal that can begin Y
         uint32_t sk0 = 0, sk1 = 0;
         if (!(sw & (IW_TERM | IW_END))) {
             const uint32_t Y = (sw >> IW_NT_SHIFT) & IW_NT_MASK;
             sk0 = T.scan_off[Y * T.ncls + cl]; sk1 = T.scan_off[Y * T.ncls + cl + 1];
         }
-        m = __ballot(sk1 > sk0);
-        while (m) {
-            const int l = __ffsll((long long)m) - 1;
-            m &= m - 1;
-            const uint32_t k0 = __builtin_amdgcn_readlane(sk0, l), k1 = __builtin_amdgcn_readlane(sk1, l);
-            for (uint32_t e = k0; e < k1; e++) {
-                const uint2 ef = T.scan_list[e];
-                if (ef.y & QF_CONT) insert(ef.x, cur);
-                if (ef.y & QF_ACCEPT) advance((ef.x & IW_POS_MASK) + 1, cur);
-            }
+        while (__ballot(sk0 < sk1)) {
+            const bool on = sk0 < sk1;
+            uint2 ef = make_uint2(0, 0);
+            if (on) ef = T.scan_list[sk0];
+            insert(on && (ef.y & QF_CONT), ef.x, cur);
+            chain(on && (ef.y & QF_ACCEPT), (ef.x & IW_POS_MASK) + 1, cur);
+            if (on) sk0++;
         }
     }
     if (saw_end) {
-        for (uint32_t i = 0; i < nnew; i++) {
-            const uint32_t w = sc_w[i], o = sc_o[i];         // every lane reads the same item
-            if (!(w & IW_END)) continue;
+        // Complete: the new items are visited in order, up to 64 at a time (completing appends more).  The
+        // completed items of a strip sit on their lanes; the items of their origin sets -- the ones that
+        // may wait for the completed nonterminal -- are numbered through and dealt to the lanes 64 at
+        // a time, so that short origin sets (a pruned chart's sets hold a handful of items) still fill the wavefront.
+        uint32_t done = 0;
+        while (done < nnew && !failed) {
+            const uint32_t hi = nnew - done < 64u ? nnew : done + 64u;
+            uint32_t w = 0, o = 0;
+            if (done + lane < hi) { w = lds_load(&sc_w[done + lane]); o = lds_load(&sc_o[done + lane]); }
             const uint32_t X = (w & IW_POS_MASK) - T.end_base;
-            if (X == T.N - 1) continue;
-            const uint2 *yp;
-            uint32_t yn;
-            S.view(o, yp, yn);
-            for (uint32_t j0 = 0; j0 < yn; j0 += 64) {
+            const bool is_end = (w & IW_END) && X != T.N - 1;                  // the start rule complete: the prefix is a sentence
+            const uint2 *yp = nullptr;
+            uint32_t yn = 0;
+            if (is_end) S.view(o, yp, yn);
+            uint32_t incl = yn;                                                // running total of the origin sets' sizes
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) { const uint32_t up = __shfl_up(incl, d); if (lane >= (uint32_t)d) incl += up; }
+            const uint32_t excl = incl - yn, total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+            const uint32_t yp_lo = (uint32_t)(uintptr_t)yp, yp_hi = (uint32_t)((uintptr_t)yp >> 32);
+            unsigned long long owners = __ballot(yn > 0);                      // lanes whose origin set is not dealt out yet
+            for (uint32_t t0 = 0; t0 < total && !failed; t0 += 64) {
+                const uint32_t t = t0 + lane;
+                uint32_t own = 0;
+                for (unsigned long long scan = owners; scan;) {                // ranges come in lane order: walk the ones that reach into this strip
+                    const int e = __ffsll((long long)scan) - 1;
+                    scan &= scan - 1;
+                    const uint32_t e_lo = __builtin_amdgcn_readlane((int)excl, e), e_hi = __builtin_amdgcn_readlane((int)incl, e);
+                    if (e_lo >= t0 + 64u) break;
+                    if (t >= e_lo && t < e_hi) own = (uint32_t)e;
+                    if (e_hi <= t0 + 64u) owners &= ~(1ull << e);
+                }
+                const uint32_t oX = __shfl(X, own), oo = __shfl(o, own), o_lo = __shfl(excl, own);
+                const uint2 *oyp = reinterpret_cast<const uint2 *>((uintptr_t)__shfl(yp_lo, own) | ((uintptr_t)__shfl(yp_hi, own) << 32));
                 uint32_t yw = IW_END, yo = 0;
-                if (j0 + lane < yn) { const uint2 y = yp[j0 + lane]; yw = y.x; yo = y.y; }
+                if (t < total) { const uint2 y = oyp[t - o_lo]; yw = y.x; yo = y.y; }
                 const bool nt = !(yw & (IW_TERM | IW_END));
                 const uint32_t Y = (yw >> IW_NT_SHIFT) & IW_NT_MASK;
                 uint32_t c0 = 0, c1 = 0;
-                if (nt) { c0 = T.comp_off[Y * T.N + X]; c1 = T.comp_off[Y * T.N + X + 1]; }
-                unsigned long long mm = __ballot(nt && c1 > c0);
-                while (mm) {
-                    const int l = __ffsll((long long)mm) - 1;
-                    mm &= mm - 1;
-                    const uint32_t lc0 = __builtin_amdgcn_readlane(c0, l), lc1 = __builtin_amdgcn_readlane(c1, l);
-                    for (uint32_t e = lc0; e < lc1; e++) {
-                        const uint32_t cw = T.comp_list[e];
-                        if (cw != 0xFFFFFFFFu) insert(cw, o);
-                        else advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l));
-                    }
+                if (nt) { c0 = T.comp_off[Y * T.N + oX]; c1 = T.comp_off[Y * T.N + oX + 1]; }
+                while (__ballot(c0 < c1)) {
+                    const bool on = c0 < c1;
+                    uint32_t cw = 0;
+                    if (on) cw = T.comp_list[c0];
+                    const bool self = on && cw == 0xFFFFFFFFu;                 // Y itself is complete: the waiting item moves on
+                    insert(on && !self, cw, oo);
+                    chain(self, (yw & IW_POS_MASK) + 1, yo);
+                    if (on) c0++;
                 }
             }
+            done = hi;
         }
     }
     if (failed) return AUT_OVER;
@@ -308,10 +381,10 @@ __device__ __forceinline__ int aut_step_wide(const TV &T, const AutSets<BaseT> &
     uint32_t kept = 0;
     for (uint32_t s0 = 0; s0 < nnew; s0 += 64) {
         uint32_t w = IW_END, o = 0;
-        if (s0 + lane < nnew) { w = sc_w[s0 + lane]; o = sc_o[s0 + lane]; }
+        if (s0 + lane < nnew) { w = lds_load(&sc_w[s0 + lane]); o = lds_load(&sc_o[s0 + lane]); }
         const bool keep = !(w & IW_END);
         const unsigned long long kb = __ballot(keep);
-        if (keep) { const uint32_t at = kept + (uint32_t)__popcll(kb & ((1ull << lane) - 1ull)); sc_w[at] = w; sc_o[at] = o; }
+        if (keep) { const uint32_t at = kept + (uint32_t)__popcll(kb & below); lds_store(&sc_w[at], w); lds_store(&sc_o[at], o); }
         kept += (uint32_t)__popcll(kb);
     }
     nnew_out = nnew;
@@ -323,7 +396,7 @@ __device__ __forceinline__ int aut_step_wide(const TV &T, const AutSets<BaseT> &
 // resulting set (sets are interned by content: the same items in the same order are the same
 // state) or make a new one.  Returns a state id or AT_DEAD / AT_SINK / AT_FAIL.
 template <class BaseT>
-__device__ __forceinline__ uint32_t aut_transition(const TV &T, const BaseT &B, const Aut &A, uint32_t *sc_w, uint32_t *sc_o, uint32_t sc_cap,
+__device__ __forceinline__ uint32_t aut_transition(const TV &T, const BaseT &B, const Aut &A, uint32_t *sc_w, uint32_t *sc_o, uint32_t *sc_h, uint32_t sc_cap,
                                                    uint32_t s, uint32_t byte, uint32_t cl, uint32_t lane) {
     const AutSets<BaseT> S{B, A};
     const uint32_t cur = s == 0 ? B.m - 1 : (AUT_REF | s);   // the source set; also what items predicted in it get as origin
@@ -331,8 +404,8 @@ __device__ __forceinline__ uint32_t aut_transition(const TV &T, const BaseT &B, 
     const uint2 *src_p;
     uint32_t src_n;
     S.view(cur, src_p, src_n);
-    int st = src_n > 48u ? AUT_WIDE : aut_step_narrow(T, S, sc_w, sc_o, sc_cap, cur, byte, cl, lane, nnew, kept);   // a wide source set rarely leaves a narrow one
-    if (st == AUT_WIDE) st = aut_step_wide(T, S, sc_w, sc_o, sc_cap, cur, byte, cl, lane, nnew, kept);
+    int st = src_n > 32u ? AUT_WIDE : aut_step_narrow(T, S, sc_w, sc_o, sc_cap, cur, byte, cl, lane, nnew, kept);   // a wide source set rarely leaves a narrow one
+    if (st == AUT_WIDE) st = aut_step_wide(T, S, sc_w, sc_o, sc_h, sc_cap, cur, byte, cl, lane, nnew, kept);
     if (st != AUT_OK) return AT_FAIL;
     if (nnew == 0) return AT_DEAD;
     if (kept == 0) return AT_SINK;
@@ -376,10 +449,10 @@ __device__ __forceinline__ uint32_t aut_transition(const TV &T, const BaseT &B, 
 
 // Compute the transition of state s on class cl (the caller owns it: its entry is AT_BUSY) and publish it.
 template <class BaseT>
-__device__ __forceinline__ void aut_resolve(const TV &T, const BaseT &B, const Aut &A, uint32_t *sc_w, uint32_t *sc_o, uint32_t sc_cap,
+__device__ __forceinline__ void aut_resolve(const TV &T, const BaseT &B, const Aut &A, uint32_t *sc_w, uint32_t *sc_o, uint32_t *sc_h, uint32_t sc_cap,
                                             uint32_t s, uint32_t cl, uint32_t lane) {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");   // the states this step reads were published by other wavefronts
-    const uint32_t r = aut_transition(T, B, A, sc_w, sc_o, sc_cap, s, A.rep[cl], cl, lane);
+    const uint32_t r = aut_transition(T, B, A, sc_w, sc_o, sc_h, sc_cap, s, A.rep[cl], cl, lane);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the new state before the transition that leads to it
     if (lane == 0) lds_store(&A.trans[s * A.ncls + cl], r);
 }
@@ -388,7 +461,7 @@ __device__ __forceinline__ void aut_resolve(const TV &T, const BaseT &B, const A
 // the help queue; wavefronts that wait or have run out of strings take them from there.  Serves one
 // request if there is one; returns false when the queue is empty.  Uniform over the wavefront.
 template <class BaseT>
-__device__ __forceinline__ bool aut_help(const TV &T, const BaseT &B, const Aut &A, uint32_t *sc_w, uint32_t *sc_o, uint32_t sc_cap, uint32_t lane, uint32_t &steps) {
+__device__ __forceinline__ bool aut_help(const TV &T, const BaseT &B, const Aut &A, uint32_t *sc_w, uint32_t *sc_o, uint32_t *sc_h, uint32_t sc_cap, uint32_t lane, uint32_t &steps) {
     uint32_t tail = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&A.ctl[4]));
     tail = tail < (uint32_t)AUT_HELP_QUEUE ? tail : (uint32_t)AUT_HELP_QUEUE;
     const uint32_t head = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&A.ctl[5]));
@@ -403,7 +476,7 @@ __device__ __forceinline__ bool aut_help(const TV &T, const BaseT &B, const Aut 
         __builtin_amdgcn_s_sleep(1);
     }
     if (!(e & HQ_VALID)) return true;                        // cannot happen: places below the end of the queue are always filled
-    aut_resolve(T, B, A, sc_w, sc_o, sc_cap, (e & ~HQ_VALID) >> 8, e & 0xFFu, lane);
+    aut_resolve(T, B, A, sc_w, sc_o, sc_h, sc_cap, (e & ~HQ_VALID) >> 8, e & 0xFFu, lane);
     steps++;
     return true;
 }
@@ -441,8 +514,9 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
     A.hash = reinterpret_cast<uint32_t *>(smem + off); off += aut_round16(A.states_cap * 4);
     A.ctl = reinterpret_cast<uint32_t *>(smem + off); off += 32;
     A.hq = reinterpret_cast<uint32_t *>(smem + off); off += AUT_HELP_QUEUE * 4;
-    uint32_t *l_so = reinterpret_cast<uint32_t *>(smem + off); off += aut_round16((BASE_SETS_LDS + 1) * 4);
-    uint2 *l_it = reinterpret_cast<uint2 *>(smem + off); off += BASE_ITEMS_LDS * 8;
+    const uint32_t base_sets_cap = (uint32_t)a.aut_base_sets, base_items_cap = (uint32_t)a.aut_base_items;
+    uint32_t *l_so = reinterpret_cast<uint32_t *>(smem + off); off += aut_round16((base_sets_cap + 1) * 4);
+    uint2 *l_it = reinterpret_cast<uint2 *>(smem + off); off += aut_round16(base_items_cap * 8);
     uint32_t *l_ent = reinterpret_cast<uint32_t *>(smem + off); off += AUT_ENT_LDS * 4;
     uint8_t *l_rep = smem + off; off += 256;
     A.rep = l_rep;
@@ -450,14 +524,14 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
     uint32_t *cslice = reinterpret_cast<uint32_t *>(smem + off); off += AUT_SUB_WORDS * 4;
     uint8_t *pairs = smem + off; off += AUT_SUB_WORDS / 2;   // slots of the word pairs that hold undecided strings
     A.arena = reinterpret_cast<uint2 *>(smem + off); off += aut_round16(A.arena_cap * 8);
-    uint32_t *sc_w = reinterpret_cast<uint32_t *>(smem + off) + (size_t)wave * 2 * sc_cap;
-    uint32_t *sc_o = sc_w + sc_cap;
+    uint32_t *sc_w = reinterpret_cast<uint32_t *>(smem + off) + (size_t)wave * (2 * sc_cap + aut_hash_places(sc_cap));
+    uint32_t *sc_o = sc_w + sc_cap, *sc_h = sc_o + sc_cap;
     // the row's chart: its LDS copy when it is small, else global memory (generic pointers either way)
     const RowChart rc = a.rows[row];
     const uint32_t *g_so = a.set_off + rc.set_base;
     const uint2 *g_it = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
     const uint32_t *g_ent = a.entries + rc.ent_base;
-    const bool base_fits = rc.n_sets <= BASE_SETS_LDS && rc.n_items <= BASE_ITEMS_LDS;   // both limits are below the block size
+    const bool base_fits = rc.n_sets <= base_sets_cap && rc.n_items <= base_items_cap;
     const bool ent_fits = rc.n_ent <= AUT_ENT_LDS;
     uint32_t so_v = 0, ent_v = 0;
     uint2 it_v = make_uint2(0, 0);
@@ -472,6 +546,10 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
     if (base_fits && tid < rc.n_items) l_it[tid] = it_v;
     if (ent_fits && tid < rc.n_ent) l_ent[tid] = ent_v;
     if (tid < 256) l_rep[tid] = rep_v;
+    if (base_fits) {                                         // a long chart: what the first load per thread did not cover
+        for (uint32_t k = tid + AUT_BLOCK; k <= rc.n_sets; k += AUT_BLOCK) l_so[k] = g_so[k];
+        for (uint32_t k = tid + AUT_BLOCK; k < rc.n_items; k += AUT_BLOCK) l_it[k] = g_it[k];
+    }
     for (uint32_t k = tid; k < A.states_cap * A.ncls; k += AUT_BLOCK) A.trans[k] = AT_NONE;
     for (uint32_t k = tid; k < A.states_cap; k += AUT_BLOCK) A.hdr[k] = make_uint2(0, 0xFFFFFFFFu);
     for (uint32_t k = tid; k < (uint32_t)AUT_HELP_QUEUE; k += AUT_BLOCK) A.hq[k] = 0;
@@ -580,10 +658,10 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
                             else lds_store(&A.trans[s * A.ncls + c], (uint32_t)AT_NONE);   // no room in the queue: the claim is given back
                         }
                     }
-                    aut_resolve(T, B, A, sc_w, sc_o, sc_cap, (uint32_t)__builtin_amdgcn_readlane((int)s, first), (uint32_t)__builtin_amdgcn_readlane((int)c, first), lane);
+                    aut_resolve(T, B, A, sc_w, sc_o, sc_h, sc_cap, (uint32_t)__builtin_amdgcn_readlane((int)s, first), (uint32_t)__builtin_amdgcn_readlane((int)c, first), lane);
                     steps++;
                 }
-                if (!progress && !aut_help(T, B, A, sc_w, sc_o, sc_cap, lane, steps)) {   // everything this wavefront waits for is being computed by others
+                if (!progress && !aut_help(T, B, A, sc_w, sc_o, sc_h, sc_cap, lane, steps)) {   // everything this wavefront waits for is being computed by others
                     __builtin_amdgcn_s_sleep(4);
                     if (++spins > (uint32_t)AUT_SPIN_LIMIT) { fail = fail || live; live = false; }   // bounded wait: hand the strings to the fallback
                 }
@@ -610,10 +688,10 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
         }
         // out of strings: serve the help queue until every batch of the block is finished
         for (uint32_t idle = 0; (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&A.ctl[6])) < n_pairs && idle < (uint32_t)AUT_SPIN_LIMIT;) {
-            if (aut_help(T, B, A, sc_w, sc_o, sc_cap, lane, steps)) idle = 0;
+            if (aut_help(T, B, A, sc_w, sc_o, sc_h, sc_cap, lane, steps)) idle = 0;
             else { __builtin_amdgcn_s_sleep(4); idle++; }
         }
-        while (aut_help(T, B, A, sc_w, sc_o, sc_cap, lane, steps)) {}       // nothing may stay marked as being computed
+        while (aut_help(T, B, A, sc_w, sc_o, sc_h, sc_cap, lane, steps)) {}       // nothing may stay marked as being computed
         __syncthreads();
         if (tid < AUT_SUB_WORDS) { const uint32_t w = word_of(tid); if (w < Wr) a.rank_mask[(size_t)row * Wr + w] = vslice[tid]; }
     }
@@ -631,13 +709,13 @@ hipError_t prepare_automaton_kernels() {
     return hipSuccess;
 }
 
-uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int arena, int scratch) {
+uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int arena, int scratch, int base_sets, int base_items) {
     return table_bytes(t, mode) + aut_round16((uint32_t)states * (uint32_t)t.n_cls * 4) + aut_round16((uint32_t)states * 8) + aut_round16((uint32_t)states * 4) + 32 + AUT_HELP_QUEUE * 4 +
-           aut_round16((BASE_SETS_LDS + 1) * 4) + BASE_ITEMS_LDS * 8 + AUT_ENT_LDS * 4 + 256 + 2 * AUT_SUB_WORDS * 4 + AUT_SUB_WORDS / 2 + aut_round16((uint32_t)arena * 8) +
-           AUT_WAVES * (uint32_t)scratch * 8;
+           aut_round16(((uint32_t)base_sets + 1) * 4) + aut_round16((uint32_t)base_items * 8) + AUT_ENT_LDS * 4 + 256 + 2 * AUT_SUB_WORDS * 4 + AUT_SUB_WORDS / 2 + aut_round16((uint32_t)arena * 8) +
+           AUT_WAVES * ((uint32_t)scratch * 8 + aut_hash_places((uint32_t)scratch) * 4);
 }
 hipError_t launch_mask_automaton(const MaskArgs &a, hipStream_t s) {
-    const uint32_t lds = automaton_lds_bytes(a.tab, a.mode, a.aut_states, a.aut_arena, a.aut_scratch);
+    const uint32_t lds = automaton_lds_bytes(a.tab, a.mode, a.aut_states, a.aut_arena, a.aut_scratch, a.aut_base_sets, a.aut_base_items);
     dim3 grid(a.aut_parts, a.batch);
     if (a.mode == 0) hipLaunchKernelGGL(mask_automaton_kernel<0>, grid, dim3(AUT_BLOCK), lds, s, a);
     else if (a.mode == 1) hipLaunchKernelGGL(mask_automaton_kernel<1>, grid, dim3(AUT_BLOCK), lds, s, a);
