@@ -1,9 +1,16 @@
 // The C boundary: argument checks, engine / state life cycle, advance, chart packing and
 // upload, kernel launches.
 #include <hip/hip_runtime_api.h>
+#include <unistd.h>
+#include <algorithm>
+#include <atomic>
+#include <condition_variable>
 #include <cstring>
-#include <unordered_map>
+#include <memory>
+#include <mutex>
 #include <new>
+#include <thread>
+#include <unordered_map>
 #include "zf_internal.h"
 #include "zf_launch.h"
 
@@ -317,14 +324,138 @@ int zf_advance(zf_state *s, int32_t token) {
     return feed_token_bytes(s, e->voc_bytes.data() + e->voc_off[token], e->voc_off[token + 1] - e->voc_off[token]);
 }
 
+// Rows of a batch are independent (one state = one query).  A byte step of an ambiguous grammar
+// costs O(set size squared) on the host, so a batch of wide charts is dealt to a few worker
+// threads; batches of small charts (the common case: a pruned chart's sets hold a handful of
+// items, Section 4.2) are fed by the caller's thread, where waking anybody would cost more than
+// the work.
+namespace {
+
+struct AdvanceJob {
+    zf_state *const *states;
+    const int32_t *ids;
+    int32_t n;
+    int32_t *rc;                 // [n]
+    std::string *err;            // [n] the error text of a row that failed
+    std::atomic<int32_t> next{0}, done{0};
+};
+
+int advance_one(zf_state *s, int32_t id) { return id < 0 ? zf_state_reset(s) : zf_advance(s, id); }
+
+bool advance_rows(AdvanceJob &j) {   // takes rows until none is left; true if it fed any
+    bool any = false;
+    for (;;) {
+        const int32_t b = j.next.fetch_add(1, std::memory_order_relaxed);
+        if (b >= j.n) return any;
+        j.rc[b] = advance_one(j.states[b], j.ids[b]);
+        if (j.rc[b] != ZF_OK) j.err[b] = zf_last_error();   // the text lives in the worker's thread: hand it over
+        j.done.fetch_add(1, std::memory_order_release);
+        any = true;
+    }
+}
+
+class AdvancePool {              // created on first use, never destroyed: its threads sleep until the process ends
+  public:
+    explicit AdvancePool(int n_workers) : n_workers_(n_workers), pid_(getpid()) {
+        for (int i = 0; i < n_workers; i++) std::thread([this] { loop(); }).detach();
+    }
+    bool usable() const { return n_workers_ > 0 && pid_ == getpid(); }   // a forked child has the object but not the threads
+    // The caller feeds rows too and returns when every row is done; a worker that wakes up late finds
+    // no row left and never touches the caller's arrays (the job object itself is shared).
+    void run(const std::shared_ptr<AdvanceJob> &j) {
+        {
+            std::lock_guard<std::mutex> lk(m_);
+            job_ = j; epoch_++;
+        }
+        cv_work_.notify_all();
+        advance_rows(*j);
+        std::unique_lock<std::mutex> lk(m_);
+        cv_done_.wait(lk, [&] { return j->done.load(std::memory_order_acquire) == j->n; });
+        job_.reset();
+    }
+
+  private:
+    void loop() {
+        uint64_t seen = 0;
+        for (;;) {
+            std::shared_ptr<AdvanceJob> j;
+            {
+                std::unique_lock<std::mutex> lk(m_);
+                cv_work_.wait(lk, [&] { return epoch_ != seen; });
+                seen = epoch_;
+                j = job_;
+            }
+            if (j && advance_rows(*j)) {
+                { std::lock_guard<std::mutex> lk(m_); }     // the caller is either before its check or already waiting
+                cv_done_.notify_one();
+            }
+        }
+    }
+    std::mutex m_;
+    std::condition_variable cv_work_, cv_done_;
+    std::shared_ptr<AdvanceJob> job_;
+    uint64_t epoch_ = 0;
+    int n_workers_ = 0;
+    pid_t pid_;
+};
+
+std::mutex g_pool_mutex;         // one batch at a time through the pool; a second caller feeds its rows itself
+AdvancePool *g_pool = nullptr;
+
+// Host cost of feeding the rows' tokens, in item visits: Scan reads the current set once per byte,
+// Complete of an ambiguous grammar pairs its items with each other, Compact sweeps the chart.
+const int64_t ADVANCE_PARALLEL_FROM = 12000;   // about 0.1 ms of one core: below that the hand-over costs more than it saves
+int64_t advance_cost(zf_state *const *states, const int32_t *ids, int32_t n) {
+    int64_t cost = 0;
+    for (int32_t b = 0; b < n; b++) {
+        const zf_state *s = states[b];
+        if (!s || ids[b] < 0 || ids[b] >= s->eng->V) continue;
+        const Chart &c = s->chart;
+        const int64_t last = c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1];
+        cost += (s->eng->voc_off[ids[b] + 1] - s->eng->voc_off[ids[b]]) * (last + last * last / 16) + (int64_t)c.items.size();
+    }
+    return cost;
+}
+
+}  // namespace
+
 int zf_advance_batch(zf_state *const *states, const int32_t *token_ids, int32_t n, int32_t *status) {
     if (!states || !token_ids || n < 0) return fail(ZF_ERR_INVALID_ARG, "null argument");
+    for (int32_t b = 0; b < n; b++) if (!states[b]) return fail(ZF_ERR_INVALID_ARG, "null state");
     int first = ZF_OK;
-    for (int32_t b = 0; b < n; b++) {
-        const int rc = token_ids[b] < 0 ? zf_state_reset(states[b]) : zf_advance(states[b], token_ids[b]);
-        if (status) status[b] = rc;
-        if (rc != ZF_OK && first == ZF_OK) first = rc;
+    bool parallel = n >= 4 && advance_cost(states, token_ids, n) >= ADVANCE_PARALLEL_FROM;
+    if (parallel) {                                       // every state at most once: a state named twice is fed twice, in order
+        std::vector<const zf_state *> seen(states, states + n);
+        std::sort(seen.begin(), seen.end());
+        parallel = std::adjacent_find(seen.begin(), seen.end()) == seen.end();
     }
+    std::unique_lock<std::mutex> pool_lock(g_pool_mutex, std::defer_lock);
+    if (parallel) parallel = pool_lock.try_lock();
+    if (parallel) {
+        if (!g_pool) {
+            const unsigned hw = std::thread::hardware_concurrency();
+            g_pool = new AdvancePool((int)std::min(15u, std::max(1u, hw) - 1u));
+        }
+        parallel = g_pool->usable();
+    }
+    if (!parallel) {
+        std::string first_err;
+        for (int32_t b = 0; b < n; b++) {
+            const int rc = advance_one(states[b], token_ids[b]);
+            if (status) status[b] = rc;
+            if (rc != ZF_OK && first == ZF_OK) { first = rc; first_err = zf_last_error(); }
+        }
+        if (first != ZF_OK) set_error(first_err);        // the caller sees the first failing row's text
+        return first;
+    }
+    std::vector<int32_t> rc_store;
+    if (!status) { rc_store.assign((size_t)n, ZF_OK); status = rc_store.data(); }
+    std::vector<std::string> errs((size_t)n);
+    auto job = std::make_shared<AdvanceJob>();
+    job->states = states; job->ids = token_ids; job->n = n; job->rc = status; job->err = errs.data();
+    g_pool->run(job);
+    for (int32_t b = n - 1; b >= 0; b--)
+        if (status[b] != ZF_OK) { first = status[b]; set_error(errs[b]); }
     return first;
 }
 

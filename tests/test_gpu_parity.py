@@ -363,6 +363,42 @@ def test_long_tokens_deep_nesting_many_classes(mode, torch_cuda, oracle_lib):
     _run_parity(torch, zf, oracle_lib.Oracle, g2, toks2, 3, 12, 4242, walk_mode=MODES[mode])
 
 
+@pytest.mark.parametrize("cap", [None, 72, 200], ids=["default-budget", "budget-72", "budget-200"])
+def test_wide_sets_of_an_ambiguous_grammar(cap, torch_cuda, oracle_lib):
+    """Sets far beyond 64 items (the ambiguous expression grammar after sums of 20 to 150 operands: every
+    operand is another origin) through the mask automaton: the set under construction then lives in LDS
+    behind a hash table and Complete deals the origin sets' items to the lanes.  With a budget of 72 or
+    200 items the wider sets run out of room and their strings must come back through the fallback pass."""
+    import paper_2506_01151_amd as zf
+    torch = torch_cuda
+    cfg = configs.CONFIGS[5]
+    g, toks = cfg.grammar(), cfg.vocab(6000)
+    off, data = wvocab.vocab_csr(toks)
+    orc = oracle_lib.Oracle(g)
+    kw = {} if cap is None else {"lane_item_cap": cap}
+    eng = zf.Engine(g, toks, device=0, state_cache_entries=-1, **kw)
+    prefixes = [b"a" + b"+b" * 20, b"a" + b"*77" * 45 + b"+", b"(a" + b"+b" * 70 + b")*c" + b"+d" * 12, b"x" + b"+(y)" * 150, b"q" + b"*r" * 160 + b"*(",
+                b"a+b", b"a" + b"+b" * 300]
+    so, ss = [], []
+    for p in prefixes:
+        a, b = orc.new_state(), eng.new_state()
+        assert a.feed_bytes(p)
+        b.advance_bytes(p)
+        so.append(a)
+        ss.append(b)
+    def last_set_size(st):
+        items, n_sets = st.chart()
+        return sum(1 for it in items if it[0] == n_sets - 1)
+    assert max(last_set_size(s) for s in ss) > 250
+    d_mask = torch.full((len(prefixes), eng.W), -1, dtype=torch.int32, device="cuda")
+    zf.compute_mask(eng, ss, d_mask)
+    got = d_mask.cpu().numpy().view(np.uint32)
+    for i, a in enumerate(so):
+        assert (got[i] == a.mask(off, data, 4)).all(), prefixes[i][:12]
+    if cap is not None:
+        assert eng.mask_report().overflow_chunks > 0, "the budget was meant to be too small for the widest sets"
+
+
 @pytest.mark.parametrize("mode", list(MODES))
 def test_many_rows_and_longest_token(mode, torch_cuda, oracle_lib):
     """A batch larger than the number of compute units (one block per row and less) and tokens of the

@@ -271,6 +271,50 @@ def test_advance_batch_equals_row_by_row():
     assert many[0].chart() == fresh.chart() and many[2].chart() == fresh.chart()
 
 
+def test_advance_batch_of_wide_charts_on_worker_threads():
+    """A batch whose rows are expensive to feed (wide sets of the ambiguous expression grammar) is dealt to
+    worker threads: same charts as row by row, over several calls; a rejected row keeps its chart, is
+    reported with its own error text, and does not stop the others; a state named twice is fed twice."""
+    import paper_2506_01151_amd as zf
+    cfg = configs.CONFIGS[5]
+    toks = cfg.vocab(3000)
+    eng = zf.Engine(cfg.grammar(), toks, device=-1)
+    plus, star, a, seven, close = (toks.index(t) for t in (b"+", b"*", b"a", b"7", b")"))
+    rows = 12
+    singles = [eng.new_state() for _ in range(rows)]
+    many = zf.StateBatch([eng.new_state() for _ in range(rows)])
+    for b in range(rows):
+        prefix = b"x" + (b"+y" if b % 2 else b"*3") * (60 + 7 * b)
+        singles[b].advance_bytes(prefix)
+        many[b].advance_bytes(prefix)
+    for step in range(6):
+        ids = [(plus, a, star, seven, -1, a)[(step + (b % 3 == 0)) % 6] if step % 2 == 0 else (a, plus, seven, star, plus, a)[(step + (b % 3 == 0)) % 6] for b in range(rows)]
+        ok = []
+        for b in range(rows):
+            if ids[b] < 0:
+                singles[b].reset()
+                ok.append(True)
+            else:
+                ok.append(singles[b].try_advance(ids[b]) == zf.ZF_OK)
+        if all(ok):
+            many.advance(ids)
+        else:
+            with pytest.raises(zf.ZfError) as ei:
+                many.advance(ids)
+            assert ei.value.code == zf.ZF_ERR_REJECTED and "cannot extend" in str(ei.value)
+        for b in range(rows):
+            assert many[b].chart() == singles[b].chart() and many[b].accepting() == singles[b].accepting(), (step, b)
+    # a state named twice in one batch: fed twice, in order
+    twice = zf.StateBatch([many[1], many[1], many[2], many[3], many[4]])
+    ref = singles[1]
+    t1 = plus if ref.clone().try_advance(plus) == zf.ZF_OK else a
+    ref.advance(t1)
+    t2 = a if ref.clone().try_advance(a) == zf.ZF_OK else plus
+    ref.advance(t2)
+    twice.advance([t1, t2, -1, -1, -1])
+    assert many[1].chart() == ref.chart()
+
+
 @pytest.mark.parametrize("seed", range(48))
 def test_random_grammars_host_walk_equals_oracle(seed, zf, oracle_lib):
     """Differential test on seeded random grammars (empty rules, unit cycles, recursion of every
