@@ -758,18 +758,20 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
         // LDS budgets of one block's automaton.  The set under construction gets the configured item
         // budget (tests set it tiny to force the fallback pass), else room for sets a few times as wide
         // as the widest current set; states and the item arena share what the tables leave of 160 KB.
-        size_t widest = 0, most_sets = 0, most_items = 0;
+        size_t widest = 0, most_sets = 0, most_items = 0, biggest_set = 0;
         for (int r = 0; r < nb; r++) {
             const Chart &c = states[miss_rows[r]]->chart;
             widest = std::max<size_t>(widest, c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1]);
             most_sets = std::max<size_t>(most_sets, c.n_sets());
             most_items = std::max<size_t>(most_items, c.set_off[c.n_sets()]);
+            for (uint32_t k = 0; k < c.n_sets(); k++) biggest_set = std::max<size_t>(biggest_set, c.set_off[k + 1] - c.set_off[k]);
         }
         int scratch = e->lane_cap_auto ? (int)std::min<size_t>(LANE_CAP_MAX, (4 * widest + 128 + 31) / 32 * 32) : e->opt.lane_item_cap;
         int n_states = AUT_STATES_DEFAULT, arena = std::max(1024, 8 * scratch);
         int base_sets = BASE_SETS_LDS, base_items = BASE_ITEMS_LDS;
+        const bool wide = biggest_set > (size_t)AUT_NARROW_SET_MAX;
         const uint32_t lds_max = 160u * 1024u;
-        auto lds_now = [&]() { return automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch, base_sets, base_items); };
+        auto lds_now = [&]() { return automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch, base_sets, base_items, wide); };
         while (lds_now() > lds_max && arena > 2 * scratch) arena /= 2;
         while (lds_now() > lds_max && n_states > 8) n_states /= 2;
         while (lds_now() > lds_max && scratch > 32) { scratch /= 2; arena = std::max(arena / 2, 2 * scratch); }
@@ -779,12 +781,13 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
             const int want_sets = (int)std::max<size_t>(BASE_SETS_LDS, (most_sets + 32) / 32 * 32 - 1);
             const int want_items = (int)std::max<size_t>(BASE_ITEMS_LDS, (most_items + 63) / 64 * 64);
             if (want_sets <= AUT_BASE_SETS_MAX && want_items <= AUT_BASE_ITEMS_MAX &&
-                automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch, want_sets, want_items) <= lds_max) {
+                automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch, want_sets, want_items, wide) <= lds_max) {
                 base_sets = want_sets; base_items = want_items;
             }
         }
         a.aut_states = n_states; a.aut_arena = arena; a.aut_scratch = scratch;
         a.aut_base_sets = base_sets; a.aut_base_items = base_items;
+        a.aut_wide = wide ? 1 : 0;
         // blocks per row: enough to fill the chip about once, at most one block per pass of AUT_SUB_WORDS words
         const int n_sub = (d->tab.Wr + AUT_SUB_WORDS - 1) / AUT_SUB_WORDS;
         a.aut_parts = std::max(1, std::min(n_sub, (2 * std::max(1, d->cus) + std::max(nb, 1) - 1) / std::max(nb, 1)));

@@ -14,6 +14,7 @@ static const int WALK_NODES_LDS = 80;      // trie nodes of a chunk the walk ker
 static const int WALK_DEPTH_MAX = 32;      // trie depth the walk kernel follows (deeper paths go to the fallback)
 static const int BASE_SETS_LDS = 31;       // a row's chart is staged into LDS when it has at most this many sets ...
 static const int BASE_ITEMS_LDS = 64;      // ... and items (the mask-automaton kernel takes larger limits from the host when LDS allows)
+static const int AUT_NARROW_SET_MAX = 8;    // charts whose sets are all this small run the kernel build without the wide variant of the byte step
 static const int AUT_BASE_SETS_MAX = 1023; // the largest limits the host asks for
 static const int AUT_BASE_ITEMS_MAX = 4096;
 static const int TABLE_LDS_BUDGET = 56 * 1024;
@@ -63,6 +64,7 @@ struct MaskArgs {
     int32_t aut_parts;         // blocks per row (grid.x)
     int32_t aut_base_sets;     // a row's chart is staged into LDS when it has at most this many sets ...
     int32_t aut_base_items;    // ... and items (both at least BASE_SETS_LDS / BASE_ITEMS_LDS)
+    int32_t aut_wide;          // 1: some set of some row's chart has more than AUT_NARROW_SET_MAX items (the kernel build with the wide byte step)
 };
 
 int choose_table_mode(const DeviceTables &t);
@@ -74,7 +76,7 @@ hipError_t prepare_automaton_kernels();
 hipError_t launch_upload(const void *pinned_src, void *dst, size_t bytes, hipStream_t s);   // bytes rounded up to 16: both buffers must hold that much
 hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s);
-uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int arena, int scratch, int base_sets, int base_items);
+uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int arena, int scratch, int base_sets, int base_items, bool wide);
 hipError_t launch_mask_automaton(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_fallback(const MaskArgs &a, hipStream_t s);
 hipError_t launch_permute(const MaskArgs &a, hipStream_t s);

@@ -43,7 +43,7 @@ struct Aut {               // one block's automaton; every pointer leads into LD
 // byte classes at once (lane = class): an item before a terminal survives a class iff its DFA has
 // an edge, an item that waits for a nonterminal iff some terminal that can begin it has one.  What
 // remains for the byte step proper are the few classes that lead somewhere.
-template <class ItemWord>
+template <bool WIDE, class ItemWord>
 __device__ __forceinline__ void aut_mark_dead(const TV &T, const Aut &A, ItemWord item, uint32_t n, uint32_t id, uint32_t lane) {
     auto survives = [&](uint32_t w, uint32_t byte, uint32_t c) -> bool {   // no branch: both kinds of look-up are made, with safe indices
         const bool term = (w & IW_TERM) != 0, end = (w & IW_END) != 0;
@@ -55,7 +55,7 @@ __device__ __forceinline__ void aut_mark_dead(const TV &T, const Aut &A, ItemWor
         const bool a_nt = T.scan_off[Y * T.ncls + c + 1] > T.scan_off[Y * T.ncls + c];
         return !end && (term ? a_term : a_nt);
     };
-    if (n > 16u) {                                           // a wide set: one item per lane, the classes in turn
+    if (WIDE && n > 16u) {                                   // a wide set: one item per lane, the classes in turn
         for (uint32_t c0 = 0; c0 < A.ncls; c0 += 64) {
             const uint32_t nc = A.ncls - c0 < 64u ? A.ncls - c0 : 64u;
             uint32_t lo = 0, hi = 0;                         // bit k: some item of this lane survives class c0 + k
@@ -112,7 +112,7 @@ struct AutSets {           // resolves origin references
 
 // Narrow variant: the set under construction lives in registers (lane j holds new item j), so the
 // duplicate test is one compare + ballot; the source set is read in strips of 64 items.
-template <class BaseT>
+template <bool WIDE, class BaseT>
 __device__ __forceinline__ int aut_step_narrow(const TV &T, const AutSets<BaseT> &S, uint32_t *sc_w, uint32_t *sc_o, uint32_t sc_cap,
                                                uint32_t cur, uint32_t byte, uint32_t cl, uint32_t lane, uint32_t &nnew_out, uint32_t &kept_out) {
     const uint2 *src;
@@ -191,7 +191,7 @@ __device__ __forceinline__ int aut_step_narrow(const TV &T, const AutSets<BaseT>
         for (;;) {
             const unsigned long long todo = __ballot(lane < nnew && (nw & IW_END)) & ~visited;
             if (!todo) break;
-            if (tries > (uint32_t)AUT_NARROW_TRIES) return AUT_WIDE;   // candidates come one at a time here: an ambiguous grammar makes hundreds, mostly duplicates
+            if (WIDE && tries > (uint32_t)AUT_NARROW_TRIES) return AUT_WIDE;   // candidates come one at a time here: an ambiguous grammar makes hundreds, mostly duplicates
             const int i = __ffsll((long long)todo) - 1;
             visited |= 1ull << i;
             const uint32_t w = __builtin_amdgcn_readlane(nw, i);
@@ -395,7 +395,7 @@ __device__ __forceinline__ int aut_step_wide(const TV &T, const AutSets<BaseT> &
 // The transition of state s on class cl: take the byte step, then find the state that holds the
 // resulting set (sets are interned by content: the same items in the same order are the same
 // state) or make a new one.  Returns a state id or AT_DEAD / AT_SINK / AT_FAIL.
-template <class BaseT>
+template <bool WIDE, class BaseT>
 __device__ __forceinline__ uint32_t aut_transition(const TV &T, const BaseT &B, const Aut &A, uint32_t *sc_w, uint32_t *sc_o, uint32_t *sc_h, uint32_t sc_cap,
                                                    uint32_t s, uint32_t byte, uint32_t cl, uint32_t lane) {
     const AutSets<BaseT> S{B, A};
@@ -404,8 +404,8 @@ __device__ __forceinline__ uint32_t aut_transition(const TV &T, const BaseT &B, 
     const uint2 *src_p;
     uint32_t src_n;
     S.view(cur, src_p, src_n);
-    int st = src_n > 32u ? AUT_WIDE : aut_step_narrow(T, S, sc_w, sc_o, sc_cap, cur, byte, cl, lane, nnew, kept);   // a wide source set rarely leaves a narrow one
-    if (st == AUT_WIDE) st = aut_step_wide(T, S, sc_w, sc_o, sc_h, sc_cap, cur, byte, cl, lane, nnew, kept);
+    int st = WIDE && src_n > 32u ? AUT_WIDE : aut_step_narrow<WIDE>(T, S, sc_w, sc_o, sc_cap, cur, byte, cl, lane, nnew, kept);   // a wide source set rarely leaves a narrow one
+    if (st == AUT_WIDE) st = WIDE ? aut_step_wide(T, S, sc_w, sc_o, sc_h, sc_cap, cur, byte, cl, lane, nnew, kept) : (int)AUT_OVER;
     if (st != AUT_OK) return AT_FAIL;
     if (nnew == 0) return AT_DEAD;
     if (kept == 0) return AT_SINK;
@@ -439,7 +439,7 @@ __device__ __forceinline__ uint32_t aut_transition(const TV &T, const BaseT &B, 
     if (id >= A.states_cap || at + kept > A.arena_cap) return AT_FAIL;
     for (uint32_t i0 = 0; i0 < kept; i0 += 64)
         if (i0 + lane < kept) A.arena[at + i0 + lane] = make_uint2(sc_w[i0 + lane], sc_o[i0 + lane]);
-    aut_mark_dead(T, A, [&](uint32_t i) { return sc_w[i]; }, kept, id, lane);
+    aut_mark_dead<WIDE>(T, A, [&](uint32_t i) { return sc_w[i]; }, kept, id, lane);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // items before the hash, the hash before the header that makes the state visible
     if (lane == 0) A.hash[id] = h;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -448,37 +448,37 @@ __device__ __forceinline__ uint32_t aut_transition(const TV &T, const BaseT &B, 
 }
 
 // Compute the transition of state s on class cl (the caller owns it: its entry is AT_BUSY) and publish it.
-template <class BaseT>
+template <bool WIDE, class BaseT>
 __device__ __forceinline__ void aut_resolve(const TV &T, const BaseT &B, const Aut &A, uint32_t *sc_w, uint32_t *sc_o, uint32_t *sc_h, uint32_t sc_cap,
                                             uint32_t s, uint32_t cl, uint32_t lane) {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");   // the states this step reads were published by other wavefronts
-    const uint32_t r = aut_transition(T, B, A, sc_w, sc_o, sc_h, sc_cap, s, A.rep[cl], cl, lane);
+    const uint32_t r = aut_transition<WIDE>(T, B, A, sc_w, sc_o, sc_h, sc_cap, s, A.rep[cl], cl, lane);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the new state before the transition that leads to it
     if (lane == 0) lds_store(&A.trans[s * A.ncls + cl], r);
 }
 
 // A wavefront whose strings miss several transitions at once computes one and leaves the others in
-// the help queue; wavefronts that wait or have run out of strings take them from there.  Serves one
-// request if there is one; returns false when the queue is empty.  Uniform over the wavefront.
-template <class BaseT>
-__device__ __forceinline__ bool aut_help(const TV &T, const BaseT &B, const Aut &A, uint32_t *sc_w, uint32_t *sc_o, uint32_t *sc_h, uint32_t sc_cap, uint32_t lane, uint32_t &steps) {
+// the help queue; wavefronts that wait or have run out of strings take them from there.  Takes one
+// request (s, cl) if there is one.  Uniform over the wavefront.
+enum { AUT_HQ_EMPTY = 0, AUT_HQ_GOT = 1, AUT_HQ_AGAIN = 2 /* another wavefront was faster: look again */ };
+__device__ __forceinline__ int aut_help_take(const Aut &A, uint32_t lane, uint32_t &s, uint32_t &cl) {
     uint32_t tail = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&A.ctl[4]));
     tail = tail < (uint32_t)AUT_HELP_QUEUE ? tail : (uint32_t)AUT_HELP_QUEUE;
     const uint32_t head = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&A.ctl[5]));
-    if (head >= tail) return false;
+    if (head >= tail) return AUT_HQ_EMPTY;
     uint32_t got = 0;
     if (lane == 0) got = atomicCAS(&A.ctl[5], head, head + 1u) == head ? 1u : 0u;
-    if (!__builtin_amdgcn_readfirstlane((int)got)) return true;            // another wavefront took it: look again
+    if (!__builtin_amdgcn_readfirstlane((int)got)) return AUT_HQ_AGAIN;
     uint32_t e = 0;
     for (int tries = 0; tries < AUT_SPIN_LIMIT; tries++) {    // the entry is written right after its place was handed out
         e = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&A.hq[head]));
         if (e & HQ_VALID) break;
         __builtin_amdgcn_s_sleep(1);
     }
-    if (!(e & HQ_VALID)) return true;                        // cannot happen: places below the end of the queue are always filled
-    aut_resolve(T, B, A, sc_w, sc_o, sc_h, sc_cap, (e & ~HQ_VALID) >> 8, e & 0xFFu, lane);
-    steps++;
-    return true;
+    if (!(e & HQ_VALID)) return AUT_HQ_AGAIN;                // cannot happen: places below the end of the queue are always filled
+    s = (e & ~HQ_VALID) >> 8;
+    cl = e & 0xFFu;
+    return AUT_HQ_GOT;
 }
 
 __host__ __device__ inline uint32_t aut_round16(uint32_t x) { return (x + 15u) & ~15u; }
@@ -488,7 +488,7 @@ __host__ __device__ inline uint32_t aut_round16(uint32_t x) { return (x + 15u) &
 // swallows whole are valid at once), lists the strings that need the parser, and its wavefronts
 // take the list in batches of 64 strings, one lane per string.  The verdicts of a slice are
 // collected in LDS and stored once: no atomics on global memory and nothing to clear beforehand.
-template <int MODE>
+template <int MODE, bool WIDE>
 __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
     extern __shared__ __align__(16) uint8_t smem[];
     const DeviceTables &D = a.tab;
@@ -524,7 +524,7 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
     uint32_t *cslice = reinterpret_cast<uint32_t *>(smem + off); off += AUT_SUB_WORDS * 4;
     uint8_t *pairs = smem + off; off += AUT_SUB_WORDS / 2;   // slots of the word pairs that hold undecided strings
     A.arena = reinterpret_cast<uint2 *>(smem + off); off += aut_round16(A.arena_cap * 8);
-    uint32_t *sc_w = reinterpret_cast<uint32_t *>(smem + off) + (size_t)wave * (2 * sc_cap + aut_hash_places(sc_cap));
+    uint32_t *sc_w = reinterpret_cast<uint32_t *>(smem + off) + (size_t)wave * (2 * sc_cap + (WIDE ? aut_hash_places(sc_cap) : 0u));   // the hash table belongs to the wide byte step
     uint32_t *sc_o = sc_w + sc_cap, *sc_h = sc_o + sc_cap;
     // the row's chart: its LDS copy when it is small, else global memory (generic pointers either way)
     const RowChart rc = a.rows[row];
@@ -604,18 +604,20 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
         }
         const BaseG B{b_so, b_it, rc.n_sets, b_so[rc.n_sets - 1], rc.n_items};
         if (j0 == 0 && wave == AUT_WAVES - 1)                // meanwhile the last wavefront settles the dead transitions of the row's current set
-            aut_mark_dead(T, A, [&](uint32_t i) { return B.it[B.last_lo + i].x; }, B.last_hi - B.last_lo, 0u, lane);
+            aut_mark_dead<WIDE>(T, A, [&](uint32_t i) { return B.it[B.last_lo + i].x; }, B.last_hi - B.last_lo, 0u, lane);
         __syncthreads();
         const uint32_t n_pairs = A.ctl[3];
-        // ---- one lane per string through the automaton, 64 neighbouring ranks at a time ----
+        // ---- one lane per string through the automaton, 64 neighbouring ranks at a time.  A wavefront that finds
+        // no batch left stays in the same loop (the byte step is expanded in one place only) and serves the
+        // help queue until every batch of the block is finished ----
         for (;;) {
             uint32_t b = 0;
             if (lane == 0) b = atomicAdd(&A.ctl[2], 1u);
             b = (uint32_t)__builtin_amdgcn_readfirstlane((int)b);
-            if (b >= n_pairs) break;
-            const uint32_t pair = pairs[b];
+            const bool batch = b < n_pairs;
+            const uint32_t pair = batch ? pairs[b] : 0u;
             const uint32_t rank = word_of(2 * pair) * 32u + lane;            // a pair lies inside one group: consecutive ranks
-            bool live = (cslice[2 * pair + (lane >> 5)] >> (lane & 31u)) & 1u;
+            bool live = batch && ((cslice[2 * pair + (lane >> 5)] >> (lane & 31u)) & 1u);
             uint32_t soff = 0, len = 0;
             Str16 c16{{0, 0, 0, 0}};
             if (live) { soff = D.str_off[rank]; len = D.str_off[rank + 1] - soff; c16 = D.str16[rank]; }
@@ -623,49 +625,68 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
             uint32_t s = 0, pos = 0, c = 0, spins = 0, t = AT_BUSY;
             bool ok = false, fail = false;
             for (;;) {
-                while (live) {                               // every lane follows its own string as far as the table goes
-                    if (pos < 16u) {
-                        const uint32_t q = pos >> 2;
-                        const uint32_t word = q == 0 ? c16.w[0] : (q == 1 ? c16.w[1] : (q == 2 ? c16.w[2] : c16.w[3]));
-                        c = (word >> ((pos & 3u) * 8u)) & 0xFFu;
-                    } else c = D.str_cls[soff + pos];
-                    t = lds_load(&A.trans[s * A.ncls + c]);
-                    if (t < AT_FAIL) { s = t; pos++; if (pos == len) { ok = true; live = false; } }
-                    else if (t == AT_DEAD) live = false;
-                    else if (t == AT_SINK) { ok = pos + 1 == len; live = false; }
-                    else if (t == AT_FAIL) { fail = true; live = false; }
-                    else break;                              // not there yet
-                }
-                const unsigned long long pend = __ballot(live);
-                if (!pend) break;
-                // Every waiting lane tries to claim the transition it misses, all at once (among lanes that miss
-                // the same one, one wins).  The first claim is computed here, the others are left in the
-                // help queue for wavefronts that have nothing to do.
-                uint32_t old = AT_BUSY;                      // lanes that found the transition being computed need not ask again
-                if (live && t == AT_NONE) old = atomicCAS(&A.trans[s * A.ncls + c], (uint32_t)AT_NONE, (uint32_t)AT_BUSY);
-                const unsigned long long won = __ballot(live && old == AT_NONE);
-                const bool progress = won != 0 || __ballot(live && old != AT_NONE && old != AT_BUSY) != 0;   // claimed, or published meanwhile
-                if (won) {
-                    const int first = __ffsll((long long)won) - 1;
-                    const unsigned long long rest = won & ~(1ull << first);
-                    if (rest) {
-                        uint32_t at = 0;
-                        if (lane == 0) at = atomicAdd(&A.ctl[4], (uint32_t)__popcll(rest));
-                        at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
-                        if ((rest >> lane) & 1ull) {
-                            const uint32_t k = at + (uint32_t)__popcll(rest & ((1ull << lane) - 1ull));
-                            if (k < (uint32_t)AUT_HELP_QUEUE) lds_store(&A.hq[k], HQ_VALID | (s << 8) | c);
-                            else lds_store(&A.trans[s * A.ncls + c], (uint32_t)AT_NONE);   // no room in the queue: the claim is given back
-                        }
+                bool have = false, progress = false;         // a transition to compute here; something this wavefront waits for has moved
+                uint32_t rs = 0, rc = 0;
+                if (batch) {
+                    while (live) {                           // every lane follows its own string as far as the table goes
+                        if (pos < 16u) {
+                            const uint32_t q = pos >> 2;
+                            const uint32_t word = q == 0 ? c16.w[0] : (q == 1 ? c16.w[1] : (q == 2 ? c16.w[2] : c16.w[3]));
+                            c = (word >> ((pos & 3u) * 8u)) & 0xFFu;
+                        } else c = D.str_cls[soff + pos];
+                        t = lds_load(&A.trans[s * A.ncls + c]);
+                        if (t < AT_FAIL) { s = t; pos++; if (pos == len) { ok = true; live = false; } }
+                        else if (t == AT_DEAD) live = false;
+                        else if (t == AT_SINK) { ok = pos + 1 == len; live = false; }
+                        else if (t == AT_FAIL) { fail = true; live = false; }
+                        else break;                          // not there yet
                     }
-                    aut_resolve(T, B, A, sc_w, sc_o, sc_h, sc_cap, (uint32_t)__builtin_amdgcn_readlane((int)s, first), (uint32_t)__builtin_amdgcn_readlane((int)c, first), lane);
-                    steps++;
+                    if (!__ballot(live)) break;
+                    // Every waiting lane tries to claim the transition it misses, all at once (among lanes that miss
+                    // the same one, one wins).  The first claim is computed here, the others are left in the
+                    // help queue for wavefronts that have nothing to do.
+                    uint32_t old = AT_BUSY;                  // lanes that found the transition being computed need not ask again
+                    if (live && t == AT_NONE) old = atomicCAS(&A.trans[s * A.ncls + c], (uint32_t)AT_NONE, (uint32_t)AT_BUSY);
+                    const unsigned long long won = __ballot(live && old == AT_NONE);
+                    progress = won != 0 || __ballot(live && old != AT_NONE && old != AT_BUSY) != 0;   // claimed, or published meanwhile
+                    if (won) {
+                        const int first = __ffsll((long long)won) - 1;
+                        const unsigned long long rest = won & ~(1ull << first);
+                        if (rest) {
+                            uint32_t at = 0;
+                            if (lane == 0) at = atomicAdd(&A.ctl[4], (uint32_t)__popcll(rest));
+                            at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+                            if ((rest >> lane) & 1ull) {
+                                const uint32_t k = at + (uint32_t)__popcll(rest & ((1ull << lane) - 1ull));
+                                if (k < (uint32_t)AUT_HELP_QUEUE) lds_store(&A.hq[k], HQ_VALID | (s << 8) | c);
+                                else lds_store(&A.trans[s * A.ncls + c], (uint32_t)AT_NONE);   // no room in the queue: the claim is given back
+                            }
+                        }
+                        have = true;
+                        rs = (uint32_t)__builtin_amdgcn_readlane((int)s, first);
+                        rc = (uint32_t)__builtin_amdgcn_readlane((int)c, first);
+                    }
                 }
-                if (!progress && !aut_help(T, B, A, sc_w, sc_o, sc_h, sc_cap, lane, steps)) {   // everything this wavefront waits for is being computed by others
+                int q = AUT_HQ_EMPTY;
+                if (!have && !progress) {                    // nothing of its own to compute: lend a hand
+                    q = aut_help_take(A, lane, rs, rc);
+                    have = q == AUT_HQ_GOT;
+                }
+                if (have) {
+                    aut_resolve<WIDE>(T, B, A, sc_w, sc_o, sc_h, sc_cap, rs, rc, lane);
+                    steps++;
+                    if (!batch) spins = 0;
+                } else if (!progress && q == AUT_HQ_EMPTY) { // everything this wavefront waits for is being computed by others
+                    if (!batch && (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&A.ctl[6])) >= n_pairs) break;   // all batches finished, nothing queued
                     __builtin_amdgcn_s_sleep(4);
-                    if (++spins > (uint32_t)AUT_SPIN_LIMIT) { fail = fail || live; live = false; }   // bounded wait: hand the strings to the fallback
+                    if (++spins > (uint32_t)AUT_SPIN_LIMIT) {   // bounded wait: hand the strings to the fallback
+                        if (!batch) break;
+                        fail = fail || live;
+                        live = false;
+                    }
                 }
             }
+            if (!batch) break;
             if (lane == 0) atomicAdd(&A.ctl[6], 1u);
             const unsigned long long okb = __ballot(ok);     // this wavefront is the only one that touches the pair's two words
             if (lane == 0 && okb) { vslice[2 * pair] |= (uint32_t)okb; vslice[2 * pair + 1] |= (uint32_t)(okb >> 32); }
@@ -686,12 +707,6 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
                 }
             }
         }
-        // out of strings: serve the help queue until every batch of the block is finished
-        for (uint32_t idle = 0; (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&A.ctl[6])) < n_pairs && idle < (uint32_t)AUT_SPIN_LIMIT;) {
-            if (aut_help(T, B, A, sc_w, sc_o, sc_h, sc_cap, lane, steps)) idle = 0;
-            else { __builtin_amdgcn_s_sleep(4); idle++; }
-        }
-        while (aut_help(T, B, A, sc_w, sc_o, sc_h, sc_cap, lane, steps)) {}       // nothing may stay marked as being computed
         __syncthreads();
         if (tid < AUT_SUB_WORDS) { const uint32_t w = word_of(tid); if (w < Wr) a.rank_mask[(size_t)row * Wr + w] = vslice[tid]; }
     }
@@ -704,22 +719,31 @@ hipError_t prepare_automaton_kernels() {
     const int max_lds = 160 * 1024;
     hipError_t e;
 #define SET_ATTR(k) if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k), hipFuncAttributeMaxDynamicSharedMemorySize, max_lds)) != hipSuccess) return e
-    SET_ATTR(mask_automaton_kernel<0>); SET_ATTR(mask_automaton_kernel<1>); SET_ATTR(mask_automaton_kernel<2>);
+    SET_ATTR((mask_automaton_kernel<0, false>)); SET_ATTR((mask_automaton_kernel<1, false>)); SET_ATTR((mask_automaton_kernel<2, false>));
+    SET_ATTR((mask_automaton_kernel<0, true>)); SET_ATTR((mask_automaton_kernel<1, true>)); SET_ATTR((mask_automaton_kernel<2, true>));
 #undef SET_ATTR
     return hipSuccess;
 }
 
-uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int arena, int scratch, int base_sets, int base_items) {
+uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int arena, int scratch, int base_sets, int base_items, bool wide) {
     return table_bytes(t, mode) + aut_round16((uint32_t)states * (uint32_t)t.n_cls * 4) + aut_round16((uint32_t)states * 8) + aut_round16((uint32_t)states * 4) + 32 + AUT_HELP_QUEUE * 4 +
            aut_round16(((uint32_t)base_sets + 1) * 4) + aut_round16((uint32_t)base_items * 8) + AUT_ENT_LDS * 4 + 256 + 2 * AUT_SUB_WORDS * 4 + AUT_SUB_WORDS / 2 + aut_round16((uint32_t)arena * 8) +
-           AUT_WAVES * ((uint32_t)scratch * 8 + aut_hash_places((uint32_t)scratch) * 4);
+           AUT_WAVES * ((uint32_t)scratch * 8 + (wide ? aut_hash_places((uint32_t)scratch) * 4 : 0u));
 }
 hipError_t launch_mask_automaton(const MaskArgs &a, hipStream_t s) {
-    const uint32_t lds = automaton_lds_bytes(a.tab, a.mode, a.aut_states, a.aut_arena, a.aut_scratch, a.aut_base_sets, a.aut_base_items);
+    const uint32_t lds = automaton_lds_bytes(a.tab, a.mode, a.aut_states, a.aut_arena, a.aut_scratch, a.aut_base_sets, a.aut_base_items, a.aut_wide != 0);
     dim3 grid(a.aut_parts, a.batch);
-    if (a.mode == 0) hipLaunchKernelGGL(mask_automaton_kernel<0>, grid, dim3(AUT_BLOCK), lds, s, a);
-    else if (a.mode == 1) hipLaunchKernelGGL(mask_automaton_kernel<1>, grid, dim3(AUT_BLOCK), lds, s, a);
-    else hipLaunchKernelGGL(mask_automaton_kernel<2>, grid, dim3(AUT_BLOCK), lds, s, a);
+    // two builds of the kernel: without the wide variant of the byte step (its code costs the narrow path ~10 %
+    // in registers and instruction fetch) for charts whose sets are all small, and with it
+    if (a.aut_wide) {
+        if (a.mode == 0) hipLaunchKernelGGL((mask_automaton_kernel<0, true>), grid, dim3(AUT_BLOCK), lds, s, a);
+        else if (a.mode == 1) hipLaunchKernelGGL((mask_automaton_kernel<1, true>), grid, dim3(AUT_BLOCK), lds, s, a);
+        else hipLaunchKernelGGL((mask_automaton_kernel<2, true>), grid, dim3(AUT_BLOCK), lds, s, a);
+    } else {
+        if (a.mode == 0) hipLaunchKernelGGL((mask_automaton_kernel<0, false>), grid, dim3(AUT_BLOCK), lds, s, a);
+        else if (a.mode == 1) hipLaunchKernelGGL((mask_automaton_kernel<1, false>), grid, dim3(AUT_BLOCK), lds, s, a);
+        else hipLaunchKernelGGL((mask_automaton_kernel<2, false>), grid, dim3(AUT_BLOCK), lds, s, a);
+    }
     return hipGetLastError();
 }
 }  // namespace zf
