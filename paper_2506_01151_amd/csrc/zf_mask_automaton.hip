@@ -404,7 +404,7 @@ __device__ __forceinline__ uint32_t aut_transition(const TV &T, const BaseT &B, 
     const uint2 *src_p;
     uint32_t src_n;
     S.view(cur, src_p, src_n);
-    int st = WIDE && src_n > 32u ? AUT_WIDE : aut_step_narrow<WIDE>(T, S, sc_w, sc_o, sc_cap, cur, byte, cl, lane, nnew, kept);   // a wide source set rarely leaves a narrow one
+    int st = WIDE && src_n > (uint32_t)AUT_NARROW_SET_MAX ? AUT_WIDE : aut_step_narrow<WIDE>(T, S, sc_w, sc_o, sc_cap, cur, byte, cl, lane, nnew, kept);   // a wide source set rarely leaves a narrow one
     if (st == AUT_WIDE) st = WIDE ? aut_step_wide(T, S, sc_w, sc_o, sc_h, sc_cap, cur, byte, cl, lane, nnew, kept) : (int)AUT_OVER;
     if (st != AUT_OK) return AT_FAIL;
     if (nnew == 0) return AT_DEAD;
