@@ -131,7 +131,13 @@ int zf_advance_bytes(zf_state *s, const uint8_t *bytes /* host */, int64_t n);
  * row b is advanced by token_ids[b], or reset to the empty prefix when token_ids[b] < 0.
  * states and token_ids are host arrays of n entries; status (host, n entries, may be null)
  * receives each row's return code.  Every row is processed; the return value is the first
- * code that is not ZF_OK.  A rejected row is left unchanged, as with zf_advance. */
+ * code that is not ZF_OK (zf_last_error then holds the text of the first failing row).  A
+ * rejected row is left unchanged, as with zf_advance; a null state fails the whole call with
+ * ZF_ERR_INVALID_ARG before any row is touched.  A state named twice is fed twice, in order.
+ * Rows are independent, so when the batch is expensive to feed (wide Earley sets of an ambiguous
+ * grammar) its rows are dealt to worker threads that the library starts on first need and keeps
+ * (at most 15; a forked child process feeds its rows on the calling thread); small batches
+ * never leave the caller's thread.  The call returns when every row is done. */
 int zf_advance_batch(zf_state *const *states, const int32_t *token_ids, int32_t n, int32_t *status);
 int zf_is_accepting(const zf_state *s, int32_t *out); /* is the prefix a sentence of the grammar? */
 int zf_state_stats(const zf_state *s, zf_stats *out);
