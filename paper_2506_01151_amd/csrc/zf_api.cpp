@@ -766,24 +766,31 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
             most_items = std::max<size_t>(most_items, c.set_off[c.n_sets()]);
             for (uint32_t k = 0; k < c.n_sets(); k++) biggest_set = std::max<size_t>(biggest_set, c.set_off[k + 1] - c.set_off[k]);
         }
-        int scratch = e->lane_cap_auto ? (int)std::min<size_t>(LANE_CAP_MAX, (4 * widest + 128 + 31) / 32 * 32) : e->opt.lane_item_cap;
-        int n_states = AUT_STATES_DEFAULT, arena = std::max(1024, 8 * scratch);
-        int base_sets = BASE_SETS_LDS, base_items = BASE_ITEMS_LDS;
-        const bool wide = biggest_set > (size_t)AUT_NARROW_SET_MAX;
+        int scratch = 0, n_states = 0, arena = 0, base_sets = 0, base_items = 0;
+        // The build without the wide byte step also takes the chart from LDS only (its pointers are then
+        // known to be LDS addresses): it serves calls whose sets are all small and whose charts all fit.
+        bool wide = biggest_set > (size_t)AUT_NARROW_SET_MAX;
         const uint32_t lds_max = 160u * 1024u;
-        auto lds_now = [&]() { return automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch, base_sets, base_items, wide); };
-        while (lds_now() > lds_max && arena > 2 * scratch) arena /= 2;
-        while (lds_now() > lds_max && n_states > 8) n_states /= 2;
-        while (lds_now() > lds_max && scratch > 32) { scratch /= 2; arena = std::max(arena / 2, 2 * scratch); }
-        if (lds_now() > lds_max) return fail(ZF_ERR_INVALID_ARG, "the grammar tables leave no LDS for the mask automaton");
-        // the rows' charts are read over and over by Complete: keep them in LDS too when the longest one fits in what is left
-        if (most_sets > (size_t)BASE_SETS_LDS || most_items > (size_t)BASE_ITEMS_LDS) {
-            const int want_sets = (int)std::max<size_t>(BASE_SETS_LDS, (most_sets + 32) / 32 * 32 - 1);
-            const int want_items = (int)std::max<size_t>(BASE_ITEMS_LDS, (most_items + 63) / 64 * 64);
-            if (want_sets <= AUT_BASE_SETS_MAX && want_items <= AUT_BASE_ITEMS_MAX &&
-                automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch, want_sets, want_items, wide) <= lds_max) {
-                base_sets = want_sets; base_items = want_items;
+        for (;;) {
+            scratch = e->lane_cap_auto ? (int)std::min<size_t>(LANE_CAP_MAX, (4 * widest + 128 + 31) / 32 * 32) : e->opt.lane_item_cap;
+            n_states = AUT_STATES_DEFAULT; arena = std::max(1024, 8 * scratch);
+            base_sets = BASE_SETS_LDS; base_items = BASE_ITEMS_LDS;
+            auto lds_now = [&]() { return automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch, base_sets, base_items, wide); };
+            while (lds_now() > lds_max && arena > 2 * scratch) arena /= 2;
+            while (lds_now() > lds_max && n_states > 8) n_states /= 2;
+            while (lds_now() > lds_max && scratch > 32) { scratch /= 2; arena = std::max(arena / 2, 2 * scratch); }
+            if (lds_now() > lds_max) return fail(ZF_ERR_INVALID_ARG, "the grammar tables leave no LDS for the mask automaton");
+            // the rows' charts are read over and over by Complete: keep them in LDS too when the longest one fits in what is left
+            if (most_sets > (size_t)BASE_SETS_LDS || most_items > (size_t)BASE_ITEMS_LDS) {
+                const int want_sets = (int)std::max<size_t>(BASE_SETS_LDS, (most_sets + 32) / 32 * 32 - 1);
+                const int want_items = (int)std::max<size_t>(BASE_ITEMS_LDS, (most_items + 63) / 64 * 64);
+                if (want_sets <= AUT_BASE_SETS_MAX && want_items <= AUT_BASE_ITEMS_MAX &&
+                    automaton_lds_bytes(d->tab, d->mode, n_states, arena, scratch, want_sets, want_items, wide) <= lds_max) {
+                    base_sets = want_sets; base_items = want_items;
+                }
             }
+            if (wide || (most_sets <= (size_t)base_sets && most_items <= (size_t)base_items)) break;
+            wide = true;                                  // some chart stays in global memory: the other build
         }
         a.aut_states = n_states; a.aut_arena = arena; a.aut_scratch = scratch;
         a.aut_base_sets = base_sets; a.aut_base_items = base_items;

@@ -488,6 +488,10 @@ __host__ __device__ inline uint32_t aut_round16(uint32_t x) { return (x + 15u) &
 // swallows whole are valid at once), lists the strings that need the parser, and its wavefronts
 // take the list in batches of 64 strings, one lane per string.  The verdicts of a slice are
 // collected in LDS and stored once: no atomics on global memory and nothing to clear beforehand.
+// MODE: which grammar tables are staged in LDS (0 all, 1 the small ones, 2 none).  WIDE: the build that
+// holds the wide variant of the byte step and its hash table; the build without it is for charts whose
+// sets are all small (the host knows: it packs them), where a set of more than 64 items fails over to the
+// fallback pass.  Keeping the wide variant out of that build keeps the narrow path's registers and code small.
 template <int MODE, bool WIDE>
 __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
     extern __shared__ __align__(16) uint8_t smem[];
@@ -533,6 +537,10 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
     const uint32_t *g_ent = a.entries + rc.ent_base;
     const bool base_fits = rc.n_sets <= base_sets_cap && rc.n_items <= base_items_cap;
     const bool ent_fits = rc.n_ent <= AUT_ENT_LDS;
+    if (!WIDE && !(base_fits && ent_fits)) {                               // never launched like this; if it were, the call must fail loudly
+        if (tid == 0) atomicAdd(&a.counters[2], 1u);
+        return;
+    }
     uint32_t so_v = 0, ent_v = 0;
     uint2 it_v = make_uint2(0, 0);
     if (base_fits && tid <= rc.n_sets) so_v = g_so[tid];
@@ -554,9 +562,9 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
     for (uint32_t k = tid; k < A.states_cap; k += AUT_BLOCK) A.hdr[k] = make_uint2(0, 0xFFFFFFFFu);
     for (uint32_t k = tid; k < (uint32_t)AUT_HELP_QUEUE; k += AUT_BLOCK) A.hq[k] = 0;
     if (tid == 0) { A.ctl[0] = 1; A.ctl[1] = 0; A.ctl[4] = 0; A.ctl[5] = 0; }
-    const uint32_t *b_ent = ent_fits ? l_ent : g_ent;
-    const uint32_t *b_so = base_fits ? l_so : g_so;
-    const uint2 *b_it = base_fits ? l_it : g_it;
+    const uint32_t *b_ent = (!WIDE || ent_fits) ? l_ent : g_ent;   // without the wide step: sets of at most AUT_NARROW_SET_MAX items, so at most that many cache rows
+    const uint32_t *b_so = (!WIDE || base_fits) ? l_so : g_so;   // the build without the wide step is launched only when every chart fits:
+    const uint2 *b_it = (!WIDE || base_fits) ? l_it : g_it;      // its chart pointers are LDS addresses at compile time
     uint32_t steps = 0;
     const uint32_t cr = (uint32_t)D.chunk_ranks;
     // The words of the row's bitmap are dealt to the blocks in groups of AUT_GROUP_WORDS, round robin:
