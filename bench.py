@@ -26,8 +26,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic of one mask_automaton_kernel launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # scaled by a plain copy of known size (profiles/mask_automaton_kernel_cfg3_hbm_traffic.txt).  It describes the kernel
 # sources with the digest below; once they change the figure is reported as null until it is measured again.
-MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 3291100, "apply_bytes_per_launch": 8508700,
-                    "kernel_sources_sha256": "9f303f942e6d2fb70952b04af0c20c0b3a1c539e5da52c7c695b670059cab2fe"}
+MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 3268600, "apply_bytes_per_launch": 8508700,
+                    "kernel_sources_sha256": "ab261ea03da5cb7c9eb35b90647d0cdee731a7b933bccf63a90b260e6b368bc8"}
 
 
 def kernel_sources_digest():
