@@ -22,11 +22,14 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# instruction issue peak of the chip: 256 compute units x 4 SIMDs x one wavefront instruction per cycle x 2.4 GHz
+ISSUE_PEAK_GINST = 256 * 4 * 2.4
 
 # HBM traffic of one mask_automaton_kernel launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # scaled by a plain copy of known size (profiles/mask_automaton_kernel_cfg3_hbm_traffic.txt).  It describes the kernel
 # sources with the digest below; once they change the figure is reported as null until it is measured again.
-MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 3268600, "apply_bytes_per_launch": 8508700,
+# instructions_per_launch: SQ_INSTS of the same kernel and workload (profiles/mask_automaton_kernel_cfg3_sq_counters.txt).
+MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 3268600, "apply_bytes_per_launch": 8508700, "instructions_per_launch": 8735653,
                     "kernel_sources_sha256": "ab261ea03da5cb7c9eb35b90647d0cdee731a7b933bccf63a90b260e6b368bc8"}
 
 
@@ -316,6 +319,13 @@ def main():
                      "note": "integer work: lazily built automaton of Earley sets + table look-ups per string; bound by the latency of the "
                              "dependent chain of Earley byte steps a block has to take (a few microseconds each), far below the HBM roof; "
                              "the event pair also spans the dispatch gap before the kernel"},
+        # second view of the mask kernel: wavefront instructions issued per second against what the SIMDs could issue.  The
+        # kernel is neither: it waits (LDS round trips, transitions other wavefronts are computing); the fraction says how much.
+        "roofline_issue": {"bound": "alu", "kernel": kname, "unit": "G wavefront instructions/s", "peak": ISSUE_PEAK_GINST,
+                           "instructions": MEASURED_TRAFFIC["instructions_per_launch"] if traffic_ok else None,
+                           "achieved": MEASURED_TRAFFIC["instructions_per_launch"] / (main_ms * 1e-3) / 1e9 if traffic_ok else None,
+                           "frac": MEASURED_TRAFFIC["instructions_per_launch"] / (main_ms * 1e-3) / 1e9 / ISSUE_PEAK_GINST if traffic_ok else None,
+                           "note": "instruction count from the SQ_INSTS counter of the profiled run (null once the kernel sources change)"},
         "roofline_apply_mask": {"bound": "hbm", "kernel": "apply_mask_vec_kernel", "achieved": apply_bytes / (apply_ms * 1e-3) / 1e9,
                                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": apply_bytes / (apply_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                 "traffic": MEASURED_TRAFFIC["apply_bytes_per_launch"] if traffic_ok else None, "algorithmic_bytes": apply_bytes,
