@@ -105,8 +105,12 @@ typedef struct {               /* facts about the last zf_compute_mask, for repo
                                   automaton) or trie chunks that hold such strings (trie walk) */
     int64_t chart_bytes;       /* bytes uploaded for the last call */
     int32_t cache_hits, cache_misses; /* rows of the last call served from / added to the state cache */
-    float main_ms, fallback_ms, permute_ms; /* kernel durations from HIP events on the call's
-                                               stream; 0 unless zf_engine_set_profiling is on */
+    float main_ms, fallback_ms, permute_ms; /* durations from HIP events on the call's stream, 0 unless
+                                               zf_engine_set_profiling is on: main_ms the mask kernel;
+                                               permute_ms the closing kernel (fallback pass for what the
+                                               mask kernel listed + permutation into token order, and the
+                                               state cache's gather); fallback_ms always 0 (that pass has
+                                               no kernel of its own) */
     int32_t parser_steps;      /* Earley byte steps the mask-automaton kernel took in the last call (all blocks) */
     int32_t cache_rows;        /* token-mask-cache bitset rows merged in the last call (sum over its rows) */
 } zf_mask_report;
@@ -156,7 +160,7 @@ int zf_position_info(const zf_engine *e, int32_t position, int32_t *lhs, int32_t
  * stream); the call waits for its own kernels so that ZF_ERR_OVERFLOW can be reported. */
 int zf_compute_mask(zf_engine *e, zf_state *const *states /* host array */, int32_t batch,
                     uint32_t *d_mask, void *hip_stream);
-/* The same, without waiting: the kernels (the fallback pass included) are only enqueued on
+/* The same, without waiting: the kernels (the fallback pass is part of the last one) are only enqueued on
  * hip_stream, so that the caller's next launches (zf_apply_mask, the sampler) queue up right
  * behind them.  ZF_ERR_OVERFLOW, if any, is reported by zf_mask_wait, which synchronises the
  * stream.  At most 4 calls may be in flight between two zf_mask_wait calls; calls on one engine

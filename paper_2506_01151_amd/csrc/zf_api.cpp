@@ -159,8 +159,8 @@ int setup_device(zf_engine *e) {
     }
     if (walk_lds_bytes(T, d->mode, e->opt.lane_item_cap) > 160u * 1024u)
         return fail(ZF_ERR_INVALID_ARG, "lane_item_cap and the grammar tables do not fit the 160 KB of LDS");
-    HIP_TRY(hipMalloc((void **)&d->d_counters, 32));
-    HIP_TRY(hipMemset(d->d_counters, 0, 32));
+    HIP_TRY(hipMalloc((void **)&d->d_counters, 64));     // two sets of eight counters (see MaskArgs::counters)
+    HIP_TRY(hipMemset(d->d_counters, 0, 64));
     HIP_TRY(hipHostMalloc((void **)&d->h_status, 16 * DeviceSide::N_SLOTS, hipHostMallocDefault));
     memset(d->h_status, 0, 16 * DeviceSide::N_SLOTS);
     for (auto &ev : d->stage_done) HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
@@ -569,10 +569,9 @@ int zf_debug_host_mask_stats(zf_engine *e, const zf_state *s, uint32_t *mask, in
     return ZF_OK;
 }
 
-// Pack and upload the charts and enqueue the kernels of one compute_mask call.  wait = true: the
-// fallback pass is launched only if the walk reported overflow (one extra host round trip in that
-// rare case) and the call returns the final status; wait = false: the fallback pass is always
-// enqueued and the status is left for zf_mask_wait.
+// Pack and upload the charts and enqueue the kernels of one compute_mask call: upload, mask kernel,
+// closing kernel (fallback pass for what the mask kernel listed + permutation into token order),
+// gather when the state cache is on.  wait = true: also wait and return the final status.
 static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait) {
     if (!e || !states || batch <= 0 || batch > MAX_BATCH || !d_mask) return fail(ZF_ERR_INVALID_ARG, "bad argument (batch must be 1..4096)");
     DeviceSide *d = e->dev;
@@ -717,8 +716,8 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     a.user_mask = d_mask;
     a.user_batch = batch;
     a.handoff_in_permute = sc ? 0 : 1;
-    a.counters = d->d_counters + 4 * d->call_parity;
-    a.counters_next = d->d_counters + 4 * (d->call_parity ^ 1u);
+    a.counters = d->d_counters + 8 * d->call_parity;
+    a.counters_next = d->d_counters + 8 * (d->call_parity ^ 1u);
     d->call_parity ^= 1u;
     a.work = d->d_work;
     a.host_status = d->h_status + 4 * slot;
@@ -811,27 +810,13 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
     if (run_kernels && d->tab.n_chunks > 0) HIP_TRY(automaton ? launch_mask_automaton(a, stream) : launch_mask_walk(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));
-    if (run_kernels && !wait && d->tab.n_chunks > 0) HIP_TRY(launch_mask_fallback(a, stream));
-    if (prof) HIP_TRY(hipEventRecord(d->ev[2], stream));
-    if (run_kernels) HIP_TRY(launch_permute(a, stream));  // the call's last kernel also hands the counters to the host and clears the next call's
+    if (run_kernels) HIP_TRY(launch_finish(a, stream));   // fallback pass (if anything was listed) + permutation; also hands the counters to the host and clears the next call's
     if (sc) HIP_TRY(launch_gather(a, stream));            // every row's finished mask from its pool slot to the caller's tensor
     if (prof) HIP_TRY(hipEventRecord(d->ev[3], stream));
     HIP_TRY(hipEventRecord(d->stage_done[slot], stream));   // the staging slot is free again once this point of the stream is reached
     d->next_slot = (slot + 1) % DeviceSide::N_SLOTS;
     d->pending++;
     if (!wait) return ZF_OK;
-    HIP_TRY(hipStreamSynchronize(stream));
-    volatile uint32_t *st = d->h_status + 4 * slot;
-    if (st[0] && !st[2] && d->tab.n_chunks > 0) {
-        // rare: some chunks outgrew LDS.  Run the fallback pass on them and permute again.
-        if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));
-        HIP_TRY(launch_mask_fallback(a, stream));
-        if (prof) HIP_TRY(hipEventRecord(d->ev[2], stream));
-        HIP_TRY(launch_permute(a, stream));
-        if (sc) HIP_TRY(launch_gather(a, stream));
-        if (prof) HIP_TRY(hipEventRecord(d->ev[3], stream));
-        HIP_TRY(hipStreamSynchronize(stream));
-    }
     return zf_mask_wait(e, hip_stream);
 }
 
@@ -869,8 +854,8 @@ int zf_mask_wait(zf_engine *e, void *hip_stream) {
     }
     if (d->pending && d->profiling) {
         (void)hipEventElapsedTime(&d->report.main_ms, d->ev[0], d->ev[1]);
-        (void)hipEventElapsedTime(&d->report.fallback_ms, d->ev[1], d->ev[2]);
-        (void)hipEventElapsedTime(&d->report.permute_ms, d->ev[2], d->ev[3]);
+        d->report.fallback_ms = 0.f;                      // the fallback pass is part of the closing kernel
+        (void)hipEventElapsedTime(&d->report.permute_ms, d->ev[1], d->ev[3]);
     }
     d->pending = 0;
     if (unresolved) forget_cached_masks(d);               // masks written by the failed call must not be served from the cache

@@ -1,13 +1,13 @@
-// HIP kernels for gfx950 around the mask kernels: the upload of the packed charts, the rank-order ->
-// token-order bit permutation, the state cache's gather, and the logit-masking kernel.
+// HIP kernels for gfx950 around the mask kernels: the upload of the packed charts, the state cache's
+// gather, and the logit-masking kernel.
 //
 // Mask path.  The distinct vocabulary strings are numbered in sorted order (their rank); verdicts
 // are first produced in rank order.  The context-independent token-mask cache (Section 4.3) settles
 // most strings from the terminals of the row's current Earley set alone; the strings it leaves
 // undecided need the parser.  Two kernels can do that part (zf_options.walk_mode), both exact:
 // the mask automaton (zf_mask_automaton.hip, default) and the trie walk (zf_mask_walk.hip, which
-// also holds the exact fallback pass of both).  permute_kernel then brings the verdicts into
-// token order.
+// also holds finish_kernel: the exact fallback pass of both, and the permutation of the verdicts
+// into token order).
 #include <hip/hip_runtime.h>
 #include "zf_launch.h"
 
@@ -21,37 +21,12 @@ __global__ __launch_bounds__(256) void upload_kernel(const uint4 *__restrict__ s
     if (i < n16) dst[i] = src[i];
 }
 
-// Verdicts are produced in trie order; the caller wants bit v at word v >> 5.  One lane per
-// token looks its bit up and a wavefront ballot packs 64 of them into two words.
-static const int PERMUTE_ROWS = 4;    // rows one thread serves: a token's rank is looked up once for all of them
-__global__ __launch_bounds__(256) void permute_kernel(MaskArgs a) {
-    const DeviceTables &D = a.tab;
-    const uint32_t v = blockIdx.x * 256 + threadIdx.x, row0 = blockIdx.y * PERMUTE_ROWS;
-    if (a.handoff_in_permute && v < 4 && row0 == 0) {  // the last kernel of the call: hand the counters to the host, clear the next call's set
-        a.host_status[v] = a.counters[v];
-        a.counters_next[v] = 0;
-    }
-    uint32_t r = 0xFFFFFFFFu;
-    if (v < (uint32_t)D.V) r = D.rank_of[v];
-    const uint32_t n_rows = (uint32_t)a.batch - row0 < (uint32_t)PERMUTE_ROWS ? (uint32_t)a.batch - row0 : (uint32_t)PERMUTE_ROWS;
-    uint32_t word[PERMUTE_ROWS];
-#pragma unroll
-    for (int k = 0; k < PERMUTE_ROWS; k++)               // all rows' words are requested before the first one is used
-        word[k] = (r != 0xFFFFFFFFu && (uint32_t)k < n_rows) ? a.rank_mask[(size_t)(row0 + k) * D.Wr + (r >> 5)] : 0u;
-    const uint32_t lane = threadIdx.x & 63, w = v >> 5;
-#pragma unroll
-    for (int k = 0; k < PERMUTE_ROWS; k++) {
-        const unsigned long long b = __ballot((word[k] >> (r & 31)) & 1u);
-        if ((uint32_t)k < n_rows && (lane & 31) == 0 && w < (uint32_t)D.W) a.out_mask[(size_t)a.dst_row[row0 + k] * D.W + w] = (uint32_t)(b >> lane);
-    }
-}
-
 // State cache (Section 5.2): copy every row's finished mask from its pool slot to the caller's
 // tensor.  When the cache is on this is the call's last kernel.
 __global__ __launch_bounds__(256) void gather_kernel(MaskArgs a) {
     const uint32_t w = blockIdx.x * 256 + threadIdx.x, row = blockIdx.y, W = (uint32_t)a.tab.W;
-    if (w < 4 && row == 0) {
-        a.host_status[w] = a.counters[w];
+    if (w < 8 && row == 0) {
+        if (w < 4) a.host_status[w] = a.counters[w];
         a.counters_next[w] = 0;
     }
     if (w < W) a.user_mask[(size_t)row * W + w] = a.out_mask[(size_t)a.row_slot[row] * W + w];
@@ -118,12 +93,6 @@ hipError_t launch_upload(const void *pinned_src, void *dst, size_t bytes, hipStr
     hipLaunchKernelGGL(upload_kernel, dim3((n16 + 255) / 256), dim3(256), 0, s, (const uint4 *)pinned_src, (uint4 *)dst, n16);
     return hipGetLastError();
 }
-hipError_t launch_permute(const MaskArgs &a, hipStream_t s) {
-    dim3 grid((a.tab.V + 255) / 256, (a.batch + PERMUTE_ROWS - 1) / PERMUTE_ROWS);
-    hipLaunchKernelGGL(permute_kernel, grid, dim3(256), 0, s, a);
-    return hipGetLastError();
-}
-
 hipError_t launch_gather(const MaskArgs &a, hipStream_t s) {
     dim3 grid((a.tab.W + 255) / 256 > 0 ? (a.tab.W + 255) / 256 : 1, a.user_batch);
     hipLaunchKernelGGL(gather_kernel, grid, dim3(256), 0, s, a);

@@ -45,7 +45,8 @@ struct MaskArgs {
     uint32_t *user_mask;       // the caller's [user_batch][W] tensor (target of the gather)
     int32_t user_batch;
     int32_t handoff_in_permute; // 1: permute is the call's last kernel (state cache off), else the gather is
-    uint32_t *counters;        // [0] chunks passed to the fallback, [1] length of the work queue, [2] chunks nobody could resolve
+    uint32_t *counters;        // [0] chunks passed to the fallback, [1] length of the work queue, [2] chunks nobody could resolve,
+                               // [3] Earley byte steps, [4] fallback wavefronts that have finished; 8 words per set
     uint32_t *host_status;     // pinned host memory: this call's counters, written by its last kernel
     uint32_t *counters_next;   // the next call's counters: cleared by this call's last kernel (no separate memset)
     uint4 *work;               // queue of (row, chunk, undecided strings, -) that need the parser walk
@@ -79,8 +80,7 @@ hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s);
 uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int arena, int scratch, int base_sets, int base_items, bool wide);
 hipError_t launch_mask_automaton(const MaskArgs &a, hipStream_t s);
-hipError_t launch_mask_fallback(const MaskArgs &a, hipStream_t s);
-hipError_t launch_permute(const MaskArgs &a, hipStream_t s);
+hipError_t launch_finish(const MaskArgs &a, hipStream_t s);   // fallback pass (when anything was listed) + permutation into token order
 hipError_t launch_gather(const MaskArgs &a, hipStream_t s);
 hipError_t launch_apply_mask(const void *logits, void *out, int dtype, int batch, int64_t row_stride, int V, int W,
                              const uint32_t *mask, hipStream_t s);

@@ -1,5 +1,5 @@
 // Mask kernel, default (zf_options.walk_mode = 0): mask_automaton_kernel.  What does not fit its LDS budgets goes to
-// mask_fallback_kernel (zf_mask_walk.hip).
+// the fallback pass of the call's closing kernel (finish_kernel, zf_mask_walk.hip).
 #include "zf_kernel_common.h"
 
 namespace zf {

@@ -1,5 +1,5 @@
 // Mask kernels, trie walk: cache_merge_kernel + mask_walk_kernel (zf_options.walk_mode = 1) and
-// mask_fallback_kernel (the exact fallback of both mask kernels).
+// finish_kernel (the exact fallback pass of both mask kernels + the permutation into token order).
 //
 // The vocabulary trie is stored in preorder, so a depth-first walk is a linear scan in which a
 // dead subtree is left through the node's skip pointer and a shared prefix is scanned once.  A
@@ -13,7 +13,7 @@
 // the nests of short data-dependent loops of an Earley step then cost ~12,000 cycles per step per
 // wavefront because every loop level runs for its longest trip count over the 64 lanes.)  Grammar
 // tables are staged in LDS once per block.  What does not fit the LDS budgets repeats the walk in
-// mask_fallback_kernel, one wavefront per chunk, with the item list in a global-memory arena.
+// the fallback pass (part of finish_kernel), one wavefront per chunk, with the item list in a global-memory arena.
 #include "zf_kernel_common.h"
 
 namespace zf {
@@ -545,16 +545,15 @@ __global__ __launch_bounds__(WALK_BLOCK) __attribute__((amdgpu_waves_per_eu(6)))
 }
 
 // Fallback: one wavefront per chunk that outgrew LDS; same walk with the strip-wise step and the
-// item list in a global-memory arena.
-__global__ __launch_bounds__(64) void mask_fallback_kernel(MaskArgs a) {
+// item list in a global-memory arena.  Wavefront gw of n_waves takes entries gw, gw + n_waves, ... of the
+// n listed ones.
+__device__ __forceinline__ void fallback_wave(const MaskArgs &a, uint32_t gw, uint32_t n_waves, uint32_t n, uint32_t lane) {
     const DeviceTables &D = a.tab;
     TV T;
     stage_tables<2>(D, nullptr, T, 0, 1);
-    const uint32_t lane = threadIdx.x;
-    uint32_t n = a.counters[0];
-    if (n > a.overflow_cap) { if (blockIdx.x == 0 && lane == 0) atomicAdd(&a.counters[2], n - a.overflow_cap); n = a.overflow_cap; }
-    GlobalStore st{a.fb_items + (size_t)blockIdx.x * FB_ITEMS_PER_WAVE, a.fb_set_start + (size_t)blockIdx.x * (FB_DEPTH_MAX + 2), (uint32_t)a.fb_cap};
-    for (uint32_t e = blockIdx.x; e < n; e += gridDim.x) {
+    if (n > a.overflow_cap) { if (gw == 0 && lane == 0) atomicAdd(&a.counters[2], n - a.overflow_cap); n = a.overflow_cap; }
+    GlobalStore st{a.fb_items + (size_t)gw * FB_ITEMS_PER_WAVE, a.fb_set_start + (size_t)gw * (FB_DEPTH_MAX + 2), (uint32_t)a.fb_cap};
+    for (uint32_t e = gw; e < n; e += n_waves) {
         const uint4 ent = a.overflow_list[e];
         const BaseG B = global_base(a, ent.x);
         const uint32_t begin = D.chunk_begin[ent.y], end = D.chunk_end[ent.y];
@@ -572,6 +571,65 @@ __global__ __launch_bounds__(64) void mask_fallback_kernel(MaskArgs a) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
+
+// The closing kernel of a call: the fallback pass (rare) and the permutation of the verdicts from
+// string-rank order into token order, in one launch.  As a kernel of its own the fallback pass costs
+// 4.5 us per call even when its list is empty (a launch and two dependent loads), and with the mask
+// automaton almost every call leaves it empty.
+//   When the list is not empty, the wavefronts of the blocks with the lowest linear index (workgroups
+// are started in index order, so these are resident before any other) walk the listed chunks first
+// and count themselves off; every block then waits for that count before it reads the verdicts.  The
+// fallback wavefronts wait for nothing, so the wait ends; it is bounded all the same, and running
+// into the bound makes the call fail with ZF_ERR_OVERFLOW.
+//   Permutation: verdicts are produced in trie order, the caller wants bit v at word v >> 5.  One lane
+// per token and PERMUTE_ROWS rows looks the token's rank up once, and a wavefront ballot packs 64
+// verdicts into two words.
+static const int FINISH_BLOCK = 256;
+static const int FINISH_WAVES = FINISH_BLOCK / 64;
+static const int PERMUTE_ROWS = 4;
+static const uint32_t FINISH_SPIN_LIMIT = 1u << 21;   // polls of about 2 us each
+__global__ __launch_bounds__(FINISH_BLOCK) void finish_kernel(MaskArgs a) {
+    const DeviceTables &D = a.tab;
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    const uint32_t v = blockIdx.x * FINISH_BLOCK + tid, row0 = blockIdx.y * PERMUTE_ROWS;
+    uint32_t r = 0xFFFFFFFFu;
+    if (v < (uint32_t)D.V) r = D.rank_of[v];             // requested alongside the fallback count: it does not depend on it
+    const uint32_t n_over = a.counters[0];
+    if (n_over != 0) {
+        const uint32_t lin = blockIdx.y * gridDim.x + blockIdx.x, n_blocks = gridDim.x * gridDim.y;
+        const uint32_t fb_waves = n_blocks * FINISH_WAVES < (uint32_t)FB_WAVES ? n_blocks * FINISH_WAVES : (uint32_t)FB_WAVES;
+        const uint32_t gw = lin * FINISH_WAVES + (tid >> 6);
+        if (gw < fb_waves) {
+            fallback_wave(a, gw, fb_waves, n_over, lane);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // its verdict bits and error counts before its count
+            if (lane == 0) atomicAdd(&a.counters[4], 1u);
+        }
+        if (tid == 0) {
+            uint32_t spins = 0;
+            while (__hip_atomic_load(&a.counters[4], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < fb_waves) {
+                __builtin_amdgcn_s_sleep(64);
+                if (++spins > FINISH_SPIN_LIMIT) { atomicAdd(&a.counters[2], 1u); break; }
+            }
+        }
+        __syncthreads();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
+    if (v < 8 && row0 == 0 && a.handoff_in_permute) {      // the last kernel of the call: hand the counters to the host, clear the next call's set
+        if (v < 4) a.host_status[v] = __hip_atomic_load(&a.counters[v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        a.counters_next[v] = 0;
+    }
+    const uint32_t n_rows = (uint32_t)a.batch - row0 < (uint32_t)PERMUTE_ROWS ? (uint32_t)a.batch - row0 : (uint32_t)PERMUTE_ROWS;
+    uint32_t word[PERMUTE_ROWS];
+#pragma unroll
+    for (int k = 0; k < PERMUTE_ROWS; k++)               // all rows' words are requested before the first one is used
+        word[k] = (r != 0xFFFFFFFFu && (uint32_t)k < n_rows) ? a.rank_mask[(size_t)(row0 + k) * D.Wr + (r >> 5)] : 0u;
+    const uint32_t w = v >> 5;
+#pragma unroll
+    for (int k = 0; k < PERMUTE_ROWS; k++) {
+        const unsigned long long b = __ballot((word[k] >> (r & 31)) & 1u);
+        if ((uint32_t)k < n_rows && (lane & 31) == 0 && w < (uint32_t)D.W) a.out_mask[(size_t)a.dst_row[row0 + k] * D.W + w] = (uint32_t)(b >> lane);
     }
 }
 
@@ -619,8 +677,9 @@ hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s) {
     else hipLaunchKernelGGL(mask_walk_kernel<2>, grid, dim3(WALK_BLOCK), lds, s, a);
     return hipGetLastError();
 }
-hipError_t launch_mask_fallback(const MaskArgs &a, hipStream_t s) {
-    hipLaunchKernelGGL(mask_fallback_kernel, dim3(FB_WAVES), dim3(64), 0, s, a);
+hipError_t launch_finish(const MaskArgs &a, hipStream_t s) {
+    dim3 grid((a.tab.V + FINISH_BLOCK - 1) / FINISH_BLOCK, (a.batch + PERMUTE_ROWS - 1) / PERMUTE_ROWS);
+    hipLaunchKernelGGL(finish_kernel, grid, dim3(FINISH_BLOCK), 0, s, a);
     return hipGetLastError();
 }
 }  // namespace zf
