@@ -21,7 +21,7 @@ static const int TABLE_LDS_BUDGET = 56 * 1024;
 static const int AUT_WAVES = 8;            // wavefronts per block of the mask-automaton kernel
 static const int AUT_BLOCK = AUT_WAVES * 64;
 static const int AUT_SUB_WORDS = 128;      // words of the rank-ordered bitmap (32 strings each) a block merges and checks per pass ...
-static const int AUT_GROUP_WORDS = 8;      // ... taken from the row in groups of this many neighbouring words, dealt to the blocks round robin
+static const int AUT_GROUP_WORDS = 4;      // ... taken from the row in groups of this many neighbouring words (two batches of 64 ranks), dealt to the blocks round robin
 static const int AUT_ENT_LDS = 64;         // token-mask-cache rows of the row's current set kept in LDS (more are read from global memory)
 static_assert(AUT_NARROW_SET_MAX <= AUT_ENT_LDS, "the kernel build for small sets keeps all cache-row numbers of a row in LDS");
 static const int AUT_TABLE_LOADS = (TABLE_LDS_BUDGET + AUT_BLOCK * 16 - 1) / (AUT_BLOCK * 16);   // 16-byte pieces of the staged tables per thread
