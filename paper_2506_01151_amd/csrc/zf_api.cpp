@@ -630,9 +630,9 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
             row_slot[b] = found;
         }
     } else for (int b = 0; b < batch; b++) miss_rows.push_back((uint32_t)b);
-    // rows with a wide current set first: their chunks are the expensive ones, and work that starts early does not
-    // end up as the kernel's tail
-    std::stable_sort(miss_rows.begin(), miss_rows.end(), [&](uint32_t x, uint32_t y) {
+    // trie walk: rows with a wide current set first: their chunks are the expensive ones, and work that starts early does
+    // not end up as the kernel's tail (the mask automaton gives every row its own blocks: the order does not matter there)
+    if (e->opt.walk_mode == 1) std::stable_sort(miss_rows.begin(), miss_rows.end(), [&](uint32_t x, uint32_t y) {
         const Chart &cx = states[x]->chart, &cy = states[y]->chart;
         return cx.set_off[cx.n_sets()] - cx.set_off[cx.n_sets() - 1] > cy.set_off[cy.n_sets()] - cy.set_off[cy.n_sets() - 1];
     });
@@ -705,14 +705,19 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     }
     MaskArgs a{};
     a.tab = d->tab;
-    a.rows = (const RowChart *)((uint8_t *)d->d_chart + off_rows);
-    a.set_off = (const uint32_t *)((uint8_t *)d->d_chart + off_so);
-    a.items = (const Item *)((uint8_t *)d->d_chart + off_items);
-    a.entries = (const uint32_t *)((uint8_t *)d->d_chart + off_ent);
+    // Where the kernels read the packed charts: with the mask automaton and the state cache off, straight from the pinned
+    // staging slot (a block needs a few hundred bytes once; the copy to device memory would be a kernel of its own at the
+    // head of the call); else from the device copy that upload_kernel makes.
+    const bool direct = e->opt.walk_mode != 1 && !sc;
+    uint8_t *chart_base = direct ? (uint8_t *)d->h_stage[slot] : (uint8_t *)d->d_chart;
+    a.rows = (const RowChart *)(chart_base + off_rows);
+    a.set_off = (const uint32_t *)(chart_base + off_so);
+    a.items = (const Item *)(chart_base + off_items);
+    a.entries = (const uint32_t *)(chart_base + off_ent);
     a.rank_mask = d->d_rank_mask;
     a.out_mask = sc ? d->d_pool : d_mask;                 // with the state cache the rows are finished in their pool slots
-    a.dst_row = (const uint32_t *)((uint8_t *)d->d_chart + off_dst);
-    a.row_slot = (const uint32_t *)((uint8_t *)d->d_chart + off_rowslot);
+    a.dst_row = direct ? nullptr : (const uint32_t *)(chart_base + off_dst);   // null: row r of the launch is row r of the output (no state cache: every row runs)
+    a.row_slot = (const uint32_t *)(chart_base + off_rowslot);
     a.user_mask = d_mask;
     a.user_batch = batch;
     a.handoff_in_permute = sc ? 0 : 1;
@@ -804,7 +809,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     d->report.main_ms = d->report.fallback_ms = d->report.permute_ms = 0.f;
     d->report.overflow_chunks = d->report.walk_chunks = d->report.parser_steps = 0;
     // everything the host has to work out is done: enqueue the upload and the kernels back to back
-    HIP_TRY(launch_upload(d->h_stage[slot], d->d_chart, total, stream));
+    if (!direct) HIP_TRY(launch_upload(d->h_stage[slot], d->d_chart, total, stream));
     const bool run_kernels = nb > 0;
     if (run_kernels && d->tab.n_chunks > 0 && !automaton) HIP_TRY(launch_cache_merge(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));

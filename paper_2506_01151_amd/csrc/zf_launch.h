@@ -40,7 +40,7 @@ struct MaskArgs {
     const uint32_t *entries;   // shared array of token-mask-cache rows (see RowChart)
     uint32_t *rank_mask;       // [batch][Wr] verdicts in trie (rank) order
     uint32_t *out_mask;        // token-order rows: the caller's tensor, or the state cache's pool
-    const uint32_t *dst_row;   // [batch] row of out_mask that row r of this launch is written to
+    const uint32_t *dst_row;   // [batch] row of out_mask that row r of this launch is written to; null = row r
     const uint32_t *row_slot;  // [user_batch] pool slot that holds the finished mask of each of the caller's rows
     uint32_t *user_mask;       // the caller's [user_batch][W] tensor (target of the gather)
     int32_t user_batch;

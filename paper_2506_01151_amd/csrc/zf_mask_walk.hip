@@ -629,7 +629,7 @@ __global__ __launch_bounds__(FINISH_BLOCK) void finish_kernel(MaskArgs a) {
 #pragma unroll
     for (int k = 0; k < PERMUTE_ROWS; k++) {
         const unsigned long long b = __ballot((word[k] >> (r & 31)) & 1u);
-        if ((uint32_t)k < n_rows && (lane & 31) == 0 && w < (uint32_t)D.W) a.out_mask[(size_t)a.dst_row[row0 + k] * D.W + w] = (uint32_t)(b >> lane);
+        if ((uint32_t)k < n_rows && (lane & 31) == 0 && w < (uint32_t)D.W) a.out_mask[(size_t)(a.dst_row ? a.dst_row[row0 + k] : row0 + k) * D.W + w] = (uint32_t)(b >> lane);
     }
 }
 
