@@ -639,14 +639,23 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     const int nb = (int)miss_rows.size();                // rows that go through the kernels
     d->report.cache_hits = n_hits; d->report.cache_misses = sc ? nb : 0;
     // ---- upload: [RowChart x nb][set offsets][items][cache rows of the token-mask cache][dst slot x nb][row slot x batch] ----
-    size_t n_off = 0, n_items = 0, n_ent = 0;
+    size_t n_off = 0, n_items = 0, n_ent = 0, max_off = 0, max_items = 0, max_ent = 0;
     const bool use_cache = !e->opt.disable_token_mask_cache;
     for (int r = 0; r < nb; r++) {
         const Chart &c = states[miss_rows[r]]->chart;
+        const size_t last = c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1];
         n_off += c.set_off.size();
         n_items += c.items.size();
-        if (use_cache) n_ent += c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1];
+        if (use_cache) n_ent += last;
+        max_off = std::max(max_off, c.set_off.size()); max_items = std::max(max_items, c.items.size());
+        if (use_cache) max_ent = std::max(max_ent, last);
     }
+    // Mask automaton: when the rows' charts are of similar size each row's sections get the same room, so that a block
+    // can request its row's sets, items and cache rows without waiting for the row's header (one memory round trip
+    // instead of two; the round trip is over PCIe when the kernels read the staging slot directly).
+    const bool uniform = e->opt.walk_mode != 1 && nb > 0 &&
+                         (size_t)nb * (4 * max_off + 8 * max_items + 4 * max_ent) <= 2 * (4 * n_off + 8 * n_items + 4 * n_ent) + 4096;
+    if (uniform) { n_off = (size_t)nb * max_off; n_items = (size_t)nb * max_items; n_ent = (size_t)nb * max_ent; }
     auto align16 = [](size_t x) { return (x + 15) & ~(size_t)15; };
     const size_t off_rows = 0, off_so = align16(sizeof(RowChart) * nb), off_items = align16(off_so + 4 * n_off);
     const size_t off_ent = align16(off_items + sizeof(Item) * n_items);
@@ -680,15 +689,16 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
         for (int r = 0; r < nb; r++) {
             const Chart &c = states[miss_rows[r]]->chart;
             const std::vector<uint32_t> &k = packed[miss_rows[r]];
+            if (uniform) { so_at = (uint32_t)(r * max_off); it_at = (uint32_t)(r * max_items); en_at = (uint32_t)(r * max_ent); }
             rows[r] = RowChart{c.n_sets(), so_at, it_at, en_at, 0, (uint32_t)c.items.size(), {0, 0}};
             if (use_cache) rows[r].n_ent = current_set_entries(e->tab, c, ents + en_at);
+            n_cache_rows += rows[r].n_ent;
             en_at += rows[r].n_ent;
             memcpy(so + so_at, k.data() + 1, 4 * c.set_off.size());
             memcpy(dev_items + 2 * (size_t)it_at, k.data() + 1 + c.set_off.size(), 8 * c.items.size());
             so_at += (uint32_t)c.set_off.size(); it_at += (uint32_t)c.items.size();
             dst[r] = sc ? row_slot[miss_rows[r]] : miss_rows[r];
         }
-        n_cache_rows = en_at;
     }
     // ---- per-call device buffers ----
     const size_t need_rank = (size_t)std::max(nb, 1) * d->tab.Wr, need_ovf = 2 * (size_t)std::max(nb, 1) * d->tab.n_chunks;   // the automaton kernel may name a chunk in two entries
@@ -718,6 +728,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     a.out_mask = sc ? d->d_pool : d_mask;                 // with the state cache the rows are finished in their pool slots
     a.dst_row = direct ? nullptr : (const uint32_t *)(chart_base + off_dst);   // null: row r of the launch is row r of the output (no state cache: every row runs)
     a.row_slot = (const uint32_t *)(chart_base + off_rowslot);
+    a.so_stride = uniform ? (uint32_t)max_off : 0u; a.it_stride = uniform ? (uint32_t)max_items : 0u; a.ent_stride = uniform ? (uint32_t)max_ent : 0u;
     a.user_mask = d_mask;
     a.user_batch = batch;
     a.handoff_in_permute = sc ? 0 : 1;

@@ -38,6 +38,7 @@ struct MaskArgs {
     const uint32_t *set_off;   // shared CSR offsets of all rows' sets
     const Item *items;         // shared item array of all rows
     const uint32_t *entries;   // shared array of token-mask-cache rows (see RowChart)
+    uint32_t so_stride, it_stride, ent_stride;   // not 0: row r's sections start at r * stride in set_off / items / entries (every row has the same room)
     uint32_t *rank_mask;       // [batch][Wr] verdicts in trie (rank) order
     uint32_t *out_mask;        // token-order rows: the caller's tensor, or the state cache's pool
     const uint32_t *dst_row;   // [batch] row of out_mask that row r of this launch is written to; null = row r

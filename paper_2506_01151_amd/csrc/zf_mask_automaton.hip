@@ -530,7 +530,16 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
     A.arena = reinterpret_cast<uint2 *>(smem + off); off += aut_round16(A.arena_cap * 8);
     uint32_t *sc_w = reinterpret_cast<uint32_t *>(smem + off) + (size_t)wave * (2 * sc_cap + (WIDE ? aut_hash_places(sc_cap) : 0u));   // the hash table belongs to the wide byte step
     uint32_t *sc_o = sc_w + sc_cap, *sc_h = sc_o + sc_cap;
-    // the row's chart: its LDS copy when it is small, else global memory (generic pointers either way)
+    // the row's chart: its LDS copy when it is small, else global memory (generic pointers either way).  When every
+    // row has the same room in the upload (strides), the pieces are requested before the row's header is known.
+    uint32_t so_v = 0, ent_v = 0;
+    uint2 it_v = make_uint2(0, 0);
+    const bool strided = a.so_stride != 0;
+    if (strided) {
+        if (tid < a.so_stride && tid <= base_sets_cap) so_v = (a.set_off + (size_t)row * a.so_stride)[tid];
+        if (tid < a.it_stride && tid < base_items_cap) it_v = (reinterpret_cast<const uint2 *>(a.items) + (size_t)row * a.it_stride)[tid];
+        if (tid < a.ent_stride && tid < (uint32_t)AUT_ENT_LDS) ent_v = (a.entries + (size_t)row * a.ent_stride)[tid];
+    }
     const RowChart rc = a.rows[row];
     const uint32_t *g_so = a.set_off + rc.set_base;
     const uint2 *g_it = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
@@ -541,11 +550,11 @@ __global__ __launch_bounds__(AUT_BLOCK) void mask_automaton_kernel(MaskArgs a) {
         if (tid == 0) atomicAdd(&a.counters[2], 1u);
         return;
     }
-    uint32_t so_v = 0, ent_v = 0;
-    uint2 it_v = make_uint2(0, 0);
-    if (base_fits && tid <= rc.n_sets) so_v = g_so[tid];
-    if (base_fits && tid < rc.n_items) it_v = g_it[tid];
-    if (ent_fits && tid < rc.n_ent) ent_v = g_ent[tid];
+    if (!strided) {
+        if (base_fits && tid <= rc.n_sets) so_v = g_so[tid];
+        if (base_fits && tid < rc.n_items) it_v = g_it[tid];
+        if (ent_fits && tid < rc.n_ent) ent_v = g_ent[tid];
+    }
     const uint8_t rep_v = tid < A.ncls ? D.cls_rep[tid] : (uint8_t)0;
 #define ZF_STAGE_STORE(u) if (tid + (u) * AUT_BLOCK < n16) reinterpret_cast<uint4 *>(smem)[tid + (u) * AUT_BLOCK] = tb##u;
     ZF_STAGE_STORE(0) ZF_STAGE_STORE(1) ZF_STAGE_STORE(2) ZF_STAGE_STORE(3) ZF_STAGE_STORE(4) ZF_STAGE_STORE(5) ZF_STAGE_STORE(6)
