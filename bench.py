@@ -2,7 +2,7 @@
 """Benchmark of the per-decode-step vocabulary mask on one MI355X.
 
 A "step" is one pass of the whole hot path over one batch: advance every row by its next
-token (host Earley + ZapFormat compaction), compute_mask (chart pack + upload, mask-automaton
+token (host Earley + ZapFormat compaction), compute_mask (chart pack into a pinned slot the kernels read in place, mask-automaton
 kernel, closing kernel = fallback pass + bit permutation; enqueued with compute_mask_async), apply_mask on that
 step's logits, and mask_wait (stream synchronisation + deferred error check).  The token
 trajectory is fixed beforehand (tests/golden/trajectory_cfgN.txt, sampled by the CPU oracle;
@@ -29,8 +29,8 @@ ISSUE_PEAK_GINST = 256 * 4 * 2.4
 # scaled by a plain copy of known size (profiles/mask_automaton_kernel_cfg3_hbm_traffic.txt).  It describes the kernel
 # sources with the digest below; once they change the figure is reported as null until it is measured again.
 # instructions_per_launch: SQ_INSTS of the same kernel and workload (profiles/mask_automaton_kernel_cfg3_sq_counters.txt).
-MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 3938000, "apply_bytes_per_launch": 8508700, "instructions_per_launch": 8827589,
-                    "kernel_sources_sha256": "d6080c28e3fc9c28b43bc1dac040a6174dd647cc9eec0f671c613f95741ddf8d"}
+MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 3752200, "apply_bytes_per_launch": 8508600, "instructions_per_launch": 8822808,
+                    "kernel_sources_sha256": "7b2a996cd9e22239b4316380dff66186c6410ae311a0760997e44e4163dfd114"}
 
 
 def kernel_sources_digest():
