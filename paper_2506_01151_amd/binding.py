@@ -283,12 +283,21 @@ def advance(state: State, token_id: int):
     state.advance(token_id)
 
 
+def _current_stream(engine: Engine) -> int:
+    """Handle of torch's current stream on the engine's device (what the library enqueues on)."""
+    import torch
+    raw = getattr(torch._C, "_cuda_getCurrentRawStream", None)   # the same handle without building a Stream object
+    if raw is not None:
+        return raw(engine.info.device)
+    return torch.cuda.current_stream(engine.info.device).cuda_stream
+
+
 def compute_mask(engine: Engine, states, mask_tensor):
     """mask_tensor: torch int32 tensor [batch, W] on the engine's device (fully overwritten)."""
     import torch
     assert mask_tensor.is_cuda and mask_tensor.is_contiguous() and mask_tensor.dtype == torch.int32
     assert tuple(mask_tensor.shape) == (len(states), engine.W)
-    engine.compute_mask(states, mask_tensor.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    engine.compute_mask(states, mask_tensor.data_ptr(), _current_stream(engine))
     return mask_tensor
 
 
@@ -297,13 +306,12 @@ def compute_mask_async(engine: Engine, states, mask_tensor):
     import torch
     assert mask_tensor.is_cuda and mask_tensor.is_contiguous() and mask_tensor.dtype == torch.int32
     assert tuple(mask_tensor.shape) == (len(states), engine.W)
-    engine.compute_mask_async(states, mask_tensor.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    engine.compute_mask_async(states, mask_tensor.data_ptr(), _current_stream(engine))
     return mask_tensor
 
 
 def mask_wait(engine: Engine):
-    import torch
-    engine.mask_wait(torch.cuda.current_stream().cuda_stream)
+    engine.mask_wait(_current_stream(engine))
 
 
 def apply_mask(engine: Engine, logits, mask_tensor, out=None):
@@ -315,5 +323,5 @@ def apply_mask(engine: Engine, logits, mask_tensor, out=None):
         out = logits
     assert out.dtype == logits.dtype and out.shape == logits.shape and out.stride() == logits.stride()
     engine.apply_mask(logits.data_ptr(), out.data_ptr(), dtype, logits.shape[0], logits.stride(0),
-                      mask_tensor.data_ptr(), torch.cuda.current_stream().cuda_stream)
+                      mask_tensor.data_ptr(), _current_stream(engine))
     return out
