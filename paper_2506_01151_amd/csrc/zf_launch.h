@@ -29,7 +29,7 @@ static const int AUT_HELP_QUEUE = 512;     // transitions one block can leave fo
 static const int AUT_STATES_DEFAULT = 64;  // automaton states a block can hold (more when LDS allows and the grammar is small)
 static const int AUT_SPIN_LIMIT = 1 << 16; // polls of a transition another wavefront is computing before giving the strings to the fallback
 static const int FB_DEPTH_MAX = 256;
-static const int FB_WAVES = 512;           // wavefronts of the fallback grid
+static const int FB_WAVES = 512;           // wavefronts of the closing kernel that run the fallback pass (each has its own arena)
 static const int FB_ITEMS_PER_WAVE = 65536; // its arena in global memory: items per wavefront (256 MB in all)
 
 struct MaskArgs {
