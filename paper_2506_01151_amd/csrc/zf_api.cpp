@@ -826,7 +826,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
     if (run_kernels && d->tab.n_chunks > 0) HIP_TRY(automaton ? launch_mask_automaton(a, stream) : launch_mask_walk(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));
-    if (run_kernels) HIP_TRY(launch_finish(a, stream));   // fallback pass (if anything was listed) + permutation; also hands the counters to the host and clears the next call's
+    if (run_kernels) HIP_TRY(launch_finish(a, d->cus, stream));   // fallback pass (if anything was listed) + permutation; also hands the counters to the host and clears the next call's
     if (sc) HIP_TRY(launch_gather(a, stream));            // every row's finished mask from its pool slot to the caller's tensor
     if (prof) HIP_TRY(hipEventRecord(d->ev[3], stream));
     HIP_TRY(hipEventRecord(d->stage_done[slot], stream));   // the staging slot is free again once this point of the stream is reached

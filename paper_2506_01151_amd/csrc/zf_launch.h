@@ -81,7 +81,7 @@ hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s);
 uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int arena, int scratch, int base_sets, int base_items, bool wide);
 hipError_t launch_mask_automaton(const MaskArgs &a, hipStream_t s);
-hipError_t launch_finish(const MaskArgs &a, hipStream_t s);   // fallback pass (when anything was listed) + permutation into token order
+hipError_t launch_finish(const MaskArgs &a, int cus, hipStream_t s);   // fallback pass (when anything was listed) + permutation into token order
 hipError_t launch_gather(const MaskArgs &a, hipStream_t s);
 hipError_t launch_apply_mask(const void *logits, void *out, int dtype, int batch, int64_t row_stride, int V, int W,
                              const uint32_t *mask, hipStream_t s);
