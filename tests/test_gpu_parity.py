@@ -429,6 +429,42 @@ def test_many_rows_and_longest_token(mode, torch_cuda, oracle_lib):
         assert (got[r] == so[r].mask(off, data, 4)).all(), r
 
 
+@pytest.mark.parametrize("cap", [None, 1], ids=["default-budget", "budget-1"])
+def test_ragged_vocabulary_many_rows_closing_kernel(cap, torch_cuda, oracle_lib):
+    """130 rows (a last group of two) over a vocabulary of 40,037 tokens (not a multiple of 32 or 64): the
+    closing kernel then serves long runs of tokens per block from LDS copies of the rows, and the last
+    block's run ends inside a mask word.  With an item budget of 1 most strings come back through the
+    fallback pass, the closing kernel's first phase, whose wavefronts the other blocks wait for."""
+    import paper_2506_01151_amd as zf
+    torch = torch_cuda
+    cfg = configs.CONFIGS[2]
+    g = cfg.grammar()
+    toks = cfg.vocab(40037)
+    off, data = wvocab.vocab_csr(toks)
+    orc = oracle_lib.Oracle(g)
+    kw = {} if cap is None else {"lane_item_cap": cap}
+    eng = zf.Engine(g, toks, device=0, state_cache_entries=-1, **kw)
+    rows = 130
+    rs = stream(cfg.seed, "ragged-rows")
+    pieces = [b"", b"[", b'{"a":', b'{"a": "', b"[1, 2", b'[{"k": [', b"tr", b'"abc', b"[[[", b'{"k":"v"', b"-1.5e", b'["\\u00', b"[1.0", b'{"k": nul']
+    so, ss = [], []
+    for r in range(rows):
+        p = pieces[rs.below(len(pieces))]
+        a, b = orc.new_state(), eng.new_state()
+        assert a.feed_bytes(p)
+        b.advance_bytes(p)
+        so.append(a)
+        ss.append(b)
+    d_mask = torch.full((rows, eng.W), -1, dtype=torch.int32, device="cuda")
+    zf.compute_mask(eng, ss, d_mask)
+    got = d_mask.cpu().numpy().view(np.uint32)
+    for r in range(rows):
+        assert (got[r] == so[r].mask(off, data, 8)).all(), r
+    assert got[:, -1].max() < (1 << (40037 % 32)), "padding bits of the last word must be zero"
+    if cap is not None:
+        assert eng.mask_report().overflow_chunks > 0
+
+
 @pytest.mark.parametrize("mode", list(MODES))
 @pytest.mark.parametrize("n_words,word_len,lds_mode", [(1500, 5, 1), (1500, 8, 2)])
 def test_grammar_tables_beyond_the_lds_budget(n_words, word_len, lds_mode, mode, torch_cuda, oracle_lib):
