@@ -3,6 +3,7 @@
 #include <hip/hip_runtime_api.h>
 #include <unistd.h>
 #include <algorithm>
+#include <chrono>
 #include <atomic>
 #include <condition_variable>
 #include <cstring>
@@ -31,7 +32,8 @@ struct DeviceSide {
     static const int N_SLOTS = 4;                    // calls that may be in flight before zf_mask_wait
     void *h_stage[N_SLOTS] = {nullptr, nullptr, nullptr, nullptr}; size_t stage_cap[N_SLOTS] = {0, 0, 0, 0};   // pinned
     hipEvent_t stage_done[N_SLOTS] = {nullptr, nullptr, nullptr, nullptr};   // the slot's upload has been consumed
-    uint32_t *h_status = nullptr;                    // pinned, [N_SLOTS][4]: counters written by each call's last kernel
+    uint32_t *h_status = nullptr;                    // pinned, [N_SLOTS][8]: counters [0..3] and the call's number [4], written by each call's last kernel
+    uint32_t call_seq = 0, last_seq = 0, last_slot = 0; // number of the newest call in flight and its slot
     uint32_t next_slot = 0, pending = 0;
     uint32_t occ_lds = 0;                            // LDS size the cached occupancy answer belongs to
     int occ_blocks = 1;
@@ -161,8 +163,8 @@ int setup_device(zf_engine *e) {
         return fail(ZF_ERR_INVALID_ARG, "lane_item_cap and the grammar tables do not fit the 160 KB of LDS");
     HIP_TRY(hipMalloc((void **)&d->d_counters, 64));     // two sets of eight counters (see MaskArgs::counters)
     HIP_TRY(hipMemset(d->d_counters, 0, 64));
-    HIP_TRY(hipHostMalloc((void **)&d->h_status, 16 * DeviceSide::N_SLOTS, hipHostMallocDefault));
-    memset(d->h_status, 0, 16 * DeviceSide::N_SLOTS);
+    HIP_TRY(hipHostMalloc((void **)&d->h_status, 32 * DeviceSide::N_SLOTS, hipHostMallocDefault));
+    memset(d->h_status, 0, 32 * DeviceSide::N_SLOTS);
     for (auto &ev : d->stage_done) HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
     HIP_TRY(hipMalloc((void **)&d->d_fb_items, (size_t)FB_ITEMS_PER_WAVE * FB_WAVES * sizeof(uint2)));
     HIP_TRY(hipMalloc((void **)&d->d_fb_ss, (size_t)(FB_DEPTH_MAX + 2) * FB_WAVES * sizeof(uint32_t)));
@@ -736,7 +738,9 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     a.counters_next = d->d_counters + 8 * (d->call_parity ^ 1u);
     d->call_parity ^= 1u;
     a.work = d->d_work;
-    a.host_status = d->h_status + 4 * slot;
+    a.host_status = d->h_status + 8 * slot;
+    if (++d->call_seq == 0) d->call_seq = 1;
+    a.seq = d->call_seq;
     a.overflow_list = d->d_overflow;
     a.overflow_cap = (uint32_t)d->overflow_cap;
     a.fb_items = d->d_fb_items;
@@ -832,7 +836,9 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     HIP_TRY(hipEventRecord(d->stage_done[slot], stream));   // the staging slot is free again once this point of the stream is reached
     d->next_slot = (slot + 1) % DeviceSide::N_SLOTS;
     d->pending++;
+    d->last_seq = a.seq; d->last_slot = slot;
     if (!wait) return ZF_OK;
+    HIP_TRY(hipStreamSynchronize(stream));               // the waiting call returns with the mask complete, not only its status known
     return zf_mask_wait(e, hip_stream);
 }
 
@@ -860,13 +866,34 @@ int zf_mask_wait(zf_engine *e, void *hip_stream) {
     if (!e || !e->dev) return fail(ZF_ERR_INVALID_ARG, "bad argument");
     DeviceSide *d = e->dev;
     HIP_TRY(hipSetDevice(d->device));
-    HIP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));
-    uint32_t unresolved = 0;
     volatile uint32_t *st = d->h_status;
+    if (d->pending) {
+        // The newest call's last kernel writes the call's number into pinned memory after its counters: poll that word
+        // instead of synchronising the stream (which also waits for whatever the caller queued behind the mask kernels,
+        // apply_mask for one, and wakes up microseconds later).  Calls of one engine run in stream order, so the older
+        // calls in flight have finished too.  Bounded: after two seconds the stream is synchronised, which also
+        // surfaces a device error.
+        volatile uint32_t *flag = st + 8 * d->last_slot + 4;
+        const auto t0 = std::chrono::steady_clock::now();
+        for (uint32_t spins = 0; *flag != d->last_seq; spins++) {
+            __builtin_ia32_pause();
+            if ((spins & 0xFFFu) == 0xFFFu && std::chrono::steady_clock::now() - t0 > std::chrono::seconds(2)) {
+                HIP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));
+                if (*flag != d->last_seq) return fail(ZF_ERR_DEVICE, "the mask kernels did not report back");
+                break;
+            }
+        }
+        std::atomic_thread_fence(std::memory_order_acquire);
+        if (d->profiling) HIP_TRY(hipEventSynchronize(d->ev[3]));
+    } else {
+        HIP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));   // nothing of this engine in flight: plain stream synchronisation
+    }
+    uint32_t unresolved = 0, overflowed = 0;
+    (void)overflowed;
     for (int k = 0; k < DeviceSide::N_SLOTS; k++) {
-        unresolved += st[4 * k + 2];
-        if (st[4 * k + 0] || st[4 * k + 1]) { d->report.overflow_chunks = st[4 * k + 0]; d->report.walk_chunks = st[4 * k + 1]; d->report.parser_steps = st[4 * k + 3]; }
-        st[4 * k + 0] = st[4 * k + 1] = st[4 * k + 2] = st[4 * k + 3] = 0;
+        unresolved += st[8 * k + 2];
+        if (st[8 * k + 0] || st[8 * k + 1]) { d->report.overflow_chunks = st[8 * k + 0]; d->report.walk_chunks = st[8 * k + 1]; d->report.parser_steps = st[8 * k + 3]; }
+        st[8 * k + 0] = st[8 * k + 1] = st[8 * k + 2] = st[8 * k + 3] = 0;
     }
     if (d->pending && d->profiling) {
         (void)hipEventElapsedTime(&d->report.main_ms, d->ev[0], d->ev[1]);

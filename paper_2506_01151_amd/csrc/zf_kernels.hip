@@ -25,11 +25,16 @@ __global__ __launch_bounds__(256) void upload_kernel(const uint4 *__restrict__ s
 // tensor.  When the cache is on this is the call's last kernel.
 __global__ __launch_bounds__(256) void gather_kernel(MaskArgs a) {
     const uint32_t w = blockIdx.x * 256 + threadIdx.x, row = blockIdx.y, W = (uint32_t)a.tab.W;
-    if (w < 8 && row == 0) {
-        if (w < 4) a.host_status[w] = a.counters[w];
-        a.counters_next[w] = 0;
-    }
     if (w < W) a.user_mask[(size_t)row * W + w] = a.out_mask[(size_t)a.row_slot[row] * W + w];
+    // the block that is started last hands the counters to the host and clears the next call's set (see finish_kernel)
+    if (blockIdx.x == gridDim.x - 1 && blockIdx.y == gridDim.y - 1) {
+        __syncthreads();
+        if (threadIdx.x < 8) a.counters_next[threadIdx.x] = 0;
+        if (threadIdx.x == 0) {                           // counters first, then the word the host waits for
+            for (int i = 0; i < 4; i++) a.host_status[i] = a.counters[i];
+            __hip_atomic_store(&a.host_status[4], a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
 }
 
 // Logit masking (Section 3.3): pure copy-or-(-inf).  16-byte accesses, consecutive lanes on

@@ -631,10 +631,6 @@ __global__ __launch_bounds__(FINISH_BLOCK) void finish_kernel(MaskArgs a, uint32
         __syncthreads();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
-    if (blockIdx.x == 0 && blockIdx.y == 0 && tid < 8 && a.handoff_in_permute) {   // the last kernel of the call: hand the counters to the host, clear the next call's set
-        if (tid < 4) a.host_status[tid] = __hip_atomic_load(&a.counters[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        a.counters_next[tid] = 0;
-    }
     const uint32_t *rows = a.rank_mask + (size_t)row0 * Wr;           // the block's rows are neighbours in memory
     if (STAGED) {
         const uint32_t n_words = n_rows * Wr, n16 = n_words / 4;
@@ -673,6 +669,17 @@ __global__ __launch_bounds__(FINISH_BLOCK) void finish_kernel(MaskArgs a, uint32
         }
 #pragma unroll
         for (int u = 0; u < AHEAD; u++) r_ahead[u] = r_next[u];
+    }
+    // The call's last kernel hands the counters to the host and clears the next call's set.  The block that is started
+    // last does it, at its end: by then nearly all of the grid has finished (the word the host polls says "the status is
+    // known"; consumers of the mask are ordered behind this kernel by the stream).
+    if (blockIdx.x == gridDim.x - 1 && blockIdx.y == gridDim.y - 1 && a.handoff_in_permute) {
+        __syncthreads();
+        if (tid < 8) a.counters_next[tid] = 0;
+        if (tid == 0) {                                   // counters first, then the word the host waits for
+            for (int i = 0; i < 4; i++) a.host_status[i] = __hip_atomic_load(&a.counters[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&a.host_status[4], a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
     }
 }
 
