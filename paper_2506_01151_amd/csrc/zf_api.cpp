@@ -888,8 +888,7 @@ int zf_mask_wait(zf_engine *e, void *hip_stream) {
     } else {
         HIP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));   // nothing of this engine in flight: plain stream synchronisation
     }
-    uint32_t unresolved = 0, overflowed = 0;
-    (void)overflowed;
+    uint32_t unresolved = 0;
     for (int k = 0; k < DeviceSide::N_SLOTS; k++) {
         unresolved += st[8 * k + 2];
         if (st[8 * k + 0] || st[8 * k + 1]) { d->report.overflow_chunks = st[8 * k + 0]; d->report.walk_chunks = st[8 * k + 1]; d->report.parser_steps = st[8 * k + 3]; }
