@@ -6,8 +6,13 @@ At every step each row draws its next token uniformly from the oracle-valid mask
 empty is reset (token id -1).  Only `oracle/` and `workloads/` are used here, so the files
 never depend on the HIP library.
 
-usage: python tests/golden/make_trajectories.py CFG [ROWS [STEPS]]
+The oracle keeps every Earley set, so on the ambiguous expression grammar a mask costs more
+with every step; `--budget-s` ends the run after that much wall time and the header states
+how many steps were reached and how long they took.
+
+usage: python tests/golden/make_trajectories.py CFG [ROWS [STEPS]] [--budget-s SECONDS] [--threads N]
 """
+import argparse
 import os
 import sys
 import time
@@ -18,27 +23,44 @@ from workloads import configs                  # noqa: E402
 from tests.helpers import OracleRun            # noqa: E402
 
 
+def write(path, cfg, rows, lines, seconds, threads, finished):
+    tmp = path + ".tmp"
+    with open(tmp, "w") as f:
+        f.write(f"# config {cfg.index} ({cfg.name}): V={cfg.V} rows={rows} steps={len(lines)} seed={cfg.seed}\n")
+        f.write("# one line per decode step: the token id fed to each row (-1 = the row was reset)\n")
+        f.write("# written by tests/golden/make_trajectories.py from the CPU oracle only\n")
+        f.write(f"# oracle wall time {seconds:.0f} s on {threads} threads" + ("" if finished else " (run still going or cut short)") + "\n")
+        f.write("\n".join(lines) + "\n")
+    os.replace(tmp, path)
+
+
 def main():
-    idx = int(sys.argv[1])
-    cfg = configs.CONFIGS[idx]
-    rows = int(sys.argv[2]) if len(sys.argv) > 2 else cfg.batch
-    steps = int(sys.argv[3]) if len(sys.argv) > 3 else cfg.steps
+    ap = argparse.ArgumentParser()
+    ap.add_argument("cfg", type=int)
+    ap.add_argument("rows", type=int, nargs="?")
+    ap.add_argument("steps", type=int, nargs="?")
+    ap.add_argument("--budget-s", type=float, default=0.0, help="stop after this much wall time (0 = run all steps)")
+    ap.add_argument("--threads", type=int, default=8)
+    ap.add_argument("--out", default=None)
+    a = ap.parse_args()
+    cfg = configs.CONFIGS[a.cfg]
+    rows = a.rows or cfg.batch
+    steps = a.steps or cfg.steps
     toks = cfg.vocab()
-    run = OracleRun(Oracle(cfg.grammar()), toks, [cfg.sampler(b) for b in range(rows)], n_threads=8)
-    out = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"trajectory_cfg{idx}.txt")
+    run = OracleRun(Oracle(cfg.grammar()), toks, [cfg.sampler(b) for b in range(rows)], n_threads=a.threads)
+    out = a.out or os.path.join(os.path.dirname(os.path.abspath(__file__)), f"trajectory_cfg{a.cfg}.txt")
     t0 = time.time()
     lines = []
     for step in range(steps):
         ids = run.step(run.masks())
         lines.append(" ".join(map(str, ids)))
-        if step % 16 == 0:
-            print(f"cfg{idx} step {step}/{steps} {time.time() - t0:.0f}s", flush=True)
-    with open(out, "w") as f:
-        f.write(f"# config {idx} ({cfg.name}): V={cfg.V} rows={rows} steps={steps} seed={cfg.seed}\n")
-        f.write("# one line per decode step: the token id fed to each row (-1 = the row was reset)\n")
-        f.write("# written by tests/golden/make_trajectories.py from the CPU oracle only\n")
-        f.write("\n".join(lines) + "\n")
-    print("wrote", out, f"{time.time() - t0:.0f}s resets={run.resets}")
+        if step % 8 == 7 or step == steps - 1:     # the file on disk is always a usable prefix
+            write(out, cfg, rows, lines, time.time() - t0, a.threads, step == steps - 1)
+            print(f"cfg{a.cfg} step {step + 1}/{steps} {time.time() - t0:.0f}s", flush=True)
+        if a.budget_s and time.time() - t0 > a.budget_s:
+            break
+    write(out, cfg, rows, lines, time.time() - t0, a.threads, True)
+    print("wrote", out, f"{len(lines)} steps {time.time() - t0:.0f}s resets={run.resets}")
 
 
 if __name__ == "__main__":
