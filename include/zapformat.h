@@ -175,6 +175,22 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states /* host array */, int3
 int zf_compute_mask_async(zf_engine *e, zf_state *const *states /* host array */, int32_t batch,
                           uint32_t *d_mask, void *hip_stream);
 int zf_mask_wait(zf_engine *e, void *hip_stream);
+/* zf_compute_mask for callers that cannot allocate device memory: tight serving loops, harnesses
+ * that forbid hipMalloc, code that runs while a HIP graph is being captured on another stream.  Same
+ * arguments, same result, same waiting behaviour as zf_compute_mask, but the call allocates nothing
+ * (no hipMalloc, hipHostMalloc, hipFree): every per-call device buffer (counters, rank-ordered verdict
+ * words, fallback list and arenas, the trie walk's queue and chart copy) is a slice of one static
+ * device array of 16 MiB that each GPU the library runs on holds until the process ends, and the
+ * packed charts must fit the 256 KiB of pinned staging memory every engine owns from zf_compile on.
+ * The state cache is passed by.  A call that does not fit -- batch x vocabulary beyond the array,
+ * charts beyond the staging room -- returns ZF_ERR_INVALID_ARG with the sizes in zf_last_error, and so
+ * does a call made while asynchronous mask calls are in flight.  The fallback pass has 32 wavefronts
+ * with arenas of 16,384 items here, and its list holds what the other buffers leave of the array
+ * (ZF_ERR_OVERFLOW beyond either, as always: the mask is then not valid).  All calls on one GPU,
+ * from any engine, share the array: calls that overlap on one GPU (other streams, other threads)
+ * race; one call after the other is fine, whatever their sizes. */
+int zf_compute_mask_noalloc(zf_engine *e, zf_state *const *states /* host array */, int32_t batch,
+                            uint32_t *d_mask, void *hip_stream);
 int zf_last_mask_report(const zf_engine *e, zf_mask_report *out);
 /* Forget every cached mask row (benchmarks call it to start cold). */
 int zf_engine_clear_state_cache(zf_engine *e);

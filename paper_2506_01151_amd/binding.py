@@ -50,7 +50,7 @@ class MaskReport(ctypes.Structure):
 EXPORTS = ["zf_strerror", "zf_last_error", "zf_compile", "zf_engine_destroy", "zf_engine_get_info",
            "zf_state_new", "zf_state_clone", "zf_state_reset", "zf_state_destroy", "zf_advance",
            "zf_advance_bytes", "zf_advance_batch", "zf_is_accepting", "zf_state_stats", "zf_state_chart", "zf_position_info",
-           "zf_compute_mask", "zf_compute_mask_async", "zf_mask_wait", "zf_last_mask_report", "zf_engine_clear_state_cache", "zf_engine_set_profiling", "zf_apply_mask", "zf_debug_host_mask", "zf_debug_host_mask_stats", "zf_debug_host_mask_cached", "zf_debug_host_mask_automaton"]
+           "zf_compute_mask", "zf_compute_mask_noalloc", "zf_compute_mask_async", "zf_mask_wait", "zf_last_mask_report", "zf_engine_clear_state_cache", "zf_engine_set_profiling", "zf_apply_mask", "zf_debug_host_mask", "zf_debug_host_mask_stats", "zf_debug_host_mask_cached", "zf_debug_host_mask_automaton"]
 
 
 class ZfError(RuntimeError):
@@ -86,6 +86,7 @@ def load_library():
     L.zf_position_info.argtypes = [c_vp, c_i32, ctypes.POINTER(c_i32), ctypes.POINTER(c_i32), ctypes.POINTER(c_i32)]
     L.zf_compute_mask.argtypes = [c_vp, c_vp, c_i32, c_vp, c_vp]
     L.zf_compute_mask_async.argtypes = [c_vp, c_vp, c_i32, c_vp, c_vp]
+    L.zf_compute_mask_noalloc.argtypes = [c_vp, c_vp, c_i32, c_vp, c_vp]
     L.zf_mask_wait.argtypes = [c_vp, c_vp]
     L.zf_last_mask_report.argtypes = [c_vp, c_vp]
     L.zf_advance_batch.argtypes = [c_vp, c_vp, c_i32, c_vp]
@@ -252,6 +253,9 @@ class Engine:
     def compute_mask(self, states, d_mask_ptr: int, stream: int = 0):
         _check(_lib.zf_compute_mask(self.h, _handles(states), len(states), d_mask_ptr, stream))
 
+    def compute_mask_noalloc(self, states, d_mask_ptr: int, stream: int = 0):
+        _check(_lib.zf_compute_mask_noalloc(self.h, _handles(states), len(states), d_mask_ptr, stream))
+
     def compute_mask_async(self, states, d_mask_ptr: int, stream: int = 0):
         _check(_lib.zf_compute_mask_async(self.h, _handles(states), len(states), d_mask_ptr, stream))
 
@@ -298,6 +302,15 @@ def compute_mask(engine: Engine, states, mask_tensor):
     assert mask_tensor.is_cuda and mask_tensor.is_contiguous() and mask_tensor.dtype == torch.int32
     assert tuple(mask_tensor.shape) == (len(states), engine.W)
     engine.compute_mask(states, mask_tensor.data_ptr(), _current_stream(engine))
+    return mask_tensor
+
+
+def compute_mask_noalloc(engine: Engine, states, mask_tensor):
+    """compute_mask through the entry point that allocates no device memory (static scratch array)."""
+    import torch
+    assert mask_tensor.is_cuda and mask_tensor.is_contiguous() and mask_tensor.dtype == torch.int32
+    assert tuple(mask_tensor.shape) == (len(states), engine.W)
+    engine.compute_mask_noalloc(states, mask_tensor.data_ptr(), _current_stream(engine))
     return mask_tensor
 
 

@@ -51,6 +51,7 @@ struct DeviceSide {
     uint32_t *d_counters = nullptr;
     uint2 *d_fb_items = nullptr;
     uint32_t *d_fb_ss = nullptr;
+    uint8_t *scratch = nullptr;          // this device's copy of the static array behind zf_compute_mask_noalloc
     zf_mask_report report{};
     uint32_t call_parity = 0;            // which of the two counter sets the next call uses
     bool profiling = false;
@@ -166,6 +167,13 @@ int setup_device(zf_engine *e) {
     HIP_TRY(hipHostMalloc((void **)&d->h_status, 32 * DeviceSide::N_SLOTS, hipHostMallocDefault));
     memset(d->h_status, 0, 32 * DeviceSide::N_SLOTS);
     for (auto &ev : d->stage_done) HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+    for (int k = 0; k < DeviceSide::N_SLOTS; k++) {     // staging room every engine has from the start (zf_compute_mask_noalloc never grows it)
+        HIP_TRY(hipHostMalloc(&d->h_stage[k], NOALLOC_STAGE_BYTES, hipHostMallocDefault));
+        d->stage_cap[k] = NOALLOC_STAGE_BYTES;
+    }
+    HIP_TRY(scratch_init(d->device));                    // once per device, with that device current
+    d->scratch = (uint8_t *)scratch_ptr(d->device);
+    if (!d->scratch) return fail(ZF_ERR_DEVICE, "the device address of the static scratch array is unknown");
     HIP_TRY(hipMalloc((void **)&d->d_fb_items, (size_t)FB_ITEMS_PER_WAVE * FB_WAVES * sizeof(uint2)));
     HIP_TRY(hipMalloc((void **)&d->d_fb_ss, (size_t)(FB_DEPTH_MAX + 2) * FB_WAVES * sizeof(uint32_t)));
     return ZF_OK;
@@ -574,7 +582,9 @@ int zf_debug_host_mask_stats(zf_engine *e, const zf_state *s, uint32_t *mask, in
 // Pack and upload the charts and enqueue the kernels of one compute_mask call: upload, mask kernel,
 // closing kernel (fallback pass for what the mask kernel listed + permutation into token order),
 // gather when the state cache is on.  wait = true: also wait and return the final status.
-static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait) {
+// noalloc = true (zf_compute_mask_noalloc): every per-call device buffer is a slice of the device's static scratch array,
+// the state cache is passed by, and a call that does not fit the array or the staging room is refused.
+static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait, bool noalloc) {
     if (!e || !states || batch <= 0 || batch > MAX_BATCH || !d_mask) return fail(ZF_ERR_INVALID_ARG, "bad argument (batch must be 1..4096)");
     DeviceSide *d = e->dev;
     if (!d) return fail(ZF_ERR_DEVICE, "engine was compiled without a device (device = -1)");
@@ -601,7 +611,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
         }
     }
     // ---- state cache: rows whose chart has been seen before only need their finished mask copied ----
-    const bool sc = !d->cache.empty() && (size_t)batch * 2 <= d->cache.size();
+    const bool sc = !noalloc && !d->cache.empty() && (size_t)batch * 2 <= d->cache.size();
     static thread_local std::vector<uint32_t> row_slot, miss_rows;
     row_slot.assign(batch, 0);
     miss_rows.clear();
@@ -663,6 +673,9 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     const size_t off_ent = align16(off_items + sizeof(Item) * n_items);
     const size_t off_dst = align16(off_ent + 4 * n_ent), off_rowslot = align16(off_dst + 4 * (size_t)nb);
     const size_t total = off_rowslot + 4 * (size_t)batch + 16;
+    if (noalloc && total > d->stage_cap[slot])
+        return fail(ZF_ERR_INVALID_ARG, "zf_compute_mask_noalloc: the packed charts (" + std::to_string(total) + " bytes) exceed the staging room of " +
+                                        std::to_string(d->stage_cap[slot]) + " bytes");
     if (total > d->stage_cap[slot]) {
         if (d->h_stage[slot]) (void)hipHostFree(d->h_stage[slot]);
         d->h_stage[slot] = nullptr; d->stage_cap[slot] = 0;
@@ -670,7 +683,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
         HIP_TRY(hipHostMalloc(&d->h_stage[slot], cap, hipHostMallocDefault));
         d->stage_cap[slot] = cap;
     }
-    if (total > d->chart_cap) {
+    if (!noalloc && total > d->chart_cap) {
         HIP_TRY(hipStreamSynchronize(stream));            // earlier calls may still read the old buffer
         if (d->d_chart) (void)hipFree(d->d_chart);
         d->d_chart = nullptr; d->chart_cap = 0;
@@ -704,7 +717,23 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     }
     // ---- per-call device buffers ----
     const size_t need_rank = (size_t)std::max(nb, 1) * d->tab.Wr, need_ovf = 2 * (size_t)std::max(nb, 1) * d->tab.n_chunks;   // the automaton kernel may name a chunk in two entries
-    if (need_rank > d->rank_cap || need_ovf > d->overflow_cap) {
+    // zf_compute_mask_noalloc: the same buffers as slices of the static array: [counters: 64 words][fallback set starts][fallback
+    // arenas][rank-ordered verdict words][device copy of the charts (trie walk)][the trie walk's queue][fallback list: what is left]
+    uint8_t *const scr = d->scratch;
+    size_t scr_ss = 0, scr_fb = 0, scr_rank = 0, scr_chart = 0, scr_work = 0, scr_ovf = 0, scr_ovf_cap = 0;
+    if (noalloc) {
+        auto align256 = [](size_t x) { return (x + 255) & ~(size_t)255; };
+        scr_ss = 256;
+        scr_fb = align256(scr_ss + (size_t)(FB_DEPTH_MAX + 2) * NOALLOC_FB_WAVES * 4);
+        scr_rank = align256(scr_fb + (size_t)NOALLOC_FB_WAVES * NOALLOC_FB_ITEMS_PER_WAVE * sizeof(uint2));
+        scr_chart = align256(scr_rank + need_rank * 4 + 16);
+        scr_work = align256(scr_chart + (e->opt.walk_mode == 1 ? total + 16 : 0));
+        scr_ovf = align256(scr_work + (e->opt.walk_mode == 1 ? (size_t)std::max(nb, 1) * d->tab.n_chunks * sizeof(uint4) + 16 : 0));
+        if (scr_ovf + 4096 * sizeof(uint4) > NOALLOC_SCRATCH_BYTES)
+            return fail(ZF_ERR_INVALID_ARG, "zf_compute_mask_noalloc: batch x vocabulary needs " + std::to_string(scr_ovf + 4096 * sizeof(uint4)) +
+                                            " bytes of scratch memory, the static array holds " + std::to_string(NOALLOC_SCRATCH_BYTES));
+        scr_ovf_cap = std::min(need_ovf, (NOALLOC_SCRATCH_BYTES - scr_ovf) / sizeof(uint4));   // a longer list fails the call loudly (ZF_ERR_OVERFLOW)
+    } else if (need_rank > d->rank_cap || need_ovf > d->overflow_cap) {
         HIP_TRY(hipStreamSynchronize(stream));
         if (d->d_rank_mask) (void)hipFree(d->d_rank_mask);
         if (d->d_overflow) (void)hipFree(d->d_overflow);
@@ -721,12 +750,12 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     // staging slot (a block needs a few hundred bytes once; the copy to device memory would be a kernel of its own at the
     // head of the call); else from the device copy that upload_kernel makes.
     const bool direct = e->opt.walk_mode != 1 && !sc;
-    uint8_t *chart_base = direct ? (uint8_t *)d->h_stage[slot] : (uint8_t *)d->d_chart;
+    uint8_t *chart_base = direct ? (uint8_t *)d->h_stage[slot] : (noalloc ? scr + scr_chart : (uint8_t *)d->d_chart);
     a.rows = (const RowChart *)(chart_base + off_rows);
     a.set_off = (const uint32_t *)(chart_base + off_so);
     a.items = (const Item *)(chart_base + off_items);
     a.entries = (const uint32_t *)(chart_base + off_ent);
-    a.rank_mask = d->d_rank_mask;
+    a.rank_mask = noalloc ? (uint32_t *)(scr + scr_rank) : d->d_rank_mask;
     a.out_mask = sc ? d->d_pool : d_mask;                 // with the state cache the rows are finished in their pool slots
     a.dst_row = direct ? nullptr : (const uint32_t *)(chart_base + off_dst);   // null: row r of the launch is row r of the output (no state cache: every row runs)
     a.row_slot = (const uint32_t *)(chart_base + off_rowslot);
@@ -734,17 +763,23 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     a.user_mask = d_mask;
     a.user_batch = batch;
     a.handoff_in_permute = sc ? 0 : 1;
-    a.counters = d->d_counters + 8 * d->call_parity;
-    a.counters_next = d->d_counters + 8 * (d->call_parity ^ 1u);
-    d->call_parity ^= 1u;
-    a.work = d->d_work;
+    if (noalloc) {                                        // cleared at the head of the call; counters_next is a spare set
+        a.counters = (uint32_t *)scr; a.counters_next = (uint32_t *)scr + 8;
+    } else {
+        a.counters = d->d_counters + 8 * d->call_parity;
+        a.counters_next = d->d_counters + 8 * (d->call_parity ^ 1u);
+        d->call_parity ^= 1u;
+    }
+    a.work = noalloc ? (uint4 *)(scr + scr_work) : d->d_work;
     a.host_status = d->h_status + 8 * slot;
     if (++d->call_seq == 0) d->call_seq = 1;
     a.seq = d->call_seq;
-    a.overflow_list = d->d_overflow;
-    a.overflow_cap = (uint32_t)d->overflow_cap;
-    a.fb_items = d->d_fb_items;
-    a.fb_set_start = d->d_fb_ss;
+    a.overflow_list = noalloc ? (uint4 *)(scr + scr_ovf) : d->d_overflow;
+    a.overflow_cap = (uint32_t)(noalloc ? scr_ovf_cap : d->overflow_cap);
+    a.fb_items = noalloc ? (uint2 *)(scr + scr_fb) : d->d_fb_items;
+    a.fb_set_start = noalloc ? (uint32_t *)(scr + scr_ss) : d->d_fb_ss;
+    a.fb_waves = noalloc ? NOALLOC_FB_WAVES : FB_WAVES;
+    a.fb_stride = noalloc ? NOALLOC_FB_ITEMS_PER_WAVE : FB_ITEMS_PER_WAVE;
     a.batch = nb;
     // Item budget of a walking wavefront: the configured one, raised for this call when the rows'
     // current sets are large (ambiguous grammars) so that such rows do not all end in the fallback.
@@ -770,7 +805,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
         // larger surpluses bring nothing more)
         a.walk_blocks = std::max(1, d->cus) * d->occ_blocks * 3 / 2;
     }
-    a.fb_cap = e->opt.fallback_item_cap;
+    a.fb_cap = (int32_t)std::min<uint32_t>((uint32_t)e->opt.fallback_item_cap, a.fb_stride);
     a.mode = d->mode;
     const bool automaton = e->opt.walk_mode != 1;
     if (automaton) {
@@ -824,7 +859,8 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     d->report.main_ms = d->report.fallback_ms = d->report.permute_ms = 0.f;
     d->report.overflow_chunks = d->report.walk_chunks = d->report.parser_steps = 0;
     // everything the host has to work out is done: enqueue the upload and the kernels back to back
-    if (!direct) HIP_TRY(launch_upload(d->h_stage[slot], d->d_chart, total, stream));
+    if (noalloc) HIP_TRY(launch_clear_words((uint32_t *)scr, 16, stream));   // the array keeps the last call's counters
+    if (!direct) HIP_TRY(launch_upload(d->h_stage[slot], chart_base, total, stream));
     const bool run_kernels = nb > 0;
     if (run_kernels && d->tab.n_chunks > 0 && !automaton) HIP_TRY(launch_cache_merge(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
@@ -848,14 +884,19 @@ static void forget_cached_masks(DeviceSide *d) {
 }
 
 // A call that fails part-way may have registered cache slots whose masks were never written.
-static int enqueue_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait) {
-    const int rc = enqueue_mask_impl(e, states, batch, d_mask, hip_stream, wait);
+static int enqueue_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait, bool noalloc = false) {
+    const int rc = enqueue_mask_impl(e, states, batch, d_mask, hip_stream, wait, noalloc);
     if (rc != ZF_OK && e && e->dev) forget_cached_masks(e->dev);
     return rc;
 }
 
 int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream) {
     return enqueue_mask(e, states, batch, d_mask, hip_stream, true);
+}
+
+int zf_compute_mask_noalloc(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream) {
+    if (e && e->dev && e->dev->pending) return fail(ZF_ERR_INVALID_ARG, "zf_compute_mask_noalloc: asynchronous mask calls are in flight: call zf_mask_wait first");
+    return enqueue_mask(e, states, batch, d_mask, hip_stream, true, true);
 }
 
 int zf_compute_mask_async(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream) {

@@ -31,6 +31,11 @@ static const int AUT_SPIN_LIMIT = 1 << 16; // polls of a transition another wave
 static const int FB_DEPTH_MAX = 256;
 static const int FB_WAVES = 512;           // wavefronts of the closing kernel that run the fallback pass (each has its own arena)
 static const int FB_ITEMS_PER_WAVE = 65536; // its arena in global memory: items per wavefront (256 MB in all)
+// The entry point that may not allocate keeps every per-call device buffer in one static device array:
+static const size_t NOALLOC_SCRATCH_BYTES = 16u << 20;
+static const int NOALLOC_FB_WAVES = 32;          // its fallback pass: fewer wavefronts ...
+static const int NOALLOC_FB_ITEMS_PER_WAVE = 16384;   // ... with smaller arenas (4 MB of the array)
+static const size_t NOALLOC_STAGE_BYTES = 256u << 10;  // pinned staging room per slot that every engine has from the start
 
 struct MaskArgs {
     DeviceTables tab;
@@ -54,8 +59,10 @@ struct MaskArgs {
     uint4 *work;               // queue of (row, chunk, undecided strings, -) that need the parser walk
     uint4 *overflow_list;      // (row, chunk, undecided strings, -) for the fallback
     uint32_t overflow_cap;
-    uint2 *fb_items;           // [FB_WAVES][FB_ITEMS_PER_WAVE]
-    uint32_t *fb_set_start;    // [FB_WAVES][FB_DEPTH_MAX + 2]
+    uint2 *fb_items;           // [fb_waves][fb_stride]
+    uint32_t *fb_set_start;    // [fb_waves][FB_DEPTH_MAX + 2]
+    uint32_t fb_waves;         // wavefronts of the fallback pass (each has its own arena) ...
+    uint32_t fb_stride;        // ... of this many items
     int32_t batch;
     int32_t lane_cap;          // item budget of a walking wavefront
     int32_t fb_cap;            // item budget of a fallback wavefront (<= FB_ITEMS_PER_WAVE)
@@ -84,6 +91,10 @@ uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int ar
 hipError_t launch_mask_automaton(const MaskArgs &a, hipStream_t s);
 hipError_t launch_finish(const MaskArgs &a, int cus, hipStream_t s);   // fallback pass (when anything was listed) + permutation into token order
 hipError_t launch_gather(const MaskArgs &a, hipStream_t s);
+// Per-device address of the static device array behind the entry point that may not allocate.
+hipError_t scratch_init(int device);            // resolves it once per device; `device` must be current
+void *scratch_ptr(int device);                  // null before scratch_init(device) has succeeded
+hipError_t launch_clear_words(uint32_t *p, uint32_t n_words, hipStream_t s);   // a fill kernel (no memset node in a captured graph)
 hipError_t launch_apply_mask(const void *logits, void *out, int dtype, int batch, int64_t row_stride, int V, int W,
                              const uint32_t *mask, hipStream_t s);
 

@@ -552,7 +552,7 @@ __device__ __forceinline__ void fallback_wave(const MaskArgs &a, uint32_t gw, ui
     TV T;
     stage_tables<2>(D, nullptr, T, 0, 1);
     if (n > a.overflow_cap) { if (gw == 0 && lane == 0) atomicAdd(&a.counters[2], n - a.overflow_cap); n = a.overflow_cap; }
-    GlobalStore st{a.fb_items + (size_t)gw * FB_ITEMS_PER_WAVE, a.fb_set_start + (size_t)gw * (FB_DEPTH_MAX + 2), (uint32_t)a.fb_cap};
+    GlobalStore st{a.fb_items + (size_t)gw * a.fb_stride, a.fb_set_start + (size_t)gw * (FB_DEPTH_MAX + 2), (uint32_t)a.fb_cap};
     for (uint32_t e = gw; e < n; e += n_waves) {
         const uint4 ent = a.overflow_list[e];
         const BaseG B = global_base(a, ent.x);
@@ -614,7 +614,7 @@ __global__ __launch_bounds__(FINISH_BLOCK) void finish_kernel(MaskArgs a, uint32
     const uint32_t n_over = a.counters[0];
     if (n_over != 0) {
         const uint32_t lin = blockIdx.y * gridDim.x + blockIdx.x, n_blocks = gridDim.x * gridDim.y;
-        const uint32_t fb_waves = n_blocks * FINISH_WAVES < (uint32_t)FB_WAVES ? n_blocks * FINISH_WAVES : (uint32_t)FB_WAVES;
+        const uint32_t fb_waves = n_blocks * FINISH_WAVES < a.fb_waves ? n_blocks * FINISH_WAVES : a.fb_waves;
         const uint32_t gw = lin * FINISH_WAVES + (tid >> 6);
         if (gw < fb_waves) {
             fallback_wave(a, gw, fb_waves, n_over, lane);
