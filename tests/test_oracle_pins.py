@@ -18,7 +18,7 @@ import pytest
 
 from workloads import grammars, vocab as wvocab
 from workloads.grammar import Lit
-from workloads.rng import SplitMix64
+from workloads.rng import SplitMix64, stream
 from oracle import Oracle
 from oracle.frontend import apply_mask, parse_regex
 
@@ -174,6 +174,87 @@ def test_membership_and_viable_prefix_brute_force(gram, alphabet, n, N, oracle_l
             assert s.check(t) == (p + t in prefixes), (p, t)
         assert (s.n_sets(), s.n_items()) == before
         assert not s.check(b"")
+
+
+def language_by_length(g, alphabet: bytes, N: int):
+    """{w over the alphabet, |w| <= N : start =>* w}, as the least solution of the grammar's language
+    equations L(X) = union over rules X -> s1 ... sm of L(s1) ... L(sm), iterated to its fixed point with
+    every string longer than N discarded (concatenation never shortens).  Returns the set for the start symbol."""
+    letters = sorted(set(alphabet))
+    short = [bytes(t) for k in range(1, 4) for t in itertools.product(letters, repeat=k)]
+    term_sets = []
+    for t in g.terminals:
+        if isinstance(t, Lit):
+            term_sets.append({t.data} if len(t.data) <= N and set(t.data) <= set(letters) else set())
+            continue
+        # bytes that occur in some short match; longer matches are enumerated over those only (checked below for lengths <= 4)
+        used = sorted({c for w in short if _term_match(t, w) for c in w})
+        m = {bytes(w) for k in range(1, N + 1) for w in itertools.product(used, repeat=k) if _term_match(t, bytes(w))}
+        full4 = {bytes(w) for k in range(1, 5) for w in itertools.product(letters, repeat=k) if _term_match(t, bytes(w))}
+        assert {w for w in m if len(w) <= 4} == full4, "a byte of this terminal only shows up in matches longer than 3"
+        term_sets.append(m)
+    L = [set() for _ in g.nonterminals]
+    changed = True
+    while changed:
+        changed = False
+        for lhs, rhs in g.rules:
+            cur = {b""}
+            for sym in rhs:
+                part = L[sym] if sym >= 0 else term_sets[~sym]
+                cur = {u + v for u in cur for v in part if len(u) + len(v) <= N}
+                if not cur:
+                    break
+            if not cur <= L[lhs]:
+                L[lhs] |= cur
+                changed = True
+    return L[g.start]
+
+
+def test_expr_grammar_brute_force_to_length_four(oracle_lib):
+    """The ambiguous expression grammar, deeper than the table above reaches: every string of up to 6 bytes over
+    a 1 + * ( ) through the oracle.  A viable prefix of 4 bytes is completed within 5 more ("((((" needs "a))))"), so the
+    language up to 9 bytes decides viability for every prefix of up to 4 bytes exactly."""
+    g = grammars.expr_grammar()
+    alphabet, n, N = b"a1+*()", 4, 9
+    language = language_by_length(g, alphabet, N)
+    for w in _all_strings(alphabet, 5):                       # the two brute-force recognizers agree where both are affordable
+        assert (w in language) == derives(g, w), w
+    prefixes = {w[:k] for w in language for k in range(min(len(w), n) + 1)}
+    o = Oracle(g)
+    n_viable = 0
+    for w in _all_strings(alphabet, 6):
+        s = o.new_state()
+        ok = s.feed_bytes(w)
+        if len(w) <= n:
+            assert ok == (w in prefixes), f"viable({w!r})"
+            n_viable += ok
+        if ok:
+            assert s.accepting() == (w in language), f"accepting({w!r})"
+        else:
+            assert w not in language, f"oracle lost the sentence {w!r}"
+    assert n_viable > 100
+    long_ones = sorted(w for w in language if len(w) > 6)
+    assert len(long_ones) > 8000
+    rs = stream(17, "expr-long-sentences")
+    for _ in range(4000):                                     # sentences of 7-9 bytes: sums and products of sums, many parse trees each
+        w = long_ones[rs.below(len(long_ones))]
+        s = o.new_state()
+        assert s.feed_bytes(w) and s.accepting(), w
+        bad = w[:-1] + (b")" if w[-1:] != b")" else b"+")     # one byte changed at the end: still decided by the enumerated language
+        s = o.new_state()
+        if s.feed_bytes(bad):
+            assert s.accepting() == (bad in language), bad
+        else:
+            assert bad not in language, bad
+    toks = [t for t in _all_strings(alphabet, 2) if t]
+    for p in _all_strings(alphabet, n - 2):
+        s = o.new_state()
+        if not s.feed_bytes(p):
+            continue
+        before = (s.n_sets(), s.n_items())
+        for t in toks:
+            assert s.check(t) == (p + t in prefixes), (p, t)
+        assert (s.n_sets(), s.n_items()) == before
 
 
 def test_nullable_sets(oracle_lib):
