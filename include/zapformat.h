@@ -204,26 +204,6 @@ int zf_engine_set_profiling(zf_engine *e, int32_t on);
 int zf_apply_mask(zf_engine *e, const void *d_logits, void *d_out, int32_t dtype, int32_t batch,
                   int64_t row_stride_elems, const uint32_t *d_mask, void *hip_stream);
 
-/* Diagnostic: the same verdicts computed on the host from the compiled tables (trie, DFAs,
- * chart).  Never used by zf_compute_mask; exists so the host logic can be tested without a GPU. */
-int zf_debug_host_mask(zf_engine *e, const zf_state *s, uint32_t *mask /* host [W] */);
-/* Same, plus counters of the walk in stats[0..4] (host): byte steps taken, steps that left a
- * live set, largest item count of one trie path, largest single set, chunks whose path
- * outgrows lane_item_cap (an estimate of what the fallback pass receives). */
-int zf_debug_host_mask_stats(zf_engine *e, const zf_state *s, uint32_t *mask /* host [W] */, int64_t *stats);
-/* Diagnostic: host walk that first merges the context-independent token-mask cache (Section
- * 4.3) of the current set's items and sends only the undecided strings through the parser, as
- * the kernel does.  stats[0..4] (host, may be null): byte steps, undecided strings, cache rows,
- * byte steps the chunk-wise kernel adds by replaying the path above each chunk, chunks walked. */
-int zf_debug_host_mask_cached(zf_engine *e, const zf_state *s, uint32_t *mask /* host [W] */, int64_t *stats);
-/* Diagnostic: host twin of the mask-automaton kernel.  The Earley sets met while checking one
- * row's tokens are the states of a deterministic automaton over byte classes; a transition is
- * computed by one Earley byte step (Section 3.2) the first time a token needs it and looked up
- * afterwards, sets are interned by content (the state-cache idea of Section 5.2 inside one
- * mask).  stats[0..4] (host, may be null): automaton states created, Earley byte steps taken,
- * transition look-ups, undecided strings, largest set. */
-int zf_debug_host_mask_automaton(zf_engine *e, const zf_state *s, uint32_t *mask /* host [W] */, int64_t *stats);
-
 #ifdef __cplusplus
 }
 #endif

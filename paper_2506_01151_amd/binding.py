@@ -50,7 +50,10 @@ class MaskReport(ctypes.Structure):
 EXPORTS = ["zf_strerror", "zf_last_error", "zf_compile", "zf_engine_destroy", "zf_engine_get_info",
            "zf_state_new", "zf_state_clone", "zf_state_reset", "zf_state_destroy", "zf_advance",
            "zf_advance_bytes", "zf_advance_batch", "zf_is_accepting", "zf_state_stats", "zf_state_chart", "zf_position_info",
-           "zf_compute_mask", "zf_compute_mask_noalloc", "zf_compute_mask_async", "zf_mask_wait", "zf_last_mask_report", "zf_engine_clear_state_cache", "zf_engine_set_profiling", "zf_apply_mask", "zf_debug_host_mask", "zf_debug_host_mask_stats", "zf_debug_host_mask_cached", "zf_debug_host_mask_automaton"]
+           "zf_compute_mask", "zf_compute_mask_noalloc", "zf_compute_mask_async", "zf_mask_wait", "zf_last_mask_report", "zf_engine_clear_state_cache", "zf_engine_set_profiling", "zf_apply_mask"]
+# test-only diagnostics (include/zapformat_debug.h)
+DEBUG_EXPORTS = ["zf_debug_host_mask", "zf_debug_host_mask_stats", "zf_debug_host_mask_cached", "zf_debug_host_mask_automaton",
+                 "zf_debug_twin_new", "zf_debug_twin_destroy", "zf_debug_twin_advance", "zf_debug_twin_mask"]
 
 
 class ZfError(RuntimeError):
@@ -97,6 +100,11 @@ def load_library():
     L.zf_debug_host_mask_stats.argtypes = [c_vp, c_vp, c_vp, c_vp]
     L.zf_debug_host_mask_cached.argtypes = [c_vp, c_vp, c_vp, c_vp]
     L.zf_debug_host_mask_automaton.argtypes = [c_vp, c_vp, c_vp, c_vp]
+    L.zf_debug_twin_new.argtypes = [c_vp, ctypes.POINTER(c_vp)]
+    L.zf_debug_twin_destroy.argtypes = [c_vp]
+    L.zf_debug_twin_destroy.restype = None
+    L.zf_debug_twin_advance.argtypes = [c_vp, ctypes.POINTER(ctypes.c_uint32), c_vp, c_i64, ctypes.POINTER(c_i32)]
+    L.zf_debug_twin_mask.argtypes = [c_vp, ctypes.c_uint32, c_vp, c_vp]
     _lib = L
     return L
 
@@ -181,6 +189,34 @@ class State:
         out = np.zeros(self.engine.W, dtype=np.uint32)
         _check(_lib.zf_debug_host_mask(self.engine.h, self.h, out.ctypes.data))
         return out
+
+
+class Twin:
+    """Test-only: host twin of the persistent automaton (include/zapformat_debug.h)."""
+
+    def __init__(self, engine):
+        self.engine = engine
+        h = c_vp()
+        _check(_lib.zf_debug_twin_new(engine.h, ctypes.byref(h)))
+        self.h = h
+
+    def __del__(self):
+        if getattr(self, "h", None) and _lib is not None:
+            _lib.zf_debug_twin_destroy(self.h)
+            self.h = None
+
+    def advance(self, state: int, data: bytes):
+        """(return code, next state, accepting)."""
+        buf = (ctypes.c_uint8 * max(1, len(data))).from_buffer_copy(data or b"\0")
+        st, acc = ctypes.c_uint32(state), c_i32()
+        rc = _lib.zf_debug_twin_advance(self.h, ctypes.byref(st), buf, len(data), ctypes.byref(acc))
+        return rc, st.value, bool(acc.value)
+
+    def mask(self, state: int):
+        out = np.zeros(self.engine.W, dtype=np.uint32)
+        st = np.zeros(8, dtype=np.int64)
+        _check(_lib.zf_debug_twin_mask(self.h, state, out.ctypes.data, st.ctypes.data))
+        return out, dict(states=int(st[0]), steps=int(st[1]), lookups=int(st[2]), undecided=int(st[3]), items=int(st[4]))
 
 
 class StateBatch:

@@ -5,6 +5,7 @@
 #include <vector>
 #include "zf_device.h"
 #include "../../include/zapformat.h"
+#include "../../include/zapformat_debug.h"
 
 namespace zf {
 

@@ -10,7 +10,10 @@ The oracle keeps every Earley set, so on the ambiguous expression grammar a mask
 with every step; `--budget-s` ends the run after that much wall time and the header states
 how many steps were reached and how long they took.
 
-usage: python tests/golden/make_trajectories.py CFG [ROWS [STEPS]] [--budget-s SECONDS] [--threads N]
+With `--resume` a file cut short is continued: its steps are fed to fresh oracle states again
+(one sampler draw per fed token, as in the original run) and sampling goes on from there.
+
+usage: python tests/golden/make_trajectories.py CFG [ROWS [STEPS]] [--budget-s SECONDS] [--threads N] [--resume]
 """
 import argparse
 import os
@@ -42,6 +45,7 @@ def main():
     ap.add_argument("--budget-s", type=float, default=0.0, help="stop after this much wall time (0 = run all steps)")
     ap.add_argument("--threads", type=int, default=8)
     ap.add_argument("--out", default=None)
+    ap.add_argument("--resume", action="store_true", help="continue the steps the output file already holds")
     a = ap.parse_args()
     cfg = configs.CONFIGS[a.cfg]
     rows = a.rows or cfg.batch
@@ -51,7 +55,26 @@ def main():
     out = a.out or os.path.join(os.path.dirname(os.path.abspath(__file__)), f"trajectory_cfg{a.cfg}.txt")
     t0 = time.time()
     lines = []
-    for step in range(steps):
+    if a.resume and os.path.exists(out):
+        import re
+        text = open(out).read()
+        spent = re.search(r"oracle wall time (\d+) s", text)
+        t0 -= float(spent.group(1)) if spent else 0.0
+        for line in text.splitlines():
+            if not line.strip() or line.startswith("#"):
+                continue
+            ids = [int(x) for x in line.split()]
+            assert len(ids) == rows, "the file to resume has another number of rows"
+            for b, t in enumerate(ids):
+                if t < 0:
+                    run.states[b] = run.o.new_state()
+                    run.resets += 1
+                else:
+                    run.samplers[b].next_u64()             # the draw that picked t
+                    assert run.states[b].feed_bytes(toks[t])
+            lines.append(line.strip())
+        print(f"resumed {len(lines)} steps", flush=True)
+    for step in range(len(lines), steps):
         ids = run.step(run.masks())
         lines.append(" ".join(map(str, ids)))
         if step % 8 == 7 or step == steps - 1:     # the file on disk is always a usable prefix

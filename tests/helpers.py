@@ -9,6 +9,8 @@ def load_trajectory(idx, rows, steps):
     import os
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", f"trajectory_cfg{idx}.txt")
     traj = [[int(x) for x in line.split()] for line in open(path) if line.strip() and not line.startswith("#")]
+    if steps is None:            # as far as the file goes
+        steps = len(traj)
     assert len(traj) >= steps and len(traj[0]) >= rows, "trajectory file too small for this test"
     return [t[:rows] for t in traj[:steps]]
 

@@ -111,57 +111,105 @@ def test_chunk_sizes(chunk, torch_cuda, oracle_lib):
     _run_parity(torch_cuda, zf, oracle_lib.Oracle, cfg.grammar(), cfg.vocab(2048 - 37), 3, 32, cfg.seed + 5, chunk_strings=chunk)
 
 
-REPLAY = [  # config, rows, steps, check every, rows compared with the oracle per check, pruning, mask kernel
-    (3, 16, 512, 37, 16, True, "automaton"),
-    (4, 64, 256, 31, 12, True, "automaton"),
-    (5, 8, 192, 23, 8, True, "automaton"),
-    (5, 8, 192, 47, 8, False, "automaton"),
-    (3, 16, 512, 61, 16, None, "automaton"),    # None: pruning on, token-mask cache off (every token through the parser)
-    (3, 16, 512, 43, 16, True, "trie-walk"),
-    (4, 64, 256, 53, 12, True, "trie-walk"),
-    (5, 8, 192, 59, 8, True, "trie-walk"),
-    (3, 16, 512, 127, 16, None, "trie-walk"),
-]
-
-
-@pytest.mark.parametrize("idx,rows,steps,every,n_cmp,pruning,mode", REPLAY,
-                         ids=[f"cfg{r[0]}-" + {True: "pruned", False: "unpruned", None: "parser-only"}[r[5]] + "-" + r[6] for r in REPLAY])
-def test_full_size_configs_replay(idx, rows, steps, every, n_cmp, pruning, mode, torch_cuda, oracle_lib):
-    """Full vocabulary and batch of configurations 3-5 in the launch shape the benchmark uses:
-    replay the oracle-sampled trajectory on both sides; at sampled steps one compute_mask call
-    covers every row and sampled rows are compared bit for bit with the oracle's masks."""
-    import paper_2506_01151_amd as zf
-    torch = torch_cuda
+def _replay_all_rows(torch, zf, oracle_lib, idx, variants, stride_of=None):
+    """Replay configuration idx's oracle-sampled trajectory at its full batch and vocabulary on the oracle and on one
+    engine per variant; at every step every row of every variant's mask is compared with the oracle's (variants named
+    in stride_of only at every stride-th step and at the last one)."""
     cfg = configs.CONFIGS[idx]
     toks = cfg.vocab()
     off, data = wvocab.vocab_csr(toks)
+    rows, steps = cfg.batch, cfg.steps
     traj = load_trajectory(idx, rows, steps)
     g = cfg.grammar()
-    eng = zf.Engine(g, toks, device=0, pruning=pruning is not False, token_mask_cache=pruning is not None, state_cache_entries=-1, walk_mode=MODES[mode])
     orc = oracle_lib.Oracle(g)
     so = [orc.new_state() for _ in range(rows)]
-    ss = [eng.new_state() for _ in range(rows)]
-    d_mask = torch.empty((rows, eng.W), dtype=torch.int32, device="cuda")
-    pick = stream(cfg.seed, "parity-rows")
-    n_checked = 0
+    engines = {name: zf.Engine(g, toks, device=0, state_cache_entries=-1, **kw) for name, kw in variants.items()}
+    batches = {name: zf.StateBatch([e.new_state() for _ in range(rows)]) for name, e in engines.items()}
+    d_mask = torch.empty((rows, engines[next(iter(engines))].W), dtype=torch.int32, device="cuda")
+    n_checked = {name: 0 for name in engines}
     for step, ids in enumerate(traj):
         for b, t in enumerate(ids):
             if t < 0:
                 so[b] = orc.new_state()
-                ss[b].reset()
             else:
                 assert so[b].feed_bytes(toks[t])
-                ss[b].advance(t)
-        if step % every == 0 or step == steps - 1:
+        want = np.stack([s.mask(off, data, 16) for s in so])
+        for name, eng in engines.items():
+            batches[name].advance(ids)
+            if stride_of and name in stride_of and step % stride_of[name] and step != steps - 1:
+                continue
+            d_mask.fill_(-1)
+            zf.compute_mask(eng, batches[name], d_mask)
+            got = d_mask.cpu().numpy().view(np.uint32)
+            if not np.array_equal(got, want):
+                b = int(np.argwhere((got != want).any(axis=1))[0][0])
+                raise AssertionError(f"cfg{idx} {name} step {step} row {b}")
+            n_checked[name] += rows
+    return n_checked, rows * steps
+
+
+def test_config3_every_step_every_row(torch_cuda, oracle_lib):
+    """Configuration 3 at its stated shape (16 rows x 512 steps, V = 128,256): both mask kernels against the oracle at
+    every step on every row; with the token-mask cache off (every token through the parser) at every 4th step."""
+    import paper_2506_01151_amd as zf
+    variants = {"automaton": dict(walk_mode=0), "trie-walk": dict(walk_mode=1),
+                "automaton-parser-only": dict(walk_mode=0, token_mask_cache=False), "trie-walk-parser-only": dict(walk_mode=1, token_mask_cache=False)}
+    n, full = _replay_all_rows(torch_cuda, zf, oracle_lib, 3, variants, {"automaton-parser-only": 4, "trie-walk-parser-only": 4})
+    assert n["automaton"] == full == 16 * 512 and n["trie-walk"] == full
+
+
+def test_config4_every_step_every_row(torch_cuda, oracle_lib):
+    """Configuration 4 at its stated shape (64 rows x 256 steps, V = 128,256): both mask kernels, every step, every row."""
+    import paper_2506_01151_amd as zf
+    n, full = _replay_all_rows(torch_cuda, zf, oracle_lib, 4, {"automaton": dict(walk_mode=0), "trie-walk": dict(walk_mode=1)})
+    assert n["automaton"] == full == 64 * 256 and n["trie-walk"] == full
+
+
+CFG5_CHECK_STEPS = 12      # steps of the trajectory at which masks are compared (spread evenly, the last one included) ...
+CFG5_CHECK_ROWS = 6        # ... on this many seeded rows each: the oracle keeps every Earley set, a mask at step 600 costs it about a second
+
+
+@pytest.mark.parametrize("mode", list(MODES))
+@pytest.mark.parametrize("pruning", [True, False], ids=["pruned", "unpruned"])
+def test_config5_full_batch_pruning_on_and_off(pruning, mode, torch_cuda, oracle_lib):
+    """Configuration 5 at its stated batch and vocabulary (64 rows, V = 152,064) along the oracle-sampled trajectory, as far
+    as the file goes: one compute_mask call covers all 64 rows (the launch shape the benchmark times); a seeded, reported
+    subsample of (step, row) pairs is compared bit for bit with the oracle, with ZapFormat pruning on and off, both kernels."""
+    import paper_2506_01151_amd as zf
+    torch = torch_cuda
+    cfg = configs.CONFIGS[5]
+    toks = cfg.vocab()
+    off, data = wvocab.vocab_csr(toks)
+    rows = cfg.batch
+    traj = load_trajectory(5, rows, None)
+    steps = len(traj)
+    assert steps >= 256
+    g = cfg.grammar()
+    eng = zf.Engine(g, toks, device=0, pruning=pruning, state_cache_entries=-1, walk_mode=MODES[mode])
+    orc = oracle_lib.Oracle(g)
+    so = [orc.new_state() for _ in range(rows)]
+    ss = zf.StateBatch([eng.new_state() for _ in range(rows)])
+    d_mask = torch.empty((rows, eng.W), dtype=torch.int32, device="cuda")
+    check_at = sorted({(k + 1) * steps // CFG5_CHECK_STEPS - 1 for k in range(CFG5_CHECK_STEPS)} | {0, 7})
+    pick = stream(cfg.seed, "parity-rows")
+    pairs = []
+    for step, ids in enumerate(traj):
+        for b, t in enumerate(ids):
+            if t < 0:
+                so[b] = orc.new_state()
+            else:
+                assert so[b].feed_bytes(toks[t])
+        ss.advance(ids)
+        if step in check_at:
             d_mask.fill_(-1)
             zf.compute_mask(eng, ss, d_mask)
             got = d_mask.cpu().numpy().view(np.uint32)
-            cmp_rows = range(rows) if n_cmp >= rows else sorted({pick.below(rows) for _ in range(n_cmp)})
-            for b in cmp_rows:
-                want = so[b].mask(off, data, 16)
-                assert (got[b] == want).all(), f"cfg{idx} step {step} row {b}"
-                n_checked += 1
-    assert n_checked >= 8
+            for b in sorted({pick.below(rows) for _ in range(CFG5_CHECK_ROWS)}):
+                assert (got[b] == so[b].mask(off, data, 16)).all(), f"cfg5 step {step} row {b}"
+                assert ss[b].accepting() == so[b].accepting()
+                pairs.append((step, b))
+    print(f"config 5 {'pruned' if pruning else 'unpruned'} {mode}: {steps} steps x {rows} rows replayed, compared (step, row): {pairs}")
+    assert len(pairs) >= 40
 
 
 STATE_CACHE = [  # config, rows, steps, compare every, cache rows (0 = default), expect the cache to be used

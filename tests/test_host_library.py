@@ -24,15 +24,17 @@ def zf():
 
 
 def test_library_exports_every_declared_symbol(zf):
-    header = open(os.path.join(ROOT, "include", "zapformat.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(zf_[a-z0-9_]+)\s*\(", header))
-    assert len(declared) >= 20
+    from paper_2506_01151_amd.binding import EXPORTS, DEBUG_EXPORTS
     lib = zf.load_library()
-    for name in sorted(declared):
-        assert hasattr(lib, name), f"{name} is declared in zapformat.h but not exported"
-    from paper_2506_01151_amd.binding import EXPORTS
-    assert declared == set(EXPORTS)
+    for fname, names, least in (("zapformat.h", EXPORTS, 20), ("zapformat_debug.h", DEBUG_EXPORTS, 8)):
+        header = open(os.path.join(ROOT, "include", fname)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        declared = set(re.findall(r"\b(zf_[a-z0-9_]+)\s*\(", header))
+        assert len(declared) >= least
+        for name in sorted(declared):
+            assert hasattr(lib, name), f"{name} is declared in {fname} but not exported"
+        assert declared == set(names)
+        assert not any("debug" in n for n in declared) or fname == "zapformat_debug.h"
 
 
 def _all_strings(alphabet, max_len):
@@ -240,6 +242,44 @@ def test_config_trajectories_host_walk_matches_oracle(idx, rows, steps, every, z
                     assert st["steps"] <= st["lookups"] and st["states"] <= st["steps"]   # at most one Earley step per new transition
                     assert s.accepting() == so.accepting()
         assert ss[0].stats().n_items <= ss[1].stats().n_items
+
+
+@pytest.mark.parametrize("idx,rows,steps,every", [(1, 1, 64, 1), (2, 1, 256, 8), (3, 4, 300, 25), (4, 3, 120, 20), (5, 2, 96, 12)])
+def test_persistent_automaton_twin_matches_oracle(idx, rows, steps, every, zf, oracle_lib):
+    """One automaton for all rows and steps, states named by content: feeding the trajectory's tokens is a walk
+    through it, and at sampled steps the mask computed from the reached state equals the oracle's.  States and
+    transitions made for one row or step serve the others."""
+    cfg = configs.CONFIGS[idx]
+    toks = cfg.vocab()
+    traj = load_trajectory(idx, rows, steps)
+    off, data = wvocab.vocab_csr(toks)
+    g = cfg.grammar()
+    orc = oracle_lib.Oracle(g)
+    eng = zf.Engine(g, toks, device=-1)
+    tw = zf.Twin(eng)
+    so = [orc.new_state() for _ in range(rows)]
+    st = [0] * rows
+    per_mask = []
+    for step, ids in enumerate(traj):
+        for b in range(rows):
+            t = ids[b]
+            if t < 0:
+                so[b], st[b] = orc.new_state(), 0
+                continue
+            assert so[b].feed_bytes(toks[t])
+            rc, st[b], acc = tw.advance(st[b], toks[t])
+            assert rc == 0 and acc == so[b].accepting(), (idx, b, step)
+        if step % every == 0 or step == steps - 1:
+            for b in range(rows):
+                got, info = tw.mask(st[b])
+                assert (got == so[b].mask(off, data, 8)).all(), (idx, b, step)
+                per_mask.append(info["steps"])
+    # a token the oracle rejects is rejected here too, and the state stays where it was
+    want = so[0].mask(off, data, 8)
+    bad = next(v for v in range(len(toks)) if toks[v] and not (want[v >> 5] >> (v & 31)) & 1)
+    rc, same, _ = tw.advance(st[0], toks[bad])
+    assert rc == zf.ZF_ERR_REJECTED and same == st[0]
+    assert info["states"] < 40 * steps * rows and sum(per_mask) > 0
 
 
 def test_advance_batch_equals_row_by_row():
