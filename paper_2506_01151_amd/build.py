@@ -6,8 +6,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libzapformat.so")
-SOURCES = ["zf_regex.cpp", "zf_compile.cpp", "zf_earley.cpp", "zf_automaton.cpp", "zf_api.cpp", "zf_kernels.hip", "zf_mask_walk.hip", "zf_mask_automaton.hip", "zf_scratch.hip"]
-HEADERS = ["zf_device.h", "zf_internal.h", "zf_launch.h", "zf_kernel_common.h"]
+SOURCES = ["zf_regex.cpp", "zf_compile.cpp", "zf_earley.cpp", "zf_automaton.cpp", "zf_api.cpp", "zf_kernels.hip", "zf_mask_walk.hip", "zf_mask_automaton.hip", "zf_mask_store.hip", "zf_scratch.hip"]
+HEADERS = ["zf_device.h", "zf_internal.h", "zf_launch.h", "zf_kernel_common.h", "zf_aut_step.h"]
 
 
 def build(force: bool = True) -> str:

@@ -52,6 +52,19 @@ struct DeviceSide {
     uint2 *d_fb_items = nullptr;
     uint32_t *d_fb_ss = nullptr;
     uint8_t *scratch = nullptr;          // this device's copy of the static array behind zf_compute_mask_noalloc
+    // The persistent automaton (walk_mode 2).
+    StoreView store{};
+    void *d_root_items = nullptr; uint32_t n_root = 0;
+    uint32_t *d_import_root = nullptr;               // [MAX_BATCH]
+    uint32_t *h_row_out = nullptr;                   // pinned, [N_SLOTS][MAX_BATCH]: the state each row of a call ends up in
+    uint32_t store_epoch = 1;                        // bumped whenever the store is cleared
+    uint32_t store_states = 0, store_items = 0;      // as of the last call that reported back
+    bool store_dirty = true;                         // the store must be cleared before its next use
+    struct CallRecord {                              // what to note in the states once the call in this slot has reported
+        bool active = false;
+        uint32_t epoch = 0;
+        std::vector<zf_state *> st; std::vector<uint32_t> gen; std::vector<uint64_t> upto;
+    } rec[N_SLOTS];
     zf_mask_report report{};
     uint32_t call_parity = 0;            // which of the two counter sets the next call uses
     bool profiling = false;
@@ -61,6 +74,7 @@ struct DeviceSide {
 namespace {
 
 const int MAX_BATCH = 4096;   // rows per zf_compute_mask call
+const uint32_t STORE_ROOT_ID = 1;
 
 int fail(int code, const std::string &m) { set_error(m); return code; }
 #define HIP_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return fail(ZF_ERR_DEVICE, std::string(#expr) + ": " + hipGetErrorString(e_)); } while (0)
@@ -93,6 +107,14 @@ void free_device(DeviceSide *d) {
     if (d->d_counters) (void)hipFree(d->d_counters);
     if (d->d_fb_items) (void)hipFree(d->d_fb_items);
     if (d->d_fb_ss) (void)hipFree(d->d_fb_ss);
+    if (d->store.hdr) (void)hipFree(d->store.hdr);
+    if (d->store.arena) (void)hipFree(d->store.arena);
+    if (d->store.trans) (void)hipFree(d->store.trans);
+    if (d->store.intern) (void)hipFree(d->store.intern);
+    if (d->store.ctl) (void)hipFree(d->store.ctl);
+    if (d->d_root_items) (void)hipFree(d->d_root_items);
+    if (d->d_import_root) (void)hipFree(d->d_import_root);
+    if (d->h_row_out) (void)hipHostFree(d->h_row_out);
     for (auto &ev : d->ev) if (ev) (void)hipEventDestroy(ev);
     delete d;
 }
@@ -171,6 +193,34 @@ int setup_device(zf_engine *e) {
         HIP_TRY(hipHostMalloc(&d->h_stage[k], NOALLOC_STAGE_BYTES, hipHostMallocDefault));
         d->stage_cap[k] = NOALLOC_STAGE_BYTES;
     }
+    if (e->store_on) {
+        // Room of the persistent automaton: states x byte classes transition words (at most 128 MB), 4 M items, a hash table of
+        // twice as many slots as states.  The host clears the store when it is half full (see enqueue_mask_impl).
+        StoreView &G = d->store;
+        uint32_t cap = 1u << 18;
+        while (cap > 4096 && (size_t)cap * (size_t)std::max(t.n_cls, 1) * 4 > ((size_t)128 << 20)) cap >>= 1;
+        G.cap_states = cap; G.cap_items = 1u << 22; G.intern_mask = 2 * cap - 1;
+        HIP_TRY(hipMalloc((void **)&G.hdr, (size_t)G.cap_states * sizeof(uint2)));
+        HIP_TRY(hipMalloc((void **)&G.arena, (size_t)G.cap_items * sizeof(uint2)));
+        HIP_TRY(hipMalloc((void **)&G.trans, (size_t)G.cap_states * std::max(t.n_cls, 1) * 4));
+        HIP_TRY(hipMalloc((void **)&G.intern, ((size_t)G.intern_mask + 1) * 8));
+        HIP_TRY(hipMalloc((void **)&G.ctl, 64));
+        HIP_TRY(hipMalloc((void **)&d->d_import_root, (size_t)MAX_BATCH * 4));
+        HIP_TRY(hipHostMalloc((void **)&d->h_row_out, (size_t)DeviceSide::N_SLOTS * MAX_BATCH * 4, hipHostMallocDefault));
+        Chart c0;                                        // the empty prefix's set, completed items dropped, as device item words
+        chart_init(t, c0);
+        std::vector<uint32_t> root;
+        for (const Item &it : c0.items) {
+            if ((t.sym[it.p] >> SYM_KIND_SHIFT) == SYM_END) continue;
+            const uint32_t aw = t.advpq[it.p];
+            root.push_back((aw & IW_TERM) ? ((aw & 0xFFFFu) | ((uint32_t)it.q << 16)) : aw);
+            root.push_back(0);
+        }
+        d->n_root = (uint32_t)root.size() / 2;
+        HIP_TRY(hipMalloc(&d->d_root_items, std::max<size_t>(root.size() * 4, 16)));
+        if (!root.empty()) HIP_TRY(hipMemcpy(d->d_root_items, root.data(), root.size() * 4, hipMemcpyHostToDevice));
+        d->store_dirty = true;
+    }
     HIP_TRY(scratch_init(d->device));                    // once per device, with that device current
     d->scratch = (uint8_t *)scratch_ptr(d->device);
     if (!d->scratch) return fail(ZF_ERR_DEVICE, "the device address of the static scratch array is unknown");
@@ -217,6 +267,13 @@ int feed_token_bytes(zf_state *s, const uint8_t *bytes, int64_t n) {
     s->accepting = accepted;
     s->items_created += created;
     s->bytes_fed += n;
+    if (s->eng->store_on) {                               // the device walks the same bytes at the next mask call
+        for (int64_t i = 0; i < n; i++) s->pending.push_back(t.cls[bytes[i]]);
+        s->fed_total += (uint64_t)n;
+        if (s->pending.size() > (size_t)STORE_PENDING_MAX) {   // too far behind: the row comes in through its chart again
+            s->pending.clear(); s->pending_base = s->fed_total; s->dev_id = 0; s->dev_epoch = 0;
+        }
+    }
     if (pruning) chart_compact(t, c);   // Compact: after Complete, before the next Predict
     return ZF_OK;
 }
@@ -265,6 +322,7 @@ int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_option
         build_trie(v, e->opt.chunk_strings, e->tab.cls, e->trie);
         build_token_mask_cache(e->tab, e->trie);
     } catch (const std::bad_alloc &) { delete e; return fail(ZF_ERR_OOM, "out of memory"); }
+    e->store_on = e->opt.device >= 0 && e->opt.walk_mode == 2 && e->opt.pruning != 0;
     if (e->opt.device >= 0) {
         int rc = setup_device(e);
         if (rc != ZF_OK) { free_device(e->dev); delete e; return rc; }
@@ -314,6 +372,8 @@ int zf_state_reset(zf_state *s) {
     c.items.resize(w);
     c.set_off[1] = (uint32_t)w;
     s->items_created = 0; s->bytes_fed = 0;
+    s->dev_id = STORE_ROOT_ID; s->dev_epoch = 0; s->generation++;
+    s->pending.clear(); s->pending_base = s->fed_total;
     return ZF_OK;
 }
 
@@ -325,7 +385,11 @@ int zf_state_clone(const zf_state *s, zf_state **out) {
     return ZF_OK;
 }
 
-void zf_state_destroy(zf_state *s) { delete s; }
+void zf_state_destroy(zf_state *s) {
+    if (s && s->eng && s->eng->dev)                       // calls in flight must not write to a state that is gone
+        for (auto &rec : s->eng->dev->rec) if (rec.active) for (auto &p : rec.st) if (p == s) p = nullptr;
+    delete s;
+}
 
 int zf_advance(zf_state *s, int32_t token) {
     if (!s) return fail(ZF_ERR_INVALID_ARG, "null argument");
@@ -579,6 +643,52 @@ int zf_debug_host_mask_stats(zf_engine *e, const zf_state *s, uint32_t *mask, in
     return ZF_OK;
 }
 
+// The packed form of a chart: [n_sets][set offsets][item word, origin]...; what the kernels read, and the state cache's key.
+static void pack_chart(const Tables &t, const Chart &c, std::vector<uint32_t> &k) {
+    k.clear();
+    k.push_back(c.n_sets());
+    k.insert(k.end(), c.set_off.begin(), c.set_off.end());
+    for (const Item &it : c.items) {   // host item -> device item word + origin
+        const uint32_t aw = t.advpq[it.p];
+        k.push_back((aw & IW_TERM) ? ((aw & 0xFFFFu) | ((uint32_t)it.q << 16)) : aw);
+        k.push_back(it.o);
+    }
+}
+
+// State cache (Section 5.2): find every row's pool slot by its packed chart; rows seen for the first time get a slot
+// (round-robin victim, never one handed out in the same call) and are listed in miss_rows.  Returns the number of hits.
+static int state_cache_lookup(DeviceSide *d, const std::vector<std::vector<uint32_t>> &packed, int32_t batch,
+                              std::vector<uint32_t> &row_slot, std::vector<uint32_t> &miss_rows) {
+    int n_hits = 0;
+    const uint32_t call = ++d->cache_call;
+    for (int b = 0; b < batch; b++) {
+        const std::vector<uint32_t> &k = packed[b];
+        uint64_t h = 0xCBF29CE484222325ull;
+        for (uint32_t w : k) { h ^= w; h *= 0x100000001B3ull; h ^= h >> 29; }
+        uint32_t found = 0xFFFFFFFFu;
+        auto range = d->cache_index.equal_range(h);
+        for (auto it = range.first; it != range.second; ++it) if (d->cache[it->second].key == k) { found = it->second; break; }
+        if (found == 0xFFFFFFFFu) {
+            while (d->cache[d->cache_victim].used && d->cache[d->cache_victim].stamp == call) d->cache_victim = (d->cache_victim + 1) % d->cache.size();
+            found = d->cache_victim;
+            d->cache_victim = (d->cache_victim + 1) % d->cache.size();
+            DeviceSide::CacheEntry &ce = d->cache[found];
+            if (ce.used) {   // evict
+                auto r2 = d->cache_index.equal_range(ce.hash);
+                for (auto it = r2.first; it != r2.second; ++it) if (it->second == found) { d->cache_index.erase(it); break; }
+            }
+            ce.hash = h; ce.key = k; ce.used = true;
+            d->cache_index.emplace(h, found);
+            miss_rows.push_back((uint32_t)b);
+        } else n_hits++;
+        d->cache[found].stamp = call;
+        row_slot[b] = found;
+    }
+    return n_hits;
+}
+
+static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait, uint32_t slot);
+
 // Pack and upload the charts and enqueue the kernels of one compute_mask call: upload, mask kernel,
 // closing kernel (fallback pass for what the mask kernel listed + permutation into token order),
 // gather when the state cache is on.  wait = true: also wait and return the final status.
@@ -595,53 +705,19 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     HIP_TRY(hipEventSynchronize(d->stage_done[slot]));   // the slot's previous upload has left the staging buffer
     for (int b = 0; b < batch; b++)
         if (!states[b] || states[b]->eng != e) return fail(ZF_ERR_INVALID_ARG, "state " + std::to_string(b) + " is null or belongs to another engine");
+    if (e->store_on && !noalloc) return enqueue_store_impl(e, states, batch, d_mask, hip_stream, wait, slot);
     // ---- the packed form of every row: [n_sets][set offsets][item word, origin]... (also the cache key) ----
     static thread_local std::vector<std::vector<uint32_t>> packed;
     if ((int)packed.size() < batch) packed.resize(batch);
-    for (int b = 0; b < batch; b++) {
-        const Chart &c = states[b]->chart;
-        std::vector<uint32_t> &k = packed[b];
-        k.clear();
-        k.push_back(c.n_sets());
-        k.insert(k.end(), c.set_off.begin(), c.set_off.end());
-        for (const Item &it : c.items) {   // host item -> device item word + origin
-            const uint32_t aw = e->tab.advpq[it.p];
-            k.push_back((aw & IW_TERM) ? ((aw & 0xFFFFu) | ((uint32_t)it.q << 16)) : aw);
-            k.push_back(it.o);
-        }
-    }
+    for (int b = 0; b < batch; b++) pack_chart(e->tab, states[b]->chart, packed[b]);
     // ---- state cache: rows whose chart has been seen before only need their finished mask copied ----
     const bool sc = !noalloc && !d->cache.empty() && (size_t)batch * 2 <= d->cache.size();
     static thread_local std::vector<uint32_t> row_slot, miss_rows;
     row_slot.assign(batch, 0);
     miss_rows.clear();
     int n_hits = 0;
-    if (sc) {
-        const uint32_t call = ++d->cache_call;
-        for (int b = 0; b < batch; b++) {
-            const std::vector<uint32_t> &k = packed[b];
-            uint64_t h = 0xCBF29CE484222325ull;
-            for (uint32_t w : k) { h ^= w; h *= 0x100000001B3ull; h ^= h >> 29; }
-            uint32_t found = 0xFFFFFFFFu;
-            auto range = d->cache_index.equal_range(h);
-            for (auto it = range.first; it != range.second; ++it) if (d->cache[it->second].key == k) { found = it->second; break; }
-            if (found == 0xFFFFFFFFu) {
-                while (d->cache[d->cache_victim].used && d->cache[d->cache_victim].stamp == call) d->cache_victim = (d->cache_victim + 1) % d->cache.size();
-                found = d->cache_victim;
-                d->cache_victim = (d->cache_victim + 1) % d->cache.size();
-                DeviceSide::CacheEntry &ce = d->cache[found];
-                if (ce.used) {   // evict
-                    auto r2 = d->cache_index.equal_range(ce.hash);
-                    for (auto it = r2.first; it != r2.second; ++it) if (it->second == found) { d->cache_index.erase(it); break; }
-                }
-                ce.hash = h; ce.key = k; ce.used = true;
-                d->cache_index.emplace(h, found);
-                miss_rows.push_back((uint32_t)b);
-            } else n_hits++;
-            d->cache[found].stamp = call;
-            row_slot[b] = found;
-        }
-    } else for (int b = 0; b < batch; b++) miss_rows.push_back((uint32_t)b);
+    if (sc) n_hits = state_cache_lookup(d, packed, batch, row_slot, miss_rows);
+    else for (int b = 0; b < batch; b++) miss_rows.push_back((uint32_t)b);
     // trie walk: rows with a wide current set first: their chunks are the expensive ones, and work that starts early does
     // not end up as the kernel's tail (the mask automaton gives every row its own blocks: the order does not matter there)
     if (e->opt.walk_mode == 1) std::stable_sort(miss_rows.begin(), miss_rows.end(), [&](uint32_t x, uint32_t y) {
@@ -878,6 +954,186 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     return zf_mask_wait(e, hip_stream);
 }
 
+// The same call through the persistent automaton (walk_mode 2): the upload names, per row, the state the row was last known
+// to be in and the byte classes fed since; the mask kernel walks them, checks the vocabulary from the state it arrives at and
+// reports that state back (pinned memory), which zf_mask_wait notes in the zf_state.  Rows the store does not know -- after it
+// was cleared, or too far behind -- bring their packed chart along and are made states of by the import kernel first.
+static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait, uint32_t slot) {
+    DeviceSide *d = e->dev;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    // ---- clear the store when it is new, half full, or has refused a request; only with no call in flight ----
+    if (d->pending == 0 && (d->store_dirty || d->store_states > d->store.cap_states / 2 || d->store_items > d->store.cap_items / 2)) {
+        HIP_TRY(launch_store_clear(d->store, (uint32_t)std::max(e->tab.n_cls, 1), d->d_root_items, d->n_root, stream));
+        d->store_epoch++;
+        d->store_states = 2; d->store_items = d->n_root;
+        d->store_dirty = false;
+    }
+    // ---- state cache (keyed by the packed chart, as on the other paths) ----
+    const bool sc = !d->cache.empty() && (size_t)batch * 2 <= d->cache.size();
+    static thread_local std::vector<std::vector<uint32_t>> packed;
+    static thread_local std::vector<uint32_t> row_slot, miss_rows, import_rows;
+    if ((int)packed.size() < batch) packed.resize(batch);
+    row_slot.assign(batch, 0);
+    miss_rows.clear();
+    int n_hits = 0;
+    if (sc) {
+        for (int b = 0; b < batch; b++) pack_chart(e->tab, states[b]->chart, packed[b]);
+        n_hits = state_cache_lookup(d, packed, batch, row_slot, miss_rows);
+    } else for (int b = 0; b < batch; b++) miss_rows.push_back((uint32_t)b);
+    const int nb = (int)miss_rows.size();
+    d->report.cache_hits = n_hits; d->report.cache_misses = sc ? nb : 0;
+    // ---- what each launched row sends ----
+    import_rows.clear();
+    const bool use_cache = !e->opt.disable_token_mask_cache;
+    size_t n_pend = 0, n_ent = 0, n_off = 0, n_items = 0, widest = 0;
+    for (int r = 0; r < nb; r++) {
+        zf_state *st = states[miss_rows[r]];
+        const Chart &c = st->chart;
+        const size_t last = c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1];
+        widest = std::max(widest, last);
+        if (use_cache) n_ent += last;
+        const bool known = st->dev_id == STORE_ROOT_ID || (st->dev_id != 0 && st->dev_epoch == d->store_epoch);
+        if (known) n_pend += st->pending.size();
+        else {
+            import_rows.push_back((uint32_t)r);
+            if (!sc) pack_chart(e->tab, c, packed[miss_rows[r]]);
+            n_off += c.set_off.size(); n_items += c.items.size();
+        }
+    }
+    const int n_imp = (int)import_rows.size();
+    auto align16 = [](size_t x) { return (x + 15) & ~(size_t)15; };
+    const size_t off_srow = 0, off_ent = align16(sizeof(StoreRow) * nb), off_pend = align16(off_ent + 4 * n_ent);
+    const size_t off_dst = align16(off_pend + n_pend), off_rowslot = align16(off_dst + 4 * (size_t)nb);
+    const size_t off_rows = align16(off_rowslot + 4 * (size_t)batch), off_so = align16(off_rows + sizeof(RowChart) * n_imp);
+    const size_t off_items = align16(off_so + 4 * n_off), off_imp = align16(off_items + sizeof(Item) * n_items);
+    const size_t total = off_imp + 4 * (size_t)n_imp + 16;
+    if (total > d->stage_cap[slot]) {
+        if (d->h_stage[slot]) (void)hipHostFree(d->h_stage[slot]);
+        d->h_stage[slot] = nullptr; d->stage_cap[slot] = 0;
+        const size_t cap = total * 2 + 4096;
+        HIP_TRY(hipHostMalloc(&d->h_stage[slot], cap, hipHostMallocDefault));
+        d->stage_cap[slot] = cap;
+    }
+    if (sc && total > d->chart_cap) {
+        HIP_TRY(hipStreamSynchronize(stream));
+        if (d->d_chart) (void)hipFree(d->d_chart);
+        d->d_chart = nullptr; d->chart_cap = 0;
+        const size_t cap = total * 2 + 4096;
+        HIP_TRY(hipMalloc(&d->d_chart, cap));
+        d->chart_cap = cap;
+    }
+    DeviceSide::CallRecord &rec = d->rec[slot];
+    rec.active = true; rec.epoch = d->store_epoch;
+    rec.st.assign(nb, nullptr); rec.gen.assign(nb, 0); rec.upto.assign(nb, 0);
+    uint32_t n_cache_rows = 0;
+    {
+        uint8_t *h = (uint8_t *)d->h_stage[slot];
+        StoreRow *srow = (StoreRow *)(h + off_srow);
+        uint32_t *ents = (uint32_t *)(h + off_ent);
+        uint8_t *pend = h + off_pend;
+        uint32_t *dst = (uint32_t *)(h + off_dst);
+        RowChart *rows = (RowChart *)(h + off_rows);
+        uint32_t *so = (uint32_t *)(h + off_so);
+        uint32_t *dev_items = (uint32_t *)(h + off_items);
+        uint32_t *imp = (uint32_t *)(h + off_imp);
+        memcpy(h + off_rowslot, row_slot.data(), 4 * (size_t)batch);
+        uint32_t en_at = 0, pe_at = 0, so_at = 0, it_at = 0, k_imp = 0;
+        for (int r = 0; r < nb; r++) {
+            zf_state *st = states[miss_rows[r]];
+            const Chart &c = st->chart;
+            StoreRow sr{};
+            sr.ent_off = en_at;
+            if (use_cache) { sr.n_ent = current_set_entries(e->tab, c, ents + en_at); sr.flags |= STORE_ROW_CACHE; }
+            en_at += sr.n_ent;
+            n_cache_rows += sr.n_ent;
+            const bool known = st->dev_id == STORE_ROOT_ID || (st->dev_id != 0 && st->dev_epoch == d->store_epoch);
+            if (known) {
+                sr.start = st->dev_id; sr.n_pending = (uint32_t)st->pending.size(); sr.pend_off = pe_at;
+                if (sr.n_pending) memcpy(pend + pe_at, st->pending.data(), sr.n_pending);
+                pe_at += sr.n_pending;
+            } else {
+                const std::vector<uint32_t> &k = packed[miss_rows[r]];
+                sr.flags |= STORE_ROW_IMPORTED;
+                rows[k_imp] = RowChart{c.n_sets(), so_at, it_at, 0, 0, (uint32_t)c.items.size(), {0, 0}};
+                memcpy(so + so_at, k.data() + 1, 4 * c.set_off.size());
+                memcpy(dev_items + 2 * (size_t)it_at, k.data() + 1 + c.set_off.size(), 8 * c.items.size());
+                so_at += (uint32_t)c.set_off.size(); it_at += (uint32_t)c.items.size();
+                imp[k_imp++] = (uint32_t)r;
+                st->pending.clear(); st->pending_base = st->fed_total;     // the chart holds everything fed so far
+            }
+            srow[r] = sr;
+            dst[r] = sc ? row_slot[miss_rows[r]] : miss_rows[r];
+            rec.st[r] = st; rec.gen[r] = st->generation; rec.upto[r] = st->fed_total;
+        }
+    }
+    const size_t need_rank = (size_t)std::max(nb, 1) * d->tab.Wr;
+    if (need_rank > d->rank_cap) {
+        HIP_TRY(hipStreamSynchronize(stream));
+        if (d->d_rank_mask) (void)hipFree(d->d_rank_mask);
+        d->d_rank_mask = nullptr; d->rank_cap = 0;
+        HIP_TRY(hipMalloc((void **)&d->d_rank_mask, need_rank * 4 + 16));
+        d->rank_cap = need_rank;
+    }
+    MaskArgs a{};
+    a.tab = d->tab;
+    a.store = d->store;
+    const bool direct = !sc;                              // the kernels read the pinned slot in place
+    uint8_t *base = direct ? (uint8_t *)d->h_stage[slot] : (uint8_t *)d->d_chart;
+    a.store_rows = (const StoreRow *)(base + off_srow);
+    a.entries = (const uint32_t *)(base + off_ent);
+    a.store_pending = base + off_pend;
+    a.store_import_root = d->d_import_root;
+    a.store_row_out = d->h_row_out + (size_t)slot * MAX_BATCH;
+    a.rows = (const RowChart *)(base + off_rows);
+    a.set_off = (const uint32_t *)(base + off_so);
+    a.items = (const Item *)(base + off_items);
+    a.rank_mask = d->d_rank_mask;
+    a.out_mask = sc ? d->d_pool : d_mask;
+    a.dst_row = direct ? nullptr : (const uint32_t *)(base + off_dst);
+    a.row_slot = (const uint32_t *)(base + off_rowslot);
+    a.user_mask = d_mask;
+    a.user_batch = batch;
+    a.handoff_in_permute = sc ? 0 : 1;
+    a.counters = d->d_counters + 8 * d->call_parity;
+    a.counters_next = d->d_counters + 8 * (d->call_parity ^ 1u);
+    d->call_parity ^= 1u;
+    a.host_status = d->h_status + 8 * slot;
+    if (++d->call_seq == 0) d->call_seq = 1;
+    a.seq = d->call_seq;
+    a.fb_waves = FB_WAVES; a.fb_stride = FB_ITEMS_PER_WAVE;   // the closing kernel's fallback pass has nothing to do on this path
+    a.batch = nb;
+    a.mode = d->mode;
+    {   // LDS of a block: the staged tables, the cache of table entries, and per wavefront the set under construction
+        int scratch = e->lane_cap_auto ? (int)std::min<size_t>(LANE_CAP_MAX, (4 * widest + 128 + 31) / 32 * 32) : e->opt.lane_item_cap;
+        while (scratch > 32 && store_lds_bytes(d->tab, d->mode, scratch) > 160u * 1024u) scratch -= 32;
+        if (store_lds_bytes(d->tab, d->mode, scratch) > 160u * 1024u) return fail(ZF_ERR_INVALID_ARG, "the grammar tables leave no LDS for the mask kernel");
+        a.aut_scratch = scratch;
+        const int n_sub = (d->tab.Wr + STORE_SUB_WORDS - 1) / STORE_SUB_WORDS;
+        a.aut_parts = std::max(1, std::min(n_sub, (STORE_BLOCKS_PER_CU * std::max(1, d->cus) + std::max(nb, 1) - 1) / std::max(nb, 1)));
+    }
+    const bool prof = d->profiling;
+    d->report.chart_bytes = (int64_t)total;
+    d->report.cache_rows = (int32_t)n_cache_rows;
+    d->report.main_ms = d->report.fallback_ms = d->report.permute_ms = 0.f;
+    d->report.overflow_chunks = d->report.walk_chunks = d->report.parser_steps = 0;
+    if (!direct) HIP_TRY(launch_upload(d->h_stage[slot], d->d_chart, total, stream));
+    if (n_imp) HIP_TRY(launch_store_import(a, (const uint32_t *)(base + off_imp), (uint32_t)n_imp, stream));
+    const bool run_kernels = nb > 0;
+    if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
+    if (run_kernels && d->tab.n_chunks > 0) HIP_TRY(launch_mask_store(a, stream));
+    if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));
+    if (run_kernels) HIP_TRY(launch_finish(a, d->cus, stream));
+    if (sc) HIP_TRY(launch_gather(a, stream));
+    if (prof) HIP_TRY(hipEventRecord(d->ev[3], stream));
+    HIP_TRY(hipEventRecord(d->stage_done[slot], stream));
+    d->next_slot = (slot + 1) % DeviceSide::N_SLOTS;
+    d->pending++;
+    d->last_seq = a.seq; d->last_slot = slot;
+    if (!wait) return ZF_OK;
+    HIP_TRY(hipStreamSynchronize(stream));
+    return zf_mask_wait(e, hip_stream);
+}
+
 static void forget_cached_masks(DeviceSide *d) {
     d->cache_index.clear();
     for (auto &ce : d->cache) ce.used = false;
@@ -930,6 +1186,29 @@ int zf_mask_wait(zf_engine *e, void *hip_stream) {
         HIP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));   // nothing of this engine in flight: plain stream synchronisation
     }
     uint32_t unresolved = 0;
+    if (e->store_on) {
+        // note where every row of the finished calls stands in the persistent automaton, oldest call first
+        for (int i = 0; i < DeviceSide::N_SLOTS; i++) {
+            const uint32_t k = (d->next_slot + i) % DeviceSide::N_SLOTS;
+            DeviceSide::CallRecord &rec = d->rec[k];
+            if (!rec.active) continue;
+            rec.active = false;
+            const bool good = st[8 * k + 2] == 0 && rec.epoch == d->store_epoch;
+            const uint32_t *out = d->h_row_out + (size_t)k * MAX_BATCH;
+            for (size_t r = 0; r < rec.st.size() && good; r++) {
+                zf_state *s = rec.st[r];
+                if (!s || s->generation != rec.gen[r] || out[r] == 0 || (out[r] >= d->store.cap_states && out[r] != 0xFFFFFFFDu)) continue;
+                if (rec.upto[r] < s->pending_base) continue;              // a later call's result is already in
+                const size_t drop = std::min<size_t>((size_t)(rec.upto[r] - s->pending_base), s->pending.size());
+                s->pending.erase(s->pending.begin(), s->pending.begin() + drop);
+                s->pending_base = rec.upto[r];
+                s->dev_id = out[r]; s->dev_epoch = rec.epoch;
+            }
+            if (st[8 * k + 5]) { d->store_states = st[8 * k + 5]; d->store_items = st[8 * k + 6]; }
+            if (st[8 * k + 7] || st[8 * k + 2]) d->store_dirty = true;    // the store refused a request, or a walk failed: start over
+            st[8 * k + 5] = st[8 * k + 6] = st[8 * k + 7] = 0;
+        }
+    }
     for (int k = 0; k < DeviceSide::N_SLOTS; k++) {
         unresolved += st[8 * k + 2];
         if (st[8 * k + 0] || st[8 * k + 1]) { d->report.overflow_chunks = st[8 * k + 0]; d->report.walk_chunks = st[8 * k + 1]; d->report.parser_steps = st[8 * k + 3]; }
@@ -948,7 +1227,7 @@ int zf_mask_wait(zf_engine *e, void *hip_stream) {
 
 int zf_engine_clear_state_cache(zf_engine *e) {
     if (!e) return fail(ZF_ERR_INVALID_ARG, "null argument");
-    if (e->dev) forget_cached_masks(e->dev);
+    if (e->dev) { forget_cached_masks(e->dev); e->dev->store_dirty = true; }   // the persistent automaton starts over as well
     return ZF_OK;
 }
 

@@ -101,6 +101,7 @@ struct zf_engine {
     std::vector<uint8_t> voc_bytes;
     bool start_nullable = false;
     bool lane_cap_auto = true;          // no explicit lane_item_cap: the budget follows the rows' set sizes
+    bool store_on = false;              // the mask calls go through the persistent automaton (walk_mode 2, pruning on, a device)
     struct DeviceSide *dev = nullptr;   // null when compiled with device = -1
 };
 
@@ -109,4 +110,12 @@ struct zf_state {
     zf::Chart chart;
     bool accepting = false;
     int64_t items_created = 0, bytes_fed = 0;
+    // Where the row stands in the engine's persistent automaton (walk_mode 2): the state it was last known to be in,
+    // and the byte classes fed since (the next mask call walks them on the device and reports the new state).
+    uint32_t dev_id = 1;                // 1 = the state of the empty prefix, valid in every epoch of the store
+    uint32_t dev_epoch = 0;             // epoch of the store dev_id belongs to
+    uint32_t generation = 0;            // bumped by every reset: results of calls enqueued before it no longer apply
+    std::vector<uint8_t> pending;
+    uint64_t fed_total = 0;             // bytes fed since the state was made; pending covers [pending_base, fed_total)
+    uint64_t pending_base = 0;
 };

@@ -32,6 +32,7 @@ __global__ __launch_bounds__(256) void gather_kernel(MaskArgs a) {
         if (threadIdx.x < 8) a.counters_next[threadIdx.x] = 0;
         if (threadIdx.x == 0) {                           // counters first, then the word the host waits for
             for (int i = 0; i < 4; i++) a.host_status[i] = a.counters[i];
+            if (a.store.ctl) for (int i = 0; i < 3; i++) a.host_status[5 + i] = a.store.ctl[i];
             __hip_atomic_store(&a.host_status[4], a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
@@ -89,8 +90,9 @@ __global__ __launch_bounds__(256) void apply_mask_scalar_kernel(const ElemT *__r
 }  // namespace
 
 hipError_t prepare_kernels() {
-    const hipError_t e = prepare_walk_kernels();
-    return e != hipSuccess ? e : prepare_automaton_kernels();
+    hipError_t e = prepare_walk_kernels();
+    if (e == hipSuccess) e = prepare_automaton_kernels();
+    return e != hipSuccess ? e : prepare_store_kernels();
 }
 
 hipError_t launch_upload(const void *pinned_src, void *dst, size_t bytes, hipStream_t s) {

@@ -37,8 +37,52 @@ static const int NOALLOC_FB_WAVES = 32;          // its fallback pass: fewer wav
 static const int NOALLOC_FB_ITEMS_PER_WAVE = 16384;   // ... with smaller arenas (4 MB of the array)
 static const size_t NOALLOC_STAGE_BYTES = 256u << 10;  // pinned staging room per slot that every engine has from the start
 
+// The persistent automaton (zf_options.walk_mode = 2): one store per engine in device memory.
+#ifndef ZF_STORE_WAVES
+#define ZF_STORE_WAVES 4
+#endif
+#ifndef ZF_STORE_SUB_WORDS
+#define ZF_STORE_SUB_WORDS 64
+#endif
+#ifndef ZF_STORE_LC_BITS
+#define ZF_STORE_LC_BITS 10
+#endif
+static const int STORE_WAVES = ZF_STORE_WAVES;  // wavefronts per block of the mask kernel over the persistent automaton
+static const int STORE_BLOCK = STORE_WAVES * 64;
+static const int STORE_SUB_WORDS = ZF_STORE_SUB_WORDS;   // words of the rank-ordered bitmap a block merges and checks per pass (at most 128: one wavefront lists the word pairs)
+static const int STORE_LC_BITS = ZF_STORE_LC_BITS;       // log2 of the entries of a block's LDS cache of table entries (8 bytes each)
+#ifndef ZF_STORE_BLOCKS_PER_CU
+#define ZF_STORE_BLOCKS_PER_CU 3
+#endif
+static const int STORE_BLOCKS_PER_CU = ZF_STORE_BLOCKS_PER_CU;   // blocks per compute unit the grid aims at (the chip should hold them all at once)
+static const int STORE_PENDING_LDS = 256;       // pending bytes of a row a block keeps in LDS (more are read from the upload)
+static const int STORE_PENDING_MAX = 4096;      // beyond this many bytes since its state was last known a row comes in through its chart again
+static const uint32_t STORE_ROW_CACHE = 1u;     // StoreRow::flags: the token-mask cache rows of the row are listed
+static const uint32_t STORE_ROW_IMPORTED = 2u;  // the row's start state is the one the import kernel made from its chart
+struct StoreView {
+    uint2 *hdr;                 // [cap_states] (first item in the arena, item count); count 0xFFFFFFFF = not published
+    uint2 *arena;               // [cap_items] (item word, name of the set the item's rule started in)
+    uint32_t *trans;            // [cap_states][n_cls] next state or AT_*
+    unsigned long long *intern; // [intern_mask + 1] content signature << 32 | state; 0 = free
+    uint32_t *ctl;              // [0] states handed out (the next name), [1] items handed out, [2] requests the store had no room for
+    uint32_t cap_states, cap_items, intern_mask;
+};
+struct StoreRow {               // one row of a call
+    uint32_t start;             // the state the row was last known to be in
+    uint32_t n_pending;         // bytes (as byte classes) fed to the row since then ...
+    uint32_t pend_off;          // ... at this offset of the call's pending bytes
+    uint32_t n_ent, ent_off;    // token-mask-cache rows of the row's current set (in MaskArgs::entries)
+    uint32_t flags;
+    uint32_t pad[2];
+};
+
 struct MaskArgs {
     DeviceTables tab;
+    StoreView store;
+    const StoreRow *store_rows;        // [batch]
+    const uint8_t *store_pending;
+    uint32_t *store_import_root;       // [batch] device memory: written by the import kernel
+    uint32_t *store_row_out;           // [batch] pinned host memory: the state every row is in after this call's walk
     const RowChart *rows;      // [batch]
     const uint32_t *set_off;   // shared CSR offsets of all rows' sets
     const Item *items;         // shared item array of all rows
@@ -89,6 +133,11 @@ hipError_t launch_cache_merge(const MaskArgs &a, hipStream_t s);
 hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s);
 uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int arena, int scratch, int base_sets, int base_items, bool wide);
 hipError_t launch_mask_automaton(const MaskArgs &a, hipStream_t s);
+hipError_t prepare_store_kernels();
+uint32_t store_lds_bytes(const DeviceTables &t, int mode, int scratch);
+hipError_t launch_mask_store(const MaskArgs &a, hipStream_t s);
+hipError_t launch_store_clear(const StoreView &G, uint32_t ncls, const void *root_items, uint32_t n_root, hipStream_t s);
+hipError_t launch_store_import(const MaskArgs &a, const uint32_t *import_rows, uint32_t n_import, hipStream_t s);
 hipError_t launch_finish(const MaskArgs &a, int cus, hipStream_t s);   // fallback pass (when anything was listed) + permutation into token order
 hipError_t launch_gather(const MaskArgs &a, hipStream_t s);
 // Per-device address of the static device array behind the entry point that may not allocate.

@@ -1,0 +1,443 @@
+// Mask kernel over the persistent automaton (zf_options.walk_mode = 2): mask_store_kernel, with the
+// kernels that set the store up and bring a row's chart into it.
+//
+// Every Earley set is named by its content: its items, each with the NAME of the set its rule started
+// in (not a position in some row's chart).  Named that way the sets of all rows and of all decode
+// steps are the states of ONE deterministic automaton over byte classes, kept in device memory for
+// the life of the engine:
+//   - feeding the token that was just decoded (Section 4.1: the update after every decoding step) is
+//     a walk of its bytes through the automaton from the row's current state: the host sends the
+//     bytes, not the chart;
+//   - the per-step token check walks every undecided vocabulary string through the same table;
+//   - a transition is computed by one wavefront-cooperative Earley byte step (Scan + Complete with
+//     tabulated Predict, Section 3.2) the first time any row, token or step needs it, and is a
+//     look-up for everybody ever after (the reuse across steps that Sections 4.4 and 5.2 aim at).
+// A state refers only to the sets its items started in, transitively, which is exactly what
+// ZapFormat's reachability closure keeps of a chart (Section 4.2.3); completed items are dropped
+// when a set is closed (Figure 3, first rule).  Nothing is ever removed from the store: when it
+// fills up the host clears it and the rows come back in from their host charts (import_kernel).
+//
+// Concurrency.  A transition entry goes NONE -> BUSY -> final value, once; whoever swaps NONE for
+// BUSY computes it; everybody else polls (the owner is a running wavefront that waits for nothing,
+// so the wait ends; it is bounded all the same).  A new state is written completely (items, dead
+// transitions, header) and released at device scope before any entry or hash-table slot names it.
+// Table entries are read with device-scope atomic loads (they bypass the per-CU cache); a
+// wavefront makes an acquire fence before it reads items it learnt of through such a load.
+#include "zf_kernel_common.h"
+#include "zf_aut_step.h"
+
+namespace zf {
+namespace {
+
+static const uint32_t STORE_ROOT = 1;                  // the state of the empty prefix
+static const uint32_t UNPUBLISHED = 0xFFFFFFFFu;
+static const int LC_BITS = STORE_LC_BITS;               // block-local cache of table entries
+static const uint32_t LC_ENTRIES = 1u << LC_BITS;
+static const unsigned long long LC_EMPTY = 0xFFFFFFFF00000000ull;
+
+__device__ __forceinline__ uint32_t g_load(const uint32_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void g_store_release(uint32_t *p, uint32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ bool t_final(uint32_t t) { return t != AT_NONE && t != AT_BUSY; }
+// A table entry changes NONE -> BUSY -> final value and never again, so a cached copy is either right or "not there
+// yet": look-ups first read through the caches and ask device memory only when the cached answer is not final.
+__device__ __forceinline__ uint32_t t_load(const uint32_t *p) {
+    uint32_t t = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    if (!t_final(t)) t = g_load(p);
+    return t;
+}
+
+// The grammar tables are needed only by a wavefront that computes a transition, which is rare once the automaton has
+// grown: the first such wavefront of a block copies them into LDS (ctl[4]: 0 = not there, 1 = being copied, 2 = there).
+__device__ __forceinline__ bool ensure_tables(uint32_t *ctl, uint8_t *smem, const uint8_t *blob, uint32_t n16, uint32_t lane) {
+    if (n16 == 0) return true;
+    uint32_t st = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&ctl[4]));
+    if (st == 0) {
+        uint32_t old = 0;
+        if (lane == 0) old = atomicCAS(&ctl[4], 0u, 1u);
+        old = (uint32_t)__builtin_amdgcn_readfirstlane((int)old);
+        if (old == 0) {
+            const uint4 *src = reinterpret_cast<const uint4 *>(blob);
+            uint4 *dst = reinterpret_cast<uint4 *>(smem);
+            for (uint32_t k = lane; k < n16; k += 64) dst[k] = src[k];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            if (lane == 0) lds_store(&ctl[4], 2u);
+            return true;
+        }
+        st = old;
+    }
+    for (uint32_t spins = 0; st != 2 && spins < (uint32_t)AUT_SPIN_LIMIT; spins++) {   // the copying wavefront waits for nothing
+        __builtin_amdgcn_s_sleep(2);
+        st = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&ctl[4]));
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    return st == 2;
+}
+
+struct StoreSets {             // resolves the name of a set to its items (device memory)
+    const StoreView &G;
+    uint32_t *errors;
+    __device__ __forceinline__ void view(uint32_t ref, const uint2 *&p, uint32_t &n) const {
+        uint2 h = make_uint2(0, 0);
+        if (ref < G.cap_states) h = G.hdr[ref];
+        // a name that leads nowhere cannot come from a correct store: read nothing, and fail the call loudly
+        if (ref >= G.cap_states || h.y > G.cap_items || h.x > G.cap_items - h.y) { h = make_uint2(0, 0); atomicAdd(errors, 1u); }
+        p = G.arena + h.x;
+        n = h.y;
+    }
+};
+
+struct Scratch { uint32_t *w, *o, *h; uint32_t cap; };   // one wavefront's set under construction (+ hash table of the wide step)
+struct Staging { uint32_t *ctl; uint8_t *smem; const uint8_t *blob; uint32_t n16; };   // what ensure_tables needs
+
+// true when state `id` holds exactly the `kept` items in the scratch
+__device__ __forceinline__ bool same_content(const StoreView &G, uint32_t id, const Scratch &sc, uint32_t kept, uint32_t lane) {
+    if (id == 0 || id >= G.cap_states) return false;
+    const uint2 hj = G.hdr[id];
+    if (hj.y != kept || hj.x > G.cap_items - kept) return false;
+    unsigned long long diff = 0;
+    for (uint32_t i0 = 0; i0 < kept; i0 += 64) {
+        bool ne = false;
+        if (i0 + lane < kept) { const uint2 x = G.arena[hj.x + i0 + lane]; ne = x.x != lds_load(&sc.w[i0 + lane]) || x.y != lds_load(&sc.o[i0 + lane]); }
+        diff |= __ballot(ne);
+    }
+    return diff == 0;
+}
+
+// The transition of state s on class cl: one Earley byte step, then the state that holds the
+// resulting set -- found by content in the store's hash table, or made.  Uniform over the wavefront.
+// Returns a state id, AT_DEAD, AT_SINK or AT_FAIL (no room in the scratch or in the store).
+__device__ __forceinline__ uint32_t store_transition(const TV &T, const StoreView &G, const uint8_t *rep, const Scratch &sc, const Staging &stg, uint32_t *errors,
+                                                     uint32_t s, uint32_t cl, uint32_t lane) {
+    if (!ensure_tables(stg.ctl, stg.smem, stg.blob, stg.n16, lane)) return AT_FAIL;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");      // s and every set it refers to were released before the entry that led here
+    const StoreSets S{G, errors};
+    uint32_t nnew = 0, kept = 0;
+    const uint2 *src_p;
+    uint32_t src_n;
+    S.view(s, src_p, src_n);
+    const uint32_t byte = rep[cl];
+    int st = src_n > (uint32_t)AUT_NARROW_SET_MAX ? (int)AUT_WIDE : aut_step_narrow<true>(T, S, sc.w, sc.o, sc.cap, s, byte, cl, lane, nnew, kept);
+    if (st == AUT_WIDE) st = aut_step_wide(T, S, sc.w, sc.o, sc.h, sc.cap, s, byte, cl, lane, nnew, kept);
+    if (st != AUT_OK) return AT_FAIL;
+    if (nnew == 0) return AT_DEAD;
+    if (kept == 0) return AT_SINK;
+    // signature of the content (never 0: 0 marks a free slot of the hash table)
+    uint32_t h = 0x811C9DC5u;
+    for (uint32_t i0 = 0; i0 < kept; i0 += 64) {
+        uint32_t x = 0;
+        if (i0 + lane < kept) { x = (lds_load(&sc.w[i0 + lane]) * 0x9E3779B1u) ^ (lds_load(&sc.o[i0 + lane]) * 0x85EBCA77u); x ^= x >> 15; x *= (2u * (i0 + lane) + 1u) * 0x2C1B3C6Du; }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d);
+        h = (h ^ x) * 0x01000193u;
+    }
+    h = (uint32_t)__builtin_amdgcn_readfirstlane((int)(h ^ kept)) | 1u;
+    uint32_t slot = (h * 0x9E3779B1u) & G.intern_mask;
+    for (uint32_t probes = 0; probes <= G.intern_mask; probes++) {
+        const unsigned long long e = __hip_atomic_load(&G.intern[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (e == 0) break;
+        if ((uint32_t)(e >> 32) == h) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // the state was released before its slot was written
+            if (same_content(G, (uint32_t)e, sc, kept, lane)) return (uint32_t)e;
+        }
+        slot = (slot + 1) & G.intern_mask;
+    }
+    uint32_t id = 0, at = 0;
+    if (lane == 0) { id = atomicAdd(&G.ctl[0], 1u); at = atomicAdd(&G.ctl[1], kept); }
+    id = (uint32_t)__builtin_amdgcn_readfirstlane((int)id);
+    at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+    if (id >= G.cap_states || at > G.cap_items - kept) { if (lane == 0) atomicAdd(&G.ctl[2], 1u); return AT_FAIL; }   // the store is full
+    for (uint32_t i0 = 0; i0 < kept; i0 += 64)
+        if (i0 + lane < kept) G.arena[at + i0 + lane] = make_uint2(lds_load(&sc.w[i0 + lane]), lds_load(&sc.o[i0 + lane]));
+    uint32_t *row = G.trans + (size_t)id * T.ncls;
+    aut_mark_dead<true>(T, T.ncls, rep, [&](uint32_t i) { return lds_load(&sc.w[i]); }, kept, lane, [&](uint32_t c) { row[c] = AT_DEAD; });
+    if (lane == 0) G.hdr[id] = make_uint2(at, kept);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");      // items, dead entries and header before anything that names the state
+    for (uint32_t probes = 0; probes <= G.intern_mask; probes++) {
+        unsigned long long old = 0;
+        if (lane == 0) old = atomicCAS(&G.intern[slot], 0ull, ((unsigned long long)h << 32) | id);
+        old = ((unsigned long long)(uint32_t)__builtin_amdgcn_readfirstlane((int)(old >> 32)) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)old);
+        if (old == 0) return id;
+        if ((uint32_t)(old >> 32) == h) {                    // somebody made the same set meanwhile: theirs is the name
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            if (same_content(G, (uint32_t)old, sc, kept, lane)) return (uint32_t)old;
+        }
+        slot = (slot + 1) & G.intern_mask;
+    }
+    return id;                                               // the table has twice as many slots as states: not reached
+}
+
+// Look the transition (s, cl) up for the whole wavefront (uniform arguments), computing it if nobody has.
+__device__ __forceinline__ uint32_t store_lookup_uniform(const TV &T, const StoreView &G, const uint8_t *rep, const Scratch &sc, const Staging &stg, uint32_t *errors,
+                                                         uint32_t *steps, uint32_t s, uint32_t cl, uint32_t lane) {
+    uint32_t *entry = G.trans + (size_t)s * T.ncls + cl;
+    for (uint32_t spins = 0; spins < (uint32_t)AUT_SPIN_LIMIT; spins++) {
+        uint32_t t = (uint32_t)__builtin_amdgcn_readfirstlane((int)t_load(entry));
+        if (t == AT_NONE) {
+            uint32_t old = 0;
+            if (lane == 0) old = atomicCAS(entry, (uint32_t)AT_NONE, (uint32_t)AT_BUSY);
+            old = (uint32_t)__builtin_amdgcn_readfirstlane((int)old);
+            if (old == AT_NONE) {
+                const uint32_t r = store_transition(T, G, rep, sc, stg, errors, s, cl, lane);
+                ++*steps;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                if (lane == 0) g_store_release(entry, r);
+                return r;
+            }
+            t = old;
+        }
+        if (t_final(t)) return t;
+        __builtin_amdgcn_s_sleep(8);
+    }
+    return AT_FAIL;
+}
+
+__host__ __device__ inline uint32_t store_round16(uint32_t x) { return (x + 15u) & ~15u; }
+
+// Grid (parts, rows), blocks of STORE_WAVES wavefronts.  A block (a) stages the grammar tables, the row's
+// token-mask-cache row numbers and pending bytes; (b) its last wavefront walks the row's pending bytes
+// (the tokens fed since the row's state was last known) from the row's state to its current state,
+// while all threads merge the token-mask cache rows of the block's share of the rank-ordered bitmap
+// (Section 4.3); (c) its wavefronts take the undecided strings, 64 neighbouring ranks at a time, one
+// lane per string, through the transition table -- first the block's cache of entries in LDS, then
+// device memory, and an Earley byte step for what nobody has computed yet.
+template <int MODE>
+__global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    const DeviceTables &D = a.tab;
+    const StoreView &G = a.store;
+    const uint32_t tid = threadIdx.x, row = blockIdx.y, wave = tid >> 6, lane = tid & 63;
+    const uint32_t Wr = (uint32_t)D.Wr, n_strings = (uint32_t)D.n_strings, ncls = (uint32_t)D.n_cls;
+    if (blockIdx.x >= (Wr + AUT_GROUP_WORDS - 1) / AUT_GROUP_WORDS) return;
+    TV T;
+    uint32_t off = table_view<MODE>(D, smem, T);
+    const uint32_t n16 = off / 16;
+    const StoreRow rin = a.store_rows[row];
+    const uint32_t sc_cap = (uint32_t)a.aut_scratch;
+    unsigned long long *lc = reinterpret_cast<unsigned long long *>(smem + off); off += LC_ENTRIES * 8;
+    uint32_t *l_ent = reinterpret_cast<uint32_t *>(smem + off); off += AUT_ENT_LDS * 4;
+    uint8_t *l_rep = smem + off; off += 256;
+    uint8_t *l_pend = smem + off; off += STORE_PENDING_LDS;
+    uint32_t *vslice = reinterpret_cast<uint32_t *>(smem + off); off += STORE_SUB_WORDS * 4;
+    uint32_t *cslice = reinterpret_cast<uint32_t *>(smem + off); off += STORE_SUB_WORDS * 4;
+    uint8_t *pairs = smem + off; off += STORE_SUB_WORDS / 2;
+    uint32_t *ctl = reinterpret_cast<uint32_t *>(smem + off); off += 32;   // [0] the row's current state, [2] next batch, [3] number of batches, [4] state of the staged tables
+    const Staging stg{ctl, smem, D.table_blob, n16};
+    Scratch sc;
+    sc.cap = sc_cap;
+    sc.w = reinterpret_cast<uint32_t *>(smem + off) + (size_t)wave * (2 * sc_cap + aut_hash_places(sc_cap));
+    sc.o = sc.w + sc_cap;
+    sc.h = sc.o + sc_cap;
+    const bool use_cache = (rin.flags & STORE_ROW_CACHE) != 0 && rin.n_ent <= (uint32_t)AUT_ENT_LDS;
+    const uint32_t n_pend_lds = rin.n_pending < (uint32_t)STORE_PENDING_LDS ? rin.n_pending : (uint32_t)STORE_PENDING_LDS;
+    uint32_t start = rin.start;
+    if (rin.flags & STORE_ROW_IMPORTED) start = a.store_import_root[row];
+    if (use_cache) for (uint32_t k = tid; k < rin.n_ent; k += STORE_BLOCK) l_ent[k] = a.entries[rin.ent_off + k];
+    for (uint32_t k = tid; k < ncls; k += STORE_BLOCK) l_rep[k] = D.cls_rep[k];
+    for (uint32_t k = tid; k < n_pend_lds; k += STORE_BLOCK) l_pend[k] = a.store_pending[rin.pend_off + k];
+    for (uint32_t k = tid; k < LC_ENTRIES; k += STORE_BLOCK) lc[k] = LC_EMPTY;
+    if (tid == 0) ctl[4] = 0;
+    uint32_t steps = 0;
+    uint32_t *errors = &a.counters[2];
+    const uint32_t n_groups = (Wr + AUT_GROUP_WORDS - 1) / AUT_GROUP_WORDS, groups_per_pass = STORE_SUB_WORDS / AUT_GROUP_WORDS;
+    for (uint32_t j0 = 0; blockIdx.x + j0 * gridDim.x < n_groups; j0 += groups_per_pass) {
+        auto word_of = [&](uint32_t t) -> uint32_t {
+            const uint32_t grp = blockIdx.x + (j0 + t / AUT_GROUP_WORDS) * gridDim.x;
+            return grp < n_groups ? grp * AUT_GROUP_WORDS + t % AUT_GROUP_WORDS : 0xFFFFFF00u;
+        };
+        if (tid == 0) { ctl[2] = 0; ctl[3] = 0; }
+        if (tid < STORE_SUB_WORDS) { vslice[tid] = 0; cslice[tid] = use_cache ? 0u : 0xFFFFFFFFu; }
+        __syncthreads();                                     // also: tables, cache rows and pending bytes are in place
+        if (j0 == 0 && wave == STORE_WAVES - 1) {
+            // ---- the row's current state: walk the bytes fed since `start` was its state ----
+            uint32_t s = start;
+            bool bad = s == 0 || (s >= G.cap_states && s != AT_SINK);
+            for (uint32_t k = 0; k < rin.n_pending && !bad; k++) {
+                const uint32_t cl = k < (uint32_t)STORE_PENDING_LDS ? (uint32_t)l_pend[k] : (uint32_t)a.store_pending[rin.pend_off + k];
+                if (s == AT_SINK || cl >= ncls) { bad = true; break; }
+                const uint32_t t = store_lookup_uniform(T, G, l_rep, sc, stg, errors, &steps, s, cl, lane);
+                if (t == AT_DEAD || t == AT_FAIL) { bad = true; break; }   // the host accepted these bytes: a dead end here is an error
+                s = t;
+            }
+            if (bad) { s = AT_FAIL; if (lane == 0) atomicAdd(errors, 1u); }
+            if (lane == 0) { ctl[0] = s; if (blockIdx.x == 0) a.store_row_out[row] = s; }
+        }
+        // ---- merge the token-mask cache rows (all threads: word slot tid % SUB, cache rows tid / SUB, + 4, ...) ----
+        if (use_cache) {
+            const uint32_t t = tid % STORE_SUB_WORDS, w = word_of(t);
+            uint32_t v = 0, c = 0;
+            if (w < Wr)
+                for (uint32_t k = tid / STORE_SUB_WORDS; k < rin.n_ent; k += STORE_BLOCK / STORE_SUB_WORDS) {
+                    const size_t r = (size_t)l_ent[k] * Wr + w;
+                    v |= D.ci_valid[r]; c |= D.ci_cd[r];
+                }
+            if (v) atomicOr(&vslice[t], v);
+            if (c) atomicOr(&cslice[t], c);
+        }
+        __syncthreads();
+        const uint32_t root = ctl[0];
+        const bool root_ok = root < AT_FAIL;                 // AT_SINK: nothing can follow; AT_FAIL: the call fails
+        if (wave == 0) {                                     // the first wavefront lists the word pairs that hold undecided strings
+            const bool act = lane < (uint32_t)STORE_SUB_WORDS / 2;
+            uint32_t want[2] = {0, 0};
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                if (!act) continue;
+                const uint32_t w = word_of(2 * tid + h), r0 = w * 32u;
+                want[h] = cslice[2 * tid + h] & ~vslice[2 * tid + h];
+                if (w >= Wr || r0 >= n_strings || !root_ok) want[h] = 0;
+                else if (n_strings - r0 < 32u) want[h] &= (1u << (n_strings - r0)) - 1u;
+                cslice[2 * tid + h] = want[h];
+                if (!root_ok) vslice[2 * tid + h] = 0;       // no string can follow a finished sentence
+            }
+            const unsigned long long nz = __ballot((want[0] | want[1]) != 0);
+            if (want[0] | want[1]) pairs[__popcll(nz & ((1ull << lane) - 1ull))] = (uint8_t)tid;
+            uint32_t cnt = (uint32_t)(__popc(want[0]) + __popc(want[1]));
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d);
+            if (lane == 0) { ctl[3] = (uint32_t)__popcll(nz); if (cnt) atomicAdd(&a.counters[1], cnt); }
+        }
+        __syncthreads();
+        const uint32_t n_pairs = ctl[3];
+        // ---- one lane per string through the table, 64 neighbouring ranks at a time ----
+        for (;;) {
+            uint32_t b = 0;
+            if (lane == 0) b = atomicAdd(&ctl[2], 1u);
+            b = (uint32_t)__builtin_amdgcn_readfirstlane((int)b);
+            if (b >= n_pairs) break;
+            const uint32_t pair = pairs[b];
+            const uint32_t rank = word_of(2 * pair) * 32u + lane;
+            bool live = ((cslice[2 * pair + (lane >> 5)] >> (lane & 31u)) & 1u) != 0;
+            uint32_t soff = 0, len = 0;
+            Str16 c16{{0, 0, 0, 0}};
+            if (live) { soff = D.str_off[rank]; len = D.str_off[rank + 1] - soff; c16 = D.str16[rank]; }
+            live = live && len > 0;
+            uint32_t s = root, pos = 0, c = 0, spins = 0, t = AT_BUSY;
+            bool ok = false, fail = false;
+            for (;;) {
+                while (live) {                               // every lane follows its own string as far as the table goes
+                    if (pos < 16u) {
+                        const uint32_t q = pos >> 2;
+                        const uint32_t word = q == 0 ? c16.w[0] : (q == 1 ? c16.w[1] : (q == 2 ? c16.w[2] : c16.w[3]));
+                        c = (word >> ((pos & 3u) * 8u)) & 0xFFu;
+                    } else c = D.str_cls[soff + pos];
+                    const uint32_t key = s * ncls + c;
+                    const uint32_t slot = (key * 0x9E3779B1u) >> (32 - LC_BITS);
+                    const unsigned long long e = __hip_atomic_load(&lc[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    if ((uint32_t)(e >> 32) == key) t = (uint32_t)e;
+                    else {
+                        t = t_load(&G.trans[key]);
+                        if (t_final(t) && t != AT_FAIL) __hip_atomic_store(&lc[slot], ((unsigned long long)key << 32) | t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    }
+                    if (t < AT_FAIL) { s = t; pos++; if (pos == len) { ok = true; live = false; } }
+                    else if (t == AT_DEAD) live = false;
+                    else if (t == AT_SINK) { ok = pos + 1 == len; live = false; }
+                    else if (t == AT_FAIL) { fail = true; live = false; }
+                    else break;                              // not there yet
+                }
+                const unsigned long long waiting = __ballot(live);
+                if (!waiting) break;
+                // one of the waiting lanes' transitions is claimed and computed here; the other lanes look again afterwards
+                const unsigned long long missing = __ballot(live && t == AT_NONE);
+                bool progress = false;
+                if (missing) {
+                    const int l = __ffsll((long long)missing) - 1;
+                    const uint32_t rs = (uint32_t)__builtin_amdgcn_readlane((int)s, l), rc = (uint32_t)__builtin_amdgcn_readlane((int)c, l);
+                    uint32_t old = 0;
+                    if (lane == 0) old = atomicCAS(&G.trans[rs * ncls + rc], (uint32_t)AT_NONE, (uint32_t)AT_BUSY);
+                    old = (uint32_t)__builtin_amdgcn_readfirstlane((int)old);
+                    if (old == AT_NONE) {
+                        const uint32_t r = store_transition(T, G, l_rep, sc, stg, errors, rs, rc, lane);
+                        steps++;
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                        if (lane == 0) g_store_release(&G.trans[rs * ncls + rc], r);
+                        progress = true;
+                    } else progress = old != AT_BUSY;        // somebody else has it, or has finished it meanwhile
+                }
+                if (progress) spins = 0;
+                else {
+                    __builtin_amdgcn_s_sleep(8);
+                    if (++spins > (uint32_t)AUT_SPIN_LIMIT) { fail = fail || live; live = false; }   // bounded wait
+                }
+            }
+            const unsigned long long okb = __ballot(ok);     // this wavefront is the only one that touches the pair's two words
+            if (lane == 0 && okb) { vslice[2 * pair] |= (uint32_t)okb; vslice[2 * pair + 1] |= (uint32_t)(okb >> 32); }
+            const unsigned long long fm = __ballot(fail);    // no room in the scratch or the store, or a wait that did not end
+            if (lane == 0 && fm) atomicAdd(errors, (uint32_t)__popcll(fm));
+        }
+        __syncthreads();
+        if (tid < STORE_SUB_WORDS) { const uint32_t w = word_of(tid); if (w < Wr) a.rank_mask[(size_t)row * Wr + w] = vslice[tid]; }
+    }
+    if (lane == 0 && steps) atomicAdd(&a.counters[3], steps);
+}
+
+// Clear the store: every transition unknown, every header unpublished, the hash table empty; then the
+// state of the empty prefix, whose items started in that very set.
+__global__ __launch_bounds__(256) void store_clear_kernel(StoreView G, uint32_t ncls, const uint2 *root_items, uint32_t n_root) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x, stride = (size_t)gridDim.x * 256;
+    for (size_t k = i; k < (size_t)G.cap_states * ncls; k += stride) G.trans[k] = AT_NONE;
+    for (size_t k = i; k < G.cap_states; k += stride) G.hdr[k] = k == STORE_ROOT ? make_uint2(0, n_root) : make_uint2(0, UNPUBLISHED);
+    for (size_t k = i; k <= G.intern_mask; k += stride) G.intern[k] = 0;
+    for (size_t k = i; k < n_root; k += stride) G.arena[k] = make_uint2(root_items[k].x, STORE_ROOT);
+    if (i == 0) { G.ctl[0] = STORE_ROOT + 1; G.ctl[1] = n_root; G.ctl[2] = 0; G.ctl[3] = 0; }
+}
+
+// Bring rows whose state the store does not know (after the store was cleared, or after more bytes than
+// a call carries) in from their host charts: every set of the packed chart becomes a state of its own,
+// origins renamed from set indices to the new names.  One block per such row.
+__global__ __launch_bounds__(256) void store_import_kernel(MaskArgs a, const uint32_t *import_rows, uint32_t n_import) {
+    const StoreView &G = a.store;
+    __shared__ uint32_t base[2];
+    const uint32_t r = import_rows[blockIdx.x];
+    const RowChart rc = a.rows[blockIdx.x];
+    if (threadIdx.x == 0) { base[0] = atomicAdd(&G.ctl[0], rc.n_sets); base[1] = atomicAdd(&G.ctl[1], rc.n_items); }
+    __syncthreads();
+    const uint32_t id0 = base[0], at0 = base[1];
+    if (id0 > G.cap_states - rc.n_sets || id0 + rc.n_sets > G.cap_states || at0 > G.cap_items - rc.n_items || rc.n_items > G.cap_items) {
+        if (threadIdx.x == 0) { atomicAdd(&G.ctl[2], 1u); atomicAdd(&a.counters[2], 1u); a.store_import_root[r] = AT_FAIL; }
+        return;
+    }
+    const uint32_t *so = a.set_off + rc.set_base;
+    const uint2 *it = reinterpret_cast<const uint2 *>(a.items) + rc.item_base;
+    for (uint32_t k = threadIdx.x; k < rc.n_items; k += 256) { const uint2 x = it[k]; G.arena[at0 + k] = make_uint2(x.x, id0 + x.y); }
+    for (uint32_t k = threadIdx.x; k < rc.n_sets; k += 256) G.hdr[id0 + k] = make_uint2(at0 + so[k], so[k + 1] - so[k]);
+    if (threadIdx.x == 0) a.store_import_root[r] = id0 + rc.n_sets - 1;
+    (void)n_import;
+}
+
+}  // namespace
+
+hipError_t prepare_store_kernels() {
+    const int max_lds = 160 * 1024;
+    hipError_t e;
+#define SET_ATTR(k) if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k), hipFuncAttributeMaxDynamicSharedMemorySize, max_lds)) != hipSuccess) return e
+    SET_ATTR(mask_store_kernel<0>); SET_ATTR(mask_store_kernel<1>); SET_ATTR(mask_store_kernel<2>);
+#undef SET_ATTR
+    return hipSuccess;
+}
+
+uint32_t store_lds_bytes(const DeviceTables &t, int mode, int scratch) {
+    return table_bytes(t, mode) + LC_ENTRIES * 8 + AUT_ENT_LDS * 4 + 256 + STORE_PENDING_LDS + 2 * STORE_SUB_WORDS * 4 + STORE_SUB_WORDS / 2 + 32 +
+           STORE_WAVES * ((uint32_t)scratch * 8 + aut_hash_places((uint32_t)scratch) * 4);
+}
+
+hipError_t launch_mask_store(const MaskArgs &a, hipStream_t s) {
+    const uint32_t lds = store_lds_bytes(a.tab, a.mode, a.aut_scratch);
+    dim3 grid(a.aut_parts, a.batch);
+    if (a.mode == 0) hipLaunchKernelGGL(mask_store_kernel<0>, grid, dim3(STORE_BLOCK), lds, s, a);
+    else if (a.mode == 1) hipLaunchKernelGGL(mask_store_kernel<1>, grid, dim3(STORE_BLOCK), lds, s, a);
+    else hipLaunchKernelGGL(mask_store_kernel<2>, grid, dim3(STORE_BLOCK), lds, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_store_clear(const StoreView &G, uint32_t ncls, const void *root_items, uint32_t n_root, hipStream_t s) {
+    hipLaunchKernelGGL(store_clear_kernel, dim3(2048), dim3(256), 0, s, G, ncls, (const uint2 *)root_items, n_root);
+    return hipGetLastError();
+}
+
+hipError_t launch_store_import(const MaskArgs &a, const uint32_t *import_rows, uint32_t n_import, hipStream_t s) {
+    if (n_import == 0) return hipSuccess;
+    hipLaunchKernelGGL(store_import_kernel, dim3(n_import), dim3(256), 0, s, a, import_rows, n_import);
+    return hipGetLastError();
+}
+
+}  // namespace zf

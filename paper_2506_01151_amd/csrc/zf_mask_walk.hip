@@ -678,6 +678,7 @@ __global__ __launch_bounds__(FINISH_BLOCK) void finish_kernel(MaskArgs a, uint32
         if (tid < 8) a.counters_next[tid] = 0;
         if (tid == 0) {                                   // counters first, then the word the host waits for
             for (int i = 0; i < 4; i++) a.host_status[i] = __hip_atomic_load(&a.counters[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (a.store.ctl) for (int i = 0; i < 3; i++) a.host_status[5 + i] = __hip_atomic_load(&a.store.ctl[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(&a.host_status[4], a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
