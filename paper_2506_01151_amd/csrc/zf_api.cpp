@@ -63,7 +63,7 @@ struct DeviceSide {
     struct CallRecord {                              // what to note in the states once the call in this slot has reported
         bool active = false;
         uint32_t epoch = 0;
-        std::vector<zf_state *> st; std::vector<uint32_t> gen; std::vector<uint64_t> upto;
+        std::vector<std::shared_ptr<StateLink>> st; std::vector<uint32_t> gen; std::vector<uint64_t> upto;
     } rec[N_SLOTS];
     zf_mask_report report{};
     uint32_t call_parity = 0;            // which of the two counter sets the next call uses
@@ -351,6 +351,7 @@ int zf_state_new(zf_engine *e, zf_state **out) {
     zf_state *s = new (std::nothrow) zf_state();
     if (!s) return fail(ZF_ERR_OOM, "out of memory");
     s->eng = e;
+    s->link = std::make_shared<StateLink>(StateLink{s});
     *out = s;
     return zf_state_reset(s);
 }
@@ -381,13 +382,13 @@ int zf_state_clone(const zf_state *s, zf_state **out) {
     if (!s || !out) return fail(ZF_ERR_INVALID_ARG, "null argument");
     zf_state *c = new (std::nothrow) zf_state(*s);
     if (!c) return fail(ZF_ERR_OOM, "out of memory");
+    c->link = std::make_shared<StateLink>(StateLink{c});
     *out = c;
     return ZF_OK;
 }
 
 void zf_state_destroy(zf_state *s) {
-    if (s && s->eng && s->eng->dev)                       // calls in flight must not write to a state that is gone
-        for (auto &rec : s->eng->dev->rec) if (rec.active) for (auto &p : rec.st) if (p == s) p = nullptr;
+    if (s && s->link) s->link->s = nullptr;               // calls in flight must not write to a state that is gone (the engine may be gone already)
     delete s;
 }
 
@@ -1024,7 +1025,7 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
     }
     DeviceSide::CallRecord &rec = d->rec[slot];
     rec.active = true; rec.epoch = d->store_epoch;
-    rec.st.assign(nb, nullptr); rec.gen.assign(nb, 0); rec.upto.assign(nb, 0);
+    rec.st.assign(nb, std::shared_ptr<StateLink>()); rec.gen.assign(nb, 0); rec.upto.assign(nb, 0);
     uint32_t n_cache_rows = 0;
     {
         uint8_t *h = (uint8_t *)d->h_stage[slot];
@@ -1043,13 +1044,17 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
             const Chart &c = st->chart;
             StoreRow sr{};
             sr.ent_off = en_at;
-            if (use_cache) { sr.n_ent = current_set_entries(e->tab, c, ents + en_at); sr.flags |= STORE_ROW_CACHE; }
+            if (use_cache) {
+                sr.n_ent = current_set_entries(e->tab, c, ents + en_at); sr.flags |= STORE_ROW_CACHE;
+                if (sr.n_ent <= (uint32_t)STORE_ROW_ENT) memcpy(sr.ent, ents + en_at, 4 * sr.n_ent);
+            }
             en_at += sr.n_ent;
             n_cache_rows += sr.n_ent;
             const bool known = st->dev_id == STORE_ROOT_ID || (st->dev_id != 0 && st->dev_epoch == d->store_epoch);
             if (known) {
                 sr.start = st->dev_id; sr.n_pending = (uint32_t)st->pending.size(); sr.pend_off = pe_at;
                 if (sr.n_pending) memcpy(pend + pe_at, st->pending.data(), sr.n_pending);
+                if (sr.n_pending <= (uint32_t)STORE_ROW_PEND) memcpy(sr.pend, st->pending.data(), sr.n_pending);
                 pe_at += sr.n_pending;
             } else {
                 const std::vector<uint32_t> &k = packed[miss_rows[r]];
@@ -1063,7 +1068,7 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
             }
             srow[r] = sr;
             dst[r] = sc ? row_slot[miss_rows[r]] : miss_rows[r];
-            rec.st[r] = st; rec.gen[r] = st->generation; rec.upto[r] = st->fed_total;
+            rec.st[r] = st->link; rec.gen[r] = st->generation; rec.upto[r] = st->fed_total;
         }
     }
     const size_t need_rank = (size_t)std::max(nb, 1) * d->tab.Wr;
@@ -1108,8 +1113,37 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
         while (scratch > 32 && store_lds_bytes(d->tab, d->mode, scratch) > 160u * 1024u) scratch -= 32;
         if (store_lds_bytes(d->tab, d->mode, scratch) > 160u * 1024u) return fail(ZF_ERR_INVALID_ARG, "the grammar tables leave no LDS for the mask kernel");
         a.aut_scratch = scratch;
-        const int n_sub = (d->tab.Wr + STORE_SUB_WORDS - 1) / STORE_SUB_WORDS;
-        a.aut_parts = std::max(1, std::min(n_sub, (STORE_BLOCKS_PER_CU * std::max(1, d->cus) + std::max(nb, 1) - 1) / std::max(nb, 1)));
+        // Blocks per row.  A wavefront takes groups of 4 words of the row's bitmap, four groups per pass, and the undecided
+        // strings among them 64 at a time; rows differ by orders of magnitude in how many strings their token-mask cache
+        // rows leave undecided, which the compiler counted per cache row.  A row gets blocks in proportion to passes +
+        // 2 x batches, at least one, at most one wavefront per group; all rows together about what the chip holds at once.
+        const int n_groups = (d->tab.Wr + AUT_GROUP_WORDS - 1) / AUT_GROUP_WORDS;
+        const int max_parts = std::max(1, (n_groups + STORE_WAVES - 1) / STORE_WAVES);
+        const int budget = std::max(nb, STORE_BLOCKS_PER_CU * std::max(1, d->cus));
+        if (nb > STORE_GRID_ROWS) {
+            a.store_uniform_parts = std::max(1, std::min((n_groups + 4 * STORE_WAVES - 1) / (4 * STORE_WAVES), budget / nb));
+        } else {
+            double weight[STORE_GRID_ROWS], sum = 0;
+            for (int r = 0; r < nb; r++) {
+                const Chart &c = states[miss_rows[r]]->chart;
+                uint32_t ent[64];
+                double und = d->tab.n_strings;
+                if (use_cache && c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1] <= 64) {
+                    const uint32_t n = current_set_entries(e->tab, c, ent);
+                    und = 0;
+                    for (uint32_t k = 0; k < n; k++) und += e->trie.ci_undecided[ent[k]];
+                    und = std::min<double>(und, d->tab.n_strings);
+                }
+                weight[r] = n_groups / 4.0 + und / 32.0;
+                sum += weight[r];
+            }
+            uint32_t at = 0;
+            for (int r = 0; r < nb; r++) {
+                a.store_first_block[r] = (uint16_t)at;
+                at += (uint32_t)std::min<double>(max_parts, std::max(1.0, budget * weight[r] / sum));
+            }
+            a.store_first_block[nb] = (uint16_t)at;
+        }
     }
     const bool prof = d->profiling;
     d->report.chart_bytes = (int64_t)total;
@@ -1193,10 +1227,11 @@ int zf_mask_wait(zf_engine *e, void *hip_stream) {
             DeviceSide::CallRecord &rec = d->rec[k];
             if (!rec.active) continue;
             rec.active = false;
+            struct Release { DeviceSide::CallRecord &r; ~Release() { r.st.clear(); } } release{rec};
             const bool good = st[8 * k + 2] == 0 && rec.epoch == d->store_epoch;
             const uint32_t *out = d->h_row_out + (size_t)k * MAX_BATCH;
             for (size_t r = 0; r < rec.st.size() && good; r++) {
-                zf_state *s = rec.st[r];
+                zf_state *s = rec.st[r] ? rec.st[r]->s : nullptr;
                 if (!s || s->generation != rec.gen[r] || out[r] == 0 || (out[r] >= d->store.cap_states && out[r] != 0xFFFFFFFDu)) continue;
                 if (rec.upto[r] < s->pending_base) continue;              // a later call's result is already in
                 const size_t drop = std::min<size_t>((size_t)(rec.upto[r] - s->pending_base), s->pending.size());

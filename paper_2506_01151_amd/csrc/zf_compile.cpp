@@ -414,6 +414,9 @@ void build_token_mask_cache(const Tables &t, Trie &tr) {
             for (int w = 0; w < Wr; w++) { V[w] |= v[w]; C[w] |= c[w]; }
         }
     }
+    tr.ci_undecided.assign(rows, 0);                     // per row: strings it leaves to the parser (the host sizes a call's grid by it)
+    for (int r = 0; r < rows; r++)
+        for (int w = 0; w < Wr; w++) tr.ci_undecided[r] += (uint32_t)__builtin_popcount(tr.ci_cd[(size_t)r * Wr + w] & ~tr.ci_valid[(size_t)r * Wr + w]);
 }
 
 }  // namespace zf

@@ -1,6 +1,7 @@
 // Host-side structures of the library (grammar tables, trie, chart, engine, state).
 #pragma once
 #include <cstdint>
+#include <memory>
 #include <string>
 #include <vector>
 #include "zf_device.h"
@@ -68,6 +69,7 @@ struct Trie {
     int chunk_ranks = 32;
     int Wr = 0;                       // words per row of a rank-ordered bitmap
     std::vector<uint32_t> ci_valid, ci_cd;   // [(Q + N) * Wr]
+    std::vector<uint32_t> ci_undecided;      // [Q + N] strings of the row that are in ci_cd but not in ci_valid
 };
 // Context-independent token-mask cache (Section 4.3): per DFA state and per nonterminal, which
 // strings are decided by the terminal alone and which need the parser.
@@ -105,8 +107,12 @@ struct zf_engine {
     struct DeviceSide *dev = nullptr;   // null when compiled with device = -1
 };
 
+struct zf_state;
+namespace zf { struct StateLink { zf_state *s; }; }   // what a mask call in flight holds of a state: cleared when the state is destroyed
+
 struct zf_state {
     zf_engine *eng;
+    std::shared_ptr<zf::StateLink> link;
     zf::Chart chart;
     bool accepting = false;
     int64_t items_created = 0, bytes_fed = 0;

@@ -55,6 +55,7 @@ static const int STORE_LC_BITS = ZF_STORE_LC_BITS;       // log2 of the entries 
 #define ZF_STORE_BLOCKS_PER_CU 3
 #endif
 static const int STORE_BLOCKS_PER_CU = ZF_STORE_BLOCKS_PER_CU;   // blocks per compute unit the grid aims at (the chip should hold them all at once)
+static const int STORE_GRID_ROWS = 64;          // batches up to this size get a block count per row
 static const int STORE_PENDING_LDS = 256;       // pending bytes of a row a block keeps in LDS (more are read from the upload)
 static const int STORE_PENDING_MAX = 4096;      // beyond this many bytes since its state was last known a row comes in through its chart again
 static const uint32_t STORE_ROW_CACHE = 1u;     // StoreRow::flags: the token-mask cache rows of the row are listed
@@ -67,14 +68,18 @@ struct StoreView {
     uint32_t *ctl;              // [0] states handed out (the next name), [1] items handed out, [2] requests the store had no room for
     uint32_t cap_states, cap_items, intern_mask;
 };
-struct StoreRow {               // one row of a call
-    uint32_t start;             // the state the row was last known to be in
-    uint32_t n_pending;         // bytes (as byte classes) fed to the row since then ...
-    uint32_t pend_off;          // ... at this offset of the call's pending bytes
-    uint32_t n_ent, ent_off;    // token-mask-cache rows of the row's current set (in MaskArgs::entries)
-    uint32_t flags;
-    uint32_t pad[2];
+static const int STORE_ROW_ENT = 10, STORE_ROW_ENT_AT = 6;      // token-mask-cache rows a record holds inline, and the word they start at
+static const int STORE_ROW_PEND = 64, STORE_ROW_PEND_AT = 16;   // pending bytes a record holds inline, and the word they start at
+struct StoreRow {               // one row of a call: 128 bytes, read by a wavefront with one load (lane k = word k)
+    uint32_t start;             // [0] the state the row was last known to be in
+    uint32_t n_pending;         // [1] bytes (as byte classes) fed to the row since then: inline when they fit ...
+    uint32_t pend_off;          // [2] ... else at this offset of the call's pending bytes
+    uint32_t n_ent, ent_off;    // [3] [4] token-mask-cache rows of the row's current set: inline when they fit, else in MaskArgs::entries
+    uint32_t flags;             // [5]
+    uint32_t ent[STORE_ROW_ENT];
+    uint8_t pend[STORE_ROW_PEND];
 };
+static_assert(sizeof(StoreRow) == 128, "a wavefront reads a row's record as 32 words");
 
 struct MaskArgs {
     DeviceTables tab;
@@ -83,6 +88,11 @@ struct MaskArgs {
     const uint8_t *store_pending;
     uint32_t *store_import_root;       // [batch] device memory: written by the import kernel
     uint32_t *store_row_out;           // [batch] pinned host memory: the state every row is in after this call's walk
+    // The grid of the store kernel is one-dimensional; a row's blocks are store_first_block[row] .. store_first_block[row + 1]
+    // (the host gives rows whose token-mask cache leaves more strings undecided more blocks), or, for batches beyond
+    // STORE_GRID_ROWS rows, store_uniform_parts blocks each.
+    uint16_t store_first_block[STORE_GRID_ROWS + 2];
+    int32_t store_uniform_parts;       // not 0: every row has this many blocks
     const RowChart *rows;      // [batch]
     const uint32_t *set_off;   // shared CSR offsets of all rows' sets
     const Item *items;         // shared item array of all rows

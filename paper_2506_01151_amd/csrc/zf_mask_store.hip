@@ -46,10 +46,14 @@ __device__ __forceinline__ uint32_t t_load(const uint32_t *p) {
     return t;
 }
 
+struct Staging { uint32_t *ctl; uint8_t *smem; const uint8_t *blob; uint32_t n16; uint8_t *rep; const uint8_t *rep_src; uint32_t ncls; };   // what ensure_tables needs
 // The grammar tables are needed only by a wavefront that computes a transition, which is rare once the automaton has
 // grown: the first such wavefront of a block copies them into LDS (ctl[4]: 0 = not there, 1 = being copied, 2 = there).
-__device__ __forceinline__ bool ensure_tables(uint32_t *ctl, uint8_t *smem, const uint8_t *blob, uint32_t n16, uint32_t lane) {
-    if (n16 == 0) return true;
+__device__ __forceinline__ bool ensure_tables(const Staging &g, uint32_t lane) {
+    uint32_t *ctl = g.ctl;
+    uint8_t *smem = g.smem;
+    const uint8_t *blob = g.blob;
+    const uint32_t n16 = g.n16;
     uint32_t st = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_load(&ctl[4]));
     if (st == 0) {
         uint32_t old = 0;
@@ -59,6 +63,7 @@ __device__ __forceinline__ bool ensure_tables(uint32_t *ctl, uint8_t *smem, cons
             const uint4 *src = reinterpret_cast<const uint4 *>(blob);
             uint4 *dst = reinterpret_cast<uint4 *>(smem);
             for (uint32_t k = lane; k < n16; k += 64) dst[k] = src[k];
+            for (uint32_t k = lane; k < g.ncls; k += 64) g.rep[k] = g.rep_src[k];   // one byte of every class
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             if (lane == 0) lds_store(&ctl[4], 2u);
             return true;
@@ -87,7 +92,6 @@ struct StoreSets {             // resolves the name of a set to its items (devic
 };
 
 struct Scratch { uint32_t *w, *o, *h; uint32_t cap; };   // one wavefront's set under construction (+ hash table of the wide step)
-struct Staging { uint32_t *ctl; uint8_t *smem; const uint8_t *blob; uint32_t n16; };   // what ensure_tables needs
 
 // true when state `id` holds exactly the `kept` items in the scratch
 __device__ __forceinline__ bool same_content(const StoreView &G, uint32_t id, const Scratch &sc, uint32_t kept, uint32_t lane) {
@@ -106,9 +110,10 @@ __device__ __forceinline__ bool same_content(const StoreView &G, uint32_t id, co
 // The transition of state s on class cl: one Earley byte step, then the state that holds the
 // resulting set -- found by content in the store's hash table, or made.  Uniform over the wavefront.
 // Returns a state id, AT_DEAD, AT_SINK or AT_FAIL (no room in the scratch or in the store).
-__device__ __forceinline__ uint32_t store_transition(const TV &T, const StoreView &G, const uint8_t *rep, const Scratch &sc, const Staging &stg, uint32_t *errors,
+__device__ __forceinline__ uint32_t store_transition(const TV &T, const StoreView &G, const Scratch &sc, const Staging &stg, uint32_t *errors,
                                                      uint32_t s, uint32_t cl, uint32_t lane) {
-    if (!ensure_tables(stg.ctl, stg.smem, stg.blob, stg.n16, lane)) return AT_FAIL;
+    if (!ensure_tables(stg, lane)) return AT_FAIL;
+    const uint8_t *rep = stg.rep;
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");      // s and every set it refers to were released before the entry that led here
     const StoreSets S{G, errors};
     uint32_t nnew = 0, kept = 0;
@@ -167,7 +172,7 @@ __device__ __forceinline__ uint32_t store_transition(const TV &T, const StoreVie
 }
 
 // Look the transition (s, cl) up for the whole wavefront (uniform arguments), computing it if nobody has.
-__device__ __forceinline__ uint32_t store_lookup_uniform(const TV &T, const StoreView &G, const uint8_t *rep, const Scratch &sc, const Staging &stg, uint32_t *errors,
+__device__ __forceinline__ uint32_t store_lookup_uniform(const TV &T, const StoreView &G, const Scratch &sc, const Staging &stg, uint32_t *errors,
                                                          uint32_t *steps, uint32_t s, uint32_t cl, uint32_t lane) {
     uint32_t *entry = G.trans + (size_t)s * T.ncls + cl;
     for (uint32_t spins = 0; spins < (uint32_t)AUT_SPIN_LIMIT; spins++) {
@@ -177,7 +182,7 @@ __device__ __forceinline__ uint32_t store_lookup_uniform(const TV &T, const Stor
             if (lane == 0) old = atomicCAS(entry, (uint32_t)AT_NONE, (uint32_t)AT_BUSY);
             old = (uint32_t)__builtin_amdgcn_readfirstlane((int)old);
             if (old == AT_NONE) {
-                const uint32_t r = store_transition(T, G, rep, sc, stg, errors, s, cl, lane);
+                const uint32_t r = store_transition(T, G, sc, stg, errors, s, cl, lane);
                 ++*steps;
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
                 if (lane == 0) g_store_release(entry, r);
@@ -193,140 +198,171 @@ __device__ __forceinline__ uint32_t store_lookup_uniform(const TV &T, const Stor
 
 __host__ __device__ inline uint32_t store_round16(uint32_t x) { return (x + 15u) & ~15u; }
 
-// Grid (parts, rows), blocks of STORE_WAVES wavefronts.  A block (a) stages the grammar tables, the row's
-// token-mask-cache row numbers and pending bytes; (b) its last wavefront walks the row's pending bytes
-// (the tokens fed since the row's state was last known) from the row's state to its current state,
-// while all threads merge the token-mask cache rows of the block's share of the rank-ordered bitmap
-// (Section 4.3); (c) its wavefronts take the undecided strings, 64 neighbouring ranks at a time, one
-// lane per string, through the transition table -- first the block's cache of entries in LDS, then
-// device memory, and an Earley byte step for what nobody has computed yet.
+// Grid (parts, rows), blocks of STORE_WAVES wavefronts.  The wavefronts of a block work on their own; what they share
+// is the block's LDS cache of table entries and (once somebody needs them) the staged grammar tables.  A wavefront
+//  (a) reads its row's record -- start state, pending bytes, token-mask-cache row numbers: one 128-byte load --
+//  (b) requests the token-mask cache words (Section 4.3) of its share of the rank-ordered bitmap, 16 words at a time,
+//      and while they are on their way walks the row's pending bytes (the tokens fed since the row's state was last
+//      known) from that state to the row's current state, then warms the LDS cache with the current state's table row,
+//  (c) takes the undecided strings of those words, 64 at a time, one lane per string, through
+//      the transition table: first the LDS cache, then device memory, and an Earley byte step for what nobody has
+//      computed yet; (d) stores its 16 verdict words.  No block-wide barrier after the first one.
 template <int MODE>
 __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a) {
     extern __shared__ __align__(16) uint8_t smem[];
     const DeviceTables &D = a.tab;
     const StoreView &G = a.store;
-    const uint32_t tid = threadIdx.x, row = blockIdx.y, wave = tid >> 6, lane = tid & 63;
+    const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const uint32_t Wr = (uint32_t)D.Wr, n_strings = (uint32_t)D.n_strings, ncls = (uint32_t)D.n_cls;
-    if (blockIdx.x >= (Wr + AUT_GROUP_WORDS - 1) / AUT_GROUP_WORDS) return;
+    const uint32_t n_groups = (Wr + AUT_GROUP_WORDS - 1) / AUT_GROUP_WORDS;
+    uint32_t row, part, parts;                               // which row this block belongs to, and which of the row's blocks it is
+    if (a.store_uniform_parts) { parts = (uint32_t)a.store_uniform_parts; row = blockIdx.x / parts; part = blockIdx.x % parts; }
+    else {
+        row = 0;
+        for (uint32_t r = 1; r < (uint32_t)a.batch; r++) row += blockIdx.x >= a.store_first_block[r] ? 1u : 0u;   // first_block is ascending
+        part = blockIdx.x - a.store_first_block[row];
+        parts = a.store_first_block[row + 1] - a.store_first_block[row];
+    }
+    const uint32_t unit = part * STORE_WAVES + wave, n_units = parts * STORE_WAVES;   // a unit = one wavefront of one of the row's blocks
+    if (part * STORE_WAVES >= n_groups) return;              // uniform over the block: not even its first wavefront has a group
+    // the row's record: lane k holds word k
+    const uint32_t rec = lane < sizeof(StoreRow) / 4 ? reinterpret_cast<const uint32_t *>(a.store_rows + row)[lane] : 0u;
     TV T;
     uint32_t off = table_view<MODE>(D, smem, T);
     const uint32_t n16 = off / 16;
-    const StoreRow rin = a.store_rows[row];
-    const uint32_t sc_cap = (uint32_t)a.aut_scratch;
-    unsigned long long *lc = reinterpret_cast<unsigned long long *>(smem + off); off += LC_ENTRIES * 8;
-    uint32_t *l_ent = reinterpret_cast<uint32_t *>(smem + off); off += AUT_ENT_LDS * 4;
     uint8_t *l_rep = smem + off; off += 256;
-    uint8_t *l_pend = smem + off; off += STORE_PENDING_LDS;
-    uint32_t *vslice = reinterpret_cast<uint32_t *>(smem + off); off += STORE_SUB_WORDS * 4;
-    uint32_t *cslice = reinterpret_cast<uint32_t *>(smem + off); off += STORE_SUB_WORDS * 4;
-    uint8_t *pairs = smem + off; off += STORE_SUB_WORDS / 2;
-    uint32_t *ctl = reinterpret_cast<uint32_t *>(smem + off); off += 32;   // [0] the row's current state, [2] next batch, [3] number of batches, [4] state of the staged tables
-    const Staging stg{ctl, smem, D.table_blob, n16};
+    unsigned long long *lc = reinterpret_cast<unsigned long long *>(smem + off); off += LC_ENTRIES * 8;
+    uint32_t *ctl = reinterpret_cast<uint32_t *>(smem + off); off += 32;   // [4] state of the staged tables
+    uint32_t *vbuf = reinterpret_cast<uint32_t *>(smem + off) + wave * 16; off += STORE_WAVES * 64;   // per wavefront: verdicts of the pass's 16 words
+    const Staging stg{ctl, smem, D.table_blob, n16, l_rep, D.cls_rep, ncls};
     Scratch sc;
-    sc.cap = sc_cap;
-    sc.w = reinterpret_cast<uint32_t *>(smem + off) + (size_t)wave * (2 * sc_cap + aut_hash_places(sc_cap));
-    sc.o = sc.w + sc_cap;
-    sc.h = sc.o + sc_cap;
-    const bool use_cache = (rin.flags & STORE_ROW_CACHE) != 0 && rin.n_ent <= (uint32_t)AUT_ENT_LDS;
-    const uint32_t n_pend_lds = rin.n_pending < (uint32_t)STORE_PENDING_LDS ? rin.n_pending : (uint32_t)STORE_PENDING_LDS;
-    uint32_t start = rin.start;
-    if (rin.flags & STORE_ROW_IMPORTED) start = a.store_import_root[row];
-    if (use_cache) for (uint32_t k = tid; k < rin.n_ent; k += STORE_BLOCK) l_ent[k] = a.entries[rin.ent_off + k];
-    for (uint32_t k = tid; k < ncls; k += STORE_BLOCK) l_rep[k] = D.cls_rep[k];
-    for (uint32_t k = tid; k < n_pend_lds; k += STORE_BLOCK) l_pend[k] = a.store_pending[rin.pend_off + k];
+    sc.cap = (uint32_t)a.aut_scratch;
+    sc.w = reinterpret_cast<uint32_t *>(smem + off) + (size_t)wave * (2 * sc.cap + aut_hash_places(sc.cap));
+    sc.o = sc.w + sc.cap;
+    sc.h = sc.o + sc.cap;
     for (uint32_t k = tid; k < LC_ENTRIES; k += STORE_BLOCK) lc[k] = LC_EMPTY;
     if (tid == 0) ctl[4] = 0;
-    uint32_t steps = 0;
+    __syncthreads();
+    if (unit >= n_groups) return;
+    auto field = [&](uint32_t k) { return (uint32_t)__builtin_amdgcn_readlane((int)rec, (int)k); };
+    const uint32_t flags = field(5), n_pending = field(1), pend_off = field(2), n_ent = field(3), ent_off = field(4);
+    uint32_t start = field(0);
+    if (flags & STORE_ROW_IMPORTED) start = a.store_import_root[row];
+    const bool use_cache = (flags & STORE_ROW_CACHE) != 0;
+    const bool ent_inline = n_ent <= (uint32_t)STORE_ROW_ENT, pend_inline = n_pending <= (uint32_t)STORE_ROW_PEND;
+    auto entry = [&](uint32_t k) -> uint32_t {               // k differs from lane to lane: a shuffle, not a broadcast
+        const uint32_t inl = (uint32_t)__shfl((int)rec, (int)(STORE_ROW_ENT_AT + (k < (uint32_t)STORE_ROW_ENT ? k : 0u)));
+        return ent_inline ? inl : a.entries[ent_off + k];
+    };
+    auto pending = [&](uint32_t k) -> uint32_t {
+        return pend_inline ? (field(STORE_ROW_PEND_AT + (k >> 2)) >> ((k & 3u) * 8u)) & 0xFFu : (uint32_t)a.store_pending[pend_off + k];
+    };
+    uint32_t steps = 0, root = AT_FAIL;
     uint32_t *errors = &a.counters[2];
-    const uint32_t n_groups = (Wr + AUT_GROUP_WORDS - 1) / AUT_GROUP_WORDS, groups_per_pass = STORE_SUB_WORDS / AUT_GROUP_WORDS;
-    for (uint32_t j0 = 0; blockIdx.x + j0 * gridDim.x < n_groups; j0 += groups_per_pass) {
+    const uint32_t slot16 = lane & 15u, grp = lane >> 4;    // lane = (word slot, one of four groups of cache rows)
+    for (uint32_t j0 = 0; unit + j0 * n_units < n_groups; j0 += 4) {
+        // the 16 words of this pass: four groups of AUT_GROUP_WORDS neighbouring words, dealt round robin over the units
         auto word_of = [&](uint32_t t) -> uint32_t {
-            const uint32_t grp = blockIdx.x + (j0 + t / AUT_GROUP_WORDS) * gridDim.x;
-            return grp < n_groups ? grp * AUT_GROUP_WORDS + t % AUT_GROUP_WORDS : 0xFFFFFF00u;
+            const uint32_t g = unit + (j0 + t / AUT_GROUP_WORDS) * n_units;
+            return g < n_groups ? g * AUT_GROUP_WORDS + t % AUT_GROUP_WORDS : 0xFFFFFF00u;
         };
-        if (tid == 0) { ctl[2] = 0; ctl[3] = 0; }
-        if (tid < STORE_SUB_WORDS) { vslice[tid] = 0; cslice[tid] = use_cache ? 0u : 0xFFFFFFFFu; }
-        __syncthreads();                                     // also: tables, cache rows and pending bytes are in place
-        if (j0 == 0 && wave == STORE_WAVES - 1) {
-            // ---- the row's current state: walk the bytes fed since `start` was its state ----
+        const uint32_t w = word_of(slot16);
+        uint32_t v = 0, c = use_cache ? 0u : 0xFFFFFFFFu;
+        // the first look-up of the pending walk is requested ahead of the cache words: loads come back in the order they were issued
+        uint32_t hop0 = AT_NONE;
+        const bool start_ok = start != 0 && start < G.cap_states;
+        if (j0 == 0 && n_pending && start_ok && pending(0) < ncls) hop0 = __hip_atomic_load(&G.trans[start * ncls + pending(0)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+        if (use_cache)
+            for (uint32_t k0 = 0; k0 < n_ent; k0 += 4) {         // uniform trip count: the row numbers come by shuffle
+                const uint32_t k = k0 + grp;
+                const uint32_t er = entry(k < n_ent ? k : 0u);
+                if (k < n_ent && w < Wr) { const size_t r = (size_t)er * Wr + w; v |= D.ci_valid[r]; c |= D.ci_cd[r]; }
+            }
+        if (j0 == 0) {
+            // ---- the row's current state: walk the bytes fed since `start` was its state (the loads above are in flight) ----
             uint32_t s = start;
             bool bad = s == 0 || (s >= G.cap_states && s != AT_SINK);
-            for (uint32_t k = 0; k < rin.n_pending && !bad; k++) {
-                const uint32_t cl = k < (uint32_t)STORE_PENDING_LDS ? (uint32_t)l_pend[k] : (uint32_t)a.store_pending[rin.pend_off + k];
+            for (uint32_t k = 0; k < n_pending && !bad; k++) {
+                const uint32_t cl = pending(k);
                 if (s == AT_SINK || cl >= ncls) { bad = true; break; }
-                const uint32_t t = store_lookup_uniform(T, G, l_rep, sc, stg, errors, &steps, s, cl, lane);
+                uint32_t t = k == 0 ? (uint32_t)__builtin_amdgcn_readfirstlane((int)hop0) : (uint32_t)AT_NONE;
+                if (!t_final(t)) t = store_lookup_uniform(T, G, sc, stg, errors, &steps, s, cl, lane);
                 if (t == AT_DEAD || t == AT_FAIL) { bad = true; break; }   // the host accepted these bytes: a dead end here is an error
                 s = t;
             }
-            if (bad) { s = AT_FAIL; if (lane == 0) atomicAdd(errors, 1u); }
-            if (lane == 0) { ctl[0] = s; if (blockIdx.x == 0) a.store_row_out[row] = s; }
-        }
-        // ---- merge the token-mask cache rows (all threads: word slot tid % SUB, cache rows tid / SUB, + 4, ...) ----
-        if (use_cache) {
-            const uint32_t t = tid % STORE_SUB_WORDS, w = word_of(t);
-            uint32_t v = 0, c = 0;
-            if (w < Wr)
-                for (uint32_t k = tid / STORE_SUB_WORDS; k < rin.n_ent; k += STORE_BLOCK / STORE_SUB_WORDS) {
-                    const size_t r = (size_t)l_ent[k] * Wr + w;
-                    v |= D.ci_valid[r]; c |= D.ci_cd[r];
+            if (bad) { s = AT_FAIL; if (lane == 0 && unit == 0) atomicAdd(errors, 1u); }
+            if (lane == 0 && unit == 0) a.store_row_out[row] = s;
+            root = s;
+            if (root < AT_FAIL) {                            // warm the block's cache with the current state's row of the table
+                for (uint32_t c0 = 0; c0 < ncls; c0 += 64) {
+                    const uint32_t cl = c0 + lane;
+                    if (cl < ncls) {
+                        const uint32_t key = root * ncls + cl, t = __hip_atomic_load(&G.trans[key], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                        if (t_final(t) && t != AT_FAIL)
+                            __hip_atomic_store(&lc[(key * 0x9E3779B1u) >> (32 - LC_BITS)], ((unsigned long long)key << 32) | t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    }
                 }
-            if (v) atomicOr(&vslice[t], v);
-            if (c) atomicOr(&cslice[t], c);
-        }
-        __syncthreads();
-        const uint32_t root = ctl[0];
-        const bool root_ok = root < AT_FAIL;                 // AT_SINK: nothing can follow; AT_FAIL: the call fails
-        if (wave == 0) {                                     // the first wavefront lists the word pairs that hold undecided strings
-            const bool act = lane < (uint32_t)STORE_SUB_WORDS / 2;
-            uint32_t want[2] = {0, 0};
-#pragma unroll
-            for (int h = 0; h < 2; h++) {
-                if (!act) continue;
-                const uint32_t w = word_of(2 * tid + h), r0 = w * 32u;
-                want[h] = cslice[2 * tid + h] & ~vslice[2 * tid + h];
-                if (w >= Wr || r0 >= n_strings || !root_ok) want[h] = 0;
-                else if (n_strings - r0 < 32u) want[h] &= (1u << (n_strings - r0)) - 1u;
-                cslice[2 * tid + h] = want[h];
-                if (!root_ok) vslice[2 * tid + h] = 0;       // no string can follow a finished sentence
             }
-            const unsigned long long nz = __ballot((want[0] | want[1]) != 0);
-            if (want[0] | want[1]) pairs[__popcll(nz & ((1ull << lane) - 1ull))] = (uint8_t)tid;
-            uint32_t cnt = (uint32_t)(__popc(want[0]) + __popc(want[1]));
-#pragma unroll
-            for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d);
-            if (lane == 0) { ctl[3] = (uint32_t)__popcll(nz); if (cnt) atomicAdd(&a.counters[1], cnt); }
         }
-        __syncthreads();
-        const uint32_t n_pairs = ctl[3];
-        // ---- one lane per string through the table, 64 neighbouring ranks at a time ----
-        for (;;) {
-            uint32_t b = 0;
-            if (lane == 0) b = atomicAdd(&ctl[2], 1u);
-            b = (uint32_t)__builtin_amdgcn_readfirstlane((int)b);
-            if (b >= n_pairs) break;
-            const uint32_t pair = pairs[b];
-            const uint32_t rank = word_of(2 * pair) * 32u + lane;
-            bool live = ((cslice[2 * pair + (lane >> 5)] >> (lane & 31u)) & 1u) != 0;
+        const bool root_ok = root < AT_FAIL;                 // AT_SINK: nothing can follow; AT_FAIL: the call fails
+        v |= __shfl_xor(v, 16); v |= __shfl_xor(v, 32);
+        c |= __shfl_xor(c, 16); c |= __shfl_xor(c, 32);
+        uint32_t want = c & ~v;
+        {
+            const uint32_t r0 = w * 32u;
+            if (w >= Wr || r0 >= n_strings || !root_ok) want = 0;
+            else if (n_strings - r0 < 32u) want &= (1u << (n_strings - r0)) - 1u;
+            if (!root_ok) v = 0;                             // no string can follow a finished sentence
+        }
+        {
+            uint32_t cnt = lane < 16u ? (uint32_t)__popc(want) : 0u;
+#pragma unroll
+            for (int d = 8; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d);
+            if (lane == 0 && cnt) atomicAdd(&a.counters[1], cnt);
+        }
+        // ---- one lane per undecided string through the table.  The undecided strings of the 16 words are numbered
+        // through (prefix sum of the words' bit counts) and taken 64 at a time, so that a batch is full whatever the
+        // pattern of the bits; verdicts go back to their words through 16 words of LDS ----
+        uint32_t incl = (uint32_t)__popc(want);              // every group of 16 lanes holds the same 16 words
+#pragma unroll
+        for (int d = 1; d < 16; d <<= 1) { const uint32_t up = __shfl_up(incl, d, 16); if (slot16 >= (uint32_t)d) incl += up; }
+        const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 15);
+        if (lane < 16u) lds_store(&vbuf[lane], 0u);
+        for (uint32_t b0 = 0; b0 < total; b0 += 64) {
+            const uint32_t i = b0 + lane;
+            bool live = i < total;
+            uint32_t slot = 0;                               // the word that holds the lane's string: the first whose running count exceeds i
+#pragma unroll
+            for (int k = 0; k < 15; k++) slot += i >= (uint32_t)__builtin_amdgcn_readlane((int)incl, k) ? 1u : 0u;
+            const uint32_t before = (uint32_t)__shfl((int)incl, (int)(slot ? slot - 1 : 0));
+            const uint32_t bits = (uint32_t)__shfl((int)want, (int)slot);
+            uint32_t n = i - (slot ? before : 0u), bit = 0;  // the n-th set bit of the word, by halving
+#pragma unroll
+            for (int sh = 16; sh >= 1; sh >>= 1) {
+                const uint32_t low = (uint32_t)__popc(bits & (((1u << sh) - 1u) << bit));
+                if (n >= low) { n -= low; bit += (uint32_t)sh; }
+            }
+            const uint32_t rank = word_of(slot) * 32u + bit;
             uint32_t soff = 0, len = 0;
             Str16 c16{{0, 0, 0, 0}};
             if (live) { soff = D.str_off[rank]; len = D.str_off[rank + 1] - soff; c16 = D.str16[rank]; }
             live = live && len > 0;
-            uint32_t s = root, pos = 0, c = 0, spins = 0, t = AT_BUSY;
+            uint32_t s = root, pos = 0, cc = 0, spins = 0, t = AT_BUSY;
             bool ok = false, fail = false;
             for (;;) {
                 while (live) {                               // every lane follows its own string as far as the table goes
                     if (pos < 16u) {
                         const uint32_t q = pos >> 2;
                         const uint32_t word = q == 0 ? c16.w[0] : (q == 1 ? c16.w[1] : (q == 2 ? c16.w[2] : c16.w[3]));
-                        c = (word >> ((pos & 3u) * 8u)) & 0xFFu;
-                    } else c = D.str_cls[soff + pos];
-                    const uint32_t key = s * ncls + c;
-                    const uint32_t slot = (key * 0x9E3779B1u) >> (32 - LC_BITS);
-                    const unsigned long long e = __hip_atomic_load(&lc[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        cc = (word >> ((pos & 3u) * 8u)) & 0xFFu;
+                    } else cc = D.str_cls[soff + pos];
+                    const uint32_t key = s * ncls + cc;
+                    const uint32_t lslot = (key * 0x9E3779B1u) >> (32 - LC_BITS);
+                    const unsigned long long e = __hip_atomic_load(&lc[lslot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     if ((uint32_t)(e >> 32) == key) t = (uint32_t)e;
                     else {
                         t = t_load(&G.trans[key]);
-                        if (t_final(t) && t != AT_FAIL) __hip_atomic_store(&lc[slot], ((unsigned long long)key << 32) | t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        if (t_final(t) && t != AT_FAIL) __hip_atomic_store(&lc[lslot], ((unsigned long long)key << 32) | t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     }
                     if (t < AT_FAIL) { s = t; pos++; if (pos == len) { ok = true; live = false; } }
                     else if (t == AT_DEAD) live = false;
@@ -334,19 +370,18 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a) {
                     else if (t == AT_FAIL) { fail = true; live = false; }
                     else break;                              // not there yet
                 }
-                const unsigned long long waiting = __ballot(live);
-                if (!waiting) break;
+                if (!__ballot(live)) break;
                 // one of the waiting lanes' transitions is claimed and computed here; the other lanes look again afterwards
                 const unsigned long long missing = __ballot(live && t == AT_NONE);
                 bool progress = false;
                 if (missing) {
                     const int l = __ffsll((long long)missing) - 1;
-                    const uint32_t rs = (uint32_t)__builtin_amdgcn_readlane((int)s, l), rc = (uint32_t)__builtin_amdgcn_readlane((int)c, l);
+                    const uint32_t rs = (uint32_t)__builtin_amdgcn_readlane((int)s, l), rc = (uint32_t)__builtin_amdgcn_readlane((int)cc, l);
                     uint32_t old = 0;
                     if (lane == 0) old = atomicCAS(&G.trans[rs * ncls + rc], (uint32_t)AT_NONE, (uint32_t)AT_BUSY);
                     old = (uint32_t)__builtin_amdgcn_readfirstlane((int)old);
                     if (old == AT_NONE) {
-                        const uint32_t r = store_transition(T, G, l_rep, sc, stg, errors, rs, rc, lane);
+                        const uint32_t r = store_transition(T, G, sc, stg, errors, rs, rc, lane);
                         steps++;
                         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
                         if (lane == 0) g_store_release(&G.trans[rs * ncls + rc], r);
@@ -359,13 +394,12 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a) {
                     if (++spins > (uint32_t)AUT_SPIN_LIMIT) { fail = fail || live; live = false; }   // bounded wait
                 }
             }
-            const unsigned long long okb = __ballot(ok);     // this wavefront is the only one that touches the pair's two words
-            if (lane == 0 && okb) { vslice[2 * pair] |= (uint32_t)okb; vslice[2 * pair + 1] |= (uint32_t)(okb >> 32); }
+            if (ok) atomicOr(&vbuf[slot], 1u << bit);
             const unsigned long long fm = __ballot(fail);    // no room in the scratch or the store, or a wait that did not end
             if (lane == 0 && fm) atomicAdd(errors, (uint32_t)__popcll(fm));
         }
-        __syncthreads();
-        if (tid < STORE_SUB_WORDS) { const uint32_t w = word_of(tid); if (w < Wr) a.rank_mask[(size_t)row * Wr + w] = vslice[tid]; }
+        if (total) v |= lds_load(&vbuf[slot16]);             // LDS serves one wavefront's accesses in issue order
+        if (lane < 16u && w < Wr) a.rank_mask[(size_t)row * Wr + w] = v;
     }
     if (lane == 0 && steps) atomicAdd(&a.counters[3], steps);
 }
@@ -416,13 +450,13 @@ hipError_t prepare_store_kernels() {
 }
 
 uint32_t store_lds_bytes(const DeviceTables &t, int mode, int scratch) {
-    return table_bytes(t, mode) + LC_ENTRIES * 8 + AUT_ENT_LDS * 4 + 256 + STORE_PENDING_LDS + 2 * STORE_SUB_WORDS * 4 + STORE_SUB_WORDS / 2 + 32 +
+    return table_bytes(t, mode) + 256 + LC_ENTRIES * 8 + 32 + STORE_WAVES * 64 +
            STORE_WAVES * ((uint32_t)scratch * 8 + aut_hash_places((uint32_t)scratch) * 4);
 }
 
 hipError_t launch_mask_store(const MaskArgs &a, hipStream_t s) {
     const uint32_t lds = store_lds_bytes(a.tab, a.mode, a.aut_scratch);
-    dim3 grid(a.aut_parts, a.batch);
+    dim3 grid(a.store_uniform_parts ? (uint32_t)a.store_uniform_parts * (uint32_t)a.batch : (uint32_t)a.store_first_block[a.batch]);
     if (a.mode == 0) hipLaunchKernelGGL(mask_store_kernel<0>, grid, dim3(STORE_BLOCK), lds, s, a);
     else if (a.mode == 1) hipLaunchKernelGGL(mask_store_kernel<1>, grid, dim3(STORE_BLOCK), lds, s, a);
     else hipLaunchKernelGGL(mask_store_kernel<2>, grid, dim3(STORE_BLOCK), lds, s, a);

@@ -49,7 +49,7 @@ def _run_parity(torch, zf, Oracle, grammar, tokens, batch, steps, seed, check_ev
     return overflow
 
 
-MODES = {"automaton": 0, "trie-walk": 1}     # zf_options.walk_mode: both mask kernels must give the oracle's bits
+MODES = {"automaton": 0, "trie-walk": 1, "store": 2}     # zf_options.walk_mode: all three mask kernels must give the oracle's bits
 
 
 @pytest.mark.parametrize("mode", list(MODES))
@@ -88,7 +88,10 @@ def test_random_grammars(seed, torch_cuda, oracle_lib):
     toks = random_grammars.random_vocab(seed, 400)
     for mode in MODES.values():
         _run_parity(torch_cuda, zf, oracle_lib.Oracle, g, toks, 3, 20, 1000 + seed, walk_mode=mode)
-        _run_parity(torch_cuda, zf, oracle_lib.Oracle, g, toks, 2, 12, 2000 + seed, lane_item_cap=3 - mode, token_mask_cache=seed % 2 == 0, walk_mode=mode)
+        if mode != 2:     # a budget of two or three items: the per-block kernels hand such sets to the fallback pass
+            _run_parity(torch_cuda, zf, oracle_lib.Oracle, g, toks, 2, 12, 2000 + seed, lane_item_cap=3 - mode, token_mask_cache=seed % 2 == 0, walk_mode=mode)
+        else:
+            _run_parity(torch_cuda, zf, oracle_lib.Oracle, g, toks, 2, 12, 2000 + seed, token_mask_cache=seed % 2 == 0, walk_mode=mode)
 
 
 def test_overflow_beyond_the_fallback_is_an_error(torch_cuda):
@@ -149,20 +152,20 @@ def _replay_all_rows(torch, zf, oracle_lib, idx, variants, stride_of=None):
 
 
 def test_config3_every_step_every_row(torch_cuda, oracle_lib):
-    """Configuration 3 at its stated shape (16 rows x 512 steps, V = 128,256): both mask kernels against the oracle at
+    """Configuration 3 at its stated shape (16 rows x 512 steps, V = 128,256): all three mask kernels against the oracle at
     every step on every row; with the token-mask cache off (every token through the parser) at every 4th step."""
     import paper_2506_01151_amd as zf
-    variants = {"automaton": dict(walk_mode=0), "trie-walk": dict(walk_mode=1),
+    variants = {"store": dict(walk_mode=2), "automaton": dict(walk_mode=0), "trie-walk": dict(walk_mode=1), "store-parser-only": dict(walk_mode=2, token_mask_cache=False),
                 "automaton-parser-only": dict(walk_mode=0, token_mask_cache=False), "trie-walk-parser-only": dict(walk_mode=1, token_mask_cache=False)}
-    n, full = _replay_all_rows(torch_cuda, zf, oracle_lib, 3, variants, {"automaton-parser-only": 4, "trie-walk-parser-only": 4})
-    assert n["automaton"] == full == 16 * 512 and n["trie-walk"] == full
+    n, full = _replay_all_rows(torch_cuda, zf, oracle_lib, 3, variants, {"automaton-parser-only": 4, "trie-walk-parser-only": 4, "store-parser-only": 4})
+    assert n["store"] == full == 16 * 512 and n["automaton"] == full and n["trie-walk"] == full
 
 
 def test_config4_every_step_every_row(torch_cuda, oracle_lib):
-    """Configuration 4 at its stated shape (64 rows x 256 steps, V = 128,256): both mask kernels, every step, every row."""
+    """Configuration 4 at its stated shape (64 rows x 256 steps, V = 128,256): all three mask kernels, every step, every row."""
     import paper_2506_01151_amd as zf
-    n, full = _replay_all_rows(torch_cuda, zf, oracle_lib, 4, {"automaton": dict(walk_mode=0), "trie-walk": dict(walk_mode=1)})
-    assert n["automaton"] == full == 64 * 256 and n["trie-walk"] == full
+    n, full = _replay_all_rows(torch_cuda, zf, oracle_lib, 4, {"store": dict(walk_mode=2), "automaton": dict(walk_mode=0), "trie-walk": dict(walk_mode=1)})
+    assert n["store"] == full == 64 * 256 and n["automaton"] == full and n["trie-walk"] == full
 
 
 CFG5_CHECK_STEPS = 12      # steps of the trajectory at which masks are compared (spread evenly, the last one included) ...
@@ -174,7 +177,7 @@ CFG5_CHECK_ROWS = 6        # ... on this many seeded rows each: the oracle keeps
 def test_config5_full_batch_pruning_on_and_off(pruning, mode, torch_cuda, oracle_lib):
     """Configuration 5 at its stated batch and vocabulary (64 rows, V = 152,064) along the oracle-sampled trajectory, as far
     as the file goes: one compute_mask call covers all 64 rows (the launch shape the benchmark times); a seeded, reported
-    subsample of (step, row) pairs is compared bit for bit with the oracle, with ZapFormat pruning on and off, both kernels."""
+    subsample of (step, row) pairs is compared bit for bit with the oracle, with ZapFormat pruning on and off, every mask kernel (with pruning off the persistent automaton is not used: the per-block automaton runs in its place)."""
     import paper_2506_01151_amd as zf
     torch = torch_cuda
     cfg = configs.CONFIGS[5]
@@ -405,6 +408,8 @@ def test_long_tokens_deep_nesting_many_classes(mode, torch_cuda, oracle_lib):
         assert (got[i] == a.mask(off, data, 4)).all(), prefixes[i]
     if mode == "automaton":
         assert eng.mask_report().overflow_chunks > 0, "runs of 120 brackets were meant to outgrow the state budget"
+    if mode == "store":
+        assert eng.mask_report().overflow_chunks == 0      # the persistent automaton has room for every nesting depth
     g2 = grammars.many_classes_grammar(100)
     toks2 = [bytes([c]) for c in range(256)] + [bytes([32 + c, 32 + (c * 7 + 3) % 100]) for c in range(100)] + [bytes([32 + c, 32 + (c * 7 + 3) % 100, 32 + (c * 5) % 100]) for c in range(100)]
     assert zf.Engine(g2, toks2, device=-1).info.n_byte_classes > 64
