@@ -250,7 +250,7 @@ def _handles(states):
 class Engine:
     """compile(grammar rules, vocab byte strings)."""
 
-    def __init__(self, grammar, vocab_tokens, *, pruning=True, lane_item_cap=0, device=0, chunk_strings=0, fallback_item_cap=0, token_mask_cache=True, state_cache_entries=0, walk_mode=0):
+    def __init__(self, grammar, vocab_tokens, *, pruning=True, lane_item_cap=0, device=0, chunk_strings=0, fallback_item_cap=0, token_mask_cache=True, state_cache_entries=0, walk_mode=2):
         load_library()
         csr = grammar.csr()
         self._keep = csr

@@ -60,6 +60,7 @@ struct DeviceSide {
     uint32_t store_epoch = 1;                        // bumped whenever the store is cleared
     uint32_t store_states = 0, store_items = 0;      // as of the last call that reported back
     bool store_dirty = true;                         // the store must be cleared before its next use
+    uint32_t store_backoff = 0, store_backoff_next = 8;   // after a call the store had no room for: calls that take the per-block automaton instead
     struct CallRecord {                              // what to note in the states once the call in this slot has reported
         bool active = false;
         uint32_t epoch = 0;
@@ -695,7 +696,7 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
 // gather when the state cache is on.  wait = true: also wait and return the final status.
 // noalloc = true (zf_compute_mask_noalloc): every per-call device buffer is a slice of the device's static scratch array,
 // the state cache is passed by, and a call that does not fit the array or the staging room is refused.
-static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait, bool noalloc) {
+static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait, bool noalloc, bool per_block) {
     if (!e || !states || batch <= 0 || batch > MAX_BATCH || !d_mask) return fail(ZF_ERR_INVALID_ARG, "bad argument (batch must be 1..4096)");
     DeviceSide *d = e->dev;
     if (!d) return fail(ZF_ERR_DEVICE, "engine was compiled without a device (device = -1)");
@@ -706,7 +707,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     HIP_TRY(hipEventSynchronize(d->stage_done[slot]));   // the slot's previous upload has left the staging buffer
     for (int b = 0; b < batch; b++)
         if (!states[b] || states[b]->eng != e) return fail(ZF_ERR_INVALID_ARG, "state " + std::to_string(b) + " is null or belongs to another engine");
-    if (e->store_on && !noalloc) return enqueue_store_impl(e, states, batch, d_mask, hip_stream, wait, slot);
+    if (e->store_on && !noalloc && !per_block) return enqueue_store_impl(e, states, batch, d_mask, hip_stream, wait, slot);
     // ---- the packed form of every row: [n_sets][set offsets][item word, origin]... (also the cache key) ----
     static thread_local std::vector<std::vector<uint32_t>> packed;
     if ((int)packed.size() < batch) packed.resize(batch);
@@ -1175,8 +1176,23 @@ static void forget_cached_masks(DeviceSide *d) {
 
 // A call that fails part-way may have registered cache slots whose masks were never written.
 static int enqueue_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait, bool noalloc = false) {
-    const int rc = enqueue_mask_impl(e, states, batch, d_mask, hip_stream, wait, noalloc);
-    if (rc != ZF_OK && e && e->dev) forget_cached_masks(e->dev);
+    DeviceSide *d = e ? e->dev : nullptr;
+    bool per_block = false;                               // persistent automaton on hold after a call it had no room for
+    if (d && e->store_on && d->store_backoff) { d->store_backoff--; per_block = true; }
+    int rc = enqueue_mask_impl(e, states, batch, d_mask, hip_stream, wait, noalloc, per_block);
+    if (rc != ZF_OK && d) forget_cached_masks(d);
+    if (rc == ZF_ERR_OVERFLOW && d && e->store_on && !noalloc && !per_block) {
+        // A set outgrew a wavefront's scratch, or the store filled up within one call.  The waiting call answers through the
+        // per-block automaton, whose fallback pass has room in global memory; either way the next calls go that way too,
+        // for longer each time it happens, and the store starts over when it is used again.
+        d->store_dirty = true;
+        d->store_backoff = d->store_backoff_next;
+        d->store_backoff_next = std::min<uint32_t>(1024, d->store_backoff_next * 2);
+        if (wait) {
+            rc = enqueue_mask_impl(e, states, batch, d_mask, hip_stream, wait, noalloc, true);
+            if (rc != ZF_OK) forget_cached_masks(d);
+        }
+    }
     return rc;
 }
 

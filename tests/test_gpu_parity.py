@@ -346,6 +346,124 @@ def test_async_calls_match_the_waiting_call(torch_cuda, oracle_lib):
     assert ei.value.code == zf.ZF_ERR_OVERFLOW
 
 
+def test_persistent_automaton_bookkeeping(torch_cuda, oracle_lib):
+    """The persistent automaton (walk_mode 2) keeps, per state, where the row stands in the device's store and which
+    bytes were fed since.  Calls in flight while rows move on, a cleared store (rows come back in through their charts),
+    a row fed more bytes than a call carries, clones, resets and a state destroyed while a call is in flight: the masks
+    equal the oracle's every time, and a repeated call takes no Earley step at all."""
+    import gc
+    import paper_2506_01151_amd as zf
+    torch = torch_cuda
+    cfg = configs.CONFIGS[2]
+    toks = cfg.vocab()
+    off, data = wvocab.vocab_csr(toks)
+    g = cfg.grammar()
+    eng = zf.Engine(g, toks, device=0, state_cache_entries=-1, walk_mode=2)
+    orc = oracle_lib.Oracle(g)
+    rows = 6
+    run = OracleRun(orc, toks, [stream(99, f"book[{b}]") for b in range(rows)])
+    ss = zf.StateBatch([eng.new_state() for _ in range(rows)])
+
+    def check(states, oracle_states, what):
+        d = torch.full((len(states), eng.W), -1, dtype=torch.int32, device="cuda")
+        zf.compute_mask(eng, states, d)
+        got = d.cpu().numpy().view(np.uint32)
+        for b, o in enumerate(oracle_states):
+            assert (got[b] == o.mask(off, data, 8)).all(), (what, b)
+
+    for _ in range(10):                                    # get going
+        ss.advance(run.step(run.masks()))
+    check(ss, run.states, "start")
+    # four calls in flight, the rows advancing in between: each call walks what was fed since the last state the host knew of
+    masks = [torch.full((rows, eng.W), -1, dtype=torch.int32, device="cuda") for _ in range(4)]
+    want = []
+    for k in range(4):
+        ss.advance(run.step(run.masks()))
+        want.append(run.masks())
+        zf.compute_mask_async(eng, ss, masks[k])
+    zf.mask_wait(eng)
+    torch.cuda.synchronize()
+    for k in range(4):
+        assert (masks[k].cpu().numpy().view(np.uint32) == want[k]).all(), f"call {k} in flight"
+    # the same states again: everything is in the table
+    check(ss, run.states, "repeat")
+    assert eng.mask_report().parser_steps == 0
+    # the store cleared: the rows come back in from their host charts
+    eng.clear_state_cache()
+    check(ss, run.states, "after clearing the store")
+    for _ in range(3):
+        ss.advance(run.step(run.masks()))
+    check(ss, run.states, "three steps after clearing")
+    # a row fed far more bytes than a call carries
+    long_o, long_s = orc.new_state(), eng.new_state()
+    text = b'{"k": "' + b"abc def " * 700
+    assert long_o.feed_bytes(text)
+    long_s.advance_bytes(text)
+    check([long_s], [long_o], "5,600 bytes at once")
+    long_s.advance_bytes(b'", "n": [1, 2')
+    assert long_o.feed_bytes(b'", "n": [1, 2')
+    check([long_s], [long_o], "and a few more")
+    # clones go their own ways; a reset row starts over
+    c_s, c_o = ss[0].clone(), run.states[0].clone()
+    m = c_o.mask(off, data, 8)
+    t = next(v for v in range(300, len(toks)) if (m[v >> 5] >> (v & 31)) & 1)
+    c_s.advance(t)
+    assert c_o.feed_bytes(toks[t])
+    check([c_s, ss[0]], [c_o, run.states[0]], "clone")
+    ss[1].reset()
+    run.states[1] = orc.new_state()
+    check(ss, run.states, "reset")
+    # a state destroyed while a call that names it is in flight
+    doomed = eng.new_state()
+    doomed.advance_bytes(b"[1, ")
+    d2 = torch.full((2, eng.W), -1, dtype=torch.int32, device="cuda")
+    zf.compute_mask_async(eng, [doomed, ss[0]], d2)
+    del doomed
+    gc.collect()
+    zf.mask_wait(eng)
+    torch.cuda.synchronize()
+    assert (d2.cpu().numpy().view(np.uint32)[1] == run.states[0].mask(off, data, 8)).all()
+    check(ss, run.states, "afterwards")
+
+
+@pytest.mark.parametrize("cap", [2, 40], ids=["budget-2", "budget-40"])
+def test_persistent_automaton_out_of_room(cap, torch_cuda, oracle_lib):
+    """A set that outgrows a wavefront's scratch fails the call on the persistent automaton; the waiting call then answers
+    through the per-block automaton and its fallback pass, the following calls go that way too for a while, and the masks
+    are the oracle's throughout.  The call that does not wait reports the overflow from mask_wait."""
+    import paper_2506_01151_amd as zf
+    torch = torch_cuda
+    cfg = configs.CONFIGS[5]
+    g, toks = cfg.grammar(), cfg.vocab(6000)
+    off, data = wvocab.vocab_csr(toks)
+    orc = oracle_lib.Oracle(g)
+    eng = zf.Engine(g, toks, device=0, state_cache_entries=-1, walk_mode=2, lane_item_cap=cap)
+    prefixes = [b"a" + b"+b" * 30, b"(x*y" + b"+(z)" * 12, b"q"]
+    so, ss = [], []
+    for p in prefixes:
+        a, b = orc.new_state(), eng.new_state()
+        assert a.feed_bytes(p)
+        b.advance_bytes(p)
+        so.append(a)
+        ss.append(b)
+    d_mask = torch.full((len(ss), eng.W), -1, dtype=torch.int32, device="cuda")
+    for rep in range(12):                                  # beyond the first back-off of 8 calls: the store is tried again, fails again
+        d_mask.fill_(-1)
+        zf.compute_mask(eng, ss, d_mask)
+        got = d_mask.cpu().numpy().view(np.uint32)
+        for i, a in enumerate(so):
+            assert (got[i] == a.mask(off, data, 4)).all(), (rep, prefixes[i][:8])
+    fresh = zf.Engine(g, toks, device=0, state_cache_entries=-1, walk_mode=2, lane_item_cap=cap)
+    s = fresh.new_state()
+    s.advance_bytes(prefixes[0])
+    zf.compute_mask_async(fresh, [s], d_mask[:1])
+    with pytest.raises(zf.ZfError) as ei:
+        zf.mask_wait(fresh)
+    assert ei.value.code == zf.ZF_ERR_OVERFLOW
+    zf.compute_mask(fresh, [s], d_mask[:1])                # and the engine goes on working
+    assert (d_mask[:1].cpu().numpy().view(np.uint32)[0] == so[0].mask(off, data, 4)).all()
+
+
 def test_edge_cases(torch_cuda, oracle_lib):
     """Empty tokens, duplicates, a vocabulary smaller than one word, rows in different states,
     a finished sentence (empty mask), V not a multiple of 32."""

@@ -19,7 +19,7 @@ def _states_after(eng, traj, rows, step):
     return ss
 
 
-@pytest.mark.parametrize("mode", [0, 1], ids=["automaton", "trie-walk"])
+@pytest.mark.parametrize("mode", [0, 1, 2], ids=["automaton", "trie-walk", "store"])
 def test_noalloc_equals_compute_mask_two_calls_in_a_row(mode, oracle_lib):
     import torch
     import paper_2506_01151_amd as zf
