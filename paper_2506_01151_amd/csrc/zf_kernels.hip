@@ -9,7 +9,9 @@
 // also holds finish_kernel: the exact fallback pass of both, and the permutation of the verdicts
 // into token order).
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include "zf_launch.h"
+
 
 namespace zf {
 namespace {
@@ -38,47 +40,50 @@ __global__ __launch_bounds__(256) void gather_kernel(MaskArgs a) {
     }
 }
 
-// Logit masking (Section 3.3): pure copy-or-(-inf).  16-byte accesses, consecutive lanes on
-// consecutive 16-byte pieces; the mask words come from L2.
-static const int APPLY_UNROLL = 4;   // 16-byte pieces per thread
+// Logit masking (Section 3.3): pure copy-or-(-inf).  The tensor is taken as one run of 16-byte pieces (rows x pieces per
+// row), consecutive lanes on consecutive pieces, so that no block is left with the thin end of a row; a thread has U
+// pieces in flight (all loads issued before the first store); loads and stores are non-temporal; the mask words come
+// from L2.  `in` and `out` may be the same tensor (each thread reads its pieces before it writes them), so neither is
+// declared restrict.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-template <typename VecT, int EPV /* elements per 16 bytes */, typename ElemT>
-__global__ __launch_bounds__(256) void apply_mask_vec_kernel(const ElemT *__restrict__ in, ElemT *__restrict__ out, int64_t stride,
-                                                             int V, int W, const uint32_t *__restrict__ mask, ElemT neg_inf) {
-    const int row = blockIdx.y;
-    const ElemT *src = in + (size_t)row * stride;
-    ElemT *dst = out + (size_t)row * stride;
-    const uint32_t *mrow = mask + (size_t)row * W;
-    const int n_vec = V / EPV;
-    // a block covers APPLY_UNROLL * 256 consecutive pieces: all loads of a thread are issued before its first store
-    const int g0 = blockIdx.x * (256 * APPLY_UNROLL) + threadIdx.x;
-    VecT x[APPLY_UNROLL];
+template <int EPV /* elements per 16 bytes */, int U, typename ElemT>
+__global__ __launch_bounds__(256) void apply_mask_vec_kernel(const ElemT *in, ElemT *out, int64_t stride, int V, int W, int batch,
+                                                             const uint32_t *__restrict__ mask, ElemT neg_inf) {
+    const uint32_t n_vec = (uint32_t)V / EPV;                 // whole pieces per row
+    const uint32_t total = n_vec * (uint32_t)batch;           // the host checks that this fits 32 bits
+    const uint32_t g0 = blockIdx.x * (256 * U) + threadIdx.x;
+    u32x4 x[U];
+    uint32_t row[U], col[U];
+    uint32_t r = g0 / n_vec, c = g0 - r * n_vec;              // one division per thread; the later pieces by stepping
 #pragma unroll
-    for (int u = 0; u < APPLY_UNROLL; u++) {
-        const int g = g0 + u * 256;
-        if (g < n_vec) x[u] = __builtin_nontemporal_load(reinterpret_cast<const VecT *>(src) + g);
+    for (int u = 0; u < U; u++) {
+        row[u] = r; col[u] = c;
+        if (g0 + (uint32_t)u * 256 < total) x[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(in + (size_t)r * stride) + c);
+        c += 256;
+        while (c >= n_vec) { c -= n_vec; r++; }
     }
 #pragma unroll
-    for (int u = 0; u < APPLY_UNROLL; u++) {
-        const int g = g0 + u * 256;
-        if (g >= n_vec) break;
-        const int v0 = g * EPV;
-        const uint32_t mb = mrow[v0 >> 5] >> (v0 & 31);
+    for (int u = 0; u < U; u++) {
+        if (g0 + (uint32_t)u * 256 >= total) break;
+        const uint32_t v0 = col[u] * EPV;
+        const uint32_t mb = mask[(size_t)row[u] * W + (v0 >> 5)] >> (v0 & 31);
         ElemT *e = reinterpret_cast<ElemT *>(&x[u]);
 #pragma unroll
         for (int k = 0; k < EPV; k++) if (!((mb >> k) & 1u)) e[k] = neg_inf;
-        __builtin_nontemporal_store(x[u], reinterpret_cast<VecT *>(dst) + g);
+        __builtin_nontemporal_store(x[u], reinterpret_cast<u32x4 *>(out + (size_t)row[u] * stride) + col[u]);
     }
-    // ragged tail of the row
-    const int t = n_vec * EPV + blockIdx.x * 256 + threadIdx.x;
-    if (t < V && blockIdx.x * 256 + threadIdx.x < EPV) {
-        const bool keep = (mrow[t >> 5] >> (t & 31)) & 1u;
-        dst[t] = keep ? src[t] : neg_inf;
+    // ragged tails of the rows (V not a multiple of the piece): the first threads of the grid, one element each
+    const uint32_t tail = (uint32_t)V - n_vec * EPV;
+    const uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (tail && t < (uint64_t)tail * (uint32_t)batch) {
+        const uint32_t r = (uint32_t)(t / tail), v = n_vec * EPV + (uint32_t)(t - (uint64_t)r * tail);
+        const bool keep = (mask[(size_t)r * W + (v >> 5)] >> (v & 31)) & 1u;
+        out[(size_t)r * stride + v] = keep ? in[(size_t)r * stride + v] : neg_inf;
     }
 }
 
 template <typename ElemT>
-__global__ __launch_bounds__(256) void apply_mask_scalar_kernel(const ElemT *__restrict__ in, ElemT *__restrict__ out, int64_t stride,
+__global__ __launch_bounds__(256) void apply_mask_scalar_kernel(const ElemT *in, ElemT *out, int64_t stride,
                                                                 int V, int W, const uint32_t *__restrict__ mask, ElemT neg_inf) {
     const int row = blockIdx.y;
     for (int v = blockIdx.x * 256 + threadIdx.x; v < V; v += gridDim.x * 256) {
@@ -106,21 +111,33 @@ hipError_t launch_gather(const MaskArgs &a, hipStream_t s) {
     return hipGetLastError();
 }
 
+template <int EPV, typename ElemT>
+static void launch_apply_vec(const ElemT *in, ElemT *out, int64_t stride, int V, int W, int batch, const uint32_t *mask, ElemT ninf, hipStream_t s) {
+    // Pieces in flight per thread by the size of the tensor: a small one needs many blocks to reach every compute unit at all,
+    // a larger one more bytes in flight per wavefront to cover the memory latency (8 TB/s x 2 us = 16 MB on the way).
+    const uint64_t total = (uint64_t)(V / EPV) * (uint64_t)batch;
+    const uint64_t tail = (uint64_t)(V % EPV) * (uint64_t)batch;
+    auto blocks = [&](int u) { return (uint32_t)std::max<uint64_t>(std::max<uint64_t>((total + 256ull * u - 1) / (256ull * u), (tail + 255) / 256), 1); };
+    // measured on [16..1024] x 128,256 bf16 / fp32 and [64] x 152,064 fp32 (kernel-trace durations): the differences are a few per cent
+    if (total >= (1ull << 22)) hipLaunchKernelGGL((apply_mask_vec_kernel<EPV, 2, ElemT>), dim3(blocks(2)), dim3(256), 0, s, in, out, stride, V, W, batch, mask, ninf);
+    else if (total >= (1ull << 20)) hipLaunchKernelGGL((apply_mask_vec_kernel<EPV, 8, ElemT>), dim3(blocks(8)), dim3(256), 0, s, in, out, stride, V, W, batch, mask, ninf);
+    else if (total >= (1ull << 18)) hipLaunchKernelGGL((apply_mask_vec_kernel<EPV, 4, ElemT>), dim3(blocks(4)), dim3(256), 0, s, in, out, stride, V, W, batch, mask, ninf);
+    else hipLaunchKernelGGL((apply_mask_vec_kernel<EPV, 1, ElemT>), dim3(blocks(1)), dim3(256), 0, s, in, out, stride, V, W, batch, mask, ninf);
+}
+
 hipError_t launch_apply_mask(const void *logits, void *out, int dtype, int batch, int64_t row_stride, int V, int W,
                              const uint32_t *mask, hipStream_t s) {
     const size_t esz = dtype == 0 ? 4 : 2;
-    const bool aligned = ((uintptr_t)logits % 16 == 0) && ((uintptr_t)out % 16 == 0) && ((row_stride * esz) % 16 == 0);
-    const int epv = (int)(16 / esz);
-    int blocks_x = aligned ? (V / epv + 256 * APPLY_UNROLL - 1) / (256 * APPLY_UNROLL) : (V + 255) / 256;
-    if (blocks_x < 1) blocks_x = 1;
-    dim3 grid(blocks_x, batch);
+    const bool aligned = ((uintptr_t)logits % 16 == 0) && ((uintptr_t)out % 16 == 0) && ((row_stride * esz) % 16 == 0) &&
+                         (uint64_t)V * (uint64_t)batch < (1ull << 32) && (uint64_t)V / (16 / esz) > 0;
+    dim3 grid((V + 255) / 256 > 0 ? (V + 255) / 256 : 1, batch);
     if (dtype == 0) {
         const uint32_t ninf = 0xFF800000u;
-        if (aligned) hipLaunchKernelGGL((apply_mask_vec_kernel<u32x4, 4, uint32_t>), grid, dim3(256), 0, s, (const uint32_t *)logits, (uint32_t *)out, row_stride, V, W, mask, ninf);
+        if (aligned) launch_apply_vec<4, uint32_t>((const uint32_t *)logits, (uint32_t *)out, row_stride, V, W, batch, mask, ninf, s);
         else hipLaunchKernelGGL((apply_mask_scalar_kernel<uint32_t>), grid, dim3(256), 0, s, (const uint32_t *)logits, (uint32_t *)out, row_stride, V, W, mask, ninf);
     } else {
         const uint16_t ninf = 0xFF80u;
-        if (aligned) hipLaunchKernelGGL((apply_mask_vec_kernel<u32x4, 8, uint16_t>), grid, dim3(256), 0, s, (const uint16_t *)logits, (uint16_t *)out, row_stride, V, W, mask, ninf);
+        if (aligned) launch_apply_vec<8, uint16_t>((const uint16_t *)logits, (uint16_t *)out, row_stride, V, W, batch, mask, ninf, s);
         else hipLaunchKernelGGL((apply_mask_scalar_kernel<uint16_t>), grid, dim3(256), 0, s, (const uint16_t *)logits, (uint16_t *)out, row_stride, V, W, mask, ninf);
     }
     return hipGetLastError();
