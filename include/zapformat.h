@@ -76,10 +76,14 @@ typedef struct {
                                   keyed by the row's pruned chart; 0 = default (2048 rows), -1 = off */
     int32_t disable_token_mask_cache; /* 1 = every token goes through the parser walk (Section 4.3
                                   optimisation off); masks are identical either way */
-    int32_t walk_mode;     /* which mask kernel checks the tokens the token-mask cache leaves undecided:
-                              0 = mask automaton (a block builds the row's automaton of Earley sets over
-                              byte classes lazily in LDS; one lane per token string), 1 = trie walk (one
-                              wavefront per chunk of the vocabulary trie).  Masks are identical. */
+    int32_t walk_mode;     /* which mask kernel checks the tokens the token-mask cache leaves undecided (masks are identical):
+                              0 = per-block automaton (a block builds the row's automaton of Earley sets over byte classes
+                              lazily in LDS, from the row's uploaded chart; one lane per token string),
+                              1 = trie walk (one wavefront per chunk of the vocabulary trie),
+                              2 = persistent automaton (one automaton for all rows and steps, kept in device memory: Earley sets
+                              named by content; a call uploads the bytes fed since the last call, not the charts, and a transition
+                              is computed once per engine; needs pruning = 1, else mode 0 runs in its place).  A call the
+                              persistent automaton has no room for is answered by mode 0 when it is a waiting call. */
 } zf_options;
 
 typedef struct {
@@ -165,13 +169,12 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states /* host array */, int3
  * behind them.  ZF_ERR_OVERFLOW, if any, is reported by zf_mask_wait.  At most 4 calls may be in
  * flight between two zf_mask_wait calls; calls on one engine must all use the same stream and must
  * not overlap from several host threads.
- *   zf_mask_wait returns once the mask kernels of the calls in flight have reported their status
- * (their last kernel writes it to pinned host memory, which the call polls; bounded: after two
- * seconds it synchronises the stream instead).  It does NOT wait for work the caller queued behind
- * them (zf_apply_mask, a sampler), and the mask tensor is to be consumed in stream order: queue its
- * readers on hip_stream, or synchronise the stream before reading it from the host or from another
- * stream (zf_compute_mask, the waiting call, does synchronise).  With no call in flight
- * zf_mask_wait synchronises hip_stream. */
+ *   zf_mask_wait returns once the mask kernels of the calls in flight are complete (the block of their
+ * last kernel that finishes last writes their status to pinned host memory, which the call polls; bounded:
+ * after two seconds it synchronises the stream instead).  It does NOT wait for work the caller queued
+ * behind them (zf_apply_mask, a sampler); readers of the mask tensor on hip_stream need nothing more,
+ * a reader on the host or on another stream synchronises the stream first (zf_compute_mask, the waiting
+ * call, does).  With no call in flight zf_mask_wait synchronises hip_stream. */
 int zf_compute_mask_async(zf_engine *e, zf_state *const *states /* host array */, int32_t batch,
                           uint32_t *d_mask, void *hip_stream);
 int zf_mask_wait(zf_engine *e, void *hip_stream);

@@ -577,43 +577,67 @@ __device__ __forceinline__ void fallback_wave(const MaskArgs &a, uint32_t gw, ui
 // The closing kernel of a call: the fallback pass (rare) and the permutation of the verdicts from
 // string-rank order into token order, in one launch.  As a kernel of its own the fallback pass costs
 // 4.5 us per call even when its list is empty (a launch and two dependent loads), and with the mask
-// automaton almost every call leaves it empty.
-//   When the list is not empty, the wavefronts of the blocks with the lowest linear index (workgroups
-// are started in index order, so these are resident before any other) walk the listed chunks first
-// and count themselves off; every block then waits for that count before it reads the verdicts.  The
-// fallback wavefronts wait for nothing, so the wait ends; it is bounded all the same, and running
+// automata almost every call leaves it empty.
+//   When the list is not empty, the wavefronts of the blocks with the lowest linear index walk the
+// listed chunks first and count themselves off; every block then waits for that count before it
+// reads the verdicts.  The host sizes the grid so that the chip holds all of its blocks at once
+// (blocks loop over row groups when a batch has more of them): every block that waits is resident
+// together with the wavefronts it waits for, whatever the order the blocks were started in, and the
+// fallback wavefronts wait for nothing, so the wait ends.  It is bounded all the same, and running
 // into the bound makes the call fail with ZF_ERR_OVERFLOW.
 //   Permutation: verdicts are produced in trie order, the caller wants bit v at word v >> 5.  One lane
 // per token and PERMUTE_ROWS rows looks the token's rank up once, and a wavefront ballot packs 64
 // verdicts into two words.
+//   Hand-over: every block draws a ticket when it is done; the block that draws the last one copies
+// the call's counters to pinned host memory and then writes the word the host polls, so the counters
+// are final and the word means "the mask is complete".
 static const int FINISH_BLOCK = 256;
 static const int FINISH_WAVES = FINISH_BLOCK / 64;
 static const int PERMUTE_ROWS = 4;
 static const int PERMUTE_AHEAD = 4;                   // rank look-ups a thread has in flight
 static const uint32_t FINISH_SPIN_LIMIT = 1u << 21;   // polls of about 2 us each
+
+// What the last kernel of a call does at the end of every block (`ticket` = the counter word its tickets are drawn from).
+__device__ __forceinline__ void hand_over(const MaskArgs &a, uint32_t ticket, uint32_t n_blocks) {
+    __shared__ uint32_t last;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // this block's counts before its ticket
+        last = atomicAdd(&a.counters[ticket], 1u) == n_blocks - 1 ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    if (threadIdx.x < 8) a.counters_next[threadIdx.x] = 0;   // the next call's set (no separate memset)
+    if (threadIdx.x == 0) {                                  // counters first, then the word the host waits for
+        for (int i = 0; i < 4; i++) a.host_status[i] = __hip_atomic_load(&a.counters[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (a.store.ctl) for (int i = 0; i < 3; i++) a.host_status[5 + i] = __hip_atomic_load(&a.store.ctl[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&a.host_status[4], a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+}
+
 // STAGED: the block copies its rows of the rank-ordered bitmap into LDS first (PERMUTE_ROWS x Wr words) and serves a
 // long run of tokens from there: 64 lanes that look 64 unrelated ranks up in global memory are 64 cache-line requests
 // per instruction, which is what bounded the unstaged version (5 us at 16 rows, 16 us at 64).  The unstaged version
-// remains for vocabularies whose rows do not fit LDS.
+// remains for vocabularies whose rows do not fit LDS and for small batches.
 template <bool STAGED>
-__global__ __launch_bounds__(FINISH_BLOCK) void finish_kernel(MaskArgs a, uint32_t tokens_per_block) {
+__global__ __launch_bounds__(FINISH_BLOCK) void finish_kernel(MaskArgs a, uint32_t tokens_per_block, uint32_t row_groups) {
     extern __shared__ __align__(16) uint32_t rows_lds[];
     const DeviceTables &D = a.tab;
-    const uint32_t tid = threadIdx.x, lane = tid & 63;
-    const uint32_t row0 = blockIdx.y * PERMUTE_ROWS, Wr = (uint32_t)D.Wr;
-    const uint32_t n_rows = (uint32_t)a.batch - row0 < (uint32_t)PERMUTE_ROWS ? (uint32_t)a.batch - row0 : (uint32_t)PERMUTE_ROWS;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, Wr = (uint32_t)D.Wr;
     const uint32_t v_begin = blockIdx.x * tokens_per_block;            // a multiple of 64: a wavefront's ballot is two whole words
     const uint32_t v_end = v_begin + tokens_per_block < (uint32_t)D.V ? v_begin + tokens_per_block : (uint32_t)D.V;
-    constexpr int AHEAD = STAGED ? PERMUTE_AHEAD : 1;     // unstaged: one token per thread (tokens_per_block = FINISH_BLOCK)
-    uint32_t r_ahead[AHEAD];                              // requested alongside the fallback count: they do not depend on it
+    constexpr int AHEAD = STAGED ? PERMUTE_AHEAD : 1;
+    uint32_t r_first[AHEAD];                              // requested alongside the fallback count: they do not depend on it
 #pragma unroll
     for (int u = 0; u < AHEAD; u++) {
         const uint32_t v = v_begin + (uint32_t)u * FINISH_BLOCK + tid;
-        r_ahead[u] = v < v_end ? D.rank_of[v] : 0xFFFFFFFFu;
+        r_first[u] = v < v_end ? D.rank_of[v] : 0xFFFFFFFFu;
     }
+    const uint32_t n_blocks = gridDim.x * gridDim.y;
     const uint32_t n_over = a.counters[0];
     if (n_over != 0) {
-        const uint32_t lin = blockIdx.y * gridDim.x + blockIdx.x, n_blocks = gridDim.x * gridDim.y;
+        const uint32_t lin = blockIdx.y * gridDim.x + blockIdx.x;
         const uint32_t fb_waves = n_blocks * FINISH_WAVES < a.fb_waves ? n_blocks * FINISH_WAVES : a.fb_waves;
         const uint32_t gw = lin * FINISH_WAVES + (tid >> 6);
         if (gw < fb_waves) {
@@ -631,57 +655,54 @@ __global__ __launch_bounds__(FINISH_BLOCK) void finish_kernel(MaskArgs a, uint32
         __syncthreads();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
-    const uint32_t *rows = a.rank_mask + (size_t)row0 * Wr;           // the block's rows are neighbours in memory
-    if (STAGED) {
-        const uint32_t n_words = n_rows * Wr, n16 = n_words / 4;
-        const uint4 *src = reinterpret_cast<const uint4 *>(rows);     // row0 * Wr * 4 bytes: 16-byte aligned when Wr is a multiple of 4
-        if (((size_t)row0 * Wr) % 4 == 0) {
-            for (uint32_t k = tid; k < n16; k += FINISH_BLOCK) reinterpret_cast<uint4 *>(rows_lds)[k] = src[k];
-            for (uint32_t k = n16 * 4 + tid; k < n_words; k += FINISH_BLOCK) rows_lds[k] = rows[k];
-        } else {
-            for (uint32_t k = tid; k < n_words; k += FINISH_BLOCK) rows_lds[k] = rows[k];
-        }
-        __syncthreads();
-        rows = rows_lds;
-    }
-    for (uint32_t v0 = v_begin; v0 < v_end; v0 += AHEAD * FINISH_BLOCK) {
-        uint32_t r_next[AHEAD];
+    for (uint32_t rg = blockIdx.y; rg < row_groups; rg += gridDim.y) {
+        const uint32_t row0 = rg * PERMUTE_ROWS;
+        const uint32_t n_rows = (uint32_t)a.batch - row0 < (uint32_t)PERMUTE_ROWS ? (uint32_t)a.batch - row0 : (uint32_t)PERMUTE_ROWS;
+        uint32_t r_ahead[AHEAD];
 #pragma unroll
-        for (int u = 0; u < AHEAD; u++) {                              // the next round's ranks are requested before this round's are used
-            const uint32_t v = v0 + (uint32_t)(AHEAD + u) * FINISH_BLOCK + tid;
-            r_next[u] = (STAGED && v < v_end) ? D.rank_of[v] : 0xFFFFFFFFu;
-        }
-#pragma unroll
-        for (int u = 0; u < AHEAD; u++) {
-            const uint32_t v = v0 + (uint32_t)u * FINISH_BLOCK + tid, r = r_ahead[u];
-            if (v0 + (uint32_t)u * FINISH_BLOCK >= v_end) break;      // uniform over the block
-            uint32_t word[PERMUTE_ROWS];
-#pragma unroll
-            for (int k = 0; k < PERMUTE_ROWS; k++)                     // all rows' words are requested before the first one is used
-                word[k] = (r != 0xFFFFFFFFu && (uint32_t)k < n_rows) ? rows[(size_t)k * Wr + (r >> 5)] : 0u;
-            const uint32_t w = v >> 5;
-#pragma unroll
-            for (int k = 0; k < PERMUTE_ROWS; k++) {
-                const unsigned long long b = __ballot((word[k] >> (r & 31)) & 1u);
-                if ((uint32_t)k < n_rows && (lane & 31) == 0 && v < v_end)   // v is the word's first token; words past the block's run belong to the next block
-                    a.out_mask[(size_t)(a.dst_row ? a.dst_row[row0 + k] : row0 + k) * D.W + w] = (uint32_t)(b >> lane);
+        for (int u = 0; u < AHEAD; u++) r_ahead[u] = r_first[u];
+        const uint32_t *rows = a.rank_mask + (size_t)row0 * Wr;           // the group's rows are neighbours in memory
+        if (STAGED) {
+            if (rg != blockIdx.y) __syncthreads();                        // the previous group's readers are done with the LDS copy
+            const uint32_t n_words = n_rows * Wr, n16 = n_words / 4;
+            const uint4 *src = reinterpret_cast<const uint4 *>(rows);     // row0 * Wr * 4 bytes: 16-byte aligned when Wr is a multiple of 4
+            if (((size_t)row0 * Wr) % 4 == 0) {
+                for (uint32_t k = tid; k < n16; k += FINISH_BLOCK) reinterpret_cast<uint4 *>(rows_lds)[k] = src[k];
+                for (uint32_t k = n16 * 4 + tid; k < n_words; k += FINISH_BLOCK) rows_lds[k] = rows[k];
+            } else {
+                for (uint32_t k = tid; k < n_words; k += FINISH_BLOCK) rows_lds[k] = rows[k];
             }
+            __syncthreads();
+            rows = rows_lds;
         }
+        for (uint32_t v0 = v_begin; v0 < v_end; v0 += AHEAD * FINISH_BLOCK) {
+            uint32_t r_next[AHEAD];
 #pragma unroll
-        for (int u = 0; u < AHEAD; u++) r_ahead[u] = r_next[u];
-    }
-    // The call's last kernel hands the counters to the host and clears the next call's set.  The block that is started
-    // last does it, at its end: by then nearly all of the grid has finished (the word the host polls says "the status is
-    // known"; consumers of the mask are ordered behind this kernel by the stream).
-    if (blockIdx.x == gridDim.x - 1 && blockIdx.y == gridDim.y - 1 && a.handoff_in_permute) {
-        __syncthreads();
-        if (tid < 8) a.counters_next[tid] = 0;
-        if (tid == 0) {                                   // counters first, then the word the host waits for
-            for (int i = 0; i < 4; i++) a.host_status[i] = __hip_atomic_load(&a.counters[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (a.store.ctl) for (int i = 0; i < 3; i++) a.host_status[5 + i] = __hip_atomic_load(&a.store.ctl[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&a.host_status[4], a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+            for (int u = 0; u < AHEAD; u++) {                              // the next round's ranks are requested before this round's are used
+                const uint32_t v = v0 + (uint32_t)(AHEAD + u) * FINISH_BLOCK + tid;
+                r_next[u] = v < v_end ? D.rank_of[v] : 0xFFFFFFFFu;
+            }
+#pragma unroll
+            for (int u = 0; u < AHEAD; u++) {
+                const uint32_t v = v0 + (uint32_t)u * FINISH_BLOCK + tid, r = r_ahead[u];
+                if (v0 + (uint32_t)u * FINISH_BLOCK >= v_end) break;      // uniform over the block
+                uint32_t word[PERMUTE_ROWS];
+#pragma unroll
+                for (int k = 0; k < PERMUTE_ROWS; k++)                     // all rows' words are requested before the first one is used
+                    word[k] = (r != 0xFFFFFFFFu && (uint32_t)k < n_rows) ? rows[(size_t)k * Wr + (r >> 5)] : 0u;
+                const uint32_t w = v >> 5;
+#pragma unroll
+                for (int k = 0; k < PERMUTE_ROWS; k++) {
+                    const unsigned long long b = __ballot((word[k] >> (r & 31)) & 1u);
+                    if ((uint32_t)k < n_rows && (lane & 31) == 0 && v < v_end)   // v is the word's first token; words past the block's run belong to the next block
+                        a.out_mask[(size_t)(a.dst_row ? a.dst_row[row0 + k] : row0 + k) * D.W + w] = (uint32_t)(b >> lane);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < AHEAD; u++) r_ahead[u] = r_next[u];
         }
     }
+    if (a.handoff_in_permute) hand_over(a, 5, n_blocks);
 }
 
 }  // namespace
@@ -697,8 +718,9 @@ hipError_t prepare_walk_kernels() {
     hipError_t e;
 #define SET_ATTR(k) if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k), hipFuncAttributeMaxDynamicSharedMemorySize, max_lds)) != hipSuccess) return e
     SET_ATTR(mask_walk_kernel<0>); SET_ATTR(mask_walk_kernel<1>); SET_ATTR(mask_walk_kernel<2>);
-    SET_ATTR(finish_kernel<true>);
 #undef SET_ATTR
+    // the closing kernel also has a static word of LDS (hand_over): leave room for it below the 160 KB
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&finish_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024)) != hipSuccess) return e;
     return hipSuccess;
 }
 
@@ -732,22 +754,41 @@ hipError_t launch_mask_walk(const MaskArgs &a, hipStream_t s) {
 hipError_t launch_finish(const MaskArgs &a, int cus, hipStream_t s) {
     const uint32_t row_groups = (uint32_t)(a.batch + PERMUTE_ROWS - 1) / PERMUTE_ROWS;
     const uint32_t lds = (uint32_t)PERMUTE_ROWS * (uint32_t)a.tab.Wr * 4u;
-    // staged: about two blocks per compute unit, each serving a run of tokens (a multiple of 64) from its LDS copy of the rows;
+    const uint32_t n_cu = (uint32_t)(cus > 0 ? cus : 256);
+    // staged: about four blocks per compute unit, each serving a run of tokens (a multiple of 64) from its LDS copy of the rows;
     // unstaged: one block per 256 tokens, one token per thread.  Staging pays when a block's run is long enough to earn the copy
     // back: from 1024 tokens on, with four blocks per compute unit (config 3, 16 rows: 5.1 us unstaged, 5.9 us staged with runs
     // of 512; config 4, 64 rows: 13.4 us unstaged, 9.4 us staged with runs of 2016; one, two, eight blocks per unit: 16.2, 11.4, 12.2 us).
     uint32_t x_blocks = ((uint32_t)a.tab.V + FINISH_BLOCK - 1) / FINISH_BLOCK;
-    const uint32_t want = (4u * (uint32_t)(cus > 0 ? cus : 256) + row_groups - 1) / row_groups;
+    const uint32_t want = (4u * n_cu + row_groups - 1) / row_groups;
     const bool staged = lds <= 150u * 1024u && (uint32_t)a.tab.V / (want > 0 ? want : 1u) >= 1024u;
     if (staged && want < x_blocks) x_blocks = want;
     if (x_blocks < 1) x_blocks = 1;
-    uint32_t tokens_per_block = staged ? (((uint32_t)a.tab.V + x_blocks - 1) / x_blocks + 63u) & ~63u : (uint32_t)FINISH_BLOCK;
+    // The chip must hold the whole grid at once (blocks may wait for the fallback wavefronts of other blocks): ask the runtime how
+    // many blocks a compute unit takes, and let blocks loop over row groups, then over longer token runs, when there are more.
+    static int occ[2] = {0, 0};
+    static uint32_t occ_lds = 0xFFFFFFFFu;
+    if (!occ[staged] || (staged && occ_lds != lds)) {
+        int n = 0;
+        const hipError_t e = staged ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, finish_kernel<true>, FINISH_BLOCK, lds)
+                                    : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, finish_kernel<false>, FINISH_BLOCK, 0);
+        if (e != hipSuccess) return e;
+        occ[staged] = n < 1 ? 1 : n;
+        if (staged) occ_lds = lds;
+    }
+    const uint32_t cap = (uint32_t)occ[staged] * n_cu;
+    uint32_t y_blocks = row_groups;
+    if (x_blocks * y_blocks > cap) {
+        y_blocks = cap / x_blocks < 1 ? 1 : (cap / x_blocks < row_groups ? cap / x_blocks : row_groups);
+        if (x_blocks * y_blocks > cap) x_blocks = cap;           // a single row group per pass and still too many blocks: longer token runs
+    }
+    uint32_t tokens_per_block = (((uint32_t)a.tab.V + x_blocks - 1) / x_blocks + (staged ? 63u : (uint32_t)FINISH_BLOCK - 1)) & ~(staged ? 63u : (uint32_t)FINISH_BLOCK - 1);
     if (tokens_per_block < 64) tokens_per_block = 64;
     x_blocks = ((uint32_t)a.tab.V + tokens_per_block - 1) / tokens_per_block;
     if (x_blocks < 1) x_blocks = 1;
-    dim3 grid(x_blocks, row_groups);
-    if (staged) hipLaunchKernelGGL(finish_kernel<true>, grid, dim3(FINISH_BLOCK), lds, s, a, tokens_per_block);
-    else hipLaunchKernelGGL(finish_kernel<false>, grid, dim3(FINISH_BLOCK), 0, s, a, tokens_per_block);
+    dim3 grid(x_blocks, y_blocks);
+    if (staged) hipLaunchKernelGGL(finish_kernel<true>, grid, dim3(FINISH_BLOCK), lds, s, a, tokens_per_block, row_groups);
+    else hipLaunchKernelGGL(finish_kernel<false>, grid, dim3(FINISH_BLOCK), 0, s, a, tokens_per_block, row_groups);
     return hipGetLastError();
 }
 }  // namespace zf

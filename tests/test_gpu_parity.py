@@ -600,6 +600,40 @@ def test_many_rows_and_longest_token(mode, torch_cuda, oracle_lib):
         assert (got[r] == so[r].mask(off, data, 4)).all(), r
 
 
+@pytest.mark.parametrize("mode", ["automaton", "store"])
+def test_largest_batch_closing_kernel_loops_over_row_groups(mode, torch_cuda, oracle_lib):
+    """4,096 rows (the largest batch a call takes) over a vocabulary of 1,000 tokens: the closing kernel's grid is capped at
+    what the chip holds at once, so its blocks loop over the 1,024 row groups; with a budget of one item the per-block
+    automaton sends strings through the fallback pass, whose wavefronts the other blocks of that grid wait for."""
+    import paper_2506_01151_amd as zf
+    torch = torch_cuda
+    cfg = configs.CONFIGS[1]
+    g = cfg.grammar()
+    toks = cfg.vocab(1000)
+    off, data = wvocab.vocab_csr(toks)
+    orc = oracle_lib.Oracle(g)
+    kw = {"lane_item_cap": 1} if mode == "automaton" else {}
+    eng = zf.Engine(g, toks, device=0, state_cache_entries=-1, walk_mode=MODES[mode], **kw)
+    pieces = [b"", b"[", b'{"a":', b'{"a": "', b"[1, 2", b'[{"k": [', b"tr", b'"abc', b"[[[", b'{"k":"v"', b"-1.5e", b'["\\u00', b"[1.0"]
+    want, proto = [], []
+    for p in pieces:
+        a, b = orc.new_state(), eng.new_state()
+        assert a.feed_bytes(p)
+        b.advance_bytes(p)
+        want.append(a.mask(off, data, 4))
+        proto.append(b)
+    rows = 4096
+    rs = stream(cfg.seed, "largest-batch")
+    pick = [rs.below(len(pieces)) for _ in range(rows)]
+    ss = [proto[k] for k in pick]                          # a state may be named many times in one call
+    d_mask = torch.full((rows, eng.W), -1, dtype=torch.int32, device="cuda")
+    zf.compute_mask(eng, ss, d_mask)
+    got = d_mask.cpu().numpy().view(np.uint32)
+    assert (got == np.stack([want[k] for k in pick])).all()
+    if mode == "automaton":
+        assert eng.mask_report().overflow_chunks > 0
+
+
 @pytest.mark.parametrize("cap", [None, 1], ids=["default-budget", "budget-1"])
 def test_ragged_vocabulary_many_rows_closing_kernel(cap, torch_cuda, oracle_lib):
     """130 rows (a last group of two) over a vocabulary of 40,037 tokens (not a multiple of 32 or 64): the
