@@ -169,12 +169,13 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states /* host array */, int3
  * behind them.  ZF_ERR_OVERFLOW, if any, is reported by zf_mask_wait.  At most 4 calls may be in
  * flight between two zf_mask_wait calls; calls on one engine must all use the same stream and must
  * not overlap from several host threads.
- *   zf_mask_wait returns once the mask kernels of the calls in flight are complete (the block of their
- * last kernel that finishes last writes their status to pinned host memory, which the call polls; bounded:
- * after two seconds it synchronises the stream instead).  It does NOT wait for work the caller queued
- * behind them (zf_apply_mask, a sampler); readers of the mask tensor on hip_stream need nothing more,
- * a reader on the host or on another stream synchronises the stream first (zf_compute_mask, the waiting
- * call, does).  With no call in flight zf_mask_wait synchronises hip_stream. */
+ *   zf_mask_wait returns once the status of the calls in flight is final (a block of their last kernel writes
+ * it to pinned host memory, which the call polls; when the fallback pass had work, whose waits can fail, it is
+ * the block that finishes last; bounded: after two seconds the stream is synchronised instead).  It does NOT
+ * wait for work the caller queued behind them (zf_apply_mask, a sampler), and the mask tensor is to be
+ * consumed in stream order: queue its readers on hip_stream, or synchronise the stream before reading it
+ * from the host or from another stream (zf_compute_mask, the waiting call, does synchronise).  With no call
+ * in flight zf_mask_wait synchronises hip_stream. */
 int zf_compute_mask_async(zf_engine *e, zf_state *const *states /* host array */, int32_t batch,
                           uint32_t *d_mask, void *hip_stream);
 int zf_mask_wait(zf_engine *e, void *hip_stream);

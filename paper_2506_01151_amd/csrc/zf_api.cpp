@@ -185,8 +185,8 @@ int setup_device(zf_engine *e) {
     }
     if (walk_lds_bytes(T, d->mode, e->opt.lane_item_cap) > 160u * 1024u)
         return fail(ZF_ERR_INVALID_ARG, "lane_item_cap and the grammar tables do not fit the 160 KB of LDS");
-    HIP_TRY(hipMalloc((void **)&d->d_counters, 64));     // two sets of eight counters (see MaskArgs::counters)
-    HIP_TRY(hipMemset(d->d_counters, 0, 64));
+    HIP_TRY(hipMalloc((void **)&d->d_counters, 2 * COUNTER_SET_WORDS * 4));     // two sets of counters (see MaskArgs::counters)
+    HIP_TRY(hipMemset(d->d_counters, 0, 2 * COUNTER_SET_WORDS * 4));
     HIP_TRY(hipHostMalloc((void **)&d->h_status, 32 * DeviceSide::N_SLOTS, hipHostMallocDefault));
     memset(d->h_status, 0, 32 * DeviceSide::N_SLOTS);
     for (auto &ev : d->stage_done) HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
@@ -801,7 +801,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     size_t scr_ss = 0, scr_fb = 0, scr_rank = 0, scr_chart = 0, scr_work = 0, scr_ovf = 0, scr_ovf_cap = 0;
     if (noalloc) {
         auto align256 = [](size_t x) { return (x + 255) & ~(size_t)255; };
-        scr_ss = 256;
+        scr_ss = 1024;
         scr_fb = align256(scr_ss + (size_t)(FB_DEPTH_MAX + 2) * NOALLOC_FB_WAVES * 4);
         scr_rank = align256(scr_fb + (size_t)NOALLOC_FB_WAVES * NOALLOC_FB_ITEMS_PER_WAVE * sizeof(uint2));
         scr_chart = align256(scr_rank + need_rank * 4 + 16);
@@ -842,10 +842,10 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     a.user_batch = batch;
     a.handoff_in_permute = sc ? 0 : 1;
     if (noalloc) {                                        // cleared at the head of the call; counters_next is a spare set
-        a.counters = (uint32_t *)scr; a.counters_next = (uint32_t *)scr + 8;
+        a.counters = (uint32_t *)scr; a.counters_next = (uint32_t *)scr + COUNTER_SET_WORDS;
     } else {
-        a.counters = d->d_counters + 8 * d->call_parity;
-        a.counters_next = d->d_counters + 8 * (d->call_parity ^ 1u);
+        a.counters = d->d_counters + COUNTER_SET_WORDS * d->call_parity;
+        a.counters_next = d->d_counters + COUNTER_SET_WORDS * (d->call_parity ^ 1u);
         d->call_parity ^= 1u;
     }
     a.work = noalloc ? (uint4 *)(scr + scr_work) : d->d_work;
@@ -937,7 +937,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     d->report.main_ms = d->report.fallback_ms = d->report.permute_ms = 0.f;
     d->report.overflow_chunks = d->report.walk_chunks = d->report.parser_steps = 0;
     // everything the host has to work out is done: enqueue the upload and the kernels back to back
-    if (noalloc) HIP_TRY(launch_clear_words((uint32_t *)scr, 16, stream));   // the array keeps the last call's counters
+    if (noalloc) HIP_TRY(launch_clear_words((uint32_t *)scr, 2 * COUNTER_SET_WORDS, stream));   // the array keeps the last call's counters
     if (!direct) HIP_TRY(launch_upload(d->h_stage[slot], chart_base, total, stream));
     const bool run_kernels = nb > 0;
     if (run_kernels && d->tab.n_chunks > 0 && !automaton) HIP_TRY(launch_cache_merge(a, stream));
@@ -1100,8 +1100,8 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
     a.user_mask = d_mask;
     a.user_batch = batch;
     a.handoff_in_permute = sc ? 0 : 1;
-    a.counters = d->d_counters + 8 * d->call_parity;
-    a.counters_next = d->d_counters + 8 * (d->call_parity ^ 1u);
+    a.counters = d->d_counters + COUNTER_SET_WORDS * d->call_parity;
+    a.counters_next = d->d_counters + COUNTER_SET_WORDS * (d->call_parity ^ 1u);
     d->call_parity ^= 1u;
     a.host_status = d->h_status + 8 * slot;
     if (++d->call_seq == 0) d->call_seq = 1;

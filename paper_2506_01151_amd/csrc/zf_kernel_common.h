@@ -109,6 +109,39 @@ __device__ __forceinline__ BaseG global_base(const MaskArgs &a, uint32_t row) {
     return B;
 }
 
+// What the last kernel of a call does at the end of every block: one block copies the call's counters to pinned host memory,
+// clears the next call's set, and then writes the word the host polls.  ticketed = false: the counters were final before this
+// kernel started (nothing in it can fail), and the block with the highest index does it at its end: the word then says "the
+// status is known", and readers of the mask are ordered behind the kernel by the stream.  ticketed = true (the closing kernel
+// with a fallback pass to run, whose waits can fail): every block draws a ticket when it is done and the block that draws
+// the last one does it, so that no error is counted after the hand-over.  Tickets are drawn in two levels (group of blocks,
+// then groups); even so they cost the kernel 5 us at 2,004 blocks (a ticket is a round trip to memory), which is why the
+// common case does without.  (An error count is a device-scope atomic followed by the counting wavefront's own release
+// fence; a fence in every block would write the L2 back each time: 6 -> 34 us.)
+__device__ __forceinline__ void hand_over(const MaskArgs &a, uint32_t lin, uint32_t n_blocks, bool ticketed) {
+    __shared__ uint32_t last;
+    if (!ticketed) { if (lin != n_blocks - 1) return; }
+    __syncthreads();
+    if (ticketed) {
+        if (threadIdx.x == 0) {
+            const uint32_t n_groups = n_blocks < (uint32_t)TICKET_GROUPS ? n_blocks : (uint32_t)TICKET_GROUPS;
+            const uint32_t g = lin % n_groups, size = n_blocks / n_groups + (g < n_blocks % n_groups ? 1u : 0u);
+            uint32_t is_last = 0;
+            if (atomicAdd(&a.counters[TICKET_AT + g], 1u) == size - 1) is_last = atomicAdd(&a.counters[TICKET_TOP], 1u) == n_groups - 1 ? 1u : 0u;
+            last = is_last;
+        }
+        __syncthreads();
+        if (!last) return;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
+    for (uint32_t k = threadIdx.x; k < (uint32_t)COUNTER_SET_WORDS; k += blockDim.x) a.counters_next[k] = 0;   // the next call's set (no separate memset)
+    if (threadIdx.x == 0) {                                  // counters first, then the word the host waits for
+        for (int i = 0; i < 4; i++) a.host_status[i] = __hip_atomic_load(&a.counters[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (a.store.ctl) for (int i = 0; i < 3; i++) a.host_status[5 + i] = __hip_atomic_load(&a.store.ctl[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&a.host_status[4], a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+}
+
 inline uint32_t table_bytes(const DeviceTables &t, int mode) {
     uint32_t n = 0;
     if (mode <= 1) for (int k = 0; k < 5; k++) n += t.small_bytes[k];

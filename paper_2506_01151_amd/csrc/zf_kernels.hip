@@ -10,7 +10,7 @@
 // into token order).
 #include <hip/hip_runtime.h>
 #include <algorithm>
-#include "zf_launch.h"
+#include "zf_kernel_common.h"
 
 
 namespace zf {
@@ -28,23 +28,7 @@ __global__ __launch_bounds__(256) void upload_kernel(const uint4 *__restrict__ s
 __global__ __launch_bounds__(256) void gather_kernel(MaskArgs a) {
     const uint32_t w = blockIdx.x * 256 + threadIdx.x, row = blockIdx.y, W = (uint32_t)a.tab.W;
     if (w < W) a.user_mask[(size_t)row * W + w] = a.out_mask[(size_t)a.row_slot[row] * W + w];
-    // every block draws a ticket when it is done; the one that draws the last hands the counters to the host and clears the
-    // next call's set (as the closing kernel does when it is the call's last kernel)
-    __shared__ uint32_t last;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        last = atomicAdd(&a.counters[6], 1u) == gridDim.x * gridDim.y - 1 ? 1u : 0u;
-    }
-    __syncthreads();
-    if (!last) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    if (threadIdx.x < 8) a.counters_next[threadIdx.x] = 0;
-    if (threadIdx.x == 0) {                               // counters first, then the word the host waits for
-        for (int i = 0; i < 4; i++) a.host_status[i] = __hip_atomic_load(&a.counters[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (a.store.ctl) for (int i = 0; i < 3; i++) a.host_status[5 + i] = __hip_atomic_load(&a.store.ctl[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&a.host_status[4], a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
-    }
+    hand_over(a, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y, false);   // the call's last kernel when the state cache is on; nothing in it can fail
 }
 
 // Logit masking (Section 3.3): pure copy-or-(-inf).  The tensor is taken as one run of 16-byte pieces (rows x pieces per

@@ -81,6 +81,11 @@ struct StoreRow {               // one row of a call: 128 bytes, read by a wavef
 };
 static_assert(sizeof(StoreRow) == 128, "a wavefront reads a row's record as 32 words");
 
+// A set of per-call counters: words 0-7 as listed at MaskArgs::counters, then the tickets the blocks of a call's last kernel
+// draw when they are done (one word per group of blocks, so that thousands of blocks do not queue up at one address, and a
+// top word the last block of each group draws from).
+static const int COUNTER_SET_WORDS = 96, TICKET_GROUPS = 64, TICKET_AT = 16, TICKET_TOP = 80;
+
 struct MaskArgs {
     DeviceTables tab;
     StoreView store;
@@ -106,8 +111,8 @@ struct MaskArgs {
     int32_t user_batch;
     int32_t handoff_in_permute; // 1: permute is the call's last kernel (state cache off), else the gather is
     uint32_t *counters;        // [0] chunks passed to the fallback, [1] length of the work queue, [2] chunks nobody could resolve,
-                               // [3] Earley byte steps, [4] fallback wavefronts that have finished, [5] blocks of the closing kernel that
-                               // are done, [6] blocks of the gather kernel that are done; 8 words per set
+                               // [3] Earley byte steps, [4] fallback wavefronts that have finished, [16..80] tickets of the call's last kernel;
+                               // COUNTER_SET_WORDS words per set
     uint32_t *host_status;     // pinned host memory, 8 words: this call's counters [0..3], written by its last kernel, then [4] = seq
     uint32_t seq;              // the call's number (never 0): the last word the call's last kernel writes, which is what the host waits for
     uint32_t *counters_next;   // the next call's counters: cleared by this call's last kernel (no separate memset)

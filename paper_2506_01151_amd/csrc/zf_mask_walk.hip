@@ -588,33 +588,12 @@ __device__ __forceinline__ void fallback_wave(const MaskArgs &a, uint32_t gw, ui
 //   Permutation: verdicts are produced in trie order, the caller wants bit v at word v >> 5.  One lane
 // per token and PERMUTE_ROWS rows looks the token's rank up once, and a wavefront ballot packs 64
 // verdicts into two words.
-//   Hand-over: every block draws a ticket when it is done; the block that draws the last one copies
-// the call's counters to pinned host memory and then writes the word the host polls, so the counters
-// are final and the word means "the mask is complete".
+//   Hand-over: see hand_over (zf_kernel_common.h).
 static const int FINISH_BLOCK = 256;
 static const int FINISH_WAVES = FINISH_BLOCK / 64;
 static const int PERMUTE_ROWS = 4;
 static const int PERMUTE_AHEAD = 4;                   // rank look-ups a thread has in flight
 static const uint32_t FINISH_SPIN_LIMIT = 1u << 21;   // polls of about 2 us each
-
-// What the last kernel of a call does at the end of every block (`ticket` = the counter word its tickets are drawn from).
-__device__ __forceinline__ void hand_over(const MaskArgs &a, uint32_t ticket, uint32_t n_blocks) {
-    __shared__ uint32_t last;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // this block's counts before its ticket
-        last = atomicAdd(&a.counters[ticket], 1u) == n_blocks - 1 ? 1u : 0u;
-    }
-    __syncthreads();
-    if (!last) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    if (threadIdx.x < 8) a.counters_next[threadIdx.x] = 0;   // the next call's set (no separate memset)
-    if (threadIdx.x == 0) {                                  // counters first, then the word the host waits for
-        for (int i = 0; i < 4; i++) a.host_status[i] = __hip_atomic_load(&a.counters[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (a.store.ctl) for (int i = 0; i < 3; i++) a.host_status[5 + i] = __hip_atomic_load(&a.store.ctl[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&a.host_status[4], a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
-    }
-}
 
 // STAGED: the block copies its rows of the rank-ordered bitmap into LDS first (PERMUTE_ROWS x Wr words) and serves a
 // long run of tokens from there: 64 lanes that look 64 unrelated ranks up in global memory are 64 cache-line requests
@@ -649,7 +628,7 @@ __global__ __launch_bounds__(FINISH_BLOCK) void finish_kernel(MaskArgs a, uint32
             uint32_t spins = 0;
             while (__hip_atomic_load(&a.counters[4], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < fb_waves) {
                 __builtin_amdgcn_s_sleep(64);
-                if (++spins > FINISH_SPIN_LIMIT) { atomicAdd(&a.counters[2], 1u); break; }
+                if (++spins > FINISH_SPIN_LIMIT) { atomicAdd(&a.counters[2], 1u); __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); break; }
             }
         }
         __syncthreads();
@@ -702,7 +681,7 @@ __global__ __launch_bounds__(FINISH_BLOCK) void finish_kernel(MaskArgs a, uint32
             for (int u = 0; u < AHEAD; u++) r_ahead[u] = r_next[u];
         }
     }
-    if (a.handoff_in_permute) hand_over(a, 5, n_blocks);
+    if (a.handoff_in_permute) hand_over(a, blockIdx.y * gridDim.x + blockIdx.x, n_blocks, n_over != 0);
 }
 
 }  // namespace
