@@ -987,12 +987,13 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
     // ---- what each launched row sends ----
     import_rows.clear();
     const bool use_cache = !e->opt.disable_token_mask_cache;
-    size_t n_pend = 0, n_ent = 0, n_off = 0, n_items = 0, widest = 0;
+    size_t n_pend = 0, n_ent = 0, n_off = 0, n_items = 0, widest = 0, biggest_set = 0;
     for (int r = 0; r < nb; r++) {
         zf_state *st = states[miss_rows[r]];
         const Chart &c = st->chart;
         const size_t last = c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1];
         widest = std::max(widest, last);
+        for (uint32_t k = 0; k < c.n_sets(); k++) biggest_set = std::max<size_t>(biggest_set, c.set_off[k + 1] - c.set_off[k]);
         if (use_cache) n_ent += last;
         const bool known = st->dev_id == STORE_ROOT_ID || (st->dev_id != 0 && st->dev_epoch == d->store_epoch);
         if (known) n_pend += st->pending.size();
@@ -1109,6 +1110,7 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
     a.fb_waves = FB_WAVES; a.fb_stride = FB_ITEMS_PER_WAVE;   // the closing kernel's fallback pass has nothing to do on this path
     a.batch = nb;
     a.mode = d->mode;
+    a.aut_wide = biggest_set > (size_t)AUT_NARROW_SET_MAX ? 1 : 0;   // a hint: which variant of the byte step to try first on larger sets
     {   // LDS of a block: the staged tables, the cache of table entries, and per wavefront the set under construction
         int scratch = e->lane_cap_auto ? (int)std::min<size_t>(LANE_CAP_MAX, (4 * widest + 128 + 31) / 32 * 32) : e->opt.lane_item_cap;
         while (scratch > 32 && store_lds_bytes(d->tab, d->mode, scratch) > 160u * 1024u) scratch -= 32;

@@ -46,7 +46,7 @@ __device__ __forceinline__ uint32_t t_load(const uint32_t *p) {
     return t;
 }
 
-struct Staging { uint32_t *ctl; uint8_t *smem; const uint8_t *blob; uint32_t n16; uint8_t *rep; const uint8_t *rep_src; uint32_t ncls; };   // what ensure_tables needs
+struct Staging { uint32_t *ctl; uint8_t *smem; const uint8_t *blob; uint32_t n16; uint8_t *rep; const uint8_t *rep_src; uint32_t ncls; bool wide_sets; };   // what ensure_tables needs; wide_sets: the rows' charts hold sets of many items
 // The grammar tables are needed only by a wavefront that computes a transition, which is rare once the automaton has
 // grown: the first such wavefront of a block copies them into LDS (ctl[4]: 0 = not there, 1 = being copied, 2 = there).
 __device__ __forceinline__ bool ensure_tables(const Staging &g, uint32_t lane) {
@@ -62,7 +62,13 @@ __device__ __forceinline__ bool ensure_tables(const Staging &g, uint32_t lane) {
         if (old == 0) {
             const uint4 *src = reinterpret_cast<const uint4 *>(blob);
             uint4 *dst = reinterpret_cast<uint4 *>(smem);
-            for (uint32_t k = lane; k < n16; k += 64) dst[k] = src[k];
+            for (uint32_t k0 = 0; k0 < n16; k0 += 64 * 8) {   // eight 16-byte loads in flight per lane
+                uint4 x[8];
+#pragma unroll
+                for (int u = 0; u < 8; u++) { const uint32_t k = k0 + (uint32_t)u * 64 + lane; x[u] = k < n16 ? src[k] : make_uint4(0, 0, 0, 0); }
+#pragma unroll
+                for (int u = 0; u < 8; u++) { const uint32_t k = k0 + (uint32_t)u * 64 + lane; if (k < n16) dst[k] = x[u]; }
+            }
             for (uint32_t k = lane; k < g.ncls; k += 64) g.rep[k] = g.rep_src[k];   // one byte of every class
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             if (lane == 0) lds_store(&ctl[4], 2u);
@@ -121,7 +127,10 @@ __device__ __forceinline__ uint32_t store_transition(const TV &T, const StoreVie
     uint32_t src_n;
     S.view(s, src_p, src_n);
     const uint32_t byte = rep[cl];
-    int st = src_n > (uint32_t)AUT_NARROW_SET_MAX ? (int)AUT_WIDE : aut_step_narrow<true>(T, S, sc.w, sc.o, sc.cap, s, byte, cl, lane, nnew, kept);
+    // the narrow step takes sets of up to 64 items; where the charts hold wide sets (an ambiguous grammar) a source set of more
+    // than a few items rarely leaves a narrow one, and the narrow step's one-candidate-at-a-time Complete would be wasted
+    const bool wide_first = src_n > 64u || (stg.wide_sets && src_n > (uint32_t)AUT_NARROW_SET_MAX);
+    int st = wide_first ? (int)AUT_WIDE : aut_step_narrow<true>(T, S, sc.w, sc.o, sc.cap, s, byte, cl, lane, nnew, kept);
     if (st == AUT_WIDE) st = aut_step_wide(T, S, sc.w, sc.o, sc.h, sc.cap, s, byte, cl, lane, nnew, kept);
     if (st != AUT_OK) return AT_FAIL;
     if (nnew == 0) return AT_DEAD;
@@ -234,7 +243,7 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a) {
     unsigned long long *lc = reinterpret_cast<unsigned long long *>(smem + off); off += LC_ENTRIES * 8;
     uint32_t *ctl = reinterpret_cast<uint32_t *>(smem + off); off += 32;   // [4] state of the staged tables
     uint32_t *vbuf = reinterpret_cast<uint32_t *>(smem + off) + wave * 16; off += STORE_WAVES * 64;   // per wavefront: verdicts of the pass's 16 words
-    const Staging stg{ctl, smem, D.table_blob, n16, l_rep, D.cls_rep, ncls};
+    const Staging stg{ctl, smem, D.table_blob, n16, l_rep, D.cls_rep, ncls, a.aut_wide != 0};
     Scratch sc;
     sc.cap = (uint32_t)a.aut_scratch;
     sc.w = reinterpret_cast<uint32_t *>(smem + off) + (size_t)wave * (2 * sc.cap + aut_hash_places(sc.cap));
