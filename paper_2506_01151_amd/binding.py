@@ -12,7 +12,8 @@ ZF_OK, ZF_ERR_INVALID_ARG, ZF_ERR_GRAMMAR, ZF_ERR_REJECTED = 0, -1, -2, -3
 ZF_ERR_RANGE, ZF_ERR_DEVICE, ZF_ERR_OOM, ZF_ERR_OVERFLOW = -4, -5, -6, -7
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libzapformat.so")
+# ZAPFORMAT_LIBRARY names another build of the same library (the sanitizer build of paper_2506_01151_amd/build.py --sanitize)
+LIB_PATH = os.environ.get("ZAPFORMAT_LIBRARY") or os.path.join(_HERE, "libzapformat.so")
 _lib = None
 
 c_i32, c_i64, c_vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p

@@ -24,8 +24,19 @@ def _run(cmd):
     return proc.returncode, err
 
 
-def build(force: bool = True, extra_flags=()) -> str:
-    """Compile every source to an object (in parallel; with force=False only what is older than its sources) and link."""
+SANITIZE = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+
+def build(force: bool = True, extra_flags=(), sanitize: bool = False) -> str:
+    """Compile every source to an object (in parallel; with force=False only what is older than its sources) and link.
+    sanitize=True builds libzapformat_asan.so instead: the host code of every source under AddressSanitizer and
+    UndefinedBehaviorSanitizer (the device code is built as always), for the CPU test suite:
+        LD_PRELOAD=$(/opt/rocm/lib/llvm/bin/clang++ -print-file-name=libclang_rt.asan-x86_64.so) ASAN_OPTIONS=detect_leaks=0 \
+        ZAPFORMAT_LIBRARY=paper_2506_01151_amd/libzapformat_asan.so python -m pytest tests -m "not gpu" -q"""
+    global OBJ, LIB
+    if sanitize:
+        OBJ, LIB = os.path.join(HERE, "_build", "asan"), os.path.join(HERE, "libzapformat_asan.so")
+        force, extra_flags = True, list(extra_flags) + SANITIZE
     os.makedirs(OBJ, exist_ok=True)
     deps = [os.path.join(CSRC, h) for h in HEADERS] + [os.path.join(HERE, "..", "include", "zapformat.h"), os.path.join(HERE, "..", "include", "zapformat_debug.h")]
     newest_dep = max(os.path.getmtime(d) for d in deps)
@@ -44,7 +55,8 @@ def build(force: bool = True, extra_flags=()) -> str:
     if failed:
         raise RuntimeError("hipcc failed")
     if jobs or not os.path.exists(LIB):
-        rc, err = _run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + [os.path.join(OBJ, s + ".o") for s in SOURCES])
+        link = ["-fsanitize=address", "-fsanitize=undefined", "-shared-libasan"] if sanitize else []
+        rc, err = _run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + link + [os.path.join(OBJ, s + ".o") for s in SOURCES])
         if err.strip():
             print(err, file=sys.stderr)
         if rc != 0:
@@ -53,4 +65,4 @@ def build(force: bool = True, extra_flags=()) -> str:
 
 
 if __name__ == "__main__":
-    print(build(force="--force" in sys.argv, extra_flags=[a for a in sys.argv[1:] if a.startswith("-D")]))
+    print(build(force="--force" in sys.argv, extra_flags=[a for a in sys.argv[1:] if a.startswith("-D")], sanitize="--sanitize" in sys.argv))

@@ -7,7 +7,7 @@ namespace {
 
 inline int kind(uint16_t code) { return code >> SYM_KIND_SHIFT; }
 
-// "each state set maintains only unique states" (Section 3.2)
+// a set holds each item once (Section 3.2)
 inline void insert(Chart &c, uint32_t set_begin, Item it, int64_t *created) {
     for (size_t i = set_begin; i < c.items.size(); i++)
         if (c.items[i].p == it.p && c.items[i].q == it.q && c.items[i].o == it.o) return;
