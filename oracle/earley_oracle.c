@@ -4,8 +4,8 @@
  * benchmark's CPU-baseline leg use it.
  *
  * A plain textbook Earley recognizer (paper Section 3.2: items (X -> a . b, j),
- * state sets S[0..n], the Predict / Scan / Complete operations, and "each state
- * set maintains only unique states") over a context-free grammar whose terminals
+ * state sets S[0..n], the Predict / Scan / Complete operations, every set holding
+ * an item at most once) over a context-free grammar whose terminals
  * are single-byte classes.  There is no trie, no automaton, no cache and no
  * pruning here.  The per-step vocabulary check (Section 3.3 / 4.1: every token of
  * the vocabulary is tested at every decoding step, invalid logits become -inf)
