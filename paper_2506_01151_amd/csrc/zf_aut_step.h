@@ -1,8 +1,9 @@
 // The wavefront-cooperative Earley byte step (Scan + Complete with tabulated Predict, Section 3.2) that the
 // mask automata are built with, in two variants, and the settling of a new state's dead transitions.  The
-// functions are templates over a "sets view" S: S.view(ref, p, n) resolves an origin reference to the items
-// of the set it names, so the same step serves an automaton that lives in one block's LDS and one that
-// lives in device memory and is kept from call to call.
+// functions are templates over a "sets view" S: S.view(ref, h, n) resolves an origin reference to a handle of
+// the set it names (a 64-bit word: lanes pass it round by shuffle) and its item count, S.item(h, i) reads item
+// i of that set -- so the same step serves an automaton that lives in one block's LDS, one that lives in
+// device memory and is kept from call to call, and the item list of a wavefront that walks the vocabulary trie.
 #pragma once
 #include "zf_kernel_common.h"
 
@@ -27,13 +28,16 @@ enum { AUT_OK = 0, AUT_WIDE = 1, AUT_OVER = 2 };
 static const int AUT_NARROW_TRIES = 96;   // insert attempts after which the narrow variant hands the step to the wide one
 
 // Narrow variant: the set under construction lives in registers (lane j holds new item j), so the
-// duplicate test is one compare + ballot; the source set is read in strips of 64 items.
-template <bool WIDE, class SetsT>
+// duplicate test is one compare + ballot; the source set is read in strips of 64 items.  With ONE_STRIP a
+// source set of more than 64 items is handed to the wide step at once (AUT_WIDE), which saves the strip
+// loop's registers in a kernel that is short of them.
+template <bool WIDE, bool ONE_STRIP = false, class SetsT>
 __device__ __forceinline__ int aut_step_narrow(const TV &T, const SetsT &S, uint32_t *sc_w, uint32_t *sc_o, uint32_t sc_cap,
                                                uint32_t cur, uint32_t byte, uint32_t cl, uint32_t lane, uint32_t &nnew_out, uint32_t &kept_out) {
-    const uint2 *src;
+    uint64_t src;
     uint32_t ns;
     S.view(cur, src, ns);
+    if (ONE_STRIP && ns > 64u) return AUT_WIDE;
     uint32_t nw = 0xFFFFFFFFu, no = 0, nnew = 0, tries = 0;  // no item word is all ones
     bool saw_end = false, failed = false;                    // failed is sticky: the step runs on and reports at its end
     const uint32_t room = sc_cap < 64u ? sc_cap : 64u;
@@ -58,7 +62,7 @@ __device__ __forceinline__ int aut_step_narrow(const TV &T, const SetsT &S, uint
     };
     for (uint32_t s0 = 0; s0 < ns; s0 += 64) {
         uint32_t sw = IW_END, so = 0;                        // lanes beyond the set hold an inert item
-        if (s0 + lane < ns) { const uint2 x = src[s0 + lane]; sw = x.x; so = x.y; }
+        if (s0 + lane < ns) { const uint2 x = S.item(src, s0 + lane); sw = x.x; so = x.y; }
         // Scan, terminal items: all DFA steps at once, then the survivors one after the other
         uint32_t nx = DFA_DEAD, aw = 0;
         if (sw & IW_TERM) {
@@ -100,6 +104,7 @@ __device__ __forceinline__ int aut_step_narrow(const TV &T, const SetsT &S, uint
                 }
             }
         }
+        if (ONE_STRIP) break;
     }
     if (saw_end) {
         // Complete: new items are visited in order; completing may append more
@@ -114,12 +119,12 @@ __device__ __forceinline__ int aut_step_narrow(const TV &T, const SetsT &S, uint
             const uint32_t X = (w & IW_POS_MASK) - T.end_base;
             if (X == T.N - 1) continue;                      // the start rule is complete: the prefix is a sentence
             const uint32_t o = __builtin_amdgcn_readlane(no, i);
-            const uint2 *yp;
+            uint64_t yp;
             uint32_t yn;
             S.view(o, yp, yn);
             for (uint32_t j0 = 0; j0 < yn; j0 += 64) {
                 uint32_t yw = IW_END, yo = 0;
-                if (j0 + lane < yn) { const uint2 y = yp[j0 + lane]; yw = y.x; yo = y.y; }
+                if (j0 + lane < yn) { const uint2 y = S.item(yp, j0 + lane); yw = y.x; yo = y.y; }
                 const bool nt = !(yw & (IW_TERM | IW_END));
                 const uint32_t Y = (yw >> IW_NT_SHIFT) & IW_NT_MASK;
                 uint32_t c0 = 0, c1 = 0, cw0 = 0;
@@ -163,7 +168,7 @@ __host__ __device__ inline uint32_t aut_hash_places(uint32_t sc_cap) {
 template <class SetsT>
 __device__ __forceinline__ int aut_step_wide(const TV &T, const SetsT &S, uint32_t *sc_w, uint32_t *sc_o, uint32_t *sc_h, uint32_t sc_cap,
                                              uint32_t cur, uint32_t byte, uint32_t cl, uint32_t lane, uint32_t &nnew_out, uint32_t &kept_out) {
-    const uint2 *src;
+    uint64_t src;
     uint32_t ns;
     S.view(cur, src, ns);
     const uint32_t places = aut_hash_places(sc_cap), pmask = places - 1u;
@@ -217,7 +222,7 @@ __device__ __forceinline__ int aut_step_wide(const TV &T, const SetsT &S, uint32
     };
     for (uint32_t s0 = 0; s0 < ns && !failed; s0 += 64) {
         uint32_t sw = IW_END, so = 0;                        // lanes beyond the set hold an inert item
-        if (s0 + lane < ns) { const uint2 x = src[s0 + lane]; sw = x.x; so = x.y; }
+        if (s0 + lane < ns) { const uint2 x = S.item(src, s0 + lane); sw = x.x; so = x.y; }
         // Scan, terminal items
         uint32_t nx = DFA_DEAD;
         if (sw & IW_TERM) nx = dfa_next(T, sw >> 16, byte, cl);
@@ -251,14 +256,14 @@ __device__ __forceinline__ int aut_step_wide(const TV &T, const SetsT &S, uint32
             if (done + lane < hi) { w = lds_load(&sc_w[done + lane]); o = lds_load(&sc_o[done + lane]); }
             const uint32_t X = (w & IW_POS_MASK) - T.end_base;
             const bool is_end = (w & IW_END) && X != T.N - 1;                  // the start rule complete: the prefix is a sentence
-            const uint2 *yp = nullptr;
+            uint64_t yp = 0;
             uint32_t yn = 0;
             if (is_end) S.view(o, yp, yn);
             uint32_t incl = yn;                                                // running total of the origin sets' sizes
 #pragma unroll
             for (int d = 1; d < 64; d <<= 1) { const uint32_t up = __shfl_up(incl, d); if (lane >= (uint32_t)d) incl += up; }
             const uint32_t excl = incl - yn, total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-            const uint32_t yp_lo = (uint32_t)(uintptr_t)yp, yp_hi = (uint32_t)((uintptr_t)yp >> 32);
+            const uint32_t yp_lo = (uint32_t)yp, yp_hi = (uint32_t)(yp >> 32);
             unsigned long long owners = __ballot(yn > 0);                      // lanes whose origin set is not dealt out yet
             for (uint32_t t0 = 0; t0 < total && !failed; t0 += 64) {
                 const uint32_t t = t0 + lane;
@@ -272,9 +277,9 @@ __device__ __forceinline__ int aut_step_wide(const TV &T, const SetsT &S, uint32
                     if (e_hi <= t0 + 64u) owners &= ~(1ull << e);
                 }
                 const uint32_t oX = __shfl(X, own), oo = __shfl(o, own), o_lo = __shfl(excl, own);
-                const uint2 *oyp = reinterpret_cast<const uint2 *>((uintptr_t)__shfl(yp_lo, own) | ((uintptr_t)__shfl(yp_hi, own) << 32));
+                const uint64_t oyp = (uint64_t)(uint32_t)__shfl(yp_lo, own) | ((uint64_t)(uint32_t)__shfl(yp_hi, own) << 32);
                 uint32_t yw = IW_END, yo = 0;
-                if (t < total) { const uint2 y = oyp[t - o_lo]; yw = y.x; yo = y.y; }
+                if (t < total) { const uint2 y = S.item(oyp, t - o_lo); yw = y.x; yo = y.y; }
                 const bool nt = !(yw & (IW_TERM | IW_END));
                 const uint32_t Y = (yw >> IW_NT_SHIFT) & IW_NT_MASK;
                 uint32_t c0 = 0, c1 = 0;

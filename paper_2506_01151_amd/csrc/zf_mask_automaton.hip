@@ -40,10 +40,11 @@ template <class BaseT>
 struct AutSets {           // resolves origin references
     const BaseT &B;
     const Aut &A;
-    __device__ __forceinline__ void view(uint32_t ref, const uint2 *&p, uint32_t &n) const {
-        if (ref & AUT_REF) { const uint2 h = A.hdr[ref & ~AUT_REF]; p = A.arena + h.x; n = h.y; }
-        else { const uint32_t lo = B.so[ref]; p = B.it + lo; n = B.so[ref + 1] - lo; }
+    __device__ __forceinline__ void view(uint32_t ref, uint64_t &h, uint32_t &n) const {   // the handle is the address of the set's first item
+        if (ref & AUT_REF) { const uint2 hd = A.hdr[ref & ~AUT_REF]; h = (uint64_t)(uintptr_t)(A.arena + hd.x); n = hd.y; }
+        else { const uint32_t lo = B.so[ref]; h = (uint64_t)(uintptr_t)(B.it + lo); n = B.so[ref + 1] - lo; }
     }
+    __device__ __forceinline__ uint2 item(uint64_t h, uint32_t i) const { return reinterpret_cast<const uint2 *>((uintptr_t)h)[i]; }
 };
 
 // The transition of state s on class cl: take the byte step, then find the state that holds the
@@ -55,7 +56,7 @@ __device__ __forceinline__ uint32_t aut_transition(const TV &T, const BaseT &B, 
     const AutSets<BaseT> S{B, A};
     const uint32_t cur = s == 0 ? B.m - 1 : (AUT_REF | s);   // the source set; also what items predicted in it get as origin
     uint32_t nnew = 0, kept = 0;
-    const uint2 *src_p;
+    uint64_t src_p;
     uint32_t src_n;
     S.view(cur, src_p, src_n);
     int st = WIDE && src_n > (uint32_t)AUT_NARROW_SET_MAX ? AUT_WIDE : aut_step_narrow<WIDE>(T, S, sc_w, sc_o, sc_cap, cur, byte, cl, lane, nnew, kept);   // a wide source set rarely leaves a narrow one

@@ -87,12 +87,13 @@ __device__ __forceinline__ bool ensure_tables(const Staging &g, uint32_t lane) {
 struct StoreSets {             // resolves the name of a set to its items (device memory)
     const StoreView &G;
     uint32_t *errors;
-    __device__ __forceinline__ void view(uint32_t ref, const uint2 *&p, uint32_t &n) const {
+    __device__ __forceinline__ uint2 item(uint64_t h, uint32_t i) const { return reinterpret_cast<const uint2 *>((uintptr_t)h)[i]; }
+    __device__ __forceinline__ void view(uint32_t ref, uint64_t &p, uint32_t &n) const {   // the handle is the address of the set's first item
         uint2 h = make_uint2(0, 0);
         if (ref < G.cap_states) h = G.hdr[ref];
         // a name that leads nowhere cannot come from a correct store: read nothing, and fail the call loudly
         if (ref >= G.cap_states || h.y > G.cap_items || h.x > G.cap_items - h.y) { h = make_uint2(0, 0); atomicAdd(errors, 1u); }
-        p = G.arena + h.x;
+        p = (uint64_t)(uintptr_t)(G.arena + h.x);
         n = h.y;
     }
 };
@@ -123,7 +124,7 @@ __device__ __forceinline__ uint32_t store_transition(const TV &T, const StoreVie
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");      // s and every set it refers to were released before the entry that led here
     const StoreSets S{G, errors};
     uint32_t nnew = 0, kept = 0;
-    const uint2 *src_p;
+    uint64_t src_p;
     uint32_t src_n;
     S.view(s, src_p, src_n);
     const uint32_t byte = rep[cl];

@@ -15,6 +15,7 @@
 // tables are staged in LDS once per block.  What does not fit the LDS budgets repeats the walk in
 // the fallback pass (part of finish_kernel), one wavefront per chunk, with the item list in a global-memory arena.
 #include "zf_kernel_common.h"
+#include "zf_aut_step.h"
 
 namespace zf {
 namespace {
@@ -46,134 +47,38 @@ struct GlobalStore {           // fallback: the wavefront's list in a global-mem
 
 enum { STEP_ALIVE = 1, STEP_KERNEL = 2, STEP_OVERFLOW = 4, STEP_WIDE = 8 /* a set wider than 64 items: redo with wave_step_big */ };
 
-// One Earley byte step at trie depth d (1-based) is done by a whole wavefront with uniform control
-// flow.  The source set is the row's current set for d == 1, else the wavefront's set of depth
-// d-1.  On entry cnt == st.start(d); on exit the new set is stored at [cnt_in, cnt_out).
-// All 64 lanes call it with identical arguments.  Lane i loads source item i, the DFA transitions of all items run in
-// parallel, the set under construction lives in registers (lane j holds new item j) so that the
-// duplicate test is one compare + ballot, and Complete loads S[origin] 64 items at a time.  Sets
-// of more than 64 items are reported as overflow (the fallback handles them).
+// One Earley byte step at trie depth d (1-based): the narrow variant of the shared wavefront-cooperative step
+// (zf_aut_step.h), with the wavefront's item list as the sets view.  The source set is the row's current set for
+// d == 1, else the wavefront's set of depth d-1.  On entry cnt == st.start(d); on exit the new set is stored at
+// [cnt_in, cnt_out).  All 64 lanes call it with identical arguments.  A new set of more than 64 items is reported
+// as STEP_WIDE (wave_step_big takes it), an exhausted item budget as STEP_OVERFLOW (the fallback pass takes the chunk).
+template <class BaseT>
+struct WalkSets {              // a set named by its index: a set of the row's chart, or the wavefront's set of one trie depth
+    const BaseT B;             // copies: the view is made anew for every step
+    const WaveLdsStore st;
+    static constexpr uint64_t IN_LIST = 1ull << 32;   // handle: index of the set's first item, in the wavefront's list with this bit, else in the row's chart
+    __device__ __forceinline__ void view(uint32_t ref, uint64_t &h, uint32_t &n) const {
+        if (ref + 1 == B.m) { h = B.last_lo; n = B.last_hi - B.last_lo; }   // the row's current set: its bounds are at hand, no load
+        else if (ref < B.m) { const uint32_t lo = B.so[ref]; h = lo; n = B.so[ref + 1] - lo; }
+        else { const int dj = (int)(ref - (B.m - 1)); const uint32_t lo = st.start(dj); h = IN_LIST | lo; n = st.start(dj + 1) - lo; }
+    }
+    __device__ __forceinline__ uint2 item(uint64_t h, uint32_t i) const {
+        const uint32_t k = (uint32_t)h + i;
+        if (h & IN_LIST) return make_uint2(st.pq[k], st.org[k]);
+        return B.it[k];
+    }
+};
 template <class BaseT>
 __device__ __forceinline__ int wave_step(const TV &T, const BaseT &B, WaveLdsStore &st, int d, uint32_t byte, uint32_t cl, uint32_t &cnt, uint32_t lane) {
-    const uint32_t nb = cnt;
-    const uint32_t cur = B.m - 1 + (uint32_t)(d - 1);
-    const bool from_base = d == 1;
-    const uint32_t sb = from_base ? B.last_lo : st.start(d - 1);
-    const uint32_t ns = (from_base ? B.last_hi : nb) - sb;
-    if (ns > 64) return STEP_WIDE;
-    uint32_t sw = IW_END, so = 0;                        // lanes beyond the set hold an inert item
-    if (lane < ns) { if (from_base) { const uint2 x = B.it[sb + lane]; sw = x.x; so = x.y; } else st.get(sb + lane, sw, so); }
-    uint32_t nw = 0xFFFFFFFFu, no = 0, nnew = 0;         // the set under construction, one item per lane (no item word is all ones)
-    bool saw_end = false;
-    bool failed = false;                                 // sticky: an item found no room (64 lanes, or the item budget)
-    const uint32_t room = st.cap - nb < 64u ? st.cap - nb : 64u;   // nb <= cap always
-    // No branch in here: an item that does not fit leaves `failed` set and the set as it is; the
-    // step runs on (every loop below is bounded by the tables and by 64 items) and reports at its end.
-    auto insert = [&](uint32_t w, uint32_t o) {          // uniform arguments
-        const bool fresh = __ballot(nw == w && no == o) == 0;
-        const bool add = fresh && nnew < room;
-        failed |= fresh && !add;
-        const bool mine = add && lane == nnew;
-        nw = mine ? w : nw;
-        no = mine ? o : no;
-        nnew += add ? 1u : 0u;
-    };
-    auto advance = [&](uint32_t p, uint32_t o) {         // dot arrives at p: skip nullable nonterminals, canonical END item
-        for (;;) {
-            const uint32_t w = T.advpq[p];
-            insert(w, o);
-            if (w & IW_END) { saw_end = true; return; }
-            if ((w & IW_TERM) || !(w & IW_NT_NULLABLE)) return;
-            p++;
-        }
-    };
-    // Scan, terminal items: all DFA steps at once, then the survivors one after the other
-    uint32_t nx = DFA_DEAD, aw = 0;
-    if (sw & IW_TERM) {
-        aw = T.advpq[(sw & IW_POS_MASK) + 1];            // the item behind the terminal, fetched alongside the DFA step in case the terminal ends here
-        nx = dfa_next(T, sw >> 16, byte, cl);
-    }
-    unsigned long long m = __ballot((nx & 0xFFFFu) != DFA_DEAD);
-    while (m) {
-        const int l = __ffsll((long long)m) - 1;
-        m &= m - 1;
-        const uint32_t lw = __builtin_amdgcn_readlane(sw, l), lo = __builtin_amdgcn_readlane(so, l), lnx = __builtin_amdgcn_readlane(nx, l);
-        if ((lnx >> 16) & QF_CONT) insert((lw & 0xFFFFu) | (lnx << 16), lo);   // no longest match: keep matching ...
-        if ((lnx >> 16) & QF_ACCEPT) {                                                                                        // ... and also finish here
-            const uint32_t law = __builtin_amdgcn_readlane(aw, l);
-            insert(law, lo);
-            if (law & IW_END) saw_end = true;
-            else if (!(law & IW_TERM) && (law & IW_NT_NULLABLE)) advance((lw & IW_POS_MASK) + 2, lo);
-        }
-    }
-    // Scan, items that wait for a nonterminal Y: the tabulated first steps of every terminal that can begin Y
-    uint32_t sk0 = 0, sk1 = 0;                           // every lane looks up the list of its own nonterminal
-    if (!(sw & (IW_TERM | IW_END))) {
-        const uint32_t Y = (sw >> IW_NT_SHIFT) & IW_NT_MASK;
-        sk0 = T.scan_off[Y * T.ncls + cl]; sk1 = T.scan_off[Y * T.ncls + cl + 1];
-    }
-    m = __ballot(sk1 > sk0);
-    while (m) {
-        const int l = __ffsll((long long)m) - 1;
-        m &= m - 1;
-        const uint32_t k0 = __builtin_amdgcn_readlane(sk0, l), k1 = __builtin_amdgcn_readlane(sk1, l);
-        for (uint32_t e0 = k0; e0 < k1; e0 += 64) {
-            uint2 ef = make_uint2(0, 0);
-            if (e0 + lane < k1) ef = T.scan_list[e0 + lane];
-            const uint32_t n_e = k1 - e0 < 64 ? k1 - e0 : 64;
-            for (uint32_t t = 0; t < n_e; t++) {
-                const uint32_t ent = __builtin_amdgcn_readlane(ef.x, t), f = __builtin_amdgcn_readlane(ef.y, t);
-                if (f & QF_CONT) insert(ent, cur);
-                if (f & QF_ACCEPT) advance((ent & IW_POS_MASK) + 1, cur);
-            }
-        }
-    }
-    if (saw_end) {
-        // Complete: new items are visited in order; completing may append more
-        unsigned long long visited = 0;
-        for (;;) {
-            const unsigned long long todo = __ballot(lane < nnew && (nw & IW_END)) & ~visited;
-            if (!todo) break;
-            const int i = __ffsll((long long)todo) - 1;
-            visited |= 1ull << i;
-            const uint32_t w = __builtin_amdgcn_readlane(nw, i);
-            const uint32_t X = (w & IW_POS_MASK) - T.end_base;
-            if (X == T.N - 1) continue;                 // the start rule is complete: the prefix is a sentence
-            const uint32_t o = __builtin_amdgcn_readlane(no, i);
-            const bool in_base = o < B.m;
-            uint32_t jb, je;
-            if (in_base) { jb = B.so[o]; je = B.so[o + 1]; }
-            else { const int dj = (int)(o - (B.m - 1)); jb = st.start(dj); je = st.start(dj + 1); }
-            for (uint32_t j0 = jb; j0 < je; j0 += 64) {
-                uint32_t yw = IW_END, yo = 0;
-                if (j0 + lane < je) { if (in_base) { const uint2 y = B.it[j0 + lane]; yw = y.x; yo = y.y; } else st.get(j0 + lane, yw, yo); }
-                const bool nt = !(yw & (IW_TERM | IW_END));
-                const uint32_t Y = (yw >> IW_NT_SHIFT) & IW_NT_MASK;
-                uint32_t c0 = 0, c1 = 0, cw0 = 0;
-                if (nt) { c0 = T.comp_off[Y * T.N + X]; c1 = T.comp_off[Y * T.N + X + 1]; }
-                if (c1 > c0) cw0 = T.comp_list[c0];     // every lane fetches the first entry of its own list
-                unsigned long long mm = __ballot(nt && c1 > c0);
-                while (mm) {
-                    const int l = __ffsll((long long)mm) - 1;
-                    mm &= mm - 1;
-                    const uint32_t lc0 = __builtin_amdgcn_readlane(c0, l), lc1 = __builtin_amdgcn_readlane(c1, l);
-                    for (uint32_t e = lc0; e < lc1; e++) {
-                        const uint32_t cw = e == lc0 ? (uint32_t)__builtin_amdgcn_readlane(cw0, l) : T.comp_list[e];
-                        if (cw != 0xFFFFFFFFu) insert(cw, o);
-                        else advance((__builtin_amdgcn_readlane(yw, l) & IW_POS_MASK) + 1, __builtin_amdgcn_readlane(yo, l));   // Y itself is complete: the waiting item moves on
-                    }
-                }
-            }
-        }
-    }
-    if (failed) return nnew >= 64u ? STEP_WIDE : STEP_OVERFLOW;   // all lanes taken: the strip-wise step may still fit; else the budget is used up
-    // completed items are needed only while their own set is processed: store the others
-    const bool keep = lane < nnew && !(nw & IW_END);
-    const unsigned long long kb = __ballot(keep);
-    if (keep) st.put(nb + __popcll(kb & ((1ull << lane) - 1ull)), nw, no);
-    cnt = nb + (uint32_t)__popcll(kb);
+    const uint32_t nb = cnt;                             // nb <= cap always
+    const WalkSets<BaseT> S{B, st};
+    uint32_t nnew = 0, kept = 0;
+    const int r = aut_step_narrow<false, true>(T, S, st.pq + nb, st.org + nb, st.cap - nb, B.m - 1 + (uint32_t)(d - 1), byte, cl, lane, nnew, kept);
+    if (r == AUT_WIDE) return STEP_WIDE;
+    if (r == AUT_OVER) return STEP_OVERFLOW;
+    cnt = nb + kept;
     st.set_start(d + 1, cnt);
-    return (nnew ? STEP_ALIVE : 0) | (kb ? STEP_KERNEL : 0);
+    return (nnew ? STEP_ALIVE : 0) | (kept ? STEP_KERNEL : 0);
 }
 
 // The wavefront step for large sets (ambiguous grammars make sets of hundreds of items): same
