@@ -38,13 +38,9 @@ static const unsigned long long LC_EMPTY = 0xFFFFFFFF00000000ull;
 __device__ __forceinline__ uint32_t g_load(const uint32_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ void g_store_release(uint32_t *p, uint32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ bool t_final(uint32_t t) { return t != AT_NONE && t != AT_BUSY; }
-// A table entry changes NONE -> BUSY -> final value and never again, so a cached copy is either right or "not there
-// yet": look-ups first read through the caches and ask device memory only when the cached answer is not final.
-__device__ __forceinline__ uint32_t t_load(const uint32_t *p) {
-    uint32_t t = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-    if (!t_final(t)) t = g_load(p);
-    return t;
-}
+// A table entry changes NONE -> BUSY -> final value and never again, so a copy read through the caches is either
+// right or "not there yet": look-ups read through the caches first and ask device memory (an atomic load, or the
+// compare-and-swap that claims the entry) only when the cached answer is not final.
 
 struct Staging { uint32_t *ctl; uint8_t *smem; const uint8_t *blob; uint32_t n16; uint8_t *rep; const uint8_t *rep_src; uint32_t ncls; bool wide_sets; };   // what ensure_tables needs; wide_sets: the rows' charts hold sets of many items
 // The grammar tables are needed only by a wavefront that computes a transition, which is rare once the automaton has
@@ -185,25 +181,23 @@ __device__ __forceinline__ uint32_t store_transition(const TV &T, const StoreVie
 __device__ __forceinline__ uint32_t store_lookup_uniform(const TV &T, const StoreView &G, const Scratch &sc, const Staging &stg, uint32_t *errors,
                                                          uint32_t *steps, uint32_t s, uint32_t cl, uint32_t lane) {
     uint32_t *entry = G.trans + (size_t)s * T.ncls + cl;
-    for (uint32_t spins = 0; spins < (uint32_t)AUT_SPIN_LIMIT; spins++) {
-        uint32_t t = (uint32_t)__builtin_amdgcn_readfirstlane((int)t_load(entry));
-        if (t == AT_NONE) {
-            uint32_t old = 0;
-            if (lane == 0) old = atomicCAS(entry, (uint32_t)AT_NONE, (uint32_t)AT_BUSY);
-            old = (uint32_t)__builtin_amdgcn_readfirstlane((int)old);
-            if (old == AT_NONE) {
-                const uint32_t r = store_transition(T, G, sc, stg, errors, s, cl, lane);
-                ++*steps;
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-                if (lane == 0) g_store_release(entry, r);
-                return r;
-            }
-            t = old;
-        }
-        if (t_final(t)) return t;
-        __builtin_amdgcn_s_sleep(8);
+    // the read through the caches answers at once when the entry is final; else the claim itself (a compare-and-swap,
+    // which returns what device memory holds) is the fresh read
+    uint32_t t = (uint32_t)__builtin_amdgcn_readfirstlane((int)__hip_atomic_load(entry, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT));
+    if (t_final(t)) return t;
+    if (lane == 0) t = atomicCAS(entry, (uint32_t)AT_NONE, (uint32_t)AT_BUSY);
+    t = (uint32_t)__builtin_amdgcn_readfirstlane((int)t);
+    if (t == AT_NONE) {
+        const uint32_t r = store_transition(T, G, sc, stg, errors, s, cl, lane);
+        ++*steps;
+        if (lane == 0) g_store_release(entry, r);            // everything the transition wrote, then the entry
+        return r;
     }
-    return AT_FAIL;
+    for (uint32_t spins = 0; !t_final(t) && spins < (uint32_t)AUT_SPIN_LIMIT; spins++) {   // the owner is a running wavefront that waits for nothing
+        __builtin_amdgcn_s_sleep(8);
+        t = (uint32_t)__builtin_amdgcn_readfirstlane((int)g_load(entry));
+    }
+    return t_final(t) ? t : (uint32_t)AT_FAIL;
 }
 
 __host__ __device__ inline uint32_t store_round16(uint32_t x) { return (x + 15u) & ~15u; }
@@ -358,7 +352,7 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a) {
             if (live) { soff = D.str_off[rank]; len = D.str_off[rank + 1] - soff; c16 = D.str16[rank]; }
             live = live && len > 0;
             uint32_t s = root, pos = 0, cc = 0, spins = 0, t = AT_BUSY;
-            bool ok = false, fail = false;
+            bool ok = false, fail = false, again = false;
             for (;;) {
                 while (live) {                               // every lane follows its own string as far as the table goes
                     if (pos < 16u) {
@@ -371,16 +365,20 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a) {
                     const unsigned long long e = __hip_atomic_load(&lc[lslot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     if ((uint32_t)(e >> 32) == key) t = (uint32_t)e;
                     else {
-                        t = t_load(&G.trans[key]);
+                        // through the caches first; an entry seen unfinished is asked of device memory only on the
+                        // way back from the claim below, which is itself a fresh read of the entry it claims
+                        t = __hip_atomic_load(&G.trans[key], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                        if (!t_final(t) && again) t = g_load(&G.trans[key]);
                         if (t_final(t) && t != AT_FAIL) __hip_atomic_store(&lc[lslot], ((unsigned long long)key << 32) | t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     }
-                    if (t < AT_FAIL) { s = t; pos++; if (pos == len) { ok = true; live = false; } }
+                    if (t < AT_FAIL) { s = t; pos++; again = false; if (pos == len) { ok = true; live = false; } }
                     else if (t == AT_DEAD) live = false;
                     else if (t == AT_SINK) { ok = pos + 1 == len; live = false; }
                     else if (t == AT_FAIL) { fail = true; live = false; }
                     else break;                              // not there yet
                 }
                 if (!__ballot(live)) break;
+                again = true;
                 // one of the waiting lanes' transitions is claimed and computed here; the other lanes look again afterwards
                 const unsigned long long missing = __ballot(live && t == AT_NONE);
                 bool progress = false;
@@ -393,8 +391,7 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a) {
                     if (old == AT_NONE) {
                         const uint32_t r = store_transition(T, G, sc, stg, errors, rs, rc, lane);
                         steps++;
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-                        if (lane == 0) g_store_release(&G.trans[rs * ncls + rc], r);
+                        if (lane == 0) g_store_release(&G.trans[rs * ncls + rc], r);   // everything the transition wrote, then the entry
                         progress = true;
                     } else progress = old != AT_BUSY;        // somebody else has it, or has finished it meanwhile
                 }
