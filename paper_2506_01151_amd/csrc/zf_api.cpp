@@ -57,9 +57,11 @@ struct DeviceSide {
     void *d_root_items = nullptr; uint32_t n_root = 0;
     uint32_t *d_import_root = nullptr;               // [MAX_BATCH]
     uint32_t *h_row_out = nullptr;                   // pinned, [N_SLOTS][MAX_BATCH]: the state each row of a call ends up in
+    uint32_t *d_row_out = nullptr;                   // the same in device memory: the mask kernel writes here, the call's last block copies it out
     uint32_t store_epoch = 1;                        // bumped whenever the store is cleared
     uint32_t store_states = 0, store_items = 0;      // as of the last call that reported back
     bool store_dirty = true;                         // the store must be cleared before its next use
+    std::vector<uint32_t> ci_undecided_tok;          // [Q + N] tokens a row of the token-mask cache leaves to the parser (sizes a call's grid)
     uint32_t store_backoff = 0, store_backoff_next = 8;   // after a call the store had no room for: calls that take the per-block automaton instead
     struct CallRecord {                              // what to note in the states once the call in this slot has reported
         bool active = false;
@@ -116,6 +118,7 @@ void free_device(DeviceSide *d) {
     if (d->d_root_items) (void)hipFree(d->d_root_items);
     if (d->d_import_root) (void)hipFree(d->d_import_root);
     if (d->h_row_out) (void)hipHostFree(d->h_row_out);
+    if (d->d_row_out) (void)hipFree(d->d_row_out);
     for (auto &ev : d->ev) if (ev) (void)hipEventDestroy(ev);
     delete d;
 }
@@ -171,6 +174,48 @@ int setup_device(zf_engine *e) {
         }
         UP(str_off, tr.str_off, nullptr); UP(str_cls, str_cls, nullptr); UP(str16, str16, nullptr); UP(cls_rep, rep, nullptr);
     }
+    if (e->store_on) {
+        // The mask kernel over the persistent automaton works in token order: every token's string as byte classes, and the
+        // rows of the token-mask cache with one bit per token (bit v = the rank-ordered row's bit for token v's string).
+        const size_t V = (size_t)e->V, W = (size_t)e->W, n_rows = tr.Wr > 0 ? tr.ci_valid.size() / (size_t)tr.Wr : 0;
+        std::vector<Str16> tok16(std::max<size_t>(V, 1), Str16{{0, 0, 0, 0}});
+        std::vector<uint8_t> tok_len(std::max<size_t>(V, 1), 0);
+        for (size_t v = 0; v < V; v++) {
+            const uint32_t r = tr.rank_of[v];
+            if (r == 0xFFFFFFFFu) continue;
+            const uint32_t n = tr.str_off[r + 1] - tr.str_off[r];
+            uint8_t first[16] = {0};
+            for (uint32_t k = 0; k < std::min<uint32_t>(16, n); k++) first[k] = t.cls[tr.str_bytes[tr.str_off[r] + k]];
+            memcpy(&tok16[v], first, 16);
+            tok_len[v] = n <= 16 ? (uint8_t)n : (uint8_t)TOK_LEN_LONG;
+        }
+        std::vector<uint32_t> valid_tok(std::max<size_t>(n_rows * W, 1), 0), cd_tok(std::max<size_t>(n_rows * W, 1), 0);
+        d->ci_undecided_tok.assign(n_rows, 0);
+        auto rows_job = [&](size_t r0, size_t r1) {
+            for (size_t r = r0; r < r1; r++) {
+                const uint32_t *sv = &tr.ci_valid[r * tr.Wr], *sc = &tr.ci_cd[r * tr.Wr];
+                uint32_t *dv = &valid_tok[r * W], *dc = &cd_tok[r * W];
+                uint32_t und = 0;
+                for (size_t v = 0; v < V; v++) {
+                    const uint32_t k = tr.rank_of[v];
+                    if (k == 0xFFFFFFFFu) continue;
+                    const uint32_t bv = (sv[k >> 5] >> (k & 31)) & 1u, bc = (sc[k >> 5] >> (k & 31)) & 1u;
+                    dv[v >> 5] |= bv << (v & 31);
+                    dc[v >> 5] |= bc << (v & 31);
+                    und += bc & ~bv;
+                }
+                d->ci_undecided_tok[r] = und;
+            }
+        };
+        const size_t n_thr = std::min<size_t>(std::max<size_t>(1, std::min<unsigned>(8, std::thread::hardware_concurrency())), std::max<size_t>(n_rows, 1));
+        if (n_thr <= 1 || n_rows * V < (size_t)1 << 22) rows_job(0, n_rows);
+        else {
+            std::vector<std::thread> pool;
+            for (size_t k = 0; k < n_thr; k++) pool.emplace_back(rows_job, n_rows * k / n_thr, n_rows * (k + 1) / n_thr);
+            for (auto &th : pool) th.join();
+        }
+        UP(tok16, tok16, nullptr); UP(tok_len, tok_len, nullptr); UP(ci_valid_tok, valid_tok, nullptr); UP(ci_cd_tok, cd_tok, nullptr);
+    }
     T.Q = t.Q;
 #undef UP
     T.N = t.N; T.n_cls = t.n_cls; T.end_base = t.end_base; T.n_nodes = (int)tr.nodes.size(); T.n_chunks = (int)tr.chunk_begin.size();
@@ -208,6 +253,8 @@ int setup_device(zf_engine *e) {
         HIP_TRY(hipMalloc((void **)&G.ctl, 64));
         HIP_TRY(hipMalloc((void **)&d->d_import_root, (size_t)MAX_BATCH * 4));
         HIP_TRY(hipHostMalloc((void **)&d->h_row_out, (size_t)DeviceSide::N_SLOTS * MAX_BATCH * 4, hipHostMallocDefault));
+        HIP_TRY(hipMalloc((void **)&d->d_row_out, (size_t)DeviceSide::N_SLOTS * MAX_BATCH * 4));
+        HIP_TRY(hipMemset(d->d_row_out, 0, (size_t)DeviceSide::N_SLOTS * MAX_BATCH * 4));
         Chart c0;                                        // the empty prefix's set, completed items dropped, as device item words
         chart_init(t, c0);
         std::vector<uint32_t> root;
@@ -1029,6 +1076,8 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
     rec.active = true; rec.epoch = d->store_epoch;
     rec.st.assign(nb, std::shared_ptr<StateLink>()); rec.gen.assign(nb, 0); rec.upto.assign(nb, 0);
     uint32_t n_cache_rows = 0;
+    static thread_local StoreMiniRows mini;               // short records: they travel in the kernel's argument block
+    const bool use_mini = nb <= STORE_MINI_ROWS;
     {
         uint8_t *h = (uint8_t *)d->h_stage[slot];
         StoreRow *srow = (StoreRow *)(h + off_srow);
@@ -1069,17 +1118,22 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
                 st->pending.clear(); st->pending_base = st->fed_total;     // the chart holds everything fed so far
             }
             srow[r] = sr;
+            d->h_row_out[(size_t)slot * MAX_BATCH + r] = 0;        // "not reported": the kernel writes the state the row arrives at
+            if (use_mini) {
+                StoreRowMini &m = mini.r[r];
+                bool fits = sr.n_pending <= (uint32_t)STORE_MINI_PEND && sr.n_ent <= (uint32_t)STORE_MINI_ENT;
+                for (uint32_t k = 0; fits && k < sr.n_ent; k++) fits = sr.ent[k] < 65536u;
+                m.start = sr.start;
+                if (fits) {
+                    m.meta = sr.n_pending | sr.n_ent << 8 | sr.flags << 16;
+                    memcpy(m.pend, sr.pend, STORE_MINI_PEND);
+                    for (uint32_t k = 0; k < (uint32_t)STORE_MINI_ENT; k++) m.ent[k] = k < sr.n_ent ? (uint16_t)sr.ent[k] : (uint16_t)0;
+                } else m.meta = (sr.flags | STORE_ROW_SPILL) << 16;
+                m.spare = 0;
+            }
             dst[r] = sc ? row_slot[miss_rows[r]] : miss_rows[r];
             rec.st[r] = st->link; rec.gen[r] = st->generation; rec.upto[r] = st->fed_total;
         }
-    }
-    const size_t need_rank = (size_t)std::max(nb, 1) * d->tab.Wr;
-    if (need_rank > d->rank_cap) {
-        HIP_TRY(hipStreamSynchronize(stream));
-        if (d->d_rank_mask) (void)hipFree(d->d_rank_mask);
-        d->d_rank_mask = nullptr; d->rank_cap = 0;
-        HIP_TRY(hipMalloc((void **)&d->d_rank_mask, need_rank * 4 + 16));
-        d->rank_cap = need_rank;
     }
     MaskArgs a{};
     a.tab = d->tab;
@@ -1091,16 +1145,19 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
     a.store_pending = base + off_pend;
     a.store_import_root = d->d_import_root;
     a.store_row_out = d->h_row_out + (size_t)slot * MAX_BATCH;
+    a.store_row_dev = d->d_row_out + (size_t)slot * MAX_BATCH;
     a.rows = (const RowChart *)(base + off_rows);
     a.set_off = (const uint32_t *)(base + off_so);
     a.items = (const Item *)(base + off_items);
-    a.rank_mask = d->d_rank_mask;
+    a.rank_mask = nullptr;                                // this kernel writes token-order rows itself: no rank-ordered bitmap, no closing kernel
     a.out_mask = sc ? d->d_pool : d_mask;
     a.dst_row = direct ? nullptr : (const uint32_t *)(base + off_dst);
     a.row_slot = (const uint32_t *)(base + off_rowslot);
     a.user_mask = d_mask;
     a.user_batch = batch;
-    a.handoff_in_permute = sc ? 0 : 1;
+    a.handoff_in_permute = 0;
+    a.handoff_in_store = sc ? 0 : 1;                      // with the state cache on, the gather is the call's last kernel
+    a.store_mini = use_mini ? 1 : 0;
     a.counters = d->d_counters + COUNTER_SET_WORDS * d->call_parity;
     a.counters_next = d->d_counters + COUNTER_SET_WORDS * (d->call_parity ^ 1u);
     d->call_parity ^= 1u;
@@ -1113,39 +1170,48 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
     a.aut_wide = biggest_set > (size_t)AUT_NARROW_SET_MAX ? 1 : 0;   // a hint: which variant of the byte step to try first on larger sets
     {   // LDS of a block: the staged tables, the cache of table entries, and per wavefront the set under construction
         int scratch = e->lane_cap_auto ? (int)std::min<size_t>(LANE_CAP_MAX, (4 * widest + 128 + 31) / 32 * 32) : e->opt.lane_item_cap;
-        while (scratch > 32 && store_lds_bytes(d->tab, d->mode, scratch) > 160u * 1024u) scratch -= 32;
-        if (store_lds_bytes(d->tab, d->mode, scratch) > 160u * 1024u) return fail(ZF_ERR_INVALID_ARG, "the grammar tables leave no LDS for the mask kernel");
+        while (scratch > 32 && store_lds_bytes(d->tab, d->mode, scratch) > (uint32_t)STORE_LDS_MAX) scratch -= 32;
+        if (store_lds_bytes(d->tab, d->mode, scratch) > (uint32_t)STORE_LDS_MAX) return fail(ZF_ERR_INVALID_ARG, "the grammar tables leave no LDS for the mask kernel");
         a.aut_scratch = scratch;
-        // Blocks per row.  A wavefront takes groups of 4 words of the row's bitmap, four groups per pass, and the undecided
-        // strings among them 64 at a time; rows differ by orders of magnitude in how many strings their token-mask cache
-        // rows leave undecided, which the compiler counted per cache row.  A row gets blocks in proportion to passes +
-        // 2 x batches, at least one, at most one wavefront per group; all rows together about what the chip holds at once.
-        const int n_groups = (d->tab.Wr + AUT_GROUP_WORDS - 1) / AUT_GROUP_WORDS;
-        const int max_parts = std::max(1, (n_groups + STORE_WAVES - 1) / STORE_WAVES);
+        // Blocks per row.  A wavefront takes the row's mask words in segments (16 words = 512 tokens, fewer for rows most of
+        // whose tokens are undecided, so that a segment holds about one batch) and the undecided tokens among them 64 at a
+        // time; rows differ by orders of magnitude in how many tokens their token-mask cache rows leave undecided, which
+        // set-up counted per cache row.  A row gets blocks in proportion to segments / 4 + batches (a batch costs about four
+        // times what an empty segment does), at least one, at most one wavefront per segment; all rows together about what
+        // the chip holds at once.
         const int budget = std::max(nb, STORE_BLOCKS_PER_CU * std::max(1, d->cus));
-        if (nb > STORE_GRID_ROWS) {
-            a.store_uniform_parts = std::max(1, std::min((n_groups + 4 * STORE_WAVES - 1) / (4 * STORE_WAVES), budget / nb));
+        if (!use_mini) {
+            const int n_seg = (d->tab.W + STORE_SEG_WORDS - 1) / STORE_SEG_WORDS;
+            a.store_uniform_parts = std::max(1, std::min(std::max(1, (n_seg + STORE_WAVES - 1) / STORE_WAVES), budget / nb));
         } else {
-            double weight[STORE_GRID_ROWS], sum = 0;
+            double weight[STORE_MINI_ROWS], sum = 0;
+            int segs[STORE_MINI_ROWS];
             for (int r = 0; r < nb; r++) {
                 const Chart &c = states[miss_rows[r]]->chart;
                 uint32_t ent[64];
-                double und = d->tab.n_strings;
+                double und = d->tab.V;
                 if (use_cache && c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1] <= 64) {
                     const uint32_t n = current_set_entries(e->tab, c, ent);
                     und = 0;
-                    for (uint32_t k = 0; k < n; k++) und += e->trie.ci_undecided[ent[k]];
-                    und = std::min<double>(und, d->tab.n_strings);
+                    for (uint32_t k = 0; k < n; k++) und += d->ci_undecided_tok[ent[k]];
+                    und = std::min<double>(und, d->tab.V);
                 }
-                weight[r] = n_groups / 4.0 + und / 32.0;
+                uint32_t seg_log2 = 4;                            // words per segment: 16, or 8, 4, 2 when 512 tokens would hold more than a batch
+                while (seg_log2 > 1 && und * (32u << seg_log2) > 64.0 * std::max(1, d->tab.V)) seg_log2--;
+                segs[r] = (d->tab.W + (1 << seg_log2) - 1) >> seg_log2;
+                mini.r[r].meta |= seg_log2 << 24;
+                // a segment that holds any undecided token costs at least one batch
+                weight[r] = segs[r] / 4.0 + std::max(std::min<double>(und, segs[r]), und / 64.0);
                 sum += weight[r];
             }
             uint32_t at = 0;
             for (int r = 0; r < nb; r++) {
+                const int max_parts = std::max(1, (segs[r] + STORE_WAVES - 1) / STORE_WAVES);
                 a.store_first_block[r] = (uint16_t)at;
                 at += (uint32_t)std::min<double>(max_parts, std::max(1.0, budget * weight[r] / sum));
             }
-            a.store_first_block[nb] = (uint16_t)at;
+            for (int r = nb; r < STORE_MINI_ROWS + 8; r++) a.store_first_block[r] = r == nb ? (uint16_t)at : (uint16_t)0xFFFF;   // the kernel compares against all of them
+            a.store_uniform_parts = 0;
         }
     }
     const bool prof = d->profiling;
@@ -1157,9 +1223,8 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
     if (n_imp) HIP_TRY(launch_store_import(a, (const uint32_t *)(base + off_imp), (uint32_t)n_imp, stream));
     const bool run_kernels = nb > 0;
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
-    if (run_kernels && d->tab.n_chunks > 0) HIP_TRY(launch_mask_store(a, stream));
+    if (run_kernels) HIP_TRY(launch_mask_store(a, mini, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));
-    if (run_kernels) HIP_TRY(launch_finish(a, d->cus, stream));
     if (sc) HIP_TRY(launch_gather(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[3], stream));
     HIP_TRY(hipEventRecord(d->stage_done[slot], stream));

@@ -50,6 +50,7 @@ struct TrieNode {
 struct alignas(16) Str16 { uint32_t w[4]; };       // 16 one-byte symbols, first symbol in the low byte of w[0]
 
 static const int MAX_TOKEN_LEN_ON_DEVICE = 255;   // deeper nodes never occur: depth is a uint8
+static const int TOK_LEN_LONG = 255;               // DeviceTables::tok_len of a token longer than the 16 classes tok16 holds
 static const int CHUNK_ANC = 16;                  // ancestors stored per chunk (longer paths use parent links)
 
 // Immutable per-engine tables in device memory.  Every array is padded to a multiple of 16 bytes
@@ -82,6 +83,12 @@ struct DeviceTables {
     // state q (row q) and per nonterminal Y (row Q + Y), in string-rank order:
     const uint32_t *ci_valid;   // strings a terminal entered in state q swallows whole
     const uint32_t *ci_cd;      // strings on which that terminal dies after passing an accepting state
+    // The same per TOKEN, for the mask kernel over the persistent automaton, which works in token order and writes the
+    // caller's mask rows itself (null unless the engine runs that kernel):
+    const Str16 *tok16;         // [V] the first 16 byte classes of token v's string (zero padded)
+    const uint8_t *tok_len;     // [V] length of token v's string; 0 = the empty token (never allowed), TOK_LEN_LONG = more than 16 bytes (see rank_of / str_off)
+    const uint32_t *ci_valid_tok; // [Q + N][W] the rows of ci_valid with bit v = the verdict on token v's string
+    const uint32_t *ci_cd_tok;    // [Q + N][W] likewise for ci_cd
     int32_t Q;
     int32_t N, n_cls, end_base, n_nodes, n_chunks, n_strings, V, W;
     int32_t chunk_ranks;        // strings per chunk: 8, 16 or 32

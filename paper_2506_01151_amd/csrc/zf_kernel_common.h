@@ -118,27 +118,45 @@ __device__ __forceinline__ BaseG global_base(const MaskArgs &a, uint32_t row) {
 // then groups); even so they cost the kernel 5 us at 2,004 blocks (a ticket is a round trip to memory), which is why the
 // common case does without.  (An error count is a device-scope atomic followed by the counting wavefront's own release
 // fence; a fence in every block would write the L2 back each time: 6 -> 34 us.)
-__device__ __forceinline__ void hand_over(const MaskArgs &a, uint32_t lin, uint32_t n_blocks, bool ticketed) {
+__device__ __forceinline__ void hand_over(const MaskArgs &a, uint32_t lin, uint32_t n_blocks, bool ticketed, uint32_t block_sum = 0, bool count_only = false) {
     __shared__ uint32_t last;
+    unsigned long long *tickets = reinterpret_cast<unsigned long long *>(a.counters + TICKET_AT);
+    const uint32_t n_groups = n_blocks < (uint32_t)TICKET_GROUPS ? n_blocks : (uint32_t)TICKET_GROUPS;
+    if (count_only) {                                        // not the call's last kernel: leave the block's share of counter [1] only
+        if (threadIdx.x == 0 && block_sum) atomicAdd(&tickets[lin % n_groups], (unsigned long long)block_sum << 32);
+        return;
+    }
     if (!ticketed) { if (lin != n_blocks - 1) return; }
     __syncthreads();
     if (ticketed) {
         if (threadIdx.x == 0) {
-            const uint32_t n_groups = n_blocks < (uint32_t)TICKET_GROUPS ? n_blocks : (uint32_t)TICKET_GROUPS;
             const uint32_t g = lin % n_groups, size = n_blocks / n_groups + (g < n_blocks % n_groups ? 1u : 0u);
             uint32_t is_last = 0;
-            if (atomicAdd(&a.counters[TICKET_AT + g], 1u) == size - 1) is_last = atomicAdd(&a.counters[TICKET_TOP], 1u) == n_groups - 1 ? 1u : 0u;
+            if ((uint32_t)atomicAdd(&tickets[g], ((unsigned long long)block_sum << 32) | 1ull) == size - 1) is_last = atomicAdd(&a.counters[TICKET_TOP], 1u) == n_groups - 1 ? 1u : 0u;
             last = is_last;
         }
         __syncthreads();
         if (!last) return;
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
-    for (uint32_t k = threadIdx.x; k < (uint32_t)COUNTER_SET_WORDS; k += blockDim.x) a.counters_next[k] = 0;   // the next call's set (no separate memset)
-    if (threadIdx.x == 0) {                                  // counters first, then the word the host waits for
-        for (int i = 0; i < 4; i++) a.host_status[i] = __hip_atomic_load(&a.counters[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (a.store.ctl) for (int i = 0; i < 3; i++) a.host_status[5 + i] = __hip_atomic_load(&a.store.ctl[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&a.host_status[4], a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    uint32_t part = 0, x = 0;
+    const uint32_t k = threadIdx.x;
+    if (k < 64) {                                            // the counters, one per lane (their loads travel together), and the partial sums of counter [1]
+        part = (uint32_t)(__hip_atomic_load(&tickets[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) part += __shfl_xor(part, d);
+        if (k < 4) x = __hip_atomic_load(&a.counters[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else if (k >= 5 && k < 8 && a.store.ctl) x = __hip_atomic_load(&a.store.ctl[k - 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (k == 1) x += part;
+    }
+    __syncthreads();                                         // the ticket words have been read: now the next call's set is cleared (it may be this very set's neighbour only, never this set)
+    for (uint32_t i = threadIdx.x; i < (uint32_t)COUNTER_SET_WORDS; i += blockDim.x) a.counters_next[i] = 0;   // the next call's set (no separate memset)
+    if (a.store_row_dev)                                     // persistent automaton: where every row of the call stands now
+        for (uint32_t i = threadIdx.x; i < (uint32_t)a.batch; i += blockDim.x) a.store_row_out[i] = __hip_atomic_load(&a.store_row_dev[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();                                         // ... before the first wavefront's release below
+    if (k < 64) {                                            // counters first, then the word the host waits for
+        if (k < 4 || (k >= 5 && k < 8 && a.store.ctl)) a.host_status[k] = x;
+        if (k == 0) __hip_atomic_store(&a.host_status[4], a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);   // a release of the wavefront's stores
     }
 }
 

@@ -50,12 +50,14 @@ static const size_t NOALLOC_STAGE_BYTES = 256u << 10;  // pinned staging room pe
 static const int STORE_WAVES = ZF_STORE_WAVES;  // wavefronts per block of the mask kernel over the persistent automaton
 static const int STORE_BLOCK = STORE_WAVES * 64;
 static const int STORE_SUB_WORDS = ZF_STORE_SUB_WORDS;   // words of the rank-ordered bitmap a block merges and checks per pass (at most 128: one wavefront lists the word pairs)
+static const int STORE_LDS_MAX = 159 * 1024;   // dynamic LDS a block of that kernel may ask for (the hand-over of the call's status has a static word of its own)
+static const int STORE_SEG_WORDS = 16;         // mask words (of 32 tokens) a wavefront merges and checks per pass
+static const int STORE_WARM_ROWS = 32;         // rows of the transition table (states one byte from a row's current state) a block reads ahead into its LDS cache
 static const int STORE_LC_BITS = ZF_STORE_LC_BITS;       // log2 of the entries of a block's LDS cache of table entries (8 bytes each)
 #ifndef ZF_STORE_BLOCKS_PER_CU
 #define ZF_STORE_BLOCKS_PER_CU 3
 #endif
 static const int STORE_BLOCKS_PER_CU = ZF_STORE_BLOCKS_PER_CU;   // blocks per compute unit the grid aims at (the chip should hold them all at once)
-static const int STORE_GRID_ROWS = 64;          // batches up to this size get a block count per row
 static const int STORE_PENDING_LDS = 256;       // pending bytes of a row a block keeps in LDS (more are read from the upload)
 static const int STORE_PENDING_MAX = 4096;      // beyond this many bytes since its state was last known a row comes in through its chart again
 static const uint32_t STORE_ROW_CACHE = 1u;     // StoreRow::flags: the token-mask cache rows of the row are listed
@@ -80,11 +82,29 @@ struct StoreRow {               // one row of a call: 128 bytes, read by a wavef
     uint8_t pend[STORE_ROW_PEND];
 };
 static_assert(sizeof(StoreRow) == 128, "a wavefront reads a row's record as 32 words");
+// The same record in 48 bytes, for calls of up to STORE_MINI_ROWS rows: it travels in the kernel's argument block, which the
+// wavefronts read without a trip to the host's memory.  A row whose record does not fit (more pending bytes, more or larger
+// cache row numbers) says so in its flags and is read from store_rows.
+static const int STORE_MINI_ROWS = 64, STORE_MINI_PEND = 16, STORE_MINI_ENT = 10;
+static const uint32_t STORE_ROW_SPILL = 4u;     // flags of a short record: the row's full record is in MaskArgs::store_rows
+struct StoreRowMini {
+    uint32_t start;                               // as StoreRow::start
+    uint32_t meta;                                // n_pending | n_ent << 8 | flags << 16 | log2(mask words per pass) << 24
+    uint8_t pend[STORE_MINI_PEND];
+    uint16_t ent[STORE_MINI_ENT];
+    uint32_t spare;
+};
+static_assert(sizeof(StoreRowMini) == 48, "short row records are twelve words");
+struct StoreMiniRows { StoreRowMini r[STORE_MINI_ROWS]; };
 
 // A set of per-call counters: words 0-7 as listed at MaskArgs::counters, then the tickets the blocks of a call's last kernel
 // draw when they are done (one word per group of blocks, so that thousands of blocks do not queue up at one address, and a
 // top word the last block of each group draws from).
-static const int COUNTER_SET_WORDS = 96, TICKET_GROUPS = 64, TICKET_AT = 16, TICKET_TOP = 80;
+// A ticket word is 64 bits: tickets drawn in the low half, and in the high half a partial sum of counter [1] (undecided tokens)
+// that the mask kernel over the persistent automaton adds with the same operation, once per block.  (Thousands of additions to
+// one word, or to one cache line, queue up at the memory channel that holds it and hold up every other request to that channel:
+// 30 us per launch when every wavefront added its count to counters[1].)  The block that hands the status over adds them up.
+static const int COUNTER_SET_WORDS = 160, TICKET_GROUPS = 64, TICKET_AT = 16, TICKET_TOP = 144;
 
 struct MaskArgs {
     DeviceTables tab;
@@ -92,12 +112,13 @@ struct MaskArgs {
     const StoreRow *store_rows;        // [batch]
     const uint8_t *store_pending;
     uint32_t *store_import_root;       // [batch] device memory: written by the import kernel
-    uint32_t *store_row_out;           // [batch] pinned host memory: the state every row is in after this call's walk
-    // The grid of the store kernel is one-dimensional; a row's blocks are store_first_block[row] .. store_first_block[row + 1]
-    // (the host gives rows whose token-mask cache leaves more strings undecided more blocks), or, for batches beyond
-    // STORE_GRID_ROWS rows, store_uniform_parts blocks each.
-    uint16_t store_first_block[STORE_GRID_ROWS + 2];
-    int32_t store_uniform_parts;       // not 0: every row has this many blocks
+    uint32_t *store_row_out;           // [batch] pinned host memory: the state every row is in after this call's walk ...
+    uint32_t *store_row_dev;           // [batch] ... which the mask kernel notes here (device memory); the block that hands the call's status over copies it out
+    // The grid of the store kernel is one-dimensional.  In calls of up to STORE_MINI_ROWS rows the host gives rows whose
+    // token-mask cache leaves more tokens undecided more blocks: row r has blocks store_first_block[r] .. store_first_block[r + 1]
+    // (ascending; 0xFFFF beyond the call's rows) and store_uniform_parts is 0; larger calls give every row store_uniform_parts blocks.
+    alignas(16) uint16_t store_first_block[STORE_MINI_ROWS + 8];
+    int32_t store_uniform_parts;
     const RowChart *rows;      // [batch]
     const uint32_t *set_off;   // shared CSR offsets of all rows' sets
     const Item *items;         // shared item array of all rows
@@ -110,8 +131,10 @@ struct MaskArgs {
     uint32_t *user_mask;       // the caller's [user_batch][W] tensor (target of the gather)
     int32_t user_batch;
     int32_t handoff_in_permute; // 1: permute is the call's last kernel (state cache off), else the gather is
+    int32_t handoff_in_store;  // 1: the mask kernel over the persistent automaton is the call's last kernel (it writes the caller's rows itself)
+    int32_t store_mini;        // 1: the rows' records are in the kernel's StoreMiniRows argument
     uint32_t *counters;        // [0] chunks passed to the fallback, [1] length of the work queue, [2] chunks nobody could resolve,
-                               // [3] Earley byte steps, [4] fallback wavefronts that have finished, [16..80] tickets of the call's last kernel;
+                               // [3] Earley byte steps, [4] fallback wavefronts that have finished, [16..144] tickets of the call's last kernel;
                                // COUNTER_SET_WORDS words per set
     uint32_t *host_status;     // pinned host memory, 8 words: this call's counters [0..3], written by its last kernel, then [4] = seq
     uint32_t seq;              // the call's number (never 0): the last word the call's last kernel writes, which is what the host waits for
@@ -151,7 +174,7 @@ uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int ar
 hipError_t launch_mask_automaton(const MaskArgs &a, hipStream_t s);
 hipError_t prepare_store_kernels();
 uint32_t store_lds_bytes(const DeviceTables &t, int mode, int scratch);
-hipError_t launch_mask_store(const MaskArgs &a, hipStream_t s);
+hipError_t launch_mask_store(const MaskArgs &a, const StoreMiniRows &mini, hipStream_t s);
 hipError_t launch_store_clear(const StoreView &G, uint32_t ncls, const void *root_items, uint32_t n_root, hipStream_t s);
 hipError_t launch_store_import(const MaskArgs &a, const uint32_t *import_rows, uint32_t n_import, hipStream_t s);
 hipError_t launch_finish(const MaskArgs &a, int cus, hipStream_t s);   // fallback pass (when anything was listed) + permutation into token order

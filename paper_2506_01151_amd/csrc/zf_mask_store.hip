@@ -42,6 +42,14 @@ __device__ __forceinline__ bool t_final(uint32_t t) { return t != AT_NONE && t !
 // right or "not there yet": look-ups read through the caches first and ask device memory (an atomic load, or the
 // compare-and-swap that claims the entry) only when the cached answer is not final.
 
+// Hundreds of wavefronts of a row can wait for the same entry: they ask less and less often, so that their polls do not
+// slow the memory channel the owner works through (at most 64 x 64 cycles between two polls: 1.7 us).
+__device__ __forceinline__ void poll_pause(uint32_t spins) {
+    if (spins < 2) __builtin_amdgcn_s_sleep(8);
+    else if (spins < 6) __builtin_amdgcn_s_sleep(24);
+    else __builtin_amdgcn_s_sleep(64);
+}
+
 struct Staging { uint32_t *ctl; uint8_t *smem; const uint8_t *blob; uint32_t n16; uint8_t *rep; const uint8_t *rep_src; uint32_t ncls; bool wide_sets; };   // what ensure_tables needs; wide_sets: the rows' charts hold sets of many items
 // The grammar tables are needed only by a wavefront that computes a transition, which is rare once the automaton has
 // grown: the first such wavefront of a block copies them into LDS (ctl[4]: 0 = not there, 1 = being copied, 2 = there).
@@ -194,50 +202,75 @@ __device__ __forceinline__ uint32_t store_lookup_uniform(const TV &T, const Stor
         return r;
     }
     for (uint32_t spins = 0; !t_final(t) && spins < (uint32_t)AUT_SPIN_LIMIT; spins++) {   // the owner is a running wavefront that waits for nothing
-        __builtin_amdgcn_s_sleep(8);
+        poll_pause(spins);
         t = (uint32_t)__builtin_amdgcn_readfirstlane((int)g_load(entry));
     }
     return t_final(t) ? t : (uint32_t)AT_FAIL;
 }
 
-__host__ __device__ inline uint32_t store_round16(uint32_t x) { return (x + 15u) & ~15u; }
-
-// Grid (parts, rows), blocks of STORE_WAVES wavefronts.  The wavefronts of a block work on their own; what they share
-// is the block's LDS cache of table entries and (once somebody needs them) the staged grammar tables.  A wavefront
-//  (a) reads its row's record -- start state, pending bytes, token-mask-cache row numbers: one 128-byte load --
-//  (b) requests the token-mask cache words (Section 4.3) of its share of the rank-ordered bitmap, 16 words at a time,
-//      and while they are on their way walks the row's pending bytes (the tokens fed since the row's state was last
-//      known) from that state to the row's current state, then warms the LDS cache with the current state's table row,
-//  (c) takes the undecided strings of those words, 64 at a time, one lane per string, through
-//      the transition table: first the LDS cache, then device memory, and an Earley byte step for what nobody has
-//      computed yet; (d) stores its 16 verdict words.  No block-wide barrier after the first one.
+// Grid (blocks of all rows), blocks of STORE_WAVES wavefronts.  The kernel works in TOKEN order and writes the caller's mask
+// rows itself: nothing has to be permuted afterwards.  The wavefronts of a block work on their own; what they share is
+// the block's LDS cache of table entries and (once somebody needs them) the staged grammar tables.  A wavefront
+//  (a) takes its row's record -- start state, pending bytes, token-mask-cache row numbers -- from the kernel's argument
+//      block (calls of up to STORE_MINI_ROWS rows), else from the call's upload with one 128-byte load;
+//  (b) requests the token-mask cache words (Section 4.3) of its segment of STORE_SEG_WORDS mask words, and while they are
+//      on their way walks the row's pending bytes (the tokens fed since the row's state was last known) from that state to
+//      the row's current state, then warms the LDS cache with the current state's table row;
+//  (c) takes the undecided tokens of the segment, 64 at a time, one lane per token, through the transition table: first the
+//      LDS cache, then device memory, and an Earley byte step for what nobody has computed yet;
+//  (d) stores the segment's words of the row's mask (the next segment's cache words are requested before (c)).
+// No block-wide barrier between the first one and the hand-over of the call's status at the end.
 template <int MODE>
-__global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a) {
+__global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, StoreMiniRows mini) {
     extern __shared__ __align__(16) uint8_t smem[];
+    __shared__ uint32_t block_undecided;                     // tokens the block's wavefronts walked through the table (for the report)
     const DeviceTables &D = a.tab;
     const StoreView &G = a.store;
     const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const uint32_t Wr = (uint32_t)D.Wr, n_strings = (uint32_t)D.n_strings, ncls = (uint32_t)D.n_cls;
-    const uint32_t n_groups = (Wr + AUT_GROUP_WORDS - 1) / AUT_GROUP_WORDS;
-    uint32_t row, part, parts;                               // which row this block belongs to, and which of the row's blocks it is
-    if (a.store_uniform_parts) { parts = (uint32_t)a.store_uniform_parts; row = blockIdx.x / parts; part = blockIdx.x % parts; }
-    else {
-        row = 0;
-        for (uint32_t r = 1; r < (uint32_t)a.batch; r++) row += blockIdx.x >= a.store_first_block[r] ? 1u : 0u;   // first_block is ascending
-        part = blockIdx.x - a.store_first_block[row];
-        parts = a.store_first_block[row + 1] - a.store_first_block[row];
-    }
+    const uint32_t W = (uint32_t)D.W, ncls = (uint32_t)D.n_cls;
+    if (tid == 0) block_undecided = 0;
+    // Grid (blocks of the row that has most, rows): the row's record -- with the number of blocks the row really has -- is
+    // the first thing read, from the kernel's argument block when the call has few enough rows (one read; a block beyond its
+    // row's count leaves at once).
+    const uint32_t use_mini = (uint32_t)a.store_mini, uniform_parts = (uint32_t)a.store_uniform_parts;
+    uint32_t n_before = 0;                                   // rows that start at or before this block (all 64 entries are compared: no loop that waits once per row)
+#pragma unroll
+    for (int r = 0; r < STORE_MINI_ROWS; r++) n_before += blockIdx.x >= a.store_first_block[r] ? 1u : 0u;
+    const uint32_t row = uniform_parts ? blockIdx.x / (uniform_parts ? uniform_parts : 1u) : n_before - 1u;
+    const uint32_t frow = row < (uint32_t)STORE_MINI_ROWS ? row : 0u;
+    const StoreRowMini m = mini.r[frow];
+    const uint32_t fb0 = a.store_first_block[frow], fb1 = a.store_first_block[frow + 1];
+    const uint32_t part = uniform_parts ? blockIdx.x - row * uniform_parts : blockIdx.x - fb0;
+    const uint32_t parts = uniform_parts ? uniform_parts : fb1 - fb0;
+    // mask words a wavefront takes per pass: the host picks fewer for rows most of whose tokens are undecided, so that a pass
+    // holds about one batch of 64 tokens and the row can be dealt to more wavefronts
+    const uint32_t sw = use_mini ? 1u << ((m.meta >> 24) & 7u) : (uint32_t)STORE_SEG_WORDS;
+    const uint32_t n_seg = (W + sw - 1) / sw;
     const uint32_t unit = part * STORE_WAVES + wave, n_units = parts * STORE_WAVES;   // a unit = one wavefront of one of the row's blocks
-    if (part * STORE_WAVES >= n_groups) return;              // uniform over the block: not even its first wavefront has a group
-    // the row's record: lane k holds word k
-    const uint32_t rec = lane < sizeof(StoreRow) / 4 ? reinterpret_cast<const uint32_t *>(a.store_rows + row)[lane] : 0u;
+    uint32_t steps = 0;
+    if (part < parts && (part * STORE_WAVES < n_seg || part == 0)) {   // uniform over the block (the row's first block reports the row's state even when there is no mask word)
+    // the row's record in the layout of StoreRow: lane k holds word k
+    uint32_t rec = 0;
+    const bool spilled = !use_mini || ((m.meta >> 16) & STORE_ROW_SPILL) != 0;
+    {
+        const uint32_t *mw = reinterpret_cast<const uint32_t *>(&m);
+        rec = lane == 0u ? m.start : rec;
+        rec = lane == 1u ? (m.meta & 0xFFu) : rec;
+        rec = lane == 3u ? ((m.meta >> 8) & 0xFFu) : rec;
+        rec = lane == 5u ? (m.meta >> 16) : rec;
+#pragma unroll
+        for (int k = 0; k < STORE_MINI_ENT; k++) rec = lane == (uint32_t)(STORE_ROW_ENT_AT + k) ? ((mw[6 + k / 2] >> (16 * (k & 1))) & 0xFFFFu) : rec;
+#pragma unroll
+        for (int k = 0; k < STORE_MINI_PEND / 4; k++) rec = lane == (uint32_t)(STORE_ROW_PEND_AT + k) ? mw[2 + k] : rec;
+    }
+    if (spilled) rec = lane < sizeof(StoreRow) / 4 ? reinterpret_cast<const uint32_t *>(a.store_rows + row)[lane] : 0u;
     TV T;
     uint32_t off = table_view<MODE>(D, smem, T);
     const uint32_t n16 = off / 16;
     uint8_t *l_rep = smem + off; off += 256;
     unsigned long long *lc = reinterpret_cast<unsigned long long *>(smem + off); off += LC_ENTRIES * 8;
     uint32_t *ctl = reinterpret_cast<uint32_t *>(smem + off); off += 32;   // [4] state of the staged tables
-    uint32_t *vbuf = reinterpret_cast<uint32_t *>(smem + off) + wave * 16; off += STORE_WAVES * 64;   // per wavefront: verdicts of the pass's 16 words
+    uint32_t *vbuf = reinterpret_cast<uint32_t *>(smem + off) + wave * STORE_SEG_WORDS; off += STORE_WAVES * STORE_SEG_WORDS * 4;   // per wavefront: verdicts of the pass's words
     const Staging stg{ctl, smem, D.table_blob, n16, l_rep, D.cls_rep, ncls, a.aut_wide != 0};
     Scratch sc;
     sc.cap = (uint32_t)a.aut_scratch;
@@ -247,13 +280,13 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a) {
     for (uint32_t k = tid; k < LC_ENTRIES; k += STORE_BLOCK) lc[k] = LC_EMPTY;
     if (tid == 0) ctl[4] = 0;
     __syncthreads();
-    if (unit >= n_groups) return;
+    if (unit < n_seg || unit == 0) {
     auto field = [&](uint32_t k) { return (uint32_t)__builtin_amdgcn_readlane((int)rec, (int)k); };
     const uint32_t flags = field(5), n_pending = field(1), pend_off = field(2), n_ent = field(3), ent_off = field(4);
     uint32_t start = field(0);
     if (flags & STORE_ROW_IMPORTED) start = a.store_import_root[row];
     const bool use_cache = (flags & STORE_ROW_CACHE) != 0;
-    const bool ent_inline = n_ent <= (uint32_t)STORE_ROW_ENT, pend_inline = n_pending <= (uint32_t)STORE_ROW_PEND;
+    const bool ent_inline = n_ent <= (uint32_t)STORE_ROW_ENT, pend_inline = n_pending <= (uint32_t)(spilled ? STORE_ROW_PEND : STORE_MINI_PEND);
     auto entry = [&](uint32_t k) -> uint32_t {               // k differs from lane to lane: a shuffle, not a broadcast
         const uint32_t inl = (uint32_t)__shfl((int)rec, (int)(STORE_ROW_ENT_AT + (k < (uint32_t)STORE_ROW_ENT ? k : 0u)));
         return ent_inline ? inl : a.entries[ent_off + k];
@@ -261,81 +294,109 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a) {
     auto pending = [&](uint32_t k) -> uint32_t {
         return pend_inline ? (field(STORE_ROW_PEND_AT + (k >> 2)) >> ((k & 3u) * 8u)) & 0xFFu : (uint32_t)a.store_pending[pend_off + k];
     };
-    uint32_t steps = 0, root = AT_FAIL;
+    uint32_t root = AT_FAIL, undecided = 0;
     uint32_t *errors = &a.counters[2];
-    const uint32_t slot16 = lane & 15u, grp = lane >> 4;    // lane = (word slot, one of four groups of cache rows)
-    for (uint32_t j0 = 0; unit + j0 * n_units < n_groups; j0 += 4) {
-        // the 16 words of this pass: four groups of AUT_GROUP_WORDS neighbouring words, dealt round robin over the units
-        auto word_of = [&](uint32_t t) -> uint32_t {
-            const uint32_t g = unit + (j0 + t / AUT_GROUP_WORDS) * n_units;
-            return g < n_groups ? g * AUT_GROUP_WORDS + t % AUT_GROUP_WORDS : 0xFFFFFF00u;
-        };
-        const uint32_t w = word_of(slot16);
-        uint32_t v = 0, c = use_cache ? 0u : 0xFFFFFFFFu;
-        // the first look-up of the pending walk is requested ahead of the cache words: loads come back in the order they were issued
-        uint32_t hop0 = AT_NONE;
-        const bool start_ok = start != 0 && start < G.cap_states;
-        if (j0 == 0 && n_pending && start_ok && pending(0) < ncls) hop0 = __hip_atomic_load(&G.trans[start * ncls + pending(0)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-        if (use_cache)
-            for (uint32_t k0 = 0; k0 < n_ent; k0 += 4) {         // uniform trip count: the row numbers come by shuffle
+    uint32_t *out_row = a.out_mask + (size_t)(a.dst_row ? a.dst_row[row] : row) * W;
+    const uint32_t slot16 = lane & 15u, grp = lane >> 4;    // lane = (word of the segment, one of four groups of cache rows)
+    static_assert(STORE_SEG_WORDS == 16, "a segment is at most one word per lane of a quarter wavefront");
+    // the token-mask cache words of segment g: every quarter of the wavefront ORs a quarter of the row's cache rows
+    auto request = [&](uint32_t g, uint32_t &v, uint32_t &c) {
+        const uint32_t w = slot16 < sw ? g * sw + slot16 : 0xFFFFFFFFu;
+        v = 0; c = use_cache ? 0u : 0xFFFFFFFFu;
+        if (use_cache && g < n_seg)
+            for (uint32_t k0 = 0; k0 < n_ent; k0 += 4) {     // uniform trip count: the row numbers come by shuffle
                 const uint32_t k = k0 + grp;
                 const uint32_t er = entry(k < n_ent ? k : 0u);
-                if (k < n_ent && w < Wr) { const size_t r = (size_t)er * Wr + w; v |= D.ci_valid[r]; c |= D.ci_cd[r]; }
+                if (k < n_ent && w < W) { const size_t r = (size_t)er * W + w; v |= D.ci_valid_tok[r]; c |= D.ci_cd_tok[r]; }
             }
-        if (j0 == 0) {
-            // ---- the row's current state: walk the bytes fed since `start` was its state (the loads above are in flight) ----
-            uint32_t s = start;
-            bool bad = s == 0 || (s >= G.cap_states && s != AT_SINK);
-            for (uint32_t k = 0; k < n_pending && !bad; k++) {
-                const uint32_t cl = pending(k);
-                if (s == AT_SINK || cl >= ncls) { bad = true; break; }
-                uint32_t t = k == 0 ? (uint32_t)__builtin_amdgcn_readfirstlane((int)hop0) : (uint32_t)AT_NONE;
-                if (!t_final(t)) t = store_lookup_uniform(T, G, sc, stg, errors, &steps, s, cl, lane);
-                if (t == AT_DEAD || t == AT_FAIL) { bad = true; break; }   // the host accepted these bytes: a dead end here is an error
-                s = t;
-            }
-            if (bad) { s = AT_FAIL; if (lane == 0 && unit == 0) atomicAdd(errors, 1u); }
-            if (lane == 0 && unit == 0) a.store_row_out[row] = s;
-            root = s;
-            if (root < AT_FAIL) {                            // warm the block's cache with the current state's row of the table
+    };
+    // the first look-up of the pending walk is requested ahead of the cache words: loads come back in the order they were issued
+    uint32_t hop0 = AT_NONE;
+    const bool start_ok = start != 0 && start < G.cap_states;
+    if (n_pending && start_ok && pending(0) < ncls) hop0 = __hip_atomic_load(&G.trans[start * ncls + pending(0)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    uint32_t v = 0, c = 0;
+    request(unit, v, c);
+    {
+        // ---- the row's current state: walk the bytes fed since `start` was its state (the loads above are in flight) ----
+        uint32_t s = start;
+        bool bad = s == 0 || (s >= G.cap_states && s != AT_SINK);
+        for (uint32_t k = 0; k < n_pending && !bad; k++) {
+            const uint32_t cl = pending(k);
+            if (s == AT_SINK || cl >= ncls) { bad = true; break; }
+            uint32_t t = k == 0 ? (uint32_t)__builtin_amdgcn_readfirstlane((int)hop0) : (uint32_t)AT_NONE;
+            if (!t_final(t)) t = store_lookup_uniform(T, G, sc, stg, errors, &steps, s, cl, lane);
+            if (t == AT_DEAD || t == AT_FAIL) { bad = true; break; }   // the host accepted these bytes: a dead end here is an error
+            s = t;
+        }
+        if (bad) { s = AT_FAIL; if (lane == 0 && unit == 0) atomicAdd(errors, 1u); }
+        // The host reads this word once it has seen the call's status.  It is written through to device memory here (no fence:
+        // a release would write the whole L2 back, and every wavefront of the chip would wait behind that), long before this
+        // block draws its ticket; the block that hands the status over reads it back and passes it on.
+        if (unit == 0 && lane == 0) __hip_atomic_store(&a.store_row_dev[row], s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        root = s;
+        if (root < AT_FAIL) {
+            // Warm the block's cache with the current state's row of the table, and with the rows of the states one byte
+            // away (every wavefront of the block takes its share of them): a row is read by neighbouring lanes, once per
+            // block.  Left to the walk below, thousands of wavefronts would ask for the same few lines at the same
+            // moment, lane by lane, and queue up at the one memory channel that holds them (8 us and more).
+            auto warm_row = [&](uint32_t st) {
                 for (uint32_t c0 = 0; c0 < ncls; c0 += 64) {
                     const uint32_t cl = c0 + lane;
-                    if (cl < ncls) {
-                        const uint32_t key = root * ncls + cl, t = __hip_atomic_load(&G.trans[key], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-                        if (t_final(t) && t != AT_FAIL)
-                            __hip_atomic_store(&lc[(key * 0x9E3779B1u) >> (32 - LC_BITS)], ((unsigned long long)key << 32) | t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    uint32_t t = AT_NONE;
+                    const uint32_t key = st * ncls + cl;
+                    if (cl < ncls) t = __hip_atomic_load(&G.trans[key], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                    if (cl < ncls && t_final(t) && t != AT_FAIL)
+                        __hip_atomic_store(&lc[(key * 0x9E3779B1u) >> (32 - LC_BITS)], ((unsigned long long)key << 32) | t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    // the states this row leads to, each once: the wavefront's share of them is warmed in turn
+                    if (st == root) {
+                        unsigned long long todo = __ballot(cl < ncls && t < AT_FAIL && t != root);
+                        uint32_t n_done = 0;
+                        while (todo && n_done < (uint32_t)STORE_WARM_ROWS) {
+                            const int l = __ffsll((long long)todo) - 1;
+                            const uint32_t nx = (uint32_t)__builtin_amdgcn_readlane((int)t, l);
+                            todo &= ~__ballot(t == nx);
+                            if (n_done % STORE_WAVES == wave && ncls <= 64u) {
+                                const uint32_t k2 = nx * ncls + lane;
+                                uint32_t t2 = AT_NONE;
+                                if (lane < ncls) t2 = __hip_atomic_load(&G.trans[k2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                                if (lane < ncls && t_final(t2) && t2 != AT_FAIL)
+                                    __hip_atomic_store(&lc[(k2 * 0x9E3779B1u) >> (32 - LC_BITS)], ((unsigned long long)k2 << 32) | t2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                            }
+                            n_done++;
+                        }
                     }
                 }
-            }
+            };
+            warm_row(root);
         }
-        const bool root_ok = root < AT_FAIL;                 // AT_SINK: nothing can follow; AT_FAIL: the call fails
+    }
+    const bool root_ok = root < AT_FAIL;                     // AT_SINK: nothing can follow; AT_FAIL: the call fails
+    for (uint32_t g = unit; g < n_seg; g += n_units) {
+        const uint32_t w = slot16 < sw ? g * sw + slot16 : 0xFFFFFFFFu;
+        uint32_t vn = 0, cn = 0;
+        request(g + n_units, vn, cn);                        // the next segment's words travel while this one's tokens are checked
         v |= __shfl_xor(v, 16); v |= __shfl_xor(v, 32);
         c |= __shfl_xor(c, 16); c |= __shfl_xor(c, 32);
         uint32_t want = c & ~v;
         {
-            const uint32_t r0 = w * 32u;
-            if (w >= Wr || r0 >= n_strings || !root_ok) want = 0;
-            else if (n_strings - r0 < 32u) want &= (1u << (n_strings - r0)) - 1u;
-            if (!root_ok) v = 0;                             // no string can follow a finished sentence
+            const uint32_t t0 = w * 32u;
+            if (w >= W || t0 >= (uint32_t)D.V || !root_ok) want = 0;
+            else if ((uint32_t)D.V - t0 < 32u) want &= (1u << ((uint32_t)D.V - t0)) - 1u;
+            if (!root_ok) v = 0;                             // no token can follow a finished sentence
         }
-        {
-            uint32_t cnt = lane < 16u ? (uint32_t)__popc(want) : 0u;
-#pragma unroll
-            for (int d = 8; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d);
-            if (lane == 0 && cnt) atomicAdd(&a.counters[1], cnt);
-        }
-        // ---- one lane per undecided string through the table.  The undecided strings of the 16 words are numbered
+        // ---- one lane per undecided token through the table.  The undecided tokens of the 16 words are numbered
         // through (prefix sum of the words' bit counts) and taken 64 at a time, so that a batch is full whatever the
         // pattern of the bits; verdicts go back to their words through 16 words of LDS ----
         uint32_t incl = (uint32_t)__popc(want);              // every group of 16 lanes holds the same 16 words
 #pragma unroll
         for (int d = 1; d < 16; d <<= 1) { const uint32_t up = __shfl_up(incl, d, 16); if (slot16 >= (uint32_t)d) incl += up; }
         const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 15);
+        undecided += total;
         if (lane < 16u) lds_store(&vbuf[lane], 0u);
         for (uint32_t b0 = 0; b0 < total; b0 += 64) {
             const uint32_t i = b0 + lane;
             bool live = i < total;
-            uint32_t slot = 0;                               // the word that holds the lane's string: the first whose running count exceeds i
+            uint32_t slot = 0;                               // the word that holds the lane's token: the first whose running count exceeds i
 #pragma unroll
             for (int k = 0; k < 15; k++) slot += i >= (uint32_t)__builtin_amdgcn_readlane((int)incl, k) ? 1u : 0u;
             const uint32_t before = (uint32_t)__shfl((int)incl, (int)(slot ? slot - 1 : 0));
@@ -346,10 +407,14 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a) {
                 const uint32_t low = (uint32_t)__popc(bits & (((1u << sh) - 1u) << bit));
                 if (n >= low) { n -= low; bit += (uint32_t)sh; }
             }
-            const uint32_t rank = word_of(slot) * 32u + bit;
+            const uint32_t token = (g * sw + slot) * 32u + bit;
             uint32_t soff = 0, len = 0;
             Str16 c16{{0, 0, 0, 0}};
-            if (live) { soff = D.str_off[rank]; len = D.str_off[rank + 1] - soff; c16 = D.str16[rank]; }
+            if (live) { len = D.tok_len[token]; c16 = D.tok16[token]; }
+            if (live && len == (uint32_t)TOK_LEN_LONG) {     // longer than the 16 classes at hand: the rest is with the string's rank
+                const uint32_t rank = D.rank_of[token];
+                soff = D.str_off[rank]; len = D.str_off[rank + 1] - soff;
+            }
             live = live && len > 0;
             uint32_t s = root, pos = 0, cc = 0, spins = 0, t = AT_BUSY;
             bool ok = false, fail = false, again = false;
@@ -397,7 +462,7 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a) {
                 }
                 if (progress) spins = 0;
                 else {
-                    __builtin_amdgcn_s_sleep(8);
+                    poll_pause(spins);
                     if (++spins > (uint32_t)AUT_SPIN_LIMIT) { fail = fail || live; live = false; }   // bounded wait
                 }
             }
@@ -406,9 +471,16 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a) {
             if (lane == 0 && fm) atomicAdd(errors, (uint32_t)__popcll(fm));
         }
         if (total) v |= lds_load(&vbuf[slot16]);             // LDS serves one wavefront's accesses in issue order
-        if (lane < 16u && w < Wr) a.rank_mask[(size_t)row * Wr + w] = v;
+        if (lane < 16u && w < W) out_row[w] = v;
+        v = vn; c = cn;
     }
     if (lane == 0 && steps) atomicAdd(&a.counters[3], steps);
+    if (lane == 0 && undecided) atomicAdd(&block_undecided, undecided);   // LDS: the block's sum travels with its ticket
+    }
+    }
+    // the call's status goes to the host from the block that finishes last (a failed look-up counts up to the end)
+    __syncthreads();
+    hand_over(a, blockIdx.x, gridDim.x, true, block_undecided, !a.handoff_in_store);
 }
 
 // Clear the store: every transition unknown, every header unpublished, the hash table empty; then the
@@ -448,7 +520,7 @@ __global__ __launch_bounds__(256) void store_import_kernel(MaskArgs a, const uin
 }  // namespace
 
 hipError_t prepare_store_kernels() {
-    const int max_lds = 160 * 1024;
+    const int max_lds = STORE_LDS_MAX;
     hipError_t e;
 #define SET_ATTR(k) if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k), hipFuncAttributeMaxDynamicSharedMemorySize, max_lds)) != hipSuccess) return e
     SET_ATTR(mask_store_kernel<0>); SET_ATTR(mask_store_kernel<1>); SET_ATTR(mask_store_kernel<2>);
@@ -457,16 +529,16 @@ hipError_t prepare_store_kernels() {
 }
 
 uint32_t store_lds_bytes(const DeviceTables &t, int mode, int scratch) {
-    return table_bytes(t, mode) + 256 + LC_ENTRIES * 8 + 32 + STORE_WAVES * 64 +
+    return table_bytes(t, mode) + 256 + LC_ENTRIES * 8 + 32 + STORE_WAVES * STORE_SEG_WORDS * 4 +
            STORE_WAVES * ((uint32_t)scratch * 8 + aut_hash_places((uint32_t)scratch) * 4);
 }
 
-hipError_t launch_mask_store(const MaskArgs &a, hipStream_t s) {
+hipError_t launch_mask_store(const MaskArgs &a, const StoreMiniRows &mini, hipStream_t s) {
     const uint32_t lds = store_lds_bytes(a.tab, a.mode, a.aut_scratch);
     dim3 grid(a.store_uniform_parts ? (uint32_t)a.store_uniform_parts * (uint32_t)a.batch : (uint32_t)a.store_first_block[a.batch]);
-    if (a.mode == 0) hipLaunchKernelGGL(mask_store_kernel<0>, grid, dim3(STORE_BLOCK), lds, s, a);
-    else if (a.mode == 1) hipLaunchKernelGGL(mask_store_kernel<1>, grid, dim3(STORE_BLOCK), lds, s, a);
-    else hipLaunchKernelGGL(mask_store_kernel<2>, grid, dim3(STORE_BLOCK), lds, s, a);
+    if (a.mode == 0) hipLaunchKernelGGL(mask_store_kernel<0>, grid, dim3(STORE_BLOCK), lds, s, a, mini);
+    else if (a.mode == 1) hipLaunchKernelGGL(mask_store_kernel<1>, grid, dim3(STORE_BLOCK), lds, s, a, mini);
+    else hipLaunchKernelGGL(mask_store_kernel<2>, grid, dim3(STORE_BLOCK), lds, s, a, mini);
     return hipGetLastError();
 }
 
