@@ -61,7 +61,10 @@ struct DeviceSide {
     uint32_t store_epoch = 1;                        // bumped whenever the store is cleared
     uint32_t store_states = 0, store_items = 0;      // as of the last call that reported back
     bool store_dirty = true;                         // the store must be cleared before its next use
-    std::vector<uint32_t> ci_undecided_tok;          // [Q + N] tokens a row of the token-mask cache leaves to the parser (sizes a call's grid)
+    // What sizes a call's grid: the tokens a row's token-mask cache rows leave to the parser.  The host keeps the token-order
+    // rows and counts the union for every set of cache rows it meets, once (a few microseconds; the sets repeat all the time).
+    std::vector<uint32_t> h_valid_tok, h_cd_tok;     // [Q + N][W]
+    std::unordered_map<uint64_t, uint32_t> undecided_of;   // signature of the list of cache rows -> undecided tokens
     uint32_t store_backoff = 0, store_backoff_next = 8;   // after a call the store had no room for: calls that take the per-block automaton instead
     struct CallRecord {                              // what to note in the states once the call in this slot has reported
         bool active = false;
@@ -189,22 +192,19 @@ int setup_device(zf_engine *e) {
             memcpy(&tok16[v], first, 16);
             tok_len[v] = n <= 16 ? (uint8_t)n : (uint8_t)TOK_LEN_LONG;
         }
-        std::vector<uint32_t> valid_tok(std::max<size_t>(n_rows * W, 1), 0), cd_tok(std::max<size_t>(n_rows * W, 1), 0);
-        d->ci_undecided_tok.assign(n_rows, 0);
+        std::vector<uint32_t> &valid_tok = d->h_valid_tok, &cd_tok = d->h_cd_tok;
+        valid_tok.assign(std::max<size_t>(n_rows * W, 1), 0); cd_tok.assign(std::max<size_t>(n_rows * W, 1), 0);
         auto rows_job = [&](size_t r0, size_t r1) {
             for (size_t r = r0; r < r1; r++) {
                 const uint32_t *sv = &tr.ci_valid[r * tr.Wr], *sc = &tr.ci_cd[r * tr.Wr];
                 uint32_t *dv = &valid_tok[r * W], *dc = &cd_tok[r * W];
-                uint32_t und = 0;
                 for (size_t v = 0; v < V; v++) {
                     const uint32_t k = tr.rank_of[v];
                     if (k == 0xFFFFFFFFu) continue;
                     const uint32_t bv = (sv[k >> 5] >> (k & 31)) & 1u, bc = (sc[k >> 5] >> (k & 31)) & 1u;
                     dv[v >> 5] |= bv << (v & 31);
                     dc[v >> 5] |= bc << (v & 31);
-                    und += bc & ~bv;
                 }
-                d->ci_undecided_tok[r] = und;
             }
         };
         const size_t n_thr = std::min<size_t>(std::max<size_t>(1, std::min<unsigned>(8, std::thread::hardware_concurrency())), std::max<size_t>(n_rows, 1));
@@ -1192,23 +1192,36 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
                 double und = d->tab.V;
                 if (use_cache && c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1] <= 64) {
                     const uint32_t n = current_set_entries(e->tab, c, ent);
-                    und = 0;
-                    for (uint32_t k = 0; k < n; k++) und += d->ci_undecided_tok[ent[k]];
-                    und = std::min<double>(und, d->tab.V);
+                    uint64_t sig = 0xCBF29CE484222325ull ^ n;
+                    for (uint32_t k = 0; k < n; k++) sig = (sig ^ ent[k]) * 0x100000001B3ull;
+                    auto it = d->undecided_of.find(sig);
+                    if (it == d->undecided_of.end()) {
+                        const size_t Wt = (size_t)d->tab.W;
+                        uint32_t cnt = 0;
+                        for (size_t w = 0; w < Wt; w++) {
+                            uint32_t v = 0, cd = 0;
+                            for (uint32_t k = 0; k < n; k++) { v |= d->h_valid_tok[ent[k] * Wt + w]; cd |= d->h_cd_tok[ent[k] * Wt + w]; }
+                            cnt += (uint32_t)__builtin_popcount(cd & ~v);
+                        }
+                        if (d->undecided_of.size() > 65536) d->undecided_of.clear();
+                        it = d->undecided_of.emplace(sig, cnt).first;
+                    }
+                    und = it->second;
                 }
-                uint32_t seg_log2 = 4;                            // words per segment: 16, or 8, 4, 2 when 512 tokens would hold more than a batch
-                while (seg_log2 > 1 && und * (32u << seg_log2) > 64.0 * std::max(1, d->tab.V)) seg_log2--;
-                segs[r] = (d->tab.W + (1 << seg_log2) - 1) >> seg_log2;
-                mini.r[r].meta |= seg_log2 << 24;
+                // words per segment: as many as are expected to hold 48 undecided tokens, at most 64 (a batch is 64: the
+                // tokens are spread unevenly, and a second, nearly empty batch costs as much as a full one)
+                const uint32_t seg_words = (uint32_t)std::max(1.0, std::min<double>(STORE_SEG_WORDS_MAX, 48.0 * std::max(1, d->tab.V) / (32.0 * std::max(und, 1.0))));
+                segs[r] = (d->tab.W + (int)seg_words - 1) / (int)seg_words;
+                mini.r[r].meta |= (seg_words - 1) << 24;
                 // a segment that holds any undecided token costs at least one batch
-                weight[r] = segs[r] / 4.0 + std::max(std::min<double>(und, segs[r]), und / 64.0);
+                weight[r] = segs[r] / 2.0 + std::max(std::min<double>(und, segs[r]), und / 64.0);
                 sum += weight[r];
             }
             uint32_t at = 0;
             for (int r = 0; r < nb; r++) {
                 const int max_parts = std::max(1, (segs[r] + STORE_WAVES - 1) / STORE_WAVES);
                 a.store_first_block[r] = (uint16_t)at;
-                at += (uint32_t)std::min<double>(max_parts, std::max(1.0, budget * weight[r] / sum));
+                at += (uint32_t)std::min<double>(max_parts, std::max<double>((segs[r] + 2 * STORE_WAVES - 1) / (2 * STORE_WAVES), budget * weight[r] / sum));   // at most two segments per wavefront
             }
             for (int r = nb; r < STORE_MINI_ROWS + 8; r++) a.store_first_block[r] = r == nb ? (uint16_t)at : (uint16_t)0xFFFF;   // the kernel compares against all of them
             a.store_uniform_parts = 0;

@@ -51,7 +51,8 @@ static const int STORE_WAVES = ZF_STORE_WAVES;  // wavefronts per block of the m
 static const int STORE_BLOCK = STORE_WAVES * 64;
 static const int STORE_SUB_WORDS = ZF_STORE_SUB_WORDS;   // words of the rank-ordered bitmap a block merges and checks per pass (at most 128: one wavefront lists the word pairs)
 static const int STORE_LDS_MAX = 159 * 1024;   // dynamic LDS a block of that kernel may ask for (the hand-over of the call's status has a static word of its own)
-static const int STORE_SEG_WORDS = 16;         // mask words (of 32 tokens) a wavefront merges and checks per pass
+static const int STORE_SEG_WORDS = 16;         // mask words (of 32 tokens) a wavefront merges and checks per pass in calls of more than STORE_MINI_ROWS rows ...
+static const int STORE_SEG_WORDS_MAX = 64;     // ... smaller calls choose 1 to 64 per row, so that a pass holds about one batch of undecided tokens
 static const int STORE_WARM_ROWS = 32;         // rows of the transition table (states one byte from a row's current state) a block reads ahead into its LDS cache
 static const int STORE_LC_BITS = ZF_STORE_LC_BITS;       // log2 of the entries of a block's LDS cache of table entries (8 bytes each)
 #ifndef ZF_STORE_BLOCKS_PER_CU
@@ -89,7 +90,7 @@ static const int STORE_MINI_ROWS = 64, STORE_MINI_PEND = 16, STORE_MINI_ENT = 10
 static const uint32_t STORE_ROW_SPILL = 4u;     // flags of a short record: the row's full record is in MaskArgs::store_rows
 struct StoreRowMini {
     uint32_t start;                               // as StoreRow::start
-    uint32_t meta;                                // n_pending | n_ent << 8 | flags << 16 | log2(mask words per pass) << 24
+    uint32_t meta;                                // n_pending | n_ent << 8 | flags << 16 | (mask words per pass - 1) << 24
     uint8_t pend[STORE_MINI_PEND];
     uint16_t ent[STORE_MINI_ENT];
     uint32_t spare;

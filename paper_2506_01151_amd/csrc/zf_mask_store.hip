@@ -244,7 +244,10 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
     const uint32_t parts = uniform_parts ? uniform_parts : fb1 - fb0;
     // mask words a wavefront takes per pass: the host picks fewer for rows most of whose tokens are undecided, so that a pass
     // holds about one batch of 64 tokens and the row can be dealt to more wavefronts
-    const uint32_t sw = use_mini ? 1u << ((m.meta >> 24) & 7u) : (uint32_t)STORE_SEG_WORDS;
+    const uint32_t sw = use_mini ? ((m.meta >> 24) & 63u) + 1u : (uint32_t)STORE_SEG_WORDS;
+    // lanes per copy of the segment: the wavefront holds the segment's words 64 / slots times over, and each copy ORs its
+    // share of the row's cache rows (16 words: four copies; up to 64 words -- rows few of whose tokens are undecided: one)
+    const uint32_t slots_log2 = sw <= 16u ? 4u : (sw <= 32u ? 5u : 6u), slots = 1u << slots_log2, n_grp = 64u >> slots_log2;
     const uint32_t n_seg = (W + sw - 1) / sw;
     const uint32_t unit = part * STORE_WAVES + wave, n_units = parts * STORE_WAVES;   // a unit = one wavefront of one of the row's blocks
     uint32_t steps = 0;
@@ -270,7 +273,7 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
     uint8_t *l_rep = smem + off; off += 256;
     unsigned long long *lc = reinterpret_cast<unsigned long long *>(smem + off); off += LC_ENTRIES * 8;
     uint32_t *ctl = reinterpret_cast<uint32_t *>(smem + off); off += 32;   // [4] state of the staged tables
-    uint32_t *vbuf = reinterpret_cast<uint32_t *>(smem + off) + wave * STORE_SEG_WORDS; off += STORE_WAVES * STORE_SEG_WORDS * 4;   // per wavefront: verdicts of the pass's words
+    uint32_t *vbuf = reinterpret_cast<uint32_t *>(smem + off) + wave * 64; off += STORE_WAVES * 64 * 4;   // per wavefront: verdicts of the pass's words
     const Staging stg{ctl, smem, D.table_blob, n16, l_rep, D.cls_rep, ncls, a.aut_wide != 0};
     Scratch sc;
     sc.cap = (uint32_t)a.aut_scratch;
@@ -297,14 +300,13 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
     uint32_t root = AT_FAIL, undecided = 0;
     uint32_t *errors = &a.counters[2];
     uint32_t *out_row = a.out_mask + (size_t)(a.dst_row ? a.dst_row[row] : row) * W;
-    const uint32_t slot16 = lane & 15u, grp = lane >> 4;    // lane = (word of the segment, one of four groups of cache rows)
-    static_assert(STORE_SEG_WORDS == 16, "a segment is at most one word per lane of a quarter wavefront");
+    const uint32_t slot16 = lane & (slots - 1u), grp = lane >> slots_log2;    // lane = (word of the segment, which copy)
     // the token-mask cache words of segment g: every quarter of the wavefront ORs a quarter of the row's cache rows
     auto request = [&](uint32_t g, uint32_t &v, uint32_t &c) {
         const uint32_t w = slot16 < sw ? g * sw + slot16 : 0xFFFFFFFFu;
         v = 0; c = use_cache ? 0u : 0xFFFFFFFFu;
         if (use_cache && g < n_seg)
-            for (uint32_t k0 = 0; k0 < n_ent; k0 += 4) {     // uniform trip count: the row numbers come by shuffle
+            for (uint32_t k0 = 0; k0 < n_ent; k0 += n_grp) { // uniform trip count: the row numbers come by shuffle
                 const uint32_t k = k0 + grp;
                 const uint32_t er = entry(k < n_ent ? k : 0u);
                 if (k < n_ent && w < W) { const size_t r = (size_t)er * W + w; v |= D.ci_valid_tok[r]; c |= D.ci_cd_tok[r]; }
@@ -316,7 +318,7 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
     if (n_pending && start_ok && pending(0) < ncls) hop0 = __hip_atomic_load(&G.trans[start * ncls + pending(0)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
     uint32_t v = 0, c = 0;
     request(unit, v, c);
-    {
+    auto find_root = [&]() {
         // ---- the row's current state: walk the bytes fed since `start` was its state (the loads above are in flight) ----
         uint32_t s = start;
         bool bad = s == 0 || (s >= G.cap_states && s != AT_SINK);
@@ -369,52 +371,67 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
             };
             warm_row(root);
         }
-    }
-    const bool root_ok = root < AT_FAIL;                     // AT_SINK: nothing can follow; AT_FAIL: the call fails
-    for (uint32_t g = unit; g < n_seg; g += n_units) {
-        const uint32_t w = slot16 < sw ? g * sw + slot16 : 0xFFFFFFFFu;
+    };
+    // One token of a batch: where its verdict goes, and its string (requested here, used a batch later).
+    struct Tok { uint32_t slot, bit, len, soff; Str16 c16; bool live; };
+    uint32_t incl = 0, want = 0;                             // of the segment in hand: running bit counts of its words, undecided bits
+    auto fetch = [&](uint32_t g, uint32_t b0, uint32_t total) -> Tok {
+        Tok k;
+        const uint32_t i = b0 + lane;
+        k.live = i < total;
+        k.slot = 0;                                          // the word that holds the lane's token: the first whose running count exceeds i
+        if (total) for (uint32_t j = 0; j + 1u < slots; j++) k.slot += i >= (uint32_t)__builtin_amdgcn_readlane((int)incl, (int)j) ? 1u : 0u;
+        const uint32_t before = (uint32_t)__shfl((int)incl, (int)(k.slot ? k.slot - 1 : 0));
+        const uint32_t bits = (uint32_t)__shfl((int)want, (int)k.slot);
+        uint32_t n = i - (k.slot ? before : 0u);             // the n-th set bit of the word, by halving
+        k.bit = 0;
+#pragma unroll
+        for (int sh = 16; sh >= 1; sh >>= 1) {
+            const uint32_t low = (uint32_t)__popc(bits & (((1u << sh) - 1u) << k.bit));
+            if (n >= low) { n -= low; k.bit += (uint32_t)sh; }
+        }
+        const uint32_t token = (g * sw + k.slot) * 32u + k.bit;
+        k.soff = 0; k.len = 0;
+        k.c16 = Str16{{0, 0, 0, 0}};
+        if (k.live) { k.len = D.tok_len[token]; k.c16 = D.tok16[token]; }
+        if (k.live && k.len == (uint32_t)TOK_LEN_LONG) {     // longer than the 16 classes at hand: the rest is with the string's rank
+            const uint32_t rank = D.rank_of[token];
+            k.soff = D.str_off[rank]; k.len = D.str_off[rank + 1] - k.soff;
+        }
+        return k;
+    };
+    bool root_ok = false;
+    // the first pass runs even for a wavefront without a segment (the row's first wavefront reports the row's state)
+    for (uint32_t g = unit, first = 1; first || g < n_seg; g += n_units, first = 0) {
+        const uint32_t w = slot16 < sw && g < n_seg ? g * sw + slot16 : 0xFFFFFFFFu;
         uint32_t vn = 0, cn = 0;
         request(g + n_units, vn, cn);                        // the next segment's words travel while this one's tokens are checked
-        v |= __shfl_xor(v, 16); v |= __shfl_xor(v, 32);
-        c |= __shfl_xor(c, 16); c |= __shfl_xor(c, 32);
-        uint32_t want = c & ~v;
+        if (slots_log2 <= 4u) { v |= __shfl_xor(v, 16); c |= __shfl_xor(c, 16); }
+        if (slots_log2 <= 5u) { v |= __shfl_xor(v, 32); c |= __shfl_xor(c, 32); }
+        want = c & ~v;
         {
             const uint32_t t0 = w * 32u;
-            if (w >= W || t0 >= (uint32_t)D.V || !root_ok) want = 0;
+            if (w >= W || t0 >= (uint32_t)D.V) want = 0;
             else if ((uint32_t)D.V - t0 < 32u) want &= (1u << ((uint32_t)D.V - t0)) - 1u;
-            if (!root_ok) v = 0;                             // no token can follow a finished sentence
         }
-        // ---- one lane per undecided token through the table.  The undecided tokens of the 16 words are numbered
+        // ---- one lane per undecided token through the table.  The undecided tokens of the segment's words are numbered
         // through (prefix sum of the words' bit counts) and taken 64 at a time, so that a batch is full whatever the
-        // pattern of the bits; verdicts go back to their words through 16 words of LDS ----
-        uint32_t incl = (uint32_t)__popc(want);              // every group of 16 lanes holds the same 16 words
-#pragma unroll
-        for (int d = 1; d < 16; d <<= 1) { const uint32_t up = __shfl_up(incl, d, 16); if (slot16 >= (uint32_t)d) incl += up; }
-        const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 15);
+        // pattern of the bits; verdicts go back to their words through LDS.  The strings of a batch are requested one
+        // batch ahead; those of the first batch travel while the row's current state is worked out ----
+        incl = (uint32_t)__popc(want);                       // every copy holds the same words
+        for (uint32_t d = 1; d < slots; d <<= 1) { const uint32_t up = __shfl_up(incl, d, (int)slots); if (slot16 >= d) incl += up; }
+        uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, (int)(slots - 1u));
+        Tok nxt = fetch(g, 0, total);
+        if (first) { find_root(); root_ok = root < AT_FAIL; }   // AT_SINK: nothing can follow; AT_FAIL: the call fails
+        if (!root_ok) { total = 0; v = 0; }                  // no token can follow a finished sentence
         undecided += total;
-        if (lane < 16u) lds_store(&vbuf[lane], 0u);
+        if (lane < slots) lds_store(&vbuf[lane], 0u);
         for (uint32_t b0 = 0; b0 < total; b0 += 64) {
-            const uint32_t i = b0 + lane;
-            bool live = i < total;
-            uint32_t slot = 0;                               // the word that holds the lane's token: the first whose running count exceeds i
-#pragma unroll
-            for (int k = 0; k < 15; k++) slot += i >= (uint32_t)__builtin_amdgcn_readlane((int)incl, k) ? 1u : 0u;
-            const uint32_t before = (uint32_t)__shfl((int)incl, (int)(slot ? slot - 1 : 0));
-            const uint32_t bits = (uint32_t)__shfl((int)want, (int)slot);
-            uint32_t n = i - (slot ? before : 0u), bit = 0;  // the n-th set bit of the word, by halving
-#pragma unroll
-            for (int sh = 16; sh >= 1; sh >>= 1) {
-                const uint32_t low = (uint32_t)__popc(bits & (((1u << sh) - 1u) << bit));
-                if (n >= low) { n -= low; bit += (uint32_t)sh; }
-            }
-            const uint32_t token = (g * sw + slot) * 32u + bit;
-            uint32_t soff = 0, len = 0;
-            Str16 c16{{0, 0, 0, 0}};
-            if (live) { len = D.tok_len[token]; c16 = D.tok16[token]; }
-            if (live && len == (uint32_t)TOK_LEN_LONG) {     // longer than the 16 classes at hand: the rest is with the string's rank
-                const uint32_t rank = D.rank_of[token];
-                soff = D.str_off[rank]; len = D.str_off[rank + 1] - soff;
-            }
+            const Tok cur = nxt;
+            if (b0 + 64 < total) nxt = fetch(g, b0 + 64, total);
+            const uint32_t slot = cur.slot, bit = cur.bit, soff = cur.soff, len = cur.len;
+            const Str16 c16 = cur.c16;
+            bool live = cur.live;
             live = live && len > 0;
             uint32_t s = root, pos = 0, cc = 0, spins = 0, t = AT_BUSY;
             bool ok = false, fail = false, again = false;
@@ -471,7 +488,7 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
             if (lane == 0 && fm) atomicAdd(errors, (uint32_t)__popcll(fm));
         }
         if (total) v |= lds_load(&vbuf[slot16]);             // LDS serves one wavefront's accesses in issue order
-        if (lane < 16u && w < W) out_row[w] = v;
+        if (lane < slots && w < W) out_row[w] = v;
         v = vn; c = cn;
     }
     if (lane == 0 && steps) atomicAdd(&a.counters[3], steps);
@@ -529,7 +546,7 @@ hipError_t prepare_store_kernels() {
 }
 
 uint32_t store_lds_bytes(const DeviceTables &t, int mode, int scratch) {
-    return table_bytes(t, mode) + 256 + LC_ENTRIES * 8 + 32 + STORE_WAVES * STORE_SEG_WORDS * 4 +
+    return table_bytes(t, mode) + 256 + LC_ENTRIES * 8 + 32 + STORE_WAVES * 64 * 4 +
            STORE_WAVES * ((uint32_t)scratch * 8 + aut_hash_places((uint32_t)scratch) * 4);
 }
 
