@@ -159,7 +159,7 @@ class Runner:
         self.d_mask = torch.empty((self.B, eng.W), dtype=torch.int32, device="cuda")
         self.states = zf.StateBatch([eng.new_state() for _ in range(self.B)])
 
-    def run(self, n_warm, n_timed, profile=False, count_hits=False, sync_steps=True, cold=True, keep_masks=None):
+    def run(self, n_warm, n_timed, profile=False, count_hits=False, sync_steps=True, cold=True, keep_masks=None, fused=True):
         zf, torch, eng = self.zf, self.torch, self.eng
         eng.set_profiling(profile)
         lat, adv = [], []
@@ -189,10 +189,13 @@ class Runner:
             t0 = time.perf_counter()
             self.states.advance(ids)                    # every row by its token (a negative id starts the row over)
             t1 = time.perf_counter()
-            eng.compute_mask_async(self.states, p_mask, h_stream)
-            if profile and i >= n_warm:
-                evs[k][0].record()
-            eng.apply_mask(p_logits[i % len(p_logits)], p_out, dt, self.B, row_stride, p_mask, h_stream)
+            if fused and not profile:                   # compute_mask and apply_mask of the step in one call (one kernel on the default path)
+                eng.compute_mask_apply_async(self.states, p_mask, p_logits[i % len(p_logits)], p_out, dt, row_stride, h_stream)
+            else:
+                eng.compute_mask_async(self.states, p_mask, h_stream)
+                if profile and i >= n_warm:
+                    evs[k][0].record()
+                eng.apply_mask(p_logits[i % len(p_logits)], p_out, dt, self.B, row_stride, p_mask, h_stream)
             if profile and i >= n_warm:
                 evs[k][1].record()
             eng.mask_wait(h_stream)                     # returns once the mask kernels are complete; apply_mask may still run

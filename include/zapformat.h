@@ -179,6 +179,15 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states /* host array */, int3
 int zf_compute_mask_async(zf_engine *e, zf_state *const *states /* host array */, int32_t batch,
                           uint32_t *d_mask, void *hip_stream);
 int zf_mask_wait(zf_engine *e, void *hip_stream);
+/* compute_mask followed by apply_mask on the same rows (Sections 4.1 and 3.3: the verdicts of a step are there to mask that
+ * step's logits), enqueued together: the result in d_mask and d_out is exactly what zf_compute_mask_async followed by
+ * zf_apply_mask(e, d_logits, d_out, dtype, batch, row_stride_elems, d_mask, hip_stream) gives, and zf_mask_wait reports as
+ * for that pair.  With the persistent automaton as the mask kernel and the state cache off, one kernel does both (a wavefront
+ * masks the logits of the tokens whose mask words it has just written), provided the pointers, the row stride and V are
+ * multiples of 16 bytes' worth of logits; in every other case the call enqueues the two kernels one after the other.  d_out may
+ * equal d_logits; dtype 0 = fp32, 1 = bf16. */
+int zf_compute_mask_apply_async(zf_engine *e, zf_state *const *states /* host array */, int32_t batch, uint32_t *d_mask,
+                                const void *d_logits, void *d_out, int32_t dtype, int64_t row_stride_elems, void *hip_stream);
 /* zf_compute_mask for callers that cannot allocate device memory: tight serving loops, harnesses
  * that forbid hipMalloc, code that runs while a HIP graph is being captured on another stream.  Same
  * arguments, same result, same waiting behaviour as zf_compute_mask, but the call allocates nothing

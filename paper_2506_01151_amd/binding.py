@@ -51,7 +51,7 @@ class MaskReport(ctypes.Structure):
 EXPORTS = ["zf_strerror", "zf_last_error", "zf_compile", "zf_engine_destroy", "zf_engine_get_info",
            "zf_state_new", "zf_state_clone", "zf_state_reset", "zf_state_destroy", "zf_advance",
            "zf_advance_bytes", "zf_advance_batch", "zf_is_accepting", "zf_state_stats", "zf_state_chart", "zf_position_info",
-           "zf_compute_mask", "zf_compute_mask_noalloc", "zf_compute_mask_async", "zf_mask_wait", "zf_last_mask_report", "zf_engine_clear_state_cache", "zf_engine_set_profiling", "zf_apply_mask"]
+           "zf_compute_mask", "zf_compute_mask_noalloc", "zf_compute_mask_async", "zf_compute_mask_apply_async", "zf_mask_wait", "zf_last_mask_report", "zf_engine_clear_state_cache", "zf_engine_set_profiling", "zf_apply_mask"]
 # test-only diagnostics (include/zapformat_debug.h)
 DEBUG_EXPORTS = ["zf_debug_host_mask", "zf_debug_host_mask_stats", "zf_debug_host_mask_cached", "zf_debug_host_mask_automaton",
                  "zf_debug_twin_new", "zf_debug_twin_destroy", "zf_debug_twin_advance", "zf_debug_twin_mask"]
@@ -91,6 +91,7 @@ def load_library():
     L.zf_compute_mask.argtypes = [c_vp, c_vp, c_i32, c_vp, c_vp]
     L.zf_compute_mask_async.argtypes = [c_vp, c_vp, c_i32, c_vp, c_vp]
     L.zf_compute_mask_noalloc.argtypes = [c_vp, c_vp, c_i32, c_vp, c_vp]
+    L.zf_compute_mask_apply_async.argtypes = [c_vp, c_vp, c_i32, c_vp, c_vp, c_vp, c_i32, c_i64, c_vp]
     L.zf_mask_wait.argtypes = [c_vp, c_vp]
     L.zf_last_mask_report.argtypes = [c_vp, c_vp]
     L.zf_advance_batch.argtypes = [c_vp, c_vp, c_i32, c_vp]
@@ -296,6 +297,9 @@ class Engine:
     def compute_mask_async(self, states, d_mask_ptr: int, stream: int = 0):
         _check(_lib.zf_compute_mask_async(self.h, _handles(states), len(states), d_mask_ptr, stream))
 
+    def compute_mask_apply_async(self, states, d_mask_ptr: int, d_logits_ptr: int, d_out_ptr: int, dtype: int, row_stride: int, stream: int = 0):
+        _check(_lib.zf_compute_mask_apply_async(self.h, _handles(states), len(states), d_mask_ptr, d_logits_ptr, d_out_ptr, dtype, row_stride, stream))
+
     def mask_wait(self, stream: int = 0):
         _check(_lib.zf_mask_wait(self.h, stream))
 
@@ -358,6 +362,20 @@ def compute_mask_async(engine: Engine, states, mask_tensor):
     assert tuple(mask_tensor.shape) == (len(states), engine.W)
     engine.compute_mask_async(states, mask_tensor.data_ptr(), _current_stream(engine))
     return mask_tensor
+
+
+def compute_mask_apply_async(engine: Engine, states, mask_tensor, logits, out=None):
+    """compute_mask and apply_mask of the same rows, enqueued together; pair with mask_wait(engine)."""
+    import torch
+    assert mask_tensor.is_cuda and mask_tensor.is_contiguous() and mask_tensor.dtype == torch.int32
+    assert tuple(mask_tensor.shape) == (len(states), engine.W)
+    assert logits.is_cuda and logits.dim() == 2 and logits.stride(1) == 1 and tuple(logits.shape) == (len(states), engine.V)
+    dtype = {torch.float32: 0, torch.bfloat16: 1}[logits.dtype]
+    if out is None:
+        out = logits
+    assert out.dtype == logits.dtype and out.shape == logits.shape and out.stride() == logits.stride()
+    engine.compute_mask_apply_async(states, mask_tensor.data_ptr(), logits.data_ptr(), out.data_ptr(), dtype, logits.stride(0), _current_stream(engine))
+    return out
 
 
 def mask_wait(engine: Engine):

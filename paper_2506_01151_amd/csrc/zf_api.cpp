@@ -737,6 +737,10 @@ static int state_cache_lookup(DeviceSide *d, const std::vector<std::vector<uint3
 }
 
 static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait, uint32_t slot);
+// zf_compute_mask_apply_async: the logits the call's mask is to be applied to.  The mask kernel over the persistent automaton
+// takes them along when it can (fused = true); whoever set the request launches the logit-masking kernel otherwise.
+struct ApplyRequest { const void *logits = nullptr; void *out = nullptr; int64_t stride = 0; int32_t dtype = 0; bool fused = false; };
+static thread_local ApplyRequest g_apply;
 
 // Pack and upload the charts and enqueue the kernels of one compute_mask call: upload, mask kernel,
 // closing kernel (fallback pass for what the mask kernel listed + permutation into token order),
@@ -1158,6 +1162,15 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
     a.handoff_in_permute = 0;
     a.handoff_in_store = sc ? 0 : 1;                      // with the state cache on, the gather is the call's last kernel
     a.store_mini = use_mini ? 1 : 0;
+    if (g_apply.out && direct && nb == batch) {            // every row runs through the kernel, row r of the call is row r of the tensors
+        const size_t esz = g_apply.dtype == 0 ? 4 : 2;
+        const bool pieces = (uintptr_t)g_apply.logits % 16 == 0 && (uintptr_t)g_apply.out % 16 == 0 && (g_apply.stride * (int64_t)esz) % 16 == 0 &&
+                            (size_t)e->V % (16 / esz) == 0;
+        if (pieces) {
+            a.apply_logits = g_apply.logits; a.apply_out = g_apply.out; a.apply_stride = g_apply.stride; a.apply_dtype = g_apply.dtype;
+            g_apply.fused = true;
+        }
+    }
     a.counters = d->d_counters + COUNTER_SET_WORDS * d->call_parity;
     a.counters_next = d->d_counters + COUNTER_SET_WORDS * (d->call_parity ^ 1u);
     d->call_parity ^= 1u;
@@ -1287,6 +1300,17 @@ int zf_compute_mask_noalloc(zf_engine *e, zf_state *const *states, int32_t batch
 
 int zf_compute_mask_async(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream) {
     return enqueue_mask(e, states, batch, d_mask, hip_stream, false);
+}
+
+int zf_compute_mask_apply_async(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, const void *d_logits, void *d_out,
+                                int32_t dtype, int64_t row_stride, void *hip_stream) {
+    if (!e || !d_logits || !d_out || (dtype != 0 && dtype != 1) || row_stride < (e ? e->V : 0)) return fail(ZF_ERR_INVALID_ARG, "bad argument");
+    g_apply = ApplyRequest{d_logits, d_out, row_stride, dtype, false};
+    const int rc = enqueue_mask(e, states, batch, d_mask, hip_stream, false);
+    const bool fused = g_apply.fused;
+    g_apply = ApplyRequest{};
+    if (rc != ZF_OK || fused) return rc;
+    return zf_apply_mask(e, d_logits, d_out, dtype, batch, row_stride, d_mask, hip_stream);   // the other mask kernels, the state cache, odd shapes: two launches
 }
 
 int zf_mask_wait(zf_engine *e, void *hip_stream) {

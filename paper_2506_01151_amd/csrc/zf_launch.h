@@ -133,6 +133,13 @@ struct MaskArgs {
     int32_t user_batch;
     int32_t handoff_in_permute; // 1: permute is the call's last kernel (state cache off), else the gather is
     int32_t handoff_in_store;  // 1: the mask kernel over the persistent automaton is the call's last kernel (it writes the caller's rows itself)
+    // zf_compute_mask_apply_async on that path: a wavefront masks the logits of the tokens whose mask words it has just written
+    // (no second kernel); null = the mask only.  Row r of the call is row r of the tensors; 16-byte pieces (V, the row stride
+    // and the pointers are multiples of a piece: the host checks).
+    const void *apply_logits;
+    void *apply_out;
+    int64_t apply_stride;      // elements between rows
+    int32_t apply_dtype;       // 0 = fp32, 1 = bf16
     int32_t store_mini;        // 1: the rows' records are in the kernel's StoreMiniRows argument
     uint32_t *counters;        // [0] chunks passed to the fallback, [1] length of the work queue, [2] chunks nobody could resolve,
                                // [3] Earley byte steps, [4] fallback wavefronts that have finished, [16..144] tickets of the call's last kernel;

@@ -102,6 +102,7 @@ struct StoreSets {             // resolves the name of a set to its items (devic
     }
 };
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 struct Scratch { uint32_t *w, *o, *h; uint32_t cap; };   // one wavefront's set under construction (+ hash table of the wide step)
 
 // true when state `id` holds exactly the `kept` items in the scratch
@@ -406,6 +407,17 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
         const uint32_t w = slot16 < sw && g < n_seg ? g * sw + slot16 : 0xFFFFFFFFu;
         uint32_t vn = 0, cn = 0;
         request(g + n_units, vn, cn);                        // the next segment's words travel while this one's tokens are checked
+        // the segment's logits (when the call masks them too): the first two pieces of every lane are requested now and
+        // wait in registers until the verdicts are in
+        const uint32_t tp = a.apply_dtype ? 8u : 4u, esz = a.apply_dtype ? 2u : 4u;   // tokens per 16-byte piece, bytes per logit
+        const uint32_t tok0 = g * sw * 32u;
+        const uint32_t n_tok = a.apply_out && g < n_seg && tok0 < (uint32_t)D.V ? (sw * 32u < (uint32_t)D.V - tok0 ? sw * 32u : (uint32_t)D.V - tok0) : 0u;
+        const uint32_t pieces = n_tok / tp;
+        const size_t l_at = ((size_t)row * (size_t)a.apply_stride + tok0) * esz;
+        const u32x4 *l_src = reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint8_t *>(a.apply_logits) + l_at);
+        u32x4 l_pre[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+#pragma unroll
+        for (int u = 0; u < 2; u++) if ((uint32_t)u * 64u + lane < pieces) l_pre[u] = __builtin_nontemporal_load(l_src + (uint32_t)u * 64u + lane);
         if (slots_log2 <= 4u) { v |= __shfl_xor(v, 16); c |= __shfl_xor(c, 16); }
         if (slots_log2 <= 5u) { v |= __shfl_xor(v, 32); c |= __shfl_xor(c, 32); }
         want = c & ~v;
@@ -489,6 +501,31 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
         }
         if (total) v |= lds_load(&vbuf[slot16]);             // LDS serves one wavefront's accesses in issue order
         if (lane < slots && w < W) out_row[w] = v;
+        if (a.apply_out && g < n_seg) {
+            // Logit masking (Section 3.3) of the segment's tokens, right here: 16-byte pieces, consecutive lanes on consecutive
+            // pieces, the mask word from the lane that holds it.  Allowed logits are copied bit for bit, the others become -inf.
+            uint8_t *dst = reinterpret_cast<uint8_t *>(a.apply_out) + l_at;
+            for (uint32_t p0 = 0; p0 < pieces; p0 += 64) {   // uniform trip count: the shuffle below is for all lanes
+                const uint32_t p = p0 + lane, t_in = p * tp;
+                const uint32_t mb = (uint32_t)__shfl((int)v, (int)((t_in >> 5) & 63u)) >> (t_in & 31u);
+                if (p < pieces) {
+                    u32x4 x = p0 == 0 ? l_pre[0] : (p0 == 64 ? l_pre[1] : __builtin_nontemporal_load(l_src + p));
+                    if (a.apply_dtype) {
+#pragma unroll
+                        for (int k = 0; k < 4; k++) {
+                            uint32_t e = x[k];
+                            if (!((mb >> (2 * k)) & 1u)) e = (e & 0xFFFF0000u) | 0xFF80u;
+                            if (!((mb >> (2 * k + 1)) & 1u)) e = (e & 0x0000FFFFu) | 0xFF800000u;
+                            x[k] = e;
+                        }
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < 4; k++) if (!((mb >> k) & 1u)) x[k] = 0xFF800000u;
+                    }
+                    __builtin_nontemporal_store(x, reinterpret_cast<u32x4 *>(dst) + p);
+                }
+            }
+        }
         v = vn; c = cn;
     }
     if (lane == 0 && steps) atomicAdd(&a.counters[3], steps);

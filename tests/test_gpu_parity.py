@@ -710,6 +710,52 @@ def test_apply_mask_full_size_bf16(torch_cuda, oracle_lib):
     assert out.view(torch.int16).cpu().numpy().view(np.uint16).tobytes() == want.tobytes()
 
 
+FUSED = [("store", "bf16", 0, True), ("store", "f32", 0, False), ("store", "bf16", 13, False), ("store-state-cache", "f32", 0, True),
+         ("automaton", "bf16", 0, False), ("trie-walk", "f32", 0, True)]
+
+
+@pytest.mark.parametrize("variant,dtype,ragged,in_place", FUSED, ids=[f"{v}-{d}-{'ragged' if r else 'even'}-{'in-place' if i else 'out'}" for v, d, r, i in FUSED])
+def test_compute_mask_apply_in_one_call(variant, dtype, ragged, in_place, torch_cuda, oracle_lib):
+    """zf_compute_mask_apply_async: the mask and the masked logits of every step against the oracle, bit for bit -- through the
+    persistent automaton (one kernel does both), with a vocabulary size that is no multiple of a 16-byte piece, with the state
+    cache on and through the other mask kernels (two kernels behind the one call)."""
+    import paper_2506_01151_amd as zf
+    from oracle.frontend import apply_mask as oracle_apply
+    torch = torch_cuda
+    cfg = configs.CONFIGS[1]
+    toks = cfg.vocab(2048 - ragged)
+    kw = {"store": dict(walk_mode=2, state_cache_entries=-1), "store-state-cache": dict(walk_mode=2, state_cache_entries=64),
+          "automaton": dict(walk_mode=0, state_cache_entries=-1), "trie-walk": dict(walk_mode=1, state_cache_entries=-1)}[variant]
+    eng = zf.Engine(cfg.grammar(), toks, device=0, **kw)
+    B, V = 5, eng.V
+    orc = oracle_lib.Oracle(cfg.grammar())
+    run = OracleRun(orc, toks, [stream(cfg.seed + 77, f"sample[{b}]") for b in range(B)])
+    states = [eng.new_state() for _ in range(B)]
+    d_mask = torch.empty((B, eng.W), dtype=torch.int32, device="cuda")
+    rng = np.random.default_rng(5)
+    ivt = torch.int32 if dtype == "f32" else torch.int16
+    for step in range(40):
+        want_mask = run.masks()
+        if dtype == "f32":
+            bits = rng.integers(0, 2**32, size=(B, V), dtype=np.uint32)
+            t = torch.from_numpy(bits.view(np.int32)).cuda().view(torch.float32)
+        else:
+            bits = rng.integers(0, 2**16, size=(B, V), dtype=np.uint16)
+            t = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+        out = t if in_place else torch.full_like(t, 1.0)
+        d_mask.fill_(0x5A5A5A5A)
+        zf.compute_mask_apply_async(eng, states, d_mask, t, out=out)
+        zf.mask_wait(eng)
+        torch.cuda.synchronize()
+        got_mask = d_mask.cpu().numpy().view(np.uint32)
+        assert np.array_equal(got_mask, want_mask), f"{variant} step {step}: mask"
+        want = oracle_apply(bits, want_mask)
+        got = out.view(ivt).cpu().numpy().view(bits.dtype)
+        assert got.tobytes() == want.tobytes(), f"{variant} step {step}: masked logits"
+        for b, tk in enumerate(run.step(want_mask)):
+            states[b].reset() if tk < 0 else states[b].advance(tk)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_apply_mask_bit_exact(dtype, torch_cuda, oracle_lib):
     import paper_2506_01151_amd as zf
