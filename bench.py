@@ -2,9 +2,11 @@
 """Benchmark of the per-decode-step vocabulary mask on one MI355X.
 
 A "step" is one pass of the whole hot path over one batch: advance every row by its next token
-(host Earley + ZapFormat compaction), compute_mask (the fed bytes go up in a pinned slot the kernel
-reads in place; mask kernel over the persistent automaton; closing kernel = bit permutation into
-token order), apply_mask on that step's logits, and mask_wait (deferred error check).  The token
+(host Earley + ZapFormat compaction), compute_mask and apply_mask on that step's logits -- enqueued
+with one call, zf_compute_mask_apply_async: the fed bytes go up in the kernel's argument block, the
+mask kernel over the persistent automaton writes the mask rows in token order and masks the logits
+of the tokens whose mask words it has just written -- and mask_wait (deferred error check).  The
+same steps through the two separate calls (two kernels) are reported beside it (`two_calls`).  The token
 trajectory is fixed beforehand (tests/golden/trajectory_cfgN.txt, sampled by the CPU oracle), so
 nothing is copied back to the host inside the timed region.  Inputs are seeded and synthetic.
 
@@ -189,15 +191,15 @@ class Runner:
             t0 = time.perf_counter()
             self.states.advance(ids)                    # every row by its token (a negative id starts the row over)
             t1 = time.perf_counter()
-            if fused and not profile:                   # compute_mask and apply_mask of the step in one call (one kernel on the default path)
+            if fused:                                   # compute_mask and apply_mask of the step in one call (one kernel on the default path)
                 eng.compute_mask_apply_async(self.states, p_mask, p_logits[i % len(p_logits)], p_out, dt, row_stride, h_stream)
             else:
                 eng.compute_mask_async(self.states, p_mask, h_stream)
                 if profile and i >= n_warm:
                     evs[k][0].record()
                 eng.apply_mask(p_logits[i % len(p_logits)], p_out, dt, self.B, row_stride, p_mask, h_stream)
-            if profile and i >= n_warm:
-                evs[k][1].record()
+                if profile and i >= n_warm:
+                    evs[k][1].record()
             eng.mask_wait(h_stream)                     # returns once the mask kernels are complete; apply_mask may still run
             if sync_steps:                              # until the masked logits are there
                 stream.synchronize()
@@ -220,7 +222,7 @@ class Runner:
                     keep_masks.append(self.d_mask.clone())
         torch.cuda.synchronize()
         total = time.perf_counter() - t_begin
-        if profile:
+        if profile and not fused:
             kern["apply"] = [a.elapsed_time(b) for a, b in evs]
         return {"total": total, "lat": lat, "adv": adv, "kern": kern, "rep": rep}
 
@@ -240,19 +242,21 @@ def side_config(zf, torch, configs, idx, steps, warm, pruning=True, walk_mode=2)
     eng = zf.Engine(cfg.grammar(), toks, device=0, pruning=pruning, state_cache_entries=-1, walk_mode=walk_mode)
     logits = [configs.make_logits(cfg, i, device="cuda") for i in range(2)]
     rn = Runner(zf, torch, cfg, eng, traj, logits)
-    r = rn.run(warm, steps, profile=False)
-    again = rn.run(0, steps, cold=False) if pruning and walk_mode == 2 else None   # the same steps with the automaton the first pass built
-    p = rn.run(0, steps, profile=True)
+    runs = sorted((rn.run(warm if k == 0 else 0, steps, profile=False) for k in range(3)), key=lambda x: x["total"])
+    r = runs[1]                                              # three passes, each from a cleared automaton: the median one
+    again = rn.run(0, steps, cold=False) if pruning and walk_mode == 2 else None   # the same steps with the automaton the last pass built
+    p = rn.run(0, steps, profile=True, fused=False)          # two calls: the mask kernel and apply_mask timed separately
+    p1 = rn.run(0, steps, profile=True)                      # one call: the kernel that does both
     B, V = cfg.batch, eng.V
     esz = logits[0].element_size()
     apply_bytes = 2 * B * V * esz + B * eng.W * 4
     apply_ms = statistics.fmean(p["kern"]["apply"])
     out = {"workload": f"configs[{idx - 1}] {cfg.name}: V={V} batch={B} logits={cfg.dtype} pruning={'on' if pruning else 'off'}",
            "trajectory": "oracle-sampled file", "steps": steps, "mask_kernel": KERNEL_OF_MODE[walk_mode if pruning else 0],
-           "value": B * V * steps / r["total"], "ms_per_step": r["total"] / steps * 1e3,
+           "value": B * V * steps / r["total"], "ms_per_step": r["total"] / steps * 1e3, "timed_passes_ms_per_step": [x["total"] / steps * 1e3 for x in runs],
            "p50_mask_apply_latency_us": pct(r["lat"], 0.5) * 1e6, "p99_mask_apply_latency_us": pct(r["lat"], 0.99) * 1e6, "max_mask_apply_latency_us": max(r["lat"]) * 1e6,
            "mean_advance_us_per_step": statistics.fmean(r["adv"]) * 1e6,
-           "kernel_ms": {k: statistics.fmean(v) for k, v in p["kern"].items()},
+           "kernel_ms": {"one_call": statistics.fmean(p1["kern"]["main"]), "two_calls": {k: statistics.fmean(v) for k, v in p["kern"].items() if v}},
            "earley_steps_per_launch": p["rep"]["steps"] / steps, "undecided_strings_per_step": p["rep"]["queued"] / steps,
            "upload_bytes_per_step": p["rep"]["upload_bytes"] / steps,
            "apply_mask": {"algorithmic_bytes": apply_bytes, "GB/s": apply_bytes / (apply_ms * 1e-3) / 1e9, "frac": apply_bytes / (apply_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -280,6 +284,7 @@ def main():
                     help="only run apply_mask with an all-ones mask on a [1024, V] tensor three times: a plain copy of known "
                          "size, used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--apply-sweep-only", action="store_true", help="only the apply_mask sweeps (for a kernel trace of them)")
+    ap.add_argument("--two-calls", action="store_true", help="with --headline-only: the steps through zf_compute_mask_async + zf_apply_mask (two kernels) instead of the one call")
     args = ap.parse_args()
     if args.gpus != 1:
         print("this benchmark runs on one GPU only: rows and vocabulary ranges would shard without any exchange, "
@@ -323,8 +328,9 @@ def main():
     rn = Runner(zf, torch, cfg, eng, traj, logits)
 
     if args.headline_only:
-        r = rn.run(Wm, K)
-        print(json.dumps({"headline_only": True, "steps": K, "warmup": Wm, "ms_per_step": r["total"] / K * 1e3, "value": B * V * K / r["total"]}))
+        r = rn.run(Wm, K, fused=not args.two_calls)
+        print(json.dumps({"headline_only": True, "calls_per_step": "two" if args.two_calls else "one", "steps": K, "warmup": Wm,
+                          "ms_per_step": r["total"] / K * 1e3, "value": B * V * K / r["total"]}))
         return
 
     # three synchronised passes (each from a cleared store): the headline is their median; latencies over all of them
@@ -336,8 +342,10 @@ def main():
     piped = rn.run(0, K, sync_steps=False)                       # steps enqueued back to back: the host runs ahead of the stream
     warm = rn.run(0, K, cold=False)                              # the same steps again with the persistent automaton left as the last pass built it
     masks = []
-    prof = rn.run(0, K, profile=True, keep_masks=masks if K <= 1024 else None)   # HIP events around each kernel
+    prof = rn.run(0, K, profile=True, keep_masks=masks if K <= 1024 else None)   # HIP events around the kernel
     kern, rep = prof["kern"], prof["rep"]
+    two = rn.run(0, K, fused=False)                              # the same steps through compute_mask_async + apply_mask: two kernels
+    two_prof = rn.run(0, K, profile=True, fused=False)
     # mask density: allowed fraction per (step, row), from the masks the profiled pass produced
     density_hist = None
     if masks:
@@ -365,18 +373,21 @@ def main():
     value = B * V * K / total
     info = eng.info
     main_ms = statistics.fmean(kern["main"])
-    apply_ms = statistics.fmean(kern["apply"])
-    # Algorithmic bytes of one mask-kernel launch: the token-mask-cache words merged (two bitsets of Wr words per selected cache
-    # row), the rank-ordered verdict words written, 24 bytes per undecided string (its first 16 byte classes and two offsets),
-    # 4 bytes per transition-table entry a string walks over (counted as one entry per byte of a mean string), and the upload.
+    apply_ms = statistics.fmean(two_prof["kern"]["apply"])
+    apply_bytes = 2 * B * V * esz + B * W * 4
+    # Algorithmic bytes of one launch of the default kernel (mask + logit masking in one): the token-mask-cache words merged (two
+    # bitsets of W words per selected cache row), the mask words written, 17 bytes per undecided token (its first 16 byte
+    # classes and its length), the logits read and written, and the upload.  The other mask kernels work in string-rank order
+    # (Wr words per row, 24 bytes per undecided string) and leave the logits to apply_mask.
     Wr = (info.n_strings + 31) // 32
     queued, crows = rep["queued"], rep["cache_rows"]
-    if args.walk_mode != 1:
+    if args.walk_mode == 2 and args.pruning:
+        mask_bytes = int(crows / K * W * 8 + B * W * 4 + queued / K * 17 + rep["upload_bytes"] / K) + 2 * B * V * esz
+    elif args.walk_mode != 1:
         mask_bytes = int(crows / K * Wr * 8 + B * Wr * 4 + queued / K * 24 + rep["upload_bytes"] / K)
     else:
         n_chunks = (info.n_strings + 31) // 32
         mask_bytes = info.n_trie_nodes * 16 + n_chunks * (8 + 64) + B * n_chunks * 4 + int(rep["upload_bytes"] / K)
-    apply_bytes = 2 * B * V * esz + B * W * 4
     traffic_ok = (args.config == MEASURED_TRAFFIC["config"] and args.pruning == 1 and args.walk_mode == 2
                   and kernel_sources_digest() == MEASURED_TRAFFIC["kernel_sources_sha256"])
     kname = KERNEL_OF_MODE[args.walk_mode]
@@ -402,12 +413,15 @@ def main():
                                     "a decode loop that samples from the masked logits cannot do that"},
         "warm_automaton": {"ms_per_step": warm["total"] / K * 1e3, "value": B * V * K / warm["total"], "p50_mask_apply_latency_us": pct(warm["lat"], 0.5) * 1e6,
                            "note": "the same steps once more without clearing the persistent automaton: every transition is a look-up"},
-        "kernel_ms": {k: statistics.fmean(v) for k, v in kern.items()},
-        "kernel_ms_p50": {k: pct(v, 0.5) for k, v in kern.items()},
-        "kernel_ms_max": {k: max(v) for k, v in kern.items()},
+        "kernel_ms": {k: statistics.fmean(v) for k, v in kern.items() if v},
+        "kernel_ms_p50": {k: pct(v, 0.5) for k, v in kern.items() if v},
+        "kernel_ms_max": {k: max(v) for k, v in kern.items() if v},
+        "two_calls": {"value": B * V * K / two["total"], "ms_per_step": two["total"] / K * 1e3, "p50_mask_apply_latency_us": pct(two["lat"], 0.5) * 1e6,
+                      "kernel_ms": {k: statistics.fmean(v) for k, v in two_prof["kern"].items() if v},
+                      "note": "the same steps through zf_compute_mask_async + zf_apply_mask: the mask kernel, then apply_mask_vec_kernel"},
         "overflow_chunks_per_step": rep["overflow"] / K,
-        "undecided_strings_per_step" if args.walk_mode != 1 else "walk_chunks_per_step": queued / K,
-        "undecided_strings_per_s": queued / max(sum(kern["main"]) * 1e-3, 1e-12),
+        ("undecided_tokens_per_step" if args.walk_mode == 2 and args.pruning else "undecided_strings_per_step") if args.walk_mode != 1 else "walk_chunks_per_step": queued / K,
+        "undecided_per_s": queued / max(sum(kern["main"]) * 1e-3, 1e-12),
         "earley_steps_per_launch": rep["steps"] / K,
         "token_mask_cache_rows_per_step": crows / K,
         "upload_bytes_per_step": rep["upload_bytes"] / K,
@@ -420,8 +434,9 @@ def main():
         "roofline": {"bound": "hbm", "kernel": kname, "achieved": mask_bytes / (main_ms * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": mask_bytes / (main_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC["bytes_per_launch"] if traffic_ok else None, "algorithmic_bytes": mask_bytes,
-                     "note": "integer work: a table walk per undecided string; what bounds it is the chain of dependent memory round trips of a "
-                             "launch (row record, cache words, strings, table entries: each a microsecond from a cold L2), far below the HBM "
+                     "note": "one launch = the mask of every row and the masking of its logits; integer work (a table walk per undecided token), "
+                             "bounded by the chain of dependent memory round trips of a wavefront (row record, cache words, strings, table "
+                             "entries, logits: 0.3 to 1.5 us each) and by the Earley steps of launches that meet new states, far below the HBM "
                              "roof; the event pair also spans the dispatch gap before the kernel"},
         "roofline_issue": {"bound": "alu", "kernel": kname, "unit": "G wavefront instructions/s", "peak": ISSUE_PEAK_GINST, "instructions": insts,
                            "achieved": insts / (main_ms * 1e-3) / 1e9 if insts else None,

@@ -74,6 +74,7 @@ struct DeviceSide {
     zf_mask_report report{};
     uint32_t call_parity = 0;            // which of the two counter sets the next call uses
     bool profiling = false;
+    bool closing_kernel = true;          // the last call enqueued a kernel behind its mask kernel (closing kernel or gather)
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
 };
 
@@ -995,6 +996,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
     if (run_kernels && d->tab.n_chunks > 0) HIP_TRY(automaton ? launch_mask_automaton(a, stream) : launch_mask_walk(a, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));
+    d->closing_kernel = true;
     if (run_kernels) HIP_TRY(launch_finish(a, d->cus, stream));   // fallback pass (if anything was listed) + permutation; also hands the counters to the host and clears the next call's
     if (sc) HIP_TRY(launch_gather(a, stream));            // every row's finished mask from its pool slot to the caller's tensor
     if (prof) HIP_TRY(hipEventRecord(d->ev[3], stream));
@@ -1249,6 +1251,7 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
     if (n_imp) HIP_TRY(launch_store_import(a, (const uint32_t *)(base + off_imp), (uint32_t)n_imp, stream));
     const bool run_kernels = nb > 0;
     if (prof) HIP_TRY(hipEventRecord(d->ev[0], stream));
+    d->closing_kernel = sc;
     if (run_kernels) HIP_TRY(launch_mask_store(a, mini, stream));
     if (prof) HIP_TRY(hipEventRecord(d->ev[1], stream));
     if (sc) HIP_TRY(launch_gather(a, stream));
@@ -1372,7 +1375,8 @@ int zf_mask_wait(zf_engine *e, void *hip_stream) {
     if (d->pending && d->profiling) {
         (void)hipEventElapsedTime(&d->report.main_ms, d->ev[0], d->ev[1]);
         d->report.fallback_ms = 0.f;                      // the fallback pass is part of the closing kernel
-        (void)hipEventElapsedTime(&d->report.permute_ms, d->ev[1], d->ev[3]);
+        if (d->closing_kernel) (void)hipEventElapsedTime(&d->report.permute_ms, d->ev[1], d->ev[3]);
+        else d->report.permute_ms = 0.f;                  // the mask kernel was the call's only kernel
     }
     d->pending = 0;
     if (unresolved) forget_cached_masks(d);               // masks written by the failed call must not be served from the cache
