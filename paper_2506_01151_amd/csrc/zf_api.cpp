@@ -756,7 +756,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     HIP_TRY(hipSetDevice(d->device));
     if (d->pending >= (uint32_t)DeviceSide::N_SLOTS) return fail(ZF_ERR_INVALID_ARG, "too many asynchronous mask calls in flight: call zf_mask_wait");
     const uint32_t slot = d->next_slot;
-    HIP_TRY(hipEventSynchronize(d->stage_done[slot]));   // the slot's previous upload has left the staging buffer
+    if (d->pending) HIP_TRY(hipEventSynchronize(d->stage_done[slot]));   // the slot's previous upload has left the staging buffer (with no call in flight zf_mask_wait has seen to that)
     for (int b = 0; b < batch; b++)
         if (!states[b] || states[b]->eng != e) return fail(ZF_ERR_INVALID_ARG, "state " + std::to_string(b) + " is null or belongs to another engine");
     if (e->store_on && !noalloc && !per_block) return enqueue_store_impl(e, states, batch, d_mask, hip_stream, wait, slot);
