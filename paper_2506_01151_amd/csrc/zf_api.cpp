@@ -70,7 +70,29 @@ struct DeviceSide {
         bool active = false;
         uint32_t epoch = 0;
         std::vector<std::shared_ptr<StateLink>> st; std::vector<uint32_t> gen; std::vector<uint64_t> upto;
+        std::vector<uint64_t> hop;                   // per row: the (state, token) pair the kernel walks, to be noted with the state it reports; 0 = none
     } rec[N_SLOTS];
+    // Where a token leads from a state of the persistent automaton, as the mask kernel has reported it: (state << 32 | token + 1)
+    // -> state.  Names are stable while the store is not cleared, so a row that is fed a token in a state some row was fed it in
+    // before is sent with the state it arrives in and no bytes to walk.  Open addressing, exact keys, emptied with the store.
+    std::vector<uint64_t> hop_key; std::vector<uint32_t> hop_val;
+    uint32_t hop_used = 0, hop_epoch = 0;
+    static const uint32_t HOP_SLOTS = 1u << 16;
+    uint32_t hop_find(uint64_t key) const {          // 0 = unknown
+        if (hop_key.empty()) return 0;
+        for (uint32_t i = (uint32_t)((key * 0x9E3779B97F4A7C15ull) >> 48);; i = (i + 1) & (HOP_SLOTS - 1)) {
+            if (hop_key[i] == key) return hop_val[i];
+            if (hop_key[i] == 0) return 0;
+        }
+    }
+    void hop_note(uint64_t key, uint32_t val) {
+        if (hop_key.empty()) { hop_key.assign(HOP_SLOTS, 0); hop_val.assign(HOP_SLOTS, 0); }
+        if (hop_used >= HOP_SLOTS / 2) { std::fill(hop_key.begin(), hop_key.end(), 0); hop_used = 0; }
+        for (uint32_t i = (uint32_t)((key * 0x9E3779B97F4A7C15ull) >> 48);; i = (i + 1) & (HOP_SLOTS - 1)) {
+            if (hop_key[i] == key) return;
+            if (hop_key[i] == 0) { hop_key[i] = key; hop_val[i] = val; hop_used++; return; }
+        }
+    }
     zf_mask_report report{};
     uint32_t call_parity = 0;            // which of the two counter sets the next call uses
     bool profiling = false;
@@ -319,6 +341,7 @@ int feed_token_bytes(zf_state *s, const uint8_t *bytes, int64_t n) {
     if (s->eng->store_on) {                               // the device walks the same bytes at the next mask call
         for (int64_t i = 0; i < n; i++) s->pending.push_back(t.cls[bytes[i]]);
         s->fed_total += (uint64_t)n;
+        s->pending_token = -1;                            // zf_advance knows better
         if (s->pending.size() > (size_t)STORE_PENDING_MAX) {   // too far behind: the row comes in through its chart again
             s->pending.clear(); s->pending_base = s->fed_total; s->dev_id = 0; s->dev_epoch = 0;
         }
@@ -423,7 +446,7 @@ int zf_state_reset(zf_state *s) {
     c.set_off[1] = (uint32_t)w;
     s->items_created = 0; s->bytes_fed = 0;
     s->dev_id = STORE_ROOT_ID; s->dev_epoch = 0; s->generation++;
-    s->pending.clear(); s->pending_base = s->fed_total;
+    s->pending.clear(); s->pending_base = s->fed_total; s->pending_token = -1;
     return ZF_OK;
 }
 
@@ -445,7 +468,10 @@ int zf_advance(zf_state *s, int32_t token) {
     if (!s) return fail(ZF_ERR_INVALID_ARG, "null argument");
     const zf_engine *e = s->eng;
     if (token < 0 || token >= e->V) return fail(ZF_ERR_RANGE, "token id out of range");
-    return feed_token_bytes(s, e->voc_bytes.data() + e->voc_off[token], e->voc_off[token + 1] - e->voc_off[token]);
+    const bool fresh = s->pending.empty();
+    const int rc = feed_token_bytes(s, e->voc_bytes.data() + e->voc_off[token], e->voc_off[token + 1] - e->voc_off[token]);
+    if (rc == ZF_OK && fresh && !s->pending.empty()) s->pending_token = token;   // the device will walk exactly this token from the state it knows
+    return rc;
 }
 
 // Rows of a batch are independent (one state = one query).  A byte step of an ambiguous grammar
@@ -1080,7 +1106,8 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
     }
     DeviceSide::CallRecord &rec = d->rec[slot];
     rec.active = true; rec.epoch = d->store_epoch;
-    rec.st.assign(nb, std::shared_ptr<StateLink>()); rec.gen.assign(nb, 0); rec.upto.assign(nb, 0);
+    rec.st.assign(nb, std::shared_ptr<StateLink>()); rec.gen.assign(nb, 0); rec.upto.assign(nb, 0); rec.hop.assign(nb, 0);
+    if (d->hop_epoch != d->store_epoch) { if (d->hop_used) std::fill(d->hop_key.begin(), d->hop_key.end(), 0); d->hop_used = 0; d->hop_epoch = d->store_epoch; }
     uint32_t n_cache_rows = 0;
     static thread_local StoreMiniRows mini;               // short records: they travel in the kernel's argument block
     const bool use_mini = nb <= STORE_MINI_ROWS;
@@ -1110,6 +1137,12 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
             const bool known = st->dev_id == STORE_ROOT_ID || (st->dev_id != 0 && st->dev_epoch == d->store_epoch);
             if (known) {
                 sr.start = st->dev_id; sr.n_pending = (uint32_t)st->pending.size(); sr.pend_off = pe_at;
+                if (sr.n_pending && st->pending_token >= 0 && st->dev_id != 0xFFFFFFFDu) {
+                    const uint64_t key = (uint64_t)st->dev_id << 32 | ((uint32_t)st->pending_token + 1u);
+                    const uint32_t to = d->hop_find(key);
+                    if (to) { sr.start = to; sr.n_pending = 0; }           // somebody has walked this token from this state before
+                    else rec.hop[r] = key;
+                }
                 if (sr.n_pending) memcpy(pend + pe_at, st->pending.data(), sr.n_pending);
                 if (sr.n_pending <= (uint32_t)STORE_ROW_PEND) memcpy(sr.pend, st->pending.data(), sr.n_pending);
                 pe_at += sr.n_pending;
@@ -1191,16 +1224,16 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
         // Blocks per row.  A wavefront takes the row's mask words in segments (16 words = 512 tokens, fewer for rows most of
         // whose tokens are undecided, so that a segment holds about one batch) and the undecided tokens among them 64 at a
         // time; rows differ by orders of magnitude in how many tokens their token-mask cache rows leave undecided, which
-        // set-up counted per cache row.  A row gets blocks in proportion to segments / 4 + batches (a batch costs about four
-        // times what an empty segment does), at least one, at most one wavefront per segment; all rows together about what
-        // the chip holds at once.
-        const int budget = std::max(nb, STORE_BLOCKS_PER_CU * std::max(1, d->cus));
+        // set-up counted per cache row.  The grid is never larger than what the chip holds at once: a block that had to wait
+        // for a place would start from nothing (LDS cache, the row's state) when the others are nearly done, which costs more
+        // than a few more passes of the wavefronts that are there.
+        const int budget = std::max(nb, std::min(STORE_BLOCKS_PER_CU, store_blocks_per_cu(d->tab, d->mode, scratch)) * std::max(1, d->cus));
         if (!use_mini) {
             const int n_seg = (d->tab.W + STORE_SEG_WORDS - 1) / STORE_SEG_WORDS;
             a.store_uniform_parts = std::max(1, std::min(std::max(1, (n_seg + STORE_WAVES - 1) / STORE_WAVES), budget / nb));
         } else {
-            double weight[STORE_MINI_ROWS], sum = 0;
-            int segs[STORE_MINI_ROWS];
+            double cost[STORE_MINI_ROWS];
+            int segs[STORE_MINI_ROWS], parts[STORE_MINI_ROWS];
             for (int r = 0; r < nb; r++) {
                 const Chart &c = states[miss_rows[r]]->chart;
                 uint32_t ent[64];
@@ -1228,16 +1261,36 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
                 const uint32_t seg_words = (uint32_t)std::max(1.0, std::min<double>(STORE_SEG_WORDS_MAX, 48.0 * std::max(1, d->tab.V) / (32.0 * std::max(und, 1.0))));
                 segs[r] = (d->tab.W + (int)seg_words - 1) / (int)seg_words;
                 mini.r[r].meta |= (seg_words - 1) << 24;
-                // a segment that holds any undecided token costs at least one batch
-                weight[r] = segs[r] / 2.0 + std::max(std::min<double>(und, segs[r]), und / 64.0);
-                sum += weight[r];
+                // what a pass costs a wavefront (microseconds, measured): an empty segment 2.8, a segment with a batch 3.7, each further batch 3
+                const double per_seg = und / segs[r];
+                cost[r] = per_seg < 1.0 ? 2.8 + 0.9 * per_seg : 3.7 + 3.0 * std::max(0.0, per_seg / 64.0 - 0.75);
+            }
+            // Every wavefront of a row takes the same number of passes (a row is as slow as its slowest wavefront).  The
+            // smallest time T is looked for in which every row, taking as many passes as fit into T, leaves the grid within
+            // what the chip holds; rows are then given passes back while blocks are left.
+            int passes[STORE_MINI_ROWS];
+            auto blocks_for = [&](int r, int n_pass) { return std::max(1, (segs[r] + n_pass * STORE_WAVES - 1) / (n_pass * STORE_WAVES)); };
+            auto need = [&](double T) {
+                int tot = 0;
+                for (int r = 0; r < nb; r++) tot += blocks_for(r, std::max(1, (int)(T / cost[r])));
+                return tot;
+            };
+            double lo = cost[0];
+            for (int r = 1; r < nb; r++) lo = std::min(lo, cost[r]);
+            double hi = lo;
+            if (need(hi) > budget) {
+                while (need(hi) > budget && hi < 1e9) hi *= 2;
+                for (int it = 0; it < 20; it++) { const double mid = 0.5 * (lo + hi); if (need(mid) <= budget) hi = mid; else lo = mid; }
+            }
+            int all = 0;
+            for (int r = 0; r < nb; r++) { passes[r] = std::max(1, (int)(hi / cost[r])); parts[r] = blocks_for(r, passes[r]); all += parts[r]; }
+            for (int r = 0; r < nb && all < budget; r++) {
+                if (passes[r] <= 1) continue;
+                const int p = blocks_for(r, passes[r] - 1);
+                if (p - parts[r] <= budget - all) { all += p - parts[r]; parts[r] = p; passes[r]--; }
             }
             uint32_t at = 0;
-            for (int r = 0; r < nb; r++) {
-                const int max_parts = std::max(1, (segs[r] + STORE_WAVES - 1) / STORE_WAVES);
-                a.store_first_block[r] = (uint16_t)at;
-                at += (uint32_t)std::min<double>(max_parts, std::max<double>((segs[r] + 2 * STORE_WAVES - 1) / (2 * STORE_WAVES), budget * weight[r] / sum));   // at most two segments per wavefront
-            }
+            for (int r = 0; r < nb; r++) { a.store_first_block[r] = (uint16_t)at; at += (uint32_t)parts[r]; }
             for (int r = nb; r < STORE_MINI_ROWS + 8; r++) a.store_first_block[r] = r == nb ? (uint16_t)at : (uint16_t)0xFFFF;   // the kernel compares against all of them
             a.store_uniform_parts = 0;
         }
@@ -1355,9 +1408,12 @@ int zf_mask_wait(zf_engine *e, void *hip_stream) {
             const uint32_t *out = d->h_row_out + (size_t)k * MAX_BATCH;
             for (size_t r = 0; r < rec.st.size() && good; r++) {
                 zf_state *s = rec.st[r] ? rec.st[r]->s : nullptr;
-                if (!s || s->generation != rec.gen[r] || out[r] == 0 || (out[r] >= d->store.cap_states && out[r] != 0xFFFFFFFDu)) continue;
+                if (out[r] == 0 || (out[r] >= d->store.cap_states && out[r] != 0xFFFFFFFDu)) continue;
+                if (rec.hop[r]) d->hop_note(rec.hop[r], out[r]);          // a fact about the automaton, whatever has become of the row
+                if (!s || s->generation != rec.gen[r]) continue;
                 if (rec.upto[r] < s->pending_base) continue;              // a later call's result is already in
                 const size_t drop = std::min<size_t>((size_t)(rec.upto[r] - s->pending_base), s->pending.size());
+                s->pending_token = -1;
                 s->pending.erase(s->pending.begin(), s->pending.begin() + drop);
                 s->pending_base = rec.upto[r];
                 s->dev_id = out[r]; s->dev_epoch = rec.epoch;

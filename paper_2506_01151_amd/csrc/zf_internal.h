@@ -124,4 +124,5 @@ struct zf_state {
     std::vector<uint8_t> pending;
     uint64_t fed_total = 0;             // bytes fed since the state was made; pending covers [pending_base, fed_total)
     uint64_t pending_base = 0;
+    int32_t pending_token = -1;         // the token whose bytes are all of `pending`, fed in state dev_id; -1 when pending is anything else
 };

@@ -149,10 +149,15 @@ __device__ __forceinline__ void hand_over(const MaskArgs &a, uint32_t lin, uint3
         else if (k >= 5 && k < 8 && a.store.ctl) x = __hip_atomic_load(&a.store.ctl[k - 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (k == 1) x += part;
     }
+    // persistent automaton: where every row of the call stands now (the first round of these loads travels with the counters')
+    uint32_t row0 = 0;
+    if (a.store_row_dev && k < (uint32_t)a.batch) row0 = __hip_atomic_load(&a.store_row_dev[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();                                         // the ticket words have been read: now the next call's set is cleared (it may be this very set's neighbour only, never this set)
     for (uint32_t i = threadIdx.x; i < (uint32_t)COUNTER_SET_WORDS; i += blockDim.x) a.counters_next[i] = 0;   // the next call's set (no separate memset)
-    if (a.store_row_dev)                                     // persistent automaton: where every row of the call stands now
-        for (uint32_t i = threadIdx.x; i < (uint32_t)a.batch; i += blockDim.x) a.store_row_out[i] = __hip_atomic_load(&a.store_row_dev[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (a.store_row_dev) {
+        if (k < (uint32_t)a.batch) a.store_row_out[k] = row0;
+        for (uint32_t i = k + blockDim.x; i < (uint32_t)a.batch; i += blockDim.x) a.store_row_out[i] = __hip_atomic_load(&a.store_row_dev[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     __syncthreads();                                         // ... before the first wavefront's release below
     if (k < 64) {                                            // counters first, then the word the host waits for
         if (k < 4 || (k >= 5 && k < 8 && a.store.ctl)) a.host_status[k] = x;

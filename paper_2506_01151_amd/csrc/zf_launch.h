@@ -58,7 +58,7 @@ static const int STORE_LC_BITS = ZF_STORE_LC_BITS;       // log2 of the entries 
 #ifndef ZF_STORE_BLOCKS_PER_CU
 #define ZF_STORE_BLOCKS_PER_CU 3
 #endif
-static const int STORE_BLOCKS_PER_CU = ZF_STORE_BLOCKS_PER_CU;   // blocks per compute unit the grid aims at (the chip should hold them all at once)
+static const int STORE_BLOCKS_PER_CU = ZF_STORE_BLOCKS_PER_CU;   // blocks per compute unit the grid is made of at most (fewer when a compute unit holds fewer at once)
 static const int STORE_PENDING_LDS = 256;       // pending bytes of a row a block keeps in LDS (more are read from the upload)
 static const int STORE_PENDING_MAX = 4096;      // beyond this many bytes since its state was last known a row comes in through its chart again
 static const uint32_t STORE_ROW_CACHE = 1u;     // StoreRow::flags: the token-mask cache rows of the row are listed
@@ -182,6 +182,7 @@ uint32_t automaton_lds_bytes(const DeviceTables &t, int mode, int states, int ar
 hipError_t launch_mask_automaton(const MaskArgs &a, hipStream_t s);
 hipError_t prepare_store_kernels();
 uint32_t store_lds_bytes(const DeviceTables &t, int mode, int scratch);
+int store_blocks_per_cu(const DeviceTables &t, int mode, int scratch);
 hipError_t launch_mask_store(const MaskArgs &a, const StoreMiniRows &mini, hipStream_t s);
 hipError_t launch_store_clear(const StoreView &G, uint32_t ncls, const void *root_items, uint32_t n_root, hipStream_t s);
 hipError_t launch_store_import(const MaskArgs &a, const uint32_t *import_rows, uint32_t n_import, hipStream_t s);

@@ -230,6 +230,14 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
     const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const uint32_t W = (uint32_t)D.W, ncls = (uint32_t)D.n_cls;
     if (tid == 0) block_undecided = 0;
+    // LDS: the cache of table entries and the staging flag come first, at offsets that do not depend on the kernel's arguments:
+    // they are cleared while the arguments are still on their way
+    unsigned long long *lc = reinterpret_cast<unsigned long long *>(smem);
+    uint32_t *ctl = reinterpret_cast<uint32_t *>(smem + LC_ENTRIES * 8);   // [4] state of the staged tables
+    uint8_t *const tables_at = smem + LC_ENTRIES * 8 + 32;
+    for (uint32_t k = tid; k < LC_ENTRIES; k += STORE_BLOCK) lc[k] = LC_EMPTY;
+    if (tid == 0) ctl[4] = 0;
+    __syncthreads();
     // Grid (blocks of the row that has most, rows): the row's record -- with the number of blocks the row really has -- is
     // the first thing read, from the kernel's argument block when the call has few enough rows (one read; a block beyond its
     // row's count leaves at once).
@@ -269,21 +277,16 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
     }
     if (spilled) rec = lane < sizeof(StoreRow) / 4 ? reinterpret_cast<const uint32_t *>(a.store_rows + row)[lane] : 0u;
     TV T;
-    uint32_t off = table_view<MODE>(D, smem, T);
+    uint32_t off = table_view<MODE>(D, tables_at, T);
     const uint32_t n16 = off / 16;
-    uint8_t *l_rep = smem + off; off += 256;
-    unsigned long long *lc = reinterpret_cast<unsigned long long *>(smem + off); off += LC_ENTRIES * 8;
-    uint32_t *ctl = reinterpret_cast<uint32_t *>(smem + off); off += 32;   // [4] state of the staged tables
-    uint32_t *vbuf = reinterpret_cast<uint32_t *>(smem + off) + wave * 64; off += STORE_WAVES * 64 * 4;   // per wavefront: verdicts of the pass's words
-    const Staging stg{ctl, smem, D.table_blob, n16, l_rep, D.cls_rep, ncls, a.aut_wide != 0};
+    uint8_t *l_rep = tables_at + off; off += 256;
+    uint32_t *vbuf = reinterpret_cast<uint32_t *>(tables_at + off) + wave * 64; off += STORE_WAVES * 64 * 4;   // per wavefront: verdicts of the pass's words
+    const Staging stg{ctl, tables_at, D.table_blob, n16, l_rep, D.cls_rep, ncls, a.aut_wide != 0};
     Scratch sc;
     sc.cap = (uint32_t)a.aut_scratch;
-    sc.w = reinterpret_cast<uint32_t *>(smem + off) + (size_t)wave * (2 * sc.cap + aut_hash_places(sc.cap));
+    sc.w = reinterpret_cast<uint32_t *>(tables_at + off) + (size_t)wave * (2 * sc.cap + aut_hash_places(sc.cap));
     sc.o = sc.w + sc.cap;
     sc.h = sc.o + sc.cap;
-    for (uint32_t k = tid; k < LC_ENTRIES; k += STORE_BLOCK) lc[k] = LC_EMPTY;
-    if (tid == 0) ctl[4] = 0;
-    __syncthreads();
     if (unit < n_seg || unit == 0) {
     auto field = [&](uint32_t k) { return (uint32_t)__builtin_amdgcn_readlane((int)rec, (int)k); };
     const uint32_t flags = field(5), n_pending = field(1), pend_off = field(2), n_ent = field(3), ent_off = field(4);
@@ -319,6 +322,25 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
     if (n_pending && start_ok && pending(0) < ncls) hop0 = __hip_atomic_load(&G.trans[start * ncls + pending(0)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
     uint32_t v = 0, c = 0;
     request(unit, v, c);
+    // The logits of a segment (when the call masks them too): 16-byte pieces, the first two of every lane requested one pass
+    // ahead (those of the first segment here), so that they wait in registers when the segment's verdicts are in.
+    const uint32_t tp = a.apply_dtype ? 8u : 4u, esz = a.apply_dtype ? 2u : 4u;   // tokens per 16-byte piece, bytes per logit
+    auto logits_of = [&](uint32_t g, uint32_t &pieces, size_t &at) {
+        const uint32_t tok0 = g * sw * 32u;
+        const uint32_t n_tok = a.apply_out && g < n_seg && tok0 < (uint32_t)D.V ? (sw * 32u < (uint32_t)D.V - tok0 ? sw * 32u : (uint32_t)D.V - tok0) : 0u;
+        pieces = n_tok / tp;
+        at = ((size_t)row * (size_t)a.apply_stride + tok0) * esz;
+    };
+    auto logits_ahead = [&](uint32_t g, u32x4 (&pre)[2]) {
+        uint32_t pieces;
+        size_t at;
+        logits_of(g, pieces, at);
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint8_t *>(a.apply_logits) + at);
+#pragma unroll
+        for (int u = 0; u < 2; u++) { pre[u] = u32x4{0, 0, 0, 0}; if ((uint32_t)u * 64u + lane < pieces) pre[u] = __builtin_nontemporal_load(src + (uint32_t)u * 64u + lane); }
+    };
+    u32x4 l_pre[2];
+    logits_ahead(unit, l_pre);
     auto find_root = [&]() {
         // ---- the row's current state: walk the bytes fed since `start` was its state (the loads above are in flight) ----
         uint32_t s = start;
@@ -353,19 +375,32 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
                     // the states this row leads to, each once: the wavefront's share of them is warmed in turn
                     if (st == root) {
                         unsigned long long todo = __ballot(cl < ncls && t < AT_FAIL && t != root);
-                        uint32_t n_done = 0;
+                        constexpr int SHARE = (STORE_WARM_ROWS + STORE_WAVES - 1) / STORE_WAVES;
+                        uint32_t mine[SHARE], n_mine = 0, n_done = 0;
+#pragma unroll
+                        for (int k = 0; k < SHARE; k++) mine[k] = 0;
                         while (todo && n_done < (uint32_t)STORE_WARM_ROWS) {
                             const int l = __ffsll((long long)todo) - 1;
                             const uint32_t nx = (uint32_t)__builtin_amdgcn_readlane((int)t, l);
                             todo &= ~__ballot(t == nx);
                             if (n_done % STORE_WAVES == wave && ncls <= 64u) {
-                                const uint32_t k2 = nx * ncls + lane;
-                                uint32_t t2 = AT_NONE;
-                                if (lane < ncls) t2 = __hip_atomic_load(&G.trans[k2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-                                if (lane < ncls && t_final(t2) && t2 != AT_FAIL)
-                                    __hip_atomic_store(&lc[(k2 * 0x9E3779B1u) >> (32 - LC_BITS)], ((unsigned long long)k2 << 32) | t2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+#pragma unroll
+                                for (int k = 0; k < SHARE; k++) mine[k] = n_mine == (uint32_t)k ? nx : mine[k];
+                                n_mine++;
                             }
                             n_done++;
+                        }
+                        uint32_t t2[SHARE];                  // the rows' loads travel together
+#pragma unroll
+                        for (int k = 0; k < SHARE; k++) {
+                            t2[k] = AT_NONE;
+                            if ((uint32_t)k < n_mine && lane < ncls) t2[k] = __hip_atomic_load(&G.trans[mine[k] * ncls + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                        }
+#pragma unroll
+                        for (int k = 0; k < SHARE; k++) {
+                            const uint32_t k2 = mine[k] * ncls + lane;
+                            if ((uint32_t)k < n_mine && lane < ncls && t_final(t2[k]) && t2[k] != AT_FAIL)
+                                __hip_atomic_store(&lc[(k2 * 0x9E3779B1u) >> (32 - LC_BITS)], ((unsigned long long)k2 << 32) | t2[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                         }
                     }
                 }
@@ -407,17 +442,12 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
         const uint32_t w = slot16 < sw && g < n_seg ? g * sw + slot16 : 0xFFFFFFFFu;
         uint32_t vn = 0, cn = 0;
         request(g + n_units, vn, cn);                        // the next segment's words travel while this one's tokens are checked
-        // the segment's logits (when the call masks them too): the first two pieces of every lane are requested now and
-        // wait in registers until the verdicts are in
-        const uint32_t tp = a.apply_dtype ? 8u : 4u, esz = a.apply_dtype ? 2u : 4u;   // tokens per 16-byte piece, bytes per logit
-        const uint32_t tok0 = g * sw * 32u;
-        const uint32_t n_tok = a.apply_out && g < n_seg && tok0 < (uint32_t)D.V ? (sw * 32u < (uint32_t)D.V - tok0 ? sw * 32u : (uint32_t)D.V - tok0) : 0u;
-        const uint32_t pieces = n_tok / tp;
-        const size_t l_at = ((size_t)row * (size_t)a.apply_stride + tok0) * esz;
+        u32x4 l_nxt[2];
+        logits_ahead(g + n_units, l_nxt);                    // and so do its logits
+        uint32_t pieces;
+        size_t l_at;
+        logits_of(g, pieces, l_at);
         const u32x4 *l_src = reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint8_t *>(a.apply_logits) + l_at);
-        u32x4 l_pre[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
-#pragma unroll
-        for (int u = 0; u < 2; u++) if ((uint32_t)u * 64u + lane < pieces) l_pre[u] = __builtin_nontemporal_load(l_src + (uint32_t)u * 64u + lane);
         if (slots_log2 <= 4u) { v |= __shfl_xor(v, 16); c |= __shfl_xor(c, 16); }
         if (slots_log2 <= 5u) { v |= __shfl_xor(v, 32); c |= __shfl_xor(c, 32); }
         want = c & ~v;
@@ -527,6 +557,7 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
             }
         }
         v = vn; c = cn;
+        l_pre[0] = l_nxt[0]; l_pre[1] = l_nxt[1];
     }
     if (lane == 0 && steps) atomicAdd(&a.counters[3], steps);
     if (lane == 0 && undecided) atomicAdd(&block_undecided, undecided);   // LDS: the block's sum travels with its ticket
@@ -585,6 +616,24 @@ hipError_t prepare_store_kernels() {
 uint32_t store_lds_bytes(const DeviceTables &t, int mode, int scratch) {
     return table_bytes(t, mode) + 256 + LC_ENTRIES * 8 + 32 + STORE_WAVES * 64 * 4 +
            STORE_WAVES * ((uint32_t)scratch * 8 + aut_hash_places((uint32_t)scratch) * 4);
+}
+
+// Blocks of the kernel one compute unit holds at once (registers and the LDS the call asks for decide); asked of the runtime once
+// per LDS size.
+int store_blocks_per_cu(const DeviceTables &t, int mode, int scratch) {
+    static thread_local uint32_t known_lds[3] = {0, 0, 0};
+    static thread_local int known[3] = {0, 0, 0};
+    const uint32_t lds = store_lds_bytes(t, mode, scratch);
+    const int m = mode < 0 ? 0 : (mode > 2 ? 2 : mode);
+    if (known[m] && known_lds[m] == lds) return known[m];
+    int n = 0;
+    hipError_t e;
+    if (m == 0) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, mask_store_kernel<0>, STORE_BLOCK, lds);
+    else if (m == 1) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, mask_store_kernel<1>, STORE_BLOCK, lds);
+    else e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, mask_store_kernel<2>, STORE_BLOCK, lds);
+    if (e != hipSuccess || n < 1) { (void)hipGetLastError(); n = 1; }
+    known[m] = n; known_lds[m] = lds;
+    return n;
 }
 
 hipError_t launch_mask_store(const MaskArgs &a, const StoreMiniRows &mini, hipStream_t s) {
