@@ -215,6 +215,67 @@ def test_config5_full_batch_pruning_on_and_off(pruning, mode, torch_cuda, oracle
     assert len(pairs) >= 40
 
 
+LONG5 = [  # pruning, mask kernel, sentences with one long sum at the top level, compare every
+    (True, "store", True, 8),
+    (True, "store", False, 8),
+    (True, "automaton", False, 16),
+    (True, "trie-walk", False, 32),
+    (False, "automaton", False, 32),
+]
+
+
+@pytest.mark.parametrize("pruning,mode,flat,every", LONG5, ids=[f"{'pruned' if p else 'unpruned'}-{m}-{'long-sums' if f else 'nested-groups'}" for p, m, f, _ in LONG5])
+def test_config5_all_1024_steps_against_the_language_description(pruning, mode, flat, every, torch_cuda, oracle_lib):
+    """Configuration 5 at its stated shape to its last decode step: 64 rows x 1,024 steps, V = 152,064.  The oracle-sampled
+    trajectory ends at step 296 (the oracle keeps every Earley set of an ambiguous grammar: a mask at step 1,000 costs it
+    minutes), so the rows here follow seeded sentences of the expression language cut into vocabulary tokens (valid by
+    construction, workloads/sentences.py), and the masks of ALL 64 rows are compared, at every `every`-th step and at the last
+    one, with the description of the language's viable prefixes in tests/expr_language.py, which the Earley oracle pins on short
+    prefixes (tests/test_oracle_pins.py) and, here, on two rows at the full vocabulary during the first steps.  Two shapes of
+    sentence: one long sum at the top level (every operator is another way to split it: even the pruned chart reaches 20,000
+    items, which only the persistent automaton's kernel is asked to take), and nested groups of two to four operands (pruned
+    charts of tens of items against 9,000 unpruned: every mask kernel, pruning on and off)."""
+    import paper_2506_01151_amd as zf
+    from tests.expr_language import ExprLanguage, ExprRow
+    from workloads.sentences import expr_sentence, cut_into_tokens
+    torch = torch_cuda
+    cfg = configs.CONFIGS[5]
+    toks = cfg.vocab()
+    off, data = wvocab.vocab_csr(toks)
+    rows, steps = cfg.batch, cfg.steps
+    seqs = [cut_into_tokens(toks, expr_sentence(cfg.seed, f"sentence[{b}]", 4 * steps + 64, flat=flat), steps) for b in range(rows)]
+    assert all(len(q) == steps for q in seqs)
+    lang = ExprLanguage(toks)
+    want_rows = [ExprRow() for _ in range(rows)]
+    eng = zf.Engine(cfg.grammar(), toks, device=0, pruning=pruning, state_cache_entries=-1, walk_mode=MODES[mode])
+    ss = zf.StateBatch([eng.new_state() for _ in range(rows)])
+    orc = oracle_lib.Oracle(cfg.grammar())
+    so = {b: orc.new_state() for b in (3, 40)}
+    d_mask = torch.empty((rows, eng.W), dtype=torch.int32, device="cuda")
+    n_checked = 0
+    for step in range(steps):
+        ids = [seqs[b][step] for b in range(rows)]
+        for b in range(rows):
+            assert want_rows[b].feed(toks[ids[b]]), (step, b)
+        ss.advance(ids)
+        if step < 24:
+            for b, s in so.items():
+                assert s.feed_bytes(toks[ids[b]])
+        if step % every == every - 1 or step == steps - 1 or step in (0, 5, 23):
+            d_mask.fill_(-1)
+            zf.compute_mask(eng, ss, d_mask)
+            got = d_mask.cpu().numpy().view(np.uint32)
+            for b in range(rows):
+                assert (got[b] == lang.mask(want_rows[b].mode, want_rows[b].depth)).all(), f"cfg5 step {step} row {b}"
+                assert ss[b].accepting() == want_rows[b].accepting(), f"cfg5 step {step} row {b} accepting"
+            if step in (0, 5, 23):
+                for b, s in so.items():
+                    assert (got[b] == s.mask(off, data, 16)).all(), f"cfg5 oracle step {step} row {b}"
+            n_checked += rows
+    print(f"config 5 {'pruned' if pruning else 'unpruned'} {mode}: {steps} steps x {rows} rows, {n_checked} masks compared")
+    assert n_checked >= rows * (steps // every)
+
+
 STATE_CACHE = [  # config, rows, steps, compare every, cache rows (0 = default), expect the cache to be used
     (3, 16, 512, 29, 0, True),
     (3, 16, 512, 41, 32, True),     # the smallest cache a batch of 16 may use: constant eviction

@@ -465,3 +465,56 @@ def test_apply_mask_closed_form(dtype, neg_inf, oracle_lib):
         assert np.isneginf(np.array([neg_inf], dtype=np.uint32).view(np.float32))[0]
     else:
         assert np.isneginf((np.array([neg_inf], dtype=np.uint32) << 16).view(np.float32))[0]
+
+
+# ---------------------------------------------------------------------------------------
+# the description of configuration 5's language that the full-length GPU test compares with (tests/expr_language.py)
+def test_expr_language_description_against_the_oracle(oracle_lib):
+    """tests/expr_language.py states the viable prefixes of E -> E+E | E*E | (E) | num | id directly (operands and operators
+    alternate, parentheses balance).  Here the Earley oracle pins it: equal masks and equal `accepting` at every step of
+    seeded sentences cut into tokens of configuration 5's vocabulary, and along the first steps of the oracle-sampled
+    trajectory of configuration 5 (tokens drawn from the oracle's own masks: nested parentheses, odd token boundaries),
+    every token of which the description must accept."""
+    from tests.expr_language import ExprLanguage, ExprRow
+    from tests.helpers import load_trajectory
+    from workloads import configs
+    from workloads.sentences import expr_sentence, cut_into_tokens
+    cfg = configs.CONFIGS[5]
+    o = Oracle(cfg.grammar())
+    toks = cfg.vocab(8192)
+    off, data = wvocab.vocab_csr(toks)
+    lang = ExprLanguage(toks)
+    for r in range(8):
+        ids = cut_into_tokens(toks, expr_sentence(cfg.seed, f"pin[{r}]", 240, max_depth=3 + r), 70)
+        s, row = o.new_state(), ExprRow()
+        assert (s.mask(off, data, 8) == lang.mask(row.mode, row.depth)).all()
+        for k, i in enumerate(ids):
+            assert s.feed_bytes(toks[i]) and row.feed(toks[i]), (r, k)
+            assert (s.mask(off, data, 8) == lang.mask(row.mode, row.depth)).all(), (r, k)
+            assert s.accepting() == row.accepting(), (r, k)
+        for bad in (b")" * (row.depth + 1), b"+*", b"1a", b"a1", b"A", b"()", b" "):      # and a few that must not follow
+            t = o.new_state()
+            assert t.feed_bytes(b"".join(toks[i] for i in ids))
+            assert t.feed_bytes(bad) == ExprRow.feed(_copy_row(row), bad) == False, (r, bad)
+    full = cfg.vocab()
+    traj = load_trajectory(5, 6, 48)
+    foff, fdata = wvocab.vocab_csr(full)
+    flang = ExprLanguage(full)
+    for b in range(6):
+        s, row = o.new_state(), ExprRow()
+        for k, ids in enumerate(traj):
+            t = ids[b]
+            if t < 0:
+                s, row = o.new_state(), ExprRow()
+                continue
+            assert s.feed_bytes(full[t]) and row.feed(full[t]), (b, k)
+            assert s.accepting() == row.accepting()
+            if k % 12 == 11:
+                assert (s.mask(foff, fdata, 8) == flang.mask(row.mode, row.depth)).all(), (b, k)
+
+
+def _copy_row(row):
+    from tests.expr_language import ExprRow
+    c = ExprRow()
+    c.mode, c.depth = row.mode, row.depth
+    return c
