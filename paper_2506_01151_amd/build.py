@@ -10,7 +10,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libzapformat.so")
 SOURCES = ["zf_regex.cpp", "zf_compile.cpp", "zf_earley.cpp", "zf_automaton.cpp", "zf_api.cpp", "zf_kernels.hip", "zf_mask_walk.hip",
            "zf_mask_automaton.hip", "zf_mask_store.hip", "zf_scratch.hip"]
-HEADERS = ["zf_device.h", "zf_internal.h", "zf_launch.h", "zf_kernel_common.h", "zf_aut_step.h"]
+HEADERS = ["zf_device.h", "zf_internal.h", "zf_launch.h", "zf_kernel_common.h", "zf_aut_step.h", "zf_host_automaton.h"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]
 # hipcc's host pass warns once per translation unit that it does not know the packed-fp32

@@ -13,6 +13,7 @@
 #include <thread>
 #include <unordered_map>
 #include "zf_internal.h"
+#include "zf_host_automaton.h"
 #include "zf_launch.h"
 
 using namespace zf;
@@ -20,6 +21,26 @@ using namespace zf;
 namespace zf {
 static thread_local std::string g_err;
 void set_error(const std::string &m) { g_err = m; }
+// Bring the state's chart up to date: the bytes fed through the host automaton since it last was, one zf_advance call at
+// a time (Scan -> Complete -> Compact -> Predict, as feed_token_bytes does without the automaton).
+static void catch_up(zf_state *s) {
+    if (s->lag.empty()) return;
+    const Tables &t = s->eng->tab;
+    Chart &c = s->chart;
+    int64_t created = 0;
+    size_t at = 0;
+    for (uint32_t cut : s->lag_cut) {
+        for (; at < cut; at++) (void)earley_step(t, c, s->lag[at], false, &created);
+        chart_compact(t, c);
+    }
+    s->items_created += created;
+    s->lag.clear(); s->lag_cut.clear();
+}
+const Chart &chart_of(const zf_state *s) {
+    catch_up(const_cast<zf_state *>(s));
+    return s->chart;
+}
+
 }  // namespace zf
 
 // Device-side resources of an engine.
@@ -302,12 +323,12 @@ int setup_device(zf_engine *e) {
 
 // Rows of the token-mask cache that the items of the current set select: the DFA state of an
 // item that stands inside (or before) a terminal, Q + Y for an item that waits for nonterminal Y.
-uint32_t current_set_entries(const Tables &t, const Chart &c, uint32_t *out) {
+uint32_t current_set_entries(const Tables &t, const Item *items, uint32_t n_items, uint32_t *out) {
     uint32_t n = 0;
-    for (uint32_t i = c.set_off[c.n_sets() - 1]; i < c.set_off[c.n_sets()]; i++) {
-        uint16_t code = t.sym[c.items[i].p];
+    for (uint32_t i = 0; i < n_items; i++) {
+        uint16_t code = t.sym[items[i].p];
         uint32_t row;
-        if ((code >> SYM_KIND_SHIFT) == SYM_TERM) row = c.items[i].q;
+        if ((code >> SYM_KIND_SHIFT) == SYM_TERM) row = items[i].q;
         else if ((code >> SYM_KIND_SHIFT) == SYM_NT) row = (uint32_t)t.Q + (code & SYM_ID_MASK_NT);
         else continue;
         bool dup = false;
@@ -316,28 +337,125 @@ uint32_t current_set_entries(const Tables &t, const Chart &c, uint32_t *out) {
     }
     return n;
 }
+uint32_t current_set_entries(const Tables &t, const Chart &c, uint32_t *out) {
+    const uint32_t lo = c.set_off[c.n_sets() - 1];
+    return current_set_entries(t, c.items.data() + lo, c.set_off[c.n_sets()] - lo, out);
+}
+
+static const size_t HOST_LAG_MAX = 1u << 16;          // bytes a chart may lag behind before it is brought up to date anyway
+static const int64_t HOST_AUT_ITEMS_MAX = 1 << 25;    // the host automaton is emptied when it is full or holds more items than this
+
+// The state's place in the host automaton (the caller holds the engine's lock).
+uint32_t host_place(zf_state *s) {
+    zf_engine *e = s->eng;
+    if (s->host_id == HostAutomaton::ROOT || s->host_id_epoch == e->host_epoch) return s->host_id;
+    const uint32_t at = e->host_aut->import(chart_of(s));   // the automaton was emptied since: the chart says where the state stands
+    if (at == 0) return 0;                             // no room
+    s->host_id = at; s->host_id_epoch = e->host_epoch;
+    return s->host_id;
+}
+
+// The items of the state's current set and the size of the largest set its chart holds -- from the host automaton when the
+// engine has one (the caller holds its lock; the chart may lag behind), else from the chart.
+struct CurrentSet { const Item *items; uint32_t n, biggest; };
+CurrentSet current_set(zf_state *s) {
+    zf_engine *e = s->eng;
+    if (e->host_aut) {
+        const uint32_t at = host_place(s);
+        if (at == HostAutomaton::SINK) return CurrentSet{nullptr, 0, 0};
+        if (at == 0) {                                     // the automaton has no room for the state's chart: the chart itself, then
+            const Chart &c = chart_of(s);
+            uint32_t biggest = 0;
+            for (uint32_t k = 0; k < c.n_sets(); k++) biggest = std::max(biggest, c.set_off[k + 1] - c.set_off[k]);
+            const uint32_t lo = c.set_off[c.n_sets() - 1];
+            return CurrentSet{c.items.data() + lo, c.set_off[c.n_sets()] - lo, biggest};
+        }
+        const HostAutomaton &A = *e->host_aut;
+        const HostAutomaton::State &hs = A.st(at);
+        return CurrentSet{hs.items.data(), (uint32_t)hs.items.size(), hs.widest};
+    }
+    const Chart &c = s->chart;
+    uint32_t biggest = 0;
+    for (uint32_t k = 0; k < c.n_sets(); k++) biggest = std::max(biggest, c.set_off[k + 1] - c.set_off[k]);
+    const uint32_t lo = c.set_off[c.n_sets() - 1];
+    return CurrentSet{c.items.data() + lo, c.set_off[c.n_sets()] - lo, biggest};
+}
 
 int feed_token_bytes(zf_state *s, const uint8_t *bytes, int64_t n) {
     if (n <= 0) return fail(ZF_ERR_REJECTED, "an empty token is never allowed");
     const Tables &t = s->eng->tab;
     const bool pruning = s->eng->opt.pruning != 0;
-    Chart &c = s->chart;
-    const uint32_t keep = c.n_sets();
-    int64_t created = 0;
-    bool accepted = false;
-    for (int64_t i = 0; i < n; i++) {
-        StepResult r = earley_step(t, c, bytes[i], !pruning, &created);
-        accepted = r.accepted;
-        // a byte is rejected when its set is empty; a completed sentence that cannot be extended
-        // is still fine as the last byte
-        if (!r.alive || (!r.kernel_nonempty && i + 1 < n)) {
-            c.truncate(keep);
-            return fail(ZF_ERR_REJECTED, "byte " + std::to_string(i) + " of the input cannot extend the prefix");
+    if (s->eng->host_aut) {
+        // Through the host automaton: a look-up per byte once the transition is known (Sections 4.4, 5.2: nothing is parsed
+        // twice), an Earley byte step the first time -- run on a private copy of the sets it reads, without the lock, so
+        // that the rows of a batch can be fed by several threads.  All or nothing, as below.
+        zf_engine *e = s->eng;
+        HostAutomaton &A = *e->host_aut;
+        std::unique_lock<std::mutex> lk(e->host_mu);
+        while (A.full() || A.n_items > HOST_AUT_ITEMS_MAX) {   // start over; the states find their way back through their charts
+            if (e->host_walkers == 0) { A.clear(); e->host_epoch++; break; }
+            lk.unlock();                                  // somebody is at work on a transition (and waits for nobody): let them finish
+            std::this_thread::yield();
+            lk.lock();
         }
+        if (s->host_id != HostAutomaton::ROOT && s->host_id_epoch != e->host_epoch) {
+            lk.unlock();
+            const Chart &c = chart_of(s);                 // the automaton was emptied since: the chart says where the state stands
+            lk.lock();
+            const uint32_t at = A.import(c);
+            if (at == 0) return fail(ZF_ERR_OOM, "the chart is too large for the host automaton");
+            s->host_id = at; s->host_id_epoch = e->host_epoch;
+        }
+        const uint32_t epoch = e->host_epoch;             // cannot change while this thread is a walker or holds the lock
+        uint32_t at = s->host_id;
+        bool accepted = false;
+        for (int64_t i = 0; i < n; i++) {
+            if (at == HostAutomaton::SINK) at = HostAutomaton::DEAD;
+            else {
+                const int cl = t.cls[bytes[i]];
+                if (A.st(at).trans[cl] == HostAutomaton::NONE) {
+                    static thread_local HostAutomaton::Work w;
+                    e->host_walkers++;
+                    lk.unlock();
+                    A.lay_out(at, w);
+                    const StepResult r = earley_step(t, w.c, bytes[i], false, nullptr);
+                    lk.lock();
+                    e->host_walkers--;
+                    if (A.st(at).trans[cl] == HostAutomaton::NONE) A.record(at, cl, r, w);   // else somebody else has made it meanwhile
+                }
+                accepted = A.st(at).acc[cl] != 0;
+                at = A.st(at).trans[cl];
+            }
+            if (at == HostAutomaton::DEAD || (at == HostAutomaton::SINK && i + 1 < n))
+                return fail(ZF_ERR_REJECTED, "byte " + std::to_string(i) + " of the input cannot extend the prefix");
+        }
+        s->host_id = at; s->host_id_epoch = epoch;
+        s->accepting = accepted;
+        lk.unlock();
+        s->bytes_fed += n;
+        s->lag.insert(s->lag.end(), bytes, bytes + n);
+        s->lag_cut.push_back((uint32_t)s->lag.size());
+        if (s->lag.size() > HOST_LAG_MAX) catch_up(s);
+    } else {
+        Chart &c = s->chart;
+        const uint32_t keep = c.n_sets();
+        int64_t created = 0;
+        bool accepted = false;
+        for (int64_t i = 0; i < n; i++) {
+            StepResult r = earley_step(t, c, bytes[i], !pruning, &created);
+            accepted = r.accepted;
+            // a byte is rejected when its set is empty; a completed sentence that cannot be extended
+            // is still fine as the last byte
+            if (!r.alive || (!r.kernel_nonempty && i + 1 < n)) {
+                c.truncate(keep);
+                return fail(ZF_ERR_REJECTED, "byte " + std::to_string(i) + " of the input cannot extend the prefix");
+            }
+        }
+        s->accepting = accepted;
+        s->items_created += created;
+        s->bytes_fed += n;
+        if (pruning) chart_compact(t, c);   // Compact: after Complete, before the next Predict
     }
-    s->accepting = accepted;
-    s->items_created += created;
-    s->bytes_fed += n;
     if (s->eng->store_on) {                               // the device walks the same bytes at the next mask call
         for (int64_t i = 0; i < n; i++) s->pending.push_back(t.cls[bytes[i]]);
         s->fed_total += (uint64_t)n;
@@ -346,7 +464,6 @@ int feed_token_bytes(zf_state *s, const uint8_t *bytes, int64_t n) {
             s->pending.clear(); s->pending_base = s->fed_total; s->dev_id = 0; s->dev_epoch = 0;
         }
     }
-    if (pruning) chart_compact(t, c);   // Compact: after Complete, before the next Predict
     return ZF_OK;
 }
 
@@ -395,9 +512,13 @@ int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_option
         build_token_mask_cache(e->tab, e->trie);
     } catch (const std::bad_alloc &) { delete e; return fail(ZF_ERR_OOM, "out of memory"); }
     e->store_on = e->opt.device >= 0 && e->opt.walk_mode == 2 && e->opt.pruning != 0;
+    if (e->opt.walk_mode == 2 && e->opt.pruning != 0) {
+        e->host_aut = new (std::nothrow) HostAutomaton(e->tab);
+        if (!e->host_aut) { delete e; return fail(ZF_ERR_OOM, "out of memory"); }
+    }
     if (e->opt.device >= 0) {
         int rc = setup_device(e);
-        if (rc != ZF_OK) { free_device(e->dev); delete e; return rc; }
+        if (rc != ZF_OK) { free_device(e->dev); delete e->host_aut; delete e; return rc; }
     }
     *out = e;
     return ZF_OK;
@@ -406,6 +527,7 @@ int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_option
 void zf_engine_destroy(zf_engine *e) {
     if (!e) return;
     free_device(e->dev);
+    delete e->host_aut;
     delete e;
 }
 
@@ -447,6 +569,8 @@ int zf_state_reset(zf_state *s) {
     s->items_created = 0; s->bytes_fed = 0;
     s->dev_id = STORE_ROOT_ID; s->dev_epoch = 0; s->generation++;
     s->pending.clear(); s->pending_base = s->fed_total; s->pending_token = -1;
+    s->lag.clear(); s->lag_cut.clear();
+    s->host_id = HostAutomaton::ROOT; s->host_id_epoch = 0;
     return ZF_OK;
 }
 
@@ -483,7 +607,7 @@ namespace {
 
 struct AdvanceJob {
     zf_state *const *states;
-    const int32_t *ids;
+    const int32_t *ids;          // null: the job is to bring the rows' charts up to date
     int32_t n;
     int32_t *rc;                 // [n]
     std::string *err;            // [n] the error text of a row that failed
@@ -497,7 +621,8 @@ bool advance_rows(AdvanceJob &j) {   // takes rows until none is left; true if i
     for (;;) {
         const int32_t b = j.next.fetch_add(1, std::memory_order_relaxed);
         if (b >= j.n) return any;
-        j.rc[b] = advance_one(j.states[b], j.ids[b]);
+        if (j.ids) j.rc[b] = advance_one(j.states[b], j.ids[b]);
+        else { (void)chart_of(j.states[b]); j.rc[b] = ZF_OK; }
         if (j.rc[b] != ZF_OK) j.err[b] = zf_last_error();   // the text lives in the worker's thread: hand it over
         j.done.fetch_add(1, std::memory_order_release);
         any = true;
@@ -560,7 +685,22 @@ int64_t advance_cost(zf_state *const *states, const int32_t *ids, int32_t n) {
     for (int32_t b = 0; b < n; b++) {
         const zf_state *s = states[b];
         if (!s || ids[b] < 0 || ids[b] >= s->eng->V) continue;
-        const Chart &c = s->chart;
+        if (s->eng->host_aut) {
+            // a walk through the host automaton costs nothing unless it meets a transition nobody has taken: then one Earley
+            // byte step per byte from there on is the likely cost
+            zf_engine *e = s->eng;
+            std::lock_guard<std::mutex> rl(e->host_mu);
+            const HostAutomaton &A = *e->host_aut;
+            const bool placed = s->host_id == HostAutomaton::ROOT || s->host_id_epoch == e->host_epoch;
+            if (placed && s->host_id == HostAutomaton::SINK) continue;
+            const uint8_t first = e->voc_bytes[(size_t)e->voc_off[ids[b]]];
+            const bool has_bytes = e->voc_off[ids[b] + 1] > e->voc_off[ids[b]];
+            if (placed && has_bytes && A.st(s->host_id).trans[e->tab.cls[first]] != HostAutomaton::NONE) continue;
+            const int64_t last = placed ? (int64_t)A.st(s->host_id).items.size() : 64, all = placed ? 8 * (int64_t)A.st(s->host_id).widest : 4096;
+            cost += (e->voc_off[ids[b] + 1] - e->voc_off[ids[b]]) * (last + last * last / 16 + all);
+            continue;
+        }
+        const Chart &c = chart_of(s);
         const int64_t last = c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1];
         cost += (s->eng->voc_off[ids[b] + 1] - s->eng->voc_off[ids[b]]) * (last + last * last / 16) + (int64_t)c.items.size();
     }
@@ -568,6 +708,45 @@ int64_t advance_cost(zf_state *const *states, const int32_t *ids, int32_t n) {
 }
 
 }  // namespace
+
+// Bring the charts of a call's rows up to date (those fed through the host automaton lag behind): the same work as feeding
+// them, so a batch of wide charts is dealt to the worker threads here as it is there.
+static void catch_up_batch(zf_state *const *states, int32_t n) {
+    int64_t cost = 0;
+    int32_t lagging = 0;
+    for (int32_t b = 0; b < n; b++) {
+        const zf_state *s = states[b];
+        if (!s || s->lag.empty()) continue;
+        const Chart &c = s->chart;
+        const int64_t last = c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1];
+        cost += (int64_t)s->lag.size() * (last + last * last / 16) + (int64_t)c.items.size() * (int64_t)s->lag_cut.size();
+        lagging++;
+    }
+    bool parallel = lagging >= 4 && cost >= ADVANCE_PARALLEL_FROM;
+    if (parallel) {
+        std::vector<const zf_state *> seen(states, states + n);
+        std::sort(seen.begin(), seen.end());
+        parallel = std::adjacent_find(seen.begin(), seen.end()) == seen.end();
+    }
+    std::unique_lock<std::mutex> pool_lock(g_pool_mutex, std::defer_lock);
+    if (parallel) parallel = pool_lock.try_lock();
+    if (parallel) {
+        if (!g_pool) {
+            const unsigned hw = std::thread::hardware_concurrency();
+            g_pool = new AdvancePool((int)std::min(15u, std::max(1u, hw) - 1u));
+        }
+        parallel = g_pool->usable();
+    }
+    if (!parallel) {
+        for (int32_t b = 0; b < n; b++) if (states[b]) (void)chart_of(states[b]);
+        return;
+    }
+    std::vector<int32_t> rc((size_t)n, ZF_OK);
+    std::vector<std::string> errs((size_t)n);
+    auto job = std::make_shared<AdvanceJob>();
+    job->states = states; job->ids = nullptr; job->n = n; job->rc = rc.data(); job->err = errs.data();
+    g_pool->run(job);
+}
 
 int zf_advance_batch(zf_state *const *states, const int32_t *token_ids, int32_t n, int32_t *status) {
     if (!states || !token_ids || n < 0) return fail(ZF_ERR_INVALID_ARG, "null argument");
@@ -623,17 +802,17 @@ int zf_is_accepting(const zf_state *s, int32_t *out) {
 
 int zf_state_stats(const zf_state *s, zf_stats *o) {
     if (!s || !o) return fail(ZF_ERR_INVALID_ARG, "null argument");
-    o->n_sets = s->chart.n_sets(); o->n_items = (int64_t)s->chart.items.size();
+    o->n_sets = chart_of(s).n_sets(); o->n_items = (int64_t)chart_of(s).items.size();
     o->items_created = s->items_created; o->bytes_fed = s->bytes_fed; o->accepting = s->accepting;
     return ZF_OK;
 }
 
 int zf_state_chart(const zf_state *s, int32_t *items, int64_t *set_off) {
     if (!s) return fail(ZF_ERR_INVALID_ARG, "null argument");
-    if (items) for (size_t i = 0; i < s->chart.items.size(); i++) {
-        items[3 * i] = s->chart.items[i].p; items[3 * i + 1] = (int32_t)s->chart.items[i].o; items[3 * i + 2] = s->chart.items[i].q;
+    if (items) for (size_t i = 0; i < chart_of(s).items.size(); i++) {
+        items[3 * i] = chart_of(s).items[i].p; items[3 * i + 1] = (int32_t)chart_of(s).items[i].o; items[3 * i + 2] = chart_of(s).items[i].q;
     }
-    if (set_off) for (size_t k = 0; k < s->chart.set_off.size(); k++) set_off[k] = s->chart.set_off[k];
+    if (set_off) for (size_t k = 0; k < chart_of(s).set_off.size(); k++) set_off[k] = chart_of(s).set_off[k];
     return ZF_OK;
 }
 
@@ -651,7 +830,7 @@ int zf_debug_host_mask_cached(zf_engine *e, const zf_state *s, uint32_t *mask, i
     if (!e || !s || !mask || s->eng != e) return fail(ZF_ERR_INVALID_ARG, "bad argument");
     const Tables &t = e->tab;
     const Trie &tr = e->trie;
-    Chart c = s->chart;
+    Chart c = chart_of(s);
     const uint32_t m0 = c.n_sets();
     std::vector<uint32_t> ents(c.set_off[m0] - c.set_off[m0 - 1] + 1);
     const uint32_t n_ent = current_set_entries(t, c, ents.data());
@@ -694,7 +873,7 @@ int zf_debug_host_mask_stats(zf_engine *e, const zf_state *s, uint32_t *mask, in
     std::vector<uint8_t> chunk_over((e->trie.n_strings + CHUNK_RANKS - 1) / CHUNK_RANKS + 1, 0);
     const Tables &t = e->tab;
     const Trie &tr = e->trie;
-    Chart c = s->chart;
+    Chart c = chart_of(s);
     const uint32_t m0 = c.n_sets();
     std::vector<uint8_t> ok(tr.n_strings, 0);
     for (uint32_t i = 0; i < tr.nodes.size();) {
@@ -786,10 +965,11 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     for (int b = 0; b < batch; b++)
         if (!states[b] || states[b]->eng != e) return fail(ZF_ERR_INVALID_ARG, "state " + std::to_string(b) + " is null or belongs to another engine");
     if (e->store_on && !noalloc && !per_block) return enqueue_store_impl(e, states, batch, d_mask, hip_stream, wait, slot);
+    catch_up_batch(states, batch);                        // these paths send the charts
     // ---- the packed form of every row: [n_sets][set offsets][item word, origin]... (also the cache key) ----
     static thread_local std::vector<std::vector<uint32_t>> packed;
     if ((int)packed.size() < batch) packed.resize(batch);
-    for (int b = 0; b < batch; b++) pack_chart(e->tab, states[b]->chart, packed[b]);
+    for (int b = 0; b < batch; b++) pack_chart(e->tab, chart_of(states[b]), packed[b]);
     // ---- state cache: rows whose chart has been seen before only need their finished mask copied ----
     const bool sc = !noalloc && !d->cache.empty() && (size_t)batch * 2 <= d->cache.size();
     static thread_local std::vector<uint32_t> row_slot, miss_rows;
@@ -801,7 +981,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     // trie walk: rows with a wide current set first: their chunks are the expensive ones, and work that starts early does
     // not end up as the kernel's tail (the mask automaton gives every row its own blocks: the order does not matter there)
     if (e->opt.walk_mode == 1) std::stable_sort(miss_rows.begin(), miss_rows.end(), [&](uint32_t x, uint32_t y) {
-        const Chart &cx = states[x]->chart, &cy = states[y]->chart;
+        const Chart &cx = chart_of(states[x]), &cy = chart_of(states[y]);
         return cx.set_off[cx.n_sets()] - cx.set_off[cx.n_sets() - 1] > cy.set_off[cy.n_sets()] - cy.set_off[cy.n_sets() - 1];
     });
     const int nb = (int)miss_rows.size();                // rows that go through the kernels
@@ -810,7 +990,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     size_t n_off = 0, n_items = 0, n_ent = 0, max_off = 0, max_items = 0, max_ent = 0;
     const bool use_cache = !e->opt.disable_token_mask_cache;
     for (int r = 0; r < nb; r++) {
-        const Chart &c = states[miss_rows[r]]->chart;
+        const Chart &c = chart_of(states[miss_rows[r]]);
         const size_t last = c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1];
         n_off += c.set_off.size();
         n_items += c.items.size();
@@ -858,7 +1038,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
         memcpy(h + off_rowslot, row_slot.data(), 4 * (size_t)batch);
         uint32_t so_at = 0, it_at = 0, en_at = 0;
         for (int r = 0; r < nb; r++) {
-            const Chart &c = states[miss_rows[r]]->chart;
+            const Chart &c = chart_of(states[miss_rows[r]]);
             const std::vector<uint32_t> &k = packed[miss_rows[r]];
             if (uniform) { so_at = (uint32_t)(r * max_off); it_at = (uint32_t)(r * max_items); en_at = (uint32_t)(r * max_ent); }
             rows[r] = RowChart{c.n_sets(), so_at, it_at, en_at, 0, (uint32_t)c.items.size(), {0, 0}};
@@ -943,7 +1123,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
     if (e->lane_cap_auto) {
         size_t widest = 0;
         for (int r = 0; r < nb; r++) {
-            const Chart &c = states[miss_rows[r]]->chart;
+            const Chart &c = chart_of(states[miss_rows[r]]);
             widest = std::max<size_t>(widest, c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1]);
         }
         size_t want_cap = (8 * widest + 64 + 31) / 32 * 32;
@@ -970,7 +1150,7 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
         // as the widest current set; states and the item arena share what the tables leave of 160 KB.
         size_t widest = 0, most_sets = 0, most_items = 0, biggest_set = 0;
         for (int r = 0; r < nb; r++) {
-            const Chart &c = states[miss_rows[r]]->chart;
+            const Chart &c = chart_of(states[miss_rows[r]]);
             widest = std::max<size_t>(widest, c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1]);
             most_sets = std::max<size_t>(most_sets, c.n_sets());
             most_items = std::max<size_t>(most_items, c.set_off[c.n_sets()]);
@@ -1042,6 +1222,8 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
 static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait, uint32_t slot) {
     DeviceSide *d = e->dev;
     hipStream_t stream = (hipStream_t)hip_stream;
+    std::unique_lock<std::mutex> host_lk;                 // the rows' current sets are read from the host automaton (a row it does not know is brought in)
+    if (e->host_aut) host_lk = std::unique_lock<std::mutex>(e->host_mu);
     // ---- clear the store when it is new, half full, or has refused a request; only with no call in flight ----
     if (d->pending == 0 && (d->store_dirty || d->store_states > d->store.cap_states / 2 || d->store_items > d->store.cap_items / 2)) {
         HIP_TRY(launch_store_clear(d->store, (uint32_t)std::max(e->tab.n_cls, 1), d->d_root_items, d->n_root, stream));
@@ -1058,9 +1240,20 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
     miss_rows.clear();
     int n_hits = 0;
     if (sc) {
-        for (int b = 0; b < batch; b++) pack_chart(e->tab, states[b]->chart, packed[b]);
+        catch_up_batch(states, batch);                    // the state cache's key is the packed chart
+        for (int b = 0; b < batch; b++) pack_chart(e->tab, chart_of(states[b]), packed[b]);
         n_hits = state_cache_lookup(d, packed, batch, row_slot, miss_rows);
-    } else for (int b = 0; b < batch; b++) miss_rows.push_back((uint32_t)b);
+    } else {
+        for (int b = 0; b < batch; b++) miss_rows.push_back((uint32_t)b);
+        // rows the store does not know come in through their charts (all of them after the store was cleared)
+        static thread_local std::vector<zf_state *> unknown;
+        unknown.clear();
+        for (int b = 0; b < batch; b++) {
+            zf_state *st = states[b];
+            if (!(st->dev_id == STORE_ROOT_ID || (st->dev_id != 0 && st->dev_epoch == d->store_epoch)) && !st->lag.empty()) unknown.push_back(st);
+        }
+        if (!unknown.empty()) catch_up_batch(unknown.data(), (int32_t)unknown.size());
+    }
     const int nb = (int)miss_rows.size();
     d->report.cache_hits = n_hits; d->report.cache_misses = sc ? nb : 0;
     // ---- what each launched row sends ----
@@ -1069,14 +1262,15 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
     size_t n_pend = 0, n_ent = 0, n_off = 0, n_items = 0, widest = 0, biggest_set = 0;
     for (int r = 0; r < nb; r++) {
         zf_state *st = states[miss_rows[r]];
-        const Chart &c = st->chart;
-        const size_t last = c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1];
+        const CurrentSet cs = current_set(st);
+        const size_t last = cs.n;
         widest = std::max(widest, last);
-        for (uint32_t k = 0; k < c.n_sets(); k++) biggest_set = std::max<size_t>(biggest_set, c.set_off[k + 1] - c.set_off[k]);
+        biggest_set = std::max<size_t>(biggest_set, cs.biggest);
         if (use_cache) n_ent += last;
         const bool known = st->dev_id == STORE_ROOT_ID || (st->dev_id != 0 && st->dev_epoch == d->store_epoch);
         if (known) n_pend += st->pending.size();
         else {
+            const Chart &c = chart_of(st);
             import_rows.push_back((uint32_t)r);
             if (!sc) pack_chart(e->tab, c, packed[miss_rows[r]]);
             n_off += c.set_off.size(); n_items += c.items.size();
@@ -1125,11 +1319,11 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
         uint32_t en_at = 0, pe_at = 0, so_at = 0, it_at = 0, k_imp = 0;
         for (int r = 0; r < nb; r++) {
             zf_state *st = states[miss_rows[r]];
-            const Chart &c = st->chart;
+            const CurrentSet cs = current_set(st);
             StoreRow sr{};
             sr.ent_off = en_at;
             if (use_cache) {
-                sr.n_ent = current_set_entries(e->tab, c, ents + en_at); sr.flags |= STORE_ROW_CACHE;
+                sr.n_ent = current_set_entries(e->tab, cs.items, cs.n, ents + en_at); sr.flags |= STORE_ROW_CACHE;
                 if (sr.n_ent <= (uint32_t)STORE_ROW_ENT) memcpy(sr.ent, ents + en_at, 4 * sr.n_ent);
             }
             en_at += sr.n_ent;
@@ -1147,6 +1341,7 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
                 if (sr.n_pending <= (uint32_t)STORE_ROW_PEND) memcpy(sr.pend, st->pending.data(), sr.n_pending);
                 pe_at += sr.n_pending;
             } else {
+                const Chart &c = chart_of(st);
                 const std::vector<uint32_t> &k = packed[miss_rows[r]];
                 sr.flags |= STORE_ROW_IMPORTED;
                 rows[k_imp] = RowChart{c.n_sets(), so_at, it_at, 0, 0, (uint32_t)c.items.size(), {0, 0}};
@@ -1235,11 +1430,11 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
             double cost[STORE_MINI_ROWS];
             int segs[STORE_MINI_ROWS], parts[STORE_MINI_ROWS];
             for (int r = 0; r < nb; r++) {
-                const Chart &c = states[miss_rows[r]]->chart;
+                const CurrentSet cs = current_set(states[miss_rows[r]]);
                 uint32_t ent[64];
                 double und = d->tab.V;
-                if (use_cache && c.set_off[c.n_sets()] - c.set_off[c.n_sets() - 1] <= 64) {
-                    const uint32_t n = current_set_entries(e->tab, c, ent);
+                if (use_cache && cs.n <= 64) {
+                    const uint32_t n = current_set_entries(e->tab, cs.items, cs.n, ent);
                     uint64_t sig = 0xCBF29CE484222325ull ^ n;
                     for (uint32_t k = 0; k < n; k++) sig = (sig ^ ent[k]) * 0x100000001B3ull;
                     auto it = d->undecided_of.find(sig);

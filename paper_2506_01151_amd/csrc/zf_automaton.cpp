@@ -19,6 +19,7 @@
 #include <cstring>
 #include <map>
 #include "zf_internal.h"
+#include "zf_host_automaton.h"
 
 namespace zf {
 namespace {
@@ -109,7 +110,7 @@ extern "C" int zf_debug_host_mask_automaton(zf_engine *e, const zf_state *s, uin
     if (!e || !s || !mask || s->eng != e) { set_error("bad argument"); return ZF_ERR_INVALID_ARG; }
     const Tables &t = e->tab;
     const Trie &tr = e->trie;
-    const Chart &c = s->chart;
+    const Chart &c = chart_of(s);
     const uint32_t m0 = c.n_sets();
     // merge the token-mask cache rows of the current set (Section 4.3), as the kernels do
     std::vector<uint32_t> valid(tr.Wr, 0), want(tr.Wr, 0);
@@ -153,90 +154,9 @@ extern "C" int zf_debug_host_mask_automaton(zf_engine *e, const zf_state *s, uin
 // transitively: what ZapFormat's reachability closure (Section 4.2.3) keeps of a chart is exactly
 // what a state can reach through these references, and completed items are dropped when a set is
 // closed, so nothing here needs a separate Compact pass.
-namespace zf {
-namespace {
-
-struct PersistentAutomaton {
-    const Tables &t;
-    static constexpr uint32_t ROOT = 1, SINK = 0xFFFFFFFDu, DEAD = 0xFFFFFFFEu, NONE = 0xFFFFFFFFu;
-    std::vector<std::vector<Item>> sets;          // state id -> items; an item's origin is a state id
-    std::vector<std::vector<uint32_t>> trans;     // state id -> [n_cls] next state, NONE, DEAD or SINK
-    std::vector<std::vector<uint8_t>> acc;        // state id -> [n_cls] the prefix is a sentence after that byte
-    std::map<std::vector<uint32_t>, uint32_t> interned;
-    int64_t n_steps = 0, n_items = 0;
-
-    explicit PersistentAutomaton(const Tables &t_) : t(t_) {
-        sets.resize(2); trans.resize(2); acc.resize(2);       // id 0 is not used
-        Chart c;
-        chart_init(t, c);
-        for (Item it : c.items) {                              // the closure of the start item; its items started in this very set
-            if ((t.sym[it.p] >> SYM_KIND_SHIFT) == SYM_END) continue;
-            it.o = ROOT;
-            sets[ROOT].push_back(it);
-        }
-        trans[ROOT].assign(t.n_cls, NONE); acc[ROOT].assign(t.n_cls, 0);
-    }
-
-    void closure(uint32_t s, std::vector<uint32_t> &ids) const {
-        if (std::find(ids.begin(), ids.end(), s) != ids.end()) return;
-        ids.push_back(s);
-        for (const Item &it : sets[s]) closure(it.o, ids);
-    }
-
-    void compute(uint32_t s, uint8_t byte) {
-        const int cl = t.cls[byte];
-        std::vector<uint32_t> ids;
-        closure(s, ids);
-        std::sort(ids.begin(), ids.end());                     // a state refers to older states only (the root to itself)
-        ids.erase(std::find(ids.begin(), ids.end(), s));
-        ids.push_back(s);                                      // the source set last: it is the chart's current set
-        auto index_of = [&](uint32_t id) { return (uint32_t)(std::find(ids.begin(), ids.end(), id) - ids.begin()); };
-        Chart c;
-        c.set_off.assign(1, 0);
-        for (uint32_t id : ids) {
-            for (Item it : sets[id]) { it.o = index_of(it.o); c.items.push_back(it); }
-            c.set_off.push_back((uint32_t)c.items.size());
-        }
-        const StepResult r = earley_step(t, c, byte, false, nullptr);
-        n_steps++;
-        acc[s][cl] = r.accepted;
-        if (!r.alive) { trans[s][cl] = DEAD; return; }
-        if (!r.kernel_nonempty) { trans[s][cl] = SINK; return; }
-        const uint32_t last = c.n_sets() - 1;
-        std::vector<Item> out(c.items.begin() + c.set_off[last], c.items.end());
-        std::vector<uint32_t> key;
-        for (Item &it : out) {
-            it.o = ids[it.o];                                  // items scanned from predictions started in the source set: index last - 1 = s
-            key.push_back((uint32_t)it.p | ((uint32_t)it.q << 16));
-            key.push_back(it.o);
-        }
-        auto found = interned.find(key);
-        if (found != interned.end()) { trans[s][cl] = found->second; return; }
-        const uint32_t id = (uint32_t)sets.size();
-        n_items += (int64_t)out.size();
-        sets.push_back(out);
-        trans.emplace_back(t.n_cls, NONE);
-        acc.emplace_back(t.n_cls, 0);
-        interned.emplace(key, id);
-        trans[s][cl] = id;
-    }
-
-    // One byte from state s; returns the next state, SINK or DEAD.
-    uint32_t step(uint32_t s, uint8_t byte, bool *accepted) {
-        if (s == SINK) { if (accepted) *accepted = false; return DEAD; }
-        const int cl = t.cls[byte];
-        if (trans[s][cl] == NONE) compute(s, byte);
-        if (accepted) *accepted = acc[s][cl] != 0;
-        return trans[s][cl];
-    }
-};
-
-}  // namespace
-}  // namespace zf
-
 struct zf_twin {
     zf_engine *eng;
-    zf::PersistentAutomaton a;
+    zf::HostAutomaton a;
     explicit zf_twin(zf_engine *e) : eng(e), a(e->tab) {}
 };
 
@@ -249,11 +169,11 @@ extern "C" void zf_debug_twin_destroy(zf_twin *t) { delete t; }
 
 extern "C" int zf_debug_twin_advance(zf_twin *tw, uint32_t *state, const uint8_t *bytes, int64_t n, int32_t *accepting) {
     if (!tw || !state || (n > 0 && !bytes) || n <= 0) { set_error("bad argument"); return ZF_ERR_INVALID_ARG; }
-    uint32_t s = *state == 0 ? PersistentAutomaton::ROOT : *state;
+    uint32_t s = *state == 0 ? HostAutomaton::ROOT : *state;
     bool acc = false;
     for (int64_t i = 0; i < n; i++) {
         s = tw->a.step(s, bytes[i], &acc);
-        if (s == PersistentAutomaton::DEAD || (s == PersistentAutomaton::SINK && i + 1 < n)) { set_error("byte " + std::to_string(i) + " cannot extend the prefix"); return ZF_ERR_REJECTED; }
+        if (s == HostAutomaton::DEAD || (s == HostAutomaton::SINK && i + 1 < n)) { set_error("byte " + std::to_string(i) + " cannot extend the prefix"); return ZF_ERR_REJECTED; }
     }
     *state = s;
     if (accepting) *accepting = acc;
@@ -265,16 +185,16 @@ extern "C" int zf_debug_twin_mask(zf_twin *tw, uint32_t state, uint32_t *mask, i
     zf_engine *e = tw->eng;
     const Tables &t = e->tab;
     const Trie &tr = e->trie;
-    PersistentAutomaton &a = tw->a;
-    const uint32_t root = state == 0 ? PersistentAutomaton::ROOT : state;
+    HostAutomaton &a = tw->a;
+    const uint32_t root = state == 0 ? HostAutomaton::ROOT : state;
     memset(mask, 0, sizeof(uint32_t) * e->W);
     const int64_t steps0 = a.n_steps;
     int64_t n_wanted = 0, n_lookups = 0;
-    if (root != PersistentAutomaton::SINK) {
-        if (root >= a.sets.size()) { set_error("unknown state"); return ZF_ERR_INVALID_ARG; }
+    if (root != HostAutomaton::SINK) {
+        if (root >= a.n_states) { set_error("unknown state"); return ZF_ERR_INVALID_ARG; }
         std::vector<uint32_t> valid(tr.Wr, 0), want(tr.Wr, 0);
         if (e->opt.disable_token_mask_cache) want.assign(tr.Wr, 0xFFFFFFFFu);
-        else for (const Item &it : a.sets[root]) {             // the token-mask cache rows of the state's items (Section 4.3)
+        else for (const Item &it : a.st(root).items) {             // the token-mask cache rows of the state's items (Section 4.3)
             const uint16_t code = t.sym[it.p];
             size_t row;
             if ((code >> SYM_KIND_SHIFT) == SYM_TERM) row = it.q;
@@ -291,7 +211,7 @@ extern "C" int zf_debug_twin_mask(zf_twin *tw, uint32_t state, uint32_t *mask, i
             for (uint32_t k = tr.str_off[r]; k < tr.str_off[r + 1] && ok; k++) {
                 n_lookups++;
                 s = a.step(s, tr.str_bytes[k], nullptr);
-                ok = s != PersistentAutomaton::DEAD;
+                ok = s != HostAutomaton::DEAD;
             }
             if (ok) valid[r >> 5] |= 1u << (r & 31);
         }
@@ -300,6 +220,6 @@ extern "C" int zf_debug_twin_mask(zf_twin *tw, uint32_t state, uint32_t *mask, i
             if (r != 0xFFFFFFFFu && ((valid[r >> 5] >> (r & 31)) & 1)) mask[v >> 5] |= 1u << (v & 31);
         }
     }
-    if (stats) { stats[0] = (int64_t)a.sets.size() - 1; stats[1] = a.n_steps - steps0; stats[2] = n_lookups; stats[3] = n_wanted; stats[4] = a.n_items; }
+    if (stats) { stats[0] = (int64_t)a.n_states - 1; stats[1] = a.n_steps - steps0; stats[2] = n_lookups; stats[3] = n_wanted; stats[4] = a.n_items; }
     return ZF_OK;
 }

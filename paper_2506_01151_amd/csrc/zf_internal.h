@@ -2,6 +2,7 @@
 #pragma once
 #include <cstdint>
 #include <memory>
+#include <mutex>
 #include <string>
 #include <vector>
 #include "zf_device.h"
@@ -10,6 +11,7 @@
 
 namespace zf {
 
+struct HostAutomaton;
 void set_error(const std::string &msg);   // thread-local detail string
 
 // ---- byte-level DFA of one terminal ---------------------------------------------------
@@ -104,6 +106,13 @@ struct zf_engine {
     bool start_nullable = false;
     bool lane_cap_auto = true;          // no explicit lane_item_cap: the budget follows the rows' set sizes
     bool store_on = false;              // the mask calls go through the persistent automaton (walk_mode 2, pruning on, a device)
+    // zf_advance through the persistent automaton on the host (walk_mode 2, pruning on): a token's bytes are walked through
+    // the table of known transitions, an Earley byte step runs only for a transition nobody has taken before, and the
+    // state's chart is brought up to date only when somebody asks for it.  One automaton per engine.
+    struct zf::HostAutomaton *host_aut = nullptr;
+    std::mutex host_mu;                 // look-ups and everything that writes; an Earley byte step for a new transition runs without it
+    int host_walkers = 0;               // threads between reading the sets a new transition needs and recording it (the automaton is not emptied meanwhile)
+    uint32_t host_epoch = 1;            // bumped when the host automaton is emptied (it is when it has grown past a bound)
     struct DeviceSide *dev = nullptr;   // null when compiled with device = -1
 };
 
@@ -125,4 +134,16 @@ struct zf_state {
     uint64_t fed_total = 0;             // bytes fed since the state was made; pending covers [pending_base, fed_total)
     uint64_t pending_base = 0;
     int32_t pending_token = -1;         // the token whose bytes are all of `pending`, fed in state dev_id; -1 when pending is anything else
+    // Where the state stands in the engine's host automaton (when the engine has one), and the bytes fed since `chart` was last
+    // brought up to date (lag_cut: where each zf_advance call's bytes end).  Everything that reads the chart goes through
+    // zf::chart_of, which feeds them to the chart first.
+    uint32_t host_id = 1;               // 1 = the state of the empty prefix, valid in every epoch
+    uint32_t host_id_epoch = 0;
+    std::vector<uint8_t> lag;
+    std::vector<uint32_t> lag_cut;
 };
+
+namespace zf {
+// The state's chart, brought up to date first when bytes were fed through the host automaton since it last was.
+const Chart &chart_of(const zf_state *s);
+}

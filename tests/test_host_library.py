@@ -355,6 +355,53 @@ def test_advance_batch_of_wide_charts_on_worker_threads():
     assert many[1].chart() == ref.chart()
 
 
+def test_advance_through_the_host_automaton_equals_plain_advance():
+    """With walk_mode 2 zf_advance walks the token's bytes through the engine's automaton of Earley sets (a look-up per byte
+    once a transition is known) and brings the chart up to date only when somebody reads it.  Same acceptance at every step,
+    same charts and statistics, same rejections as the plain Scan/Complete/Compact advance of a walk_mode 0 engine: along
+    sentences with long sums (wide sets, several threads at work in one batch), twice over (the second time every transition
+    is known), with clones and resets on the way."""
+    import paper_2506_01151_amd as zf
+    from workloads.sentences import expr_sentence, cut_into_tokens
+    cfg = configs.CONFIGS[5]
+    toks = cfg.vocab(6000)
+    rows, steps = 16, 160
+    seqs = [cut_into_tokens(toks, expr_sentence(cfg.seed, f"host[{b}]", 4 * steps + 64, flat=b % 4 != 3), steps) for b in range(rows)]
+    fast, plain = (zf.Engine(cfg.grammar(), toks, device=-1, walk_mode=m) for m in (2, 0))
+    bad = toks.index(b")")
+    for again in range(2):
+        bf, bp = (zf.StateBatch([e.new_state() for _ in range(rows)]) for e in (fast, plain))
+        at = [0] * rows                                            # where every row stands in its sentence
+        for k in range(steps):
+            ids = [seqs[b][at[b]] for b in range(rows)]
+            if k == 50:
+                ids[3], at[3] = -1, -1                             # a reset on the way: the row starts its sentence again
+            bf.advance(ids)
+            bp.advance(ids)
+            at = [x + 1 for x in at]
+            for b in range(rows):
+                assert bf[b].accepting() == bp[b].accepting(), (again, k, b)
+            if k in (0, 7, 50, 51, 120, steps - 1):
+                for b in range(0, rows, 3):
+                    assert bf[b].chart() == bp[b].chart(), (again, k, b)
+                    sf, sp = bf[b].stats(), bp[b].stats()
+                    assert (sf.n_sets, sf.n_items, sf.items_created, sf.bytes_fed) == (sp.n_sets, sp.n_items, sp.items_created, sp.bytes_fed)
+            if k == 90:
+                cf, cp = bf[5].clone(), bp[5].clone()              # a clone goes its own way
+                for t in seqs[5][at[5]:at[5] + 20]:
+                    cf.advance(t)
+                    cp.advance(t)
+                assert cf.chart() == cp.chart() and cf.accepting() == cp.accepting()
+                for t in (bad, toks.index(b"+"), toks.index(b"("), toks.index(b"7"), toks.index(b"q")):
+                    rf, rp = bf[6].clone().try_advance(t), bp[6].clone().try_advance(t)   # what one refuses the other refuses ...
+                    assert rf == rp, t
+                # ... and a refused token moves nothing
+                sf, sp = bf[7].clone(), bp[7].clone()
+                first_bad = next(t for t in range(len(toks)) if sp.clone().try_advance(t) == zf.ZF_ERR_REJECTED)
+                assert sf.try_advance(first_bad) == zf.ZF_ERR_REJECTED and sp.try_advance(first_bad) == zf.ZF_ERR_REJECTED
+                assert sf.chart() == sp.chart() == bp[7].chart() and sf.accepting() == sp.accepting()
+
+
 @pytest.mark.parametrize("seed", range(48))
 def test_random_grammars_host_walk_equals_oracle(seed, zf, oracle_lib):
     """Differential test on seeded random grammars (empty rules, unit cycles, recursion of every
