@@ -1428,7 +1428,7 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
             a.store_uniform_parts = std::max(1, std::min(std::max(1, (n_seg + STORE_WAVES - 1) / STORE_WAVES), budget / nb));
         } else {
             double cost[STORE_MINI_ROWS];
-            int segs[STORE_MINI_ROWS], parts[STORE_MINI_ROWS];
+            int segs[STORE_MINI_ROWS], parts[STORE_MINI_ROWS], seg_w[STORE_MINI_ROWS];
             for (int r = 0; r < nb; r++) {
                 const CurrentSet cs = current_set(states[miss_rows[r]]);
                 uint32_t ent[64];
@@ -1455,7 +1455,7 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
                 // tokens are spread unevenly, and a second, nearly empty batch costs as much as a full one)
                 const uint32_t seg_words = (uint32_t)std::max(1.0, std::min<double>(STORE_SEG_WORDS_MAX, 48.0 * std::max(1, d->tab.V) / (32.0 * std::max(und, 1.0))));
                 segs[r] = (d->tab.W + (int)seg_words - 1) / (int)seg_words;
-                mini.r[r].meta |= (seg_words - 1) << 24;
+                seg_w[r] = (int)seg_words;
                 // what a pass costs a wavefront (microseconds, measured): an empty segment 2.8, a segment with a batch 3.7, each further batch 3
                 const double per_seg = und / segs[r];
                 cost[r] = per_seg < 1.0 ? 2.8 + 0.9 * per_seg : 3.7 + 3.0 * std::max(0.0, per_seg / 64.0 - 0.75);
@@ -1483,6 +1483,19 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
                 if (passes[r] <= 1) continue;
                 const int p = blocks_for(r, passes[r] - 1);
                 if (p - parts[r] <= budget - all) { all += p - parts[r]; parts[r] = p; passes[r]--; }
+            }
+#ifndef ZF_MERGE_SEGMENTS
+#define ZF_MERGE_SEGMENTS 1
+#endif
+            for (int r = 0; r < nb; r++) {
+                // A wavefront that has several segments to take takes them as fewer, wider ones (up to 64 words): the strings of a
+                // segment's first batch are waited for, those of its further batches travel while the batch before is checked.
+                if (ZF_MERGE_SEGMENTS && passes[r] > 1 && seg_w[r] < STORE_SEG_WORDS_MAX) {
+                    const int words_per_wave = (d->tab.W + parts[r] * STORE_WAVES - 1) / (parts[r] * STORE_WAVES);
+                    const int n_pass = (words_per_wave + STORE_SEG_WORDS_MAX - 1) / STORE_SEG_WORDS_MAX;
+                    seg_w[r] = std::max(seg_w[r], std::min<int>(STORE_SEG_WORDS_MAX, (words_per_wave + n_pass - 1) / n_pass));
+                }
+                mini.r[r].meta |= (uint32_t)(seg_w[r] - 1) << 24;
             }
             uint32_t at = 0;
             for (int r = 0; r < nb; r++) { a.store_first_block[r] = (uint16_t)at; at += (uint32_t)parts[r]; }

@@ -409,14 +409,14 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
         }
     };
     // One token of a batch: where its verdict goes, and its string (requested here, used a batch later).
-    struct Tok { uint32_t slot, bit, len, soff; Str16 c16; bool live; };
+    struct Tok { uint32_t slot, bit, len, token; Str16 c16; bool live; };
     uint32_t incl = 0, want = 0;                             // of the segment in hand: running bit counts of its words, undecided bits
     auto fetch = [&](uint32_t g, uint32_t b0, uint32_t total) -> Tok {
         Tok k;
         const uint32_t i = b0 + lane;
         k.live = i < total;
-        k.slot = 0;                                          // the word that holds the lane's token: the first whose running count exceeds i
-        if (total) for (uint32_t j = 0; j + 1u < slots; j++) k.slot += i >= (uint32_t)__builtin_amdgcn_readlane((int)incl, (int)j) ? 1u : 0u;
+        k.slot = 0;                                          // the word that holds the lane's token: the first whose running count exceeds i (by bisection)
+        for (uint32_t half = slots >> 1; half; half >>= 1) k.slot += i >= (uint32_t)__shfl((int)incl, (int)(k.slot + half - 1u)) ? half : 0u;
         const uint32_t before = (uint32_t)__shfl((int)incl, (int)(k.slot ? k.slot - 1 : 0));
         const uint32_t bits = (uint32_t)__shfl((int)want, (int)k.slot);
         uint32_t n = i - (k.slot ? before : 0u);             // the n-th set bit of the word, by halving
@@ -426,14 +426,10 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
             const uint32_t low = (uint32_t)__popc(bits & (((1u << sh) - 1u) << k.bit));
             if (n >= low) { n -= low; k.bit += (uint32_t)sh; }
         }
-        const uint32_t token = (g * sw + k.slot) * 32u + k.bit;
-        k.soff = 0; k.len = 0;
+        k.token = (g * sw + k.slot) * 32u + k.bit;
+        k.len = 0;
         k.c16 = Str16{{0, 0, 0, 0}};
-        if (k.live) { k.len = D.tok_len[token]; k.c16 = D.tok16[token]; }
-        if (k.live && k.len == (uint32_t)TOK_LEN_LONG) {     // longer than the 16 classes at hand: the rest is with the string's rank
-            const uint32_t rank = D.rank_of[token];
-            k.soff = D.str_off[rank]; k.len = D.str_off[rank + 1] - k.soff;
-        }
+        if (k.live) { k.len = D.tok_len[k.token]; k.c16 = D.tok16[k.token]; }   // requested here, looked at a batch later: nothing below waits for them
         return k;
     };
     bool root_ok = false;
@@ -471,35 +467,60 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
         for (uint32_t b0 = 0; b0 < total; b0 += 64) {
             const Tok cur = nxt;
             if (b0 + 64 < total) nxt = fetch(g, b0 + 64, total);
-            const uint32_t slot = cur.slot, bit = cur.bit, soff = cur.soff, len = cur.len;
+            const uint32_t slot = cur.slot, bit = cur.bit;
+            uint32_t soff = 0, len = cur.len;
             const Str16 c16 = cur.c16;
             bool live = cur.live;
+            const bool long_one = live & (len == (uint32_t)TOK_LEN_LONG);   // longer than the 16 classes at hand: the rest is with the string's rank
+            if (__ballot(long_one)) {
+                if (long_one) {
+                    const uint32_t rank = D.rank_of[cur.token];
+                    soff = D.str_off[rank]; len = D.str_off[rank + 1] - soff;
+                }
+            }
             live = live && len > 0;
             uint32_t s = root, pos = 0, cc = 0, spins = 0, t = AT_BUSY;
             bool ok = false, fail = false, again = false;
             for (;;) {
-                while (live) {                               // every lane follows its own string as far as the table goes
-                    if (pos < 16u) {
-                        const uint32_t q = pos >> 2;
-                        const uint32_t word = q == 0 ? c16.w[0] : (q == 1 ? c16.w[1] : (q == 2 ? c16.w[2] : c16.w[3]));
-                        cc = (word >> ((pos & 3u) * 8u)) & 0xFFu;
-                    } else cc = D.str_cls[soff + pos];
-                    const uint32_t key = s * ncls + cc;
-                    const uint32_t lslot = (key * 0x9E3779B1u) >> (32 - LC_BITS);
+                // Every lane follows its own string as far as the table goes: all lanes that can move take a step together,
+                // written without branches on per-lane conditions (selects and mask arithmetic; the two rare cases -- a string
+                // beyond 16 bytes, an entry that is not in the block's LDS cache -- sit behind wavefront-uniform tests).
+                bool stuck = false;                          // the table has no final answer for the lane's next step yet
+                for (;;) {
+                    const bool go = live & !stuck;
+                    if (!__ballot(go)) break;
+                    const uint32_t q = pos >> 2;
+                    const uint32_t word = q == 0 ? c16.w[0] : (q == 1 ? c16.w[1] : (q == 2 ? c16.w[2] : c16.w[3]));
+                    uint32_t c_new = (word >> ((pos & 3u) * 8u)) & 0xFFu;
+                    const bool far = go & (pos >= 16u);
+                    if (__ballot(far)) { if (far) c_new = D.str_cls[soff + pos]; }
+                    const uint32_t key = s * ncls + c_new;
+                    const uint32_t lslot = go ? (key * 0x9E3779B1u) >> (32 - LC_BITS) : 0u;
                     const unsigned long long e = __hip_atomic_load(&lc[lslot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                    if ((uint32_t)(e >> 32) == key) t = (uint32_t)e;
-                    else {
-                        // through the caches first; an entry seen unfinished is asked of device memory only on the
-                        // way back from the claim below, which is itself a fresh read of the entry it claims
-                        t = __hip_atomic_load(&G.trans[key], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-                        if (!t_final(t) && again) t = g_load(&G.trans[key]);
-                        if (t_final(t) && t != AT_FAIL) __hip_atomic_store(&lc[lslot], ((unsigned long long)key << 32) | t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    const bool hit = (uint32_t)(e >> 32) == key;
+                    uint32_t t_new = hit ? (uint32_t)e : (uint32_t)AT_NONE;
+                    const bool miss = go & !hit;
+                    if (__ballot(miss)) {
+                        if (miss) {
+                            // through the caches first; an entry seen unfinished is asked of device memory only on the
+                            // way back from the claim below, which is itself a fresh read of the entry it claims
+                            t_new = __hip_atomic_load(&G.trans[key], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                            if (!t_final(t_new) && again) t_new = g_load(&G.trans[key]);
+                            if (t_final(t_new) && t_new != AT_FAIL) __hip_atomic_store(&lc[lslot], ((unsigned long long)key << 32) | t_new, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        }
                     }
-                    if (t < AT_FAIL) { s = t; pos++; again = false; if (pos == len) { ok = true; live = false; } }
-                    else if (t == AT_DEAD) live = false;
-                    else if (t == AT_SINK) { ok = pos + 1 == len; live = false; }
-                    else if (t == AT_FAIL) { fail = true; live = false; }
-                    else break;                              // not there yet
+                    // (& and | on purpose: && and || would ask for a branch apiece)
+                    const bool adv = go & (t_new < AT_FAIL);  // a state: the lane moves on
+                    const bool wait = go & ((t_new == AT_NONE) | (t_new == AT_BUSY));
+                    s = adv ? t_new : s;
+                    pos += adv ? 1u : 0u;
+                    t = go ? t_new : t;
+                    cc = go ? c_new : cc;
+                    again = again & !adv;
+                    ok = ok | (adv & (pos == len)) | (go & (t_new == AT_SINK) & (pos + 1u == len));
+                    fail = fail | (go & (t_new == AT_FAIL));
+                    stuck = stuck | wait;
+                    live = live & (!go | wait | (adv & (pos != len)));
                 }
                 if (!__ballot(live)) break;
                 again = true;
@@ -535,11 +556,10 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
             // Logit masking (Section 3.3) of the segment's tokens, right here: 16-byte pieces, consecutive lanes on consecutive
             // pieces, the mask word from the lane that holds it.  Allowed logits are copied bit for bit, the others become -inf.
             uint8_t *dst = reinterpret_cast<uint8_t *>(a.apply_out) + l_at;
-            for (uint32_t p0 = 0; p0 < pieces; p0 += 64) {   // uniform trip count: the shuffle below is for all lanes
-                const uint32_t p = p0 + lane, t_in = p * tp;
+            auto mask_piece = [&](uint32_t p, u32x4 x) {     // all lanes call it together: the shuffle is for all of them
+                const uint32_t t_in = p * tp;
                 const uint32_t mb = (uint32_t)__shfl((int)v, (int)((t_in >> 5) & 63u)) >> (t_in & 31u);
                 if (p < pieces) {
-                    u32x4 x = p0 == 0 ? l_pre[0] : (p0 == 64 ? l_pre[1] : __builtin_nontemporal_load(l_src + p));
                     if (a.apply_dtype) {
 #pragma unroll
                         for (int k = 0; k < 4; k++) {
@@ -554,6 +574,15 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
                     }
                     __builtin_nontemporal_store(x, reinterpret_cast<u32x4 *>(dst) + p);
                 }
+            };
+            mask_piece(lane, l_pre[0]);
+            if (pieces > 64u) mask_piece(64u + lane, l_pre[1]);
+            for (uint32_t p0 = 128; p0 < pieces; p0 += 256) {   // what was not requested ahead: four pieces per lane in flight
+                u32x4 x[4];
+#pragma unroll
+                for (int u = 0; u < 4; u++) { const uint32_t p = p0 + (uint32_t)u * 64u + lane; x[u] = u32x4{0, 0, 0, 0}; if (p < pieces) x[u] = __builtin_nontemporal_load(l_src + p); }
+#pragma unroll
+                for (int u = 0; u < 4; u++) if (p0 + (uint32_t)u * 64u < pieces) mask_piece(p0 + (uint32_t)u * 64u + lane, x[u]);
             }
         }
         v = vn; c = cn;
