@@ -1303,6 +1303,8 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
     rec.st.assign(nb, std::shared_ptr<StateLink>()); rec.gen.assign(nb, 0); rec.upto.assign(nb, 0); rec.hop.assign(nb, 0);
     if (d->hop_epoch != d->store_epoch) { if (d->hop_used) std::fill(d->hop_key.begin(), d->hop_key.end(), 0); d->hop_used = 0; d->hop_epoch = d->store_epoch; }
     uint32_t n_cache_rows = 0;
+    static thread_local std::vector<uint32_t> row_n_ent, row_ent_at, row_n_items;
+    row_n_ent.assign(nb, 0); row_ent_at.assign(nb, 0); row_n_items.assign(nb, 0);
     static thread_local StoreMiniRows mini;               // short records: they travel in the kernel's argument block
     const bool use_mini = nb <= STORE_MINI_ROWS;
     {
@@ -1326,6 +1328,7 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
                 sr.n_ent = current_set_entries(e->tab, cs.items, cs.n, ents + en_at); sr.flags |= STORE_ROW_CACHE;
                 if (sr.n_ent <= (uint32_t)STORE_ROW_ENT) memcpy(sr.ent, ents + en_at, 4 * sr.n_ent);
             }
+            row_n_ent[r] = sr.n_ent; row_ent_at[r] = en_at; row_n_items[r] = cs.n;
             en_at += sr.n_ent;
             n_cache_rows += sr.n_ent;
             const bool known = st->dev_id == STORE_ROOT_ID || (st->dev_id != 0 && st->dev_epoch == d->store_epoch);
@@ -1427,14 +1430,13 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
             const int n_seg = (d->tab.W + STORE_SEG_WORDS - 1) / STORE_SEG_WORDS;
             a.store_uniform_parts = std::max(1, std::min(std::max(1, (n_seg + STORE_WAVES - 1) / STORE_WAVES), budget / nb));
         } else {
-            double cost[STORE_MINI_ROWS];
+            double cost[STORE_MINI_ROWS], inv_cost[STORE_MINI_ROWS];
             int segs[STORE_MINI_ROWS], parts[STORE_MINI_ROWS], seg_w[STORE_MINI_ROWS];
             for (int r = 0; r < nb; r++) {
-                const CurrentSet cs = current_set(states[miss_rows[r]]);
-                uint32_t ent[64];
                 double und = d->tab.V;
-                if (use_cache && cs.n <= 64) {
-                    const uint32_t n = current_set_entries(e->tab, cs.items, cs.n, ent);
+                if (use_cache && row_n_items[r] <= 64) {
+                    const uint32_t n = row_n_ent[r];              // the row's cache-row numbers, as gathered for its record
+                    const uint32_t *ent = (const uint32_t *)((uint8_t *)d->h_stage[slot] + off_ent) + row_ent_at[r];
                     uint64_t sig = 0xCBF29CE484222325ull ^ n;
                     for (uint32_t k = 0; k < n; k++) sig = (sig ^ ent[k]) * 0x100000001B3ull;
                     auto it = d->undecided_of.find(sig);
@@ -1459,6 +1461,7 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
                 // what a pass costs a wavefront (microseconds, measured): an empty segment 2.8, a segment with a batch 3.7, each further batch 3
                 const double per_seg = und / segs[r];
                 cost[r] = per_seg < 1.0 ? 2.8 + 0.9 * per_seg : 3.7 + 3.0 * std::max(0.0, per_seg / 64.0 - 0.75);
+                inv_cost[r] = 1.0 / cost[r];
             }
             // Every wavefront of a row takes the same number of passes (a row is as slow as its slowest wavefront).  The
             // smallest time T is looked for in which every row, taking as many passes as fit into T, leaves the grid within
@@ -1467,18 +1470,18 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
             auto blocks_for = [&](int r, int n_pass) { return std::max(1, (segs[r] + n_pass * STORE_WAVES - 1) / (n_pass * STORE_WAVES)); };
             auto need = [&](double T) {
                 int tot = 0;
-                for (int r = 0; r < nb; r++) tot += blocks_for(r, std::max(1, (int)(T / cost[r])));
+                for (int r = 0; r < nb; r++) tot += blocks_for(r, std::max(1, (int)(T * inv_cost[r])));
                 return tot;
             };
             double lo = cost[0];
             for (int r = 1; r < nb; r++) lo = std::min(lo, cost[r]);
             double hi = lo;
             if (need(hi) > budget) {
-                while (need(hi) > budget && hi < 1e9) hi *= 2;
-                for (int it = 0; it < 20; it++) { const double mid = 0.5 * (lo + hi); if (need(mid) <= budget) hi = mid; else lo = mid; }
+                while (need(hi) > budget && hi < 1e9) { lo = hi; hi *= 2; }
+                for (int it = 0; it < 6; it++) { const double mid = 0.5 * (lo + hi); if (need(mid) <= budget) hi = mid; else lo = mid; }   // to 2 %: the blocks left over go back to the rows below
             }
             int all = 0;
-            for (int r = 0; r < nb; r++) { passes[r] = std::max(1, (int)(hi / cost[r])); parts[r] = blocks_for(r, passes[r]); all += parts[r]; }
+            for (int r = 0; r < nb; r++) { passes[r] = std::max(1, (int)(hi * inv_cost[r])); parts[r] = blocks_for(r, passes[r]); all += parts[r]; }
             for (int r = 0; r < nb && all < budget; r++) {
                 if (passes[r] <= 1) continue;
                 const int p = blocks_for(r, passes[r] - 1);

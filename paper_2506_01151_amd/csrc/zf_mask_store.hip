@@ -242,13 +242,27 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
     // the first thing read, from the kernel's argument block when the call has few enough rows (one read; a block beyond its
     // row's count leaves at once).
     const uint32_t use_mini = (uint32_t)a.store_mini, uniform_parts = (uint32_t)a.store_uniform_parts;
-    uint32_t n_before = 0;                                   // rows that start at or before this block (all 64 entries are compared: no loop that waits once per row)
+    // Which row the block belongs to is known only once the rows' first blocks have been read, and the row's record only
+    // after that: so lane l asks for the first block AND the twelve words of the record of row l, all at once, and the
+    // wavefront picks its row's out of the lanes (one trip to the argument block instead of two, one after the other).
+    static_assert(STORE_MINI_ROWS == 64 && sizeof(StoreRowMini) == 48, "one short record per lane");
+    uint32_t rw[12];
+    {
+        const uint32_t *mp = reinterpret_cast<const uint32_t *>(&mini);
 #pragma unroll
-    for (int r = 0; r < STORE_MINI_ROWS; r++) n_before += blockIdx.x >= a.store_first_block[r] ? 1u : 0u;
+        for (int k = 0; k < 12; k++) rw[k] = mp[lane * 12u + (uint32_t)k];
+    }
+    const uint32_t fbv = a.store_first_block[lane], fbv2 = a.store_first_block[lane + 1u];
+    const uint32_t n_before = (uint32_t)__popcll(__ballot(blockIdx.x >= fbv));   // rows that start at or before this block (0xFFFF beyond the call's rows)
     const uint32_t row = uniform_parts ? blockIdx.x / (uniform_parts ? uniform_parts : 1u) : n_before - 1u;
     const uint32_t frow = row < (uint32_t)STORE_MINI_ROWS ? row : 0u;
-    const StoreRowMini m = mini.r[frow];
-    const uint32_t fb0 = a.store_first_block[frow], fb1 = a.store_first_block[frow + 1];
+    StoreRowMini m;
+    {
+        uint32_t *mw = reinterpret_cast<uint32_t *>(&m);
+#pragma unroll
+        for (int k = 0; k < 12; k++) mw[k] = (uint32_t)__builtin_amdgcn_readlane((int)rw[k], (int)frow);
+    }
+    const uint32_t fb0 = (uint32_t)__builtin_amdgcn_readlane((int)fbv, (int)frow), fb1 = (uint32_t)__builtin_amdgcn_readlane((int)fbv2, (int)frow);
     const uint32_t part = uniform_parts ? blockIdx.x - row * uniform_parts : blockIdx.x - fb0;
     const uint32_t parts = uniform_parts ? uniform_parts : fb1 - fb0;
     // mask words a wavefront takes per pass: the host picks fewer for rows most of whose tokens are undecided, so that a pass
