@@ -83,7 +83,9 @@ typedef struct {
                               2 = persistent automaton (one automaton for all rows and steps, kept in device memory: Earley sets
                               named by content; a call uploads the bytes fed since the last call, not the charts, and a transition
                               is computed once per engine; needs pruning = 1, else mode 0 runs in its place).  A call the
-                              persistent automaton has no room for is answered by mode 0 when it is a waiting call. */
+                              persistent automaton has no room for is answered by mode 0 when it is a waiting call.  With mode 2
+                              and pruning = 1 zf_advance, too, goes through such an automaton, kept on the host (a look-up per
+                              byte once a transition is known; results are those of the plain advance) -- with or without a device. */
 } zf_options;
 
 typedef struct {
@@ -132,7 +134,8 @@ int zf_state_reset(zf_state *s);
 void zf_state_destroy(zf_state *s);
 
 /* advance(state, token_id): feed the token's bytes through Scan -> Complete -> Compact ->
- * Predict (Sections 3.2, 4.2).  All or nothing: on ZF_ERR_REJECTED the state is unchanged. */
+ * Predict (Sections 3.2, 4.2).  All or nothing: on ZF_ERR_REJECTED the state is unchanged.
+ * States of one engine may be advanced from several threads at once (one thread per state). */
 int zf_advance(zf_state *s, int32_t token_id);
 int zf_advance_bytes(zf_state *s, const uint8_t *bytes /* host */, int64_t n);
 /* One decode step of a whole batch (the generation loop of Section 3.3 applied to every row):
