@@ -1654,6 +1654,12 @@ int zf_mask_wait(zf_engine *e, void *hip_stream) {
 int zf_engine_clear_state_cache(zf_engine *e) {
     if (!e) return fail(ZF_ERR_INVALID_ARG, "null argument");
     if (e->dev) { forget_cached_masks(e->dev); e->dev->store_dirty = true; }   // the persistent automaton starts over as well
+    if (e->host_aut) {                                    // and so does the host's: the states find their way back through their charts
+        std::unique_lock<std::mutex> lk(e->host_mu);
+        while (e->host_walkers != 0) { lk.unlock(); std::this_thread::yield(); lk.lock(); }   // somebody is at work on a transition (and waits for nobody)
+        e->host_aut->clear();
+        e->host_epoch++;
+    }
     return ZF_OK;
 }
 

@@ -376,6 +376,8 @@ def test_advance_through_the_host_automaton_equals_plain_advance():
             ids = [seqs[b][at[b]] for b in range(rows)]
             if k == 50:
                 ids[3], at[3] = -1, -1                             # a reset on the way: the row starts its sentence again
+            if k == 100 + 20 * again:
+                fast.clear_state_cache()                           # the automaton is emptied under the rows' feet: they come back in through their charts
             bf.advance(ids)
             bp.advance(ids)
             at = [x + 1 for x in at]
