@@ -494,21 +494,25 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
             }
             live = live && len > 0;
             uint32_t s = root, pos = 0, cc = 0, spins = 0, t = AT_BUSY;
+            uint32_t c_far = 0xFFFFFFFFu;                    // class of the byte at `pos` of a string beyond the 16 at hand, once it has been fetched
             bool ok = false, fail = false, again = false;
             for (;;) {
                 // Every lane follows its own string as far as the table goes: all lanes that can move take a step together,
-                // written without branches on per-lane conditions (selects and mask arithmetic; the two rare cases -- a string
-                // beyond 16 bytes, an entry that is not in the block's LDS cache -- sit behind wavefront-uniform tests).
+                // written without branches on per-lane conditions (selects and mask arithmetic; an entry that is not in the
+                // block's LDS cache sits behind a wavefront-uniform test).  No result of a load from device memory is used
+                // on the way round when every lane finds its entry: the loop never waits for what was requested ahead
+                // (the next batch's strings, the next segment's words and logits).  A lane beyond its 16th byte stops
+                // here and has the byte fetched below.
                 bool stuck = false;                          // the table has no final answer for the lane's next step yet
                 for (;;) {
-                    const bool go = live & !stuck;
+                    const bool beyond = pos >= 16u;
+                    const bool go = live & !stuck & (!beyond | (c_far != 0xFFFFFFFFu));
                     if (!__ballot(go)) break;
                     const uint32_t q = pos >> 2;
                     const uint32_t word = q == 0 ? c16.w[0] : (q == 1 ? c16.w[1] : (q == 2 ? c16.w[2] : c16.w[3]));
                     uint32_t c_new = (word >> ((pos & 3u) * 8u)) & 0xFFu;
-                    const bool far = go & (pos >= 16u);
-                    if (__ballot(far)) { if (far) c_new = D.str_cls[soff + pos]; }
-                    const uint32_t key = s * ncls + c_new;
+                    c_new = beyond ? c_far : c_new;
+                    const uint32_t key = __umul24(s, ncls) + c_new;          // a state has at most 18 bits, a class 8
                     const uint32_t lslot = go ? (key * 0x9E3779B1u) >> (32 - LC_BITS) : 0u;
                     const unsigned long long e = __hip_atomic_load(&lc[lslot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     const bool hit = (uint32_t)(e >> 32) == key;
@@ -528,6 +532,7 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
                     const bool wait = go & ((t_new == AT_NONE) | (t_new == AT_BUSY));
                     s = adv ? t_new : s;
                     pos += adv ? 1u : 0u;
+                    c_far = adv ? 0xFFFFFFFFu : c_far;
                     t = go ? t_new : t;
                     cc = go ? c_new : cc;
                     again = again & !adv;
@@ -537,6 +542,16 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
                     live = live & (!go | wait | (adv & (pos != len)));
                 }
                 if (!__ballot(live)) break;
+                {
+                    const bool fetch_far = live & !stuck & (pos >= 16u) & (c_far == 0xFFFFFFFFu);
+                    if (__ballot(fetch_far)) {               // strings beyond 16 bytes: the next byte's class, then round again
+                        if (fetch_far) {
+                            c_far = D.str_cls[soff + pos];
+                            asm volatile("" : "+v"(c_far));  // waited for here, not at the top of the loop above
+                        }
+                        continue;
+                    }
+                }
                 again = true;
                 // one of the waiting lanes' transitions is claimed and computed here; the other lanes look again afterwards
                 const unsigned long long missing = __ballot(live && t == AT_NONE);
@@ -559,6 +574,11 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
                     poll_pause(spins);
                     if (++spins > (uint32_t)AUT_SPIN_LIMIT) { fail = fail || live; live = false; }   // bounded wait
                 }
+                // Nothing this slow path asked of device memory is outstanding when the walk above starts again (vmcnt 0; the
+                // other two counters left alone).  Said explicitly, because the compiler otherwise has to assume that one of
+                // the loads in here may still be on its way to a register the walk reuses, and waits at the top of the walk on
+                // every round -- for the strings, words and logits requested ahead as well.
+                __builtin_amdgcn_s_waitcnt(0x0F70);
             }
             if (ok) atomicOr(&vbuf[slot], 1u << bit);
             const unsigned long long fm = __ballot(fail);    // no room in the scratch or the store, or a wait that did not end
