@@ -484,81 +484,93 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
             const uint32_t slot = cur.slot, bit = cur.bit;
             uint32_t soff = 0, len = cur.len;
             const Str16 c16 = cur.c16;
-            bool live = cur.live;
-            const bool long_one = live & (len == (uint32_t)TOK_LEN_LONG);   // longer than the 16 classes at hand: the rest is with the string's rank
+            const bool long_one = cur.live & (len == (uint32_t)TOK_LEN_LONG);   // longer than the 16 classes at hand: the rest is with the string's rank
             if (__ballot(long_one)) {
                 if (long_one) {
                     const uint32_t rank = D.rank_of[cur.token];
                     soff = D.str_off[rank]; len = D.str_off[rank + 1] - soff;
                 }
             }
-            live = live && len > 0;
-            uint32_t s = root, pos = 0, cc = 0, spins = 0, t = AT_BUSY;
-            uint32_t c_far = 0xFFFFFFFFu;                    // class of the byte at `pos` of a string beyond the 16 at hand, once it has been fetched
-            bool ok = false, fail = false, again = false;
+            // Where a lane stands with its string, in ONE register: the loop below carries no per-lane truth value from one
+            // round to the next.  (Carried truth values live in scalar register pairs, and every one of them costs three
+            // scalar instructions per round to merge; the four vector units of a compute unit share one scalar unit, which
+            // was what bounded the walk.)
+            enum : uint32_t { PH_GO = 0,      // takes a step in the next round
+                              PH_NONE = 1,    // waits: nobody has computed the entry it needs
+                              PH_BUSY = 2,    // waits: somebody is computing it
+                              PH_FAR = 3,     // beyond the 16 bytes at hand: the next byte has to be fetched
+                              PH_OK = 4,      // done: the whole string went through (codes from here on: done)
+                              PH_DEAD = 5,    // done: the string cannot follow
+                              PH_FAIL = 6 };  // done: no room, or a wait that did not end
+            // what a step that found no state makes of a lane, a nibble per special value (~value = 0 .. 4): not computed,
+            // dead, nothing can follow (the one string that ends right here is picked out below), being computed, no room
+            constexpr uint32_t PH_OF_SPECIAL = (PH_NONE << 0) | (PH_DEAD << 4) | (PH_DEAD << 8) | (PH_BUSY << 12) | (PH_FAIL << 16);
+            static_assert(AT_NONE == ~0u && AT_DEAD == ~1u && AT_SINK == ~2u && AT_BUSY == ~3u && AT_FAIL == ~4u, "the nibbles above");
+            uint32_t ph = cur.live && len > 0 ? (uint32_t)PH_GO : (uint32_t)PH_DEAD;
+            uint32_t s = root, pos = 0, spins = 0, rounds = 0;
+            uint32_t c_far = 0;                              // class of the byte at `pos` of a string beyond the 16 at hand (fetched while the lane is PH_FAR)
+            const uint32_t w0 = c16.w[0], w1 = c16.w[1], w2 = c16.w[2], w3 = c16.w[3];
+            auto class_at = [&](uint32_t at) -> uint32_t {  // byte `at` of the sixteen at hand: the half that holds it, then one byte permute
+                const bool upper = (at & 8u) != 0;
+                const uint32_t c_near = __builtin_amdgcn_perm(upper ? w3 : w1, upper ? w2 : w0, (at & 7u) | 0x0C0C0C00u);
+                return at >= 16u ? c_far : c_near;
+            };
             for (;;) {
                 // Every lane follows its own string as far as the table goes: all lanes that can move take a step together,
-                // written without branches on per-lane conditions (selects and mask arithmetic; an entry that is not in the
-                // block's LDS cache sits behind a wavefront-uniform test).  No result of a load from device memory is used
-                // on the way round when every lane finds its entry: the loop never waits for what was requested ahead
-                // (the next batch's strings, the next segment's words and logits).  A lane beyond its 16th byte stops
-                // here and has the byte fetched below.
-                bool stuck = false;                          // the table has no final answer for the lane's next step yet
+                // written without branches on per-lane conditions (selects; an entry that is not in the block's LDS cache
+                // sits behind a wavefront-uniform test).  No result of a load from device memory is used on the way round
+                // when every lane finds its entry: the loop never waits for what was requested ahead (the next batch's
+                // strings, the next segment's words and logits).
+                ph = ph == PH_NONE || ph == PH_BUSY ? (uint32_t)PH_GO : ph;   // those that waited look again
                 for (;;) {
-                    const bool beyond = pos >= 16u;
-                    const bool go = live & !stuck & (!beyond | (c_far != 0xFFFFFFFFu));
-                    if (!__ballot(go)) break;
-                    const uint32_t q = pos >> 2;
-                    const uint32_t word = q == 0 ? c16.w[0] : (q == 1 ? c16.w[1] : (q == 2 ? c16.w[2] : c16.w[3]));
-                    uint32_t c_new = (word >> ((pos & 3u) * 8u)) & 0xFFu;
-                    c_new = beyond ? c_far : c_new;
+                    const bool go = ph == PH_GO;
+                    if (!__builtin_amdgcn_ballot_w64(go)) break;
+                    const uint32_t c_new = class_at(pos);
                     const uint32_t key = __umul24(s, ncls) + c_new;          // a state has at most 18 bits, a class 8
                     const uint32_t lslot = go ? (key * 0x9E3779B1u) >> (32 - LC_BITS) : 0u;
                     const unsigned long long e = __hip_atomic_load(&lc[lslot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     const bool hit = (uint32_t)(e >> 32) == key;
                     uint32_t t_new = hit ? (uint32_t)e : (uint32_t)AT_NONE;
                     const bool miss = go & !hit;
-                    if (__ballot(miss)) {
+                    if (__builtin_amdgcn_ballot_w64(miss)) {
                         if (miss) {
                             // through the caches first; an entry seen unfinished is asked of device memory only on the
                             // way back from the claim below, which is itself a fresh read of the entry it claims
                             t_new = __hip_atomic_load(&G.trans[key], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-                            if (!t_final(t_new) && again) t_new = g_load(&G.trans[key]);
+                            if (!t_final(t_new) && rounds) t_new = g_load(&G.trans[key]);
                             if (t_final(t_new) && t_new != AT_FAIL) __hip_atomic_store(&lc[lslot], ((unsigned long long)key << 32) | t_new, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                         }
                     }
-                    // (& and | on purpose: && and || would ask for a branch apiece)
-                    const bool adv = go & (t_new < AT_FAIL);  // a state: the lane moves on
-                    const bool wait = go & ((t_new == AT_NONE) | (t_new == AT_BUSY));
+                    const bool state = t_new < AT_FAIL;      // a state: the lane moves on
+                    const uint32_t pos1 = pos + 1u;
+                    const bool ends = pos1 == len;
+                    uint32_t nx = __builtin_amdgcn_ubfe(PH_OF_SPECIAL, (~t_new) << 2, 4u);
+                    nx = state ? (pos1 >= 16u ? (uint32_t)PH_FAR : (uint32_t)PH_GO) : nx;
+                    nx = ((state | (t_new == AT_SINK)) & ends) ? (uint32_t)PH_OK : nx;   // (& and | on purpose: && and || would ask for a branch apiece)
+                    const bool adv = go & state;
                     s = adv ? t_new : s;
-                    pos += adv ? 1u : 0u;
-                    c_far = adv ? 0xFFFFFFFFu : c_far;
-                    t = go ? t_new : t;
-                    cc = go ? c_new : cc;
-                    again = again & !adv;
-                    ok = ok | (adv & (pos == len)) | (go & (t_new == AT_SINK) & (pos + 1u == len));
-                    fail = fail | (go & (t_new == AT_FAIL));
-                    stuck = stuck | wait;
-                    live = live & (!go | wait | (adv & (pos != len)));
+                    pos = adv ? pos1 : pos;
+                    ph = go ? nx : ph;
                 }
-                if (!__ballot(live)) break;
+                if (!__builtin_amdgcn_ballot_w64(ph < PH_OK)) break;
                 {
-                    const bool fetch_far = live & !stuck & (pos >= 16u) & (c_far == 0xFFFFFFFFu);
-                    if (__ballot(fetch_far)) {               // strings beyond 16 bytes: the next byte's class, then round again
+                    const bool fetch_far = ph == PH_FAR;
+                    if (__builtin_amdgcn_ballot_w64(fetch_far)) {   // strings beyond 16 bytes: the next byte's class, then round again
                         if (fetch_far) {
                             c_far = D.str_cls[soff + pos];
                             asm volatile("" : "+v"(c_far));  // waited for here, not at the top of the loop above
+                            ph = PH_GO;
                         }
                         continue;
                     }
                 }
-                again = true;
+                rounds++;
                 // one of the waiting lanes' transitions is claimed and computed here; the other lanes look again afterwards
-                const unsigned long long missing = __ballot(live && t == AT_NONE);
+                const unsigned long long missing = __builtin_amdgcn_ballot_w64(ph == PH_NONE);
                 bool progress = false;
                 if (missing) {
                     const int l = __ffsll((long long)missing) - 1;
-                    const uint32_t rs = (uint32_t)__builtin_amdgcn_readlane((int)s, l), rc = (uint32_t)__builtin_amdgcn_readlane((int)cc, l);
+                    const uint32_t rs = (uint32_t)__builtin_amdgcn_readlane((int)s, l), rc = (uint32_t)__builtin_amdgcn_readlane((int)class_at(pos), l);
                     uint32_t old = 0;
                     if (lane == 0) old = atomicCAS(&G.trans[rs * ncls + rc], (uint32_t)AT_NONE, (uint32_t)AT_BUSY);
                     old = (uint32_t)__builtin_amdgcn_readfirstlane((int)old);
@@ -572,7 +584,7 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
                 if (progress) spins = 0;
                 else {
                     poll_pause(spins);
-                    if (++spins > (uint32_t)AUT_SPIN_LIMIT) { fail = fail || live; live = false; }   // bounded wait
+                    if (++spins > (uint32_t)AUT_SPIN_LIMIT) ph = ph < PH_OK ? (uint32_t)PH_FAIL : ph;   // bounded wait
                 }
                 // Nothing this slow path asked of device memory is outstanding when the walk above starts again (vmcnt 0; the
                 // other two counters left alone).  Said explicitly, because the compiler otherwise has to assume that one of
@@ -580,8 +592,8 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
                 // every round -- for the strings, words and logits requested ahead as well.
                 __builtin_amdgcn_s_waitcnt(0x0F70);
             }
-            if (ok) atomicOr(&vbuf[slot], 1u << bit);
-            const unsigned long long fm = __ballot(fail);    // no room in the scratch or the store, or a wait that did not end
+            if (ph == PH_OK) atomicOr(&vbuf[slot], 1u << bit);
+            const unsigned long long fm = __builtin_amdgcn_ballot_w64(ph == PH_FAIL);    // no room in the scratch or the store, or a wait that did not end
             if (lane == 0 && fm) atomicAdd(errors, (uint32_t)__popcll(fm));
         }
         if (total) v |= lds_load(&vbuf[slot16]);             // LDS serves one wavefront's accesses in issue order
