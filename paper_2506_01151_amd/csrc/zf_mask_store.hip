@@ -308,8 +308,15 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
     if (flags & STORE_ROW_IMPORTED) start = a.store_import_root[row];
     const bool use_cache = (flags & STORE_ROW_CACHE) != 0;
     const bool ent_inline = n_ent <= (uint32_t)STORE_ROW_ENT, pend_inline = n_pending <= (uint32_t)(spilled ? STORE_ROW_PEND : STORE_MINI_PEND);
-    auto entry = [&](uint32_t k) -> uint32_t {               // k differs from lane to lane: a shuffle, not a broadcast
-        const uint32_t inl = (uint32_t)__shfl((int)rec, (int)(STORE_ROW_ENT_AT + (k < (uint32_t)STORE_ROW_ENT ? k : 0u)));
+    // the row number of cache row k0 + (the lane's group): the groups' numbers are read out of the record one by one (lane
+    // reads with a uniform index: no trip through LDS, which a shuffle would be) and each lane keeps its group's
+    auto entry = [&](uint32_t k0, uint32_t k) -> uint32_t {
+        uint32_t inl = 0;
+        for (uint32_t j = 0; j < n_grp; j++) {
+            const uint32_t kj = k0 + j < (uint32_t)STORE_ROW_ENT ? k0 + j : 0u;
+            const uint32_t ej = (uint32_t)__builtin_amdgcn_readlane((int)rec, (int)(STORE_ROW_ENT_AT + kj));
+            inl = (lane >> slots_log2) == j ? ej : inl;
+        }
         return ent_inline ? inl : a.entries[ent_off + k];
     };
     auto pending = [&](uint32_t k) -> uint32_t {
@@ -326,7 +333,7 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
         if (use_cache && g < n_seg)
             for (uint32_t k0 = 0; k0 < n_ent; k0 += n_grp) { // uniform trip count: the row numbers come by shuffle
                 const uint32_t k = k0 + grp;
-                const uint32_t er = entry(k < n_ent ? k : 0u);
+                const uint32_t er = entry(k0, k < n_ent ? k : 0u);
                 if (k < n_ent && w < W) { const size_t r = (size_t)er * W + w; v |= D.ci_valid_tok[r]; c |= D.ci_cd_tok[r]; }
             }
     };
@@ -471,7 +478,15 @@ __global__ __launch_bounds__(STORE_BLOCK) void mask_store_kernel(MaskArgs a, Sto
         // pattern of the bits; verdicts go back to their words through LDS.  The strings of a batch are requested one
         // batch ahead; those of the first batch travel while the row's current state is worked out ----
         incl = (uint32_t)__popc(want);                       // every copy holds the same words
-        for (uint32_t d = 1; d < slots; d <<= 1) { const uint32_t up = __shfl_up(incl, d, (int)slots); if (slot16 >= d) incl += up; }
+        // running sums over each copy's lanes by data-parallel-primitive moves (a row of 16 lanes shifts by 1, 2, 4, 8 with
+        // zeros coming in; then the last lane of a row is broadcast into the next row, of the lower half into the upper half):
+        // six vector instructions where shuffles would be six trips through LDS
+        incl += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)incl, 0x111, 0xF, 0xF, true);   // row_shr:1
+        incl += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)incl, 0x112, 0xF, 0xF, true);   // row_shr:2
+        incl += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)incl, 0x114, 0xF, 0xF, true);   // row_shr:4
+        incl += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)incl, 0x118, 0xF, 0xF, true);   // row_shr:8
+        if (slots_log2 >= 5u) incl += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)incl, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1 and 3
+        if (slots_log2 >= 6u) incl += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)incl, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2 and 3
         uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, (int)(slots - 1u));
         Tok nxt = fetch(g, 0, total);
         if (first) { find_root(); root_ok = root < AT_FAIL; }   // AT_SINK: nothing can follow; AT_FAIL: the call fails
