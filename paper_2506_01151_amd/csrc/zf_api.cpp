@@ -1487,6 +1487,14 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
                 const int p = blocks_for(r, passes[r] - 1);
                 if (p - parts[r] <= budget - all) { all += p - parts[r]; parts[r] = p; passes[r]--; }
             }
+            // Blocks are dealt to the eight XCDs in turn, and every XCD has an L2 of its own.  When rows start at multiples of eight,
+            // the blocks that take the same stretch of the vocabulary for different rows run on the same XCD and find each other's
+            // strings and cache rows in its L2.  So rows of eight blocks or more are rounded UP to a multiple of eight while blocks are
+            // left over (never down: fewer blocks would mean more passes); a block beyond the row's segments leaves at once.
+            for (int r = 0; r < nb; r++) {
+                const int up = (8 - (parts[r] & 7)) & 7;
+                if (parts[r] >= 8 && up && all + up <= budget) { parts[r] += up; all += up; }
+            }
 #ifndef ZF_MERGE_SEGMENTS
 #define ZF_MERGE_SEGMENTS 1
 #endif
