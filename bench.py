@@ -12,8 +12,12 @@ nothing is copied back to the host inside the timed region.  Inputs are seeded a
 
 Prints ONE JSON line.  `value` = batch * V * steps / wall time of a pass in which every step ends
 with the stream synchronised (a decode loop samples step t+1's token from step t's masked logits),
-the median of three such passes; every pass starts with the persistent automaton and the state
-cache cleared.  The same steps without the per-step stream synchronisation are reported beside it.
+the median of three such passes.  Every pass starts with the rows at the beginning of the trajectory
+and the persistent automaton and the state cache cleared, takes the first `--warmup` steps of the
+trajectory untimed and the next `--steps` steps timed: every step of the trajectory is met once per
+pass, so nothing a pass has seen before serves its timed steps, beyond what the same rows' earlier
+steps have left in the engine.  The same steps without the per-step stream synchronisation are
+reported beside it.
 """
 import argparse
 import json
@@ -33,7 +37,7 @@ KERNEL_OF_MODE = {0: "mask_automaton_kernel", 1: "mask_walk_kernel", 2: "mask_st
 # HBM traffic of one launch of the default mask kernel on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # scaled by a plain copy of known size (profiles/mask_store_kernel_cfg3_hbm_traffic.txt), and SQ_INSTS of the same runs.  The
 # figures describe the kernel sources with the digest below; once they change they are reported as null until measured again.
-MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 15938791, "apply_bytes_per_launch": 8501688, "instructions_per_launch": 6374894,
+MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 16101391, "apply_bytes_per_launch": 8501707, "instructions_per_launch": 6413660,
                     "kernel_sources_sha256": "8301433a8197285e3e7f4d0201ac6b36823d2c20eb510f4af6f0ddfe1ea424af"}
 
 
@@ -86,8 +90,9 @@ def extend_trajectory(zf, eng, cfg, traj, rows, steps):
     return traj
 
 
-def cpu_baseline(cfg, toks, traj, budget_s=15.0):
-    """The CPU oracle's mask loop, timed on this host on a bounded sample of (step, row)."""
+def cpu_baseline(cfg, toks, traj, skip=0, budget_s=15.0):
+    """The CPU oracle's mask loop, timed on this host on a bounded sample of (step, row): the timed steps of the
+    trajectory (those after the first `skip`), from the first one on, while the budget lasts."""
     from oracle import Oracle
     from workloads import vocab as wvocab
     orc = Oracle(cfg.grammar())
@@ -102,7 +107,7 @@ def cpu_baseline(cfg, toks, traj, budget_s=15.0):
                 states[b] = orc.new_state()
             else:
                 states[b].feed_bytes(toks[t])
-        if spent < budget_s:
+        if step >= skip and spent < budget_s:
             t0 = time.perf_counter()
             for s in states:
                 s.mask(off, data, 0)
@@ -111,7 +116,7 @@ def cpu_baseline(cfg, toks, traj, budget_s=15.0):
             threads = orc.last_threads
             sample_steps.append(step)
     return {"value": n_masks * len(toks) / spent, "unit": "vocab tokens checked/s", "cores": threads, "kind": "oracle",
-            "sample": f"{n_masks} masks: all {rows} rows at the first {len(sample_steps)} steps of the same trajectory, {spent:.1f} s"}
+            "sample": f"{n_masks} masks: all {rows} rows at the first {len(sample_steps)} timed steps of the same trajectory, {spent:.1f} s"}
 
 
 def apply_mask_sweep(zf, eng, torch, dtype, batches, launches=24):
@@ -177,18 +182,17 @@ class Runner:
         dt = {torch.float32: 0, torch.bfloat16: 1}[self.out.dtype]
         row_stride = self.out.stride(0)
         t_begin = None
+        assert n_warm + n_timed <= len(self.traj), "the trajectory is shorter than warm-up + timed steps"
         for s in self.states:
             s.reset()
+        if cold:
+            eng.clear_state_cache()                     # a pass starts with nothing: cached masks and the persistent automaton start over
         for i in range(n_warm + n_timed):
-            if i == n_warm:     # the timed steps replay the trajectory from its first step
-                for s in self.states:
-                    s.reset()
-                if cold:
-                    eng.clear_state_cache()             # nothing the warm-up computed serves the timed steps: cached masks and the persistent automaton start over
+            if i == n_warm:     # the timed steps go on where the warm-up steps stopped: every step of the trajectory is met once per pass
                 torch.cuda.synchronize()
                 t_begin = time.perf_counter()
-            k = i if i < n_warm else i - n_warm
-            ids = self.traj[k % len(self.traj)]
+            k = i - n_warm
+            ids = self.traj[i]
             t0 = time.perf_counter()
             self.states.advance(ids)                    # every row by its token (a negative id starts the row over)
             t1 = time.perf_counter()
@@ -237,17 +241,17 @@ def side_config(zf, torch, configs, idx, steps, warm, pruning=True, walk_mode=2)
     by HIP events, on the oracle-sampled trajectory."""
     cfg = configs.CONFIGS[idx]
     toks = cfg.vocab()
-    traj = load_trajectory(idx, cfg.batch, steps)
-    if len(traj) < steps:
+    traj = load_trajectory(idx, cfg.batch, warm + steps)
+    if len(traj) < warm + steps:
         return {"skipped": f"tests/golden/trajectory_cfg{idx}.txt holds {len(traj)} steps of {cfg.batch} rows"}
     eng = zf.Engine(cfg.grammar(), toks, device=0, pruning=pruning, state_cache_entries=-1, walk_mode=walk_mode)
     logits = [configs.make_logits(cfg, i, device="cuda") for i in range(2)]
     rn = Runner(zf, torch, cfg, eng, traj, logits)
-    runs = sorted((rn.run(warm if k == 0 else 0, steps, profile=False) for k in range(3)), key=lambda x: x["total"])
+    runs = sorted((rn.run(warm, steps, profile=False) for k in range(3)), key=lambda x: x["total"])
     r = runs[1]                                              # three passes, each from a cleared automaton: the median one
-    again = rn.run(0, steps, cold=False) if pruning and walk_mode == 2 else None   # the same steps with the automaton the last pass built
-    p = rn.run(0, steps, profile=True, fused=False)          # two calls: the mask kernel and apply_mask timed separately
-    p1 = rn.run(0, steps, profile=True)                      # one call: the kernel that does both
+    again = rn.run(warm, steps, cold=False) if pruning and walk_mode == 2 else None   # the same steps with the automaton the last pass built
+    p = rn.run(warm, steps, profile=True, fused=False)          # two calls: the mask kernel and apply_mask timed separately
+    p1 = rn.run(warm, steps, profile=True)                      # one call: the kernel that does both
     B, V = cfg.batch, eng.V
     esz = logits[0].element_size()
     apply_bytes = 2 * B * V * esz + B * eng.W * 4
@@ -271,8 +275,8 @@ def side_config(zf, torch, configs, idx, steps, warm, pruning=True, walk_mode=2)
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=512)
-    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--steps", type=int, default=480, help="timed steps of a pass; they follow the warm-up steps on the same trajectory (default: 32 + 480 = the 512 oracle-sampled steps)")
+    ap.add_argument("--warmup", type=int, default=32, help="untimed steps at the start of every pass")
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-side-configs", action="store_true", help="leave configurations 4 and 5 and the apply_mask sweeps out")
@@ -304,11 +308,11 @@ def main():
     # headline engine: state cache off, so every row of every step goes through the mask kernels
     eng = zf.Engine(cfg.grammar(), toks, device=0, pruning=bool(args.pruning), state_cache_entries=-1, walk_mode=args.walk_mode)
     V, W = eng.V, eng.W
-    traj = load_trajectory(args.config, B, K)
+    traj = load_trajectory(args.config, B, Wm + K)
     traj_src = "oracle-sampled file"
-    if len(traj) < K:
+    if len(traj) < Wm + K:
         traj_src = f"library-sampled beyond step {len(traj)}, not oracle-checked"
-        traj = extend_trajectory(zf, eng, cfg, traj, B, K)
+        traj = extend_trajectory(zf, eng, cfg, traj, B, Wm + K)
 
     if args.traffic_calibration:
         x = torch.zeros((1024, V), dtype=torch.bfloat16, device="cuda")
@@ -335,18 +339,18 @@ def main():
         return
 
     # three synchronised passes (each from a cleared store): the headline is their median; latencies over all of them
-    sync = [rn.run(Wm if k == 0 else 0, K) for k in range(3)]
+    sync = [rn.run(Wm, K) for k in range(3)]
     sync_totals = sorted(r["total"] for r in sync)
     total = sync_totals[1]
     lat = [x for r in sync for x in r["lat"]]
     adv = [x for r in sync for x in r["adv"]]
-    piped = rn.run(0, K, sync_steps=False)                       # steps enqueued back to back: the host runs ahead of the stream
-    warm = rn.run(0, K, cold=False)                              # the same steps again with the persistent automaton left as the last pass built it
+    piped = rn.run(Wm, K, sync_steps=False)                       # steps enqueued back to back: the host runs ahead of the stream
+    warm = rn.run(Wm, K, cold=False)                              # the same steps again with the persistent automaton left as the last pass built it
     masks = []
-    prof = rn.run(0, K, profile=True, keep_masks=masks if K <= 1024 else None)   # HIP events around the kernel
+    prof = rn.run(Wm, K, profile=True, keep_masks=masks if K <= 1024 else None)   # HIP events around the kernel
     kern, rep = prof["kern"], prof["rep"]
-    two = rn.run(0, K, fused=False)                              # the same steps through compute_mask_async + apply_mask: two kernels
-    two_prof = rn.run(0, K, profile=True, fused=False)
+    two = rn.run(Wm, K, fused=False)                              # the same steps through compute_mask_async + apply_mask: two kernels
+    two_prof = rn.run(Wm, K, profile=True, fused=False)
     # mask density: allowed fraction per (step, row), from the masks the profiled pass produced
     density_hist = None
     if masks:
@@ -358,7 +362,7 @@ def main():
         del masks
     # the same steps with the state cache (Section 5.2) on, starting cold
     eng_sc = zf.Engine(cfg.grammar(), toks, device=0, pruning=bool(args.pruning), walk_mode=args.walk_mode)
-    sc = Runner(zf, torch, cfg, eng_sc, traj, logits).run(0, K, count_hits=True)
+    sc = Runner(zf, torch, cfg, eng_sc, traj, logits).run(Wm, K, count_hits=True)
     del eng_sc
     # and with the other mask kernels, state cache off
     others = {}
@@ -366,7 +370,7 @@ def main():
         if mode == args.walk_mode:
             continue
         eng_alt = zf.Engine(cfg.grammar(), toks, device=0, pruning=bool(args.pruning), state_cache_entries=-1, walk_mode=mode)
-        r = Runner(zf, torch, cfg, eng_alt, traj, logits).run(0, K)
+        r = Runner(zf, torch, cfg, eng_alt, traj, logits).run(Wm, K)
         others[KERNEL_OF_MODE[mode]] = {"value": B * V * K / r["total"], "ms_per_step": r["total"] / K * 1e3, "p50_mask_apply_latency_us": pct(r["lat"], 0.5) * 1e6}
         del eng_alt
 
@@ -400,9 +404,10 @@ def main():
         "dtype": "u32", "data": "synthetic",
         "config": {"workload": f"configs[{args.config - 1}] {cfg.name}: grammar={cfg.grammar().name} V={V} batch={B} "
                                f"logits={cfg.dtype} pruning={'on' if args.pruning else 'off'}", "trajectory": traj_src,
+                   "trajectory_steps": f"steps 0..{Wm - 1} untimed (warm-up), steps {Wm}..{Wm + K - 1} timed, in every pass",
                    "mask_kernel": kname},
         "timed_passes": {"n": 3, "ms_per_step": [t / K * 1e3 for t in sync_totals],
-                         "note": "every step ends with the stream synchronised; each pass starts from a cleared persistent automaton; value = the median pass"},
+                         "note": "every step ends with the stream synchronised; each pass starts from a cleared persistent automaton, runs the warm-up steps and then the timed steps of the same trajectory; value = the median pass"},
         "decode_tokens_per_s": B * K / total,      # one constraint-satisfying token per row and step (the unit of the paper's Table 1)
         "paper_context": "Table 1 of the paper: 8,207.85 tokens/s for its CPU engine on Llama3 / json_schema (parsing + mask generation, "
                          "RTX 3090 + EPYC 7452 host, real tokenizer and data): other hardware, other inputs; context, not a baseline",
@@ -461,7 +466,7 @@ def main():
         result["config_5_pruning_on"] = side_config(zf, torch, configs, 5, 96, 8, pruning=True)
         result["config_5_pruning_off"] = side_config(zf, torch, configs, 5, 96, 8, pruning=False)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, toks, traj[:K])
+        result["cpu_baseline"] = cpu_baseline(cfg, toks, traj[:Wm + K], skip=Wm)
     print(json.dumps(result))
 
 
