@@ -86,6 +86,15 @@ typedef struct {
                               persistent automaton has no room for is answered by mode 0 when it is a waiting call.  With mode 2
                               and pruning = 1 zf_advance, too, goes through such an automaton, kept on the host (a look-up per
                               byte once a transition is known; results are those of the plain advance) -- with or without a device. */
+    int32_t precompute_states; /* walk_mode 2: how much of the persistent automaton is built before the first decode step.  When the
+                              engine is compiled, and again whenever zf_engine_clear_state_cache empties it, the automaton is
+                              explored breadth first from the state of the empty prefix, one byte of every byte class at a time,
+                              and the mask at every state found is computed once (a mask call computes every transition its
+                              walk of the vocabulary meets), until no new state turns up, this many states have been visited,
+                              or a quarter of a second has passed.  A grammar without recursion has a finite automaton and gets
+                              it whole, the way engines for regular constraints build theirs at compile time; of a recursive
+                              grammar the states nearest the start are built.  Masks are the same with or without.
+                              0 = default (4096 states), -1 = off */
 } zf_options;
 
 typedef struct {

@@ -30,7 +30,7 @@ class VocabDesc(ctypes.Structure):
 
 
 class Options(ctypes.Structure):
-    _fields_ = [("pruning", c_i32), ("lane_item_cap", c_i32), ("device", c_i32), ("chunk_strings", c_i32), ("fallback_item_cap", c_i32), ("state_cache_entries", c_i32), ("disable_token_mask_cache", c_i32), ("walk_mode", c_i32)]
+    _fields_ = [("pruning", c_i32), ("lane_item_cap", c_i32), ("device", c_i32), ("chunk_strings", c_i32), ("fallback_item_cap", c_i32), ("state_cache_entries", c_i32), ("disable_token_mask_cache", c_i32), ("walk_mode", c_i32), ("precompute_states", c_i32)]
 
 
 class Stats(ctypes.Structure):
@@ -252,7 +252,7 @@ def _handles(states):
 class Engine:
     """compile(grammar rules, vocab byte strings)."""
 
-    def __init__(self, grammar, vocab_tokens, *, pruning=True, lane_item_cap=0, device=0, chunk_strings=0, fallback_item_cap=0, token_mask_cache=True, state_cache_entries=0, walk_mode=2):
+    def __init__(self, grammar, vocab_tokens, *, pruning=True, lane_item_cap=0, device=0, chunk_strings=0, fallback_item_cap=0, token_mask_cache=True, state_cache_entries=0, walk_mode=2, precompute_states=0):
         load_library()
         csr = grammar.csr()
         self._keep = csr
@@ -264,7 +264,7 @@ class Engine:
         np.cumsum([len(t) for t in vocab_tokens], out=off[1:])
         data = np.frombuffer(b"".join(vocab_tokens) or b"\0", dtype=np.uint8).copy()
         vd = VocabDesc(len(vocab_tokens), off.ctypes.data, data.ctypes.data)
-        opt = Options(int(bool(pruning)), lane_item_cap, device, chunk_strings, fallback_item_cap, state_cache_entries, int(not token_mask_cache), walk_mode)
+        opt = Options(int(bool(pruning)), lane_item_cap, device, chunk_strings, fallback_item_cap, state_cache_entries, int(not token_mask_cache), walk_mode, precompute_states)
         h = c_vp()
         self.h = None
         _check(_lib.zf_compile(ctypes.byref(gd), ctypes.byref(vd), ctypes.byref(opt), ctypes.byref(h)))

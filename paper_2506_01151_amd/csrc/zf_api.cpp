@@ -12,6 +12,7 @@
 #include <new>
 #include <thread>
 #include <unordered_map>
+#include <unordered_set>
 #include "zf_internal.h"
 #include "zf_host_automaton.h"
 #include "zf_launch.h"
@@ -486,6 +487,8 @@ const char *zf_strerror(int code) {
 }
 const char *zf_last_error(void) { return g_err.c_str(); }
 
+static void explore_from_the_empty_prefix(zf_engine *e);
+
 int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_options *opt, zf_engine **out) {
     if (!g || !v || !out || v->V < 0 || (v->V && !v->off)) return fail(ZF_ERR_INVALID_ARG, "null argument");
     for (int i = 0; i < v->V; i++) {
@@ -494,7 +497,7 @@ int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_option
     }
     zf_engine *e = new (std::nothrow) zf_engine();
     if (!e) return fail(ZF_ERR_OOM, "out of memory");
-    e->opt = opt ? *opt : zf_options{1, 0, 0, 0, 0, 0, 0, 0};
+    e->opt = opt ? *opt : zf_options{1, 0, 0, 0, 0, 0, 0, 0, 0};
     e->lane_cap_auto = e->opt.lane_item_cap <= 0;
     if (e->opt.lane_item_cap <= 0) e->opt.lane_item_cap = LANE_CAP_DEFAULT;
     if (e->opt.lane_item_cap > LANE_CAP_MAX) e->opt.lane_item_cap = LANE_CAP_MAX;
@@ -503,6 +506,8 @@ int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_option
     if (e->opt.state_cache_entries < 0) e->opt.state_cache_entries = 0;
     if (e->opt.state_cache_entries > 65536) e->opt.state_cache_entries = 65536;
     if (e->opt.chunk_strings != 8 && e->opt.chunk_strings != 16 && e->opt.chunk_strings != 32) e->opt.chunk_strings = 8;
+    if (e->opt.precompute_states == 0) e->opt.precompute_states = 4096;
+    if (e->opt.precompute_states < 0) e->opt.precompute_states = 0;
     try {
         if (!build_tables(g, e->tab)) { delete e; return ZF_ERR_GRAMMAR; }
         e->V = v->V; e->W = (v->V + 31) / 32;
@@ -520,6 +525,7 @@ int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_option
         int rc = setup_device(e);
         if (rc != ZF_OK) { free_device(e->dev); delete e->host_aut; delete e; return rc; }
     }
+    explore_from_the_empty_prefix(e);
     *out = e;
     return ZF_OK;
 }
@@ -1568,6 +1574,67 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
     return enqueue_mask(e, states, batch, d_mask, hip_stream, true);
 }
 
+// What the persistent automaton holds when a decode loop starts (zf_options.precompute_states).  The automaton is explored
+// breadth first from the state of the empty prefix, one byte class at a time (every DFA treats the bytes of a class alike, so one
+// byte per class stands for all), on the host and, by computing the mask at every state found, on the device: a mask call
+// computes every transition its walk of the vocabulary needs, so the device learns the states a token's length ahead of the
+// exploration.  The exploration ends when no new state turns up -- a grammar without recursion has a finite automaton, which is
+// then built whole, as engines for regular constraints build theirs when they compile -- or at the budget of states or of
+// time.  It uses the library's own calls and nothing else (states, advance by bytes, compute_mask): what it leaves behind is
+// what a decode loop that happened to visit these prefixes would have left.  Failures are not errors: the engine then starts
+// with whatever was learnt, or with nothing, as it did before there was an exploration.
+static void explore_from_the_empty_prefix(zf_engine *e) {
+    if (!e || !e->store_on || !e->dev || !e->host_aut || e->opt.precompute_states <= 0) return;
+    DeviceSide *d = e->dev;
+    if (d->pending != 0) return;                          // calls in flight: the store is cleared lazily, and starts empty
+    const auto t0 = std::chrono::steady_clock::now();
+    auto spent = [&]() { return std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count(); };
+    const double budget_s = 0.25;
+    const size_t budget_states = (size_t)e->opt.precompute_states;
+    hipError_t he = hipSetDevice(e->opt.device);
+    uint32_t *d_tmp = nullptr;
+    constexpr int ROWS = STORE_MINI_ROWS;
+    if (he != hipSuccess || hipMalloc((void **)&d_tmp, (size_t)ROWS * (size_t)std::max(e->W, 1) * 4) != hipSuccess) { (void)hipGetLastError(); return; }
+    std::vector<uint8_t> rep(std::max(e->tab.n_cls, 0), 0);   // one byte of every class
+    std::vector<char> have(rep.size(), 0);
+    for (int b = 0; b < 256; b++) { const int c = e->tab.cls[b]; if (c >= 0 && c < (int)rep.size() && !have[c]) { have[c] = 1; rep[c] = (uint8_t)b; } }
+    // Breadth first, 64 states at a time: the masks at the states in hand (the device meets them and everything a token's length
+    // ahead; the host then knows their names on the device), then the states one byte further, which inherit their parent's
+    // name and one pending byte.
+    std::vector<zf_state *> queue;
+    size_t head = 0;
+    std::unordered_set<uint32_t> seen;
+    zf_state *root = nullptr;
+    bool ok = zf_state_new(e, &root) == ZF_OK;
+    if (ok) { queue.push_back(root); seen.insert(HostAutomaton::ROOT); }
+    const uint32_t epoch = e->host_epoch;
+    while (ok && head < queue.size() && spent() < budget_s) {
+        const size_t n = std::min<size_t>(ROWS, queue.size() - head);
+        ok = enqueue_mask(e, queue.data() + head, (int32_t)n, d_tmp, nullptr, true) == ZF_OK;
+        for (size_t k = head; ok && k < head + n; k++) {
+            for (size_t c = 0; c < rep.size() && seen.size() < budget_states; c++) {
+                if (!have[c]) continue;
+                zf_state *child = nullptr;
+                if (zf_state_clone(queue[k], &child) != ZF_OK) { ok = false; break; }
+                const bool alive = zf_advance_bytes(child, &rep[c], 1) == ZF_OK && e->host_epoch == epoch &&
+                                   child->host_id != HostAutomaton::SINK && child->host_id != HostAutomaton::DEAD;
+                if (alive && seen.insert(child->host_id).second) queue.push_back(child);
+                else zf_state_destroy(child);
+            }
+            zf_state_destroy(queue[k]);
+            queue[k] = nullptr;
+        }
+        head += n;
+        if (e->host_epoch != epoch) ok = false;           // the host automaton filled up and started over: enough
+    }
+    for (zf_state *st : queue) if (st) zf_state_destroy(st);
+    (void)hipFree(d_tmp);
+    g_err.clear();                                        // a rejected byte is how a dead class shows: not the caller's error
+    if (d->store_backoff) {                               // a state the store had no room for: the engine starts as if nothing had been explored
+        d->store_backoff = 0; d->store_backoff_next = 8; d->store_dirty = true;
+    }
+}
+
 int zf_compute_mask_noalloc(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream) {
     if (e && e->dev && e->dev->pending) return fail(ZF_ERR_INVALID_ARG, "zf_compute_mask_noalloc: asynchronous mask calls are in flight: call zf_mask_wait first");
     return enqueue_mask(e, states, batch, d_mask, hip_stream, true, true);
@@ -1668,6 +1735,7 @@ int zf_engine_clear_state_cache(zf_engine *e) {
         e->host_aut->clear();
         e->host_epoch++;
     }
+    explore_from_the_empty_prefix(e);                     // back to what the engine knew when it was compiled
     return ZF_OK;
 }
 

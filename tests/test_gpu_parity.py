@@ -595,6 +595,42 @@ def test_long_tokens_deep_nesting_many_classes(mode, torch_cuda, oracle_lib):
     _run_parity(torch, zf, oracle_lib.Oracle, g2, toks2, 3, 12, 4242, walk_mode=MODES[mode])
 
 
+def test_exploration_at_compile_time_changes_no_mask(torch_cuda, oracle_lib):
+    """zf_options.precompute_states: the automaton explored from the empty prefix when the engine is compiled and
+    whenever it is emptied.  A grammar without recursion (the W2 sequence, a JSON schema with fixed keys cut short
+    by its budget) and a recursive one; masks against the oracle with the exploration on, off, and after the engine
+    has been emptied in mid-sentence; and the first steps of a decode loop find more of their transitions
+    computed with it than without."""
+    import paper_2506_01151_amd as zf
+    torch = torch_cuda
+    cfg = configs.CONFIGS[2]
+    g, toks = cfg.grammar(), cfg.vocab()
+    for pre in (-1, 64, 0):
+        _run_parity(torch, zf, oracle_lib.Oracle, g, toks, 4, 24, 991, walk_mode=2, precompute_states=pre)
+    _run_parity(torch, zf, oracle_lib.Oracle, grammars.w2_grammar(), [b"a", b"b", b"ab", b"ba", b""], 2, 6, 5, walk_mode=2)
+    cfg3 = configs.CONFIGS[3]
+    g3, toks3 = cfg3.grammar(), cfg3.vocab(8000)
+    steps_taken = {}
+    for pre in (-1, 0):
+        eng = zf.Engine(g3, toks3, device=0, state_cache_entries=-1, walk_mode=2, precompute_states=pre)
+        orc = oracle_lib.Oracle(g3)
+        run = OracleRun(orc, toks3, [stream(77, f"sample[{b}]") for b in range(4)])
+        states = [eng.new_state() for _ in range(4)]
+        d_mask = torch.empty((4, eng.W), dtype=torch.int32, device="cuda")
+        total = 0
+        for step in range(12):
+            want = run.masks()
+            zf.compute_mask(eng, states, d_mask)
+            total += eng.mask_report().parser_steps
+            assert (d_mask.cpu().numpy().view(np.uint32) == want).all(), (pre, step)
+            if step == 6:
+                eng.clear_state_cache()                     # emptied (and explored again) under the rows' feet
+            for b, t in enumerate(run.step(want)):
+                states[b].reset() if t < 0 else states[b].advance(t)
+        steps_taken[pre] = total
+    assert steps_taken[0] < steps_taken[-1], steps_taken
+
+
 @pytest.mark.parametrize("cap", [None, 72, 200], ids=["default-budget", "budget-72", "budget-200"])
 def test_wide_sets_of_an_ambiguous_grammar(cap, torch_cuda, oracle_lib):
     """Sets far beyond 64 items (the ambiguous expression grammar after sums of 20 to 150 operands: every
