@@ -218,7 +218,10 @@ int zf_compute_mask_noalloc(zf_engine *e, zf_state *const *states /* host array 
                             uint32_t *d_mask, void *hip_stream);
 int zf_last_mask_report(const zf_engine *e, zf_mask_report *out);
 /* Forget every cached mask row and empty the persistent automata on the device and on the host: everything is
- * parsed again the next time it is needed (benchmarks call it to start cold).  Results do not change. */
+ * parsed again the next time it is needed (benchmarks call it to start cold).  Results do not change.  With
+ * zf_options.precompute_states on, and no asynchronous mask call in flight, the automata are then explored from the
+ * empty prefix again as when the engine was compiled (mask calls on the null stream, which this call waits for):
+ * the engine is back to what it knew after zf_compile, not to nothing. */
 int zf_engine_clear_state_cache(zf_engine *e);
 /* on != 0: zf_compute_mask brackets each of its kernels with HIP events (a few microseconds
  * of extra host time per call) and zf_last_mask_report returns their durations. */
