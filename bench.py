@@ -117,7 +117,7 @@ def cpu_baseline(cfg, toks, traj, skip=0, budget_s=15.0):
             threads = orc.last_threads
             sample_steps.append(step)
     return {"value": n_masks * len(toks) / spent, "unit": "vocab tokens checked/s", "cores": threads, "kind": "oracle",
-            "sample": f"{n_masks} masks: all {rows} rows at the first {len(sample_steps)} timed steps of the same trajectory, {spent:.1f} s"}
+            "sample": f"{n_masks} masks: all {rows} rows at steps {sample_steps[0] if sample_steps else 0}..{sample_steps[-1] if sample_steps else 0} of the same trajectory (from the first timed step on), {spent:.1f} s"}
 
 
 def apply_mask_sweep(zf, eng, torch, dtype, batches, launches=24):
@@ -479,7 +479,9 @@ def main():
         result["config_5_pruning_on"] = side_config(zf, torch, configs, 5, 96, 8, pruning=True)
         result["config_5_pruning_off"] = side_config(zf, torch, configs, 5, 96, 8, pruning=False)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, toks, traj[:Wm + K], skip=Wm)
+        # the oracle's sample starts with the timed steps and, when those are few, goes on along the same trajectory until its time budget is used
+        full = load_trajectory(args.config, B, 1 << 30)
+        result["cpu_baseline"] = cpu_baseline(cfg, toks, full if len(full) >= Wm + K and traj_src == "oracle-sampled file" else traj[:Wm + K], skip=Wm)
     print(json.dumps(result))
 
 
