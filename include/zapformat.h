@@ -91,10 +91,10 @@ typedef struct {
                               explored breadth first from the state of the empty prefix, one byte of every byte class at a time,
                               and the mask at every state found is computed once (a mask call computes every transition its
                               walk of the vocabulary meets), until no new state turns up, this many states have been visited,
-                              or a quarter of a second has passed.  A grammar without recursion has a finite automaton and gets
+                              a second has passed, or the store is a quarter full.  A grammar without recursion has a finite automaton and gets
                               it whole, the way engines for regular constraints build theirs at compile time; of a recursive
                               grammar the states nearest the start are built.  Masks are the same with or without.
-                              0 = default (4096 states), -1 = off */
+                              0 = default (65536 states), -1 = off */
 } zf_options;
 
 typedef struct {

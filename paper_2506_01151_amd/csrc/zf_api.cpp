@@ -93,7 +93,23 @@ struct DeviceSide {
         uint32_t epoch = 0;
         std::vector<std::shared_ptr<StateLink>> st; std::vector<uint32_t> gen; std::vector<uint64_t> upto;
         std::vector<uint64_t> hop;                   // per row: the (state, token) pair the kernel walks, to be noted with the state it reports; 0 = none
+        std::vector<uint32_t> host;                  // per row: the state's name in the host automaton, to be noted with the name the kernel reports; 0 = none
+        uint32_t host_epoch = 0;                     // ... and the epoch of the host automaton that name belongs to
     } rec[N_SLOTS];
+    // The device's name of a state of the host automaton, as the mask kernel has reported it for a row that stood there.  The two
+    // automata hold the same sets under different names; once a state's device name is known, a row that arrives in it is sent
+    // with that name and no bytes to walk, whatever token took it there.  Valid while neither automaton has been emptied.
+    std::vector<uint32_t> name_of_host;
+    uint32_t name_host_epoch = 0, name_store_epoch = 0;
+    uint32_t name_find(uint32_t host_id, uint32_t host_epoch, uint32_t st_epoch) const {   // 0 = unknown
+        return host_epoch == name_host_epoch && st_epoch == name_store_epoch && host_id < name_of_host.size() ? name_of_host[host_id] : 0u;
+    }
+    void name_note(uint32_t host_id, uint32_t host_epoch, uint32_t st_epoch, uint32_t dev) {
+        if (host_epoch != name_host_epoch || st_epoch != name_store_epoch) { name_of_host.clear(); name_host_epoch = host_epoch; name_store_epoch = st_epoch; }
+        if (host_id >= (1u << 22)) return;
+        if (host_id >= name_of_host.size()) name_of_host.resize(std::max<size_t>(host_id + 1, name_of_host.size() * 2), 0u);
+        name_of_host[host_id] = dev;
+    }
     // Where a token leads from a state of the persistent automaton, as the mask kernel has reported it: (state << 32 | token + 1)
     // -> state.  Names are stable while the store is not cleared, so a row that is fed a token in a state some row was fed it in
     // before is sent with the state it arrives in and no bytes to walk.  Open addressing, exact keys, emptied with the store.
@@ -506,7 +522,7 @@ int zf_compile(const zf_grammar_desc *g, const zf_vocab_desc *v, const zf_option
     if (e->opt.state_cache_entries < 0) e->opt.state_cache_entries = 0;
     if (e->opt.state_cache_entries > 65536) e->opt.state_cache_entries = 65536;
     if (e->opt.chunk_strings != 8 && e->opt.chunk_strings != 16 && e->opt.chunk_strings != 32) e->opt.chunk_strings = 8;
-    if (e->opt.precompute_states == 0) e->opt.precompute_states = 4096;
+    if (e->opt.precompute_states == 0) e->opt.precompute_states = 65536;
     if (e->opt.precompute_states < 0) e->opt.precompute_states = 0;
     try {
         if (!build_tables(g, e->tab)) { delete e; return ZF_ERR_GRAMMAR; }
@@ -1225,6 +1241,15 @@ static int enqueue_mask_impl(zf_engine *e, zf_state *const *states, int32_t batc
 // to be in and the byte classes fed since; the mask kernel walks them, checks the vocabulary from the state it arrives at and
 // reports that state back (pinned memory), which zf_mask_wait notes in the zf_state.  Rows the store does not know -- after it
 // was cleared, or too far behind -- bring their packed chart along and are made states of by the import kernel first.
+// The state's name in the host automaton, when it has a current one there (the caller holds the host automaton's lock) ...
+static bool host_name_valid(const zf_engine *e, const zf_state *st) {
+    return e->host_aut && st->host_id != HostAutomaton::ROOT && st->host_id_epoch == e->host_epoch && st->host_id < HostAutomaton::SINK && st->host_id != 0;
+}
+// ... and the device's name of that state, 0 when the device has not reported one
+static uint32_t device_name_of(const zf_engine *e, const zf_state *st) {
+    return host_name_valid(e, st) ? e->dev->name_find(st->host_id, e->host_epoch, e->dev->store_epoch) : 0u;
+}
+
 static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t batch, uint32_t *d_mask, void *hip_stream, bool wait, uint32_t slot) {
     DeviceSide *d = e->dev;
     hipStream_t stream = (hipStream_t)hip_stream;
@@ -1256,7 +1281,9 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
         unknown.clear();
         for (int b = 0; b < batch; b++) {
             zf_state *st = states[b];
-            if (!(st->dev_id == STORE_ROOT_ID || (st->dev_id != 0 && st->dev_epoch == d->store_epoch)) && !st->lag.empty()) unknown.push_back(st);
+            if (st->dev_id == STORE_ROOT_ID || (st->dev_id != 0 && st->dev_epoch == d->store_epoch) || st->lag.empty()) continue;
+            if (device_name_of(e, st)) continue;          // the device knows the state under the name the host automaton has for it: no chart needed
+            unknown.push_back(st);
         }
         if (!unknown.empty()) catch_up_batch(unknown.data(), (int32_t)unknown.size());
     }
@@ -1264,6 +1291,8 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
     d->report.cache_hits = n_hits; d->report.cache_misses = sc ? nb : 0;
     // ---- what each launched row sends ----
     import_rows.clear();
+    static thread_local std::vector<uint32_t> row_named;  // per launched row: the device's name of the state it stands in, when the host automaton's name for it has one (0: not known)
+    row_named.assign(miss_rows.size(), 0);
     const bool use_cache = !e->opt.disable_token_mask_cache;
     size_t n_pend = 0, n_ent = 0, n_off = 0, n_items = 0, widest = 0, biggest_set = 0;
     for (int r = 0; r < nb; r++) {
@@ -1273,8 +1302,10 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
         widest = std::max(widest, last);
         biggest_set = std::max<size_t>(biggest_set, cs.biggest);
         if (use_cache) n_ent += last;
+        row_named[r] = device_name_of(e, st);
         const bool known = st->dev_id == STORE_ROOT_ID || (st->dev_id != 0 && st->dev_epoch == d->store_epoch);
-        if (known) n_pend += st->pending.size();
+        if (row_named[r]) {}                               // sent with its name on the device: no bytes, no chart
+        else if (known) n_pend += st->pending.size();
         else {
             const Chart &c = chart_of(st);
             import_rows.push_back((uint32_t)r);
@@ -1307,6 +1338,7 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
     DeviceSide::CallRecord &rec = d->rec[slot];
     rec.active = true; rec.epoch = d->store_epoch;
     rec.st.assign(nb, std::shared_ptr<StateLink>()); rec.gen.assign(nb, 0); rec.upto.assign(nb, 0); rec.hop.assign(nb, 0);
+    rec.host.assign(nb, 0); rec.host_epoch = e->host_epoch;
     if (d->hop_epoch != d->store_epoch) { if (d->hop_used) std::fill(d->hop_key.begin(), d->hop_key.end(), 0); d->hop_used = 0; d->hop_epoch = d->store_epoch; }
     uint32_t n_cache_rows = 0;
     static thread_local std::vector<uint32_t> row_n_ent, row_ent_at, row_n_items;
@@ -1337,8 +1369,13 @@ static int enqueue_store_impl(zf_engine *e, zf_state *const *states, int32_t bat
             row_n_ent[r] = sr.n_ent; row_ent_at[r] = en_at; row_n_items[r] = cs.n;
             en_at += sr.n_ent;
             n_cache_rows += sr.n_ent;
-            const bool known = st->dev_id == STORE_ROOT_ID || (st->dev_id != 0 && st->dev_epoch == d->store_epoch);
-            if (known) {
+            // the state's name in the host automaton, when it has one there: the key to its name on the device
+            const uint32_t named = row_named[r];
+            if (!named && host_name_valid(e, st)) rec.host[r] = st->host_id;
+            const bool known = named != 0 || st->dev_id == STORE_ROOT_ID || (st->dev_id != 0 && st->dev_epoch == d->store_epoch);
+            if (named) {                                   // the device knows this very state: nothing to walk, nothing to bring in
+                sr.start = named; sr.n_pending = 0; sr.pend_off = pe_at;
+            } else if (known) {
                 sr.start = st->dev_id; sr.n_pending = (uint32_t)st->pending.size(); sr.pend_off = pe_at;
                 if (sr.n_pending && st->pending_token >= 0 && st->dev_id != 0xFFFFFFFDu) {
                     const uint64_t key = (uint64_t)st->dev_id << 32 | ((uint32_t)st->pending_token + 1u);
@@ -1580,7 +1617,7 @@ int zf_compute_mask(zf_engine *e, zf_state *const *states, int32_t batch, uint32
 // computes every transition its walk of the vocabulary needs, so the device learns the states a token's length ahead of the
 // exploration.  The exploration ends when no new state turns up -- a grammar without recursion has a finite automaton, which is
 // then built whole, as engines for regular constraints build theirs when they compile -- or at the budget of states or of
-// time.  It uses the library's own calls and nothing else (states, advance by bytes, compute_mask): what it leaves behind is
+// time, or when the store is a quarter full.  It uses the library's own calls and nothing else (states, advance by bytes, compute_mask): what it leaves behind is
 // what a decode loop that happened to visit these prefixes would have left.  Failures are not errors: the engine then starts
 // with whatever was learnt, or with nothing, as it did before there was an exploration.
 static void explore_from_the_empty_prefix(zf_engine *e) {
@@ -1589,7 +1626,7 @@ static void explore_from_the_empty_prefix(zf_engine *e) {
     if (d->pending != 0) return;                          // calls in flight: the store is cleared lazily, and starts empty
     const auto t0 = std::chrono::steady_clock::now();
     auto spent = [&]() { return std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count(); };
-    const double budget_s = 0.25;
+    const double budget_s = 1.0;
     const size_t budget_states = (size_t)e->opt.precompute_states;
     hipError_t he = hipSetDevice(e->opt.device);
     uint32_t *d_tmp = nullptr;
@@ -1601,7 +1638,7 @@ static void explore_from_the_empty_prefix(zf_engine *e) {
     // Breadth first, 64 states at a time: the masks at the states in hand (the device meets them and everything a token's length
     // ahead; the host then knows their names on the device), then the states one byte further, which inherit their parent's
     // name and one pending byte.
-    std::vector<zf_state *> queue;
+    std::vector<zf_state *> queue, edges;
     size_t head = 0;
     std::unordered_set<uint32_t> seen;
     zf_state *root = nullptr;
@@ -1619,14 +1656,26 @@ static void explore_from_the_empty_prefix(zf_engine *e) {
                 const bool alive = zf_advance_bytes(child, &rep[c], 1) == ZF_OK && e->host_epoch == epoch &&
                                    child->host_id != HostAutomaton::SINK && child->host_id != HostAutomaton::DEAD;
                 if (alive && seen.insert(child->host_id).second) queue.push_back(child);
+                else if (alive) edges.push_back(child);   // a way into a state met before: the device has to have walked it too
                 else zf_state_destroy(child);
             }
             zf_state_destroy(queue[k]);
             queue[k] = nullptr;
         }
         head += n;
+        // the transitions that led to states met before: a row that takes one has the device walk it (its mask is made of look-ups,
+        // or is the first visit of a state whose turn in the queue comes later)
+        while (ok && edges.size() >= (size_t)ROWS) {
+            ok = enqueue_mask(e, edges.data() + edges.size() - ROWS, ROWS, d_tmp, nullptr, true) == ZF_OK;
+            for (int k = 0; k < ROWS; k++) { zf_state_destroy(edges.back()); edges.pop_back(); }
+        }
         if (e->host_epoch != epoch) ok = false;           // the host automaton filled up and started over: enough
+        // a quarter of the store is the most the exploration takes: the store starts over when it is half full, and what a
+        // decode loop adds needs room
+        if (d->store_states > d->store.cap_states / 4 || d->store_items > d->store.cap_items / 4) break;
     }
+    if (ok && !edges.empty() && spent() < budget_s) (void)enqueue_mask(e, edges.data(), (int32_t)edges.size(), d_tmp, nullptr, true);
+    for (zf_state *st : edges) zf_state_destroy(st);
     for (zf_state *st : queue) if (st) zf_state_destroy(st);
     (void)hipFree(d_tmp);
     g_err.clear();                                        // a rejected byte is how a dead class shows: not the caller's error
@@ -1696,6 +1745,7 @@ int zf_mask_wait(zf_engine *e, void *hip_stream) {
                 zf_state *s = rec.st[r] ? rec.st[r]->s : nullptr;
                 if (out[r] == 0 || (out[r] >= d->store.cap_states && out[r] != 0xFFFFFFFDu)) continue;
                 if (rec.hop[r]) d->hop_note(rec.hop[r], out[r]);          // a fact about the automaton, whatever has become of the row
+                if (r < rec.host.size() && rec.host[r] && out[r] != 0xFFFFFFFDu) d->name_note(rec.host[r], rec.host_epoch, rec.epoch, out[r]);   // and so is this
                 if (!s || s->generation != rec.gen[r]) continue;
                 if (rec.upto[r] < s->pending_base) continue;              // a later call's result is already in
                 const size_t drop = std::min<size_t>((size_t)(rec.upto[r] - s->pending_base), s->pending.size());
