@@ -38,8 +38,8 @@ KERNEL_OF_MODE = {0: "mask_automaton_kernel", 1: "mask_walk_kernel", 2: "mask_st
 # HBM traffic of one launch of the default mask kernel on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # scaled by a plain copy of known size (profiles/mask_store_kernel_cfg3_hbm_traffic.txt), and SQ_INSTS of the same runs.  The
 # figures describe the kernel sources with the digest below; once they change they are reported as null until measured again.
-MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 16071990, "apply_bytes_per_launch": 8501691, "instructions_per_launch": 6383670,
-                    "kernel_sources_sha256": "0aa86de6cb32b1218e6ee2192708324c9e88f0c1e06021e6fb1a6242d535b857"}
+MEASURED_TRAFFIC = {"config": 3, "bytes_per_launch": 16006507, "apply_bytes_per_launch": 8501824, "instructions_per_launch": 5960564,
+                    "kernel_sources_sha256": "17eae1b830e6e8492fd31c03d3d05e3300788c4e57feb5a5198f7bed1dc8a4c0"}
 
 
 def kernel_sources_digest():

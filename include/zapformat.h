@@ -92,8 +92,8 @@ typedef struct {
                               and the mask at every state found is computed once (a mask call computes every transition its
                               walk of the vocabulary meets), until no new state turns up, this many states have been visited,
                               a second has passed, or the store is a quarter full.  A grammar without recursion has a finite automaton and gets
-                              it whole, the way engines for regular constraints build theirs at compile time; of a recursive
-                              grammar the states nearest the start are built.  Masks are the same with or without.
+                              it whole, the way engines for regular constraints build theirs at compile time (a decode loop then
+                              computes no transition at all); of a recursive grammar the states nearest the start are built.  Masks are the same with or without.
                               0 = default (65536 states), -1 = off */
 } zf_options;
 
